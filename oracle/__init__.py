@@ -1,0 +1,178 @@
+"""ctypes access to the fp64 CPU oracle (oracle/e2f_oracle.c).
+
+TEST INFRASTRUCTURE ONLY: imported by tests/, by __graft_entry__.smoke() and by the cpu_baseline leg
+of bench.py.  Nothing in the product package imports this module, and this module imports nothing
+from the product package.
+"""
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "e2f_oracle.c")
+_LIB = os.path.join(_HERE, "libe2f_oracle.so")
+
+
+def build(force=False):
+    """Compile the oracle with gcc (host only).  -ffp-contract=off keeps the binary32 cutoff predicate free of FMA."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-fopenmp", "-ffp-contract=off", "-fPIC", "-shared", "-Wall", "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+class _Config(ctypes.Structure):
+    _fields_ = [("L", ctypes.c_int), ("C", ctypes.c_int), ("H", ctypes.c_int), ("B", ctypes.c_int),
+                ("lf", ctypes.c_int), ("cutoff", ctypes.c_double)]
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        build()
+        L = ctypes.CDLL(_LIB)
+        dp = ctypes.POINTER(ctypes.c_double)
+        ip = ctypes.POINTER(ctypes.c_int32)
+        lp = ctypes.POINTER(ctypes.c_int64)
+        L.e2fo_solid_harmonics.argtypes = [ctypes.c_int, dp, dp]
+        L.e2fo_solid_harmonics.restype = None
+        L.e2fo_cg_complex.argtypes = [ctypes.c_int] * 6
+        L.e2fo_cg_complex.restype = ctypes.c_double
+        L.e2fo_cg_real.argtypes = [ctypes.c_int] * 3 + [dp]
+        L.e2fo_cg_real.restype = None
+        L.e2fo_wigner_D_real.argtypes = [ctypes.c_int, ctypes.c_double, ctypes.c_double, ctypes.c_double, dp]
+        L.e2fo_wigner_D_real.restype = None
+        L.e2fo_align_angles.argtypes = [dp, dp, dp]
+        L.e2fo_align_angles.restype = None
+        L.e2fo_P_path.argtypes = [ctypes.c_int] * 3 + [ip, dp]
+        L.e2fo_P_path.restype = ctypes.c_int
+        L.e2fo_message.argtypes = [ctypes.c_int, ctypes.c_int, dp, dp, ctypes.c_int, dp, ctypes.c_int,
+                                   ctypes.c_double, dp]
+        L.e2fo_message.restype = None
+        L.e2fo_neighbor_list.argtypes = [dp, ip, ctypes.c_int, ctypes.c_int, ctypes.c_float, ctypes.c_int, lp,
+                                         ctypes.POINTER(ip)]
+        L.e2fo_neighbor_list.restype = ctypes.c_int
+        L.e2fo_free.argtypes = [ctypes.c_void_p]
+        L.e2fo_free.restype = None
+        L.e2fo_attn_forward.argtypes = [ctypes.POINTER(_Config), dp, dp, ctypes.c_int, dp, dp, dp, dp, dp, dp, dp,
+                                        lp, ip, ip, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_double, dp]
+        L.e2fo_attn_forward.restype = ctypes.c_int
+        _lib = L
+    return _lib
+
+
+def _d(a):
+    return a.ctypes.data_as(ctypes.POINTER(ctypes.c_double))
+
+
+def _f64(a):
+    return np.ascontiguousarray(a, dtype=np.float64)
+
+
+def solid_harmonics(l, r):
+    r = _f64(r)
+    out = np.empty(2 * l + 1)
+    lib().e2fo_solid_harmonics(l, _d(r), _d(out))
+    return out
+
+
+def cg_complex(j1, m1, j2, m2, j, m):
+    return lib().e2fo_cg_complex(j1, m1, j2, m2, j, m)
+
+
+def cg_real(li, lf, lo):
+    """Real-basis CG tensor [2lo+1][2li+1][2lf+1]."""
+    out = np.empty((2 * lo + 1, 2 * li + 1, 2 * lf + 1))
+    lib().e2fo_cg_real(li, lf, lo, _d(out))
+    return out
+
+
+def wigner_D_real(l, alpha, beta, gamma):
+    """Real-basis D(Rz(alpha) Ry(beta) Rz(gamma)) with Y(R x) = D Y(x)."""
+    out = np.empty((2 * l + 1, 2 * l + 1))
+    lib().e2fo_wigner_D_real(l, alpha, beta, gamma, _d(out))
+    return out
+
+
+def align_angles(r):
+    r = _f64(r)
+    th, ph = ctypes.c_double(), ctypes.c_double()
+    lib().e2fo_align_angles(_d(r), ctypes.byref(th), ctypes.byref(ph))
+    return th.value, ph.value
+
+
+def P_path(li, lf, lo):
+    """(src, coef, worst): for each mo the one contributing input offset (or -1), its coefficient, and the
+    largest number of contributing inputs found for any mo."""
+    src = np.empty(2 * lo + 1, dtype=np.int32)
+    coef = np.empty(2 * lo + 1)
+    worst = lib().e2fo_P_path(li, lf, lo, src.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)), _d(coef))
+    return src, coef, worst
+
+
+def message(L, lf, w_path, v, r, mode="dense", chi=0.0):
+    """Edge message for one pair; v is [(L+1)^2] or [(L+1)^2][C]."""
+    v = _f64(v)
+    squeeze = v.ndim == 1
+    v2 = np.ascontiguousarray(v.reshape(v.shape[0], -1))
+    w = _f64(w_path)
+    r = _f64(r)
+    out = np.empty_like(v2)
+    lib().e2fo_message(L, lf, _d(w), _d(v2), v2.shape[1], _d(r), 0 if mode == "dense" else 1, float(chi), _d(out))
+    return out[:, 0] if squeeze else out
+
+
+def neighbor_list(pos, seg_offsets, cutoff, use_cells=False):
+    """CSR neighbour lists (offsets int64[N+1], idx int32[E]); neighbours sorted by index."""
+    pos = _f64(pos)
+    seg = np.ascontiguousarray(seg_offsets, dtype=np.int32)
+    N, S = pos.shape[0], seg.shape[0] - 1
+    offsets = np.empty(N + 1, dtype=np.int64)
+    ptr = ctypes.POINTER(ctypes.c_int32)()
+    lib().e2fo_neighbor_list(_d(pos),
+                             seg.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)), N, S, ctypes.c_float(cutoff),
+                             1 if use_cells else 0, offsets.ctypes.data_as(ctypes.POINTER(ctypes.c_int64)),
+                             ctypes.byref(ptr))
+    E = int(offsets[-1])
+    idx = np.ctypeslib.as_array(ptr, shape=(max(E, 1),))[:E].copy()
+    lib().e2fo_free(ptr)
+    return offsets, idx
+
+
+def attn_forward(cfg, pos, h, seg_offsets, weights, targets=None, message_mode="dense", softmax_mode="twopass",
+                 use_cells=False, chi=0.0, nbr=None):
+    """The operator.  cfg: dict(L, C, H, B, lf, cutoff); weights: dict(WQ1, WQ2, WK1, WK2, WV [L+1][C][C],
+    Wb [H][B], w_path [L+1][L+1]); returns float64 [n_targets][(L+1)^2][C]."""
+    c = _Config(cfg["L"], cfg["C"], cfg["H"], cfg["B"], cfg["lf"], float(np.float32(cfg["cutoff"])))
+    pos = _f64(pos)
+    h = _f64(h)
+    N = pos.shape[0]
+    n = (cfg["L"] + 1) ** 2
+    assert h.shape == (N, n, cfg["C"])
+    if nbr is None:
+        nbr = neighbor_list(pos, seg_offsets, np.float32(cfg["cutoff"]), use_cells)
+    offsets, idx = nbr
+    idx = np.ascontiguousarray(idx, dtype=np.int32)
+    if idx.size == 0:
+        idx = np.zeros(1, dtype=np.int32)
+    W = {k: _f64(weights[k]) for k in ("WQ1", "WQ2", "WK1", "WK2", "WV", "Wb", "w_path")}
+    ip = ctypes.POINTER(ctypes.c_int32)
+    if targets is None:
+        tptr, nt = ip(), N
+    else:
+        targets = np.ascontiguousarray(targets, dtype=np.int32)
+        tptr, nt = targets.ctypes.data_as(ip), targets.shape[0]
+    out = np.empty((nt, n, cfg["C"]))
+    rc = lib().e2fo_attn_forward(ctypes.byref(c), _d(pos), _d(h), N,
+                                 _d(W["WQ1"]), _d(W["WQ2"]), _d(W["WK1"]), _d(W["WK2"]), _d(W["WV"]), _d(W["Wb"]),
+                                 _d(W["w_path"]), offsets.ctypes.data_as(ctypes.POINTER(ctypes.c_int64)),
+                                 idx.ctypes.data_as(ip), tptr, nt, 0 if message_mode == "dense" else 1,
+                                 0 if softmax_mode == "twopass" else 1, float(chi), _d(out))
+    if rc != 0:
+        raise ValueError("oracle rejected the configuration")
+    return out
