@@ -1,0 +1,141 @@
+/*
+ * e2f - node-centric on-the-fly equivariant attention forward pass (E2Former-V2) for AMD MI355X (gfx950).
+ *
+ * C ABI of libe2f.so.  The operator, for every atom i (paper: Preliminaries, Sec. 3.2-3.4):
+ *
+ *   N(i)    = { j != i in the same segment with |r_j - r_i| < cutoff }
+ *   q_i,k_j = concat_l < W1^(l) h^(l), W2^(l) h^(l) >           (Eq. qk; W acts on channels, <,> sums over m)
+ *   s_ij,h  = q_i,h . k_j,h / sqrt(d_k) + b_h(|r_ij|)            (Eq. kernel_score)
+ *   a_ij,h  = softmax_j(s_ij,h) * phi(|r_ij|)                    (Eq. attn; the gate is outside the softmax)
+ *   out_i   = sum_j a_ij,head(c) * ( v_j (x) R^(lf)(r_ij) )      (m_i = sum_j alpha_ij m_ij, v = W_V h)
+ *
+ * with the tensor product evaluated through Equivariant Axis-Aligned Sparsification (Sec. 3.3: rotate
+ * v_j into the frame whose z-axis is r_ij, apply the sparse re-indexing operator P, rotate back) and the
+ * sum over neighbours evaluated as the streaming online-softmax reduction of Algorithm 1, so that no
+ * per-pair tensor is written to memory by e2f_attn_forward.
+ *
+ * Conventions
+ *   - Component (l,m) of an irreps feature has index l*l + l + m; features are [atom][component][channel],
+ *     channel innermost.  The real basis orders l=1 as (y,z,x); harmonics are Racah-normalised.
+ *   - Head h owns channels [h*C/H, (h+1)*C/H) of every degree; d_k = (L_max+1)*C/H.
+ *   - b_h(d) = sum_b Wb[h][b] exp(-gamma (d - mu_b)^2), mu_b = b*cutoff/(B-1), gamma = (B-1)^2/(2 cutoff^2);
+ *     phi(d) = (1 + cos(pi d/cutoff))/2.
+ *   - The neighbour predicate is evaluated in binary32 as d2 = (dx*dx + dy*dy) + dz*dz (each operation
+ *     rounded, no fused multiply-add), 0 < d2 < cutoff*cutoff.
+ *   - An atom without neighbours gets a zero output.
+ *
+ * Memory: every pointer marked "device" is GPU memory owned by the caller; the library never frees it.
+ * Pointers marked "host" are ordinary process memory.  All work is enqueued on the HIP stream passed in
+ * (a hipStream_t cast to void*; NULL is the default stream).  e2f_build_cells and e2f_attn_forward
+ * allocate no device memory and do not synchronise with the host; e2f_attn_forward_materialized,
+ * e2f_count_neighbors and e2f_list_neighbors are measurement/test entry points that may do both.
+ * Errors are reported through the return code; no entry point aborts or throws.  Arguments are checked
+ * before anything is launched.
+ */
+#ifndef E2F_H
+#define E2F_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct e2f_ctx e2f_ctx;     /* configuration + constant tables (host object) */
+typedef struct e2f_cells e2f_cells; /* host handle onto a cell list living in caller-provided device memory */
+
+typedef enum {
+    E2F_OK = 0,
+    E2F_ERR_INVALID_ARG = 1,         /* null pointer, negative size, inconsistent configuration */
+    E2F_ERR_UNSUPPORTED = 2,         /* valid in principle, not implemented (e.g. L_max > 4, lf > 1) */
+    E2F_ERR_WORKSPACE_TOO_SMALL = 3, /* ws_bytes below the value the matching *_workspace_bytes returns */
+    E2F_ERR_HIP = 4,                 /* a HIP runtime call failed */
+    E2F_ERR_OOM = 5                  /* device allocation failed (materialized baseline only) */
+} e2f_status;
+
+typedef enum { E2F_F32 = 0, E2F_BF16 = 1 } e2f_dtype;
+
+typedef struct {
+    int32_t L_max;      /* highest degree, 0..4 */
+    int32_t C;          /* channels per degree; multiple of 16; C <= 64 or C a multiple of 64, C <= 256 */
+    int32_t H;          /* heads; C % H == 0 */
+    int32_t B;          /* radial basis functions, >= 1 */
+    int32_t lf;         /* degree of the geometric filter R^(lf)(r_ij): 0 or 1 */
+    float cutoff;       /* > 0 */
+    int32_t feat_dtype; /* e2f_dtype of h and of the five projection matrices */
+} e2f_config;
+
+typedef struct {
+    /* device; [L_max+1][C_out][C_in], feat_dtype; applied as (W h)[co] = sum_ci W[l][co][ci] h[l,m][ci]  (Eq. qk) */
+    const void *WQ1, *WQ2, *WK1, *WK2, *WV;
+    const float *Wb;     /* device; [H][B] radial bias weights (b(r) of Eq. attn) */
+    const float *w_path; /* device; [L_max+1][L_max+1] indexed [l_in][l_out]; entries off the allowed paths are ignored */
+} e2f_weights;
+
+const char *e2f_status_string(e2f_status s);
+
+/* Validate the configuration and build the constant tables.  *ctx is written only on E2F_OK. */
+e2f_status e2f_create(const e2f_config *cfg, e2f_ctx **ctx);
+void e2f_destroy(e2f_ctx *ctx);
+
+/*
+ * Cell lists (not part of the paper, which takes a padded neighbour table as given in Sec. 3.4; here the
+ * neighbour sets N(i) are found on the GPU from positions).  Every segment [seg_offsets[s], seg_offsets[s+1])
+ * gets its own uniform grid of edge >= cutoff over its bounding box; atoms are ordered by (segment, cell,
+ * atom index).  The result is deterministic.
+ *   pos          device float [N][3]
+ *   seg_offsets  device int32 [S+1], non-decreasing, seg_offsets[0] = 0, seg_offsets[S] = N (not checked on the host)
+ *   ws           device, at least e2f_cells_workspace_bytes(ctx, N, S) bytes, 256-byte aligned; the cell list
+ *                lives there until the caller reuses the memory
+ *   *cells       host handle, release with e2f_cells_destroy (this does not touch ws)
+ */
+size_t e2f_cells_workspace_bytes(const e2f_ctx *ctx, int32_t N, int32_t S);
+e2f_status e2f_build_cells(e2f_ctx *ctx, const float *pos, const int32_t *seg_offsets, int32_t N, int32_t S, void *ws,
+                           size_t ws_bytes, e2f_cells **cells, void *hip_stream);
+void e2f_cells_destroy(e2f_cells *cells);
+
+/*
+ * Neighbour sets as the kernels see them, for checking against a reference (test entry points).
+ *   degree   device int32 [N]: |N(i)| for every atom, in the caller's atom order
+ *   offsets  device int64 [N+1]: exclusive prefix sum of degree
+ *   idx      device int32 [offsets[N]]: the members of N(i) (caller's atom indices), unordered within a row
+ */
+e2f_status e2f_count_neighbors(e2f_ctx *ctx, const e2f_cells *cells, const float *pos, int32_t N, int32_t *degree,
+                               void *hip_stream);
+e2f_status e2f_list_neighbors(e2f_ctx *ctx, const e2f_cells *cells, const float *pos, int32_t N, const int64_t *offsets,
+                              int32_t *idx, void *hip_stream);
+
+/*
+ * The fused forward pass (Sec. 3.4, Algorithm 1, with pair geometry, the edge-frame rotation and the EAAS
+ * re-indexing of Sec. 3.3 evaluated inside the kernel).
+ *   cells        from e2f_build_cells for the same pos / seg_offsets / N / S
+ *   pos          device float [N][3]
+ *   h            device feat_dtype [N][(L_max+1)^2][C]
+ *   out          device float [N][(L_max+1)^2][C], caller's atom order, fully overwritten
+ *   ws           device, at least e2f_attn_workspace_bytes(ctx, N) bytes (a closed-form O(N) size: sorted
+ *                positions, q, k, v), 256-byte aligned
+ * Peak activation memory of the call is ws_bytes + sizeof(out).
+ */
+size_t e2f_attn_workspace_bytes(const e2f_ctx *ctx, int32_t N);
+e2f_status e2f_attn_forward(e2f_ctx *ctx, const e2f_cells *cells, const float *pos, const void *h,
+                            const int32_t *seg_offsets, int32_t N, int32_t S, const e2f_weights *w, float *out,
+                            void *ws, size_t ws_bytes, void *hip_stream);
+
+/*
+ * Edge-centric baseline with the same result: builds the edge list and writes per-edge tensors (geometry,
+ * rotation matrices, scores, attention weights, messages) to device memory, then reduces them per atom -
+ * the "materialize per edge" regime the paper compares against (App. A; Table triton-role).  It allocates
+ * O(E) device memory internally, synchronises with the host, and exists only to compare latency and memory.
+ *   edges_out       host, optional: number of directed pairs E
+ *   peak_bytes_out  host, optional: bytes of device memory the call allocated on top of ws and out
+ */
+e2f_status e2f_attn_forward_materialized(e2f_ctx *ctx, const e2f_cells *cells, const float *pos, const void *h,
+                                         const int32_t *seg_offsets, int32_t N, int32_t S, const e2f_weights *w,
+                                         float *out, void *ws, size_t ws_bytes, void *hip_stream, size_t *edges_out,
+                                         size_t *peak_bytes_out);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* E2F_H */

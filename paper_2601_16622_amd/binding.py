@@ -1,0 +1,228 @@
+"""Thin ctypes binding over libe2f.so: argument marshalling only.
+
+Function names follow include/e2f.h.  PyTorch supplies device memory and the current HIP stream; every step of
+the operator runs inside the library's kernels.  Loading fails loudly when the library has not been built
+(`python -m paper_2601_16622_amd.build`): there is no fallback path.
+"""
+import ctypes
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "csrc", "libe2f.so")
+
+E2F_OK = 0
+E2F_F32, E2F_BF16 = 0, 1
+
+EXPORTS = ["e2f_status_string", "e2f_create", "e2f_destroy", "e2f_cells_workspace_bytes", "e2f_build_cells",
+           "e2f_cells_destroy", "e2f_count_neighbors", "e2f_list_neighbors", "e2f_attn_workspace_bytes",
+           "e2f_attn_forward", "e2f_attn_forward_materialized"]
+
+
+class Config(ctypes.Structure):
+    _fields_ = [("L_max", ctypes.c_int32), ("C", ctypes.c_int32), ("H", ctypes.c_int32), ("B", ctypes.c_int32),
+                ("lf", ctypes.c_int32), ("cutoff", ctypes.c_float), ("feat_dtype", ctypes.c_int32)]
+
+
+class Weights(ctypes.Structure):
+    _fields_ = [(k, ctypes.c_void_p) for k in ("WQ1", "WQ2", "WK1", "WK2", "WV", "Wb", "w_path")]
+
+
+class E2fError(RuntimeError):
+    def __init__(self, code, where):
+        self.code = code
+        super().__init__(f"{where}: {status_string(code)} (status {code})")
+
+
+_lib = None
+
+
+def load():
+    """Load libe2f.so and declare the signatures of include/e2f.h."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is missing - build it with `python -m paper_2601_16622_amd.build`")
+    L = ctypes.CDLL(LIB_PATH)
+    vp, i32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_size_t
+    L.e2f_status_string.argtypes = [ctypes.c_int]
+    L.e2f_status_string.restype = ctypes.c_char_p
+    L.e2f_create.argtypes = [ctypes.POINTER(Config), ctypes.POINTER(vp)]
+    L.e2f_create.restype = ctypes.c_int
+    L.e2f_destroy.argtypes = [vp]
+    L.e2f_destroy.restype = None
+    L.e2f_cells_workspace_bytes.argtypes = [vp, i32, i32]
+    L.e2f_cells_workspace_bytes.restype = sz
+    L.e2f_build_cells.argtypes = [vp, vp, vp, i32, i32, vp, sz, ctypes.POINTER(vp), vp]
+    L.e2f_build_cells.restype = ctypes.c_int
+    L.e2f_cells_destroy.argtypes = [vp]
+    L.e2f_cells_destroy.restype = None
+    L.e2f_count_neighbors.argtypes = [vp, vp, vp, i32, vp, vp]
+    L.e2f_count_neighbors.restype = ctypes.c_int
+    L.e2f_list_neighbors.argtypes = [vp, vp, vp, i32, vp, vp, vp]
+    L.e2f_list_neighbors.restype = ctypes.c_int
+    L.e2f_attn_workspace_bytes.argtypes = [vp, i32]
+    L.e2f_attn_workspace_bytes.restype = sz
+    L.e2f_attn_forward.argtypes = [vp, vp, vp, vp, vp, i32, i32, ctypes.POINTER(Weights), vp, vp, sz, vp]
+    L.e2f_attn_forward.restype = ctypes.c_int
+    L.e2f_attn_forward_materialized.argtypes = [vp, vp, vp, vp, vp, i32, i32, ctypes.POINTER(Weights), vp, vp, sz, vp,
+                                                ctypes.POINTER(sz), ctypes.POINTER(sz)]
+    L.e2f_attn_forward_materialized.restype = ctypes.c_int
+    _lib = L
+    return L
+
+
+def status_string(code):
+    return load().e2f_status_string(int(code)).decode()
+
+
+def _check(code, where):
+    if code != E2F_OK:
+        raise E2fError(code, where)
+
+
+def _stream():
+    import torch
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _ptr(t):
+    return ctypes.c_void_p(t.data_ptr() if t is not None and t.numel() > 0 else 0)
+
+
+def e2f_create(L_max, C, H, B, lf, cutoff, feat_dtype):
+    cfg = Config(L_max, C, H, B, lf, float(cutoff), E2F_BF16 if feat_dtype in ("bf16", E2F_BF16) else E2F_F32)
+    ctx = ctypes.c_void_p()
+    _check(load().e2f_create(ctypes.byref(cfg), ctypes.byref(ctx)), "e2f_create")
+    return ctx
+
+
+def e2f_destroy(ctx):
+    load().e2f_destroy(ctx)
+
+
+def e2f_cells_workspace_bytes(ctx, N, S):
+    return load().e2f_cells_workspace_bytes(ctx, N, S)
+
+
+def e2f_build_cells(ctx, pos, seg_offsets, ws):
+    """pos float32 [N][3], seg_offsets int32 [S+1], ws uint8 workspace (all CUDA tensors).  Returns the cells handle."""
+    N, S = pos.shape[0], seg_offsets.shape[0] - 1
+    cells = ctypes.c_void_p()
+    _check(load().e2f_build_cells(ctx, _ptr(pos), _ptr(seg_offsets), N, S, _ptr(ws), ws.numel(), ctypes.byref(cells),
+                                  _stream()), "e2f_build_cells")
+    return cells
+
+
+def e2f_cells_destroy(cells):
+    load().e2f_cells_destroy(cells)
+
+
+def e2f_count_neighbors(ctx, cells, pos, degree):
+    _check(load().e2f_count_neighbors(ctx, cells, _ptr(pos), pos.shape[0], _ptr(degree), _stream()),
+           "e2f_count_neighbors")
+
+
+def e2f_list_neighbors(ctx, cells, pos, offsets, idx):
+    _check(load().e2f_list_neighbors(ctx, cells, _ptr(pos), pos.shape[0], _ptr(offsets), _ptr(idx), _stream()),
+           "e2f_list_neighbors")
+
+
+def e2f_attn_workspace_bytes(ctx, N):
+    return load().e2f_attn_workspace_bytes(ctx, N)
+
+
+def _weights(w):
+    return Weights(*[w[k].data_ptr() for k in ("WQ1", "WQ2", "WK1", "WK2", "WV", "Wb", "w_path")])
+
+
+def e2f_attn_forward(ctx, cells, pos, h, seg_offsets, weights, out, ws):
+    N, S = pos.shape[0], seg_offsets.shape[0] - 1
+    wt = _weights(weights)
+    _check(load().e2f_attn_forward(ctx, cells, _ptr(pos), _ptr(h), _ptr(seg_offsets), N, S, ctypes.byref(wt),
+                                   _ptr(out), _ptr(ws), ws.numel(), _stream()), "e2f_attn_forward")
+
+
+def e2f_attn_forward_materialized(ctx, cells, pos, h, seg_offsets, weights, out, ws):
+    """Returns (n_edges, peak_bytes_allocated_inside)."""
+    N, S = pos.shape[0], seg_offsets.shape[0] - 1
+    wt = _weights(weights)
+    edges, peak = ctypes.c_size_t(0), ctypes.c_size_t(0)
+    _check(load().e2f_attn_forward_materialized(ctx, cells, _ptr(pos), _ptr(h), _ptr(seg_offsets), N, S,
+                                                ctypes.byref(wt), _ptr(out), _ptr(ws), ws.numel(), _stream(),
+                                                ctypes.byref(edges), ctypes.byref(peak)),
+           "e2f_attn_forward_materialized")
+    return edges.value, peak.value
+
+
+class Problem:
+    """Device-resident copy of one workload (see workloads.py) plus the library objects needed to run it."""
+
+    def __init__(self, wl, device="cuda:0"):
+        import torch
+        cfg = wl["cfg"]
+        self.cfg = cfg
+        self.device = torch.device(device)
+        fdt = torch.bfloat16 if cfg["dtype"] == "bf16" else torch.float32
+        self.N = wl["pos"].shape[0]
+        self.S = wl["seg"].shape[0] - 1
+        self.n = (cfg["L"] + 1) ** 2
+        self.pos = torch.from_numpy(np.ascontiguousarray(wl["pos"], dtype=np.float32)).to(self.device)
+        self.seg = torch.from_numpy(np.ascontiguousarray(wl["seg"], dtype=np.int32)).to(self.device)
+        self.h = torch.from_numpy(np.ascontiguousarray(wl["h"], dtype=np.float32)).to(self.device).to(fdt).contiguous()
+        self.weights = {}
+        for k, v in wl["weights"].items():
+            t = torch.from_numpy(np.ascontiguousarray(v, dtype=np.float32)).to(self.device)
+            self.weights[k] = (t.to(fdt) if k.startswith("W") and k != "Wb" else t).contiguous()
+        self.ctx = e2f_create(cfg["L"], cfg["C"], cfg["H"], cfg["B"], cfg["lf"], cfg["cutoff"], cfg["dtype"])
+        self.cells_ws = torch.empty(max(e2f_cells_workspace_bytes(self.ctx, self.N, self.S), 256), dtype=torch.uint8,
+                                    device=self.device)
+        self.attn_ws = torch.empty(max(e2f_attn_workspace_bytes(self.ctx, self.N), 256), dtype=torch.uint8,
+                                   device=self.device)
+        self.out = torch.empty((self.N, self.n, cfg["C"]), dtype=torch.float32, device=self.device)
+        self.cells = None
+
+    def build_cells(self):
+        if self.cells is not None:
+            e2f_cells_destroy(self.cells)
+        self.cells = e2f_build_cells(self.ctx, self.pos, self.seg, self.cells_ws)
+        return self.cells
+
+    def forward(self):
+        e2f_attn_forward(self.ctx, self.cells, self.pos, self.h, self.seg, self.weights, self.out, self.attn_ws)
+        return self.out
+
+    def forward_materialized(self, out=None):
+        out = self.out if out is None else out
+        return e2f_attn_forward_materialized(self.ctx, self.cells, self.pos, self.h, self.seg, self.weights, out,
+                                             self.attn_ws)
+
+    def neighbors(self):
+        """(degree int32 [N], offsets int64 [N+1], idx int32 [E]) as numpy arrays, rows sorted."""
+        import torch
+        deg = torch.zeros(self.N, dtype=torch.int32, device=self.device)
+        e2f_count_neighbors(self.ctx, self.cells, self.pos, deg)
+        offsets = torch.zeros(self.N + 1, dtype=torch.int64, device=self.device)
+        offsets[1:] = torch.cumsum(deg.to(torch.int64), 0)
+        E = int(offsets[-1].item())
+        idx = torch.full((max(E, 1),), -1, dtype=torch.int32, device=self.device)
+        e2f_list_neighbors(self.ctx, self.cells, self.pos, offsets, idx)
+        torch.cuda.synchronize()
+        offs = offsets.cpu().numpy()
+        idx = idx.cpu().numpy()[:E]
+        for i in range(self.N):
+            idx[offs[i]:offs[i + 1]].sort()
+        return deg.cpu().numpy(), offs, idx
+
+    def activation_bytes(self):
+        return self.attn_ws.numel() + self.out.numel() * 4
+
+    def close(self):
+        if self.cells is not None:
+            e2f_cells_destroy(self.cells)
+            self.cells = None
+        if self.ctx is not None:
+            e2f_destroy(self.ctx)
+            self.ctx = None

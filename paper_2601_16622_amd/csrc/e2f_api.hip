@@ -1,0 +1,223 @@
+// C ABI of libe2f.so: argument checks, workspace layout, and the sequence of launches per entry point.
+#include <math.h>
+#include <new>
+
+#include "e2f_internal.h"
+
+namespace {
+
+bool aligned256(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 255u) == 0; }
+
+// <l m; 1 0 | l' m> for l' = l+1, l, l-1 (textbook closed forms of the Clebsch-Gordan coefficients with
+// j2 = 1, m2 = 0).  These are the non-zero entries of the re-indexing operator P for lf = 1 (Sec. 3.3,
+// Def. of P; App. C): even l_i+l_f+l_o keeps the order m, odd maps -m to m with the sign of m.
+double cg_up(int l, int m) { return sqrt((double)((l + 1 - m) * (l + 1 + m)) / (double)((2 * l + 1) * (l + 1))); }
+double cg_same(int l, int m) { return l == 0 ? 0.0 : (double)m / sqrt((double)(l * (l + 1))); }
+double cg_down(int l, int m) { return l == 0 ? 0.0 : -sqrt((double)((l - m) * (l + m)) / (double)(l * (2 * l + 1))); }
+
+size_t cells_ws_layout(int32_t N, int32_t S, void* ws, e2f_cells* c) {
+    const int32_t max_cells = 27 * S + 2 * N + 1;
+    size_t off = 0;
+    auto take = [&](size_t bytes) {
+        char* p = ws ? static_cast<char*>(ws) + off : nullptr;
+        off += e2f_align_up(bytes);
+        return p;
+    };
+    char* grid = take((size_t)(S > 0 ? S : 1) * sizeof(E2fSegGrid));
+    char* cell_start = take((size_t)(max_cells + 1) * 4);
+    char* perm = take((size_t)N * 4);
+    char* scell = take((size_t)N * 4);
+    char* sseg = take((size_t)N * 4);
+    char* atom_slot = take((size_t)N * 4);
+    char* bbox = take((size_t)(S > 0 ? S : 1) * 6 * 4);
+    char* atom_seg = take((size_t)N * 4);
+    char* atom_cell = take((size_t)N * 4);
+    char* cell_fill = take((size_t)max_cells * 4);
+    char* tmp_slot = take((size_t)N * 4);
+    if (c) {
+        c->view.grid = (const E2fSegGrid*)grid;
+        c->view.cell_start = (const int32_t*)cell_start;
+        c->view.perm = (const int32_t*)perm;
+        c->view.scell = (const int32_t*)scell;
+        c->view.sseg = (const int32_t*)sseg;
+        c->view.atom_slot = (const int32_t*)atom_slot;
+        c->view.N = N;
+        c->view.S = S;
+        c->bbox = (int32_t*)bbox;
+        c->atom_seg = (int32_t*)atom_seg;
+        c->atom_cell = (int32_t*)atom_cell;
+        c->cell_fill = (int32_t*)cell_fill;
+        c->tmp_slot = (int32_t*)tmp_slot;
+        c->max_cells = max_cells;
+    }
+    return off;
+}
+
+e2f_status check_forward_args(const e2f_ctx* ctx, const e2f_cells* cells, const float* pos, const void* h,
+                              const int32_t* seg_offsets, int32_t N, int32_t S, const e2f_weights* w, const float* out,
+                              const void* ws, size_t ws_bytes) {
+    if (!ctx || !cells || !w || N < 0 || S < 0) return E2F_ERR_INVALID_ARG;
+    if (cells->view.N != N || cells->view.S != S) return E2F_ERR_INVALID_ARG;
+    if (N == 0) return E2F_OK;
+    if (!pos || !h || !seg_offsets || !out || !ws) return E2F_ERR_INVALID_ARG;
+    if (cells->pos != pos) return E2F_ERR_INVALID_ARG;
+    if (!w->WQ1 || !w->WQ2 || !w->WK1 || !w->WK2 || !w->WV || !w->Wb || !w->w_path) return E2F_ERR_INVALID_ARG;
+    if (!aligned256(ws)) return E2F_ERR_INVALID_ARG;
+    if ((reinterpret_cast<uintptr_t>(h) & 15u) || (reinterpret_cast<uintptr_t>(out) & 15u)) return E2F_ERR_INVALID_ARG;
+    if (ws_bytes < e2f_attn_workspace_bytes(ctx, N)) return E2F_ERR_WORKSPACE_TOO_SMALL;
+    return E2F_OK;
+}
+
+}  // namespace
+
+E2fAttnWs e2f_attn_ws_layout(const e2f_ctx* ctx, int32_t N, void* ws) {
+    E2fAttnWs L;
+    size_t off = 0;
+    auto take = [&](size_t bytes) {
+        char* p = ws ? static_cast<char*>(ws) + off : nullptr;
+        off += e2f_align_up(bytes);
+        return p;
+    };
+    const size_t esz = ctx->cfg.feat_dtype == E2F_BF16 ? 2 : 4;
+    L.spos = (float4*)take((size_t)N * sizeof(float4));
+    L.q = (float*)take((size_t)N * (ctx->cfg.L_max + 1) * ctx->cfg.C * 4);
+    L.k = (float*)take((size_t)N * (ctx->cfg.L_max + 1) * ctx->cfg.C * 4);
+    L.v = (void*)take((size_t)N * ctx->n * ctx->cfg.C * esz);
+    L.cw = (float*)take((size_t)E2F_MAX_N * 3 * 4);
+    L.bytes = off;
+    return L;
+}
+
+extern "C" {
+
+const char* e2f_status_string(e2f_status s) {
+    switch (s) {
+        case E2F_OK: return "ok";
+        case E2F_ERR_INVALID_ARG: return "invalid argument";
+        case E2F_ERR_UNSUPPORTED: return "unsupported configuration";
+        case E2F_ERR_WORKSPACE_TOO_SMALL: return "workspace too small";
+        case E2F_ERR_HIP: return "HIP runtime error";
+        case E2F_ERR_OOM: return "out of device memory";
+    }
+    return "unknown status";
+}
+
+e2f_status e2f_create(const e2f_config* cfg, e2f_ctx** ctx_out) {
+    if (!cfg || !ctx_out) return E2F_ERR_INVALID_ARG;
+    if (cfg->L_max < 0 || cfg->C <= 0 || cfg->H <= 0 || cfg->B <= 0 || cfg->lf < 0) return E2F_ERR_INVALID_ARG;
+    if (!(cfg->cutoff > 0.0f) || !isfinite(cfg->cutoff)) return E2F_ERR_INVALID_ARG;
+    if (cfg->C % cfg->H != 0) return E2F_ERR_INVALID_ARG;
+    if (cfg->feat_dtype != E2F_F32 && cfg->feat_dtype != E2F_BF16) return E2F_ERR_INVALID_ARG;
+    if (cfg->lf > cfg->L_max && cfg->lf != 0) return E2F_ERR_INVALID_ARG;
+    if (cfg->L_max > E2F_MAX_L || cfg->lf > 1 || cfg->H > E2F_MAX_H) return E2F_ERR_UNSUPPORTED;
+    // channel tiling of the kernels: 16-wide MFMA tiles (32-deep for bf16), lanes over channels in the fused kernel
+    if (cfg->C % 16 != 0 || cfg->C > 256 || (cfg->C > 64 && cfg->C % 64 != 0)) return E2F_ERR_UNSUPPORTED;
+    if (cfg->feat_dtype == E2F_BF16 && cfg->C % 32 != 0) return E2F_ERR_UNSUPPORTED;
+    const int cpl = cfg->C <= 64 ? 1 : cfg->C / 64;
+    const int Ch = cfg->C / cfg->H;
+    if (Ch % cpl != 0) return E2F_ERR_UNSUPPORTED;
+    const int lph = Ch / cpl;  // lanes per head must be a power of two (butterfly reduction of q.k)
+    if ((lph & (lph - 1)) != 0) return E2F_ERR_UNSUPPORTED;
+
+    e2f_ctx* c = new (std::nothrow) e2f_ctx;
+    if (!c) return E2F_ERR_OOM;
+    c->cfg = *cfg;
+    c->n = (cfg->L_max + 1) * (cfg->L_max + 1);
+    c->Ch = Ch;
+    c->cpl = cpl;
+    c->tau = (float)(1.0 / sqrt((double)((cfg->L_max + 1) * Ch)));
+    c->rc2 = cfg->cutoff * cfg->cutoff;  // binary32 product, as the predicate defines it
+    const double bm1 = cfg->B > 1 ? (double)(cfg->B - 1) : 1.0;
+    c->rbf_gamma = (float)(0.5 * bm1 * bm1 / ((double)cfg->cutoff * (double)cfg->cutoff));
+    c->rbf_step = (float)((double)cfg->cutoff / bm1);
+    for (int x = 0; x < E2F_MAX_N; ++x)
+        for (int t = 0; t < 3; ++t) c->coefP[x][t] = 0.0f;
+    for (int lo = 0; lo <= cfg->L_max; ++lo)
+        for (int m = -lo; m <= lo; ++m) {
+            const int comp = lo * lo + lo + m, am = m < 0 ? -m : m;
+            if (cfg->lf == 0) {
+                c->coefP[comp][1] = 1.0f;
+            } else {
+                if (lo >= 1 && am <= lo - 1) c->coefP[comp][0] = (float)cg_up(lo - 1, am);   // l_i = lo-1
+                c->coefP[comp][1] = (float)cg_same(lo, m);                                  // l_i = lo, from -m
+                if (lo + 1 <= cfg->L_max) c->coefP[comp][2] = (float)cg_down(lo + 1, am);    // l_i = lo+1
+            }
+        }
+    *ctx_out = c;
+    return E2F_OK;
+}
+
+void e2f_destroy(e2f_ctx* ctx) { delete ctx; }
+
+size_t e2f_cells_workspace_bytes(const e2f_ctx* ctx, int32_t N, int32_t S) {
+    if (!ctx || N < 0 || S < 0) return 0;
+    return cells_ws_layout(N, S, nullptr, nullptr);
+}
+
+e2f_status e2f_build_cells(e2f_ctx* ctx, const float* pos, const int32_t* seg_offsets, int32_t N, int32_t S, void* ws,
+                           size_t ws_bytes, e2f_cells** cells, void* hip_stream) {
+    if (!ctx || !cells || N < 0 || S < 0) return E2F_ERR_INVALID_ARG;
+    if (N > 0 && (S < 1 || !pos || !seg_offsets || !ws)) return E2F_ERR_INVALID_ARG;
+    if ((int64_t)27 * S + (int64_t)2 * N + 1 > 0x7fffffff) return E2F_ERR_UNSUPPORTED;
+    if (N > 0 && !aligned256(ws)) return E2F_ERR_INVALID_ARG;
+    if (N > 0 && ws_bytes < cells_ws_layout(N, S, nullptr, nullptr)) return E2F_ERR_WORKSPACE_TOO_SMALL;
+    e2f_cells* c = new (std::nothrow) e2f_cells;
+    if (!c) return E2F_ERR_OOM;
+    cells_ws_layout(N, S, ws, c);
+    c->pos = pos;
+    const e2f_status rc = e2f_launch_build_cells(ctx, c, pos, seg_offsets, static_cast<hipStream_t>(hip_stream));
+    if (rc != E2F_OK) {
+        delete c;
+        return rc;
+    }
+    *cells = c;
+    return E2F_OK;
+}
+
+void e2f_cells_destroy(e2f_cells* cells) { delete cells; }
+
+e2f_status e2f_count_neighbors(e2f_ctx* ctx, const e2f_cells* cells, const float* pos, int32_t N, int32_t* degree,
+                               void* hip_stream) {
+    if (!ctx || !cells || N != cells->view.N) return E2F_ERR_INVALID_ARG;
+    if (N > 0 && (!pos || !degree || pos != cells->pos)) return E2F_ERR_INVALID_ARG;
+    return e2f_launch_count_neighbors(ctx, cells->view, pos, degree, static_cast<hipStream_t>(hip_stream));
+}
+
+e2f_status e2f_list_neighbors(e2f_ctx* ctx, const e2f_cells* cells, const float* pos, int32_t N, const int64_t* offsets,
+                              int32_t* idx, void* hip_stream) {
+    if (!ctx || !cells || N != cells->view.N) return E2F_ERR_INVALID_ARG;
+    if (N > 0 && (!pos || !offsets || !idx || pos != cells->pos)) return E2F_ERR_INVALID_ARG;
+    return e2f_launch_list_neighbors(ctx, cells->view, pos, offsets, idx, static_cast<hipStream_t>(hip_stream));
+}
+
+size_t e2f_attn_workspace_bytes(const e2f_ctx* ctx, int32_t N) {
+    if (!ctx || N < 0) return 0;
+    return e2f_attn_ws_layout(ctx, N, nullptr).bytes;
+}
+
+e2f_status e2f_attn_forward(e2f_ctx* ctx, const e2f_cells* cells, const float* pos, const void* h,
+                            const int32_t* seg_offsets, int32_t N, int32_t S, const e2f_weights* w, float* out,
+                            void* ws, size_t ws_bytes, void* hip_stream) {
+    e2f_status rc = check_forward_args(ctx, cells, pos, h, seg_offsets, N, S, w, out, ws, ws_bytes);
+    if (rc != E2F_OK || N == 0) return rc;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    const E2fAttnWs L = e2f_attn_ws_layout(ctx, N, ws);
+    if ((rc = e2f_launch_prepare(ctx, cells->view, pos, w, L, st)) != E2F_OK) return rc;
+    if ((rc = e2f_launch_project_mfma(ctx, cells->view, h, w, L, st)) != E2F_OK) return rc;
+    return e2f_launch_fused(ctx, cells->view, w, L, out, st);
+}
+
+e2f_status e2f_attn_forward_materialized(e2f_ctx* ctx, const e2f_cells* cells, const float* pos, const void* h,
+                                         const int32_t* seg_offsets, int32_t N, int32_t S, const e2f_weights* w,
+                                         float* out, void* ws, size_t ws_bytes, void* hip_stream, size_t* edges_out,
+                                         size_t* peak_bytes_out) {
+    e2f_status rc = check_forward_args(ctx, cells, pos, h, seg_offsets, N, S, w, out, ws, ws_bytes);
+    if (edges_out) *edges_out = 0;
+    if (peak_bytes_out) *peak_bytes_out = 0;
+    if (rc != E2F_OK || N == 0) return rc;
+    const E2fAttnWs L = e2f_attn_ws_layout(ctx, N, ws);
+    return e2f_run_materialized(ctx, cells->view, pos, h, w, L, out, static_cast<hipStream_t>(hip_stream), edges_out,
+                                peak_bytes_out);
+}
+
+}  // extern "C"

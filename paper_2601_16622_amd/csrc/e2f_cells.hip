@@ -1,0 +1,260 @@
+// GPU cell lists: per-segment bounding boxes, grids of edge >= cutoff, a deterministic counting sort of the
+// atoms by (segment, cell, atom index), and the neighbour-set test kernels that walk the result.
+#include <limits.h>
+
+#include "e2f_device.h"
+
+namespace {
+
+__device__ __forceinline__ int float_to_ordered(float f) {
+    int i = __float_as_int(f);
+    return i >= 0 ? i : i ^ 0x7fffffff;
+}
+__device__ __forceinline__ float ordered_to_float(int i) { return __int_as_float(i >= 0 ? i : i ^ 0x7fffffff); }
+
+__global__ void k_cells_init(int32_t* bbox, int S, int32_t* cell_start, int32_t* cell_fill, int max_cells) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < S * 6) bbox[i] = (i % 6 < 3) ? INT_MAX : INT_MIN;
+    if (i <= max_cells) cell_start[i] = 0;
+    if (i < max_cells) cell_fill[i] = 0;
+}
+
+// Segment of every atom (binary search in the offsets) and the segment bounding boxes.
+__global__ void k_cells_bbox(const float* __restrict__ pos, const int32_t* __restrict__ seg_offsets, int N, int S,
+                             int32_t* __restrict__ atom_seg, int32_t* __restrict__ bbox) {
+    const int a = blockIdx.x * blockDim.x + threadIdx.x;
+    const bool live = a < N;
+    int s = 0;
+    float x = 0.f, y = 0.f, z = 0.f;
+    if (live) {
+        int lo = 0, hi = S;  // largest s with seg_offsets[s] <= a
+        while (hi - lo > 1) {
+            const int mid = (lo + hi) >> 1;
+            if (seg_offsets[mid] <= a) lo = mid; else hi = mid;
+        }
+        s = lo;
+        atom_seg[a] = s;
+        x = pos[3 * a]; y = pos[3 * a + 1]; z = pos[3 * a + 2];
+    }
+    // one set of atomics per wave when the whole wave sits in one segment
+    const int s0 = __shfl(s, 0);
+    const bool uniform = __all(live && s == s0);
+    if (uniform) {
+        float mnx = x, mny = y, mnz = z, mxx = x, mxy = y, mxz = z;
+        for (int off = 32; off > 0; off >>= 1) {
+            mnx = fminf(mnx, __shfl_xor(mnx, off)); mny = fminf(mny, __shfl_xor(mny, off));
+            mnz = fminf(mnz, __shfl_xor(mnz, off)); mxx = fmaxf(mxx, __shfl_xor(mxx, off));
+            mxy = fmaxf(mxy, __shfl_xor(mxy, off)); mxz = fmaxf(mxz, __shfl_xor(mxz, off));
+        }
+        if ((threadIdx.x & 63) == 0) {
+            atomicMin(&bbox[s * 6 + 0], float_to_ordered(mnx)); atomicMin(&bbox[s * 6 + 1], float_to_ordered(mny));
+            atomicMin(&bbox[s * 6 + 2], float_to_ordered(mnz)); atomicMax(&bbox[s * 6 + 3], float_to_ordered(mxx));
+            atomicMax(&bbox[s * 6 + 4], float_to_ordered(mxy)); atomicMax(&bbox[s * 6 + 5], float_to_ordered(mxz));
+        }
+    } else if (live) {
+        atomicMin(&bbox[s * 6 + 0], float_to_ordered(x)); atomicMin(&bbox[s * 6 + 1], float_to_ordered(y));
+        atomicMin(&bbox[s * 6 + 2], float_to_ordered(z)); atomicMax(&bbox[s * 6 + 3], float_to_ordered(x));
+        atomicMax(&bbox[s * 6 + 4], float_to_ordered(y)); atomicMax(&bbox[s * 6 + 5], float_to_ordered(z));
+    }
+}
+
+// One block: grid of every segment (edge doubled until the segment stays within its cell budget of
+// 27 + 2 * atoms, so the total never exceeds the workspace), then an exclusive scan of the cell counts.
+__global__ void k_cells_grid(const int32_t* __restrict__ bbox, const int32_t* __restrict__ seg_offsets, int S,
+                             float edge0, E2fSegGrid* __restrict__ grid) {
+    __shared__ int s_part[1024];
+    __shared__ int s_carry;
+    if (threadIdx.x == 0) s_carry = 0;
+    __syncthreads();
+    for (int s0 = 0; s0 < S; s0 += blockDim.x) {
+        const int s = s0 + threadIdx.x;
+        int cells = 0;
+        E2fSegGrid g = {0.f, 0.f, 0.f, 1.f, 1, 1, 1, 0};
+        if (s < S) {
+            const int ns = seg_offsets[s + 1] - seg_offsets[s];
+            cells = 1;  // an empty segment keeps one empty cell
+            if (ns > 0) {
+                const float mnx = ordered_to_float(bbox[s * 6 + 0]), mny = ordered_to_float(bbox[s * 6 + 1]);
+                const float mnz = ordered_to_float(bbox[s * 6 + 2]), mxx = ordered_to_float(bbox[s * 6 + 3]);
+                const float mxy = ordered_to_float(bbox[s * 6 + 4]), mxz = ordered_to_float(bbox[s * 6 + 5]);
+                const long long budget = 27ll + 2ll * ns;
+                float edge = edge0;
+                long long nx = 1, ny = 1, nz = 1;
+                bool fits = false;
+                for (int it = 0; it < 200 && !fits; ++it) {  // bounded: edge overflows to inf long before
+                    nx = (long long)floorf((mxx - mnx) / edge) + 1;
+                    ny = (long long)floorf((mxy - mny) / edge) + 1;
+                    nz = (long long)floorf((mxz - mnz) / edge) + 1;
+                    fits = nx >= 1 && ny >= 1 && nz >= 1 && nx <= budget && ny <= budget && nz <= budget &&
+                           nx * ny * nz <= budget;
+                    if (!fits) edge *= 2.0f;
+                }
+                if (!fits) {  // non-finite coordinates: one cell holds the whole segment
+                    nx = ny = nz = 1;
+                    edge = edge0;
+                }
+                g.ox = mnx; g.oy = mny; g.oz = mnz; g.inv_edge = 1.0f / edge;
+                g.nx = (int)nx; g.ny = (int)ny; g.nz = (int)nz;
+                cells = (int)(nx * ny * nz);
+            }
+        }
+        // block-wide exclusive scan of `cells`
+        s_part[threadIdx.x] = cells;
+        __syncthreads();
+        for (int off = 1; off < (int)blockDim.x; off <<= 1) {
+            int v = (threadIdx.x >= (unsigned)off) ? s_part[threadIdx.x - off] : 0;
+            __syncthreads();
+            s_part[threadIdx.x] += v;
+            __syncthreads();
+        }
+        const int incl = s_part[threadIdx.x];
+        const int carry = s_carry;
+        if (s < S) {
+            g.base = carry + incl - cells;
+            grid[s] = g;
+        }
+        __syncthreads();
+        if (threadIdx.x == blockDim.x - 1) s_carry = carry + incl;
+        __syncthreads();
+    }
+}
+
+__global__ void k_cells_assign(const float* __restrict__ pos, const int32_t* __restrict__ atom_seg,
+                               const E2fSegGrid* __restrict__ grid, int N, int32_t* __restrict__ atom_cell,
+                               int32_t* __restrict__ cell_count /* = cell_start + 1 */) {
+    const int a = blockIdx.x * blockDim.x + threadIdx.x;
+    if (a >= N) return;
+    const E2fSegGrid g = grid[atom_seg[a]];
+    int cx = (int)floorf((pos[3 * a] - g.ox) * g.inv_edge);
+    int cy = (int)floorf((pos[3 * a + 1] - g.oy) * g.inv_edge);
+    int cz = (int)floorf((pos[3 * a + 2] - g.oz) * g.inv_edge);
+    cx = min(max(cx, 0), g.nx - 1); cy = min(max(cy, 0), g.ny - 1); cz = min(max(cz, 0), g.nz - 1);
+    const int c = g.base + (cz * g.ny + cy) * g.nx + cx;
+    atom_cell[a] = c;
+    atomicAdd(&cell_count[c], 1);
+}
+
+// One block: in-place inclusive scan of data[0..n) (data[0] is 0, data[c+1] the count of cell c), which turns
+// the counts into first-slot offsets.
+__global__ void k_cells_scan(int32_t* __restrict__ data, int n) {
+    __shared__ int s_part[1024];
+    __shared__ int s_carry;
+    if (threadIdx.x == 0) s_carry = 0;
+    __syncthreads();
+    for (int i0 = 0; i0 < n; i0 += blockDim.x) {
+        const int i = i0 + threadIdx.x;
+        const int val = (i < n) ? data[i] : 0;
+        s_part[threadIdx.x] = val;
+        __syncthreads();
+        for (int off = 1; off < (int)blockDim.x; off <<= 1) {
+            int v = (threadIdx.x >= (unsigned)off) ? s_part[threadIdx.x - off] : 0;
+            __syncthreads();
+            s_part[threadIdx.x] += v;
+            __syncthreads();
+        }
+        const int incl = s_part[threadIdx.x];
+        const int carry = s_carry;
+        if (i < n) data[i] = carry + incl;
+        __syncthreads();
+        if (threadIdx.x == blockDim.x - 1) s_carry = carry + incl;
+        __syncthreads();
+    }
+}
+
+__global__ void k_cells_scatter(const int32_t* __restrict__ atom_cell, const int32_t* __restrict__ cell_start, int N,
+                                int32_t* __restrict__ cell_fill, int32_t* __restrict__ tmp_slot) {
+    const int a = blockIdx.x * blockDim.x + threadIdx.x;
+    if (a >= N) return;
+    const int c = atom_cell[a];
+    tmp_slot[cell_start[c] + atomicAdd(&cell_fill[c], 1)] = a;
+}
+
+// The scatter above fills each cell in arrival order; ranking every atom among its cell mates by atom index
+// makes the final order independent of that.
+__global__ void k_cells_rank(const int32_t* __restrict__ tmp_slot, const int32_t* __restrict__ atom_cell,
+                             const int32_t* __restrict__ atom_seg, const int32_t* __restrict__ cell_start, int N,
+                             int32_t* __restrict__ perm, int32_t* __restrict__ scell, int32_t* __restrict__ sseg,
+                             int32_t* __restrict__ atom_slot) {
+    const int t = blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= N) return;
+    const int a = tmp_slot[t];
+    const int c = atom_cell[a];
+    const int b = cell_start[c], e = cell_start[c + 1];
+    int rank = 0;
+    for (int u = b; u < e; ++u) rank += (tmp_slot[u] < a) ? 1 : 0;
+    perm[b + rank] = a;
+    scell[b + rank] = c;
+    sseg[b + rank] = atom_seg[a];
+    atom_slot[a] = b + rank;
+}
+
+// One wave per target: walk the 27-cell stencil 64 candidates at a time.
+template <bool LIST>
+__global__ __launch_bounds__(64) void k_neighbors(E2fCellsView cv, const float* __restrict__ pos, float rc2,
+                                                  int32_t* __restrict__ degree, const int64_t* __restrict__ offsets,
+                                                  int32_t* __restrict__ idx) {
+    const int t = blockIdx.x, lane = threadIdx.x;
+    const int ai = cv.perm[t];
+    const float xi = pos[3 * ai], yi = pos[3 * ai + 1], zi = pos[3 * ai + 2];
+    int lo[9], hi[9];
+    e2f::stencil_rows(cv, t, lo, hi);
+    int cnt = 0;
+    const int64_t out0 = LIST ? offsets[ai] : 0;
+    for (int r = 0; r < 9; ++r)
+        for (int base = lo[r]; base < hi[r]; base += 64) {
+            const int j = base + lane;
+            bool ok = false;
+            int aj = 0;
+            if (j < hi[r] && j != t) {
+                aj = cv.perm[j];
+                ok = e2f::is_neighbor(e2f::dist2_exact(xi, yi, zi, pos[3 * aj], pos[3 * aj + 1], pos[3 * aj + 2]), rc2);
+            }
+            const unsigned long long mask = __ballot(ok);
+            if (LIST && ok) idx[out0 + cnt + __popcll(mask & ((1ull << lane) - 1ull))] = aj;
+            cnt += __popcll(mask);
+        }
+    if (!LIST && lane == 0) degree[ai] = cnt;
+}
+
+}  // namespace
+
+e2f_status e2f_launch_build_cells(const e2f_ctx* ctx, e2f_cells* c, const float* pos, const int32_t* seg_offsets,
+                                  hipStream_t st) {
+    const int N = c->view.N, S = c->view.S;
+    if (N == 0) return E2F_OK;
+    const int tb = 256;
+    int32_t* cell_start = const_cast<int32_t*>(c->view.cell_start);
+    const int n_init = c->max_cells + 1 > S * 6 ? c->max_cells + 1 : S * 6;
+    k_cells_init<<<(n_init + tb - 1) / tb, tb, 0, st>>>(c->bbox, S, cell_start, c->cell_fill, c->max_cells);
+    k_cells_bbox<<<(N + tb - 1) / tb, tb, 0, st>>>(pos, seg_offsets, N, S, c->atom_seg, c->bbox);
+    // edge a hair above the cutoff: the binary32 predicate can accept a pair whose exact |dx| exceeds the
+    // cutoff by rounding, and cell coordinates carry rounding of their own
+    k_cells_grid<<<1, 1024, 0, st>>>(c->bbox, seg_offsets, S, ctx->cfg.cutoff * 1.0001f,
+                                     const_cast<E2fSegGrid*>(c->view.grid));
+    k_cells_assign<<<(N + tb - 1) / tb, tb, 0, st>>>(pos, c->atom_seg, c->view.grid, N, c->atom_cell, cell_start + 1);
+    k_cells_scan<<<1, 1024, 0, st>>>(cell_start, c->max_cells + 1);
+    k_cells_scatter<<<(N + tb - 1) / tb, tb, 0, st>>>(c->atom_cell, cell_start, N, c->cell_fill, c->tmp_slot);
+    k_cells_rank<<<(N + tb - 1) / tb, tb, 0, st>>>(c->tmp_slot, c->atom_cell, c->atom_seg, cell_start, N,
+                                                  const_cast<int32_t*>(c->view.perm),
+                                                  const_cast<int32_t*>(c->view.scell),
+                                                  const_cast<int32_t*>(c->view.sseg),
+                                                  const_cast<int32_t*>(c->view.atom_slot));
+    E2F_HIP_CHECK(hipGetLastError());
+    return E2F_OK;
+}
+
+e2f_status e2f_launch_count_neighbors(const e2f_ctx* ctx, const E2fCellsView& cv, const float* pos, int32_t* degree,
+                                      hipStream_t st) {
+    if (cv.N == 0) return E2F_OK;
+    k_neighbors<false><<<cv.N, 64, 0, st>>>(cv, pos, ctx->rc2, degree, nullptr, nullptr);
+    E2F_HIP_CHECK(hipGetLastError());
+    return E2F_OK;
+}
+
+e2f_status e2f_launch_list_neighbors(const e2f_ctx* ctx, const E2fCellsView& cv, const float* pos,
+                                     const int64_t* offsets, int32_t* idx, hipStream_t st) {
+    if (cv.N == 0) return E2F_OK;
+    k_neighbors<true><<<cv.N, 64, 0, st>>>(cv, pos, ctx->rc2, nullptr, offsets, idx);
+    E2F_HIP_CHECK(hipGetLastError());
+    return E2F_OK;
+}

@@ -1,0 +1,225 @@
+// Device-side building blocks: cutoff predicate, stencil walk over the cell list, pair geometry,
+// Wigner matrices of the edge-aligning rotation, and the EAAS message for a lane's channels.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include "e2f_internal.h"
+#include "e2f_wigner_gen.h"
+
+namespace e2f {
+
+// Offset of the degree-l block in a packed array of (2l+1)x(2l+1) matrices: sum_{l'<l} (2l'+1)^2.
+__host__ __device__ constexpr int d_offset(int l) { return l * (4 * l * l - 1) / 3; }
+
+// Squared distance exactly as the neighbour predicate defines it: every operation rounded to binary32,
+// no fused multiply-add, order (dx*dx + dy*dy) + dz*dz.
+__device__ __forceinline__ float dist2_exact(float xi, float yi, float zi, float xj, float yj, float zj) {
+#pragma clang fp contract(off)
+    float dx = xj - xi;
+    float dy = yj - yi;
+    float dz = zj - zi;
+    float xx = dx * dx;
+    float yy = dy * dy;
+    float zz = dz * dz;
+    float s = xx + yy;
+    return s + zz;
+}
+
+__device__ __forceinline__ bool is_neighbor(float d2, float rc2) { return d2 < rc2 && d2 > 0.0f; }
+
+// The 27-cell stencil of a target as 9 contiguous runs of sorted slots (cells along x are adjacent in the
+// sorted order).  Runs that fall outside the segment's grid come back empty.
+__device__ __forceinline__ void stencil_rows(const E2fCellsView& cv, int slot, int (&lo)[9], int (&hi)[9]) {
+    const E2fSegGrid g = cv.grid[cv.sseg[slot]];
+    const int local = cv.scell[slot] - g.base;
+    const int cx = local % g.nx;
+    const int cy = (local / g.nx) % g.ny;
+    const int cz = local / (g.nx * g.ny);
+    const int x0 = max(cx - 1, 0), x1 = min(cx + 1, g.nx - 1);
+#pragma unroll
+    for (int r = 0; r < 9; ++r) {
+        const int y = cy + (r % 3) - 1, z = cz + (r / 3) - 1;
+        if (y < 0 || y >= g.ny || z < 0 || z >= g.nz) {
+            lo[r] = 0;
+            hi[r] = 0;
+        } else {
+            const int row = g.base + (z * g.ny + y) * g.nx;
+            lo[r] = cv.cell_start[row + x0];
+            hi[r] = cv.cell_start[row + x1 + 1];
+        }
+    }
+}
+
+template <int l>
+__device__ __forceinline__ void delta_align(const float* c, const float* s, float* d) {
+    if constexpr (l == 0) e2f_delta_align_l0(c, s, d);
+    if constexpr (l == 1) e2f_delta_align_l1(c, s, d);
+    if constexpr (l == 2) e2f_delta_align_l2(c, s, d);
+    if constexpr (l == 3) e2f_delta_align_l3(c, s, d);
+    if constexpr (l == 4) e2f_delta_align_l4(c, s, d);
+}
+
+// Degree-l block of D(R), R = Ry(-theta) Rz(-phi) (the rotation taking r/|r| to +z; Sec. 3.3), in the
+// real basis with Y(R x) = D(R) Y(x):  D = Delta(-theta) Z(-phi), Delta from the generated series and Z
+// the rotation of each (m,-m) pair by m*phi.  ck/sk = cos/sin(k theta), cm/sm = cos/sin(m phi).
+template <int l>
+__device__ __forceinline__ void align_block(const float* ck, const float* sk, const float* cm, const float* sm, float* D) {
+    constexpr int n = 2 * l + 1;
+    float dl[n * n];
+    delta_align<l>(ck, sk, dl);
+#pragma unroll
+    for (int a = 0; a <= l; ++a) {  // cosine-type rows
+        D[(a + l) * n + l] = dl[(a + l) * n + l];
+#pragma unroll
+        for (int m = 1; m <= l; ++m) {
+            D[(a + l) * n + l + m] = dl[(a + l) * n + l + m] * cm[m];
+            D[(a + l) * n + l - m] = dl[(a + l) * n + l + m] * sm[m];
+        }
+    }
+#pragma unroll
+    for (int a = 1; a <= l; ++a) {  // sine-type rows
+        D[(l - a) * n + l] = 0.0f;
+#pragma unroll
+        for (int m = 1; m <= l; ++m) {
+            D[(l - a) * n + l + m] = -dl[(l - a) * n + l - m] * sm[m];
+            D[(l - a) * n + l - m] = dl[(l - a) * n + l - m] * cm[m];
+        }
+    }
+}
+
+template <int L, int l = 0>
+__device__ __forceinline__ void align_all_blocks(const float* ck, const float* sk, const float* cm, const float* sm,
+                                                 float* D) {
+    align_block<l>(ck, sk, cm, sm, D + d_offset(l));
+    if constexpr (l < L) align_all_blocks<L, l + 1>(ck, sk, cm, sm, D);
+}
+
+// All blocks l = 0..L of D(R_ij) for the pair vector (dx,dy,dz) of length d > 0, packed at d_offset(l).
+template <int L>
+__device__ __forceinline__ void align_D(float dx, float dy, float dz, float d, float* D) {
+    const float inv = 1.0f / d;
+    const float rho = sqrtf(dx * dx + dy * dy);
+    const float ct = dz * inv, st = rho * inv;
+    float cp = 1.0f, sp = 0.0f;
+    if (rho > 0.0f) {
+        const float ir = 1.0f / rho;
+        cp = dx * ir;
+        sp = dy * ir;
+    }
+    float ck[E2F_MAX_L + 1], sk[E2F_MAX_L + 1], cm[E2F_MAX_L + 1], sm[E2F_MAX_L + 1];
+    ck[0] = 1.0f; sk[0] = 0.0f; cm[0] = 1.0f; sm[0] = 0.0f;
+#pragma unroll
+    for (int k = 1; k <= L; ++k) {
+        ck[k] = ck[k - 1] * ct - sk[k - 1] * st;
+        sk[k] = sk[k - 1] * ct + ck[k - 1] * st;
+        cm[k] = cm[k - 1] * cp - sm[k - 1] * sp;
+        sm[k] = sm[k - 1] * cp + cm[k - 1] * sp;
+    }
+    align_all_blocks<L>(ck, sk, cm, sm, D);
+}
+
+// Radial pieces of Eq. attn: gate phi(d) and the Gaussian basis value g_b(d).
+__device__ __forceinline__ float radial_gate(float d, float cutoff) {
+    return 0.5f * (1.0f + cosf(3.14159265358979323846f * d / cutoff));
+}
+__device__ __forceinline__ float radial_basis(float d, int b, float step, float gamma) {
+    const float t = d - (float)b * step;
+    return __expf(-gamma * t * t);
+}
+
+__device__ __forceinline__ float bf16_bits_to_float(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
+__device__ __forceinline__ uint16_t float_to_bf16_bits(float f) {  // round to nearest even
+    uint32_t u = __float_as_uint(f);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+template <typename T>
+__device__ __forceinline__ float load_as_float(const T* p);
+template <>
+__device__ __forceinline__ float load_as_float<float>(const float* p) { return *p; }
+template <>
+__device__ __forceinline__ float load_as_float<uint16_t>(const uint16_t* p) { return bf16_bits_to_float(*p); }
+
+template <typename T>
+__device__ __forceinline__ void store_from_float(T* p, float x);
+template <>
+__device__ __forceinline__ void store_from_float<float>(float* p, float x) { *p = x; }
+template <>
+__device__ __forceinline__ void store_from_float<uint16_t>(uint16_t* p, float x) { *p = float_to_bf16_bits(x); }
+
+// EAAS message for NC channels held by one thread, accumulated into acc (Prop. EAAS, Sec. 3.3):
+//   acc[lo] += D^T ( wgt * P( D v ) ),  P from cw[(comp)*3 + {lo-1, lo, lo+1}] (path weights included).
+// Dp points at the packed blocks of D(R_ij); `wgt` already contains |r|^lf and the attention weight.
+// LF = 0 needs no rotation (P is the identity on each degree).
+template <int L, int LF, int NC, typename DPtr>
+__device__ __forceinline__ void eaas_accumulate(const float (&v)[(L + 1) * (L + 1)][NC], DPtr Dp, const float* cw,
+                                                float wgt, float (&acc)[(L + 1) * (L + 1)][NC]) {
+    constexpr int n = (L + 1) * (L + 1);
+    if constexpr (LF == 0) {
+#pragma unroll
+        for (int x = 0; x < n; ++x) {
+            const float f = wgt * cw[x * 3 + 1];
+#pragma unroll
+            for (int u = 0; u < NC; ++u) acc[x][u] += f * v[x][u];
+        }
+    } else {
+        float vt[n][NC];
+#pragma unroll
+        for (int l = 0; l <= L; ++l) {
+            const int nl = 2 * l + 1, base = l * l, off = d_offset(l);
+#pragma unroll
+            for (int a = 0; a < nl; ++a) {
+#pragma unroll
+                for (int u = 0; u < NC; ++u) vt[base + a][u] = 0.0f;
+#pragma unroll
+                for (int b = 0; b < nl; ++b) {
+                    if (a < l && b == l) continue;  // sine-type rows have no m = 0 column
+                    const float dab = Dp[off + a * nl + b];
+#pragma unroll
+                    for (int u = 0; u < NC; ++u) vt[base + a][u] += dab * v[base + b][u];
+                }
+            }
+        }
+#pragma unroll
+        for (int lo = 0; lo <= L; ++lo) {
+            const int nl = 2 * lo + 1, base = lo * lo, off = d_offset(lo);
+            float y[2 * L + 1][NC];
+#pragma unroll
+            for (int a = 0; a < nl; ++a) {
+                const int m = a - lo, am = m < 0 ? -m : m;
+#pragma unroll
+                for (int u = 0; u < NC; ++u) y[a][u] = 0.0f;
+                if (lo >= 1 && am <= lo - 1) {  // from degree lo-1, same order
+                    const float c = cw[(base + a) * 3 + 0];
+#pragma unroll
+                    for (int u = 0; u < NC; ++u) y[a][u] += c * vt[(lo - 1) * (lo - 1) + (lo - 1) + m][u];
+                }
+                if (lo >= 1 && m != 0) {  // from degree lo, opposite order
+                    const float c = cw[(base + a) * 3 + 1];
+#pragma unroll
+                    for (int u = 0; u < NC; ++u) y[a][u] += c * vt[base + lo - m][u];
+                }
+                if (lo + 1 <= L) {  // from degree lo+1, same order
+                    const float c = cw[(base + a) * 3 + 2];
+#pragma unroll
+                    for (int u = 0; u < NC; ++u) y[a][u] += c * vt[(lo + 1) * (lo + 1) + (lo + 1) + m][u];
+                }
+#pragma unroll
+                for (int u = 0; u < NC; ++u) y[a][u] *= wgt;
+            }
+#pragma unroll
+            for (int a = 0; a < nl; ++a) {
+#pragma unroll
+                for (int b = 0; b < nl; ++b) {
+                    if (a < lo && b == lo) continue;
+                    const float dab = Dp[off + a * nl + b];
+#pragma unroll
+                    for (int u = 0; u < NC; ++u) acc[base + b][u] += dab * y[a][u];
+                }
+            }
+        }
+    }
+}
+
+}  // namespace e2f

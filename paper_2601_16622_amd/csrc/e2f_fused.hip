@@ -1,0 +1,218 @@
+// Fused on-the-fly equivariant attention (Sec. 3.4, Algorithm 1) with the pair geometry, the edge-frame
+// rotation and the EAAS re-indexing (Sec. 3.3) evaluated inside the kernel.
+//
+// k_fused_valu: one wave per target atom, lanes over channels (CPL channels per lane).  The wave walks the
+// target's 27-cell stencil 64 candidates at a time, keeps the slots that pass the cutoff predicate in an LDS
+// list, and consumes the list in chunks of PB pairs:
+//   lanes 0..PB-1   build one pair each: D(R_ij) blocks, radial bias per head, gate * |r|^lf   -> LDS
+//   all lanes       logits of the chunk (q.k reduced over the lanes of a head), chunk maximum, one rescale
+//                   of the running (mu, z, A) per chunk, then per pair: A += e^{s-mu} phi D^T P D v_j
+// Nothing per pair is written to global memory; out_i = A/z is stored once, in the caller's atom order.
+#include "e2f_device.h"
+
+namespace {
+
+struct FusedParams {
+    E2fCellsView cv;
+    const float4* spos;
+    const float* q;
+    const float* k;
+    const void* v;
+    const float* cw;
+    const float* Wb;
+    float* out;
+    int C, H, B, Ch;
+    float tau, rc2, cutoff, rbf_step, rbf_gamma;
+};
+
+constexpr int PB = 16;    // pairs per chunk
+constexpr int CAP = 192;  // capacity of the neighbour list in LDS
+
+template <int L, int LF, int CPL, typename VT>
+__global__ __launch_bounds__(64) void k_fused_valu(FusedParams P) {
+    constexpr int n = (L + 1) * (L + 1);
+    constexpr int DS = e2f::d_offset(L + 1);
+    constexpr int DSP = (DS + 3) & ~3;
+    __shared__ int s_list[CAP];
+    __shared__ __attribute__((aligned(16))) float s_D[PB * DSP];
+    __shared__ float s_bias[PB * E2F_MAX_H];
+    __shared__ float s_wgt[PB];
+
+    const int t = blockIdx.x, lane = threadIdx.x;
+    const int C = P.C, H = P.H;
+    const int nlanes = C / CPL;
+    const bool active = lane < nlanes;
+    const int c0 = active ? lane * CPL : 0;  // idle lanes shadow lane 0's loads and store nothing
+    const int head = c0 / P.Ch;
+    const int lanes_per_head = P.Ch / CPL;
+    const float4 pi = P.spos[t];
+
+    float q[L + 1][CPL];
+#pragma unroll
+    for (int l = 0; l <= L; ++l)
+#pragma unroll
+        for (int u = 0; u < CPL; ++u) q[l][u] = P.q[((size_t)t * (L + 1) + l) * C + c0 + u];
+
+    float A[n][CPL];
+#pragma unroll
+    for (int x = 0; x < n; ++x)
+#pragma unroll
+        for (int u = 0; u < CPL; ++u) A[x][u] = 0.0f;
+    float mu = -INFINITY, z = 0.0f;
+
+    int lo[9], hi[9];
+    e2f::stencil_rows(P.cv, t, lo, hi);
+
+    int row = 0, base = lo[0];
+    bool rows_done = false;
+    while (true) {
+        // ---- fill the list
+        int cnt = 0;
+        while (!rows_done && cnt + 64 <= CAP) {
+            if (base >= hi[row]) {
+                ++row;
+                if (row == 9) { rows_done = true; break; }
+                base = lo[row];
+                continue;
+            }
+            const int j = base + lane;
+            bool ok = false;
+            if (j < hi[row] && j != t) {
+                const float4 pj = P.spos[j];
+                ok = e2f::is_neighbor(e2f::dist2_exact(pi.x, pi.y, pi.z, pj.x, pj.y, pj.z), P.rc2);
+            }
+            const unsigned long long mask = __ballot(ok);
+            if (ok) s_list[cnt + __popcll(mask & ((1ull << lane) - 1ull))] = j;
+            cnt += __popcll(mask);
+            base += 64;
+        }
+        __syncthreads();
+        // ---- consume it
+        for (int p0 = 0; p0 < cnt; p0 += PB) {
+            const int np = min(PB, cnt - p0);
+            if (lane < np) {
+                const int j = s_list[p0 + lane];
+                const float4 pj = P.spos[j];
+                const float dx = pj.x - pi.x, dy = pj.y - pi.y, dz = pj.z - pi.z;
+                const float d = sqrtf(dx * dx + dy * dy + dz * dz);
+                if constexpr (LF != 0) {
+                    float D[DS];
+                    e2f::align_D<L>(dx, dy, dz, d, D);
+#pragma unroll
+                    for (int e = 0; e < DS; ++e) s_D[lane * DSP + e] = D[e];
+                }
+                for (int hh = 0; hh < H; ++hh) {
+                    float acc = 0.0f;
+                    for (int b = 0; b < P.B; ++b) acc += P.Wb[hh * P.B + b] * e2f::radial_basis(d, b, P.rbf_step, P.rbf_gamma);
+                    s_bias[lane * E2F_MAX_H + hh] = acc;
+                }
+                s_wgt[lane] = e2f::radial_gate(d, P.cutoff) * (LF == 1 ? d : 1.0f);
+            }
+            __syncthreads();
+            // logits of the chunk (Eq. kernel_score)
+            float s_arr[PB];
+            float cmax = -INFINITY;
+#pragma unroll
+            for (int p = 0; p < PB; ++p) {
+                s_arr[p] = -INFINITY;
+                if (p < np) {
+                    const int j = s_list[p0 + p];
+                    const float* kj = P.k + (size_t)j * (L + 1) * C + c0;
+                    float dot = 0.0f;
+#pragma unroll
+                    for (int l = 0; l <= L; ++l)
+#pragma unroll
+                        for (int u = 0; u < CPL; ++u) dot += q[l][u] * kj[l * C + u];
+                    for (int off = 1; off < lanes_per_head; off <<= 1) dot += __shfl_xor(dot, off);
+                    s_arr[p] = dot * P.tau + s_bias[p * E2F_MAX_H + head];
+                    cmax = fmaxf(cmax, s_arr[p]);
+                }
+            }
+            // one rescale of the running state per chunk (Algorithm 1, lines mu', z, A, taken chunk-wise)
+            const float mu_new = fmaxf(mu, cmax);
+            const float scale = __expf(mu - mu_new);  // 0 on the first chunk (mu = -inf)
+            z *= scale;
+#pragma unroll
+            for (int x = 0; x < n; ++x)
+#pragma unroll
+                for (int u = 0; u < CPL; ++u) A[x][u] *= scale;
+            mu = mu_new;
+#pragma unroll 1
+            for (int p = 0; p < np; ++p) {
+                // s_arr is indexed by a runtime p: select without dynamic register indexing
+                float sp = s_arr[0];
+#pragma unroll
+                for (int x = 1; x < PB; ++x) sp = (p == x) ? s_arr[x] : sp;
+                const float pe = __expf(sp - mu);
+                z += pe;
+                const float wgt = pe * s_wgt[p];
+                const int j = s_list[p0 + p];
+                const VT* vj = (const VT*)P.v + (size_t)j * n * C + c0;
+                float vin[n][CPL];
+#pragma unroll
+                for (int x = 0; x < n; ++x)
+#pragma unroll
+                    for (int u = 0; u < CPL; ++u) vin[x][u] = e2f::load_as_float(vj + x * C + u);
+                e2f::eaas_accumulate<L, LF, CPL>(vin, s_D + p * DSP, P.cw, wgt, A);
+            }
+            __syncthreads();
+        }
+        if (rows_done) break;
+    }
+
+    if (active) {
+        const float inv = z > 0.0f ? 1.0f / z : 0.0f;
+        float* o = P.out + (size_t)P.cv.perm[t] * n * C + c0;
+#pragma unroll
+        for (int x = 0; x < n; ++x)
+#pragma unroll
+            for (int u = 0; u < CPL; ++u) o[x * C + u] = A[x][u] * inv;
+    }
+}
+
+template <int L, int LF, int CPL>
+void launch_valu_dtype(const e2f_ctx* ctx, const FusedParams& P, hipStream_t st) {
+    if (ctx->cfg.feat_dtype == E2F_BF16)
+        k_fused_valu<L, LF, CPL, uint16_t><<<P.cv.N, 64, 0, st>>>(P);
+    else
+        k_fused_valu<L, LF, CPL, float><<<P.cv.N, 64, 0, st>>>(P);
+}
+
+template <int L, int LF>
+bool launch_valu_cpl(const e2f_ctx* ctx, const FusedParams& P, hipStream_t st) {
+    switch (ctx->cpl) {
+        case 1: launch_valu_dtype<L, LF, 1>(ctx, P, st); return true;
+        case 2: launch_valu_dtype<L, LF, 2>(ctx, P, st); return true;
+        case 3: launch_valu_dtype<L, LF, 3>(ctx, P, st); return true;
+        case 4: launch_valu_dtype<L, LF, 4>(ctx, P, st); return true;
+    }
+    return false;
+}
+
+template <int L>
+bool launch_valu_lf(const e2f_ctx* ctx, const FusedParams& P, hipStream_t st) {
+    return ctx->cfg.lf == 0 ? launch_valu_cpl<L, 0>(ctx, P, st) : launch_valu_cpl<L, 1>(ctx, P, st);
+}
+
+}  // namespace
+
+e2f_status e2f_launch_fused(const e2f_ctx* ctx, const E2fCellsView& cv, const e2f_weights* w, const E2fAttnWs& ws,
+                            float* out, hipStream_t st) {
+    if (cv.N == 0) return E2F_OK;
+    FusedParams P;
+    P.cv = cv;
+    P.spos = ws.spos; P.q = ws.q; P.k = ws.k; P.v = ws.v; P.cw = ws.cw; P.Wb = w->Wb; P.out = out;
+    P.C = ctx->cfg.C; P.H = ctx->cfg.H; P.B = ctx->cfg.B; P.Ch = ctx->Ch;
+    P.tau = ctx->tau; P.rc2 = ctx->rc2; P.cutoff = ctx->cfg.cutoff; P.rbf_step = ctx->rbf_step; P.rbf_gamma = ctx->rbf_gamma;
+    bool ok = false;
+    switch (ctx->cfg.L_max) {
+        case 0: ok = launch_valu_lf<0>(ctx, P, st); break;
+        case 1: ok = launch_valu_lf<1>(ctx, P, st); break;
+        case 2: ok = launch_valu_lf<2>(ctx, P, st); break;
+        case 3: ok = launch_valu_lf<3>(ctx, P, st); break;
+        case 4: ok = launch_valu_lf<4>(ctx, P, st); break;
+    }
+    if (!ok) return E2F_ERR_UNSUPPORTED;
+    E2F_HIP_CHECK(hipGetLastError());
+    return E2F_OK;
+}

@@ -1,0 +1,92 @@
+// Internal declarations shared by the translation units of libe2f.so (host objects, device views, launchers).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/e2f.h"
+
+#define E2F_MAX_L 4
+#define E2F_MAX_N ((E2F_MAX_L + 1) * (E2F_MAX_L + 1))
+#define E2F_MAX_H 32
+
+// Per-segment uniform grid: cell (x,y,z) of the segment has global id base + (z*ny + y)*nx + x.
+struct E2fSegGrid {
+    float ox, oy, oz, inv_edge;
+    int32_t nx, ny, nz, base;
+};
+
+// Device view of a cell list (all pointers into the caller's cells workspace).
+struct E2fCellsView {
+    const E2fSegGrid* grid;     // [S]
+    const int32_t* cell_start;  // [max_cells + 1] first sorted slot of each global cell
+    const int32_t* perm;        // [N] sorted slot -> caller's atom index
+    const int32_t* scell;       // [N] global cell id of the atom in each sorted slot
+    const int32_t* sseg;        // [N] segment of the atom in each sorted slot
+    const int32_t* atom_slot;   // [N] caller's atom index -> sorted slot
+    int32_t N, S;
+};
+
+struct e2f_cells {
+    E2fCellsView view;
+    // scratch used while building
+    int32_t* bbox;       // [S][6] order-preserving integer images of min/max coordinates
+    int32_t* atom_seg;   // [N]
+    int32_t* atom_cell;  // [N]
+    int32_t* cell_fill;  // [max_cells]
+    int32_t* tmp_slot;   // [N]
+    int32_t max_cells;
+    const float* pos;    // the positions the list was built from (identity check only)
+};
+
+struct e2f_ctx {
+    e2f_config cfg;
+    int32_t n;         // (L_max+1)^2
+    int32_t Ch;        // channels per head
+    int32_t cpl;       // channels per lane in the fused kernel
+    float tau;         // 1/sqrt(d_k)
+    float rc2;         // cutoff*cutoff rounded to binary32
+    float rbf_gamma;   // (B-1)^2 / (2 cutoff^2)
+    float rbf_step;    // cutoff/(B-1)
+    // coupling coefficients of the re-indexing operator P for lf (without path weights):
+    // coefP[comp][0..2] multiplies the aligned input of degree lo-1, lo (opposite order), lo+1.
+    float coefP[E2F_MAX_N][3];
+};
+
+// Layout of the O(N) attention workspace.
+struct E2fAttnWs {
+    float4* spos;   // [N] sorted positions (w unused)
+    float* q;       // [N][L+1][C] sorted order
+    float* k;       // [N][L+1][C]
+    void* v;        // [N][n][C] sorted order, float or bf16 (follows feat_dtype)
+    float* cw;      // [n][3] P coefficients times path weights
+    size_t bytes;
+};
+E2fAttnWs e2f_attn_ws_layout(const e2f_ctx* ctx, int32_t N, void* ws);
+
+static inline size_t e2f_align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
+
+#define E2F_HIP_CHECK(expr)                      \
+    do {                                         \
+        hipError_t e__ = (expr);                 \
+        if (e__ != hipSuccess) return E2F_ERR_HIP; \
+    } while (0)
+
+// ---- launchers (each returns after enqueueing on `st`) ----
+e2f_status e2f_launch_build_cells(const e2f_ctx* ctx, e2f_cells* c, const float* pos, const int32_t* seg_offsets,
+                                  hipStream_t st);
+e2f_status e2f_launch_count_neighbors(const e2f_ctx* ctx, const E2fCellsView& cv, const float* pos, int32_t* degree,
+                                      hipStream_t st);
+e2f_status e2f_launch_list_neighbors(const e2f_ctx* ctx, const E2fCellsView& cv, const float* pos,
+                                     const int64_t* offsets, int32_t* idx, hipStream_t st);
+e2f_status e2f_launch_prepare(const e2f_ctx* ctx, const E2fCellsView& cv, const float* pos, const e2f_weights* w,
+                              const E2fAttnWs& ws, hipStream_t st);
+e2f_status e2f_launch_project_mfma(const e2f_ctx* ctx, const E2fCellsView& cv, const void* h, const e2f_weights* w,
+                                   const E2fAttnWs& ws, hipStream_t st);
+e2f_status e2f_launch_project_simple(const e2f_ctx* ctx, const E2fCellsView& cv, const void* h, const e2f_weights* w,
+                                     float* q, float* k, float* v, hipStream_t st);
+e2f_status e2f_launch_fused(const e2f_ctx* ctx, const E2fCellsView& cv, const e2f_weights* w, const E2fAttnWs& ws,
+                            float* out, hipStream_t st);
+e2f_status e2f_run_materialized(const e2f_ctx* ctx, const E2fCellsView& cv, const float* pos, const void* h,
+                                const e2f_weights* w, const E2fAttnWs& ws, float* out, hipStream_t st,
+                                size_t* edges_out, size_t* peak_bytes_out);
