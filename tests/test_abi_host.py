@@ -1,0 +1,92 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol the header declares,
+validates configurations, reports closed-form workspace sizes and rejects bad arguments before launching."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2601_16622_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(B.LIB_PATH):
+        from paper_2601_16622_amd import build
+        build.build(verbose=False)
+    return B.load()
+
+
+def test_every_declared_symbol_is_exported(lib):
+    header = open(os.path.join(ROOT, "include", "e2f.h")).read()
+    declared = set(re.findall(r"\b(e2f_[a-z_]+)\s*\(", header))
+    assert declared == set(B.EXPORTS)
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_status_strings(lib):
+    texts = {B.status_string(c) for c in range(6)}
+    assert len(texts) == 6 and "ok" in texts
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(L_max=-1), 1), (dict(C=0), 1), (dict(H=3), 1), (dict(B=0), 1), (dict(cutoff=0.0), 1),
+    (dict(cutoff=float("nan")), 1), (dict(feat_dtype=7), 1), (dict(L_max=0, lf=1), 1),
+    (dict(L_max=5), 2), (dict(lf=2), 2), (dict(C=24, H=2), 2), (dict(C=320, H=8), 2), (dict(C=16, H=2, feat_dtype=1), 2),
+])
+def test_create_rejects_bad_configurations(lib, kw, code):
+    base = dict(L_max=2, C=128, H=8, B=8, lf=1, cutoff=5.0, feat_dtype=0)
+    base.update(kw)
+    cfg = B.Config(*[base[k] for k in ("L_max", "C", "H", "B", "lf", "cutoff", "feat_dtype")])
+    ctx = ctypes.c_void_p()
+    assert lib.e2f_create(ctypes.byref(cfg), ctypes.byref(ctx)) == code
+    assert not ctx.value
+
+
+def test_workspace_sizes_are_linear_in_N(lib):
+    ctx = B.e2f_create(4, 128, 8, 8, 1, 6.0, "bf16")
+    try:
+        sizes = [B.e2f_attn_workspace_bytes(ctx, N) for N in (10_000, 20_000, 40_000)]
+        # sorted positions 16 B, q and k fp32 (L+1)*C each, v bf16 n*C, per atom; constant tail
+        per_atom = 16 + 2 * 5 * 128 * 4 + 25 * 128 * 2
+        assert abs((sizes[1] - sizes[0]) - 10_000 * per_atom) <= 2048
+        assert abs((sizes[2] - sizes[1]) - 20_000 * per_atom) <= 2048
+        c = [B.e2f_cells_workspace_bytes(ctx, N, 4) for N in (1000, 2000, 3000)]
+        assert abs((c[2] - c[1]) - (c[1] - c[0])) <= 4096
+        assert B.e2f_attn_workspace_bytes(ctx, -1) == 0
+    finally:
+        B.e2f_destroy(ctx)
+
+
+def test_entry_points_reject_bad_arguments_before_launching(lib):
+    ctx = B.e2f_create(1, 16, 2, 8, 1, 5.0, "f32")
+    try:
+        cells = ctypes.c_void_p()
+        null = ctypes.c_void_p(0)
+        # null positions with N > 0, negative N, unaligned / too small workspace
+        assert lib.e2f_build_cells(ctx, null, null, 4, 1, null, 0, ctypes.byref(cells), null) == 1
+        assert lib.e2f_build_cells(ctx, null, null, -1, 1, null, 0, ctypes.byref(cells), null) == 1
+        fake = ctypes.c_void_p(4096)
+        assert lib.e2f_build_cells(ctx, fake, fake, 4, 1, ctypes.c_void_p(4096 + 8), 1 << 20, ctypes.byref(cells), null) == 1
+        assert lib.e2f_build_cells(ctx, fake, fake, 4, 1, fake, 16, ctypes.byref(cells), null) == 3
+        # an empty problem is valid and launches nothing
+        assert lib.e2f_build_cells(ctx, null, null, 0, 0, null, 0, ctypes.byref(cells), null) == 0
+        w = B.Weights(*([0] * 7))
+        assert lib.e2f_attn_forward(ctx, cells, null, null, null, 0, 0, ctypes.byref(w), null, null, 0, null) == 0
+        assert lib.e2f_attn_forward(ctx, cells, null, null, null, 5, 1, ctypes.byref(w), null, null, 0, null) == 1
+        assert lib.e2f_attn_forward(ctx, null, null, null, null, 0, 0, ctypes.byref(w), null, null, 0, null) == 1
+        lib.e2f_cells_destroy(cells)
+    finally:
+        B.e2f_destroy(ctx)
+
+
+def test_product_package_does_not_import_the_oracle():
+    pkg = os.path.join(ROOT, "paper_2601_16622_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h", ".cpp")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "import oracle" not in text and "from oracle" not in text and "e2fo_" not in text, f
