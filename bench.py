@@ -1,0 +1,169 @@
+"""Benchmark of the fused node-centric equivariant attention forward pass on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W]
+
+A step is one pass of the whole hot path over the scaling-point workload (one box of 10 000 atoms at
+0.1 atoms/A^3, cutoff 6 A, L_max = 4, C = 128, H = 8, bf16 features with fp32 accumulation): e2f_build_cells
+followed by e2f_attn_forward, inputs already resident in device memory.  Prints one JSON line with whole-job
+atoms/s, the roofline figure of the dominant kernel (timed with HIP events on the launch stream by the
+library's profiling hooks), the fp64 CPU oracle timed on this host, and the fused-vs-materialized comparison.
+"""
+import argparse
+import json
+import os
+import re
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+# MI355X published peaks used for the roofline: fp32 vector 157.3 TFLOP/s
+# (256 CUs x 4 SIMDs x 16 lanes x 2 (packed) x 2 (FMA) x 2.4 GHz), bf16 dense MFMA 2.5 PFLOP/s, HBM 8 TB/s.
+PEAK_ALU_TFLOPS = 157.3
+
+
+def flop_model(cfg, N, E):
+    """Algorithmic flops of the method (1 MAC = 2 flop; block-diagonal Wigner matrices, no padding counted)."""
+    L, C, H, B = cfg["L"], cfg["C"], cfg["H"], cfg["B"]
+    n = (L + 1) ** 2
+    S2 = sum((2 * l + 1) ** 2 for l in range(L + 1))
+    nnzP = sum(1 for lo in range(L + 1) for m in range(-lo, lo + 1)
+               for li in (lo - 1, lo, lo + 1) if 0 <= li <= L and not (li == lo and m == 0) and abs(m) <= li) \
+        if cfg["lf"] == 1 else n
+    f_node = 2 * 5 * n * C * C + 2 * 2 * n * C
+    f_edge = 2 * (L + 1) * C + 2 * H * B + 2 * S2 * C + 2 * nnzP * C + 2 * S2 * C + 2 * n * C
+    return f_node, f_edge, N * f_node + E * f_edge
+
+
+def read_traffic():
+    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 counter summary, if any."""
+    path = os.path.join(ROOT, "profiles", "fused_attention_scaling10k_pmc.txt")
+    if not os.path.exists(path):
+        return None
+    m = re.search(r"traffic_bytes_per_launch:\s*([0-9.eE+]+)", open(path).read())
+    return float(m.group(1)) if m else None
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-materialized", action="store_true")
+    ap.add_argument("--workload", default="scaling", help="scaling | large | small | tiny | box<N>")
+    ap.add_argument("--copy-calibration", type=int, default=0, metavar="BYTES",
+                    help="also run a plain device copy of this many bytes (reference for HBM counter scaling)")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on one GPU only (the path has no multi-GPU code); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2601_16622_amd import binding as B, workloads as W
+    B.load()
+    assert torch.cuda.is_available(), "bench.py needs the MI355X"
+
+    if args.copy_calibration > 0:
+        src = torch.ones(args.copy_calibration // 4, dtype=torch.float32, device="cuda:0")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
+    wl = W.by_name(args.workload, 0)
+    cfg = wl["cfg"]
+    P = B.Problem(wl, "cuda:0")
+    N = P.N
+
+    def step():
+        P.build_cells()
+        P.forward()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    B.e2f_profile_begin(P.ctx, args.steps)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    stage_ms, calls = B.e2f_profile_end(P.ctx)
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    deg, _, _ = P.neighbors()
+    E = int(deg.sum())
+    f_node, f_edge, f_alg = flop_model(cfg, N, E)
+
+    # forward alone (cells prebuilt), same protocol
+    for _ in range(3):
+        P.forward()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        P.forward()
+    torch.cuda.synchronize()
+    fwd_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+
+    attn_ms = stage_ms["attention"]
+    achieved = E * f_edge / (attn_ms * 1e-3) / 1e12 if attn_ms > 0 else 0.0
+    roofline = {"bound": "alu", "kernel": "k_fused_valu", "achieved": round(achieved, 3), "peak": PEAK_ALU_TFLOPS,
+                "unit": "TFLOP/s", "frac": round(achieved / PEAK_ALU_TFLOPS, 4), "traffic": read_traffic(),
+                "kernel_ms": round(attn_ms, 4), "flops_per_launch": E * f_edge, "pairs_per_launch": E,
+                "stage_ms": {k: round(v, 4) for k, v in stage_ms.items()}}
+
+    result = {
+        "metric": "atoms/sec of fused equivariant attention forward (cells + projections + attention)",
+        "value": round(N / (ms_per_step * 1e-3), 1), "unit": "atoms/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16" if cfg["dtype"] == "bf16" else "f32", "data": "synthetic",
+        "config": {"workload": f"{args.workload}: N={N} atoms, E={E} directed pairs, cutoff {cfg['cutoff']} A, "
+                               f"L_max={cfg['L']}, C={cfg['C']}, H={cfg['H']}, B={cfg['B']}, lf={cfg['lf']}, "
+                               f"{cfg['dtype']} features, fp32 accumulation"},
+        "tflops": round(f_alg / (ms_per_step * 1e-3) / 1e12, 3),
+        "forward_only_ms": round(fwd_ms, 4),
+        "forward_only_atoms_per_s": round(N / (fwd_ms * 1e-3), 1),
+        "peak_activation_bytes": P.activation_bytes(),
+        "roofline": roofline,
+    }
+
+    if not args.no_materialized:
+        try:
+            out_m = torch.empty_like(P.out)
+            P.forward_materialized(out_m)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            reps = 3
+            for _ in range(reps):
+                _, peak = P.forward_materialized(out_m)
+            torch.cuda.synchronize()
+            mat_ms = (time.perf_counter() - t0) * 1e3 / reps
+            result["materialized"] = {"ms": round(mat_ms, 3), "peak_bytes": int(peak) + P.activation_bytes(),
+                                      "fused_speedup": round(mat_ms / fwd_ms, 2),
+                                      "memory_ratio": round((peak + P.activation_bytes()) / P.activation_bytes(), 1)}
+        except B.E2fError as e:
+            result["materialized"] = {"error": str(e)}
+
+    if not args.no_cpu_baseline:
+        import oracle
+        nbr = oracle.neighbor_list(wl["pos"], wl["seg"], np.float32(cfg["cutoff"]), use_cells=True)
+        n_t = min(N, 10_000)
+        targets = None if n_t == N else np.random.default_rng(0).choice(N, n_t, replace=False).astype(np.int32)
+        t0 = time.perf_counter()
+        oracle.attn_forward(cfg, wl["pos"], wl["h"], wl["seg"], wl["weights"], targets=targets, nbr=nbr)
+        dt = time.perf_counter() - t0
+        result["cpu_baseline"] = {"value": round(n_t / dt, 1), "unit": "atoms/s", "cores": oracle.num_threads(),
+                                  "kind": "oracle",
+                                  "sample": f"{n_t} of {N} target atoms of the same workload, fp64 dense-CG route, "
+                                            f"{dt:.1f} s wall"}
+    P.close()
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

@@ -135,6 +135,18 @@ e2f_status e2f_attn_forward_materialized(e2f_ctx *ctx, const e2f_cells *cells, c
                                          float *out, void *ws, size_t ws_bytes, void *hip_stream, size_t *edges_out,
                                          size_t *peak_bytes_out);
 
+/*
+ * Per-stage timing of e2f_attn_forward for benchmarks (measurement aid; callers that do not ask for it pay
+ * nothing).  e2f_profile_begin creates HIP events for up to max_calls calls; while profiling is on, every
+ * e2f_attn_forward records events between its stages on the stream it is given (no synchronisation).
+ * e2f_profile_end waits for the recorded events, writes the mean duration in milliseconds of each stage
+ * (E2F_STAGE_*) over the recorded calls into stage_ms (host float[E2F_N_STAGES]), the number of calls into
+ * *calls (host), destroys the events and switches profiling off.
+ */
+enum { E2F_STAGE_PREPARE = 0, E2F_STAGE_PROJECT = 1, E2F_STAGE_ATTENTION = 2, E2F_N_STAGES = 3 };
+e2f_status e2f_profile_begin(e2f_ctx *ctx, int32_t max_calls);
+e2f_status e2f_profile_end(e2f_ctx *ctx, float *stage_ms, int32_t *calls);
+
 #ifdef __cplusplus
 }
 #endif

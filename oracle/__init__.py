@@ -62,6 +62,8 @@ def lib():
         L.e2fo_attn_forward.argtypes = [ctypes.POINTER(_Config), dp, dp, ctypes.c_int, dp, dp, dp, dp, dp, dp, dp,
                                         lp, ip, ip, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_double, dp]
         L.e2fo_attn_forward.restype = ctypes.c_int
+        L.e2fo_num_threads.argtypes = []
+        L.e2fo_num_threads.restype = ctypes.c_int
         _lib = L
     return _lib
 
@@ -72,6 +74,10 @@ def _d(a):
 
 def _f64(a):
     return np.ascontiguousarray(a, dtype=np.float64)
+
+
+def num_threads():
+    return lib().e2fo_num_threads()
 
 
 def solid_harmonics(l, r):

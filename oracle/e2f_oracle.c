@@ -654,3 +654,11 @@ int e2fo_attn_forward(const e2fo_config *cfg, const double *pos, const double *h
     free(v);
     return 0;
 }
+
+/* Number of OpenMP threads the parallel loops above use (reported next to timings). */
+#ifdef _OPENMP
+#include <omp.h>
+int e2fo_num_threads(void) { return omp_get_max_threads(); }
+#else
+int e2fo_num_threads(void) { return 1; }
+#endif

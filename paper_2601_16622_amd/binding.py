@@ -17,7 +17,8 @@ E2F_F32, E2F_BF16 = 0, 1
 
 EXPORTS = ["e2f_status_string", "e2f_create", "e2f_destroy", "e2f_cells_workspace_bytes", "e2f_build_cells",
            "e2f_cells_destroy", "e2f_count_neighbors", "e2f_list_neighbors", "e2f_attn_workspace_bytes",
-           "e2f_attn_forward", "e2f_attn_forward_materialized"]
+           "e2f_attn_forward", "e2f_attn_forward_materialized", "e2f_profile_begin", "e2f_profile_end"]
+STAGES = ("prepare", "project", "attention")
 
 
 class Config(ctypes.Structure):
@@ -70,6 +71,10 @@ def load():
     L.e2f_attn_forward_materialized.argtypes = [vp, vp, vp, vp, vp, i32, i32, ctypes.POINTER(Weights), vp, vp, sz, vp,
                                                 ctypes.POINTER(sz), ctypes.POINTER(sz)]
     L.e2f_attn_forward_materialized.restype = ctypes.c_int
+    L.e2f_profile_begin.argtypes = [vp, i32]
+    L.e2f_profile_begin.restype = ctypes.c_int
+    L.e2f_profile_end.argtypes = [vp, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(i32)]
+    L.e2f_profile_end.restype = ctypes.c_int
     _lib = L
     return L
 
@@ -155,6 +160,18 @@ def e2f_attn_forward_materialized(ctx, cells, pos, h, seg_offsets, weights, out,
                                                 ctypes.byref(edges), ctypes.byref(peak)),
            "e2f_attn_forward_materialized")
     return edges.value, peak.value
+
+
+def e2f_profile_begin(ctx, max_calls):
+    _check(load().e2f_profile_begin(ctx, max_calls), "e2f_profile_begin")
+
+
+def e2f_profile_end(ctx):
+    """Returns ({stage: mean ms}, calls)."""
+    ms = (ctypes.c_float * len(STAGES))()
+    calls = ctypes.c_int32(0)
+    _check(load().e2f_profile_end(ctx, ms, ctypes.byref(calls)), "e2f_profile_end")
+    return {k: float(ms[i]) for i, k in enumerate(STAGES)}, calls.value
 
 
 class Problem:

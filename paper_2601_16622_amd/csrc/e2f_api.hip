@@ -143,11 +143,61 @@ e2f_status e2f_create(const e2f_config* cfg, e2f_ctx** ctx_out) {
                 if (lo + 1 <= cfg->L_max) c->coefP[comp][2] = (float)cg_down(lo + 1, am);    // l_i = lo+1
             }
         }
+    c->prof_events = nullptr;
+    c->prof_capacity = 0;
+    c->prof_calls = 0;
     *ctx_out = c;
     return E2F_OK;
 }
 
-void e2f_destroy(e2f_ctx* ctx) { delete ctx; }
+void e2f_destroy(e2f_ctx* ctx) {
+    if (!ctx) return;
+    if (ctx->prof_events) {
+        for (int i = 0; i < ctx->prof_capacity * (E2F_N_STAGES + 1); ++i) (void)hipEventDestroy(ctx->prof_events[i]);
+        delete[] ctx->prof_events;
+    }
+    delete ctx;
+}
+
+e2f_status e2f_profile_begin(e2f_ctx* ctx, int32_t max_calls) {
+    if (!ctx || max_calls <= 0 || max_calls > 4096 || ctx->prof_events) return E2F_ERR_INVALID_ARG;
+    const int ne = max_calls * (E2F_N_STAGES + 1);
+    hipEvent_t* ev = new (std::nothrow) hipEvent_t[ne];
+    if (!ev) return E2F_ERR_OOM;
+    for (int i = 0; i < ne; ++i)
+        if (hipEventCreate(&ev[i]) != hipSuccess) {
+            for (int j = 0; j < i; ++j) (void)hipEventDestroy(ev[j]);
+            delete[] ev;
+            return E2F_ERR_HIP;
+        }
+    ctx->prof_events = ev;
+    ctx->prof_capacity = max_calls;
+    ctx->prof_calls = 0;
+    return E2F_OK;
+}
+
+e2f_status e2f_profile_end(e2f_ctx* ctx, float* stage_ms, int32_t* calls) {
+    if (!ctx || !stage_ms || !calls || !ctx->prof_events) return E2F_ERR_INVALID_ARG;
+    e2f_status rc = E2F_OK;
+    double sum[E2F_N_STAGES] = {0.0, 0.0, 0.0};
+    for (int c = 0; c < ctx->prof_calls && rc == E2F_OK; ++c) {
+        hipEvent_t* ev = ctx->prof_events + c * (E2F_N_STAGES + 1);
+        if (hipEventSynchronize(ev[E2F_N_STAGES]) != hipSuccess) rc = E2F_ERR_HIP;
+        for (int s = 0; s < E2F_N_STAGES && rc == E2F_OK; ++s) {
+            float ms = 0.0f;
+            if (hipEventElapsedTime(&ms, ev[s], ev[s + 1]) != hipSuccess) rc = E2F_ERR_HIP;
+            sum[s] += ms;
+        }
+    }
+    *calls = ctx->prof_calls;
+    for (int s = 0; s < E2F_N_STAGES; ++s) stage_ms[s] = ctx->prof_calls > 0 ? (float)(sum[s] / ctx->prof_calls) : 0.0f;
+    for (int i = 0; i < ctx->prof_capacity * (E2F_N_STAGES + 1); ++i) (void)hipEventDestroy(ctx->prof_events[i]);
+    delete[] ctx->prof_events;
+    ctx->prof_events = nullptr;
+    ctx->prof_capacity = 0;
+    ctx->prof_calls = 0;
+    return rc;
+}
 
 size_t e2f_cells_workspace_bytes(const e2f_ctx* ctx, int32_t N, int32_t S) {
     if (!ctx || N < 0 || S < 0) return 0;
@@ -202,9 +252,19 @@ e2f_status e2f_attn_forward(e2f_ctx* ctx, const e2f_cells* cells, const float* p
     if (rc != E2F_OK || N == 0) return rc;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     const E2fAttnWs L = e2f_attn_ws_layout(ctx, N, ws);
+    hipEvent_t* ev = (ctx->prof_events && ctx->prof_calls < ctx->prof_capacity)
+                         ? ctx->prof_events + ctx->prof_calls * (E2F_N_STAGES + 1) : nullptr;
+    if (ev) E2F_HIP_CHECK(hipEventRecord(ev[0], st));
     if ((rc = e2f_launch_prepare(ctx, cells->view, pos, w, L, st)) != E2F_OK) return rc;
+    if (ev) E2F_HIP_CHECK(hipEventRecord(ev[1], st));
     if ((rc = e2f_launch_project_mfma(ctx, cells->view, h, w, L, st)) != E2F_OK) return rc;
-    return e2f_launch_fused(ctx, cells->view, w, L, out, st);
+    if (ev) E2F_HIP_CHECK(hipEventRecord(ev[2], st));
+    if ((rc = e2f_launch_fused(ctx, cells->view, w, L, out, st)) != E2F_OK) return rc;
+    if (ev) {
+        E2F_HIP_CHECK(hipEventRecord(ev[3], st));
+        ctx->prof_calls++;
+    }
+    return E2F_OK;
 }
 
 e2f_status e2f_attn_forward_materialized(e2f_ctx* ctx, const e2f_cells* cells, const float* pos, const void* h,

@@ -51,6 +51,9 @@ struct e2f_ctx {
     // coupling coefficients of the re-indexing operator P for lf (without path weights):
     // coefP[comp][0..2] multiplies the aligned input of degree lo-1, lo (opposite order), lo+1.
     float coefP[E2F_MAX_N][3];
+    // optional per-stage timing (e2f_profile_begin / e2f_profile_end)
+    hipEvent_t* prof_events;  // [prof_capacity][E2F_N_STAGES + 1]
+    int32_t prof_capacity, prof_calls;
 };
 
 // Layout of the O(N) attention workspace.
