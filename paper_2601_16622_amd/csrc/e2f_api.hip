@@ -1,5 +1,7 @@
 // C ABI of libe2f.so: argument checks, workspace layout, and the sequence of launches per entry point.
 #include <math.h>
+#include <stdlib.h>
+#include <string.h>
 #include <new>
 
 #include "e2f_internal.h"
@@ -82,7 +84,10 @@ E2fAttnWs e2f_attn_ws_layout(const e2f_ctx* ctx, int32_t N, void* ws) {
     L.spos = (float4*)take((size_t)N * sizeof(float4));
     L.q = (float*)take((size_t)N * (ctx->cfg.L_max + 1) * ctx->cfg.C * 4);
     L.k = (float*)take((size_t)N * (ctx->cfg.L_max + 1) * ctx->cfg.C * 4);
-    L.v = (void*)take((size_t)N * ctx->n * ctx->cfg.C * esz);
+    // tiled v of the MFMA attention kernel: 16-row tiles per head, two tiles when L_max >= 3
+    const size_t v_elems = ctx->use_mfma_attn ? (size_t)ctx->cfg.H * (ctx->cfg.L_max >= 3 ? 2 : 1) * 256
+                                              : (size_t)ctx->n * ctx->cfg.C;
+    L.v = (void*)take((size_t)N * v_elems * esz);
     L.cw = (float*)take((size_t)E2F_MAX_N * 3 * 4);
     L.bytes = off;
     return L;
@@ -143,6 +148,9 @@ e2f_status e2f_create(const e2f_config* cfg, e2f_ctx** ctx_out) {
                 if (lo + 1 <= cfg->L_max) c->coefP[comp][2] = (float)cg_down(lo + 1, am);    // l_i = lo+1
             }
         }
+    // E2F_ATTENTION=valu in the environment keeps the attention stage off the matrix cores (for A/B timing)
+    const char* pick = getenv("E2F_ATTENTION");
+    c->use_mfma_attn = e2f_fused_mfma_supported(c) && !(pick && strcmp(pick, "valu") == 0);
     c->prof_events = nullptr;
     c->prof_capacity = 0;
     c->prof_calls = 0;
@@ -259,7 +267,9 @@ e2f_status e2f_attn_forward(e2f_ctx* ctx, const e2f_cells* cells, const float* p
     if (ev) E2F_HIP_CHECK(hipEventRecord(ev[1], st));
     if ((rc = e2f_launch_project_mfma(ctx, cells->view, h, w, L, st)) != E2F_OK) return rc;
     if (ev) E2F_HIP_CHECK(hipEventRecord(ev[2], st));
-    if ((rc = e2f_launch_fused(ctx, cells->view, w, L, out, st)) != E2F_OK) return rc;
+    rc = ctx->use_mfma_attn ? e2f_launch_fused_mfma(ctx, cells->view, w, L, out, st)
+                            : e2f_launch_fused(ctx, cells->view, w, L, out, st);
+    if (rc != E2F_OK) return rc;
     if (ev) {
         E2F_HIP_CHECK(hipEventRecord(ev[3], st));
         ctx->prof_calls++;

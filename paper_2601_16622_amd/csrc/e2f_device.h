@@ -50,6 +50,13 @@ __device__ __forceinline__ void stencil_rows(const E2fCellsView& cv, int slot, i
     }
 }
 
+// Workgroups are dealt to the 8 XCDs round-robin and every XCD has its own L2.  Give each XCD one contiguous
+// range of work items (targets in cell order), so that the neighbour rows its waves share stay in its L2.
+__device__ __forceinline__ int xcd_remap(int bid, int nblocks) {
+    const int q = nblocks >> 3, r = nblocks & 7, x = bid & 7;
+    return x * q + min(x, r) + (bid >> 3);
+}
+
 template <int l>
 __device__ __forceinline__ void delta_align(const float* c, const float* s, float* d) {
     if constexpr (l == 0) e2f_delta_align_l0(c, s, d);
@@ -62,6 +69,8 @@ __device__ __forceinline__ void delta_align(const float* c, const float* s, floa
 // Degree-l block of D(R), R = Ry(-theta) Rz(-phi) (the rotation taking r/|r| to +z; Sec. 3.3), in the
 // real basis with Y(R x) = D(R) Y(x):  D = Delta(-theta) Z(-phi), Delta from the generated series and Z
 // the rotation of each (m,-m) pair by m*phi.  ck/sk = cos/sin(k theta), cm/sm = cos/sin(m phi).
+// D may point into LDS: every entry is written once, as soon as it is known, so that the blocks never
+// have to be held in registers together.
 template <int l>
 __device__ __forceinline__ void align_block(const float* ck, const float* sk, const float* cm, const float* sm, float* D) {
     constexpr int n = 2 * l + 1;

@@ -8,6 +8,8 @@
 //   all lanes       logits of the chunk (q.k reduced over the lanes of a head), chunk maximum, one rescale
 //                   of the running (mu, z, A) per chunk, then per pair: A += e^{s-mu} phi D^T P D v_j
 // Nothing per pair is written to global memory; out_i = A/z is stored once, in the caller's atom order.
+#include <stdlib.h>
+
 #include "e2f_device.h"
 
 namespace {
@@ -23,6 +25,7 @@ struct FusedParams {
     float* out;
     int C, H, B, Ch;
     float tau, rc2, cutoff, rbf_step, rbf_gamma;
+    int xcd;
 };
 
 constexpr int PB = 16;    // pairs per chunk
@@ -38,7 +41,7 @@ __global__ __launch_bounds__(64) void k_fused_valu(FusedParams P) {
     __shared__ float s_bias[PB * E2F_MAX_H];
     __shared__ float s_wgt[PB];
 
-    const int t = blockIdx.x, lane = threadIdx.x;
+    const int t = (P.xcd ? e2f::xcd_remap(blockIdx.x, gridDim.x) : (int)blockIdx.x), lane = threadIdx.x;
     const int C = P.C, H = P.H;
     const int nlanes = C / CPL;
     const bool active = lane < nlanes;
@@ -95,12 +98,7 @@ __global__ __launch_bounds__(64) void k_fused_valu(FusedParams P) {
                 const float4 pj = P.spos[j];
                 const float dx = pj.x - pi.x, dy = pj.y - pi.y, dz = pj.z - pi.z;
                 const float d = sqrtf(dx * dx + dy * dy + dz * dz);
-                if constexpr (LF != 0) {
-                    float D[DS];
-                    e2f::align_D<L>(dx, dy, dz, d, D);
-#pragma unroll
-                    for (int e = 0; e < DS; ++e) s_D[lane * DSP + e] = D[e];
-                }
+                if constexpr (LF != 0) e2f::align_D<L>(dx, dy, dz, d, s_D + lane * DSP);
                 for (int hh = 0; hh < H; ++hh) {
                     float acc = 0.0f;
                     for (int b = 0; b < P.B; ++b) acc += P.Wb[hh * P.B + b] * e2f::radial_basis(d, b, P.rbf_step, P.rbf_gamma);
@@ -203,6 +201,7 @@ e2f_status e2f_launch_fused(const e2f_ctx* ctx, const E2fCellsView& cv, const e2
     P.cv = cv;
     P.spos = ws.spos; P.q = ws.q; P.k = ws.k; P.v = ws.v; P.cw = ws.cw; P.Wb = w->Wb; P.out = out;
     P.C = ctx->cfg.C; P.H = ctx->cfg.H; P.B = ctx->cfg.B; P.Ch = ctx->Ch;
+    { const char* e = getenv("E2F_XCD"); P.xcd = !(e && e[0] == '0'); }
     P.tau = ctx->tau; P.rc2 = ctx->rc2; P.cutoff = ctx->cfg.cutoff; P.rbf_step = ctx->rbf_step; P.rbf_gamma = ctx->rbf_gamma;
     bool ok = false;
     switch (ctx->cfg.L_max) {

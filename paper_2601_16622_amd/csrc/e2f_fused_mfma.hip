@@ -1,0 +1,381 @@
+// Fused on-the-fly equivariant attention on the matrix cores (bf16 operands, fp32 accumulation), for heads of
+// 16 channels.  Same algorithm as k_fused_valu (Sec. 3.4, Algorithm 1 with the geometry and the EAAS steps of
+// Sec. 3.3 inside the kernel); what changes is where the two block rotations and the re-indexing run.
+//
+// The (L+1)^2 components are split into two 16-row tiles, HI = {l=4 (9 rows), l=3 (7 rows)} and
+// LO = {l=2 (5), l=1 (3), l=0 (1), 7 unused}.  For one pair (i,j) and one head (16 channels):
+//
+//   Vt_hi = D1_hi . V_hi      Vt_lo = D1_lo . V_lo          2 x v_mfma_f32_16x16x16_bf16   (rotate in)
+//   B2    = bf16( w * [Vt_hi ; Vt_lo] )                      w = e^{s-mu} * phi * |r|^lf, per (pair, head)
+//   A_hi += M_hi . B2         A_lo += M_lo . B2             2 x v_mfma_f32_16x16x32_bf16   (re-index + rotate back)
+//
+// with D1 the block-diagonal Wigner matrix of the aligning rotation in tile order and M = D^T P (the
+// re-indexing operator folded into the back rotation, path weights included).  The accumulator layout of the
+// first pair of MFMAs (lane (g,c) holds rows 4g..4g+3 of channel c) is exactly the B-operand layout of the
+// second pair, so Vt never leaves the lane.  The running attention output A_i of Algorithm 1 is the MFMA
+// accumulator itself.
+//
+// One wave per target atom.  Pairs are found as in k_fused_valu; per super-chunk of up to SC pairs, lanes =
+// pairs compute the fp32 Wigner blocks, radial bias and gate into LDS (uniform code, no divergence).  Every
+// lane then assembles its own A-operand fragments of D1 and M for one pair at a time from those blocks, using
+// per-lane tables of LDS offsets and P coefficients built once at kernel start.
+#include <stdio.h>
+#include <stdlib.h>
+
+#include "e2f_device.h"
+
+namespace {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+
+struct MfmaParams {
+    E2fCellsView cv;
+    const float4* spos;
+    const float* q;
+    const float* k;
+    const uint16_t* vt;  // [slot][H][NT][16 channels][16 tile rows] bf16
+    const float* cw;
+    const float* Wb;
+    float* out;
+    int B;
+    float tau, rc2, cutoff, rbf_step, rbf_gamma;
+    int xcd;
+    unsigned long long* dbg;
+};
+
+constexpr int SC = 32;     // pairs per super-chunk
+constexpr int CAPM = 160;  // capacity of the neighbour list in LDS
+
+// Tile order of the components.  tile 0 = HI, tile 1 = LO.
+__device__ __forceinline__ bool tile_row_to_lm(int tile, int row, int L, int& l, int& m) {
+    if (tile == 0) {
+        if (row < 9) { l = 4; m = row - 4; } else { l = 3; m = row - 12; }
+    } else {
+        if (row < 5) { l = 2; m = row - 2; } else if (row < 8) { l = 1; m = row - 6; } else if (row == 8) { l = 0; m = 0; } else return false;
+    }
+    return l <= L;
+}
+
+__device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
+    f32x2 v = {a, b};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
+}
+
+template <int L, int H>
+__global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) void k_fused_mfma(MfmaParams P) {
+    constexpr int DS = e2f::d_offset(L + 1);
+    constexpr int ZERO = DS;                          // slot that always holds 0
+    constexpr int DST = (DS + 1) | 1;                 // odd stride: lanes = pairs write without bank conflicts
+    constexpr bool HAS_HI = L >= 3;
+    constexpr int NT = HAS_HI ? 2 : 1;
+    constexpr int T0 = HAS_HI ? 0 : 1;                // first tile in use
+    constexpr int C = 16 * H;
+    __shared__ int s_list[CAPM];
+    __shared__ float s_D[SC * DST];
+    __shared__ float s_bias[SC * H];
+    __shared__ float s_wgt[SC];
+    __shared__ float s_s[SC * H];
+    __shared__ int s_lo[9], s_hi[9];
+    __shared__ float s_cw[E2F_MAX_N * 3];
+
+#ifdef E2F_TIMING
+    unsigned long long tacc[6] = {0, 0, 0, 0, 0, 0};
+    unsigned long long tprev = __builtin_amdgcn_s_memtime();
+#define TICK(k) { unsigned long long now_ = __builtin_amdgcn_s_memtime(); tacc[k] += now_ - tprev; tprev = now_; }
+#else
+#define TICK(k)
+#endif
+    const int t = (P.xcd ? e2f::xcd_remap(blockIdx.x, gridDim.x) : (int)blockIdx.x);
+    const int lane = threadIdx.x, i = lane & 15, g = lane >> 4;
+    const float4 pi = P.spos[t];
+    for (int x = lane; x < (L + 1) * (L + 1) * 3; x += 64) s_cw[x] = P.cw[x];
+    __syncthreads();
+
+    // ---- per-lane fragment tables (constant for the whole kernel)
+    // D1 fragment of tile T: A[i][4g+r] = D^l[a][b] if row i = (l,a) and column 4g+r = (l,b) of the same degree.
+    // M fragment of out tile T: A[i][8g+r], K index 8g+r <-> aligned row (r<4: HI row 4g+r, r>=4: LO row 4g+r-4)
+    //   = (li,mi);  out row i = (lo,b):  M = D^lo[mo][b] * coef  with
+    //   li = lo-1: mo = mi, coef = cw[.][0];  li = lo: mo = -mi (mi != 0), coef = cw[.][1];  li = lo+1: mo = mi, cw[.][2].
+    int offD1[NT][4], offM[NT][8];
+    float cM[NT][8];
+#pragma unroll
+    for (int T = 0; T < NT; ++T) {
+        const int tile = T0 + T;
+        int li_, a_;
+        const bool row_ok = tile_row_to_lm(tile, i, L, li_, a_);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            int lc, b;
+            const bool col_ok = tile_row_to_lm(tile, 4 * g + r, L, lc, b);
+            offD1[T][r] = (row_ok && col_ok && lc == li_) ? e2f::d_offset(li_) + (a_ + li_) * (2 * li_ + 1) + (b + li_) : ZERO;
+        }
+#pragma unroll
+        for (int r = 0; r < 8; ++r) {
+            const int ktile = HAS_HI ? (r < 4 ? 0 : 1) : 1;
+            const int krow = 4 * g + (r & 3);
+            int li, mi;
+            const bool k_ok = (HAS_HI || r >= 4) && tile_row_to_lm(ktile, krow, L, li, mi);
+            int off = ZERO;
+            float coef = 0.0f;
+            if (row_ok && k_ok) {
+                const int lo = li_, b = a_;
+                int mo = 0, which = -1;
+                if (li == lo - 1) { mo = mi; which = 0; }
+                else if (li == lo && mi != 0) { mo = -mi; which = 1; }
+                else if (li == lo + 1 && (mi <= lo && -mi <= lo)) { mo = mi; which = 2; }
+                if (which >= 0) {
+                    off = e2f::d_offset(lo) + (mo + lo) * (2 * lo + 1) + (b + lo);
+                    coef = s_cw[(lo * lo + lo + mo) * 3 + which];
+                }
+            }
+            offM[T][r] = off;
+            cM[T][r] = coef;
+        }
+    }
+
+    // ---- logits run with lanes over channels: lane <-> channels 2*lane, 2*lane+1; its head is lane/8
+    const bool lg_active = lane < C / 2;
+    const int c0 = lg_active ? 2 * lane : 0;
+    const int head = c0 / 16;
+    float q[L + 1][2];
+#pragma unroll
+    for (int l = 0; l <= L; ++l) {
+        q[l][0] = P.q[((size_t)t * (L + 1) + l) * C + c0];
+        q[l][1] = P.q[((size_t)t * (L + 1) + l) * C + c0 + 1];
+    }
+
+    f32x4 acc[H][NT];
+#pragma unroll
+    for (int h = 0; h < H; ++h)
+#pragma unroll
+        for (int T = 0; T < NT; ++T) acc[h][T] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    float mu = -INFINITY, z = 0.0f;
+
+    {
+        int lo[9], hi[9];
+        e2f::stencil_rows(P.cv, t, lo, hi);
+#pragma unroll
+        for (int r = 0; r < 9; ++r)
+            if (lane == 0) { s_lo[r] = lo[r]; s_hi[r] = hi[r]; }
+    }
+    __syncthreads();
+
+    int row = 0, base = s_lo[0];
+    bool rows_done = false;
+    while (true) {
+        // ---- fill the list
+        int cnt = 0;
+        while (!rows_done && cnt + 64 <= CAPM) {
+            if (base >= s_hi[row]) {
+                ++row;
+                if (row == 9) { rows_done = true; break; }
+                base = s_lo[row];
+                continue;
+            }
+            const int j = base + lane;
+            bool ok = false;
+            if (j < s_hi[row] && j != t) {
+                const float4 pj = P.spos[j];
+                ok = e2f::is_neighbor(e2f::dist2_exact(pi.x, pi.y, pi.z, pj.x, pj.y, pj.z), P.rc2);
+            }
+            const unsigned long long mask = __ballot(ok);
+            if (ok) s_list[cnt + __popcll(mask & ((1ull << lane) - 1ull))] = j;
+            cnt += __popcll(mask);
+            base += 64;
+        }
+        __syncthreads();
+        TICK(0)
+        for (int p0 = 0; p0 < cnt; p0 += SC) {
+            const int np = min(SC, cnt - p0);
+            // ---- lanes = pairs: Wigner blocks (fp32), radial bias, gate
+            if (lane < np) {
+                const int j = s_list[p0 + lane];
+                const float4 pj = P.spos[j];
+                const float dx = pj.x - pi.x, dy = pj.y - pi.y, dz = pj.z - pi.z;
+                const float d = sqrtf(dx * dx + dy * dy + dz * dz);
+                e2f::align_D<L>(dx, dy, dz, d, s_D + lane * DST);
+                s_D[lane * DST + ZERO] = 0.0f;
+                for (int hh = 0; hh < H; ++hh) {
+                    float a = 0.0f;
+                    for (int b = 0; b < P.B; ++b) a += P.Wb[hh * P.B + b] * e2f::radial_basis(d, b, P.rbf_step, P.rbf_gamma);
+                    s_bias[lane * H + hh] = a;
+                }
+                s_wgt[lane] = e2f::radial_gate(d, P.cutoff) * d;
+            }
+            __syncthreads();
+            TICK(1)
+            // ---- pass 1: logits of the super-chunk (Eq. kernel_score) and their maximum per head
+            float cmax = -INFINITY;
+            for (int pb = 0; pb < np; pb += 8) {
+                // all key rows of the batch are requested before the first one is used
+                float2 kk[8][L + 1];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const int j = s_list[p0 + min(pb + u, np - 1)];
+                    const float* kj = P.k + (size_t)j * (L + 1) * C + c0;
+#pragma unroll
+                    for (int l = 0; l <= L; ++l) kk[u][l] = *reinterpret_cast<const float2*>(kj + l * C);
+                }
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    float dot = 0.0f;
+#pragma unroll
+                    for (int l = 0; l <= L; ++l) dot += q[l][0] * kk[u][l].x + q[l][1] * kk[u][l].y;
+                    dot += __shfl_xor(dot, 1);
+                    dot += __shfl_xor(dot, 2);
+                    dot += __shfl_xor(dot, 4);
+                    if (pb + u < np) {
+                        const float s = dot * P.tau + s_bias[(pb + u) * H + head];
+                        cmax = fmaxf(cmax, s);
+                        if ((lane & 7) == 0 && lg_active) s_s[(pb + u) * H + head] = s;
+                    }
+                }
+            }
+            TICK(2)
+            // ---- one rescale of (mu, z, A) per super-chunk
+            const float mu_new = fmaxf(mu, cmax);
+            const float scale = __expf(mu - mu_new);
+            z *= scale;
+            mu = mu_new;
+#pragma unroll
+            for (int h = 0; h < H; ++h) {
+                const float sc = __shfl(scale, 8 * h);
+#pragma unroll
+                for (int T = 0; T < NT; ++T) acc[h][T] *= sc;
+            }
+            __syncthreads();
+            TICK(3)
+            // ---- pass 2: per pair, assemble the fragments, then 4 MFMAs per head
+            // The value rows of pair p+1 are requested before pair p is computed (two register sets, loop
+            // unrolled by two so that no copies are needed).
+            auto load_v = [&](int p, s16x4 (&dst)[H][NT]) {
+                const int j = s_list[p0 + p];
+                const uint16_t* vj = P.vt + (size_t)j * H * NT * 256 + i * 16 + 4 * g;
+#pragma unroll
+                for (int h = 0; h < H; ++h)
+#pragma unroll
+                    for (int T = 0; T < NT; ++T) dst[h][T] = *reinterpret_cast<const s16x4*>(vj + (h * NT + T) * 256);
+            };
+            auto compute = [&](int p, const s16x4 (&vv)[H][NT]) {
+                const float pe = __expf(s_s[p * H + head] - mu);
+                z += pe;
+                const float wl = pe * s_wgt[p];
+                const float* Dp = s_D + p * DST;
+                s16x4 d1[NT];
+                bf16x8 mf[NT];
+#pragma unroll
+                for (int T = 0; T < NT; ++T) {
+                    uint32_t u0 = pack_bf16(Dp[offD1[T][0]], Dp[offD1[T][1]]);
+                    uint32_t u1 = pack_bf16(Dp[offD1[T][2]], Dp[offD1[T][3]]);
+                    d1[T] = __builtin_bit_cast(s16x4, make_uint2(u0, u1));
+                    uint32_t m0 = pack_bf16(Dp[offM[T][0]] * cM[T][0], Dp[offM[T][1]] * cM[T][1]);
+                    uint32_t m1 = pack_bf16(Dp[offM[T][2]] * cM[T][2], Dp[offM[T][3]] * cM[T][3]);
+                    uint32_t m2 = pack_bf16(Dp[offM[T][4]] * cM[T][4], Dp[offM[T][5]] * cM[T][5]);
+                    uint32_t m3 = pack_bf16(Dp[offM[T][6]] * cM[T][6], Dp[offM[T][7]] * cM[T][7]);
+                    mf[T] = __builtin_bit_cast(bf16x8, make_uint4(m0, m1, m2, m3));
+                }
+#pragma unroll
+                for (int h = 0; h < H; ++h) {
+                    const float w = __shfl(wl, 8 * h);
+                    f32x4 vt[2];
+                    vt[0] = (f32x4){0.f, 0.f, 0.f, 0.f};
+                    vt[1] = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                    for (int T = 0; T < NT; ++T)
+                        vt[T0 + T] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(d1[T], vv[h][T], (f32x4){0.f, 0.f, 0.f, 0.f}, 0, 0, 0);
+                    const uint32_t b0 = pack_bf16(vt[0][0] * w, vt[0][1] * w), b1 = pack_bf16(vt[0][2] * w, vt[0][3] * w);
+                    const uint32_t b2 = pack_bf16(vt[1][0] * w, vt[1][1] * w), b3 = pack_bf16(vt[1][2] * w, vt[1][3] * w);
+                    const bf16x8 bb = __builtin_bit_cast(bf16x8, make_uint4(b0, b1, b2, b3));
+#pragma unroll
+                    for (int T = 0; T < NT; ++T)
+                        acc[h][T] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(mf[T], bb, acc[h][T], 0, 0, 0);
+                }
+            };
+            s16x4 va[H][NT], vb[H][NT];
+            load_v(0, va);
+#pragma unroll 1
+            for (int p = 0; p < np; p += 2) {
+                load_v(min(p + 1, np - 1), vb);
+                compute(p, va);
+                if (p + 1 < np) {
+                    load_v(min(p + 2, np - 1), va);
+                    compute(p + 1, vb);
+                }
+            }
+            __syncthreads();
+            TICK(4)
+        }
+        if (rows_done) break;
+    }
+
+    // ---- out_i = A / z, caller's atom order; lane (g,i) holds tile rows 4g..4g+3 of channel 16h + i
+    const float zinv = z > 0.0f ? 1.0f / z : 0.0f;
+    float* o = P.out + (size_t)P.cv.perm[t] * (L + 1) * (L + 1) * C;
+#pragma unroll
+    for (int h = 0; h < H; ++h) {
+        const float zi = __shfl(zinv, 8 * h);
+#pragma unroll
+        for (int T = 0; T < NT; ++T)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                int l, m;
+                if (tile_row_to_lm(T0 + T, 4 * g + r, L, l, m)) o[(l * l + l + m) * C + 16 * h + i] = acc[h][T][r] * zi;
+            }
+    }
+#ifdef E2F_TIMING
+    TICK(5)
+    if (lane == 0 && P.dbg)
+        for (int k = 0; k < 6; ++k) atomicAdd(P.dbg + k, tacc[k]);
+#endif
+}
+
+template <int L>
+bool launch_h(const e2f_ctx* ctx, const MfmaParams& P, hipStream_t st) {
+    switch (ctx->cfg.H) {
+        case 1: k_fused_mfma<L, 1><<<P.cv.N, 64, 0, st>>>(P); return true;
+        case 2: k_fused_mfma<L, 2><<<P.cv.N, 64, 0, st>>>(P); return true;
+        case 4: k_fused_mfma<L, 4><<<P.cv.N, 64, 0, st>>>(P); return true;
+        case 8: k_fused_mfma<L, 8><<<P.cv.N, 64, 0, st>>>(P); return true;
+    }
+    return false;
+}
+
+}  // namespace
+
+bool e2f_fused_mfma_supported(const e2f_ctx* ctx) {
+    const int H = ctx->cfg.H;
+    return ctx->cfg.feat_dtype == E2F_BF16 && ctx->cfg.lf == 1 && ctx->Ch == 16 && ctx->cfg.L_max >= 1 &&
+           (H == 1 || H == 2 || H == 4 || H == 8);
+}
+
+e2f_status e2f_launch_fused_mfma(const e2f_ctx* ctx, const E2fCellsView& cv, const e2f_weights* w, const E2fAttnWs& ws,
+                                 float* out, hipStream_t st) {
+    if (cv.N == 0) return E2F_OK;
+    MfmaParams P;
+    P.cv = cv;
+    P.spos = ws.spos; P.q = ws.q; P.k = ws.k; P.vt = (const uint16_t*)ws.v; P.cw = ws.cw; P.Wb = w->Wb; P.out = out;
+    P.B = ctx->cfg.B;
+    P.dbg = nullptr;
+#ifdef E2F_TIMING
+    static unsigned long long* dbg = nullptr;
+    if (!dbg) { (void)hipMalloc((void**)&dbg, 64); (void)hipMemset(dbg, 0, 64); }
+    P.dbg = dbg;
+    { unsigned long long hst[6]; (void)hipMemcpy(hst, dbg, 48, hipMemcpyDeviceToHost); if (getenv("E2F_TIMING_PRINT")) fprintf(stderr, "sections(cum) fill %llu geom %llu pass1 %llu rescale %llu pass2 %llu epi %llu\n", hst[0], hst[1], hst[2], hst[3], hst[4], hst[5]); }
+#endif
+    { const char* e = getenv("E2F_XCD"); P.xcd = !(e && e[0] == '0'); }
+    P.tau = ctx->tau; P.rc2 = ctx->rc2; P.cutoff = ctx->cfg.cutoff; P.rbf_step = ctx->rbf_step; P.rbf_gamma = ctx->rbf_gamma;
+    bool ok = false;
+    switch (ctx->cfg.L_max) {
+        case 1: ok = launch_h<1>(ctx, P, st); break;
+        case 2: ok = launch_h<2>(ctx, P, st); break;
+        case 3: ok = launch_h<3>(ctx, P, st); break;
+        case 4: ok = launch_h<4>(ctx, P, st); break;
+    }
+    if (!ok) return E2F_ERR_UNSUPPORTED;
+    E2F_HIP_CHECK(hipGetLastError());
+    return E2F_OK;
+}

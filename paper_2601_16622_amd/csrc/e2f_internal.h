@@ -44,6 +44,7 @@ struct e2f_ctx {
     int32_t n;         // (L_max+1)^2
     int32_t Ch;        // channels per head
     int32_t cpl;       // channels per lane in the fused kernel
+    bool use_mfma_attn;  // attention on the matrix cores (bf16, heads of 16 channels, lf = 1); v is stored tiled
     float tau;         // 1/sqrt(d_k)
     float rc2;         // cutoff*cutoff rounded to binary32
     float rbf_gamma;   // (B-1)^2 / (2 cutoff^2)
@@ -90,6 +91,9 @@ e2f_status e2f_launch_project_simple(const e2f_ctx* ctx, const E2fCellsView& cv,
                                      float* q, float* k, float* v, hipStream_t st);
 e2f_status e2f_launch_fused(const e2f_ctx* ctx, const E2fCellsView& cv, const e2f_weights* w, const E2fAttnWs& ws,
                             float* out, hipStream_t st);
+bool e2f_fused_mfma_supported(const e2f_ctx* ctx);
+e2f_status e2f_launch_fused_mfma(const e2f_ctx* ctx, const E2fCellsView& cv, const e2f_weights* w, const E2fAttnWs& ws,
+                                 float* out, hipStream_t st);
 e2f_status e2f_run_materialized(const e2f_ctx* ctx, const E2fCellsView& cv, const float* pos, const void* h,
                                 const e2f_weights* w, const E2fAttnWs& ws, float* out, hipStream_t st,
                                 size_t* edges_out, size_t* peak_bytes_out);

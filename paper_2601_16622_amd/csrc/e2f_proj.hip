@@ -69,7 +69,10 @@ struct Frag<float> {
 
 // C is the channel count (compile time so that fragments stay in registers), MG the number of orders m
 // whose A fragments are held at once, CT the number of 16-wide output tiles per wave.
-template <typename T, int C, int MG, int CT>
+// TILED: store v for the MFMA attention kernel, bf16 [slot][head][tile][16 channels][16 tile rows] with the
+// components in tile order (HI: l=4 rows 0..8, l=3 rows 9..15; LO: l=2 rows 0..4, l=1 rows 5..7, l=0 row 8,
+// rows 9..15 zero), heads of 16 channels.
+template <typename T, int C, int MG, int CT, bool TILED>
 __global__ __launch_bounds__(64) void k_project_mfma(E2fCellsView cv, const T* __restrict__ h,
                                                      const T* __restrict__ WQ1, const T* __restrict__ WQ2,
                                                      const T* __restrict__ WK1, const T* __restrict__ WK2,
@@ -142,7 +145,20 @@ __global__ __launch_bounds__(64) void k_project_mfma(E2fCellsView cv, const T* _
 #pragma unroll
                     for (int r = 0; r < 4; ++r) {
                         const int slot = tile * 16 + 4 * g + r;
-                        if (slot < N) e2f::store_from_float(v + ((size_t)slot * n + l * l + m0 + mm) * C + co, p[r]);
+                        if (slot >= N) continue;
+                        if constexpr (!TILED) {
+                            e2f::store_from_float(v + ((size_t)slot * n + l * l + m0 + mm) * C + co, p[r]);
+                        } else {
+                            const int NT = L >= 3 ? 2 : 1, mi = m0 + mm;
+                            const int TI = l >= 3 ? 0 : NT - 1;
+                            const int pos = l == 4 ? mi : (l == 3 ? 9 + mi : (l == 2 ? mi : (l == 1 ? 5 + mi : 8)));
+                            T* dst = v + ((((size_t)slot * (C / 16) + (co >> 4)) * NT + TI) * 16 + (co & 15)) * 16;
+                            e2f::store_from_float(dst + pos, p[r]);
+                            if (l == 0)
+                                for (int z = 9; z < 16; ++z) e2f::store_from_float(dst + z, 0.0f);
+                            if (l == 3 && L == 3 && mi == 0)
+                                for (int z = 0; z < 9; ++z) e2f::store_from_float(dst + z, 0.0f);
+                        }
                     }
                 }
             }
@@ -198,7 +214,7 @@ __global__ void k_project_simple(E2fCellsView cv, const T* __restrict__ h, const
 
 template <typename T, int C>
 bool launch_mfma(const e2f_ctx* ctx, const E2fCellsView& cv, const void* h, const e2f_weights* w, const E2fAttnWs& ws,
-                 hipStream_t st) {
+                 hipStream_t st, bool tiled) {
     if constexpr (C % Frag<T>::KSTEP != 0) {
         return false;
     } else {
@@ -206,24 +222,29 @@ bool launch_mfma(const e2f_ctx* ctx, const E2fCellsView& cv, const void* h, cons
         constexpr int MG = sizeof(T) == 2 ? (C <= 128 ? 9 : 4) : (C <= 64 ? 9 : (C <= 128 ? 5 : 2));
         constexpr int CT = (C / 16) % 4 == 0 ? 4 : ((C / 16) % 2 == 0 ? 2 : 1);
         const dim3 grid((cv.N + 15) / 16, ctx->cfg.L_max + 1, C / 16 / CT);
-        k_project_mfma<T, C, MG, CT><<<grid, 64, 0, st>>>(cv, (const T*)h, (const T*)w->WQ1, (const T*)w->WQ2,
-                                                         (const T*)w->WK1, (const T*)w->WK2, (const T*)w->WV,
-                                                         ctx->cfg.L_max, ws.q, ws.k, (T*)ws.v);
+        if (tiled)
+            k_project_mfma<T, C, MG, CT, true><<<grid, 64, 0, st>>>(cv, (const T*)h, (const T*)w->WQ1, (const T*)w->WQ2,
+                                                                   (const T*)w->WK1, (const T*)w->WK2, (const T*)w->WV,
+                                                                   ctx->cfg.L_max, ws.q, ws.k, (T*)ws.v);
+        else
+            k_project_mfma<T, C, MG, CT, false><<<grid, 64, 0, st>>>(cv, (const T*)h, (const T*)w->WQ1, (const T*)w->WQ2,
+                                                                    (const T*)w->WK1, (const T*)w->WK2, (const T*)w->WV,
+                                                                    ctx->cfg.L_max, ws.q, ws.k, (T*)ws.v);
         return true;
     }
 }
 
 template <typename T>
 bool dispatch_mfma(const e2f_ctx* ctx, const E2fCellsView& cv, const void* h, const e2f_weights* w,
-                   const E2fAttnWs& ws, hipStream_t st) {
+                   const E2fAttnWs& ws, hipStream_t st, bool tiled) {
     switch (ctx->cfg.C) {
-        case 16: return launch_mfma<T, 16>(ctx, cv, h, w, ws, st);
-        case 32: return launch_mfma<T, 32>(ctx, cv, h, w, ws, st);
-        case 48: return launch_mfma<T, 48>(ctx, cv, h, w, ws, st);
-        case 64: return launch_mfma<T, 64>(ctx, cv, h, w, ws, st);
-        case 128: return launch_mfma<T, 128>(ctx, cv, h, w, ws, st);
-        case 192: return launch_mfma<T, 192>(ctx, cv, h, w, ws, st);
-        case 256: return launch_mfma<T, 256>(ctx, cv, h, w, ws, st);
+        case 16: return launch_mfma<T, 16>(ctx, cv, h, w, ws, st, tiled);
+        case 32: return launch_mfma<T, 32>(ctx, cv, h, w, ws, st, tiled);
+        case 48: return launch_mfma<T, 48>(ctx, cv, h, w, ws, st, tiled);
+        case 64: return launch_mfma<T, 64>(ctx, cv, h, w, ws, st, tiled);
+        case 128: return launch_mfma<T, 128>(ctx, cv, h, w, ws, st, tiled);
+        case 192: return launch_mfma<T, 192>(ctx, cv, h, w, ws, st, tiled);
+        case 256: return launch_mfma<T, 256>(ctx, cv, h, w, ws, st, tiled);
     }
     return false;
 }
@@ -244,8 +265,8 @@ e2f_status e2f_launch_prepare(const e2f_ctx* ctx, const E2fCellsView& cv, const 
 e2f_status e2f_launch_project_mfma(const e2f_ctx* ctx, const E2fCellsView& cv, const void* h, const e2f_weights* w,
                                    const E2fAttnWs& ws, hipStream_t st) {
     if (cv.N == 0) return E2F_OK;
-    const bool ok = ctx->cfg.feat_dtype == E2F_BF16 ? dispatch_mfma<uint16_t>(ctx, cv, h, w, ws, st)
-                                                    : dispatch_mfma<float>(ctx, cv, h, w, ws, st);
+    const bool ok = ctx->cfg.feat_dtype == E2F_BF16 ? dispatch_mfma<uint16_t>(ctx, cv, h, w, ws, st, ctx->use_mfma_attn)
+                                                    : dispatch_mfma<float>(ctx, cv, h, w, ws, st, false);
     if (!ok) return E2F_ERR_UNSUPPORTED;
     E2F_HIP_CHECK(hipGetLastError());
     return E2F_OK;
