@@ -89,6 +89,7 @@ E2fAttnWs e2f_attn_ws_layout(const e2f_ctx* ctx, int32_t N, void* ws) {
                                               : (size_t)ctx->n * ctx->cfg.C;
     L.v = (void*)take((size_t)N * v_elems * esz);
     L.cw = (float*)take((size_t)E2F_MAX_N * 3 * 4);
+    L.wbT = (float*)take((size_t)ctx->cfg.B * ctx->cfg.H * 4);
     L.bytes = off;
     return L;
 }

@@ -106,12 +106,13 @@ __device__ __forceinline__ void align_all_blocks(const float* ck, const float* s
 // All blocks l = 0..L of D(R_ij) for the pair vector (dx,dy,dz) of length d > 0, packed at d_offset(l).
 template <int L>
 __device__ __forceinline__ void align_D(float dx, float dy, float dz, float d, float* D) {
-    const float inv = 1.0f / d;
-    const float rho = sqrtf(dx * dx + dy * dy);
+    // hardware reciprocal and square root (1 ulp): the angles only feed rotation matrices
+    const float inv = __builtin_amdgcn_rcpf(d);
+    const float rho = __builtin_amdgcn_sqrtf(dx * dx + dy * dy);
     const float ct = dz * inv, st = rho * inv;
     float cp = 1.0f, sp = 0.0f;
     if (rho > 0.0f) {
-        const float ir = 1.0f / rho;
+        const float ir = __builtin_amdgcn_rcpf(rho);
         cp = dx * ir;
         sp = dy * ir;
     }
@@ -129,7 +130,7 @@ __device__ __forceinline__ void align_D(float dx, float dy, float dz, float d, f
 
 // Radial pieces of Eq. attn: gate phi(d) and the Gaussian basis value g_b(d).
 __device__ __forceinline__ float radial_gate(float d, float cutoff) {
-    return 0.5f * (1.0f + cosf(3.14159265358979323846f * d / cutoff));
+    return 0.5f * (1.0f + __cosf(3.14159265358979323846f * d / cutoff));
 }
 __device__ __forceinline__ float radial_basis(float d, int b, float step, float gamma) {
     const float t = d - (float)b * step;

@@ -39,7 +39,7 @@ struct MfmaParams {
     const float* k;
     const uint16_t* vt;  // [slot][H][NT][16 channels][16 tile rows] bf16
     const float* cw;
-    const float* Wb;
+    const float* WbT;  // [B][H]
     float* out;
     int B;
     float tau, rc2, cutoff, rbf_step, rbf_gamma;
@@ -48,7 +48,7 @@ struct MfmaParams {
 };
 
 constexpr int SC = 32;     // pairs per super-chunk
-constexpr int CAPM = 160;  // capacity of the neighbour list in LDS
+constexpr int CAPM = 320;  // capacity of the neighbour list in LDS (a fill step can add up to 256)
 
 // Tile order of the components.  tile 0 = HI, tile 1 = LO.
 __device__ __forceinline__ bool tile_row_to_lm(int tile, int row, int L, int& l, int& m) {
@@ -79,7 +79,6 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) void
     __shared__ float s_bias[SC * H];
     __shared__ float s_wgt[SC];
     __shared__ float s_s[SC * H];
-    __shared__ int s_lo[9], s_hi[9];
     __shared__ float s_cw[E2F_MAX_N * 3];
 
 #ifdef E2F_TIMING
@@ -155,38 +154,44 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) void
         for (int T = 0; T < NT; ++T) acc[h][T] = (f32x4){0.f, 0.f, 0.f, 0.f};
     float mu = -INFINITY, z = 0.0f;
 
+    // The 9 stencil runs as one candidate range [0, pre[9]): candidate c lies in run r when pre[r] <= c < pre[r+1].
+    int lo[9], pre[10];
     {
-        int lo[9], hi[9];
+        int hi[9];
         e2f::stencil_rows(P.cv, t, lo, hi);
+        pre[0] = 0;
 #pragma unroll
-        for (int r = 0; r < 9; ++r)
-            if (lane == 0) { s_lo[r] = lo[r]; s_hi[r] = hi[r]; }
+        for (int r = 0; r < 9; ++r) pre[r + 1] = pre[r] + (hi[r] - lo[r]);
     }
-    __syncthreads();
-
-    int row = 0, base = s_lo[0];
-    bool rows_done = false;
+    const int n_cand = pre[9];
+    int cbase = 0;
     while (true) {
-        // ---- fill the list
+        // ---- fill the list: 4 x 64 candidates per step, their positions requested together
         int cnt = 0;
-        while (!rows_done && cnt + 64 <= CAPM) {
-            if (base >= s_hi[row]) {
-                ++row;
-                if (row == 9) { rows_done = true; break; }
-                base = s_lo[row];
-                continue;
+        while (cbase < n_cand && cnt + 256 <= CAPM) {
+            int jj[4];
+            float4 pj[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int c = cbase + 64 * u + lane;
+                int j = -1;
+#pragma unroll
+                for (int r = 0; r < 9; ++r)
+                    if (c >= pre[r] && c < pre[r + 1]) j = lo[r] + c - pre[r];
+                jj[u] = j;
+                pj[u] = P.spos[j >= 0 ? j : t];
             }
-            const int j = base + lane;
-            bool ok = false;
-            if (j < s_hi[row] && j != t) {
-                const float4 pj = P.spos[j];
-                ok = e2f::is_neighbor(e2f::dist2_exact(pi.x, pi.y, pi.z, pj.x, pj.y, pj.z), P.rc2);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const bool ok = jj[u] >= 0 && jj[u] != t &&
+                                e2f::is_neighbor(e2f::dist2_exact(pi.x, pi.y, pi.z, pj[u].x, pj[u].y, pj[u].z), P.rc2);
+                const unsigned long long mask = __ballot(ok);
+                if (ok) s_list[cnt + __popcll(mask & ((1ull << lane) - 1ull))] = jj[u];
+                cnt += __popcll(mask);
             }
-            const unsigned long long mask = __ballot(ok);
-            if (ok) s_list[cnt + __popcll(mask & ((1ull << lane) - 1ull))] = j;
-            cnt += __popcll(mask);
-            base += 64;
+            cbase += 256;
         }
+        const bool rows_done = cbase >= n_cand;
         __syncthreads();
         TICK(0)
         for (int p0 = 0; p0 < cnt; p0 += SC) {
@@ -199,11 +204,16 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) void
                 const float d = sqrtf(dx * dx + dy * dy + dz * dz);
                 e2f::align_D<L>(dx, dy, dz, d, s_D + lane * DST);
                 s_D[lane * DST + ZERO] = 0.0f;
-                for (int hh = 0; hh < H; ++hh) {
-                    float a = 0.0f;
-                    for (int b = 0; b < P.B; ++b) a += P.Wb[hh * P.B + b] * e2f::radial_basis(d, b, P.rbf_step, P.rbf_gamma);
-                    s_bias[lane * H + hh] = a;
+                float bias[H];
+#pragma unroll
+                for (int hh = 0; hh < H; ++hh) bias[hh] = 0.0f;
+                for (int b = 0; b < P.B; ++b) {  // WbT is [B][H]: one uniform load per basis function
+                    const float gb = e2f::radial_basis(d, b, P.rbf_step, P.rbf_gamma);
+#pragma unroll
+                    for (int hh = 0; hh < H; ++hh) bias[hh] += P.WbT[b * H + hh] * gb;
                 }
+#pragma unroll
+                for (int hh = 0; hh < H; ++hh) s_bias[lane * H + hh] = bias[hh];
                 s_wgt[lane] = e2f::radial_gate(d, P.cutoff) * d;
             }
             __syncthreads();
@@ -357,7 +367,7 @@ e2f_status e2f_launch_fused_mfma(const e2f_ctx* ctx, const E2fCellsView& cv, con
     if (cv.N == 0) return E2F_OK;
     MfmaParams P;
     P.cv = cv;
-    P.spos = ws.spos; P.q = ws.q; P.k = ws.k; P.vt = (const uint16_t*)ws.v; P.cw = ws.cw; P.Wb = w->Wb; P.out = out;
+    P.spos = ws.spos; P.q = ws.q; P.k = ws.k; P.vt = (const uint16_t*)ws.v; P.cw = ws.cw; P.WbT = ws.wbT; P.out = out;
     P.B = ctx->cfg.B;
     P.dbg = nullptr;
 #ifdef E2F_TIMING

@@ -64,6 +64,7 @@ struct E2fAttnWs {
     float* k;       // [N][L+1][C]
     void* v;        // [N][n][C] sorted order, float or bf16 (follows feat_dtype)
     float* cw;      // [n][3] P coefficients times path weights
+    float* wbT;     // [B][H] radial bias weights, transposed
     size_t bytes;
 };
 E2fAttnWs e2f_attn_ws_layout(const e2f_ctx* ctx, int32_t N, void* ws);

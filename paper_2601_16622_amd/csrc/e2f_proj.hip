@@ -18,8 +18,10 @@ struct CoefTable {
 
 // spos[slot] = position of the atom in that slot; cw[comp][t] = P coefficient times its path weight.
 __global__ void k_prepare(E2fCellsView cv, const float* __restrict__ pos, const float* __restrict__ w_path, int L,
-                          int lf, CoefTable tab, float4* __restrict__ spos, float* __restrict__ cw) {
+                          int lf, CoefTable tab, float4* __restrict__ spos, float* __restrict__ cw,
+                          const float* __restrict__ Wb, int H, int B, float* __restrict__ wbT) {
     const int t = blockIdx.x * blockDim.x + threadIdx.x;
+    if (t < H * B) wbT[(t % B) * H + t / B] = Wb[t];
     if (t < cv.N) {
         const int a = cv.perm[t];
         spos[t] = make_float4(pos[3 * a], pos[3 * a + 1], pos[3 * a + 2], 0.0f);
@@ -256,8 +258,10 @@ e2f_status e2f_launch_prepare(const e2f_ctx* ctx, const E2fCellsView& cv, const 
     CoefTable tab;
     for (int x = 0; x < E2F_MAX_N; ++x)
         for (int t = 0; t < 3; ++t) tab.c[x][t] = ctx->coefP[x][t];
-    const int work = cv.N > ctx->n * 3 ? cv.N : ctx->n * 3;
-    k_prepare<<<(work + 255) / 256, 256, 0, st>>>(cv, pos, w->w_path, ctx->cfg.L_max, ctx->cfg.lf, tab, ws.spos, ws.cw);
+    int work = cv.N > ctx->n * 3 ? cv.N : ctx->n * 3;
+    if (ctx->cfg.H * ctx->cfg.B > work) work = ctx->cfg.H * ctx->cfg.B;
+    k_prepare<<<(work + 255) / 256, 256, 0, st>>>(cv, pos, w->w_path, ctx->cfg.L_max, ctx->cfg.lf, tab, ws.spos, ws.cw,
+                                                 w->Wb, ctx->cfg.H, ctx->cfg.B, ws.wbT);
     E2F_HIP_CHECK(hipGetLastError());
     return E2F_OK;
 }
