@@ -60,6 +60,11 @@ __device__ __forceinline__ bool tile_row_to_lm(int tile, int row, int L, int& l,
     return l <= L;
 }
 
+// Value held by a lane known at compile time, as a wave-uniform scalar (no LDS traffic, unlike __shfl).
+__device__ __forceinline__ float read_lane(float x, int src_lane) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, x), src_lane));
+}
+
 __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
     f32x2 v = {a, b};
     return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
@@ -253,7 +258,7 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) void
             mu = mu_new;
 #pragma unroll
             for (int h = 0; h < H; ++h) {
-                const float sc = __shfl(scale, 8 * h);
+                const float sc = read_lane(scale, 8 * h);
 #pragma unroll
                 for (int T = 0; T < NT; ++T) acc[h][T] *= sc;
             }
@@ -270,50 +275,69 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) void
 #pragma unroll
                     for (int T = 0; T < NT; ++T) dst[h][T] = *reinterpret_cast<const s16x4*>(vj + (h * NT + T) * 256);
             };
-            auto compute = [&](int p, const s16x4 (&vv)[H][NT]) {
-                const float pe = __expf(s_s[p * H + head] - mu);
-                z += pe;
-                const float wl = pe * s_wgt[p];
-                const float* Dp = s_D + p * DST;
+            // Fragments of one pair: D1 (rotate in) and M = D^T P (re-index + rotate back), bf16.
+            struct Frags {
                 s16x4 d1[NT];
                 bf16x8 mf[NT];
+                float wl;
+            };
+            auto assemble = [&](int p) {
+                Frags f;
+                const float pe = __expf(s_s[p * H + head] - mu);
+                f.wl = pe * s_wgt[p];   // per lane: weight of this lane's head; pe is added to z when the pair is consumed
+                const float* Dp = s_D + p * DST;
 #pragma unroll
                 for (int T = 0; T < NT; ++T) {
                     uint32_t u0 = pack_bf16(Dp[offD1[T][0]], Dp[offD1[T][1]]);
                     uint32_t u1 = pack_bf16(Dp[offD1[T][2]], Dp[offD1[T][3]]);
-                    d1[T] = __builtin_bit_cast(s16x4, make_uint2(u0, u1));
+                    f.d1[T] = __builtin_bit_cast(s16x4, make_uint2(u0, u1));
                     uint32_t m0 = pack_bf16(Dp[offM[T][0]] * cM[T][0], Dp[offM[T][1]] * cM[T][1]);
                     uint32_t m1 = pack_bf16(Dp[offM[T][2]] * cM[T][2], Dp[offM[T][3]] * cM[T][3]);
                     uint32_t m2 = pack_bf16(Dp[offM[T][4]] * cM[T][4], Dp[offM[T][5]] * cM[T][5]);
                     uint32_t m3 = pack_bf16(Dp[offM[T][6]] * cM[T][6], Dp[offM[T][7]] * cM[T][7]);
-                    mf[T] = __builtin_bit_cast(bf16x8, make_uint4(m0, m1, m2, m3));
+                    f.mf[T] = __builtin_bit_cast(bf16x8, make_uint4(m0, m1, m2, m3));
                 }
+                return f;
+            };
+            // Heads are software-pipelined: the rotate-in MFMAs of head h+1 are issued before the scale/convert
+            // work of head h, so that the matrix pipe and the vector ALU overlap inside one wave.
+            auto rotate_in = [&](const Frags& f, const s16x4 (&vv)[H][NT], int h, f32x4 (&vt)[2]) {
+                vt[0] = (f32x4){0.f, 0.f, 0.f, 0.f};
+                vt[1] = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int T = 0; T < NT; ++T)
+                    vt[T0 + T] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(f.d1[T], vv[h][T], (f32x4){0.f, 0.f, 0.f, 0.f}, 0, 0, 0);
+            };
+            auto compute = [&](const Frags& f, const s16x4 (&vv)[H][NT]) {
+                f32x4 vt[2][2];
+                rotate_in(f, vv, 0, vt[0]);
 #pragma unroll
                 for (int h = 0; h < H; ++h) {
-                    const float w = __shfl(wl, 8 * h);
-                    f32x4 vt[2];
-                    vt[0] = (f32x4){0.f, 0.f, 0.f, 0.f};
-                    vt[1] = (f32x4){0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                    for (int T = 0; T < NT; ++T)
-                        vt[T0 + T] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(d1[T], vv[h][T], (f32x4){0.f, 0.f, 0.f, 0.f}, 0, 0, 0);
-                    const uint32_t b0 = pack_bf16(vt[0][0] * w, vt[0][1] * w), b1 = pack_bf16(vt[0][2] * w, vt[0][3] * w);
-                    const uint32_t b2 = pack_bf16(vt[1][0] * w, vt[1][1] * w), b3 = pack_bf16(vt[1][2] * w, vt[1][3] * w);
+                    if (h + 1 < H) rotate_in(f, vv, h + 1, vt[(h + 1) & 1]);
+                    const float w = read_lane(f.wl, 8 * h);
+                    const f32x4* v2 = vt[h & 1];
+                    const uint32_t b0 = pack_bf16(v2[0][0] * w, v2[0][1] * w), b1 = pack_bf16(v2[0][2] * w, v2[0][3] * w);
+                    const uint32_t b2 = pack_bf16(v2[1][0] * w, v2[1][1] * w), b3 = pack_bf16(v2[1][2] * w, v2[1][3] * w);
                     const bf16x8 bb = __builtin_bit_cast(bf16x8, make_uint4(b0, b1, b2, b3));
 #pragma unroll
                     for (int T = 0; T < NT; ++T)
-                        acc[h][T] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(mf[T], bb, acc[h][T], 0, 0, 0);
+                        acc[h][T] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f.mf[T], bb, acc[h][T], 0, 0, 0);
                 }
             };
             s16x4 va[H][NT], vb[H][NT];
             load_v(0, va);
+            Frags fa = assemble(0), fb;
 #pragma unroll 1
             for (int p = 0; p < np; p += 2) {
                 load_v(min(p + 1, np - 1), vb);
-                compute(p, va);
+                fb = assemble(min(p + 1, np - 1));
+                z += __expf(s_s[p * H + head] - mu);
+                compute(fa, va);
                 if (p + 1 < np) {
                     load_v(min(p + 2, np - 1), va);
-                    compute(p + 1, vb);
+                    fa = assemble(min(p + 2, np - 1));
+                    z += __expf(s_s[(p + 1) * H + head] - mu);
+                    compute(fb, vb);
                 }
             }
             __syncthreads();
@@ -327,7 +351,7 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) void
     float* o = P.out + (size_t)P.cv.perm[t] * (L + 1) * (L + 1) * C;
 #pragma unroll
     for (int h = 0; h < H; ++h) {
-        const float zi = __shfl(zinv, 8 * h);
+        const float zi = read_lane(zinv, 8 * h);
 #pragma unroll
         for (int T = 0; T < NT; ++T)
 #pragma unroll
