@@ -112,10 +112,23 @@ def main():
 
     attn_ms = stage_ms["attention"]
     achieved = E * f_edge / (attn_ms * 1e-3) / 1e12 if attn_ms > 0 else 0.0
-    roofline = {"bound": "alu", "kernel": "k_fused_valu", "achieved": round(achieved, 3), "peak": PEAK_ALU_TFLOPS,
+    on_mfma = (cfg["dtype"] == "bf16" and cfg["C"] // cfg["H"] == 16 and cfg["lf"] == 1 and cfg["L"] >= 1
+               and cfg["H"] in (1, 2, 4, 8) and os.environ.get("E2F_ATTENTION") != "valu")
+    # formal bound of the attention kernel: max(HBM time, MFMA time of the dense pieces, plain-ALU time of the rest)
+    L, C, H, B = cfg["L"], cfg["C"], cfg["H"], cfg["B"]
+    n = (L + 1) ** 2
+    S2 = sum((2 * l + 1) ** 2 for l in range(L + 1))
+    f_dense = E * (2 * (L + 1) * C + 4 * S2 * C)
+    f_rest = E * f_edge - f_dense
+    esz = 2 if cfg["dtype"] == "bf16" else 4
+    hbm_bytes = N * (16 + 2 * (L + 1) * C * 4 + n * C * esz + n * C * 4)
+    t_roof_ms = max(hbm_bytes / 8e12, f_dense / (2.5e15 if esz == 2 else 157.3e12), f_rest / 157.3e12) * 1e3
+    roofline = {"bound": "alu", "kernel": "k_fused_mfma" if on_mfma else "k_fused_valu",
+                "achieved": round(achieved, 3), "peak": PEAK_ALU_TFLOPS,
                 "unit": "TFLOP/s", "frac": round(achieved / PEAK_ALU_TFLOPS, 4), "traffic": read_traffic(),
                 "kernel_ms": round(attn_ms, 4), "flops_per_launch": E * f_edge, "pairs_per_launch": E,
-                "stage_ms": {k: round(v, 4) for k, v in stage_ms.items()}}
+                "stage_ms": {k: round(v, 4) for k, v in stage_ms.items()},
+                "t_roof_ms": round(t_roof_ms, 4), "frac_of_t_roof": round(t_roof_ms / attn_ms, 4) if attn_ms > 0 else 0.0}
 
     result = {
         "metric": "atoms/sec of fused equivariant attention forward (cells + projections + attention)",
