@@ -135,29 +135,26 @@ __global__ void k_cells_assign(const float* __restrict__ pos, const int32_t* __r
 }
 
 // One block: in-place inclusive scan of data[0..n) (data[0] is 0, data[c+1] the count of cell c), which turns
-// the counts into first-slot offsets.
+// the counts into first-slot offsets.  Every thread sums one contiguous chunk, the chunk sums are scanned across
+// the block, and a second sweep writes the running totals.
 __global__ void k_cells_scan(int32_t* __restrict__ data, int n) {
     __shared__ int s_part[1024];
-    __shared__ int s_carry;
-    if (threadIdx.x == 0) s_carry = 0;
+    const int chunk = (n + (int)blockDim.x - 1) / (int)blockDim.x;
+    const int b = min((int)threadIdx.x * chunk, n), e = min(b + chunk, n);
+    int sum = 0;
+    for (int i = b; i < e; ++i) sum += data[i];
+    s_part[threadIdx.x] = sum;
     __syncthreads();
-    for (int i0 = 0; i0 < n; i0 += blockDim.x) {
-        const int i = i0 + threadIdx.x;
-        const int val = (i < n) ? data[i] : 0;
-        s_part[threadIdx.x] = val;
+    for (int off = 1; off < (int)blockDim.x; off <<= 1) {
+        const int v = (threadIdx.x >= (unsigned)off) ? s_part[threadIdx.x - off] : 0;
         __syncthreads();
-        for (int off = 1; off < (int)blockDim.x; off <<= 1) {
-            int v = (threadIdx.x >= (unsigned)off) ? s_part[threadIdx.x - off] : 0;
-            __syncthreads();
-            s_part[threadIdx.x] += v;
-            __syncthreads();
-        }
-        const int incl = s_part[threadIdx.x];
-        const int carry = s_carry;
-        if (i < n) data[i] = carry + incl;
+        s_part[threadIdx.x] += v;
         __syncthreads();
-        if (threadIdx.x == blockDim.x - 1) s_carry = carry + incl;
-        __syncthreads();
+    }
+    int run = s_part[threadIdx.x] - sum;
+    for (int i = b; i < e; ++i) {
+        run += data[i];
+        data[i] = run;
     }
 }
 

@@ -71,6 +71,25 @@ struct Frag<float> {
 
 // C is the channel count (compile time so that fragments stay in registers), MG the number of orders m
 // whose A fragments are held at once, CT the number of 16-wide output tiles per wave.
+// Stores cnt consecutive bf16 values val[0..cnt) at row[pos0..pos0+cnt): 4-byte stores wherever two neighbours
+// share an aligned word, 2-byte stores at the ragged ends.  row is 4-byte aligned; pos0 and cnt are wave-uniform.
+template <int MAXN>
+__device__ __forceinline__ void store_run_bf16(uint16_t* row, int pos0, const float (&val)[MAXN], int cnt) {
+    const int lead = pos0 & 1;
+    if (lead && cnt > 0) row[pos0] = e2f::float_to_bf16_bits(val[0]);
+#pragma unroll
+    for (int k = 0; k + 1 < MAXN; ++k) {
+        // pairs start at k = lead, lead + 2, ...
+        if (((k - lead) & 1) == 0 && k >= lead && k + 1 < cnt) {
+            const uint32_t w = (uint32_t)e2f::float_to_bf16_bits(val[k]) | ((uint32_t)e2f::float_to_bf16_bits(val[k + 1]) << 16);
+            *reinterpret_cast<uint32_t*>(row + pos0 + k) = w;
+        }
+    }
+#pragma unroll
+    for (int k = 0; k < MAXN; ++k)
+        if (k == cnt - 1 && k >= lead && ((k - lead) & 1) == 0) row[pos0 + k] = e2f::float_to_bf16_bits(val[k]);
+}
+
 // TILED: store v for the MFMA attention kernel, bf16 [slot][head][tile][16 channels][16 tile rows] with the
 // components in tile order (HI: l=4 rows 0..8, l=3 rows 9..15; LO: l=2 rows 0..4, l=1 rows 5..7, l=0 row 8,
 // rows 9..15 zero), heads of 16 channels.
@@ -133,34 +152,44 @@ __global__ __launch_bounds__(64) void k_project_mfma(E2fCellsView cv, const T* _
                 }
                 if (which == 0) qacc[ct] = acc; else kacc[ct] = acc;
             }
-            // v: stored per order
+            // v: one projection, stored per order (accumulator layout: lane (g, i) holds rows 4g + r, column i)
             typename F::type BV[NS];
 #pragma unroll
             for (int S = 0; S < NS; ++S) BV[S] = F::load(WV + wr, S, g);
+            f32x4 pv[MG];
 #pragma unroll
             for (int mm = 0; mm < MG; ++mm) {
+                pv[mm] = (f32x4){0.f, 0.f, 0.f, 0.f};
                 if (m0 + mm < nl) {
-                    f32x4 p = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                    for (int S = 0; S < NS; ++S) p = F::mma(A[mm][S], BV[S], p);
-                    // accumulator layout: lane (g, i) holds rows 4g + r, column i
+                    for (int S = 0; S < NS; ++S) pv[mm] = F::mma(A[mm][S], BV[S], pv[mm]);
+                }
+            }
 #pragma unroll
-                    for (int r = 0; r < 4; ++r) {
-                        const int slot = tile * 16 + 4 * g + r;
-                        if (slot >= N) continue;
-                        if constexpr (!TILED) {
-                            e2f::store_from_float(v + ((size_t)slot * n + l * l + m0 + mm) * C + co, p[r]);
-                        } else {
-                            const int NT = L >= 3 ? 2 : 1, mi = m0 + mm;
-                            const int TI = l >= 3 ? 0 : NT - 1;
-                            const int pos = l == 4 ? mi : (l == 3 ? 9 + mi : (l == 2 ? mi : (l == 1 ? 5 + mi : 8)));
-                            T* dst = v + ((((size_t)slot * (C / 16) + (co >> 4)) * NT + TI) * 16 + (co & 15)) * 16;
-                            e2f::store_from_float(dst + pos, p[r]);
-                            if (l == 0)
-                                for (int z = 9; z < 16; ++z) e2f::store_from_float(dst + z, 0.0f);
-                            if (l == 3 && L == 3 && mi == 0)
-                                for (int z = 0; z < 9; ++z) e2f::store_from_float(dst + z, 0.0f);
-                        }
+            for (int r = 0; r < 4; ++r) {
+                const int slot = tile * 16 + 4 * g + r;
+                if (slot >= N) continue;
+                if constexpr (!TILED) {
+#pragma unroll
+                    for (int mm = 0; mm < MG; ++mm)
+                        if (m0 + mm < nl) e2f::store_from_float(v + ((size_t)slot * n + l * l + m0 + mm) * C + co, pv[mm][r]);
+                } else {
+                    const int NT = L >= 3 ? 2 : 1;
+                    const int TI = l >= 3 ? 0 : NT - 1;
+                    const int pos_l = l == 4 ? 0 : (l == 3 ? 9 : (l == 2 ? 0 : (l == 1 ? 5 : 8)));
+                    uint16_t* row = reinterpret_cast<uint16_t*>(v) +
+                                    ((((size_t)slot * (C / 16) + (co >> 4)) * NT + TI) * 16 + (co & 15)) * 16;
+                    float val[MG];
+#pragma unroll
+                    for (int mm = 0; mm < MG; ++mm) val[mm] = pv[mm][r];
+                    store_run_bf16<MG>(row, pos_l + m0, val, min(MG, nl - m0));
+                    if (l == 0) {  // rows 9..15 of the LO tile are padding and must read as zero
+                        const float zero[7] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+                        store_run_bf16<7>(row, 9, zero, 7);
+                    }
+                    if (l == 3 && L == 3 && m0 == 0) {  // without l = 4 the first nine HI rows are padding
+                        const float zero[9] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+                        store_run_bf16<9>(row, 0, zero, 9);
                     }
                 }
             }
@@ -177,6 +206,275 @@ __global__ __launch_bounds__(64) void k_project_mfma(E2fCellsView cv, const T* _
                 k[((size_t)slot * (L + 1) + l) * C + co] = kacc[ct][r];
             }
         }
+    }
+}
+
+// Weight-stationary variant for bf16 features (the fast path): a wave keeps the five 16 x C weight tiles of one
+// degree l and one 16-channel output tile in registers as MFMA A operands and streams atoms through as B
+// operands, 16 atoms x one order m at a time, with the next slab of h requested before the current one is used.
+// Accumulator layout: lane (g, j) holds output channels 16*ct + 4g..4g+3 of atom j, so q and k go out as 16-byte
+// stores and v as runs of consecutive orders.  All (l, channel tile) waves of one group of TPW atom tiles are
+// dispatched back to back onto the same XCD, so that the partial rows they write (q, k rows are shared by the
+// channel tiles, tiled v rows by two degrees) merge in that XCD's L2 before they reach memory, and the h rows
+// they all read are fetched once.
+template <int C, bool TILED>
+__global__ __launch_bounds__(64) void k_project_ws(E2fCellsView cv, const uint16_t* __restrict__ h,
+                                                   const uint16_t* __restrict__ WQ1, const uint16_t* __restrict__ WQ2,
+                                                   const uint16_t* __restrict__ WK1, const uint16_t* __restrict__ WK2,
+                                                   const uint16_t* __restrict__ WV, int L, int tpw,
+                                                   float* __restrict__ q, float* __restrict__ k,
+                                                   uint16_t* __restrict__ v) {
+    typedef Frag<uint16_t> F;
+    constexpr int NS = C / F::KSTEP;
+    constexpr int NCT = C / 16;
+    const int N = cv.N, n = (L + 1) * (L + 1);
+    const int n_tiles = (N + 15) / 16;
+    // block -> (XCD, position inside the XCD's queue) -> (group of atom tiles, degree, channel tile)
+    const int per_group = (L + 1) * NCT;
+    const int xcd = blockIdx.x & 7, rest = blockIdx.x >> 3;
+    const int group = (rest / per_group) * 8 + xcd, lc = rest % per_group;
+    const int l = lc / NCT, ct = lc % NCT, nl = 2 * l + 1;
+    const int lane = threadIdx.x, j = lane & 15, g = lane >> 4;
+    const int tile0 = group * tpw, tile1 = min(tile0 + tpw, n_tiles);
+    if (tile0 >= tile1) return;
+
+    // stationary A operands: row (16 ct + j) of each weight matrix of degree l
+    const size_t wrow = ((size_t)l * C + (ct * 16 + j)) * C;
+    F::type Wf[5][NS];
+#pragma unroll
+    for (int S = 0; S < NS; ++S) {
+        Wf[0][S] = F::load(WQ1 + wrow, S, g);
+        Wf[1][S] = F::load(WQ2 + wrow, S, g);
+        Wf[2][S] = F::load(WK1 + wrow, S, g);
+        Wf[3][S] = F::load(WK2 + wrow, S, g);
+        Wf[4][S] = F::load(WV + wrow, S, g);
+    }
+
+    auto load_x = [&](int tile, int m, F::type (&X)[NS]) {
+        const int slot = min(tile * 16 + j, N - 1);  // clamped atoms are computed and not stored
+        const uint16_t* row = h + ((size_t)cv.perm[slot] * n + l * l + m) * C;
+#pragma unroll
+        for (int S = 0; S < NS; ++S) X[S] = F::load(row, S, g);
+    };
+
+    // The weight tiles must have arrived before the streaming loads start: inside the loop the only loads in
+    // flight are then the ring's own, in order, and the waits the compiler inserts leave PD-1 slabs outstanding
+    // (with the weight loads still pending at loop entry every step would wait for everything).
+    {
+        typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+#pragma unroll
+        for (int w = 0; w < 5; ++w)
+#pragma unroll
+            for (int S = 0; S < NS; ++S) asm volatile("" ::"v"(__builtin_bit_cast(u32x4, Wf[w][S])));
+    }
+    // The (atom tile, order) steps of this wave form one sequence; PD slabs of h are in flight at any time
+    // (memory latency is several steps long), in a ring of register buffers indexed at compile time.
+    constexpr int PD = 4;
+    const int n_steps = (tile1 - tile0) * nl;
+    F::type X[PD][NS];
+#pragma unroll
+    for (int u = 0; u < PD; ++u) {
+        const int su = min(u, max(n_steps - 1, 0));
+        load_x(tile0 + su / nl, su % nl, X[u]);
+    }
+    f32x4 qacc = {0.f, 0.f, 0.f, 0.f}, kacc = {0.f, 0.f, 0.f, 0.f};
+    float vrun[4][2 * E2F_MAX_L + 1];
+    for (int s0 = 0; s0 < n_steps; s0 += PD) {
+#pragma unroll
+        for (int u = 0; u < PD; ++u) {
+            const int st = s0 + u;
+            if (st < n_steps) {
+                const int tile = tile0 + st / nl, m = st % nl;
+                const int slot = tile * 16 + j;
+                // five independent accumulation chains, interleaved so that no MFMA waits for its predecessor
+                f32x4 p[5];
+#pragma unroll
+                for (int w = 0; w < 5; ++w) p[w] = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int S = 0; S < NS; ++S)
+#pragma unroll
+                    for (int w = 0; w < 5; ++w) p[w] = F::mma(Wf[w][S], X[u][S], p[w]);
+                // this buffer is free again: request the slab PD steps ahead (clamped to the last step)
+                {
+                    const int sn = min(st + PD, n_steps - 1);
+                    load_x(tile0 + sn / nl, sn % nl, X[u]);
+                }
+                qacc += p[0] * p[1];
+                kacc += p[2] * p[3];
+                if constexpr (TILED) {
+#pragma unroll
+                    for (int mm = 0; mm < 2 * E2F_MAX_L + 1; ++mm)
+                        if (mm == m) {
+#pragma unroll
+                            for (int r = 0; r < 4; ++r) vrun[r][mm] = p[4][r];
+                        }
+                } else if (slot < N) {
+                    uint16_t* dst = v + ((size_t)slot * n + l * l + m) * C + ct * 16 + 4 * g;
+                    const uint32_t w0 = (uint32_t)e2f::float_to_bf16_bits(p[4][0]) | ((uint32_t)e2f::float_to_bf16_bits(p[4][1]) << 16);
+                    const uint32_t w1 = (uint32_t)e2f::float_to_bf16_bits(p[4][2]) | ((uint32_t)e2f::float_to_bf16_bits(p[4][3]) << 16);
+                    *reinterpret_cast<uint2*>(dst) = make_uint2(w0, w1);
+                }
+                if (m == nl - 1) {  // last order of this atom tile: q, k (and the tiled v rows) go out
+                    if (slot < N) {
+                        *reinterpret_cast<f32x4*>(q + ((size_t)slot * (L + 1) + l) * C + ct * 16 + 4 * g) = qacc;
+                        *reinterpret_cast<f32x4*>(k + ((size_t)slot * (L + 1) + l) * C + ct * 16 + 4 * g) = kacc;
+                        if constexpr (TILED) {
+                            const int NT = L >= 3 ? 2 : 1;
+                            const int TI = l >= 3 ? 0 : NT - 1;
+                            const int pos_l = l == 4 ? 0 : (l == 3 ? 9 : (l == 2 ? 0 : (l == 1 ? 5 : 8)));
+#pragma unroll
+                            for (int r = 0; r < 4; ++r) {
+                                uint16_t* row = v + ((((size_t)slot * NCT + ct) * NT + TI) * 16 + 4 * g + r) * 16;
+                                store_run_bf16<2 * E2F_MAX_L + 1>(row, pos_l, vrun[r], nl);
+                                if (l == 0) {
+                                    const float zero[7] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+                                    store_run_bf16<7>(row, 9, zero, 7);
+                                }
+                                if (l == 3 && L == 3) {
+                                    const float zero[9] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+                                    store_run_bf16<9>(row, 0, zero, 9);
+                                }
+                            }
+                        }
+                    }
+                    qacc = (f32x4){0.f, 0.f, 0.f, 0.f};
+                    kacc = (f32x4){0.f, 0.f, 0.f, 0.f};
+                }
+            }
+        }
+    }
+}
+
+// Workgroup variant of the weight-stationary projection for the tiled v layout.  Global stores inside the
+// streaming loop would share the wave's memory counter with the prefetched loads and force every wait to drain
+// all of them, so nothing is stored while streaming: three waves split the degrees of one (32 atoms, 16
+// channels) block between them (balanced by their number of orders), put q, k and the bf16 v tiles into LDS,
+// and after a barrier the whole workgroup copies the finished block out with 16-byte, fully coalesced stores
+// (every (atom, head) owns 1 KB of contiguous v).
+constexpr int WG_TPW = 2;      // atom tiles (of 16) per workgroup
+constexpr int WG_WAVES = 3;
+struct WgRoles {
+    int n_deg[WG_WAVES];
+    int deg[WG_WAVES][E2F_MAX_L + 1];
+};
+
+template <int C>
+__global__ __launch_bounds__(64 * WG_WAVES) void k_project_wg(E2fCellsView cv, const uint16_t* __restrict__ h,
+                                                              const uint16_t* __restrict__ WQ1,
+                                                              const uint16_t* __restrict__ WQ2,
+                                                              const uint16_t* __restrict__ WK1,
+                                                              const uint16_t* __restrict__ WK2,
+                                                              const uint16_t* __restrict__ WV, int L, WgRoles roles,
+                                                              float* __restrict__ q, float* __restrict__ k,
+                                                              uint16_t* __restrict__ v) {
+    typedef Frag<uint16_t> F;
+    constexpr int NS = C / F::KSTEP;
+    constexpr int NCT = C / 16;
+    constexpr int PD = 4;
+    __shared__ __attribute__((aligned(16))) uint16_t s_v[WG_TPW * 16 * 2 * 256];          // [tile][atom][T][ch][pos]
+    __shared__ __attribute__((aligned(16))) float s_q[WG_TPW * 16 * (E2F_MAX_L + 1) * 16];  // [tile][atom][l][ch]
+    __shared__ __attribute__((aligned(16))) float s_k[WG_TPW * 16 * (E2F_MAX_L + 1) * 16];
+
+    const int N = cv.N, n = (L + 1) * (L + 1), NT = L >= 3 ? 2 : 1;
+    const int n_tiles = (N + 15) / 16;
+    const int xcd = blockIdx.x & 7, rest = blockIdx.x >> 3;
+    const int group = (rest / NCT) * 8 + xcd, ct = rest % NCT;
+    const int tile0 = group * WG_TPW, tile1 = min(tile0 + WG_TPW, n_tiles);
+    if (tile0 >= tile1) return;   // whole workgroup leaves together
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, j = lane & 15, g = lane >> 4;
+
+    for (int x = tid; x < WG_TPW * 16 * 2 * 256 / 8; x += 64 * WG_WAVES)
+        reinterpret_cast<uint4*>(s_v)[x] = make_uint4(0u, 0u, 0u, 0u);   // padding rows must read as zero
+    // Atom index of this lane's row in every tile, fetched once: an index load inside the streaming loop would
+    // have to be waited for, and waiting for the youngest load drains all the older ones.
+    int atom_of[WG_TPW];
+#pragma unroll
+    for (int x = 0; x < WG_TPW; ++x) atom_of[x] = cv.perm[min((tile0 + x) * 16 + j, N - 1)];
+    __syncthreads();
+
+    for (int di = 0; di < roles.n_deg[wave]; ++di) {
+        const int l = roles.deg[wave][di], nl = 2 * l + 1;
+        const size_t wrow = ((size_t)l * C + (ct * 16 + j)) * C;
+        F::type Wf[5][NS];
+#pragma unroll
+        for (int S = 0; S < NS; ++S) {
+            Wf[0][S] = F::load(WQ1 + wrow, S, g);
+            Wf[1][S] = F::load(WQ2 + wrow, S, g);
+            Wf[2][S] = F::load(WK1 + wrow, S, g);
+            Wf[3][S] = F::load(WK2 + wrow, S, g);
+            Wf[4][S] = F::load(WV + wrow, S, g);
+        }
+        {   // the weight tiles must have arrived before the streaming loads start (see k_project_ws)
+            typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+#pragma unroll
+            for (int w = 0; w < 5; ++w)
+#pragma unroll
+                for (int S = 0; S < NS; ++S) asm volatile("" ::"v"(__builtin_bit_cast(u32x4, Wf[w][S])));
+        }
+        const int n_steps = (tile1 - tile0) * nl;
+        auto load_x = [&](int st, F::type (&X)[NS]) {
+            const int lt = st / nl, m = st - lt * nl;
+            int atom = atom_of[0];
+#pragma unroll
+            for (int x = 1; x < WG_TPW; ++x) atom = (lt == x) ? atom_of[x] : atom;
+            const uint16_t* row = h + ((size_t)atom * n + l * l + m) * C;
+#pragma unroll
+            for (int S = 0; S < NS; ++S) X[S] = F::load(row, S, g);
+        };
+        F::type X[PD][NS];
+#pragma unroll
+        for (int u = 0; u < PD; ++u) load_x(min(u, n_steps - 1), X[u]);
+        const int TI = l >= 3 ? 0 : NT - 1;
+        const int pos_l = l == 4 ? 0 : (l == 3 ? 9 : (l == 2 ? 0 : (l == 1 ? 5 : 8)));
+        f32x4 qacc = {0.f, 0.f, 0.f, 0.f}, kacc = {0.f, 0.f, 0.f, 0.f};
+        for (int s0 = 0; s0 < n_steps; s0 += PD) {
+#pragma unroll
+            for (int u = 0; u < PD; ++u) {
+                const int st = s0 + u;
+                if (st < n_steps) {
+                    const int lt = st / nl, m = st - lt * nl;   // local tile, order
+                    f32x4 p[5];
+#pragma unroll
+                    for (int w = 0; w < 5; ++w) p[w] = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                    for (int S = 0; S < NS; ++S)
+#pragma unroll
+                        for (int w = 0; w < 5; ++w) p[w] = F::mma(Wf[w][S], X[u][S], p[w]);
+                    load_x(min(st + PD, n_steps - 1), X[u]);
+                    qacc += p[0] * p[1];
+                    kacc += p[2] * p[3];
+                    // accumulator layout: lane (g, j) holds channels 4g..4g+3 of atom j
+                    uint16_t* vrow = s_v + (((lt * 16 + j) * 2 + TI) * 16 + 4 * g) * 16 + pos_l + m;
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) vrow[r * 16] = e2f::float_to_bf16_bits(p[4][r]);
+                    if (m == nl - 1) {
+                        *reinterpret_cast<f32x4*>(s_q + ((lt * 16 + j) * (E2F_MAX_L + 1) + l) * 16 + 4 * g) = qacc;
+                        *reinterpret_cast<f32x4*>(s_k + ((lt * 16 + j) * (E2F_MAX_L + 1) + l) * 16 + 4 * g) = kacc;
+                        qacc = (f32x4){0.f, 0.f, 0.f, 0.f};
+                        kacc = (f32x4){0.f, 0.f, 0.f, 0.f};
+                    }
+                }
+            }
+        }
+    }
+    __syncthreads();
+    // ---- copy out: v, 16 bytes per thread; every (atom, head = ct) block of NT*512 bytes is contiguous
+    const int n_atoms = min(tile1 * 16, N) - tile0 * 16;
+    const int v_chunks = NT * 32;   // 16-byte chunks per atom
+    for (int x = tid; x < n_atoms * v_chunks; x += 64 * WG_WAVES) {
+        const int a = x / v_chunks, c16 = x - a * v_chunks;
+        const int T = NT == 2 ? c16 / 32 : 1, inner = c16 % 32;
+        const uint4 val = *reinterpret_cast<const uint4*>(s_v + ((a * 2 + T) * 256) + inner * 8);
+        const size_t slot = (size_t)tile0 * 16 + a;
+        *reinterpret_cast<uint4*>(v + ((slot * NCT + ct) * NT) * 256 + c16 * 8) = val;
+    }
+    // q and k: 64 contiguous bytes per (atom, degree)
+    for (int x = tid; x < n_atoms * (L + 1) * 4; x += 64 * WG_WAVES) {
+        const int a = x / ((L + 1) * 4), rem = x - a * (L + 1) * 4, l = rem >> 2, c4 = rem & 3;
+        const size_t slot = (size_t)tile0 * 16 + a;
+        const size_t dst = (slot * (L + 1) + l) * C + ct * 16 + c4 * 4;
+        *reinterpret_cast<f32x4*>(q + dst) = *reinterpret_cast<const f32x4*>(s_q + (a * (E2F_MAX_L + 1) + l) * 16 + c4 * 4);
+        *reinterpret_cast<f32x4*>(k + dst) = *reinterpret_cast<const f32x4*>(s_k + (a * (E2F_MAX_L + 1) + l) * 16 + c4 * 4);
     }
 }
 
@@ -236,6 +534,77 @@ bool launch_mfma(const e2f_ctx* ctx, const E2fCellsView& cv, const void* h, cons
     }
 }
 
+template <int C>
+bool launch_ws(const e2f_ctx* ctx, const E2fCellsView& cv, const void* h, const e2f_weights* w, const E2fAttnWs& ws,
+               hipStream_t st, bool tiled) {
+    if constexpr (C % 32 != 0 || C > 128) {
+        return false;   // five stationary weight tiles must fit the register file
+    } else {
+        const int L = ctx->cfg.L_max, n_tiles = (cv.N + 15) / 16;
+        const int tpw = 4;
+        const int groups = (n_tiles + tpw - 1) / tpw;
+        const int blocks = ((groups + 7) / 8) * (L + 1) * (C / 16) * 8;
+        const uint16_t* hh = (const uint16_t*)h;
+        if (tiled)
+            k_project_ws<C, true><<<blocks, 64, 0, st>>>(cv, hh, (const uint16_t*)w->WQ1, (const uint16_t*)w->WQ2,
+                                                         (const uint16_t*)w->WK1, (const uint16_t*)w->WK2,
+                                                         (const uint16_t*)w->WV, L, tpw, ws.q, ws.k, (uint16_t*)ws.v);
+        else
+            k_project_ws<C, false><<<blocks, 64, 0, st>>>(cv, hh, (const uint16_t*)w->WQ1, (const uint16_t*)w->WQ2,
+                                                          (const uint16_t*)w->WK1, (const uint16_t*)w->WK2,
+                                                          (const uint16_t*)w->WV, L, tpw, ws.q, ws.k, (uint16_t*)ws.v);
+        return true;
+    }
+}
+
+template <int C>
+bool launch_wg(const e2f_ctx* ctx, const E2fCellsView& cv, const void* h, const e2f_weights* w, const E2fAttnWs& ws,
+               hipStream_t st) {
+    if constexpr (C % 32 != 0 || C > 128) {
+        return false;
+    } else {
+        const int L = ctx->cfg.L_max, n_tiles = (cv.N + 15) / 16;
+        // degrees, largest first, each to the wave with the least work so far
+        WgRoles roles;
+        int load[WG_WAVES];
+        for (int wv = 0; wv < WG_WAVES; ++wv) { roles.n_deg[wv] = 0; load[wv] = 0; }
+        for (int l = L; l >= 0; --l) {
+            int best = 0;
+            for (int wv = 1; wv < WG_WAVES; ++wv)
+                if (load[wv] < load[best]) best = wv;
+            roles.deg[best][roles.n_deg[best]++] = l;
+            load[best] += 2 * l + 1;
+        }
+        const int groups = (n_tiles + WG_TPW - 1) / WG_TPW;
+        const int blocks = ((groups + 7) / 8) * 8 * (C / 16);
+        k_project_wg<C><<<blocks, 64 * WG_WAVES, 0, st>>>(cv, (const uint16_t*)h, (const uint16_t*)w->WQ1,
+                                                         (const uint16_t*)w->WQ2, (const uint16_t*)w->WK1,
+                                                         (const uint16_t*)w->WK2, (const uint16_t*)w->WV, L, roles,
+                                                         ws.q, ws.k, (uint16_t*)ws.v);
+        return true;
+    }
+}
+
+bool dispatch_wg(const e2f_ctx* ctx, const E2fCellsView& cv, const void* h, const e2f_weights* w, const E2fAttnWs& ws,
+                 hipStream_t st) {
+    switch (ctx->cfg.C) {
+        case 32: return launch_wg<32>(ctx, cv, h, w, ws, st);
+        case 64: return launch_wg<64>(ctx, cv, h, w, ws, st);
+        case 128: return launch_wg<128>(ctx, cv, h, w, ws, st);
+    }
+    return false;
+}
+
+bool dispatch_ws(const e2f_ctx* ctx, const E2fCellsView& cv, const void* h, const e2f_weights* w, const E2fAttnWs& ws,
+                 hipStream_t st, bool tiled) {
+    switch (ctx->cfg.C) {
+        case 32: return launch_ws<32>(ctx, cv, h, w, ws, st, tiled);
+        case 64: return launch_ws<64>(ctx, cv, h, w, ws, st, tiled);
+        case 128: return launch_ws<128>(ctx, cv, h, w, ws, st, tiled);
+    }
+    return false;
+}
+
 template <typename T>
 bool dispatch_mfma(const e2f_ctx* ctx, const E2fCellsView& cv, const void* h, const e2f_weights* w,
                    const E2fAttnWs& ws, hipStream_t st, bool tiled) {
@@ -269,8 +638,13 @@ e2f_status e2f_launch_prepare(const e2f_ctx* ctx, const E2fCellsView& cv, const 
 e2f_status e2f_launch_project_mfma(const e2f_ctx* ctx, const E2fCellsView& cv, const void* h, const e2f_weights* w,
                                    const E2fAttnWs& ws, hipStream_t st) {
     if (cv.N == 0) return E2F_OK;
-    const bool ok = ctx->cfg.feat_dtype == E2F_BF16 ? dispatch_mfma<uint16_t>(ctx, cv, h, w, ws, st, ctx->use_mfma_attn)
-                                                    : dispatch_mfma<float>(ctx, cv, h, w, ws, st, false);
+    bool ok;
+    if (ctx->cfg.feat_dtype == E2F_BF16)
+        ok = (ctx->use_mfma_attn && dispatch_wg(ctx, cv, h, w, ws, st)) ||
+             dispatch_ws(ctx, cv, h, w, ws, st, ctx->use_mfma_attn) ||
+             dispatch_mfma<uint16_t>(ctx, cv, h, w, ws, st, ctx->use_mfma_attn);
+    else
+        ok = dispatch_mfma<float>(ctx, cv, h, w, ws, st, false);
     if (!ok) return E2F_ERR_UNSUPPORTED;
     E2F_HIP_CHECK(hipGetLastError());
     return E2F_OK;
