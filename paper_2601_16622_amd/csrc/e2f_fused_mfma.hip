@@ -3,17 +3,20 @@
 // Sec. 3.3 inside the kernel); what changes is where the two block rotations and the re-indexing run.
 //
 // The (L+1)^2 components are split into two 16-row tiles, HI = {l=4 (9 rows), l=3 (7 rows)} and
-// LO = {l=2 (5), l=1 (3), l=0 (1), 7 unused}.  For one pair (i,j) and one head (16 channels):
+// LO = {l=2 (5), l=1 (3), l=0 (1), 7 unused}; a 32-long contraction index k = 8g + r stands for HI row 4g+r
+// (r < 4) or LO row 4g+r-4 (r >= 4).  With D1 the block-diagonal Wigner matrix of the aligning rotation and
+// M = D1^T P (the re-indexing operator folded into the back rotation, path weights included), the message
+// operator of a pair is G = M D1 = D^T P D.  Per pair, once, for every (input tile Tb, output tile To):
 //
-//   Vt_hi = D1_hi . V_hi      Vt_lo = D1_lo . V_lo          2 x v_mfma_f32_16x16x16_bf16   (rotate in)
-//   B2    = bf16( w * [Vt_hi ; Vt_lo] )                      w = e^{s-mu} * phi * |r|^lf, per (pair, head)
-//   A_hi += M_hi . B2         A_lo += M_lo . B2             2 x v_mfma_f32_16x16x32_bf16   (re-index + rotate back)
+//   X[Tb][To] = D1c[Tb] . M[To]^T          4 x v_mfma_f32_16x16x32_bf16   (X[b][o] = G[o][b])
 //
-// with D1 the block-diagonal Wigner matrix of the aligning rotation in tile order and M = D^T P (the
-// re-indexing operator folded into the back rotation, path weights included).  The accumulator layout of the
-// first pair of MFMAs (lane (g,c) holds rows 4g..4g+3 of channel c) is exactly the B-operand layout of the
-// second pair, so Vt never leaves the lane.  The running attention output A_i of Algorithm 1 is the MFMA
-// accumulator itself.
+// whose accumulator layout (lane (g,o) holds rows b = 4g..4g+3 of column o) is exactly the A-operand layout of
+// G[To] for the contraction over the 32 input rows, so G never leaves the lane: A[To] = bf16([X[HI][To]; X[LO][To]]).
+// Then for every head (16 channels), with V the neighbour's value rows in tile order as the B operand:
+//
+//   A_i[To] += w * ( G[To] . V )            2 x v_mfma_f32_16x16x32_bf16 + 8 FMAs,  w = e^{s-mu} phi |r|^lf
+//
+// The running attention output A_i of Algorithm 1 is held in the lanes as 16x16 fp32 tiles per (head, tile).
 //
 // One wave per target atom.  Pairs are found as in k_fused_valu; per super-chunk of up to SC pairs, lanes =
 // pairs compute the fp32 Wigner blocks, radial bias and gate into LDS (uniform code, no divergence).  Every
@@ -100,9 +103,10 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) void
     __syncthreads();
 
     // ---- per-lane fragment tables (constant for the whole kernel)
-    // D1 fragment of tile T: A[i][4g+r] = D^l[a][b] if row i = (l,a) and column 4g+r = (l,b) of the same degree.
-    // M fragment of out tile T: A[i][8g+r], K index 8g+r <-> aligned row (r<4: HI row 4g+r, r>=4: LO row 4g+r-4)
-    //   = (li,mi);  out row i = (lo,b):  M = D^lo[mo][b] * coef  with
+    // D1c fragment of input tile T: A[i = b][k], k <-> aligned row 4g+r of the same tile: D^l[a][b] if that row
+    //   (l,a) and column i = (l,b) have the same degree.
+    // M fragment of out tile T: B[k][j] = M[j][k], k = 8g+r <-> aligned row (r<4: HI row 4g+r, r>=4: LO row 4g+r-4)
+    //   = (li,mi);  out row j = (lo,b):  M = D^lo[mo][b] * coef  with
     //   li = lo-1: mo = mi, coef = cw[.][0];  li = lo: mo = -mi (mi != 0), coef = cw[.][1];  li = lo+1: mo = mi, cw[.][2].
     int offD1[NT][4], offM[NT][8];
     float cM[NT][8];
@@ -113,9 +117,9 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) void
         const bool row_ok = tile_row_to_lm(tile, i, L, li_, a_);
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-            int lc, b;
-            const bool col_ok = tile_row_to_lm(tile, 4 * g + r, L, lc, b);
-            offD1[T][r] = (row_ok && col_ok && lc == li_) ? e2f::d_offset(li_) + (a_ + li_) * (2 * li_ + 1) + (b + li_) : ZERO;
+            int lr, a;
+            const bool al_ok = tile_row_to_lm(tile, 4 * g + r, L, lr, a);
+            offD1[T][r] = (row_ok && al_ok && lr == li_) ? e2f::d_offset(li_) + (a + li_) * (2 * li_ + 1) + (a_ + li_) : ZERO;
         }
 #pragma unroll
         for (int r = 0; r < 8; ++r) {
@@ -145,12 +149,6 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) void
     const bool lg_active = lane < C / 2;
     const int c0 = lg_active ? 2 * lane : 0;
     const int head = c0 / 16;
-    float q[L + 1][2];
-#pragma unroll
-    for (int l = 0; l <= L; ++l) {
-        q[l][0] = P.q[((size_t)t * (L + 1) + l) * C + c0];
-        q[l][1] = P.q[((size_t)t * (L + 1) + l) * C + c0 + 1];
-    }
 
     f32x4 acc[H][NT];
 #pragma unroll
@@ -176,9 +174,13 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) void
         while (cbase < n_cand && cnt + 256 <= CAPM) {
             int jj[4];
             float4 pj[4];
+            // keep the lane id opaque here: otherwise every (lane - pre[r]) is hoisted out of the loop into its
+            // own register and the kernel spills
+            int ln = lane;
+            asm volatile("" : "+v"(ln));
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
-                const int c = cbase + 64 * u + lane;
+                const int c = cbase + 64 * u + ln;
                 int j = -1;
 #pragma unroll
                 for (int r = 0; r < 9; ++r)
@@ -225,6 +227,14 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) void
             TICK(1)
             // ---- pass 1: logits of the super-chunk (Eq. kernel_score) and their maximum per head
             float cmax = -INFINITY;
+            // the query row is re-read per super-chunk (cache hit) instead of living in registers across pass 2
+            float q[L + 1][2];
+#pragma unroll
+            for (int l = 0; l <= L; ++l) {
+                const float2 qq = *reinterpret_cast<const float2*>(P.q + ((size_t)t * (L + 1) + l) * C + c0);
+                q[l][0] = qq.x;
+                q[l][1] = qq.y;
+            }
             for (int pb = 0; pb < np; pb += 8) {
                 // all key rows of the batch are requested before the first one is used
                 float2 kk[8][L + 1];
@@ -265,20 +275,15 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) void
             __syncthreads();
             TICK(3)
             // ---- pass 2: per pair, assemble the fragments, then 4 MFMAs per head
-            // The value rows of pair p+1 are requested before pair p is computed (two register sets, loop
-            // unrolled by two so that no copies are needed).
-            auto load_v = [&](int p, s16x4 (&dst)[H][NT]) {
+            // Value rows live in one register set: as soon as head h of pair p has gone through its MFMAs, its
+            // registers are refilled with head h of pair p+1, so every load has almost a whole pair of work to land.
+            auto v_ptr = [&](int p) {
                 const int j = s_list[p0 + p];
-                const uint16_t* vj = P.vt + (size_t)j * H * NT * 256 + i * 16 + 4 * g;
-#pragma unroll
-                for (int h = 0; h < H; ++h)
-#pragma unroll
-                    for (int T = 0; T < NT; ++T) dst[h][T] = *reinterpret_cast<const s16x4*>(vj + (h * NT + T) * 256);
+                return P.vt + (size_t)j * H * NT * 256 + i * 16 + 4 * g;
             };
-            // Fragments of one pair: D1 (rotate in) and M = D^T P (re-index + rotate back), bf16.
+            // The operator of one pair, G = D^T P D, as bf16 A operands per output tile.
             struct Frags {
-                s16x4 d1[NT];
-                bf16x8 mf[NT];
+                bf16x8 ga[NT];
                 float wl;
             };
             auto assemble = [&](int p) {
@@ -286,58 +291,79 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) void
                 const float pe = __expf(s_s[p * H + head] - mu);
                 f.wl = pe * s_wgt[p];   // per lane: weight of this lane's head; pe is added to z when the pair is consumed
                 const float* Dp = s_D + p * DST;
+                bf16x8 d1c[NT], mf[NT];
 #pragma unroll
                 for (int T = 0; T < NT; ++T) {
-                    uint32_t u0 = pack_bf16(Dp[offD1[T][0]], Dp[offD1[T][1]]);
-                    uint32_t u1 = pack_bf16(Dp[offD1[T][2]], Dp[offD1[T][3]]);
-                    f.d1[T] = __builtin_bit_cast(s16x4, make_uint2(u0, u1));
-                    uint32_t m0 = pack_bf16(Dp[offM[T][0]] * cM[T][0], Dp[offM[T][1]] * cM[T][1]);
-                    uint32_t m1 = pack_bf16(Dp[offM[T][2]] * cM[T][2], Dp[offM[T][3]] * cM[T][3]);
-                    uint32_t m2 = pack_bf16(Dp[offM[T][4]] * cM[T][4], Dp[offM[T][5]] * cM[T][5]);
-                    uint32_t m3 = pack_bf16(Dp[offM[T][6]] * cM[T][6], Dp[offM[T][7]] * cM[T][7]);
-                    f.mf[T] = __builtin_bit_cast(bf16x8, make_uint4(m0, m1, m2, m3));
+                    const uint32_t u0 = pack_bf16(Dp[offD1[T][0]], Dp[offD1[T][1]]);
+                    const uint32_t u1 = pack_bf16(Dp[offD1[T][2]], Dp[offD1[T][3]]);
+                    // rows of the HI tile sit at r < 4 of the contraction index, rows of the LO tile at r >= 4
+                    d1c[T] = (T0 + T == 0) ? __builtin_bit_cast(bf16x8, make_uint4(u0, u1, 0u, 0u))
+                                           : __builtin_bit_cast(bf16x8, make_uint4(0u, 0u, u0, u1));
+                    const uint32_t m0 = pack_bf16(Dp[offM[T][0]] * cM[T][0], Dp[offM[T][1]] * cM[T][1]);
+                    const uint32_t m1 = pack_bf16(Dp[offM[T][2]] * cM[T][2], Dp[offM[T][3]] * cM[T][3]);
+                    const uint32_t m2 = pack_bf16(Dp[offM[T][4]] * cM[T][4], Dp[offM[T][5]] * cM[T][5]);
+                    const uint32_t m3 = pack_bf16(Dp[offM[T][6]] * cM[T][6], Dp[offM[T][7]] * cM[T][7]);
+                    mf[T] = __builtin_bit_cast(bf16x8, make_uint4(m0, m1, m2, m3));
+                }
+#pragma unroll
+                for (int To = 0; To < NT; ++To) {
+                    f32x4 x[2];
+                    x[0] = (f32x4){0.f, 0.f, 0.f, 0.f};
+                    x[1] = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                    for (int Tb = 0; Tb < NT; ++Tb)
+                        x[T0 + Tb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(d1c[Tb], mf[To], (f32x4){0.f, 0.f, 0.f, 0.f}, 0, 0, 0);
+                    f.ga[To] = __builtin_bit_cast(bf16x8, make_uint4(pack_bf16(x[0][0], x[0][1]), pack_bf16(x[0][2], x[0][3]),
+                                                                     pack_bf16(x[1][0], x[1][1]), pack_bf16(x[1][2], x[1][3])));
                 }
                 return f;
             };
-            // Heads are software-pipelined: the rotate-in MFMAs of head h+1 are issued before the scale/convert
-            // work of head h, so that the matrix pipe and the vector ALU overlap inside one wave.
-            auto rotate_in = [&](const Frags& f, const s16x4 (&vv)[H][NT], int h, f32x4 (&vt)[2]) {
-                vt[0] = (f32x4){0.f, 0.f, 0.f, 0.f};
-                vt[1] = (f32x4){0.f, 0.f, 0.f, 0.f};
+            s16x4 vv[H][NT];
+            {
+                const uint16_t* v0 = v_ptr(0);
+#pragma unroll
+                for (int h = 0; h < H; ++h)
+#pragma unroll
+                    for (int T = 0; T < NT; ++T) vv[h][T] = *reinterpret_cast<const s16x4*>(v0 + (h * NT + T) * 256);
+            }
+            // Heads are software-pipelined: the MFMAs of head h+1 are issued before the accumulate FMAs of head h,
+            // so that the matrix pipe and the vector ALU overlap inside one wave.
+            auto head_mfma = [&](const Frags& f, int h, f32x4 (&tmp)[NT]) {
+                uint2 vhi = make_uint2(0u, 0u), vlo;
+                if constexpr (HAS_HI) {
+                    vhi = __builtin_bit_cast(uint2, vv[h][0]);
+                    vlo = __builtin_bit_cast(uint2, vv[h][1]);
+                } else {
+                    vlo = __builtin_bit_cast(uint2, vv[h][0]);
+                }
+                const bf16x8 bv = __builtin_bit_cast(bf16x8, make_uint4(vhi.x, vhi.y, vlo.x, vlo.y));
 #pragma unroll
                 for (int T = 0; T < NT; ++T)
-                    vt[T0 + T] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(f.d1[T], vv[h][T], (f32x4){0.f, 0.f, 0.f, 0.f}, 0, 0, 0);
+                    tmp[T] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f.ga[T], bv, (f32x4){0.f, 0.f, 0.f, 0.f}, 0, 0, 0);
             };
-            auto compute = [&](const Frags& f, const s16x4 (&vv)[H][NT]) {
-                f32x4 vt[2][2];
-                rotate_in(f, vv, 0, vt[0]);
+            auto compute = [&](const Frags& f, const uint16_t* vnext) {
+                f32x4 tmp[2][NT];
+                head_mfma(f, 0, tmp[0]);
 #pragma unroll
                 for (int h = 0; h < H; ++h) {
-                    if (h + 1 < H) rotate_in(f, vv, h + 1, vt[(h + 1) & 1]);
+                    if (h + 1 < H) head_mfma(f, h + 1, tmp[(h + 1) & 1]);
                     const float w = read_lane(f.wl, 8 * h);
-                    const f32x4* v2 = vt[h & 1];
-                    const uint32_t b0 = pack_bf16(v2[0][0] * w, v2[0][1] * w), b1 = pack_bf16(v2[0][2] * w, v2[0][3] * w);
-                    const uint32_t b2 = pack_bf16(v2[1][0] * w, v2[1][1] * w), b3 = pack_bf16(v2[1][2] * w, v2[1][3] * w);
-                    const bf16x8 bb = __builtin_bit_cast(bf16x8, make_uint4(b0, b1, b2, b3));
 #pragma unroll
-                    for (int T = 0; T < NT; ++T)
-                        acc[h][T] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f.mf[T], bb, acc[h][T], 0, 0, 0);
+                    for (int T = 0; T < NT; ++T) vv[h][T] = *reinterpret_cast<const s16x4*>(vnext + (h * NT + T) * 256);
+#pragma unroll
+                    for (int T = 0; T < NT; ++T) acc[h][T] += w * tmp[h & 1][T];
                 }
             };
-            s16x4 va[H][NT], vb[H][NT];
-            load_v(0, va);
             Frags fa = assemble(0), fb;
 #pragma unroll 1
             for (int p = 0; p < np; p += 2) {
-                load_v(min(p + 1, np - 1), vb);
                 fb = assemble(min(p + 1, np - 1));
                 z += __expf(s_s[p * H + head] - mu);
-                compute(fa, va);
+                compute(fa, v_ptr(min(p + 1, np - 1)));
                 if (p + 1 < np) {
-                    load_v(min(p + 2, np - 1), va);
                     fa = assemble(min(p + 2, np - 1));
                     z += __expf(s_s[(p + 1) * H + head] - mu);
-                    compute(fb, vb);
+                    compute(fb, v_ptr(min(p + 2, np - 1)));
                 }
             }
             __syncthreads();
