@@ -55,6 +55,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-materialized", action="store_true")
     ap.add_argument("--workload", default="scaling", help="scaling | large | small | tiny | box<N>")
+    ap.add_argument("--sweep", action="store_true",
+                    help="also time the Large-N boxes (20k, 50k, 100k atoms) and fit peak activation bytes against N")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="BYTES",
                     help="also run a plain device copy of this many bytes (reference for HBM counter scaling)")
     args = ap.parse_args()
@@ -115,13 +117,13 @@ def main():
     on_mfma = (cfg["dtype"] == "bf16" and cfg["C"] // cfg["H"] == 16 and cfg["lf"] == 1 and cfg["L"] >= 1
                and cfg["H"] in (1, 2, 4, 8) and os.environ.get("E2F_ATTENTION") != "valu")
     # formal bound of the attention kernel: max(HBM time, MFMA time of the dense pieces, plain-ALU time of the rest)
-    L, C, H, B = cfg["L"], cfg["C"], cfg["H"], cfg["B"]
-    n = (L + 1) ** 2
-    S2 = sum((2 * l + 1) ** 2 for l in range(L + 1))
-    f_dense = E * (2 * (L + 1) * C + 4 * S2 * C)
+    Lm, Cc = cfg["L"], cfg["C"]
+    n = (Lm + 1) ** 2
+    S2 = sum((2 * l + 1) ** 2 for l in range(Lm + 1))
+    f_dense = E * (2 * (Lm + 1) * Cc + 4 * S2 * Cc)
     f_rest = E * f_edge - f_dense
     esz = 2 if cfg["dtype"] == "bf16" else 4
-    hbm_bytes = N * (16 + 2 * (L + 1) * C * 4 + n * C * esz + n * C * 4)
+    hbm_bytes = N * (16 + 2 * (Lm + 1) * Cc * 4 + n * Cc * esz + n * Cc * 4)
     t_roof_ms = max(hbm_bytes / 8e12, f_dense / (2.5e15 if esz == 2 else 157.3e12), f_rest / 157.3e12) * 1e3
     roofline = {"bound": "alu", "kernel": "k_fused_mfma" if on_mfma else "k_fused_valu",
                 "achieved": round(achieved, 3), "peak": PEAK_ALU_TFLOPS,
@@ -175,6 +177,39 @@ def main():
                                   "sample": f"{n_t} of {N} target atoms of the same workload, fp64 dense-CG route, "
                                             f"{dt:.1f} s wall"}
     P.close()
+
+    if args.sweep:
+        rows = [{"N": N, "forward_ms": round(fwd_ms, 4), "step_ms": round(ms_per_step, 4),
+                 "peak_activation_bytes": result["peak_activation_bytes"], "pairs": E}]
+        for n_atoms in (20_000, 50_000, 100_000):
+            wl2 = W.box(n_atoms, 0)
+            P2 = B.Problem(wl2, "cuda:0")
+            for _ in range(3):
+                P2.build_cells()
+                P2.forward()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(10):
+                P2.build_cells()
+                P2.forward()
+            torch.cuda.synchronize()
+            step2 = (time.perf_counter() - t0) * 1e2
+            t0 = time.perf_counter()
+            for _ in range(10):
+                P2.forward()
+            torch.cuda.synchronize()
+            fwd2 = (time.perf_counter() - t0) * 1e2
+            deg2, _, _ = P2.neighbors()
+            rows.append({"N": n_atoms, "forward_ms": round(fwd2, 4), "step_ms": round(step2, 4),
+                         "peak_activation_bytes": P2.activation_bytes(), "pairs": int(deg2.sum())})
+            P2.close()
+            del P2, wl2
+        xs = np.array([r["N"] for r in rows], dtype=np.float64)
+        ys = np.array([r["peak_activation_bytes"] for r in rows], dtype=np.float64)
+        slope, icpt = np.polyfit(xs, ys, 1)
+        r2 = 1.0 - np.sum((ys - (slope * xs + icpt)) ** 2) / np.sum((ys - ys.mean()) ** 2)
+        result["large_n"] = {"rows": rows, "bytes_per_atom": round(float(slope), 2), "intercept_bytes": round(float(icpt), 1),
+                             "r2": round(float(r2), 8)}
     print(json.dumps(result))
 
 
