@@ -463,7 +463,7 @@ __global__ __launch_bounds__(64 * WG_WAVES) void k_project_wg(E2fCellsView cv, c
     const int v_chunks = NT * 32;   // 16-byte chunks per atom
     for (int x = tid; x < n_atoms * v_chunks; x += 64 * WG_WAVES) {
         const int a = x / v_chunks, c16 = x - a * v_chunks;
-        const int T = NT == 2 ? c16 / 32 : 1, inner = c16 % 32;
+        const int T = NT == 2 ? c16 / 32 : 0, inner = c16 % 32;
         const uint4 val = *reinterpret_cast<const uint4*>(s_v + ((a * 2 + T) * 256) + inner * 8);
         const size_t slot = (size_t)tile0 * 16 + a;
         *reinterpret_cast<uint4*>(v + ((slot * NCT + ct) * NT) * 256 + c16 * 8) = val;

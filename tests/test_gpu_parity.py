@@ -103,6 +103,12 @@ def _custom(seed, N, L, C, H, B, lf, dtype, cutoff=3.0, side=6.0, seg=None):
     dict(N=90, L=4, C=64, H=8, B=16, lf=1, dtype="f32"),       # L = 4 in fp32, one channel per lane
     dict(N=33, L=1, C=256, H=8, B=8, lf=1, dtype="bf16"),      # four channels per lane
     dict(N=120, L=2, C=16, H=1, B=8, lf=1, dtype="f32", seg=[0, 0, 1, 40, 40, 119, 120]),  # empty and 1-atom segments
+    dict(N=70, L=2, C=64, H=4, B=8, lf=1, dtype="bf16"),       # matrix-core path with the low tile only
+    dict(N=45, L=1, C=32, H=2, B=3, lf=1, dtype="bf16"),       # matrix-core path, L = 1
+    dict(N=150, L=4, C=16 * 1, H=1, B=8, lf=1, dtype="f32"),   # one head of 16 channels in fp32 (vector-ALU path)
+    dict(N=83, L=4, C=64, H=4, B=8, lf=1, dtype="bf16", seg=[0, 30, 30, 83]),  # matrix-core path, 4 heads, segments
+    dict(N=64, L=2, C=64, H=2, B=8, lf=1, dtype="bf16"),       # bf16 with 32-channel heads: vector-ALU path, bf16 v
+    dict(N=64, L=3, C=64, H=4, B=8, lf=0, dtype="bf16"),       # bf16, lf = 0
 ])
 def test_other_shapes_and_degenerate_inputs(torch_cuda, kw):
     run_case(torch_cuda, _custom(5, **kw))
