@@ -50,11 +50,20 @@ __device__ __forceinline__ void stencil_rows(const E2fCellsView& cv, int slot, i
     }
 }
 
-// Workgroups are dealt to the 8 XCDs round-robin and every XCD has its own L2.  Give each XCD one contiguous
-// range of work items (targets in cell order), so that the neighbour rows its waves share stay in its L2.
-__device__ __forceinline__ int xcd_remap(int bid, int nblocks) {
-    const int q = nblocks >> 3, r = nblocks & 7, x = bid & 7;
-    return x * q + min(x, r) + (bid >> 3);
+// Workgroups are dealt to the 8 XCDs round-robin and every XCD has its own L2.  Work items (targets in cell
+// order) are cut into chunks of XCD_CHUNK consecutive items and chunk c goes to XCD c % 8: an XCD works on
+// contiguous stretches, so the neighbour rows its waves share stay in its L2, while every XCD still sees all
+// regions of the system (boundary cells carry fewer pairs than interior ones).  Returns -1 for padding blocks;
+// launch xcd_grid(n) blocks.
+constexpr int XCD_CHUNK = 128;
+__host__ __device__ inline int xcd_grid(int n) {
+    const int chunks = (n + XCD_CHUNK - 1) / XCD_CHUNK;
+    return ((chunks + 7) / 8) * 8 * XCD_CHUNK;
+}
+__device__ __forceinline__ int xcd_remap(int bid, int n) {
+    const int xcd = bid & 7, idx = bid >> 3;
+    const int t = ((idx / XCD_CHUNK) * 8 + xcd) * XCD_CHUNK + idx % XCD_CHUNK;
+    return t < n ? t : -1;
 }
 
 template <int l>

@@ -25,7 +25,6 @@ struct FusedParams {
     float* out;
     int C, H, B, Ch;
     float tau, rc2, cutoff, rbf_step, rbf_gamma;
-    int xcd;
 };
 
 constexpr int PB = 16;    // pairs per chunk
@@ -41,7 +40,8 @@ __global__ __launch_bounds__(64) void k_fused_valu(FusedParams P) {
     __shared__ float s_bias[PB * E2F_MAX_H];
     __shared__ float s_wgt[PB];
 
-    const int t = (P.xcd ? e2f::xcd_remap(blockIdx.x, gridDim.x) : (int)blockIdx.x), lane = threadIdx.x;
+    const int t = e2f::xcd_remap(blockIdx.x, P.cv.N), lane = threadIdx.x;
+    if (t < 0) return;  // padding block of the XCD map (whole wave)
     const int C = P.C, H = P.H;
     const int nlanes = C / CPL;
     const bool active = lane < nlanes;
@@ -171,9 +171,9 @@ __global__ __launch_bounds__(64) void k_fused_valu(FusedParams P) {
 template <int L, int LF, int CPL>
 void launch_valu_dtype(const e2f_ctx* ctx, const FusedParams& P, hipStream_t st) {
     if (ctx->cfg.feat_dtype == E2F_BF16)
-        k_fused_valu<L, LF, CPL, uint16_t><<<P.cv.N, 64, 0, st>>>(P);
+        k_fused_valu<L, LF, CPL, uint16_t><<<e2f::xcd_grid(P.cv.N), 64, 0, st>>>(P);
     else
-        k_fused_valu<L, LF, CPL, float><<<P.cv.N, 64, 0, st>>>(P);
+        k_fused_valu<L, LF, CPL, float><<<e2f::xcd_grid(P.cv.N), 64, 0, st>>>(P);
 }
 
 template <int L, int LF>
@@ -201,7 +201,6 @@ e2f_status e2f_launch_fused(const e2f_ctx* ctx, const E2fCellsView& cv, const e2
     P.cv = cv;
     P.spos = ws.spos; P.q = ws.q; P.k = ws.k; P.v = ws.v; P.cw = ws.cw; P.Wb = w->Wb; P.out = out;
     P.C = ctx->cfg.C; P.H = ctx->cfg.H; P.B = ctx->cfg.B; P.Ch = ctx->Ch;
-    { const char* e = getenv("E2F_XCD"); P.xcd = !(e && e[0] == '0'); }
     P.tau = ctx->tau; P.rc2 = ctx->rc2; P.cutoff = ctx->cfg.cutoff; P.rbf_step = ctx->rbf_step; P.rbf_gamma = ctx->rbf_gamma;
     bool ok = false;
     switch (ctx->cfg.L_max) {

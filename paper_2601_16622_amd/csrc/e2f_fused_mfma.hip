@@ -46,7 +46,6 @@ struct MfmaParams {
     float* out;
     int B;
     float tau, rc2, cutoff, rbf_step, rbf_gamma;
-    int xcd;
     unsigned long long* dbg;
 };
 
@@ -96,7 +95,8 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) void
 #else
 #define TICK(k)
 #endif
-    const int t = (P.xcd ? e2f::xcd_remap(blockIdx.x, gridDim.x) : (int)blockIdx.x);
+    const int t = e2f::xcd_remap(blockIdx.x, P.cv.N);
+    if (t < 0) return;  // padding block of the XCD map (whole wave)
     const int lane = threadIdx.x, i = lane & 15, g = lane >> 4;
     const float4 pi = P.spos[t];
     for (int x = lane; x < (L + 1) * (L + 1) * 3; x += 64) s_cw[x] = P.cw[x];
@@ -396,10 +396,10 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) void
 template <int L>
 bool launch_h(const e2f_ctx* ctx, const MfmaParams& P, hipStream_t st) {
     switch (ctx->cfg.H) {
-        case 1: k_fused_mfma<L, 1><<<P.cv.N, 64, 0, st>>>(P); return true;
-        case 2: k_fused_mfma<L, 2><<<P.cv.N, 64, 0, st>>>(P); return true;
-        case 4: k_fused_mfma<L, 4><<<P.cv.N, 64, 0, st>>>(P); return true;
-        case 8: k_fused_mfma<L, 8><<<P.cv.N, 64, 0, st>>>(P); return true;
+        case 1: k_fused_mfma<L, 1><<<e2f::xcd_grid(P.cv.N), 64, 0, st>>>(P); return true;
+        case 2: k_fused_mfma<L, 2><<<e2f::xcd_grid(P.cv.N), 64, 0, st>>>(P); return true;
+        case 4: k_fused_mfma<L, 4><<<e2f::xcd_grid(P.cv.N), 64, 0, st>>>(P); return true;
+        case 8: k_fused_mfma<L, 8><<<e2f::xcd_grid(P.cv.N), 64, 0, st>>>(P); return true;
     }
     return false;
 }
@@ -426,7 +426,6 @@ e2f_status e2f_launch_fused_mfma(const e2f_ctx* ctx, const E2fCellsView& cv, con
     P.dbg = dbg;
     { unsigned long long hst[6]; (void)hipMemcpy(hst, dbg, 48, hipMemcpyDeviceToHost); if (getenv("E2F_TIMING_PRINT")) fprintf(stderr, "sections(cum) fill %llu geom %llu pass1 %llu rescale %llu pass2 %llu epi %llu\n", hst[0], hst[1], hst[2], hst[3], hst[4], hst[5]); }
 #endif
-    { const char* e = getenv("E2F_XCD"); P.xcd = !(e && e[0] == '0'); }
     P.tau = ctx->tau; P.rc2 = ctx->rc2; P.cutoff = ctx->cfg.cutoff; P.rbf_step = ctx->rbf_step; P.rbf_gamma = ctx->rbf_gamma;
     bool ok = false;
     switch (ctx->cfg.L_max) {
