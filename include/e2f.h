@@ -48,7 +48,7 @@ typedef struct e2f_cells e2f_cells; /* host handle onto a cell list living in ca
 typedef enum {
     E2F_OK = 0,
     E2F_ERR_INVALID_ARG = 1,         /* null pointer, negative size, inconsistent configuration */
-    E2F_ERR_UNSUPPORTED = 2,         /* valid in principle, not implemented (e.g. L_max > 4, lf > 1) */
+    E2F_ERR_UNSUPPORTED = 2,         /* valid in principle, not implemented (e.g. L_max > 4, lf > 2) */
     E2F_ERR_WORKSPACE_TOO_SMALL = 3, /* ws_bytes below the value the matching *_workspace_bytes returns */
     E2F_ERR_HIP = 4,                 /* a HIP runtime call failed */
     E2F_ERR_OOM = 5                  /* device allocation failed (materialized baseline only) */
@@ -61,7 +61,7 @@ typedef struct {
     int32_t C;          /* channels per degree; multiple of 16; C <= 64 or C a multiple of 64, C <= 256 */
     int32_t H;          /* heads; C % H == 0 */
     int32_t B;          /* radial basis functions, >= 1 */
-    int32_t lf;         /* degree of the geometric filter R^(lf)(r_ij): 0 or 1 */
+    int32_t lf;         /* degree of the geometric filter R^(lf)(r_ij): 0, 1 or 2 (lf <= L_max unless 0) */
     float cutoff;       /* > 0 */
     int32_t feat_dtype; /* e2f_dtype of h and of the five projection matrices */
 } e2f_config;

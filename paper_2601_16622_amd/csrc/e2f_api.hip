@@ -10,12 +10,28 @@ namespace {
 
 bool aligned256(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 255u) == 0; }
 
-// <l m; 1 0 | l' m> for l' = l+1, l, l-1 (textbook closed forms of the Clebsch-Gordan coefficients with
-// j2 = 1, m2 = 0).  These are the non-zero entries of the re-indexing operator P for lf = 1 (Sec. 3.3,
-// Def. of P; App. C): even l_i+l_f+l_o keeps the order m, odd maps -m to m with the sign of m.
-double cg_up(int l, int m) { return sqrt((double)((l + 1 - m) * (l + 1 + m)) / (double)((2 * l + 1) * (l + 1))); }
-double cg_same(int l, int m) { return l == 0 ? 0.0 : (double)m / sqrt((double)(l * (l + 1))); }
-double cg_down(int l, int m) { return l == 0 ? 0.0 : -sqrt((double)((l - m) * (l + m)) / (double)(l * (2 * l + 1))); }
+// Clebsch-Gordan coefficient <j1 m1; j2 m2 | j m> (Condon-Shortley phases) by Racah's closed formula, in double.
+// Only the m2 = 0 column is needed: it holds the non-zero entries of the re-indexing operator P (Sec. 3.3,
+// Def. of P; App. C): for even l_i+l_f+l_o the order m is kept, for odd it is taken from -m with the sign of m.
+double factorial(int n) {
+    double f = 1.0;
+    for (int x = 2; x <= n; ++x) f *= x;
+    return f;
+}
+double clebsch_gordan(int j1, int m1, int j2, int m2, int j, int m) {
+    if (m1 + m2 != m || j > j1 + j2 || j < abs(j1 - j2) || abs(m1) > j1 || abs(m2) > j2 || abs(m) > j) return 0.0;
+    const double delta = factorial(j1 + j2 - j) * factorial(j1 - j2 + j) * factorial(-j1 + j2 + j) / factorial(j1 + j2 + j + 1);
+    const double norm = (2.0 * j + 1.0) * delta * factorial(j1 + m1) * factorial(j1 - m1) * factorial(j2 + m2) *
+                        factorial(j2 - m2) * factorial(j + m) * factorial(j - m);
+    double sum = 0.0;
+    for (int t = 0; t <= j1 + j2 - j; ++t) {
+        const int d1 = j1 + j2 - j - t, d2 = j1 - m1 - t, d3 = j2 + m2 - t, d4 = j - j2 + m1 + t, d5 = j - j1 - m2 + t;
+        if (d1 < 0 || d2 < 0 || d3 < 0 || d4 < 0 || d5 < 0) continue;
+        const double term = 1.0 / (factorial(t) * factorial(d1) * factorial(d2) * factorial(d3) * factorial(d4) * factorial(d5));
+        sum += (t % 2) ? -term : term;
+    }
+    return sqrt(norm) * sum;
+}
 
 size_t cells_ws_layout(int32_t N, int32_t S, void* ws, e2f_cells* c) {
     const int32_t max_cells = 27 * S + 2 * N + 1;
@@ -88,7 +104,7 @@ E2fAttnWs e2f_attn_ws_layout(const e2f_ctx* ctx, int32_t N, void* ws) {
     const size_t v_elems = ctx->use_mfma_attn ? (size_t)ctx->cfg.H * (ctx->cfg.L_max >= 3 ? 2 : 1) * 256
                                               : (size_t)ctx->n * ctx->cfg.C;
     L.v = (void*)take((size_t)N * v_elems * esz);
-    L.cw = (float*)take((size_t)E2F_MAX_N * 3 * 4);
+    L.cw = (float*)take((size_t)E2F_MAX_N * E2F_NP * 4);
     L.wbT = (float*)take((size_t)ctx->cfg.B * ctx->cfg.H * 4);
     L.bytes = off;
     return L;
@@ -115,7 +131,7 @@ e2f_status e2f_create(const e2f_config* cfg, e2f_ctx** ctx_out) {
     if (cfg->C % cfg->H != 0) return E2F_ERR_INVALID_ARG;
     if (cfg->feat_dtype != E2F_F32 && cfg->feat_dtype != E2F_BF16) return E2F_ERR_INVALID_ARG;
     if (cfg->lf > cfg->L_max && cfg->lf != 0) return E2F_ERR_INVALID_ARG;
-    if (cfg->L_max > E2F_MAX_L || cfg->lf > 1 || cfg->H > E2F_MAX_H) return E2F_ERR_UNSUPPORTED;
+    if (cfg->L_max > E2F_MAX_L || cfg->lf > E2F_MAX_LF || cfg->H > E2F_MAX_H) return E2F_ERR_UNSUPPORTED;
     // channel tiling of the kernels: 16-wide MFMA tiles (32-deep for bf16), lanes over channels in the fused kernel
     if (cfg->C % 16 != 0 || cfg->C > 256 || (cfg->C > 64 && cfg->C % 64 != 0)) return E2F_ERR_UNSUPPORTED;
     if (cfg->feat_dtype == E2F_BF16 && cfg->C % 32 != 0) return E2F_ERR_UNSUPPORTED;
@@ -137,16 +153,17 @@ e2f_status e2f_create(const e2f_config* cfg, e2f_ctx** ctx_out) {
     c->rbf_gamma = (float)(0.5 * bm1 * bm1 / ((double)cfg->cutoff * (double)cfg->cutoff));
     c->rbf_step = (float)((double)cfg->cutoff / bm1);
     for (int x = 0; x < E2F_MAX_N; ++x)
-        for (int t = 0; t < 3; ++t) c->coefP[x][t] = 0.0f;
+        for (int t = 0; t < E2F_NP; ++t) c->coefP[x][t] = 0.0f;
+    const int lf = cfg->lf;
     for (int lo = 0; lo <= cfg->L_max; ++lo)
         for (int m = -lo; m <= lo; ++m) {
             const int comp = lo * lo + lo + m, am = m < 0 ? -m : m;
-            if (cfg->lf == 0) {
-                c->coefP[comp][1] = 1.0f;
-            } else {
-                if (lo >= 1 && am <= lo - 1) c->coefP[comp][0] = (float)cg_up(lo - 1, am);   // l_i = lo-1
-                c->coefP[comp][1] = (float)cg_same(lo, m);                                  // l_i = lo, from -m
-                if (lo + 1 <= cfg->L_max) c->coefP[comp][2] = (float)cg_down(lo + 1, am);    // l_i = lo+1
+            for (int kk = 0; kk <= 2 * lf; ++kk) {
+                const int li = lo - lf + kk;
+                if (li < 0 || li > cfg->L_max || am > li) continue;
+                const double cg = clebsch_gordan(li, am, lf, 0, lo, am);
+                // odd l_i + l_f + l_o (odd kk): the entry couples order -m to m and carries the sign of m
+                c->coefP[comp][kk] = (float)((kk % 2) ? (m > 0 ? cg : (m < 0 ? -cg : 0.0)) : cg);
             }
         }
     // E2F_ATTENTION=valu in the environment keeps the attention stage off the matrix cores (for A/B timing)

@@ -168,8 +168,9 @@ template <>
 __device__ __forceinline__ void store_from_float<uint16_t>(uint16_t* p, float x) { *p = float_to_bf16_bits(x); }
 
 // EAAS message for NC channels held by one thread, accumulated into acc (Prop. EAAS, Sec. 3.3):
-//   acc[lo] += D^T ( wgt * P( D v ) ),  P from cw[(comp)*3 + {lo-1, lo, lo+1}] (path weights included).
-// Dp points at the packed blocks of D(R_ij); `wgt` already contains |r|^lf and the attention weight.
+//   acc[lo] += D^T ( wgt * P( D v ) ),  P from cw[comp * E2F_NP + k] (path weights included), where k selects the
+//   input degree l_in = l_out - LF + k; even k reads the same order m, odd k reads order -m (and m = 0 drops out).
+// Dp points at the packed blocks of D(R_ij); `wgt` already contains |r|^LF and the attention weight.
 // LF = 0 needs no rotation (P is the identity on each degree).
 template <int L, int LF, int NC, typename DPtr>
 __device__ __forceinline__ void eaas_accumulate(const float (&v)[(L + 1) * (L + 1)][NC], DPtr Dp, const float* cw,
@@ -178,7 +179,7 @@ __device__ __forceinline__ void eaas_accumulate(const float (&v)[(L + 1) * (L + 
     if constexpr (LF == 0) {
 #pragma unroll
         for (int x = 0; x < n; ++x) {
-            const float f = wgt * cw[x * 3 + 1];
+            const float f = wgt * cw[x * E2F_NP];
 #pragma unroll
             for (int u = 0; u < NC; ++u) acc[x][u] += f * v[x][u];
         }
@@ -209,20 +210,15 @@ __device__ __forceinline__ void eaas_accumulate(const float (&v)[(L + 1) * (L + 
                 const int m = a - lo, am = m < 0 ? -m : m;
 #pragma unroll
                 for (int u = 0; u < NC; ++u) y[a][u] = 0.0f;
-                if (lo >= 1 && am <= lo - 1) {  // from degree lo-1, same order
-                    const float c = cw[(base + a) * 3 + 0];
 #pragma unroll
-                    for (int u = 0; u < NC; ++u) y[a][u] += c * vt[(lo - 1) * (lo - 1) + (lo - 1) + m][u];
-                }
-                if (lo >= 1 && m != 0) {  // from degree lo, opposite order
-                    const float c = cw[(base + a) * 3 + 1];
+                for (int k = 0; k <= 2 * LF; ++k) {
+                    const int li = lo - LF + k;
+                    if (li < 0 || li > L || LF - li > lo || am > li) continue;  // no such path / order
+                    if ((k & 1) && m == 0) continue;
+                    const int ms = (k & 1) ? -m : m;
+                    const float c = cw[(base + a) * E2F_NP + k];
 #pragma unroll
-                    for (int u = 0; u < NC; ++u) y[a][u] += c * vt[base + lo - m][u];
-                }
-                if (lo + 1 <= L) {  // from degree lo+1, same order
-                    const float c = cw[(base + a) * 3 + 2];
-#pragma unroll
-                    for (int u = 0; u < NC; ++u) y[a][u] += c * vt[(lo + 1) * (lo + 1) + (lo + 1) + m][u];
+                    for (int u = 0; u < NC; ++u) y[a][u] += c * vt[li * li + li + ms][u];
                 }
 #pragma unroll
                 for (int u = 0; u < NC; ++u) y[a][u] *= wgt;
@@ -239,6 +235,14 @@ __device__ __forceinline__ void eaas_accumulate(const float (&v)[(L + 1) * (L + 
             }
         }
     }
+}
+
+// |r|^LF
+template <int LF>
+__device__ __forceinline__ float pow_lf(float d) {
+    if constexpr (LF == 0) return 1.0f;
+    if constexpr (LF == 1) return d;
+    return d * d;
 }
 
 }  // namespace e2f

@@ -104,7 +104,7 @@ __global__ __launch_bounds__(64) void k_fused_valu(FusedParams P) {
                     for (int b = 0; b < P.B; ++b) acc += P.Wb[hh * P.B + b] * e2f::radial_basis(d, b, P.rbf_step, P.rbf_gamma);
                     s_bias[lane * E2F_MAX_H + hh] = acc;
                 }
-                s_wgt[lane] = e2f::radial_gate(d, P.cutoff) * (LF == 1 ? d : 1.0f);
+                s_wgt[lane] = e2f::radial_gate(d, P.cutoff) * e2f::pow_lf<LF>(d);
             }
             __syncthreads();
             // logits of the chunk (Eq. kernel_score)
@@ -189,7 +189,12 @@ bool launch_valu_cpl(const e2f_ctx* ctx, const FusedParams& P, hipStream_t st) {
 
 template <int L>
 bool launch_valu_lf(const e2f_ctx* ctx, const FusedParams& P, hipStream_t st) {
-    return ctx->cfg.lf == 0 ? launch_valu_cpl<L, 0>(ctx, P, st) : launch_valu_cpl<L, 1>(ctx, P, st);
+    switch (ctx->cfg.lf) {
+        case 0: return launch_valu_cpl<L, 0>(ctx, P, st);
+        case 1: return launch_valu_cpl<L, 1>(ctx, P, st);
+        case 2: return launch_valu_cpl<L, 2>(ctx, P, st);
+    }
+    return false;
 }
 
 }  // namespace

@@ -44,7 +44,7 @@ struct MfmaParams {
     const float* cw;
     const float* WbT;  // [B][H]
     float* out;
-    int B;
+    int B, lf;
     float tau, rc2, cutoff, rbf_step, rbf_gamma;
     unsigned long long* dbg;
 };
@@ -86,7 +86,7 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) void
     __shared__ float s_bias[SC * H];
     __shared__ float s_wgt[SC];
     __shared__ float s_s[SC * H];
-    __shared__ float s_cw[E2F_MAX_N * 3];
+    __shared__ float s_cw[E2F_MAX_N * E2F_NP];
 
 #ifdef E2F_TIMING
     unsigned long long tacc[6] = {0, 0, 0, 0, 0, 0};
@@ -99,15 +99,15 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) void
     if (t < 0) return;  // padding block of the XCD map (whole wave)
     const int lane = threadIdx.x, i = lane & 15, g = lane >> 4;
     const float4 pi = P.spos[t];
-    for (int x = lane; x < (L + 1) * (L + 1) * 3; x += 64) s_cw[x] = P.cw[x];
+    for (int x = lane; x < (L + 1) * (L + 1) * E2F_NP; x += 64) s_cw[x] = P.cw[x];
     __syncthreads();
 
     // ---- per-lane fragment tables (constant for the whole kernel)
     // D1c fragment of input tile T: A[i = b][k], k <-> aligned row 4g+r of the same tile: D^l[a][b] if that row
     //   (l,a) and column i = (l,b) have the same degree.
     // M fragment of out tile T: B[k][j] = M[j][k], k = 8g+r <-> aligned row (r<4: HI row 4g+r, r>=4: LO row 4g+r-4)
-    //   = (li,mi);  out row j = (lo,b):  M = D^lo[mo][b] * coef  with
-    //   li = lo-1: mo = mi, coef = cw[.][0];  li = lo: mo = -mi (mi != 0), coef = cw[.][1];  li = lo+1: mo = mi, cw[.][2].
+    //   = (li,mi);  out row j = (lo,b):  M = D^lo[mo][b] * cw[(lo,mo)][kk]  with kk = li - lo + lf the path index;
+    //   even kk: mo = mi, odd kk: mo = -mi (mi != 0).
     int offD1[NT][4], offM[NT][8];
     float cM[NT][8];
 #pragma unroll
@@ -131,13 +131,13 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) void
             float coef = 0.0f;
             if (row_ok && k_ok) {
                 const int lo = li_, b = a_;
-                int mo = 0, which = -1;
-                if (li == lo - 1) { mo = mi; which = 0; }
-                else if (li == lo && mi != 0) { mo = -mi; which = 1; }
-                else if (li == lo + 1 && (mi <= lo && -mi <= lo)) { mo = mi; which = 2; }
-                if (which >= 0) {
-                    off = e2f::d_offset(lo) + (mo + lo) * (2 * lo + 1) + (b + lo);
-                    coef = s_cw[(lo * lo + lo + mo) * 3 + which];
+                const int kk = li - lo + P.lf;   // path index: l_in = l_out - lf + kk
+                if (kk >= 0 && kk <= 2 * P.lf && P.lf - li <= lo && !((kk & 1) && mi == 0)) {
+                    const int mo = (kk & 1) ? -mi : mi;
+                    if (mo <= lo && -mo <= lo) {
+                        off = e2f::d_offset(lo) + (mo + lo) * (2 * lo + 1) + (b + lo);
+                        coef = s_cw[(lo * lo + lo + mo) * E2F_NP + kk];
+                    }
                 }
             }
             offM[T][r] = off;
@@ -221,7 +221,7 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) void
                 }
 #pragma unroll
                 for (int hh = 0; hh < H; ++hh) s_bias[lane * H + hh] = bias[hh];
-                s_wgt[lane] = e2f::radial_gate(d, P.cutoff) * d;
+                s_wgt[lane] = e2f::radial_gate(d, P.cutoff) * (P.lf == 2 ? d * d : d);
             }
             __syncthreads();
             TICK(1)
@@ -408,7 +408,7 @@ bool launch_h(const e2f_ctx* ctx, const MfmaParams& P, hipStream_t st) {
 
 bool e2f_fused_mfma_supported(const e2f_ctx* ctx) {
     const int H = ctx->cfg.H;
-    return ctx->cfg.feat_dtype == E2F_BF16 && ctx->cfg.lf == 1 && ctx->Ch == 16 && ctx->cfg.L_max >= 1 &&
+    return ctx->cfg.feat_dtype == E2F_BF16 && (ctx->cfg.lf == 1 || ctx->cfg.lf == 2) && ctx->Ch == 16 && ctx->cfg.L_max >= 1 &&
            (H == 1 || H == 2 || H == 4 || H == 8);
 }
 
@@ -419,6 +419,7 @@ e2f_status e2f_launch_fused_mfma(const e2f_ctx* ctx, const E2fCellsView& cv, con
     P.cv = cv;
     P.spos = ws.spos; P.q = ws.q; P.k = ws.k; P.vt = (const uint16_t*)ws.v; P.cw = ws.cw; P.WbT = ws.wbT; P.out = out;
     P.B = ctx->cfg.B;
+    P.lf = ctx->cfg.lf;
     P.dbg = nullptr;
 #ifdef E2F_TIMING
     static unsigned long long* dbg = nullptr;

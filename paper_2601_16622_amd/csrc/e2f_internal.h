@@ -9,6 +9,8 @@
 #define E2F_MAX_L 4
 #define E2F_MAX_N ((E2F_MAX_L + 1) * (E2F_MAX_L + 1))
 #define E2F_MAX_H 32
+#define E2F_MAX_LF 2
+#define E2F_NP (2 * E2F_MAX_LF + 1)  // coupling paths per output degree: l_in = l_out - lf + k, k = 0..2 lf
 
 // Per-segment uniform grid: cell (x,y,z) of the segment has global id base + (z*ny + y)*nx + x.
 struct E2fSegGrid {
@@ -49,9 +51,9 @@ struct e2f_ctx {
     float rc2;         // cutoff*cutoff rounded to binary32
     float rbf_gamma;   // (B-1)^2 / (2 cutoff^2)
     float rbf_step;    // cutoff/(B-1)
-    // coupling coefficients of the re-indexing operator P for lf (without path weights):
-    // coefP[comp][0..2] multiplies the aligned input of degree lo-1, lo (opposite order), lo+1.
-    float coefP[E2F_MAX_N][3];
+    // coupling coefficients of the re-indexing operator P for lf (without path weights): coefP[comp][k] multiplies
+    // the aligned input of degree l_in = l_out - lf + k; even k keeps the order m, odd k takes it from -m.
+    float coefP[E2F_MAX_N][E2F_NP];
     // optional per-stage timing (e2f_profile_begin / e2f_profile_end)
     hipEvent_t* prof_events;  // [prof_capacity][E2F_N_STAGES + 1]
     int32_t prof_capacity, prof_calls;
@@ -63,7 +65,7 @@ struct E2fAttnWs {
     float* q;       // [N][L+1][C] sorted order
     float* k;       // [N][L+1][C]
     void* v;        // [N][n][C] sorted order, float or bf16 (follows feat_dtype)
-    float* cw;      // [n][3] P coefficients times path weights
+    float* cw;      // [n][E2F_NP] P coefficients times path weights
     float* wbT;     // [B][H] radial bias weights, transposed
     size_t bytes;
 };

@@ -88,7 +88,7 @@ __global__ void k_edge_geometry(int64_t E, const int32_t* __restrict__ src, cons
 #pragma unroll
         for (int x = 0; x < DS; ++x) D[e * DSP + x] = Dl[x];
     }
-    const float wgt = e2f::radial_gate(d, cutoff) * (LF == 1 ? d : 1.0f);
+    const float wgt = e2f::radial_gate(d, cutoff) * e2f::pow_lf<LF>(d);
     for (int hh = 0; hh < H; ++hh) {
         float acc = 0.0f;
         for (int b = 0; b < B; ++b) acc += Wb[hh * B + b] * e2f::radial_basis(d, b, rbf_step, rbf_gamma);
@@ -244,8 +244,12 @@ e2f_status run(const e2f_ctx* ctx, const E2fCellsView& cv, const void* h, const 
 template <int L>
 e2f_status run_lf(const e2f_ctx* ctx, const E2fCellsView& cv, const void* h, const e2f_weights* w, const E2fAttnWs& ws,
                   float* out, hipStream_t st, size_t* edges_out, size_t* peak_bytes_out) {
-    return ctx->cfg.lf == 0 ? run<L, 0>(ctx, cv, h, w, ws, out, st, edges_out, peak_bytes_out)
-                            : run<L, 1>(ctx, cv, h, w, ws, out, st, edges_out, peak_bytes_out);
+    switch (ctx->cfg.lf) {
+        case 0: return run<L, 0>(ctx, cv, h, w, ws, out, st, edges_out, peak_bytes_out);
+        case 1: return run<L, 1>(ctx, cv, h, w, ws, out, st, edges_out, peak_bytes_out);
+        case 2: return run<L, 2>(ctx, cv, h, w, ws, out, st, edges_out, peak_bytes_out);
+    }
+    return E2F_ERR_UNSUPPORTED;
 }
 
 }  // namespace

@@ -13,7 +13,7 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
 struct CoefTable {
-    float c[E2F_MAX_N][3];
+    float c[E2F_MAX_N][E2F_NP];
 };
 
 // spos[slot] = position of the atom in that slot; cw[comp][t] = P coefficient times its path weight.
@@ -27,14 +27,14 @@ __global__ void k_prepare(E2fCellsView cv, const float* __restrict__ pos, const 
         spos[t] = make_float4(pos[3 * a], pos[3 * a + 1], pos[3 * a + 2], 0.0f);
     }
     const int n = (L + 1) * (L + 1);
-    if (t < n * 3) {
-        const int comp = t / 3, which = t % 3;
+    if (t < n * E2F_NP) {
+        const int comp = t / E2F_NP, kk = t % E2F_NP;
         int lo = 0;
         while ((lo + 1) * (lo + 1) <= comp) ++lo;
-        const int li = (lf == 0) ? lo : lo + which - 1;
+        const int li = lo - lf + kk;
         float w = 0.0f;
-        if (li >= 0 && li <= L && !(lf == 0 && which != 1)) w = w_path[li * (L + 1) + lo];
-        cw[t] = w * tab.c[comp][which];
+        if (kk <= 2 * lf && li >= 0 && li <= L) w = w_path[li * (L + 1) + lo];
+        cw[t] = w * tab.c[comp][kk];
     }
 }
 
@@ -626,8 +626,8 @@ e2f_status e2f_launch_prepare(const e2f_ctx* ctx, const E2fCellsView& cv, const 
                               const E2fAttnWs& ws, hipStream_t st) {
     CoefTable tab;
     for (int x = 0; x < E2F_MAX_N; ++x)
-        for (int t = 0; t < 3; ++t) tab.c[x][t] = ctx->coefP[x][t];
-    int work = cv.N > ctx->n * 3 ? cv.N : ctx->n * 3;
+        for (int t = 0; t < E2F_NP; ++t) tab.c[x][t] = ctx->coefP[x][t];
+    int work = cv.N > ctx->n * E2F_NP ? cv.N : ctx->n * E2F_NP;
     if (ctx->cfg.H * ctx->cfg.B > work) work = ctx->cfg.H * ctx->cfg.B;
     k_prepare<<<(work + 255) / 256, 256, 0, st>>>(cv, pos, w->w_path, ctx->cfg.L_max, ctx->cfg.lf, tab, ws.spos, ws.cw,
                                                  w->Wb, ctx->cfg.H, ctx->cfg.B, ws.wbT);

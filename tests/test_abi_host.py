@@ -35,7 +35,7 @@ def test_status_strings(lib):
 @pytest.mark.parametrize("kw,code", [
     (dict(L_max=-1), 1), (dict(C=0), 1), (dict(H=3), 1), (dict(B=0), 1), (dict(cutoff=0.0), 1),
     (dict(cutoff=float("nan")), 1), (dict(feat_dtype=7), 1), (dict(L_max=0, lf=1), 1),
-    (dict(L_max=5), 2), (dict(lf=2), 2), (dict(C=24, H=2), 2), (dict(C=320, H=8), 2), (dict(C=16, H=2, feat_dtype=1), 2),
+    (dict(L_max=5), 2), (dict(lf=3, L_max=4), 2), (dict(lf=2, L_max=1), 1), (dict(C=24, H=2), 2), (dict(C=320, H=8), 2), (dict(C=16, H=2, feat_dtype=1), 2),
 ])
 def test_create_rejects_bad_configurations(lib, kw, code):
     base = dict(L_max=2, C=128, H=8, B=8, lf=1, cutoff=5.0, feat_dtype=0)
@@ -50,8 +50,8 @@ def test_workspace_sizes_are_linear_in_N(lib):
     ctx = B.e2f_create(4, 128, 8, 8, 1, 6.0, "bf16")
     try:
         sizes = [B.e2f_attn_workspace_bytes(ctx, N) for N in (10_000, 20_000, 40_000)]
-        # sorted positions 16 B, q and k fp32 (L+1)*C each, v bf16 n*C, per atom; constant tail
-        per_atom = 16 + 2 * 5 * 128 * 4 + 25 * 128 * 2
+        # per atom: sorted position 16 B, q and k fp32 (L+1)*C each, v bf16 in two 16x16 tiles per 16-channel head
+        per_atom = 16 + 2 * 5 * 128 * 4 + 8 * 2 * 256 * 2
         assert abs((sizes[1] - sizes[0]) - 10_000 * per_atom) <= 2048
         assert abs((sizes[2] - sizes[1]) - 20_000 * per_atom) <= 2048
         c = [B.e2f_cells_workspace_bytes(ctx, N, 4) for N in (1000, 2000, 3000)]

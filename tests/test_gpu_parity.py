@@ -109,6 +109,10 @@ def _custom(seed, N, L, C, H, B, lf, dtype, cutoff=3.0, side=6.0, seg=None):
     dict(N=83, L=4, C=64, H=4, B=8, lf=1, dtype="bf16", seg=[0, 30, 30, 83]),  # matrix-core path, 4 heads, segments
     dict(N=64, L=2, C=64, H=2, B=8, lf=1, dtype="bf16"),       # bf16 with 32-channel heads: vector-ALU path, bf16 v
     dict(N=64, L=3, C=64, H=4, B=8, lf=0, dtype="bf16"),       # bf16, lf = 0
+    dict(N=60, L=2, C=32, H=2, B=8, lf=2, dtype="f32"),        # degree-2 filter, vector-ALU path
+    dict(N=72, L=4, C=16, H=2, B=8, lf=2, dtype="f32"),        # degree-2 filter, L = 4
+    dict(N=90, L=4, C=64, H=4, B=8, lf=2, dtype="bf16"),       # degree-2 filter on the matrix-core path
+    dict(N=50, L=2, C=32, H=2, B=8, lf=2, dtype="bf16"),       # degree-2 filter, low tile only
 ])
 def test_other_shapes_and_degenerate_inputs(torch_cuda, kw):
     run_case(torch_cuda, _custom(5, **kw))
