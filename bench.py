@@ -57,6 +57,8 @@ def main():
     ap.add_argument("--workload", default="scaling", help="scaling | large | small | tiny | box<N>")
     ap.add_argument("--sweep", action="store_true",
                     help="also time the Large-N boxes (20k, 50k, 100k atoms) and fit peak activation bytes against N")
+    ap.add_argument("--tp", action="store_true",
+                    help="also time the stand-alone EAAS tensor product at the shape of the paper's tensor-product table")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="BYTES",
                     help="also run a plain device copy of this many bytes (reference for HBM counter scaling)")
     args = ap.parse_args()
@@ -177,6 +179,31 @@ def main():
                                   "sample": f"{n_t} of {N} target atoms of the same workload, fp64 dense-CG route, "
                                             f"{dt:.1f} s wall"}
     P.close()
+
+    if args.tp:
+        # (128x0e+128x1e+128x2e) (x) (1x2e), fp32, 1k..32k products; paper's numbers are from an NVIDIA H20
+        paper_ms = {1000: 0.15, 2000: 0.22, 4000: 0.35, 8000: 0.65, 16000: 1.20, 32000: 2.25}
+        ctx = B.e2f_create(2, 128, 1, 1, 2, 1.0, "f32")
+        rows = []
+        for T in sorted(paper_ms):
+            ht = torch.randn((T, 9, 128), dtype=torch.float32, device="cuda:0")
+            rt = torch.randn((T, 3), dtype=torch.float32, device="cuda:0")
+            wt = torch.rand((3, 3), dtype=torch.float32, device="cuda:0") + 0.5
+            ot = torch.empty_like(ht)
+            for _ in range(10):
+                B.e2f_eaas_tensor_product(ctx, ht, rt, wt, ot)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(50):
+                B.e2f_eaas_tensor_product(ctx, ht, rt, wt, ot)
+            torch.cuda.synchronize()
+            ms = (time.perf_counter() - t0) * 1e3 / 50
+            nbytes = T * (9 * 128 * 4 * 2 + 12)
+            rows.append({"T": T, "ms": round(ms, 4), "GB_per_s": round(nbytes / ms / 1e6, 1),
+                         "paper_H20_ms": paper_ms[T]})
+        B.e2f_destroy(ctx)
+        result["eaas_tensor_product"] = {"shape": "(128x0e+128x1e+128x2e) x (1x2e), fp32", "bound": "hbm",
+                                         "peak_GB_per_s": 8000, "rows": rows}
 
     if args.sweep:
         rows = [{"N": N, "forward_ms": round(fwd_ms, 4), "step_ms": round(ms_per_step, 4),

@@ -136,6 +136,19 @@ e2f_status e2f_attn_forward_materialized(e2f_ctx *ctx, const e2f_cells *cells, c
                                          size_t *peak_bytes_out);
 
 /*
+ * Stand-alone EAAS tensor product (Sec. 3.3, Prop. EAAS; the operation of the paper's tensor-product timing table):
+ * out[t] = h[t] (x) R^(lf)(r[t]) for t = 0..T-1, channel-wise with path weights, evaluated as rotate into the frame
+ * of r[t], re-index with P, rotate back.  Uses L_max, C, lf and feat_dtype of the context.
+ *   h       device feat_dtype [T][(L_max+1)^2][C]
+ *   r       device float [T][3]; r[t] = 0 gives out[t] = 0 when lf > 0
+ *   w_path  device float [L_max+1][L_max+1] indexed [l_in][l_out]
+ *   out     device float [T][(L_max+1)^2][C], fully overwritten
+ * Allocates nothing, does not synchronise.
+ */
+e2f_status e2f_eaas_tensor_product(e2f_ctx *ctx, const void *h, const float *r, const float *w_path, float *out,
+                                   int32_t T, void *hip_stream);
+
+/*
  * Per-stage timing of e2f_attn_forward for benchmarks (measurement aid; callers that do not ask for it pay
  * nothing).  e2f_profile_begin creates HIP events for up to max_calls calls; while profiling is on, every
  * e2f_attn_forward records events between its stages on the stream it is given (no synchronisation).

@@ -17,7 +17,8 @@ E2F_F32, E2F_BF16 = 0, 1
 
 EXPORTS = ["e2f_status_string", "e2f_create", "e2f_destroy", "e2f_cells_workspace_bytes", "e2f_build_cells",
            "e2f_cells_destroy", "e2f_count_neighbors", "e2f_list_neighbors", "e2f_attn_workspace_bytes",
-           "e2f_attn_forward", "e2f_attn_forward_materialized", "e2f_profile_begin", "e2f_profile_end"]
+           "e2f_attn_forward", "e2f_attn_forward_materialized", "e2f_profile_begin", "e2f_profile_end",
+           "e2f_eaas_tensor_product"]
 STAGES = ("prepare", "project", "attention")
 
 
@@ -71,6 +72,8 @@ def load():
     L.e2f_attn_forward_materialized.argtypes = [vp, vp, vp, vp, vp, i32, i32, ctypes.POINTER(Weights), vp, vp, sz, vp,
                                                 ctypes.POINTER(sz), ctypes.POINTER(sz)]
     L.e2f_attn_forward_materialized.restype = ctypes.c_int
+    L.e2f_eaas_tensor_product.argtypes = [vp, vp, vp, vp, vp, i32, vp]
+    L.e2f_eaas_tensor_product.restype = ctypes.c_int
     L.e2f_profile_begin.argtypes = [vp, i32]
     L.e2f_profile_begin.restype = ctypes.c_int
     L.e2f_profile_end.argtypes = [vp, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(i32)]
@@ -160,6 +163,12 @@ def e2f_attn_forward_materialized(ctx, cells, pos, h, seg_offsets, weights, out,
                                                 ctypes.byref(edges), ctypes.byref(peak)),
            "e2f_attn_forward_materialized")
     return edges.value, peak.value
+
+
+def e2f_eaas_tensor_product(ctx, h, r, w_path, out):
+    """h [T][n][C] (feature dtype), r float32 [T][3], w_path float32 [L+1][L+1], out float32 [T][n][C]."""
+    _check(load().e2f_eaas_tensor_product(ctx, _ptr(h), _ptr(r), _ptr(w_path), _ptr(out), h.shape[0], _stream()),
+           "e2f_eaas_tensor_product")
 
 
 def e2f_profile_begin(ctx, max_calls):

@@ -295,6 +295,13 @@ e2f_status e2f_attn_forward(e2f_ctx* ctx, const e2f_cells* cells, const float* p
     return E2F_OK;
 }
 
+e2f_status e2f_eaas_tensor_product(e2f_ctx* ctx, const void* h, const float* r, const float* w_path, float* out,
+                                   int32_t T, void* hip_stream) {
+    if (!ctx || T < 0) return E2F_ERR_INVALID_ARG;
+    if (T > 0 && (!h || !r || !w_path || !out)) return E2F_ERR_INVALID_ARG;
+    return e2f_launch_tensor_product(ctx, h, r, w_path, out, T, static_cast<hipStream_t>(hip_stream));
+}
+
 e2f_status e2f_attn_forward_materialized(e2f_ctx* ctx, const e2f_cells* cells, const float* pos, const void* h,
                                          const int32_t* seg_offsets, int32_t N, int32_t S, const e2f_weights* w,
                                          float* out, void* ws, size_t ws_bytes, void* hip_stream, size_t* edges_out,
