@@ -149,6 +149,24 @@ def main():
         "roofline": roofline,
     }
 
+    # the paper's own factorized pipeline (node-level products around Algorithm 1) on the same inputs
+    try:
+        out_f = torch.empty_like(P.out)
+        for _ in range(3):
+            P.forward_factorized(out_f)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        reps = 20
+        for _ in range(reps):
+            P.forward_factorized(out_f)
+        torch.cuda.synchronize()
+        fact_ms = (time.perf_counter() - t0) * 1e3 / reps
+        result["factorized"] = {"ms": round(fact_ms, 4), "atoms_per_s": round(N / (fact_ms * 1e-3), 1),
+                                "workspace_bytes": int(B.e2f_attn_factorized_workspace_bytes(P.ctx, N)),
+                                "max_abs_diff_vs_fused": float((out_f - P.out).abs().max())}
+    except B.E2fError as e:
+        result["factorized"] = {"error": str(e)}
+
     if not args.no_materialized:
         try:
             out_m = torch.empty_like(P.out)

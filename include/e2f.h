@@ -136,6 +136,19 @@ e2f_status e2f_attn_forward_materialized(e2f_ctx *ctx, const e2f_cells *cells, c
                                          size_t *peak_bytes_out);
 
 /*
+ * The paper's factorized node-centric pipeline for lf = 1 (Eq. e2former_final with l = 1; Sec. 3.2, three-stage data
+ * flow; Sec. 3.4 Algorithm 1): source terms h'_j = v_j (x) R(r_j - o) by node-level EAAS, Algorithm 1 streaming over
+ * the precomputed rows [h'_j ; v_j] with scalar weights alpha_ij only, target coupling A1_i - A0_i (x) R(r_i - o).
+ * o is the centre of the atom's segment.  Same arguments and result as e2f_attn_forward (up to rounding); the
+ * workspace is larger (three more fp32 [N][(L_max+1)^2][C] arrays) but still O(N).  Requires lf = 1 and a
+ * power-of-two number of channels per head, at most 64.  Allocates nothing, does not synchronise.
+ */
+size_t e2f_attn_factorized_workspace_bytes(const e2f_ctx *ctx, int32_t N);
+e2f_status e2f_attn_forward_factorized(e2f_ctx *ctx, const e2f_cells *cells, const float *pos, const void *h,
+                                       const int32_t *seg_offsets, int32_t N, int32_t S, const e2f_weights *w,
+                                       float *out, void *ws, size_t ws_bytes, void *hip_stream);
+
+/*
  * Stand-alone EAAS tensor product (Sec. 3.3, Prop. EAAS; the operation of the paper's tensor-product timing table):
  * out[t] = h[t] (x) R^(lf)(r[t]) for t = 0..T-1, channel-wise with path weights, evaluated as rotate into the frame
  * of r[t], re-index with P, rotate back.  Uses L_max, C, lf and feat_dtype of the context.

@@ -18,7 +18,7 @@ E2F_F32, E2F_BF16 = 0, 1
 EXPORTS = ["e2f_status_string", "e2f_create", "e2f_destroy", "e2f_cells_workspace_bytes", "e2f_build_cells",
            "e2f_cells_destroy", "e2f_count_neighbors", "e2f_list_neighbors", "e2f_attn_workspace_bytes",
            "e2f_attn_forward", "e2f_attn_forward_materialized", "e2f_profile_begin", "e2f_profile_end",
-           "e2f_eaas_tensor_product"]
+           "e2f_eaas_tensor_product", "e2f_attn_factorized_workspace_bytes", "e2f_attn_forward_factorized"]
 STAGES = ("prepare", "project", "attention")
 
 
@@ -72,6 +72,10 @@ def load():
     L.e2f_attn_forward_materialized.argtypes = [vp, vp, vp, vp, vp, i32, i32, ctypes.POINTER(Weights), vp, vp, sz, vp,
                                                 ctypes.POINTER(sz), ctypes.POINTER(sz)]
     L.e2f_attn_forward_materialized.restype = ctypes.c_int
+    L.e2f_attn_factorized_workspace_bytes.argtypes = [vp, i32]
+    L.e2f_attn_factorized_workspace_bytes.restype = sz
+    L.e2f_attn_forward_factorized.argtypes = [vp, vp, vp, vp, vp, i32, i32, ctypes.POINTER(Weights), vp, vp, sz, vp]
+    L.e2f_attn_forward_factorized.restype = ctypes.c_int
     L.e2f_eaas_tensor_product.argtypes = [vp, vp, vp, vp, vp, i32, vp]
     L.e2f_eaas_tensor_product.restype = ctypes.c_int
     L.e2f_profile_begin.argtypes = [vp, i32]
@@ -153,6 +157,17 @@ def e2f_attn_forward(ctx, cells, pos, h, seg_offsets, weights, out, ws):
                                    _ptr(out), _ptr(ws), ws.numel(), _stream()), "e2f_attn_forward")
 
 
+def e2f_attn_factorized_workspace_bytes(ctx, N):
+    return load().e2f_attn_factorized_workspace_bytes(ctx, N)
+
+
+def e2f_attn_forward_factorized(ctx, cells, pos, h, seg_offsets, weights, out, ws):
+    N, S = pos.shape[0], seg_offsets.shape[0] - 1
+    wt = _weights(weights)
+    _check(load().e2f_attn_forward_factorized(ctx, cells, _ptr(pos), _ptr(h), _ptr(seg_offsets), N, S, ctypes.byref(wt),
+                                              _ptr(out), _ptr(ws), ws.numel(), _stream()), "e2f_attn_forward_factorized")
+
+
 def e2f_attn_forward_materialized(ctx, cells, pos, h, seg_offsets, weights, out, ws):
     """Returns (n_edges, peak_bytes_allocated_inside)."""
     N, S = pos.shape[0], seg_offsets.shape[0] - 1
@@ -219,6 +234,15 @@ class Problem:
     def forward(self):
         e2f_attn_forward(self.ctx, self.cells, self.pos, self.h, self.seg, self.weights, self.out, self.attn_ws)
         return self.out
+
+    def forward_factorized(self, out=None):
+        import torch
+        out = self.out if out is None else out
+        need = e2f_attn_factorized_workspace_bytes(self.ctx, self.N)
+        if getattr(self, "fact_ws", None) is None or self.fact_ws.numel() < need:
+            self.fact_ws = torch.empty(max(need, 256), dtype=torch.uint8, device=self.device)
+        e2f_attn_forward_factorized(self.ctx, self.cells, self.pos, self.h, self.seg, self.weights, out, self.fact_ws)
+        return out
 
     def forward_materialized(self, out=None):
         out = self.out if out is None else out

@@ -88,7 +88,7 @@ e2f_status check_forward_args(const e2f_ctx* ctx, const e2f_cells* cells, const 
 
 }  // namespace
 
-E2fAttnWs e2f_attn_ws_layout(const e2f_ctx* ctx, int32_t N, void* ws) {
+E2fAttnWs e2f_attn_ws_layout(const e2f_ctx* ctx, int32_t N, void* ws, bool tiled_v) {
     E2fAttnWs L;
     size_t off = 0;
     auto take = [&](size_t bytes) {
@@ -101,7 +101,7 @@ E2fAttnWs e2f_attn_ws_layout(const e2f_ctx* ctx, int32_t N, void* ws) {
     L.q = (float*)take((size_t)N * (ctx->cfg.L_max + 1) * ctx->cfg.C * 4);
     L.k = (float*)take((size_t)N * (ctx->cfg.L_max + 1) * ctx->cfg.C * 4);
     // tiled v of the MFMA attention kernel: 16-row tiles per head, two tiles when L_max >= 3
-    const size_t v_elems = ctx->use_mfma_attn ? (size_t)ctx->cfg.H * (ctx->cfg.L_max >= 3 ? 2 : 1) * 256
+    const size_t v_elems = tiled_v ? (size_t)ctx->cfg.H * (ctx->cfg.L_max >= 3 ? 2 : 1) * 256
                                               : (size_t)ctx->n * ctx->cfg.C;
     L.v = (void*)take((size_t)N * v_elems * esz);
     L.cw = (float*)take((size_t)E2F_MAX_N * E2F_NP * 4);
@@ -268,7 +268,7 @@ e2f_status e2f_list_neighbors(e2f_ctx* ctx, const e2f_cells* cells, const float*
 
 size_t e2f_attn_workspace_bytes(const e2f_ctx* ctx, int32_t N) {
     if (!ctx || N < 0) return 0;
-    return e2f_attn_ws_layout(ctx, N, nullptr).bytes;
+    return e2f_attn_ws_layout(ctx, N, nullptr, ctx->use_mfma_attn).bytes;
 }
 
 e2f_status e2f_attn_forward(e2f_ctx* ctx, const e2f_cells* cells, const float* pos, const void* h,
@@ -277,13 +277,13 @@ e2f_status e2f_attn_forward(e2f_ctx* ctx, const e2f_cells* cells, const float* p
     e2f_status rc = check_forward_args(ctx, cells, pos, h, seg_offsets, N, S, w, out, ws, ws_bytes);
     if (rc != E2F_OK || N == 0) return rc;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
-    const E2fAttnWs L = e2f_attn_ws_layout(ctx, N, ws);
+    const E2fAttnWs L = e2f_attn_ws_layout(ctx, N, ws, ctx->use_mfma_attn);
     hipEvent_t* ev = (ctx->prof_events && ctx->prof_calls < ctx->prof_capacity)
                          ? ctx->prof_events + ctx->prof_calls * (E2F_N_STAGES + 1) : nullptr;
     if (ev) E2F_HIP_CHECK(hipEventRecord(ev[0], st));
     if ((rc = e2f_launch_prepare(ctx, cells->view, pos, w, L, st)) != E2F_OK) return rc;
     if (ev) E2F_HIP_CHECK(hipEventRecord(ev[1], st));
-    if ((rc = e2f_launch_project_mfma(ctx, cells->view, h, w, L, st)) != E2F_OK) return rc;
+    if ((rc = e2f_launch_project_mfma(ctx, cells->view, h, w, L, ctx->use_mfma_attn, st)) != E2F_OK) return rc;
     if (ev) E2F_HIP_CHECK(hipEventRecord(ev[2], st));
     rc = ctx->use_mfma_attn ? e2f_launch_fused_mfma(ctx, cells->view, w, L, out, st)
                             : e2f_launch_fused(ctx, cells->view, w, L, out, st);
@@ -293,6 +293,44 @@ e2f_status e2f_attn_forward(e2f_ctx* ctx, const e2f_cells* cells, const float* p
         ctx->prof_calls++;
     }
     return E2F_OK;
+}
+
+static E2fFactWs fact_ws_layout(const e2f_ctx* ctx, int32_t N, void* ws, size_t attn_bytes) {
+    E2fFactWs F;
+    size_t off = attn_bytes;
+    auto take = [&](size_t bytes) {
+        char* p = ws ? static_cast<char*>(ws) + off : nullptr;
+        off += e2f_align_up(bytes);
+        return p;
+    };
+    const size_t rows = (size_t)N * ctx->n * ctx->cfg.C * 4;
+    F.hp = (float*)take(rows);
+    F.a1 = (float*)take(rows);
+    F.a0 = (float*)take(rows);
+    F.bytes = off;
+    return F;
+}
+
+size_t e2f_attn_factorized_workspace_bytes(const e2f_ctx* ctx, int32_t N) {
+    if (!ctx || N < 0) return 0;
+    return fact_ws_layout(ctx, N, nullptr, e2f_attn_ws_layout(ctx, N, nullptr, false).bytes).bytes;
+}
+
+e2f_status e2f_attn_forward_factorized(e2f_ctx* ctx, const e2f_cells* cells, const float* pos, const void* h,
+                                       const int32_t* seg_offsets, int32_t N, int32_t S, const e2f_weights* w,
+                                       float* out, void* ws, size_t ws_bytes, void* hip_stream) {
+    if (!ctx) return E2F_ERR_INVALID_ARG;
+    if (!e2f_factorized_supported(ctx)) return E2F_ERR_UNSUPPORTED;
+    // same argument checks as the fused call, against this call's own workspace size
+    e2f_status rc = check_forward_args(ctx, cells, pos, h, seg_offsets, N, S, w, out, ws, (size_t)-1);
+    if (rc != E2F_OK || N == 0) return rc;
+    if (ws_bytes < e2f_attn_factorized_workspace_bytes(ctx, N)) return E2F_ERR_WORKSPACE_TOO_SMALL;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    const E2fAttnWs L = e2f_attn_ws_layout(ctx, N, ws, false);
+    const E2fFactWs F = fact_ws_layout(ctx, N, ws, L.bytes);
+    if ((rc = e2f_launch_prepare(ctx, cells->view, pos, w, L, st)) != E2F_OK) return rc;
+    if ((rc = e2f_launch_project_mfma(ctx, cells->view, h, w, L, false, st)) != E2F_OK) return rc;
+    return e2f_launch_factorized(ctx, cells->view, L, F, out, st);
 }
 
 e2f_status e2f_eaas_tensor_product(e2f_ctx* ctx, const void* h, const float* r, const float* w_path, float* out,
@@ -310,7 +348,7 @@ e2f_status e2f_attn_forward_materialized(e2f_ctx* ctx, const e2f_cells* cells, c
     if (edges_out) *edges_out = 0;
     if (peak_bytes_out) *peak_bytes_out = 0;
     if (rc != E2F_OK || N == 0) return rc;
-    const E2fAttnWs L = e2f_attn_ws_layout(ctx, N, ws);
+    const E2fAttnWs L = e2f_attn_ws_layout(ctx, N, ws, ctx->use_mfma_attn);
     return e2f_run_materialized(ctx, cells->view, pos, h, w, L, out, static_cast<hipStream_t>(hip_stream), edges_out,
                                 peak_bytes_out);
 }

@@ -69,7 +69,15 @@ struct E2fAttnWs {
     float* wbT;     // [B][H] radial bias weights, transposed
     size_t bytes;
 };
-E2fAttnWs e2f_attn_ws_layout(const e2f_ctx* ctx, int32_t N, void* ws);
+E2fAttnWs e2f_attn_ws_layout(const e2f_ctx* ctx, int32_t N, void* ws, bool tiled_v);
+
+// Extra O(N) buffers of the factorized pipeline, placed after the attention workspace (untiled v).
+struct E2fFactWs {
+    float* hp;   // [N][n][C] source terms h'
+    float* a1;   // [N][n][C] aggregated source terms
+    float* a0;   // [N][n][C] aggregated values
+    size_t bytes;
+};
 
 static inline size_t e2f_align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
 
@@ -89,7 +97,10 @@ e2f_status e2f_launch_list_neighbors(const e2f_ctx* ctx, const E2fCellsView& cv,
 e2f_status e2f_launch_prepare(const e2f_ctx* ctx, const E2fCellsView& cv, const float* pos, const e2f_weights* w,
                               const E2fAttnWs& ws, hipStream_t st);
 e2f_status e2f_launch_project_mfma(const e2f_ctx* ctx, const E2fCellsView& cv, const void* h, const e2f_weights* w,
-                                   const E2fAttnWs& ws, hipStream_t st);
+                                   const E2fAttnWs& ws, bool tiled_v, hipStream_t st);
+bool e2f_factorized_supported(const e2f_ctx* ctx);
+e2f_status e2f_launch_factorized(const e2f_ctx* ctx, const E2fCellsView& cv, const E2fAttnWs& ws, const E2fFactWs& fw,
+                                 float* out, hipStream_t st);
 e2f_status e2f_launch_project_simple(const e2f_ctx* ctx, const E2fCellsView& cv, const void* h, const e2f_weights* w,
                                      float* q, float* k, float* v, hipStream_t st);
 e2f_status e2f_launch_fused(const e2f_ctx* ctx, const E2fCellsView& cv, const e2f_weights* w, const E2fAttnWs& ws,

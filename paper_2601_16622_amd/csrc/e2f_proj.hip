@@ -636,13 +636,12 @@ e2f_status e2f_launch_prepare(const e2f_ctx* ctx, const E2fCellsView& cv, const 
 }
 
 e2f_status e2f_launch_project_mfma(const e2f_ctx* ctx, const E2fCellsView& cv, const void* h, const e2f_weights* w,
-                                   const E2fAttnWs& ws, hipStream_t st) {
+                                   const E2fAttnWs& ws, bool tiled_v, hipStream_t st) {
     if (cv.N == 0) return E2F_OK;
     bool ok;
     if (ctx->cfg.feat_dtype == E2F_BF16)
-        ok = (ctx->use_mfma_attn && dispatch_wg(ctx, cv, h, w, ws, st)) ||
-             dispatch_ws(ctx, cv, h, w, ws, st, ctx->use_mfma_attn) ||
-             dispatch_mfma<uint16_t>(ctx, cv, h, w, ws, st, ctx->use_mfma_attn);
+        ok = (tiled_v && dispatch_wg(ctx, cv, h, w, ws, st)) || dispatch_ws(ctx, cv, h, w, ws, st, tiled_v) ||
+             dispatch_mfma<uint16_t>(ctx, cv, h, w, ws, st, tiled_v);
     else
         ok = dispatch_mfma<float>(ctx, cv, h, w, ws, st, false);
     if (!ok) return E2F_ERR_UNSUPPORTED;

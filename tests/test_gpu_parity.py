@@ -47,6 +47,16 @@ def run_case(torch, wl, targets=None, check_materialized=True, message_mode="den
         for l in range(cfg["L"] + 1):   # no degree may hide behind the others
             if np.linalg.norm(ref[:, l * l:(l + 1) ** 2]) > 0:
                 assert rel_l2(fused[sel][:, l * l:(l + 1) ** 2], ref[:, l * l:(l + 1) ** 2]) <= TOL[cfg["dtype"]]
+        Ch = cfg["C"] // cfg["H"]
+        if cfg["lf"] == 1 and Ch <= 64 and Ch & (Ch - 1) == 0:
+            # the paper's factorized pipeline (node-level source/target products around Algorithm 1) gives the same result
+            out_f = torch.full_like(P.out, float("nan"))
+            P.forward_factorized(out_f)
+            torch.cuda.synchronize()
+            fact = out_f.cpu().numpy().astype(np.float64)
+            assert np.isfinite(fact).all()
+            errf = rel_l2(fact[sel], ref)
+            assert errf <= TOL[cfg["dtype"]], f"factorized rel L2 {errf}"
         if check_materialized:
             out_m = torch.full_like(P.out, float("nan"))
             E, peak = P.forward_materialized(out_m)
