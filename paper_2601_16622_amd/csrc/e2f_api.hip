@@ -88,7 +88,7 @@ e2f_status check_forward_args(const e2f_ctx* ctx, const e2f_cells* cells, const 
 
 }  // namespace
 
-E2fAttnWs e2f_attn_ws_layout(const e2f_ctx* ctx, int32_t N, void* ws, bool tiled_v) {
+E2fAttnWs e2f_attn_ws_layout(const e2f_ctx* ctx, int32_t N, void* ws, int v_layout) {
     E2fAttnWs L;
     size_t off = 0;
     auto take = [&](size_t bytes) {
@@ -98,12 +98,25 @@ E2fAttnWs e2f_attn_ws_layout(const e2f_ctx* ctx, int32_t N, void* ws, bool tiled
     };
     const size_t esz = ctx->cfg.feat_dtype == E2F_BF16 ? 2 : 4;
     L.spos = (float4*)take((size_t)N * sizeof(float4));
-    L.q = (float*)take((size_t)N * (ctx->cfg.L_max + 1) * ctx->cfg.C * 4);
-    L.k = (float*)take((size_t)N * (ctx->cfg.L_max + 1) * ctx->cfg.C * 4);
-    // tiled v of the MFMA attention kernel: 16-row tiles per head, two tiles when L_max >= 3
-    const size_t v_elems = tiled_v ? (size_t)ctx->cfg.H * (ctx->cfg.L_max >= 3 ? 2 : 1) * 256
-                                              : (size_t)ctx->n * ctx->cfg.C;
-    L.v = (void*)take((size_t)N * v_elems * esz);
+    L.q = L.k = nullptr;
+    L.v = nullptr;
+    L.q16 = L.k16 = L.v4 = nullptr;
+    L.G = nullptr;
+    if (v_layout == 2) {
+        const size_t H = ctx->cfg.H, DKP = ((size_t)(ctx->cfg.L_max + 1) * 16 + 31) / 32 * 32;
+        const size_t N4 = ((size_t)N + 3) / 4 * 4;
+        L.q16 = (uint16_t*)take((size_t)N * H * DKP * 2);
+        L.k16 = (uint16_t*)take(N4 * H * DKP * 2);
+        L.v4 = (uint16_t*)take(N4 / 4 * H * ctx->n * 64 * 2);
+        L.G = (float*)take((size_t)3 * E2F_MAX_N * E2F_MAX_N * 4);
+    } else {
+        L.q = (float*)take((size_t)N * (ctx->cfg.L_max + 1) * ctx->cfg.C * 4);
+        L.k = (float*)take((size_t)N * (ctx->cfg.L_max + 1) * ctx->cfg.C * 4);
+        // tiled v of the per-pair MFMA attention kernel: 16-row tiles per head, two tiles when L_max >= 3
+        const size_t v_elems = v_layout == 1 ? (size_t)ctx->cfg.H * (ctx->cfg.L_max >= 3 ? 2 : 1) * 256
+                                             : (size_t)ctx->n * ctx->cfg.C;
+        L.v = (void*)take((size_t)N * v_elems * esz);
+    }
     L.cw = (float*)take((size_t)E2F_MAX_N * E2F_NP * 4);
     L.wbT = (float*)take((size_t)ctx->cfg.B * ctx->cfg.H * 4);
     L.bytes = off;
@@ -166,9 +179,13 @@ e2f_status e2f_create(const e2f_config* cfg, e2f_ctx** ctx_out) {
                 c->coefP[comp][kk] = (float)((kk % 2) ? (m > 0 ? cg : (m < 0 ? -cg : 0.0)) : cg);
             }
         }
-    // E2F_ATTENTION=valu in the environment keeps the attention stage off the matrix cores (for A/B timing)
+    // Attention kernel: the per-pair matrix-core kernel where it applies, else the ALU kernel.  E2F_ATTENTION in the
+    // environment overrides the choice (for A/B timing): "valu" keeps the stage off the matrix cores, "tile" selects
+    // the tile kernel where that one applies.
     const char* pick = getenv("E2F_ATTENTION");
-    c->use_mfma_attn = e2f_fused_mfma_supported(c) && !(pick && strcmp(pick, "valu") == 0);
+    const bool only_valu = pick && strcmp(pick, "valu") == 0, want_tile = pick && strcmp(pick, "tile") == 0;
+    c->use_tile_attn = want_tile && e2f_tile_supported(c);
+    c->use_mfma_attn = !c->use_tile_attn && e2f_fused_mfma_supported(c) && !only_valu;
     c->prof_events = nullptr;
     c->prof_capacity = 0;
     c->prof_calls = 0;
@@ -268,7 +285,7 @@ e2f_status e2f_list_neighbors(e2f_ctx* ctx, const e2f_cells* cells, const float*
 
 size_t e2f_attn_workspace_bytes(const e2f_ctx* ctx, int32_t N) {
     if (!ctx || N < 0) return 0;
-    return e2f_attn_ws_layout(ctx, N, nullptr, ctx->use_mfma_attn).bytes;
+    return e2f_attn_ws_layout(ctx, N, nullptr, e2f_v_layout(ctx)).bytes;
 }
 
 e2f_status e2f_attn_forward(e2f_ctx* ctx, const e2f_cells* cells, const float* pos, const void* h,
@@ -277,16 +294,17 @@ e2f_status e2f_attn_forward(e2f_ctx* ctx, const e2f_cells* cells, const float* p
     e2f_status rc = check_forward_args(ctx, cells, pos, h, seg_offsets, N, S, w, out, ws, ws_bytes);
     if (rc != E2F_OK || N == 0) return rc;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
-    const E2fAttnWs L = e2f_attn_ws_layout(ctx, N, ws, ctx->use_mfma_attn);
+    const E2fAttnWs L = e2f_attn_ws_layout(ctx, N, ws, e2f_v_layout(ctx));
     hipEvent_t* ev = (ctx->prof_events && ctx->prof_calls < ctx->prof_capacity)
                          ? ctx->prof_events + ctx->prof_calls * (E2F_N_STAGES + 1) : nullptr;
     if (ev) E2F_HIP_CHECK(hipEventRecord(ev[0], st));
     if ((rc = e2f_launch_prepare(ctx, cells->view, pos, w, L, st)) != E2F_OK) return rc;
     if (ev) E2F_HIP_CHECK(hipEventRecord(ev[1], st));
-    if ((rc = e2f_launch_project_mfma(ctx, cells->view, h, w, L, ctx->use_mfma_attn, st)) != E2F_OK) return rc;
+    if ((rc = e2f_launch_project_mfma(ctx, cells->view, h, w, L, e2f_v_layout(ctx), st)) != E2F_OK) return rc;
     if (ev) E2F_HIP_CHECK(hipEventRecord(ev[2], st));
-    rc = ctx->use_mfma_attn ? e2f_launch_fused_mfma(ctx, cells->view, w, L, out, st)
-                            : e2f_launch_fused(ctx, cells->view, w, L, out, st);
+    rc = ctx->use_tile_attn   ? e2f_launch_tile(ctx, cells->view, L, out, st)
+         : ctx->use_mfma_attn ? e2f_launch_fused_mfma(ctx, cells->view, w, L, out, st)
+                              : e2f_launch_fused(ctx, cells->view, w, L, out, st);
     if (rc != E2F_OK) return rc;
     if (ev) {
         E2F_HIP_CHECK(hipEventRecord(ev[3], st));
@@ -313,7 +331,7 @@ static E2fFactWs fact_ws_layout(const e2f_ctx* ctx, int32_t N, void* ws, size_t 
 
 size_t e2f_attn_factorized_workspace_bytes(const e2f_ctx* ctx, int32_t N) {
     if (!ctx || N < 0) return 0;
-    return fact_ws_layout(ctx, N, nullptr, e2f_attn_ws_layout(ctx, N, nullptr, false).bytes).bytes;
+    return fact_ws_layout(ctx, N, nullptr, e2f_attn_ws_layout(ctx, N, nullptr, 0).bytes).bytes;
 }
 
 e2f_status e2f_attn_forward_factorized(e2f_ctx* ctx, const e2f_cells* cells, const float* pos, const void* h,
@@ -326,10 +344,10 @@ e2f_status e2f_attn_forward_factorized(e2f_ctx* ctx, const e2f_cells* cells, con
     if (rc != E2F_OK || N == 0) return rc;
     if (ws_bytes < e2f_attn_factorized_workspace_bytes(ctx, N)) return E2F_ERR_WORKSPACE_TOO_SMALL;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
-    const E2fAttnWs L = e2f_attn_ws_layout(ctx, N, ws, false);
+    const E2fAttnWs L = e2f_attn_ws_layout(ctx, N, ws, 0);
     const E2fFactWs F = fact_ws_layout(ctx, N, ws, L.bytes);
     if ((rc = e2f_launch_prepare(ctx, cells->view, pos, w, L, st)) != E2F_OK) return rc;
-    if ((rc = e2f_launch_project_mfma(ctx, cells->view, h, w, L, false, st)) != E2F_OK) return rc;
+    if ((rc = e2f_launch_project_mfma(ctx, cells->view, h, w, L, 0, st)) != E2F_OK) return rc;
     return e2f_launch_factorized(ctx, cells->view, L, F, out, st);
 }
 
@@ -348,7 +366,7 @@ e2f_status e2f_attn_forward_materialized(e2f_ctx* ctx, const e2f_cells* cells, c
     if (edges_out) *edges_out = 0;
     if (peak_bytes_out) *peak_bytes_out = 0;
     if (rc != E2F_OK || N == 0) return rc;
-    const E2fAttnWs L = e2f_attn_ws_layout(ctx, N, ws, ctx->use_mfma_attn);
+    const E2fAttnWs L = e2f_attn_ws_layout(ctx, N, ws, e2f_v_layout(ctx));
     return e2f_run_materialized(ctx, cells->view, pos, h, w, L, out, static_cast<hipStream_t>(hip_stream), edges_out,
                                 peak_bytes_out);
 }

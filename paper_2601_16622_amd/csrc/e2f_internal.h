@@ -46,7 +46,8 @@ struct e2f_ctx {
     int32_t n;         // (L_max+1)^2
     int32_t Ch;        // channels per head
     int32_t cpl;       // channels per lane in the fused kernel
-    bool use_mfma_attn;  // attention on the matrix cores (bf16, heads of 16 channels, lf = 1); v is stored tiled
+    bool use_mfma_attn;  // per-pair attention on the matrix cores (bf16, heads of 16 channels); v is stored tiled
+    bool use_tile_attn;  // tile attention kernel (bf16, heads of 16 channels, lf = 1); q, k, v in its group layout
     float tau;         // 1/sqrt(d_k)
     float rc2;         // cutoff*cutoff rounded to binary32
     float rbf_gamma;   // (B-1)^2 / (2 cutoff^2)
@@ -67,9 +68,16 @@ struct E2fAttnWs {
     void* v;        // [N][n][C] sorted order, float or bf16 (follows feat_dtype)
     float* cw;      // [n][E2F_NP] P coefficients times path weights
     float* wbT;     // [B][H] radial bias weights, transposed
+    // layout of the tile attention kernel (v_layout 2; q, k, v above are then unused)
+    uint16_t* q16;       // [N][H][DKP] binary16, q * tau * log2(e)
+    uint16_t* k16;       // [4*ceil(N/4)][H][DKP] binary16
+    uint16_t* v4;        // [ceil(N/4)][H][n][16 channels][4 slots] bf16
+    float* G;            // [3][25][25] axis operators of the degree-1 filter
     size_t bytes;
 };
-E2fAttnWs e2f_attn_ws_layout(const e2f_ctx* ctx, int32_t N, void* ws, bool tiled_v);
+// v_layout: 0 plain [N][n][C], 1 component tiles of the per-pair MFMA kernel, 2 slot groups of the tile kernel
+E2fAttnWs e2f_attn_ws_layout(const e2f_ctx* ctx, int32_t N, void* ws, int v_layout);
+static inline int e2f_v_layout(const e2f_ctx* ctx) { return ctx->use_tile_attn ? 2 : (ctx->use_mfma_attn ? 1 : 0); }
 
 // Extra O(N) buffers of the factorized pipeline, placed after the attention workspace (untiled v).
 struct E2fFactWs {
@@ -97,7 +105,7 @@ e2f_status e2f_launch_list_neighbors(const e2f_ctx* ctx, const E2fCellsView& cv,
 e2f_status e2f_launch_prepare(const e2f_ctx* ctx, const E2fCellsView& cv, const float* pos, const e2f_weights* w,
                               const E2fAttnWs& ws, hipStream_t st);
 e2f_status e2f_launch_project_mfma(const e2f_ctx* ctx, const E2fCellsView& cv, const void* h, const e2f_weights* w,
-                                   const E2fAttnWs& ws, bool tiled_v, hipStream_t st);
+                                   const E2fAttnWs& ws, int v_layout, hipStream_t st);
 bool e2f_factorized_supported(const e2f_ctx* ctx);
 e2f_status e2f_launch_factorized(const e2f_ctx* ctx, const E2fCellsView& cv, const E2fAttnWs& ws, const E2fFactWs& fw,
                                  float* out, hipStream_t st);
@@ -108,6 +116,8 @@ e2f_status e2f_launch_fused(const e2f_ctx* ctx, const E2fCellsView& cv, const e2
 e2f_status e2f_launch_tensor_product(const e2f_ctx* ctx, const void* h, const float* r, const float* w_path, float* out,
                                      int32_t T, hipStream_t st);
 bool e2f_fused_mfma_supported(const e2f_ctx* ctx);
+bool e2f_tile_supported(const e2f_ctx* ctx);
+e2f_status e2f_launch_tile(const e2f_ctx* ctx, const E2fCellsView& cv, const E2fAttnWs& ws, float* out, hipStream_t st);
 e2f_status e2f_launch_fused_mfma(const e2f_ctx* ctx, const E2fCellsView& cv, const e2f_weights* w, const E2fAttnWs& ws,
                                  float* out, hipStream_t st);
 e2f_status e2f_run_materialized(const e2f_ctx* ctx, const E2fCellsView& cv, const float* pos, const void* h,

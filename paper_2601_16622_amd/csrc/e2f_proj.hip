@@ -358,7 +358,16 @@ struct WgRoles {
     int deg[WG_WAVES][E2F_MAX_L + 1];
 };
 
-template <int C>
+// Outputs in the layout of the tile attention kernel (VL = 2): q and k per head in binary16, DKP = (L+1)*16
+// features padded to a multiple of 32 (q times qscale), and v in groups of four consecutive slots,
+// bf16 [slot/4][head][component][16 channels][4 slots]; rows beyond N read as zero.
+struct WgGroupOut {
+    uint16_t *q16, *k16, *v4;
+    float qscale;
+    int DKP;
+};
+
+template <int C, int VL>
 __global__ __launch_bounds__(64 * WG_WAVES) void k_project_wg(E2fCellsView cv, const uint16_t* __restrict__ h,
                                                               const uint16_t* __restrict__ WQ1,
                                                               const uint16_t* __restrict__ WQ2,
@@ -366,7 +375,7 @@ __global__ __launch_bounds__(64 * WG_WAVES) void k_project_wg(E2fCellsView cv, c
                                                               const uint16_t* __restrict__ WK2,
                                                               const uint16_t* __restrict__ WV, int L, WgRoles roles,
                                                               float* __restrict__ q, float* __restrict__ k,
-                                                              uint16_t* __restrict__ v) {
+                                                              uint16_t* __restrict__ v, WgGroupOut go) {
     typedef Frag<uint16_t> F;
     constexpr int NS = C / F::KSTEP;
     constexpr int NCT = C / 16;
@@ -460,6 +469,50 @@ __global__ __launch_bounds__(64 * WG_WAVES) void k_project_wg(E2fCellsView cv, c
     __syncthreads();
     // ---- copy out: v, 16 bytes per thread; every (atom, head = ct) block of NT*512 bytes is contiguous
     const int n_atoms = min(tile1 * 16, N) - tile0 * 16;
+    if constexpr (VL == 2) {
+        const int n_groups = (n_atoms + 3) >> 2;
+        // v: 16-byte units of two channels, 8 bytes (four slots) per (group, component, channel)
+        for (int x = tid; x < n_groups * n * 8; x += 64 * WG_WAVES) {
+            const int gl = x / (n * 8), rem = x - gl * n * 8, comp = rem >> 3, ch = (rem & 7) * 2;
+            int l = 0;
+            while ((l + 1) * (l + 1) <= comp) ++l;
+            const int m = comp - l * l;
+            const int T = l >= 3 ? 0 : NT - 1;
+            const int pos = (l == 4 ? 0 : (l == 3 ? 9 : (l == 2 ? 0 : (l == 1 ? 5 : 8)))) + m;
+            uint16_t val[8];
+#pragma unroll
+            for (int s2 = 0; s2 < 2; ++s2)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int a = 4 * gl + i;
+                    val[4 * s2 + i] = a < n_atoms ? s_v[((a * 2 + T) * 16 + ch + s2) * 16 + pos] : (uint16_t)0;
+                }
+            uint4 pk;
+            pk.x = val[0] | ((uint32_t)val[1] << 16);
+            pk.y = val[2] | ((uint32_t)val[3] << 16);
+            pk.z = val[4] | ((uint32_t)val[5] << 16);
+            pk.w = val[6] | ((uint32_t)val[7] << 16);
+            *reinterpret_cast<uint4*>(go.v4 + ((((size_t)tile0 * 4 + gl) * NCT + ct) * n + comp) * 64 + ch * 4) = pk;
+        }
+        // q, k: 16-byte units of eight features (feature = l*16 + channel) in binary16
+        const int u_per = go.DKP >> 3, DK = (L + 1) * 16;
+        for (int x = tid; x < n_groups * 4 * u_per; x += 64 * WG_WAVES) {
+            const int a = x / u_per, f0 = (x - a * u_per) * 8;
+            const size_t slot = (size_t)tile0 * 16 + a;
+            typedef _Float16 h16x8 __attribute__((ext_vector_type(8)));
+            h16x8 qv, kv;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const bool real = a < n_atoms && f0 + i < DK;
+                qv[i] = (_Float16)(real ? s_q[a * (E2F_MAX_L + 1) * 16 + f0 + i] * go.qscale : 0.0f);
+                kv[i] = (_Float16)(real ? s_k[a * (E2F_MAX_L + 1) * 16 + f0 + i] : 0.0f);
+            }
+            const size_t dst = (slot * NCT + ct) * go.DKP + f0;
+            *reinterpret_cast<h16x8*>(go.k16 + dst) = kv;
+            if (a < n_atoms) *reinterpret_cast<h16x8*>(go.q16 + dst) = qv;
+        }
+        return;
+    }
     const int v_chunks = NT * 32;   // 16-byte chunks per atom
     for (int x = tid; x < n_atoms * v_chunks; x += 64 * WG_WAVES) {
         const int a = x / v_chunks, c16 = x - a * v_chunks;
@@ -559,7 +612,7 @@ bool launch_ws(const e2f_ctx* ctx, const E2fCellsView& cv, const void* h, const 
 
 template <int C>
 bool launch_wg(const e2f_ctx* ctx, const E2fCellsView& cv, const void* h, const e2f_weights* w, const E2fAttnWs& ws,
-               hipStream_t st) {
+               hipStream_t st, int v_layout) {
     if constexpr (C % 32 != 0 || C > 128) {
         return false;
     } else {
@@ -577,20 +630,30 @@ bool launch_wg(const e2f_ctx* ctx, const E2fCellsView& cv, const void* h, const 
         }
         const int groups = (n_tiles + WG_TPW - 1) / WG_TPW;
         const int blocks = ((groups + 7) / 8) * 8 * (C / 16);
-        k_project_wg<C><<<blocks, 64 * WG_WAVES, 0, st>>>(cv, (const uint16_t*)h, (const uint16_t*)w->WQ1,
-                                                         (const uint16_t*)w->WQ2, (const uint16_t*)w->WK1,
-                                                         (const uint16_t*)w->WK2, (const uint16_t*)w->WV, L, roles,
-                                                         ws.q, ws.k, (uint16_t*)ws.v);
+        WgGroupOut go;
+        go.q16 = ws.q16; go.k16 = ws.k16; go.v4 = ws.v4;
+        go.qscale = ctx->tau * 1.44269504088896341f;   // logits in base-2 units
+        go.DKP = ((L + 1) * 16 + 31) / 32 * 32;
+        if (v_layout == 2)
+            k_project_wg<C, 2><<<blocks, 64 * WG_WAVES, 0, st>>>(cv, (const uint16_t*)h, (const uint16_t*)w->WQ1,
+                                                                (const uint16_t*)w->WQ2, (const uint16_t*)w->WK1,
+                                                                (const uint16_t*)w->WK2, (const uint16_t*)w->WV, L, roles,
+                                                                ws.q, ws.k, (uint16_t*)ws.v, go);
+        else
+            k_project_wg<C, 1><<<blocks, 64 * WG_WAVES, 0, st>>>(cv, (const uint16_t*)h, (const uint16_t*)w->WQ1,
+                                                                (const uint16_t*)w->WQ2, (const uint16_t*)w->WK1,
+                                                                (const uint16_t*)w->WK2, (const uint16_t*)w->WV, L, roles,
+                                                                ws.q, ws.k, (uint16_t*)ws.v, go);
         return true;
     }
 }
 
 bool dispatch_wg(const e2f_ctx* ctx, const E2fCellsView& cv, const void* h, const e2f_weights* w, const E2fAttnWs& ws,
-                 hipStream_t st) {
+                 hipStream_t st, int v_layout) {
     switch (ctx->cfg.C) {
-        case 32: return launch_wg<32>(ctx, cv, h, w, ws, st);
-        case 64: return launch_wg<64>(ctx, cv, h, w, ws, st);
-        case 128: return launch_wg<128>(ctx, cv, h, w, ws, st);
+        case 32: return launch_wg<32>(ctx, cv, h, w, ws, st, v_layout);
+        case 64: return launch_wg<64>(ctx, cv, h, w, ws, st, v_layout);
+        case 128: return launch_wg<128>(ctx, cv, h, w, ws, st, v_layout);
     }
     return false;
 }
@@ -636,11 +699,14 @@ e2f_status e2f_launch_prepare(const e2f_ctx* ctx, const E2fCellsView& cv, const 
 }
 
 e2f_status e2f_launch_project_mfma(const e2f_ctx* ctx, const E2fCellsView& cv, const void* h, const e2f_weights* w,
-                                   const E2fAttnWs& ws, bool tiled_v, hipStream_t st) {
+                                   const E2fAttnWs& ws, int v_layout, hipStream_t st) {
     if (cv.N == 0) return E2F_OK;
     bool ok;
-    if (ctx->cfg.feat_dtype == E2F_BF16)
-        ok = (tiled_v && dispatch_wg(ctx, cv, h, w, ws, st)) || dispatch_ws(ctx, cv, h, w, ws, st, tiled_v) ||
+    const bool tiled_v = v_layout == 1;
+    if (v_layout == 2)
+        ok = ctx->cfg.feat_dtype == E2F_BF16 && dispatch_wg(ctx, cv, h, w, ws, st, 2);
+    else if (ctx->cfg.feat_dtype == E2F_BF16)
+        ok = (tiled_v && dispatch_wg(ctx, cv, h, w, ws, st, 1)) || dispatch_ws(ctx, cv, h, w, ws, st, tiled_v) ||
              dispatch_mfma<uint16_t>(ctx, cv, h, w, ws, st, tiled_v);
     else
         ok = dispatch_mfma<float>(ctx, cv, h, w, ws, st, false);

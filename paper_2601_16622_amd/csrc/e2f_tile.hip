@@ -1,0 +1,522 @@
+// Tile form of the fused on-the-fly attention for a degree-1 filter (Sec. 3.4, Algorithm 1, with the linear
+// factorization of the filter, Eq. e2former_final at l = 1): the message is linear in the pair vector,
+//     v_j (x) R^(1)(r_ij) = sum_mu (r_ij)_mu  G_mu v_j ,        G_mu = (.) (x) R^(1)(e_mu),  mu = x, y, z,
+// so   out_i = (1/z_i) sum_mu G_mu T_i,mu   with   T_i,mu = sum_j e^{s_ij - m_i} phi(d_ij) (r_ij)_mu v_j .
+// Both dense pieces run on the matrix cores over tiles of 16 target atoms x 32 candidate atoms:
+//     S^T = K Q^T          (logits; q and k in binary16, 11-bit significands)
+//     T_mu += W_mu V       (aggregation; W_mu[i][j] = e^{s_ij - m_i} phi(d_ij) (r_ij)_mu in bf16, zero off the
+//                           neighbour set, V the value rows of the 32 candidates)
+// Candidates are groups of four consecutive sorted slots taken from the 27-cell stencil of the tile; the pair
+// geometry (distance, cutoff predicate, radial bias, gate) is evaluated per (target, candidate) in registers, the
+// softmax is online with a lazily moved reference m_i, and the three axis operators G_mu (built by the EAAS route,
+// D^T P D for the three axis frames, path weights included) are applied once per target in the epilogue, using
+// only their non-zero entries.  Nothing per pair is written to global memory.
+//
+// One wave owns (tile, head, half of the component pairs); the two halves of a head form a workgroup and add
+// their partial outputs through LDS.  Register layout notes (v_mfma_f32_16x16x32_bf16, lane = 16 g + i):
+//   A operand: lane holds A[i][8g..8g+7]; B operand: lane holds B[8g..8g+7][i]; result: lane holds C[4g..4g+3][i].
+// The logits come out as S^T[candidate row 4g+r][target i] for two 16-candidate halves; read as the A operand of the
+// aggregation the same registers are W[target i][k = 8g + r'] with k -> (first half, row 4g+r') for r' < 4 and
+// (second half, row 4g+r'-4) otherwise, and the V operand is loaded in that same order of k.
+#include <stdio.h>
+#include <stdlib.h>
+
+#include "e2f_axis_pattern.h"
+#include "e2f_device.h"
+
+namespace {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+
+constexpr int CAPG = 256;      // candidate groups (of four slots) held in LDS per batch
+constexpr int TILE_BLK = 16;   // consecutive tiles whose (tile, head) items form one XCD chunk, head-major
+constexpr float M_STEP = 6.0f; // the softmax reference moves when a logit exceeds it by this much (base-2 units)
+
+struct TileParams {
+    E2fCellsView cv;
+    const float4* spos;
+    const uint16_t *q16, *k16, *v4;
+    const float* G;
+    const float* WbT;
+    float* out;
+    int C, H, B, n_tiles;
+    float rc2, cutoff, rbf_step, rbf_gamma;
+#ifdef E2F_TIMING
+    unsigned long long* dbg;
+#endif
+};
+
+#ifdef E2F_TIMING
+#define TICK(k) { unsigned long long now_ = __builtin_amdgcn_s_memtime(); tacc[k] += now_ - tprev; tprev = now_; }
+#else
+#define TICK(k)
+#endif
+
+__device__ __forceinline__ float read_lane(float x, int src_lane) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, x), src_lane));
+}
+__device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
+    f32x2 v = {a, b};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
+}
+__device__ __forceinline__ f32x4 mfma(bf16x8 a, bf16x8 b, f32x4 c) {
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
+}
+__device__ __forceinline__ f32x4 mfma(f16x8 a, f16x8 b, f32x4 c) {
+    return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0);
+}
+
+// The candidate list in LDS is private to a wave, whose LDS operations complete in order: ordering them in the
+// instruction stream is all that is needed, no workgroup barrier.
+__device__ __forceinline__ void wave_lds_sync() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+}
+// Workgroups are dealt to the 8 XCDs round-robin, each XCD with its own L2.  A chunk of TILE_BLK consecutive tiles
+// (neighbours in space) goes to one XCD and is run head by head, so that the workgroups resident on an XCD at any
+// time read the k and v rows of one head over one small region.
+__device__ __forceinline__ bool tile_xcd_remap(int bid, int n_tiles, int H, int& tile, int& head) {
+    const int xcd = bid & 7, idx = bid >> 3, per = TILE_BLK * H;
+    const int chunk = (idx / per) * 8 + xcd, within = idx % per;
+    head = within / TILE_BLK;
+    tile = chunk * TILE_BLK + within % TILE_BLK;
+    return tile < n_tiles;
+}
+
+// The three axis operators, column by column: G[mu][x_out][x_in] = (e_{x_in} (x) R^(1)(e_mu))[x_out].
+template <int L>
+__global__ void k_axis_ops(const float* __restrict__ cw, float* __restrict__ G) {
+    constexpr int n = (L + 1) * (L + 1), DS = e2f::d_offset(L + 1);
+    const int tid = threadIdx.x;
+    if (tid >= 3 * n) return;
+    const int mu = tid / n, xi = tid % n;
+    float D[DS];
+    e2f::align_D<L>(mu == 0 ? 1.0f : 0.0f, mu == 1 ? 1.0f : 0.0f, mu == 2 ? 1.0f : 0.0f, 1.0f, D);
+    float v[n][1], acc[n][1];
+#pragma unroll
+    for (int x = 0; x < n; ++x) {
+        v[x][0] = x == xi ? 1.0f : 0.0f;
+        acc[x][0] = 0.0f;
+    }
+    e2f::eaas_accumulate<L, 1, 1>(v, D, cw, 1.0f, acc);
+#pragma unroll
+    for (int xo = 0; xo < n; ++xo) G[(mu * E2F_MAX_N + xo) * E2F_MAX_N + xi] = acc[xo][0];
+}
+
+// One wave: component pairs [CP0, CP1) of one (tile, head).  po[x_out] receives this wave's share of
+// sum_mu G_mu T_mu (rows = targets 4g..4g+3, column = channel lane%16), z_rows the softmax sums of those targets.
+template <int L, int CP0, int CP1>
+__device__ __forceinline__ void tile_wave(const TileParams& P, int tile, int head, int* s_ent, float4* s_pos,
+                                          f32x4 (&po)[(L + 1) * (L + 1)], f32x4& z_rows) {
+    constexpr int n = (L + 1) * (L + 1), X0 = 2 * CP0, NX = (2 * CP1 < n ? 2 * CP1 : n) - X0;   // this wave's components
+    constexpr int DK = (L + 1) * 16, KS = (DK + 31) / 32, DKP = KS * 32;
+    const int lane = threadIdx.x & 63, tn = lane & 15, g = lane >> 4;
+#ifdef E2F_TIMING
+    unsigned long long tacc[6] = {0, 0, 0, 0, 0, 0};
+    unsigned long long tprev = __builtin_amdgcn_s_memtime();
+#endif
+    const int N = P.cv.N, H = P.H;
+    const int t0 = tile * 16, nt = min(16, N - t0);
+    const int tslot = min(t0 + tn, N - 1);
+    const float4 tp = P.spos[tslot];
+    const int tseg = P.cv.sseg[tslot];
+    int tcx, trow;
+    {
+        const E2fSegGrid tg = P.cv.grid[tseg];
+        const int loc = P.cv.scell[tslot] - tg.base;
+        tcx = loc % tg.nx;
+        trow = loc / tg.nx;
+    }
+
+    // radial bias of this head as a polynomial in u = e^{2 gamma step d}:  b(d) = e^{-gamma d^2} sum_b cb[b] u^b,
+    // cb[b] = Wb[h][b] e^{-gamma (b step)^2} (log2 e folded in)
+    float cb[8];
+    {
+        const float bs = (float)lane * P.rbf_step;
+        const float mine = lane < P.B ? P.WbT[lane * H + head] * __expf(-P.rbf_gamma * bs * bs) * 1.44269504088896341f : 0.0f;
+#pragma unroll
+        for (int b = 0; b < 8; ++b) cb[b] = read_lane(mine, b);
+    }
+    const float c_u = 2.0f * P.rbf_gamma * P.rbf_step * 1.44269504088896341f;
+    const float c_g = -P.rbf_gamma * 1.44269504088896341f;
+
+    f16x8 qf[KS];
+    {
+        const size_t qoff = ((size_t)tslot * H + head) * DKP + 8 * g;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) qf[ks] = *reinterpret_cast<const f16x8*>(P.q16 + qoff + 32 * ks);
+    }
+
+    f32x4 acc[3][NX];
+#pragma unroll
+    for (int mu = 0; mu < 3; ++mu)
+#pragma unroll
+        for (int x = 0; x < NX; ++x) acc[mu][x] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    float m_ref = -INFINITY, z = 0.0f;
+
+    TICK(0)
+    int a = 0;
+    while (a < nt) {
+        // ---- a pass: the targets [a, b) of the tile that share a row of cells (same segment, same y and z cell)
+        const int seg_a = __builtin_amdgcn_readlane(tseg, a), row_a = __builtin_amdgcn_readlane(trow, a);
+        const bool same = tseg == seg_a && trow == row_a && lane >= a && lane < nt;   // lanes 0..15 carry the targets
+        const unsigned bits = (unsigned)(__ballot(same) & 0xFFFFull);
+        const unsigned stop = ~bits & ((1u << nt) - 1u) & ~((1u << a) - 1u);
+        const int b = stop ? __builtin_ctz(stop) : nt;
+        const bool t_active = tn >= a && tn < b;
+        const int cxa = __builtin_amdgcn_readlane(tcx, a), cxb = __builtin_amdgcn_readlane(tcx, b - 1);
+        int lo[9], hi[9], pre[10];
+        {
+            const E2fSegGrid G = P.cv.grid[seg_a];
+            const int cy = row_a % G.ny, cz = row_a / G.ny;
+            const int x0 = max(cxa - 1, 0), x1 = min(cxb + 1, G.nx - 1);
+            pre[0] = 0;
+#pragma unroll
+            for (int r = 0; r < 9; ++r) {
+                const int y = cy + (r % 3) - 1, zc = cz + (r / 3) - 1;
+                if (y < 0 || y >= G.ny || zc < 0 || zc >= G.nz) {
+                    lo[r] = 0;
+                    hi[r] = 0;
+                } else {
+                    const int row = G.base + (zc * G.ny + y) * G.nx;
+                    lo[r] = P.cv.cell_start[row + x0];
+                    hi[r] = P.cv.cell_start[row + x1 + 1];
+                }
+                pre[r + 1] = pre[r] + (hi[r] > lo[r] ? ((hi[r] + 3) >> 2) - (lo[r] >> 2) : 0);
+            }
+        }
+        // bounding box of the pass's targets: a candidate group is kept if one of its slots can be within the
+        // cutoff of the box (pruning only; the predicate itself is evaluated per pair below)
+        float bx0 = t_active ? tp.x : INFINITY, bx1 = t_active ? tp.x : -INFINITY;
+        float by0 = t_active ? tp.y : INFINITY, by1 = t_active ? tp.y : -INFINITY;
+        float bz0 = t_active ? tp.z : INFINITY, bz1 = t_active ? tp.z : -INFINITY;
+#pragma unroll
+        for (int off = 1; off < 16; off <<= 1) {
+            bx0 = fminf(bx0, __shfl_xor(bx0, off)); bx1 = fmaxf(bx1, __shfl_xor(bx1, off));
+            by0 = fminf(by0, __shfl_xor(by0, off)); by1 = fmaxf(by1, __shfl_xor(by1, off));
+            bz0 = fminf(bz0, __shfl_xor(bz0, off)); bz1 = fmaxf(bz1, __shfl_xor(bz1, off));
+        }
+        const float prune2 = P.rc2 * 1.001f;
+
+        const int total = pre[9];
+        int fbase = 0;
+        while (fbase < total) {
+            // ---- a batch of the candidate list: entries (group << 4 | valid slots) and the slots' positions in LDS
+            int cnt = 0;
+            while (fbase < total && cnt + 64 <= CAPG) {
+                // four steps of 16 groups: all positions are requested before the first is looked at
+                int ln = lane;
+                asm volatile("" : "+v"(ln));   // keeps (lane - pre[r]) from being hoisted out of the loop
+                int grp[4];
+                bool valid[4];
+                float4 pj[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int fg = fbase + 16 * u + (ln >> 2);
+                    int gq = -1, rlo = 0, rhi = 0;
+#pragma unroll
+                    for (int r = 0; r < 9; ++r)
+                        if (fg >= pre[r] && fg < pre[r + 1]) {
+                            gq = (lo[r] >> 2) + fg - pre[r];
+                            rlo = lo[r];
+                            rhi = hi[r];
+                        }
+                    const int slot = 4 * gq + (ln & 3);
+                    grp[u] = gq;
+                    valid[u] = gq >= 0 && slot >= rlo && slot < rhi;
+                    pj[u] = P.spos[valid[u] ? slot : tslot];
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const float ex = fmaxf(fmaxf(bx0 - pj[u].x, pj[u].x - bx1), 0.0f);
+                    const float ey = fmaxf(fmaxf(by0 - pj[u].y, pj[u].y - by1), 0.0f);
+                    const float ez = fmaxf(fmaxf(bz0 - pj[u].z, pj[u].z - bz1), 0.0f);
+                    const bool near = valid[u] && (ex * ex + ey * ey + ez * ez) < prune2;
+                    const int sh = lane & ~3;
+                    const unsigned near4 = (unsigned)(__ballot(near) >> sh) & 0xFu;
+                    const unsigned valid4 = (unsigned)(__ballot(valid[u]) >> sh) & 0xFu;
+                    const unsigned long long leaders = __ballot(near4 != 0u && (lane & 3) == 0);
+                    const int e = cnt + __popcll(leaders & ((1ull << sh) - 1ull));
+                    if (near4 != 0u) {
+                        if ((lane & 3) == 0) s_ent[e] = (grp[u] << 4) | (int)valid4;
+                        s_pos[e * 4 + (lane & 3)] = pj[u];
+                    }
+                    cnt += __popcll(leaders);
+                }
+                fbase += 64;
+            }
+            if (lane < 8) s_ent[cnt + lane] = 0;   // pads the last chunk: group 0, no valid slot,
+            if (lane < 32) s_pos[cnt * 4 + lane] = tp; // finite positions (their weights are forced to zero)
+            wave_lds_sync();
+            TICK(1)
+            const int nch = (cnt + 7) >> 3;
+#ifdef E2F_TIMING
+            if (lane == 0 && P.dbg) { atomicAdd(P.dbg + 6, (unsigned long long)nch); atomicAdd(P.dbg + 7, 1ull); }
+#endif
+            if (nch > 0) {
+
+            auto load_K = [&](int c, f16x8 (&kf)[2][KS]) {
+#pragma unroll
+                for (int mt = 0; mt < 2; ++mt) {
+                    const int e = s_ent[8 * c + 4 * mt + (tn >> 2)];
+                    const size_t off = ((size_t)(4 * (e >> 4) + (tn & 3)) * H + head) * DKP + 8 * g;
+#pragma unroll
+                    for (int ks = 0; ks < KS; ++ks) kf[mt][ks] = *reinterpret_cast<const f16x8*>(P.k16 + off + 32 * ks);
+                }
+            };
+            auto logits = [&](const f16x8 (&kf)[2][KS], f32x4 (&S)[2]) {
+#pragma unroll
+                for (int mt = 0; mt < 2; ++mt) {
+                    S[mt] = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                    for (int ks = 0; ks < KS; ++ks) S[mt] = mfma(kf[mt][ks], qf[ks], S[mt]);
+                }
+            };
+            // v rows of component X0 + x for the lane's two entries: k = 8g..8g+3 from entry g, 8g+4..8g+7 from entry 4+g
+            auto load_V = [&](int c, int x, u32x2& va, u32x2& vb) {
+                const int ea = s_ent[8 * c + g] >> 4, eb = s_ent[8 * c + 4 + g] >> 4;
+                va = *reinterpret_cast<const u32x2*>(P.v4 + (((size_t)ea * H + head) * n + X0 + x) * 64 + tn * 4);
+                vb = *reinterpret_cast<const u32x2*>(P.v4 + (((size_t)eb * H + head) * n + X0 + x) * 64 + tn * 4);
+            };
+            // Softmax weights of a chunk for this lane's target and its eight candidates, in two steps so that the
+            // (rare) move of the softmax reference sits outside the streaming loop: the loop's accumulators are then
+            // touched by matrix instructions only and stay in the accumulator register file.
+            struct Scores {
+                float s2[8], gate[8], rx[8], ry[8], rz[8], cmax;
+            };
+            auto scores = [&](int c, const f32x4 (&S)[2], Scores& sc) {
+                float cmax = -INFINITY;
+#pragma unroll
+                for (int mt = 0; mt < 2; ++mt) {
+                    const int ei = 8 * c + 4 * mt + g;
+                    const int e = s_ent[ei];
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        const int u = 4 * mt + r;
+                        const float4 pj = s_pos[ei * 4 + r];
+                        const float d2 = e2f::dist2_exact(tp.x, tp.y, tp.z, pj.x, pj.y, pj.z);
+                        // (bitwise on purpose: the eight candidates are evaluated side by side, not branch by branch)
+                        const bool ok = (((e >> r) & 1) != 0) & t_active & ((4 * (e >> 4) + r) != t0 + tn) &
+                                        (d2 < P.rc2) & (d2 > 0.0f);
+                        const float d = __builtin_amdgcn_sqrtf(d2);
+                        const float uu = __builtin_amdgcn_exp2f(c_u * d);
+                        float poly = cb[7];
+#pragma unroll
+                        for (int bb = 6; bb >= 0; --bb) poly = poly * uu + cb[bb];
+                        const float bias = __builtin_amdgcn_exp2f(c_g * d2) * poly;
+                        sc.s2[u] = ok ? S[mt][r] + bias : -INFINITY;
+                        sc.gate[u] = e2f::radial_gate(d, P.cutoff);
+                        sc.rx[u] = pj.x - tp.x;
+                        sc.ry[u] = pj.y - tp.y;
+                        sc.rz[u] = pj.z - tp.z;
+                        cmax = fmaxf(cmax, sc.s2[u]);
+                    }
+                }
+                cmax = fmaxf(cmax, __shfl_xor(cmax, 16));
+                sc.cmax = fmaxf(cmax, __shfl_xor(cmax, 32));
+                // A target's first neighbours set its reference; its accumulator rows are still zero then.
+                if (m_ref == -INFINITY) m_ref = sc.cmax;
+                // Later the reference moves only for a logit well above it, and the rows have to be rescaled.
+                return __ballot(sc.cmax > m_ref + M_STEP) != 0ull;
+            };
+            auto move_reference = [&](const Scores& sc) {
+                const bool move = sc.cmax > m_ref + M_STEP;
+                const float m_new = move ? sc.cmax : m_ref;
+                const float f = move ? __builtin_amdgcn_exp2f(m_ref - m_new) : 1.0f;   // m_ref is finite when move holds
+                z *= f;
+                m_ref = m_new;
+                // Rows of the accumulators are targets: T <- diag(f) T on the matrix cores in fp32.  Slice r of the
+                // product pairs A_r[i][g] = f_i [i == 4g + r] with B_r[g][j] = T[4g + r][j], register r of lane (j, g).
+                float ar[4];
+#pragma unroll
+                for (int r = 0; r < 4; ++r) ar[r] = tn == 4 * g + r ? f : 0.0f;
+#pragma unroll
+                for (int mu = 0; mu < 3; ++mu)
+#pragma unroll
+                    for (int x = 0; x < NX; ++x) {
+                        f32x4 d = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) d = __builtin_amdgcn_mfma_f32_16x16x4f32(ar[r], acc[mu][x][r], d, 0, 0, 0);
+                        acc[mu][x] = d;
+                    }
+            };
+            auto finish = [&](const Scores& sc, bf16x8 (&W)[3]) {
+                uint32_t wp[3][4];
+#pragma unroll
+                for (int u = 0; u < 8; u += 2) {
+                    float pg[2];
+#pragma unroll
+                    for (int d = 0; d < 2; ++d) {
+                        const float p = sc.s2[u + d] > -INFINITY ? __builtin_amdgcn_exp2f(sc.s2[u + d] - m_ref) : 0.0f;
+                        z += p;
+                        pg[d] = p * sc.gate[u + d];
+                    }
+                    wp[0][u >> 1] = pack_bf16(pg[0] * sc.rx[u], pg[1] * sc.rx[u + 1]);
+                    wp[1][u >> 1] = pack_bf16(pg[0] * sc.ry[u], pg[1] * sc.ry[u + 1]);
+                    wp[2][u >> 1] = pack_bf16(pg[0] * sc.rz[u], pg[1] * sc.rz[u + 1]);
+                }
+#pragma unroll
+                for (int mu = 0; mu < 3; ++mu)
+                    W[mu] = __builtin_bit_cast(bf16x8, (u32x4){wp[mu][0], wp[mu][1], wp[mu][2], wp[mu][3]});
+            };
+
+            // ---- chunks of 8 entries (32 candidates), software pipelined: while chunk c is aggregated, the logits
+            // and weights of chunk c+1 are computed and the k rows of chunk c+2 and the v rows of chunk c+1 are in flight
+            f16x8 kf[2][KS];
+            u32x2 va[NX], vb[NX];
+            f32x4 S[2];
+            bf16x8 W[3];
+            Scores sc;
+            load_K(0, kf);
+#pragma unroll
+            for (int x = 0; x < NX; ++x) load_V(0, x, va[x], vb[x]);
+            logits(kf, S);
+            load_K(min(1, nch - 1), kf);
+            if (scores(0, S, sc)) move_reference(sc);
+            finish(sc, W);
+            TICK(2)
+            int c = 0;
+            while (true) {
+                bool pending = false;
+                while (c < nch) {   // the streaming loop
+                    const int c1 = min(c + 1, nch - 1), c2 = min(c + 2, nch - 1);
+                    logits(kf, S);   // of chunk c1
+                    load_K(c2, kf);
+#pragma unroll
+                    for (int x = 0; x < NX; ++x) {
+                        const bf16x8 bv = __builtin_bit_cast(bf16x8, __builtin_shufflevector(va[x], vb[x], 0, 1, 2, 3));
+#pragma unroll
+                        for (int mu = 0; mu < 3; ++mu) acc[mu][x] = mfma(W[mu], bv, acc[mu][x]);
+                        load_V(c1, x, va[x], vb[x]);
+                    }
+                    ++c;
+                    if (c < nch) {
+                        pending = scores(c, S, sc);
+                        if (pending) break;
+                        finish(sc, W);
+                    }
+                }
+                if (!pending) break;
+                move_reference(sc);
+                finish(sc, W);
+            }
+            }
+            TICK(3)
+            wave_lds_sync();   // the list is rebuilt by the next batch
+        }
+        a = b;
+    }
+
+    // ---- epilogue: this wave's share of sum_mu G_mu T_mu, non-zero entries only
+#pragma unroll
+    for (int xo = 0; xo < n; ++xo) po[xo] = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int mu = 0; mu < 3; ++mu)
+#pragma unroll
+        for (int xo = 0; xo < n; ++xo)
+#pragma unroll
+            for (int x = 0; x < NX; ++x) {
+                const int xi = X0 + x;
+                if ((E2F_AXIS_NZ[mu][xo] >> xi) & 1u) po[xo] += P.G[(mu * E2F_MAX_N + xo) * E2F_MAX_N + xi] * acc[mu][x];
+            }
+    TICK(4)
+#ifdef E2F_TIMING
+    if (lane == 0 && P.dbg)
+        for (int k = 0; k < 6; ++k) atomicAdd(P.dbg + k, tacc[k]);
+#endif
+    z += __shfl_xor(z, 16);
+    z += __shfl_xor(z, 32);
+#pragma unroll
+    for (int r = 0; r < 4; ++r) z_rows[r] = __shfl(z, 4 * g + r);
+}
+
+template <int L, int NCW>
+__global__ __launch_bounds__(64 * NCW) __attribute__((amdgpu_waves_per_eu(1, 1))) void k_tile(TileParams P) {
+    constexpr int n = (L + 1) * (L + 1), NCP = (n + 1) / 2, HALF = (NCP + 1) / 2;
+    __shared__ int s_ent[NCW][CAPG + 8];
+    __shared__ float4 s_pos[NCW][(CAPG + 8) * 4];
+    __shared__ f32x4 s_po[NCW > 1 ? n * 64 : 1];
+    int tile, head;
+    if (!tile_xcd_remap(blockIdx.x, P.n_tiles, P.H, tile, head)) return;   // whole workgroup
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, ch = lane & 15, g = lane >> 4;
+    f32x4 po[n], z_rows;
+    if constexpr (NCW == 1) {
+        tile_wave<L, 0, NCP>(P, tile, head, s_ent[0], s_pos[0], po, z_rows);
+    } else {
+        if (wave == 0)
+            tile_wave<L, 0, HALF>(P, tile, head, s_ent[0], s_pos[0], po, z_rows);
+        else
+            tile_wave<L, HALF, NCP>(P, tile, head, s_ent[1], s_pos[1], po, z_rows);
+        if (wave == 1) {
+#pragma unroll
+            for (int xo = 0; xo < n; ++xo) s_po[xo * 64 + lane] = po[xo];
+        }
+        __syncthreads();
+        if (wave == 1) return;
+#pragma unroll
+        for (int xo = 0; xo < n; ++xo) po[xo] += s_po[xo * 64 + lane];
+    }
+    const int t0 = tile * 16;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const int t = t0 + 4 * g + r;
+        if (t < P.cv.N) {
+            const float inv = z_rows[r] > 0.0f ? 1.0f / z_rows[r] : 0.0f;
+            float* o = P.out + (size_t)P.cv.perm[t] * n * P.C + head * 16 + ch;
+#pragma unroll
+            for (int xo = 0; xo < n; ++xo) o[xo * P.C] = po[xo][r] * inv;
+        }
+    }
+}
+
+template <int L>
+void launch_L(const TileParams& P, const float* cw, float* G, hipStream_t st) {
+    k_axis_ops<L><<<1, 128, 0, st>>>(cw, G);
+    constexpr int n = (L + 1) * (L + 1);
+    const int chunks = (P.n_tiles + TILE_BLK - 1) / TILE_BLK;
+    const int grid = ((chunks + 7) / 8) * 8 * TILE_BLK * P.H;
+    if constexpr (n >= 9)
+        k_tile<L, 2><<<grid, 128, 0, st>>>(P);
+    else
+        k_tile<L, 1><<<grid, 64, 0, st>>>(P);
+}
+
+}  // namespace
+
+bool e2f_tile_supported(const e2f_ctx* ctx) {
+    const int C = ctx->cfg.C;
+    return ctx->cfg.feat_dtype == E2F_BF16 && ctx->cfg.lf == 1 && ctx->Ch == 16 && ctx->cfg.L_max >= 1 &&
+           ctx->cfg.B <= 8 && (C == 32 || C == 64 || C == 128);
+}
+
+e2f_status e2f_launch_tile(const e2f_ctx* ctx, const E2fCellsView& cv, const E2fAttnWs& ws, float* out, hipStream_t st) {
+    if (cv.N == 0) return E2F_OK;
+    TileParams P;
+    P.cv = cv;
+    P.spos = ws.spos; P.q16 = ws.q16; P.k16 = ws.k16; P.v4 = ws.v4; P.G = ws.G; P.WbT = ws.wbT;
+    P.out = out;
+    P.C = ctx->cfg.C; P.H = ctx->cfg.H; P.B = ctx->cfg.B; P.n_tiles = (cv.N + 15) / 16;
+    P.rc2 = ctx->rc2; P.cutoff = ctx->cfg.cutoff; P.rbf_step = ctx->rbf_step; P.rbf_gamma = ctx->rbf_gamma;
+#ifdef E2F_TIMING
+    static unsigned long long* dbg = nullptr;
+    if (!dbg) { (void)hipMalloc((void**)&dbg, 64); (void)hipMemset(dbg, 0, 64); }
+    P.dbg = dbg;
+    { unsigned long long hst[8]; (void)hipMemcpy(hst, dbg, 64, hipMemcpyDeviceToHost); if (getenv("E2F_TIMING_PRINT")) fprintf(stderr, "sections(cum) setup %llu list %llu prologue %llu loop %llu epilogue %llu chunks %llu batches %llu\n", hst[0], hst[1], hst[2], hst[3], hst[4], hst[6], hst[7]); }
+#endif
+    switch (ctx->cfg.L_max) {
+        case 1: launch_L<1>(P, ws.cw, ws.G, st); break;
+        case 2: launch_L<2>(P, ws.cw, ws.G, st); break;
+        case 3: launch_L<3>(P, ws.cw, ws.G, st); break;
+        case 4: launch_L<4>(P, ws.cw, ws.G, st); break;
+        default: return E2F_ERR_UNSUPPORTED;
+    }
+    E2F_HIP_CHECK(hipGetLastError());
+    return E2F_OK;
+}

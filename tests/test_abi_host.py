@@ -4,6 +4,8 @@ import ctypes
 import os
 import re
 
+import numpy as np
+
 import pytest
 
 from paper_2601_16622_amd import binding as B
@@ -110,6 +112,28 @@ def test_factorized_entry_point_sizes_and_limits(lib):
             assert lib.e2f_attn_forward_factorized(ctx, None, None, None, None, 0, 0, ctypes.byref(w), None, None, 0, None) == 2
         finally:
             B.e2f_destroy(ctx)
+
+
+def test_axis_operator_pattern_matches_the_dense_definition():
+    """The compile-time sparsity pattern of the three axis operators G_mu = (.) (x) R^(1)(e_mu) used by the tile kernel
+    is exactly the non-zero pattern of the oracle's dense Clebsch-Gordan message for r = e_mu (216 entries, L_max = 4)."""
+    import re
+    import oracle as O
+    txt = open(os.path.join(ROOT, "paper_2601_16622_amd", "csrc", "e2f_axis_pattern.h")).read()
+    rows = re.findall(r"\{((?:0x[0-9a-f]+u,? ?)+)\}", txt)
+    mask = [[int(x.strip().rstrip("u"), 16) for x in r.split(",")] for r in rows]
+    assert len(mask) == 3 and all(len(r) == 25 for r in mask)
+    w = np.random.default_rng(0).uniform(0.5, 1.5, (5, 5))
+    total = 0
+    for mu in range(3):
+        for xi in range(25):
+            v = np.zeros((25, 1))
+            v[xi] = 1.0
+            col = np.asarray(O.message(4, 1, w, v, np.eye(3)[mu], mode="dense")).reshape(25)
+            for xo in range(25):
+                assert bool((mask[mu][xo] >> xi) & 1) == bool(abs(col[xo]) > 1e-12), (mu, xo, xi)
+                total += (mask[mu][xo] >> xi) & 1
+    assert total == 216
 
 
 def test_product_package_does_not_import_the_oracle():

@@ -128,6 +128,24 @@ def test_other_shapes_and_degenerate_inputs(torch_cuda, kw):
     run_case(torch_cuda, _custom(5, **kw))
 
 
+@pytest.mark.parametrize("name", ["large", "scaling", "odd"])
+def test_tile_kernel_matches_the_oracle(torch_cuda, name, monkeypatch):
+    """The tile form of the attention stage (16 targets x 32 candidates on the matrix cores, linear factorization of the
+    degree-1 filter), selected through the environment; multi-segment tiles, partial last tile, L_max < 4."""
+    from paper_2601_16622_amd import workloads as W
+    monkeypatch.setenv("E2F_ATTENTION", "tile")
+    if name == "large":
+        wl = W.by_name("large", 0)
+        tg = np.random.default_rng(1).choice(wl["pos"].shape[0], 300, replace=False).astype(np.int32)
+    elif name == "scaling":
+        wl = W.scaling_point(0)
+        tg = np.random.default_rng(2).choice(10_000, 200, replace=False).astype(np.int32)
+    else:
+        wl = _custom(5, 333, 2, 64, 4, 5, 1, "bf16", cutoff=3.5, side=9.0, seg=[0, 7, 8, 150, 333])
+        tg = None
+    run_case(torch_cuda, wl, tg, check_materialized=False, message_mode="eaas")
+
+
 def test_isolated_atoms_and_crowded_cells(torch_cuda):
     """Atoms with no neighbour give zeros; a target with more neighbours than one LDS list holds still matches."""
     from paper_2601_16622_amd import workloads as W
