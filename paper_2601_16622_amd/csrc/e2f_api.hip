@@ -179,12 +179,11 @@ e2f_status e2f_create(const e2f_config* cfg, e2f_ctx** ctx_out) {
                 c->coefP[comp][kk] = (float)((kk % 2) ? (m > 0 ? cg : (m < 0 ? -cg : 0.0)) : cg);
             }
         }
-    // Attention kernel: the per-pair matrix-core kernel where it applies, else the ALU kernel.  E2F_ATTENTION in the
-    // environment overrides the choice (for A/B timing): "valu" keeps the stage off the matrix cores, "tile" selects
-    // the tile kernel where that one applies.
+    // Attention kernel: the tile kernel where it applies, else the per-pair matrix-core kernel, else the ALU kernel.
+    // E2F_ATTENTION=valu | pair | tile in the environment narrows the choice (for A/B timing).
     const char* pick = getenv("E2F_ATTENTION");
-    const bool only_valu = pick && strcmp(pick, "valu") == 0, want_tile = pick && strcmp(pick, "tile") == 0;
-    c->use_tile_attn = want_tile && e2f_tile_supported(c);
+    const bool only_valu = pick && strcmp(pick, "valu") == 0, only_pair = pick && strcmp(pick, "pair") == 0;
+    c->use_tile_attn = e2f_tile_supported(c) && !only_valu && !only_pair;
     c->use_mfma_attn = !c->use_tile_attn && e2f_fused_mfma_supported(c) && !only_valu;
     c->prof_events = nullptr;
     c->prof_capacity = 0;

@@ -110,14 +110,56 @@ __global__ void k_axis_ops(const float* __restrict__ cw, float* __restrict__ G) 
     for (int xo = 0; xo < n; ++xo) G[(mu * E2F_MAX_N + xo) * E2F_MAX_N + xi] = acc[xo][0];
 }
 
-// One wave: component pairs [CP0, CP1) of one (tile, head).  po[x_out] receives this wave's share of
-// sum_mu G_mu T_mu (rows = targets 4g..4g+3, column = channel lane%16), z_rows the softmax sums of those targets.
-template <int L, int CP0, int CP1>
-__device__ __forceinline__ void tile_wave(const TileParams& P, int tile, int head, int* s_ent, float4* s_pos,
-                                          f32x4 (&po)[(L + 1) * (L + 1)], f32x4& z_rows) {
-    constexpr int n = (L + 1) * (L + 1), X0 = 2 * CP0, NX = (2 * CP1 < n ? 2 * CP1 : n) - X0;   // this wave's components
+// Epilogue share of one wave: po[x_out] = sum_mu sum_{x_in in [X0, X0 + NX)} G_mu[x_out][x_in] T_mu[x_in], non-zero
+// entries of the axis operators only (rows = targets 4g..4g+3, column = channel lane%16).
+// acc[mu][x] holds component XBASE + x; components below XFIRST belong to another wave and are skipped.
+template <int L, int XBASE, int XFIRST, int NX>
+__device__ __forceinline__ void axis_epilogue(const float* __restrict__ G, const f32x4 (&acc)[3][NX],
+                                              f32x4 (&po)[(L + 1) * (L + 1)]) {
+    constexpr int n = (L + 1) * (L + 1);
+#pragma unroll
+    for (int mu = 0; mu < 3; ++mu)
+#pragma unroll
+        for (int xo = 0; xo < n; ++xo)
+#pragma unroll
+            for (int x = 0; x < NX; ++x) {
+                const int xi = XBASE + x;
+                if (xi >= XFIRST && xi < n && ((E2F_AXIS_NZ[mu][xo] >> xi) & 1u))
+                    po[xo] += G[(mu * E2F_MAX_N + xo) * E2F_MAX_N + xi] * acc[mu][x];
+            }
+}
+
+// One workgroup of four waves per (tile of 16 targets, head).  The waves share the candidate list and the softmax
+// weights through LDS and split the rest:
+//   list      each wave scans a quarter of the stencil's slot groups; the kept groups are packed in order
+//   weights   chunks of 32 candidates are taken four at a time; wave w computes the logits (matrix cores), the pair
+//             geometry and the weights W_mu of chunk 4G + w and publishes them (3 KB per chunk)
+//   aggregate every wave applies all four chunks' W_mu to its own quarter of the components, T_mu += W_mu V
+// The softmax reference of a target is common to the four waves: it is set by the target's first neighbours and
+// moved (with a rescale of the accumulator rows) only when a later logit exceeds it by M_STEP.
+template <int L>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void k_tile(TileParams P) {
+    constexpr int n = (L + 1) * (L + 1), NX = (n + 3) / 4;
     constexpr int DK = (L + 1) * 16, KS = (DK + 31) / 32, DKP = KS * 32;
-    const int lane = threadIdx.x & 63, tn = lane & 15, g = lane >> 4;
+    // LDS: the list and the weights while streaming; the same bytes hold the partial outputs at the end
+    constexpr int LIST_BYTES = (CAPG + 32) * 4 + (CAPG + 32) * 4 * 16, W_BYTES = 4 * 3 * 64 * 16;
+    constexpr int PO_BYTES = n * 64 * 16;
+    constexpr int MAIN_BYTES = LIST_BYTES + W_BYTES > PO_BYTES ? LIST_BYTES + W_BYTES : PO_BYTES;
+    __shared__ __attribute__((aligned(16))) unsigned char s_raw[MAIN_BYTES];
+    __shared__ float s_cmax[4][16];
+    __shared__ float s_z[4][16];
+    __shared__ int s_cnt[4];
+    int* s_ent = reinterpret_cast<int*>(s_raw);
+    float4* s_pos = reinterpret_cast<float4*>(s_raw + (CAPG + 32) * 4);
+    u32x4* s_W = reinterpret_cast<u32x4*>(s_raw + LIST_BYTES);   // [chunk of the group][mu][lane]
+    f32x4* s_po = reinterpret_cast<f32x4*>(s_raw);
+
+    int tile, head;
+    if (!tile_xcd_remap(blockIdx.x, P.n_tiles, P.H, tile, head)) return;   // whole workgroup
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, tn = lane & 15, g = lane >> 4;
+    // first component of this wave; the last wave is shifted back so that all hold NX real components (it repeats
+    // a few of its neighbour's and leaves them out of the epilogue)
+    const int x0 = min(wave * NX, n - NX);
 #ifdef E2F_TIMING
     unsigned long long tacc[6] = {0, 0, 0, 0, 0, 0};
     unsigned long long tprev = __builtin_amdgcn_s_memtime();
@@ -176,7 +218,7 @@ __device__ __forceinline__ void tile_wave(const TileParams& P, int tile, int hea
         {
             const E2fSegGrid G = P.cv.grid[seg_a];
             const int cy = row_a % G.ny, cz = row_a / G.ny;
-            const int x0 = max(cxa - 1, 0), x1 = min(cxb + 1, G.nx - 1);
+            const int xa = max(cxa - 1, 0), xb = min(cxb + 1, G.nx - 1);
             pre[0] = 0;
 #pragma unroll
             for (int r = 0; r < 9; ++r) {
@@ -186,8 +228,8 @@ __device__ __forceinline__ void tile_wave(const TileParams& P, int tile, int hea
                     hi[r] = 0;
                 } else {
                     const int row = G.base + (zc * G.ny + y) * G.nx;
-                    lo[r] = P.cv.cell_start[row + x0];
-                    hi[r] = P.cv.cell_start[row + x1 + 1];
+                    lo[r] = P.cv.cell_start[row + xa];
+                    hi[r] = P.cv.cell_start[row + xb + 1];
                 }
                 pre[r + 1] = pre[r] + (hi[r] > lo[r] ? ((hi[r] + 3) >> 2) - (lo[r] >> 2) : 0);
             }
@@ -206,20 +248,20 @@ __device__ __forceinline__ void tile_wave(const TileParams& P, int tile, int hea
         const float prune2 = P.rc2 * 1.001f;
 
         const int total = pre[9];
-        int fbase = 0;
-        while (fbase < total) {
-            // ---- a batch of the candidate list: entries (group << 4 | valid slots) and the slots' positions in LDS
-            int cnt = 0;
-            while (fbase < total && cnt + 64 <= CAPG) {
-                // four steps of 16 groups: all positions are requested before the first is looked at
+        for (int fbase = 0; fbase < total; fbase += 256) {
+            // ---- a batch of the candidate list: 256 slot groups, 64 per wave, kept groups packed in order into
+            // entries (group << 4 | valid slots) with the slots' positions beside them
+            int grp[4];
+            unsigned near4[4], valid4[4];
+            unsigned long long leaders[4];
+            float4 pj[4];
+            {
                 int ln = lane;
                 asm volatile("" : "+v"(ln));   // keeps (lane - pre[r]) from being hoisted out of the loop
-                int grp[4];
                 bool valid[4];
-                float4 pj[4];
 #pragma unroll
                 for (int u = 0; u < 4; ++u) {
-                    const int fg = fbase + 16 * u + (ln >> 2);
+                    const int fg = fbase + 64 * wave + 16 * u + (ln >> 2);
                     int gq = -1, rlo = 0, rhi = 0;
 #pragma unroll
                     for (int r = 0; r < 9; ++r)
@@ -233,6 +275,7 @@ __device__ __forceinline__ void tile_wave(const TileParams& P, int tile, int hea
                     valid[u] = gq >= 0 && slot >= rlo && slot < rhi;
                     pj[u] = P.spos[valid[u] ? slot : tslot];
                 }
+                int mine = 0;
 #pragma unroll
                 for (int u = 0; u < 4; ++u) {
                     const float ex = fmaxf(fmaxf(bx0 - pj[u].x, pj[u].x - bx1), 0.0f);
@@ -240,238 +283,222 @@ __device__ __forceinline__ void tile_wave(const TileParams& P, int tile, int hea
                     const float ez = fmaxf(fmaxf(bz0 - pj[u].z, pj[u].z - bz1), 0.0f);
                     const bool near = valid[u] && (ex * ex + ey * ey + ez * ez) < prune2;
                     const int sh = lane & ~3;
-                    const unsigned near4 = (unsigned)(__ballot(near) >> sh) & 0xFu;
-                    const unsigned valid4 = (unsigned)(__ballot(valid[u]) >> sh) & 0xFu;
-                    const unsigned long long leaders = __ballot(near4 != 0u && (lane & 3) == 0);
-                    const int e = cnt + __popcll(leaders & ((1ull << sh) - 1ull));
-                    if (near4 != 0u) {
-                        if ((lane & 3) == 0) s_ent[e] = (grp[u] << 4) | (int)valid4;
-                        s_pos[e * 4 + (lane & 3)] = pj[u];
-                    }
-                    cnt += __popcll(leaders);
+                    near4[u] = (unsigned)(__ballot(near) >> sh) & 0xFu;
+                    valid4[u] = (unsigned)(__ballot(valid[u]) >> sh) & 0xFu;
+                    leaders[u] = __ballot(near4[u] != 0u && (lane & 3) == 0);
+                    mine += __popcll(leaders[u]);
                 }
-                fbase += 64;
+                if (lane == 0) s_cnt[wave] = mine;
             }
-            if (lane < 8) s_ent[cnt + lane] = 0;   // pads the last chunk: group 0, no valid slot,
-            if (lane < 32) s_pos[cnt * 4 + lane] = tp; // finite positions (their weights are forced to zero)
-            wave_lds_sync();
+            __syncthreads();   // every wave has finished with the previous list
+            int cnt = 0, e0 = 0;
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+                const int cw_ = s_cnt[w];
+                e0 += w < wave ? cw_ : 0;
+                cnt += cw_;
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int sh = lane & ~3;
+                const int e = e0 + __popcll(leaders[u] & ((1ull << sh) - 1ull));
+                if (near4[u] != 0u) {
+                    if ((lane & 3) == 0) s_ent[e] = (grp[u] << 4) | (int)valid4[u];
+                    s_pos[e * 4 + (lane & 3)] = pj[u];
+                }
+                e0 += __popcll(leaders[u]);
+            }
+            // pad to whole groups of four chunks: entries of group 0 with no valid slot, finite positions
+            if (wave == 0 && lane < 32) s_ent[cnt + lane] = 0;
+            if (wave == 1) {
+                s_pos[cnt * 4 + lane] = tp;
+                s_pos[cnt * 4 + 64 + lane] = tp;
+            }
+            __syncthreads();
             TICK(1)
-            const int nch = (cnt + 7) >> 3;
+            const int nch = (cnt + 7) >> 3, ngr = (nch + 3) >> 2;
 #ifdef E2F_TIMING
-            if (lane == 0 && P.dbg) { atomicAdd(P.dbg + 6, (unsigned long long)nch); atomicAdd(P.dbg + 7, 1ull); }
+            if (threadIdx.x == 0 && P.dbg) { atomicAdd(P.dbg + 6, (unsigned long long)nch); atomicAdd(P.dbg + 7, 1ull); }
 #endif
-            if (nch > 0) {
-
-            auto load_K = [&](int c, f16x8 (&kf)[2][KS]) {
+            if (ngr > 0) {
+                auto load_K = [&](int c, f16x8 (&kf)[2][KS]) {
 #pragma unroll
-                for (int mt = 0; mt < 2; ++mt) {
-                    const int e = s_ent[8 * c + 4 * mt + (tn >> 2)];
-                    const size_t off = ((size_t)(4 * (e >> 4) + (tn & 3)) * H + head) * DKP + 8 * g;
+                    for (int mt = 0; mt < 2; ++mt) {
+                        const int e = s_ent[8 * c + 4 * mt + (tn >> 2)];
+                        const size_t off = ((size_t)(4 * (e >> 4) + (tn & 3)) * H + head) * DKP + 8 * g;
 #pragma unroll
-                    for (int ks = 0; ks < KS; ++ks) kf[mt][ks] = *reinterpret_cast<const f16x8*>(P.k16 + off + 32 * ks);
-                }
-            };
-            auto logits = [&](const f16x8 (&kf)[2][KS], f32x4 (&S)[2]) {
+                        for (int ks = 0; ks < KS; ++ks) kf[mt][ks] = *reinterpret_cast<const f16x8*>(P.k16 + off + 32 * ks);
+                    }
+                };
+                // v rows of this wave's component x for the lane's two entries: k = 8g..8g+3 from entry g of the
+                // chunk, 8g+4..8g+7 from entry 4+g
+                auto load_V = [&](int c, int x, u32x2& va, u32x2& vb) {
+                    const int ea = s_ent[8 * c + g] >> 4, eb = s_ent[8 * c + 4 + g] >> 4;
+                    va = *reinterpret_cast<const u32x2*>(P.v4 + (((size_t)ea * H + head) * n + x0) * 64 + tn * 4 + x * 64);
+                    vb = *reinterpret_cast<const u32x2*>(P.v4 + (((size_t)eb * H + head) * n + x0) * 64 + tn * 4 + x * 64);
+                };
+                f16x8 kf[2][KS];
+                u32x2 va[NX], vb[NX];
+                load_K(min(wave, nch - 1), kf);
 #pragma unroll
-                for (int mt = 0; mt < 2; ++mt) {
-                    S[mt] = (f32x4){0.f, 0.f, 0.f, 0.f};
+                for (int x = 0; x < NX; ++x) load_V(0, x, va[x], vb[x]);
+                TICK(2)
+                for (int G = 0; G < ngr; ++G) {
+                    // ---- logits, pair geometry and cutoff mask of this wave's chunk
+                    const int cm = 4 * G + wave;
+                    f32x4 S[2];
 #pragma unroll
-                    for (int ks = 0; ks < KS; ++ks) S[mt] = mfma(kf[mt][ks], qf[ks], S[mt]);
-                }
-            };
-            // v rows of component X0 + x for the lane's two entries: k = 8g..8g+3 from entry g, 8g+4..8g+7 from entry 4+g
-            auto load_V = [&](int c, int x, u32x2& va, u32x2& vb) {
-                const int ea = s_ent[8 * c + g] >> 4, eb = s_ent[8 * c + 4 + g] >> 4;
-                va = *reinterpret_cast<const u32x2*>(P.v4 + (((size_t)ea * H + head) * n + X0 + x) * 64 + tn * 4);
-                vb = *reinterpret_cast<const u32x2*>(P.v4 + (((size_t)eb * H + head) * n + X0 + x) * 64 + tn * 4);
-            };
-            // Softmax weights of a chunk for this lane's target and its eight candidates, in two steps so that the
-            // (rare) move of the softmax reference sits outside the streaming loop: the loop's accumulators are then
-            // touched by matrix instructions only and stay in the accumulator register file.
-            struct Scores {
-                float s2[8], gate[8], rx[8], ry[8], rz[8], cmax;
-            };
-            auto scores = [&](int c, const f32x4 (&S)[2], Scores& sc) {
-                float cmax = -INFINITY;
+                    for (int mt = 0; mt < 2; ++mt) {
+                        S[mt] = (f32x4){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                for (int mt = 0; mt < 2; ++mt) {
-                    const int ei = 8 * c + 4 * mt + g;
-                    const int e = s_ent[ei];
+                        for (int ks = 0; ks < KS; ++ks) S[mt] = mfma(kf[mt][ks], qf[ks], S[mt]);
+                    }
+                    load_K(min(cm + 4, nch - 1), kf);
+                    float s2[8], gate[8];
+                    float cmax = -INFINITY;
 #pragma unroll
-                    for (int r = 0; r < 4; ++r) {
-                        const int u = 4 * mt + r;
-                        const float4 pj = s_pos[ei * 4 + r];
-                        const float d2 = e2f::dist2_exact(tp.x, tp.y, tp.z, pj.x, pj.y, pj.z);
-                        // (bitwise on purpose: the eight candidates are evaluated side by side, not branch by branch)
-                        const bool ok = (((e >> r) & 1) != 0) & t_active & ((4 * (e >> 4) + r) != t0 + tn) &
-                                        (d2 < P.rc2) & (d2 > 0.0f);
-                        const float d = __builtin_amdgcn_sqrtf(d2);
-                        const float uu = __builtin_amdgcn_exp2f(c_u * d);
-                        float poly = cb[7];
+                    for (int mt = 0; mt < 2; ++mt) {
+                        const int ei = 8 * cm + 4 * mt + g;
+                        const int e = s_ent[ei];
 #pragma unroll
-                        for (int bb = 6; bb >= 0; --bb) poly = poly * uu + cb[bb];
-                        const float bias = __builtin_amdgcn_exp2f(c_g * d2) * poly;
-                        sc.s2[u] = ok ? S[mt][r] + bias : -INFINITY;
-                        sc.gate[u] = e2f::radial_gate(d, P.cutoff);
-                        sc.rx[u] = pj.x - tp.x;
-                        sc.ry[u] = pj.y - tp.y;
-                        sc.rz[u] = pj.z - tp.z;
-                        cmax = fmaxf(cmax, sc.s2[u]);
+                        for (int r = 0; r < 4; ++r) {
+                            const int u = 4 * mt + r;
+                            const float4 pc = s_pos[ei * 4 + r];
+                            const float d2 = e2f::dist2_exact(tp.x, tp.y, tp.z, pc.x, pc.y, pc.z);
+                            // (bitwise on purpose: the eight candidates are evaluated side by side)
+                            const bool ok = (((e >> r) & 1) != 0) & t_active & ((4 * (e >> 4) + r) != t0 + tn) &
+                                            (d2 < P.rc2) & (d2 > 0.0f);
+                            const float d = __builtin_amdgcn_sqrtf(d2);
+                            const float uu = __builtin_amdgcn_exp2f(c_u * d);
+                            float poly = cb[7];
+#pragma unroll
+                            for (int bb = 6; bb >= 0; --bb) poly = poly * uu + cb[bb];
+                            const float bias = __builtin_amdgcn_exp2f(c_g * d2) * poly;
+                            s2[u] = ok ? S[mt][r] + bias : -INFINITY;
+                            gate[u] = e2f::radial_gate(d, P.cutoff);
+                            cmax = fmaxf(cmax, s2[u]);
+                        }
+                    }
+                    cmax = fmaxf(cmax, __shfl_xor(cmax, 16));
+                    cmax = fmaxf(cmax, __shfl_xor(cmax, 32));
+                    if (lane < 16) s_cmax[wave][lane] = cmax;
+                    __syncthreads();
+                    // ---- the group's largest logit per target, the same in all four waves
+                    const float gmax = fmaxf(fmaxf(s_cmax[0][tn], s_cmax[1][tn]), fmaxf(s_cmax[2][tn], s_cmax[3][tn]));
+                    if (m_ref == -INFINITY) m_ref = gmax;   // first neighbours: the accumulator rows are still zero
+                    const bool move = gmax > m_ref + M_STEP;
+                    if (__builtin_expect(__ballot(move) != 0ull, 0)) {
+                        const float f = move ? __builtin_amdgcn_exp2f(m_ref - gmax) : 1.0f;
+                        m_ref = move ? gmax : m_ref;
+                        z *= f;
+                        // Rows of the accumulators are targets: T <- diag(f) T on the matrix cores in fp32.  Slice r
+                        // pairs A_r[i][g] = f_i [i == 4g + r] with B_r[g][j] = T[4g + r][j], register r of lane (j, g).
+                        float ar[4];
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) ar[r] = tn == 4 * g + r ? f : 0.0f;
+#pragma unroll
+                        for (int mu = 0; mu < 3; ++mu)
+#pragma unroll
+                            for (int x = 0; x < NX; ++x) {
+                                f32x4 d = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                                for (int r = 0; r < 4; ++r)
+                                    d = __builtin_amdgcn_mfma_f32_16x16x4f32(ar[r], acc[mu][x][r], d, 0, 0, 0);
+                                acc[mu][x] = d;
+                            }
+                    }
+                    // ---- weights of this wave's chunk -> LDS
+                    {
+                        uint32_t wp[3][4];
+#pragma unroll
+                        for (int u = 0; u < 8; u += 2) {
+                            float pg[2], rx[2], ry[2], rz[2];
+#pragma unroll
+                            for (int d = 0; d < 2; ++d) {
+                                const float p = s2[u + d] > -INFINITY ? __builtin_amdgcn_exp2f(s2[u + d] - m_ref) : 0.0f;
+                                z += p;
+                                pg[d] = p * gate[u + d];
+                                const float4 pc = s_pos[(8 * cm + 4 * ((u + d) >> 2) + g) * 4 + ((u + d) & 3)];
+                                rx[d] = pc.x - tp.x;
+                                ry[d] = pc.y - tp.y;
+                                rz[d] = pc.z - tp.z;
+                            }
+                            wp[0][u >> 1] = pack_bf16(pg[0] * rx[0], pg[1] * rx[1]);
+                            wp[1][u >> 1] = pack_bf16(pg[0] * ry[0], pg[1] * ry[1]);
+                            wp[2][u >> 1] = pack_bf16(pg[0] * rz[0], pg[1] * rz[1]);
+                        }
+#pragma unroll
+                        for (int mu = 0; mu < 3; ++mu)
+                            s_W[(wave * 3 + mu) * 64 + lane] = (u32x4){wp[mu][0], wp[mu][1], wp[mu][2], wp[mu][3]};
+                    }
+                    __syncthreads();
+                    // ---- aggregate the four chunks of the group into this wave's components
+#pragma unroll
+                    for (int cc = 0; cc < 4; ++cc) {
+                        const int c = 4 * G + cc;
+                        if (c < nch) {
+                            bf16x8 W[3];
+#pragma unroll
+                            for (int mu = 0; mu < 3; ++mu) W[mu] = __builtin_bit_cast(bf16x8, s_W[(cc * 3 + mu) * 64 + lane]);
+                            const int cnext = min(c + 1, nch - 1);
+#pragma unroll
+                            for (int x = 0; x < NX; ++x) {
+                                const bf16x8 bv = __builtin_bit_cast(bf16x8, __builtin_shufflevector(va[x], vb[x], 0, 1, 2, 3));
+#pragma unroll
+                                for (int mu = 0; mu < 3; ++mu) acc[mu][x] = mfma(W[mu], bv, acc[mu][x]);
+                                load_V(cnext, x, va[x], vb[x]);
+                            }
+                        }
                     }
                 }
-                cmax = fmaxf(cmax, __shfl_xor(cmax, 16));
-                sc.cmax = fmaxf(cmax, __shfl_xor(cmax, 32));
-                // A target's first neighbours set its reference; its accumulator rows are still zero then.
-                if (m_ref == -INFINITY) m_ref = sc.cmax;
-                // Later the reference moves only for a logit well above it, and the rows have to be rescaled.
-                return __ballot(sc.cmax > m_ref + M_STEP) != 0ull;
-            };
-            auto move_reference = [&](const Scores& sc) {
-                const bool move = sc.cmax > m_ref + M_STEP;
-                const float m_new = move ? sc.cmax : m_ref;
-                const float f = move ? __builtin_amdgcn_exp2f(m_ref - m_new) : 1.0f;   // m_ref is finite when move holds
-                z *= f;
-                m_ref = m_new;
-                // Rows of the accumulators are targets: T <- diag(f) T on the matrix cores in fp32.  Slice r of the
-                // product pairs A_r[i][g] = f_i [i == 4g + r] with B_r[g][j] = T[4g + r][j], register r of lane (j, g).
-                float ar[4];
-#pragma unroll
-                for (int r = 0; r < 4; ++r) ar[r] = tn == 4 * g + r ? f : 0.0f;
-#pragma unroll
-                for (int mu = 0; mu < 3; ++mu)
-#pragma unroll
-                    for (int x = 0; x < NX; ++x) {
-                        f32x4 d = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                        for (int r = 0; r < 4; ++r) d = __builtin_amdgcn_mfma_f32_16x16x4f32(ar[r], acc[mu][x][r], d, 0, 0, 0);
-                        acc[mu][x] = d;
-                    }
-            };
-            auto finish = [&](const Scores& sc, bf16x8 (&W)[3]) {
-                uint32_t wp[3][4];
-#pragma unroll
-                for (int u = 0; u < 8; u += 2) {
-                    float pg[2];
-#pragma unroll
-                    for (int d = 0; d < 2; ++d) {
-                        const float p = sc.s2[u + d] > -INFINITY ? __builtin_amdgcn_exp2f(sc.s2[u + d] - m_ref) : 0.0f;
-                        z += p;
-                        pg[d] = p * sc.gate[u + d];
-                    }
-                    wp[0][u >> 1] = pack_bf16(pg[0] * sc.rx[u], pg[1] * sc.rx[u + 1]);
-                    wp[1][u >> 1] = pack_bf16(pg[0] * sc.ry[u], pg[1] * sc.ry[u + 1]);
-                    wp[2][u >> 1] = pack_bf16(pg[0] * sc.rz[u], pg[1] * sc.rz[u + 1]);
-                }
-#pragma unroll
-                for (int mu = 0; mu < 3; ++mu)
-                    W[mu] = __builtin_bit_cast(bf16x8, (u32x4){wp[mu][0], wp[mu][1], wp[mu][2], wp[mu][3]});
-            };
-
-            // ---- chunks of 8 entries (32 candidates), software pipelined: while chunk c is aggregated, the logits
-            // and weights of chunk c+1 are computed and the k rows of chunk c+2 and the v rows of chunk c+1 are in flight
-            f16x8 kf[2][KS];
-            u32x2 va[NX], vb[NX];
-            f32x4 S[2];
-            bf16x8 W[3];
-            Scores sc;
-            load_K(0, kf);
-#pragma unroll
-            for (int x = 0; x < NX; ++x) load_V(0, x, va[x], vb[x]);
-            logits(kf, S);
-            load_K(min(1, nch - 1), kf);
-            if (scores(0, S, sc)) move_reference(sc);
-            finish(sc, W);
-            TICK(2)
-            int c = 0;
-            while (true) {
-                bool pending = false;
-                while (c < nch) {   // the streaming loop
-                    const int c1 = min(c + 1, nch - 1), c2 = min(c + 2, nch - 1);
-                    logits(kf, S);   // of chunk c1
-                    load_K(c2, kf);
-#pragma unroll
-                    for (int x = 0; x < NX; ++x) {
-                        const bf16x8 bv = __builtin_bit_cast(bf16x8, __builtin_shufflevector(va[x], vb[x], 0, 1, 2, 3));
-#pragma unroll
-                        for (int mu = 0; mu < 3; ++mu) acc[mu][x] = mfma(W[mu], bv, acc[mu][x]);
-                        load_V(c1, x, va[x], vb[x]);
-                    }
-                    ++c;
-                    if (c < nch) {
-                        pending = scores(c, S, sc);
-                        if (pending) break;
-                        finish(sc, W);
-                    }
-                }
-                if (!pending) break;
-                move_reference(sc);
-                finish(sc, W);
-            }
             }
             TICK(3)
-            wave_lds_sync();   // the list is rebuilt by the next batch
         }
         a = b;
     }
 
-    // ---- epilogue: this wave's share of sum_mu G_mu T_mu, non-zero entries only
+    // ---- epilogue: out = (1/z) sum_mu G_mu T_mu; the four waves' shares are added through LDS
+    f32x4 po[n];
 #pragma unroll
     for (int xo = 0; xo < n; ++xo) po[xo] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    switch (wave) {
+        case 0: axis_epilogue<L, 0, 0, NX>(P.G, acc, po); break;
+        case 1: axis_epilogue<L, (NX < n - NX ? NX : n - NX), NX, NX>(P.G, acc, po); break;
+        case 2: axis_epilogue<L, (2 * NX < n - NX ? 2 * NX : n - NX), 2 * NX, NX>(P.G, acc, po); break;
+        default: axis_epilogue<L, (3 * NX < n - NX ? 3 * NX : n - NX), 3 * NX, NX>(P.G, acc, po); break;
+    }
+    z += __shfl_xor(z, 16);
+    z += __shfl_xor(z, 32);
+    if (lane < 16) s_z[wave][lane] = z;
+    __syncthreads();   // the list and the weights are dead: their bytes take the partial outputs
+    for (int w = 1; w < 4; ++w) {
+        if (wave == w) {
 #pragma unroll
-    for (int mu = 0; mu < 3; ++mu)
-#pragma unroll
-        for (int xo = 0; xo < n; ++xo)
-#pragma unroll
-            for (int x = 0; x < NX; ++x) {
-                const int xi = X0 + x;
-                if ((E2F_AXIS_NZ[mu][xo] >> xi) & 1u) po[xo] += P.G[(mu * E2F_MAX_N + xo) * E2F_MAX_N + xi] * acc[mu][x];
+            for (int xo = 0; xo < n; ++xo) {
+                if (w == 1)
+                    s_po[xo * 64 + lane] = po[xo];
+                else
+                    s_po[xo * 64 + lane] += po[xo];
             }
+        }
+        __syncthreads();
+    }
     TICK(4)
 #ifdef E2F_TIMING
     if (lane == 0 && P.dbg)
         for (int k = 0; k < 6; ++k) atomicAdd(P.dbg + k, tacc[k]);
 #endif
-    z += __shfl_xor(z, 16);
-    z += __shfl_xor(z, 32);
-#pragma unroll
-    for (int r = 0; r < 4; ++r) z_rows[r] = __shfl(z, 4 * g + r);
-}
-
-template <int L, int NCW>
-__global__ __launch_bounds__(64 * NCW) __attribute__((amdgpu_waves_per_eu(1, 1))) void k_tile(TileParams P) {
-    constexpr int n = (L + 1) * (L + 1), NCP = (n + 1) / 2, HALF = (NCP + 1) / 2;
-    __shared__ int s_ent[NCW][CAPG + 8];
-    __shared__ float4 s_pos[NCW][(CAPG + 8) * 4];
-    __shared__ f32x4 s_po[NCW > 1 ? n * 64 : 1];
-    int tile, head;
-    if (!tile_xcd_remap(blockIdx.x, P.n_tiles, P.H, tile, head)) return;   // whole workgroup
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, ch = lane & 15, g = lane >> 4;
-    f32x4 po[n], z_rows;
-    if constexpr (NCW == 1) {
-        tile_wave<L, 0, NCP>(P, tile, head, s_ent[0], s_pos[0], po, z_rows);
-    } else {
-        if (wave == 0)
-            tile_wave<L, 0, HALF>(P, tile, head, s_ent[0], s_pos[0], po, z_rows);
-        else
-            tile_wave<L, HALF, NCP>(P, tile, head, s_ent[1], s_pos[1], po, z_rows);
-        if (wave == 1) {
-#pragma unroll
-            for (int xo = 0; xo < n; ++xo) s_po[xo * 64 + lane] = po[xo];
-        }
-        __syncthreads();
-        if (wave == 1) return;
-#pragma unroll
-        for (int xo = 0; xo < n; ++xo) po[xo] += s_po[xo * 64 + lane];
-    }
-    const int t0 = tile * 16;
+    if (wave != 0) return;
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
         const int t = t0 + 4 * g + r;
-        if (t < P.cv.N) {
-            const float inv = z_rows[r] > 0.0f ? 1.0f / z_rows[r] : 0.0f;
-            float* o = P.out + (size_t)P.cv.perm[t] * n * P.C + head * 16 + ch;
+        if (t < N) {
+            const int tt = 4 * g + r;
+            const float zt = s_z[0][tt] + s_z[1][tt] + s_z[2][tt] + s_z[3][tt];
+            const float inv = zt > 0.0f ? 1.0f / zt : 0.0f;
+            float* o = P.out + (size_t)P.cv.perm[t] * n * P.C + head * 16 + tn;
 #pragma unroll
-            for (int xo = 0; xo < n; ++xo) o[xo * P.C] = po[xo][r] * inv;
+            for (int xo = 0; xo < n; ++xo) o[xo * P.C] = (po[xo][r] + s_po[xo * 64 + lane][r]) * inv;
         }
     }
 }
@@ -479,13 +506,9 @@ __global__ __launch_bounds__(64 * NCW) __attribute__((amdgpu_waves_per_eu(1, 1))
 template <int L>
 void launch_L(const TileParams& P, const float* cw, float* G, hipStream_t st) {
     k_axis_ops<L><<<1, 128, 0, st>>>(cw, G);
-    constexpr int n = (L + 1) * (L + 1);
     const int chunks = (P.n_tiles + TILE_BLK - 1) / TILE_BLK;
     const int grid = ((chunks + 7) / 8) * 8 * TILE_BLK * P.H;
-    if constexpr (n >= 9)
-        k_tile<L, 2><<<grid, 128, 0, st>>>(P);
-    else
-        k_tile<L, 1><<<grid, 64, 0, st>>>(P);
+    k_tile<L><<<grid, 256, 0, st>>>(P);
 }
 
 }  // namespace

@@ -52,8 +52,9 @@ def test_workspace_sizes_are_linear_in_N(lib):
     ctx = B.e2f_create(4, 128, 8, 8, 1, 6.0, "bf16")
     try:
         sizes = [B.e2f_attn_workspace_bytes(ctx, N) for N in (10_000, 20_000, 40_000)]
-        # per atom: sorted position 16 B, q and k fp32 (L+1)*C each, v bf16 in two 16x16 tiles per 16-channel head
-        per_atom = 16 + 2 * 5 * 128 * 4 + 8 * 2 * 256 * 2
+        # per atom (tile kernel): sorted position 16 B, q and k binary16 with 96 features per head (80 padded to a
+        # multiple of 32), v bf16 [25][128]
+        per_atom = 16 + 2 * 8 * 96 * 2 + 25 * 128 * 2
         assert abs((sizes[1] - sizes[0]) - 10_000 * per_atom) <= 2048
         assert abs((sizes[2] - sizes[1]) - 20_000 * per_atom) <= 2048
         c = [B.e2f_cells_workspace_bytes(ctx, N, 4) for N in (1000, 2000, 3000)]

@@ -128,12 +128,14 @@ def test_other_shapes_and_degenerate_inputs(torch_cuda, kw):
     run_case(torch_cuda, _custom(5, **kw))
 
 
+@pytest.mark.parametrize("kernel", ["tile", "pair", "valu"])
 @pytest.mark.parametrize("name", ["large", "scaling", "odd"])
-def test_tile_kernel_matches_the_oracle(torch_cuda, name, monkeypatch):
-    """The tile form of the attention stage (16 targets x 32 candidates on the matrix cores, linear factorization of the
-    degree-1 filter), selected through the environment; multi-segment tiles, partial last tile, L_max < 4."""
+def test_each_attention_kernel_matches_the_oracle(torch_cuda, name, kernel, monkeypatch):
+    """The three forms of the attention stage on the same bf16 inputs, selected through the environment: the tile form
+    (16 targets x 32 candidates on the matrix cores, linear factorization of the degree-1 filter; the default where it
+    applies), the per-pair matrix-core form and the ALU form; multi-segment tiles, partial last tile, L_max < 4."""
     from paper_2601_16622_amd import workloads as W
-    monkeypatch.setenv("E2F_ATTENTION", "tile")
+    monkeypatch.setenv("E2F_ATTENTION", kernel)
     if name == "large":
         wl = W.by_name("large", 0)
         tg = np.random.default_rng(1).choice(wl["pos"].shape[0], 300, replace=False).astype(np.int32)
