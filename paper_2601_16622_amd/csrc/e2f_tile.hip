@@ -36,7 +36,7 @@ typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 
 constexpr int CAPG = 256;      // candidate groups (of four slots) held in LDS per batch
 constexpr int TILE_BLK = 16;   // consecutive tiles whose (tile, head) items form one XCD chunk, head-major
-constexpr float M_STEP = 6.0f; // the softmax reference moves when a logit exceeds it by this much (base-2 units)
+constexpr float M_STEP = 20.0f; // the softmax reference moves when a logit exceeds it by this much (base-2 units)
 
 struct TileParams {
     E2fCellsView cv;
