@@ -52,6 +52,7 @@ size_t cells_ws_layout(int32_t N, int32_t S, void* ws, e2f_cells* c) {
     char* atom_cell = take((size_t)N * 4);
     char* cell_fill = take((size_t)max_cells * 4);
     char* tmp_slot = take((size_t)N * 4);
+    char* atom_sub = take((size_t)N * 4);
     if (c) {
         c->view.grid = (const E2fSegGrid*)grid;
         c->view.cell_start = (const int32_t*)cell_start;
@@ -66,6 +67,7 @@ size_t cells_ws_layout(int32_t N, int32_t S, void* ws, e2f_cells* c) {
         c->atom_cell = (int32_t*)atom_cell;
         c->cell_fill = (int32_t*)cell_fill;
         c->tmp_slot = (int32_t*)tmp_slot;
+        c->atom_sub = (int32_t*)atom_sub;
         c->max_cells = max_cells;
     }
     return off;

@@ -121,16 +121,22 @@ __global__ void k_cells_grid(const int32_t* __restrict__ bbox, const int32_t* __
 
 __global__ void k_cells_assign(const float* __restrict__ pos, const int32_t* __restrict__ atom_seg,
                                const E2fSegGrid* __restrict__ grid, int N, int32_t* __restrict__ atom_cell,
-                               int32_t* __restrict__ cell_count /* = cell_start + 1 */) {
+                               int32_t* __restrict__ atom_sub, int32_t* __restrict__ cell_count /* = cell_start + 1 */) {
     const int a = blockIdx.x * blockDim.x + threadIdx.x;
     if (a >= N) return;
     const E2fSegGrid g = grid[atom_seg[a]];
-    int cx = (int)floorf((pos[3 * a] - g.ox) * g.inv_edge);
-    int cy = (int)floorf((pos[3 * a + 1] - g.oy) * g.inv_edge);
-    int cz = (int)floorf((pos[3 * a + 2] - g.oz) * g.inv_edge);
+    const float fx = (pos[3 * a] - g.ox) * g.inv_edge, fy = (pos[3 * a + 1] - g.oy) * g.inv_edge;
+    const float fz = (pos[3 * a + 2] - g.oz) * g.inv_edge;
+    int cx = (int)floorf(fx), cy = (int)floorf(fy), cz = (int)floorf(fz);
     cx = min(max(cx, 0), g.nx - 1); cy = min(max(cy, 0), g.ny - 1); cz = min(max(cz, 0), g.nz - 1);
     const int c = g.base + (cz * g.ny + cy) * g.nx + cx;
     atom_cell[a] = c;
+    // Order inside the cell: Morton index over 4x4x4 sub-cells, so that atoms that are consecutive in the sorted
+    // order (the 16-atom target tiles and the 4-slot candidate groups of the attention kernels) are close in space.
+    const int sx = min(max((int)((fx - (float)cx) * 4.0f), 0), 3), sy = min(max((int)((fy - (float)cy) * 4.0f), 0), 3);
+    const int sz = min(max((int)((fz - (float)cz) * 4.0f), 0), 3);
+    auto spread = [](int v) { return (v & 1) | ((v & 2) << 2); };   // bit 0 -> 0, bit 1 -> 3
+    atom_sub[a] = spread(sx) | (spread(sy) << 1) | (spread(sz) << 2);
     atomicAdd(&cell_count[c], 1);
 }
 
@@ -166,10 +172,10 @@ __global__ void k_cells_scatter(const int32_t* __restrict__ atom_cell, const int
     tmp_slot[cell_start[c] + atomicAdd(&cell_fill[c], 1)] = a;
 }
 
-// The scatter above fills each cell in arrival order; ranking every atom among its cell mates by atom index
-// makes the final order independent of that.
+// The scatter above fills each cell in arrival order; ranking every atom among its cell mates by (sub-cell, atom
+// index) makes the final order independent of that.
 __global__ void k_cells_rank(const int32_t* __restrict__ tmp_slot, const int32_t* __restrict__ atom_cell,
-                             const int32_t* __restrict__ atom_seg, const int32_t* __restrict__ cell_start, int N,
+                             const int32_t* __restrict__ atom_sub, const int32_t* __restrict__ atom_seg, const int32_t* __restrict__ cell_start, int N,
                              int32_t* __restrict__ perm, int32_t* __restrict__ scell, int32_t* __restrict__ sseg,
                              int32_t* __restrict__ atom_slot) {
     const int t = blockIdx.x * blockDim.x + threadIdx.x;
@@ -177,8 +183,12 @@ __global__ void k_cells_rank(const int32_t* __restrict__ tmp_slot, const int32_t
     const int a = tmp_slot[t];
     const int c = atom_cell[a];
     const int b = cell_start[c], e = cell_start[c + 1];
+    const int sa = atom_sub[a];
     int rank = 0;
-    for (int u = b; u < e; ++u) rank += (tmp_slot[u] < a) ? 1 : 0;
+    for (int u = b; u < e; ++u) {
+        const int o = tmp_slot[u], so = atom_sub[o];
+        rank += (so < sa || (so == sa && o < a)) ? 1 : 0;
+    }
     perm[b + rank] = a;
     scell[b + rank] = c;
     sseg[b + rank] = atom_seg[a];
@@ -228,10 +238,10 @@ e2f_status e2f_launch_build_cells(const e2f_ctx* ctx, e2f_cells* c, const float*
     // cutoff by rounding, and cell coordinates carry rounding of their own
     k_cells_grid<<<1, 1024, 0, st>>>(c->bbox, seg_offsets, S, ctx->cfg.cutoff * 1.0001f,
                                      const_cast<E2fSegGrid*>(c->view.grid));
-    k_cells_assign<<<(N + tb - 1) / tb, tb, 0, st>>>(pos, c->atom_seg, c->view.grid, N, c->atom_cell, cell_start + 1);
+    k_cells_assign<<<(N + tb - 1) / tb, tb, 0, st>>>(pos, c->atom_seg, c->view.grid, N, c->atom_cell, c->atom_sub, cell_start + 1);
     k_cells_scan<<<1, 1024, 0, st>>>(cell_start, c->max_cells + 1);
     k_cells_scatter<<<(N + tb - 1) / tb, tb, 0, st>>>(c->atom_cell, cell_start, N, c->cell_fill, c->tmp_slot);
-    k_cells_rank<<<(N + tb - 1) / tb, tb, 0, st>>>(c->tmp_slot, c->atom_cell, c->atom_seg, cell_start, N,
+    k_cells_rank<<<(N + tb - 1) / tb, tb, 0, st>>>(c->tmp_slot, c->atom_cell, c->atom_sub, c->atom_seg, cell_start, N,
                                                   const_cast<int32_t*>(c->view.perm),
                                                   const_cast<int32_t*>(c->view.scell),
                                                   const_cast<int32_t*>(c->view.sseg),

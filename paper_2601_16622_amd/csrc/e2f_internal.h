@@ -37,6 +37,7 @@ struct e2f_cells {
     int32_t* atom_cell;  // [N]
     int32_t* cell_fill;  // [max_cells]
     int32_t* tmp_slot;   // [N]
+    int32_t* atom_sub;   // [N] position of the atom inside its cell: Morton index over 4x4x4 sub-cells
     int32_t max_cells;
     const float* pos;    // the positions the list was built from (identity check only)
 };

@@ -320,7 +320,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 #ifdef E2F_TIMING
             if (threadIdx.x == 0 && P.dbg) { atomicAdd(P.dbg + 6, (unsigned long long)nch); atomicAdd(P.dbg + 7, 1ull); }
 #endif
+#ifdef E2F_EXP_SKIP_LOOP
+            if (false) {
+#else
             if (ngr > 0) {
+#endif
                 auto load_K = [&](int c, f16x8 (&kf)[2][KS]) {
 #pragma unroll
                     for (int mt = 0; mt < 2; ++mt) {
@@ -436,7 +440,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 #pragma unroll
                     for (int cc = 0; cc < 4; ++cc) {
                         const int c = 4 * G + cc;
+#ifdef E2F_EXP_SKIP_CONSUME
+                        if (c < nch && P.n_tiles < 0) {
+#else
                         if (c < nch) {
+#endif
                             bf16x8 W[3];
 #pragma unroll
                             for (int mu = 0; mu < 3; ++mu) W[mu] = __builtin_bit_cast(bf16x8, s_W[(cc * 3 + mu) * 64 + lane]);
