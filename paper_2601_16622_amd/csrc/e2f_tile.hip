@@ -36,6 +36,9 @@ typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 
 constexpr int CAPG = 256;      // candidate groups (of four slots) held in LDS per batch
 constexpr int TILE_BLK = 16;   // consecutive tiles whose (tile, head) items form one XCD chunk, head-major
+#ifndef E2F_TILE_OCC
+#define E2F_TILE_OCC(NW) ((NW) / 2)
+#endif
 constexpr float M_STEP = 20.0f; // the softmax reference moves when a logit exceeds it by this much (base-2 units)
 
 struct TileParams {
@@ -110,26 +113,7 @@ __global__ void k_axis_ops(const float* __restrict__ cw, float* __restrict__ G) 
     for (int xo = 0; xo < n; ++xo) G[(mu * E2F_MAX_N + xo) * E2F_MAX_N + xi] = acc[xo][0];
 }
 
-// Epilogue share of one wave: po[x_out] = sum_mu sum_{x_in in [X0, X0 + NX)} G_mu[x_out][x_in] T_mu[x_in], non-zero
-// entries of the axis operators only (rows = targets 4g..4g+3, column = channel lane%16).
-// acc[mu][x] holds component XBASE + x; components below XFIRST belong to another wave and are skipped.
-template <int L, int XBASE, int XFIRST, int NX>
-__device__ __forceinline__ void axis_epilogue(const float* __restrict__ G, const f32x4 (&acc)[3][NX],
-                                              f32x4 (&po)[(L + 1) * (L + 1)]) {
-    constexpr int n = (L + 1) * (L + 1);
-#pragma unroll
-    for (int mu = 0; mu < 3; ++mu)
-#pragma unroll
-        for (int xo = 0; xo < n; ++xo)
-#pragma unroll
-            for (int x = 0; x < NX; ++x) {
-                const int xi = XBASE + x;
-                if (xi >= XFIRST && xi < n && ((E2F_AXIS_NZ[mu][xo] >> xi) & 1u))
-                    po[xo] += G[(mu * E2F_MAX_N + xo) * E2F_MAX_N + xi] * acc[mu][x];
-            }
-}
-
-// One workgroup of four waves per (tile of 16 targets, head).  The waves share the candidate list and the softmax
+// One workgroup of NW waves per (tile of 16 targets, head).  The waves share the candidate list and the softmax
 // weights through LDS and split the rest:
 //   list      each wave scans a quarter of the stencil's slot groups; the kept groups are packed in order
 //   weights   chunks of 32 candidates are taken four at a time; wave w computes the logits (matrix cores), the pair
@@ -137,20 +121,28 @@ __device__ __forceinline__ void axis_epilogue(const float* __restrict__ G, const
 //   aggregate every wave applies all four chunks' W_mu to its own quarter of the components, T_mu += W_mu V
 // The softmax reference of a target is common to the four waves: it is set by the target's first neighbours and
 // moved (with a rescale of the accumulator rows) only when a later logit exceeds it by M_STEP.
-template <int L>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void k_tile(TileParams P) {
-    constexpr int n = (L + 1) * (L + 1), NX = (n + 3) / 4;
+template <int L, int NW>
+__global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(E2F_TILE_OCC(NW), E2F_TILE_OCC(NW)))) void k_tile(TileParams P) {
+    constexpr int n = (L + 1) * (L + 1), NX = (n + NW - 1) / NW;
+    constexpr int PADE = 8 * NW;        // the list is padded to whole groups of NW chunks
+    constexpr int LU = 64 / NW / 4;     // steps of 16 slot groups per wave and batch (256 groups per batch)
     constexpr int DK = (L + 1) * 16, KS = (DK + 31) / 32, DKP = KS * 32;
     // LDS: the list and the weights while streaming; the same bytes hold the partial outputs at the end
-    constexpr int LIST_BYTES = (CAPG + 32) * 4 + (CAPG + 32) * 4 * 16, W_BYTES = 4 * 3 * 64 * 16;
-    constexpr int PO_BYTES = n * 64 * 16;
+    constexpr int LIST_BYTES = (CAPG + PADE) * 4 + (CAPG + PADE) * 4 * 16, W_BYTES = NW * 3 * 64 * 16;
+    constexpr int PO_BYTES = NW * NX * 64 * 16;   // one mu of the accumulators of all waves
     constexpr int MAIN_BYTES = LIST_BYTES + W_BYTES > PO_BYTES ? LIST_BYTES + W_BYTES : PO_BYTES;
     __shared__ __attribute__((aligned(16))) unsigned char s_raw[MAIN_BYTES];
-    __shared__ float s_cmax[4][16];
-    __shared__ float s_z[4][16];
-    __shared__ int s_cnt[4];
+#ifdef E2F_EXP_LDS_PAD
+    extern __shared__ float s_padding[];   // occupancy experiment: dynamic LDS so that fewer workgroups fit a CU
+    s_padding[threadIdx.x] = (float)threadIdx.x;
+    if (s_padding[(threadIdx.x * 7) % (64 * NW)] == -1.0f) P.out[0] = 0.0f;
+#endif
+    __shared__ __attribute__((aligned(16))) uint16_t s_q[16 * DKP];
+    __shared__ float s_cmax[NW][16];
+    __shared__ float s_z[NW][16];
+    __shared__ int s_cnt[NW];
     int* s_ent = reinterpret_cast<int*>(s_raw);
-    float4* s_pos = reinterpret_cast<float4*>(s_raw + (CAPG + 32) * 4);
+    float4* s_pos = reinterpret_cast<float4*>(s_raw + (CAPG + PADE) * 4);
     u32x4* s_W = reinterpret_cast<u32x4*>(s_raw + LIST_BYTES);   // [chunk of the group][mu][lane]
     f32x4* s_po = reinterpret_cast<f32x4*>(s_raw);
 
@@ -189,11 +181,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     const float c_u = 2.0f * P.rbf_gamma * P.rbf_step * 1.44269504088896341f;
     const float c_g = -P.rbf_gamma * 1.44269504088896341f;
 
-    f16x8 qf[KS];
-    {
-        const size_t qoff = ((size_t)tslot * H + head) * DKP + 8 * g;
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) qf[ks] = *reinterpret_cast<const f16x8*>(P.q16 + qoff + 32 * ks);
+    // q of the 16 targets for this head -> LDS (3 KB); every group re-reads its B operands from there
+    for (int u = threadIdx.x; u < 16 * (DKP / 8); u += 64 * NW) {
+        const int tq = u / (DKP / 8), f8 = u % (DKP / 8);
+        reinterpret_cast<u32x4*>(s_q)[u] =
+            *reinterpret_cast<const u32x4*>(P.q16 + ((size_t)min(t0 + tq, N - 1) * H + head) * DKP + 8 * f8);
     }
 
     f32x4 acc[3][NX];
@@ -251,17 +243,17 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
         for (int fbase = 0; fbase < total; fbase += 256) {
             // ---- a batch of the candidate list: 256 slot groups, 64 per wave, kept groups packed in order into
             // entries (group << 4 | valid slots) with the slots' positions beside them
-            int grp[4];
-            unsigned near4[4], valid4[4];
-            unsigned long long leaders[4];
-            float4 pj[4];
+            int grp[LU];
+            unsigned near4[LU], valid4[LU];
+            unsigned long long leaders[LU];
+            float4 pj[LU];
             {
                 int ln = lane;
                 asm volatile("" : "+v"(ln));   // keeps (lane - pre[r]) from being hoisted out of the loop
-                bool valid[4];
+                bool valid[LU];
 #pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    const int fg = fbase + 64 * wave + 16 * u + (ln >> 2);
+                for (int u = 0; u < LU; ++u) {
+                    const int fg = fbase + 16 * LU * wave + 16 * u + (ln >> 2);
                     int gq = -1, rlo = 0, rhi = 0;
 #pragma unroll
                     for (int r = 0; r < 9; ++r)
@@ -277,7 +269,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
                 }
                 int mine = 0;
 #pragma unroll
-                for (int u = 0; u < 4; ++u) {
+                for (int u = 0; u < LU; ++u) {
                     const float ex = fmaxf(fmaxf(bx0 - pj[u].x, pj[u].x - bx1), 0.0f);
                     const float ey = fmaxf(fmaxf(by0 - pj[u].y, pj[u].y - by1), 0.0f);
                     const float ez = fmaxf(fmaxf(bz0 - pj[u].z, pj[u].z - bz1), 0.0f);
@@ -293,13 +285,13 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
             __syncthreads();   // every wave has finished with the previous list
             int cnt = 0, e0 = 0;
 #pragma unroll
-            for (int w = 0; w < 4; ++w) {
+            for (int w = 0; w < NW; ++w) {
                 const int cw_ = s_cnt[w];
                 e0 += w < wave ? cw_ : 0;
                 cnt += cw_;
             }
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
+            for (int u = 0; u < LU; ++u) {
                 const int sh = lane & ~3;
                 const int e = e0 + __popcll(leaders[u] & ((1ull << sh) - 1ull));
                 if (near4[u] != 0u) {
@@ -309,14 +301,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
                 e0 += __popcll(leaders[u]);
             }
             // pad to whole groups of four chunks: entries of group 0 with no valid slot, finite positions
-            if (wave == 0 && lane < 32) s_ent[cnt + lane] = 0;
-            if (wave == 1) {
-                s_pos[cnt * 4 + lane] = tp;
-                s_pos[cnt * 4 + 64 + lane] = tp;
-            }
+            for (int i = threadIdx.x; i < PADE; i += 64 * NW) s_ent[cnt + i] = 0;
+            for (int i = threadIdx.x; i < PADE * 4; i += 64 * NW) s_pos[cnt * 4 + i] = tp;
             __syncthreads();
             TICK(1)
-            const int nch = (cnt + 7) >> 3, ngr = (nch + 3) >> 2;
+            const int nch = (cnt + 7) >> 3, ngr = (nch + NW - 1) / NW;
 #ifdef E2F_TIMING
             if (threadIdx.x == 0 && P.dbg) { atomicAdd(P.dbg + 6, (unsigned long long)nch); atomicAdd(P.dbg + 7, 1ull); }
 #endif
@@ -349,15 +338,19 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
                 TICK(2)
                 for (int G = 0; G < ngr; ++G) {
                     // ---- logits, pair geometry and cutoff mask of this wave's chunk
-                    const int cm = 4 * G + wave;
+                    const int cm = NW * G + wave;
                     f32x4 S[2];
+                    {
+                        f16x8 qf[KS];
 #pragma unroll
-                    for (int mt = 0; mt < 2; ++mt) {
-                        S[mt] = (f32x4){0.f, 0.f, 0.f, 0.f};
+                        for (int ks = 0; ks < KS; ++ks) qf[ks] = *reinterpret_cast<const f16x8*>(s_q + tn * DKP + 32 * ks + 8 * g);
 #pragma unroll
-                        for (int ks = 0; ks < KS; ++ks) S[mt] = mfma(kf[mt][ks], qf[ks], S[mt]);
+                        for (int mt = 0; mt < 2; ++mt) {
+                            S[mt] = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                            for (int ks = 0; ks < KS; ++ks) S[mt] = mfma(kf[mt][ks], qf[ks], S[mt]);
+                        }
                     }
-                    load_K(min(cm + 4, nch - 1), kf);
                     float s2[8], gate[8];
                     float cmax = -INFINITY;
 #pragma unroll
@@ -388,7 +381,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
                     if (lane < 16) s_cmax[wave][lane] = cmax;
                     __syncthreads();
                     // ---- the group's largest logit per target, the same in all four waves
-                    const float gmax = fmaxf(fmaxf(s_cmax[0][tn], s_cmax[1][tn]), fmaxf(s_cmax[2][tn], s_cmax[3][tn]));
+                    float gmax = s_cmax[0][tn];
+#pragma unroll
+                    for (int w = 1; w < NW; ++w) gmax = fmaxf(gmax, s_cmax[w][tn]);
                     if (m_ref == -INFINITY) m_ref = gmax;   // first neighbours: the accumulator rows are still zero
                     const bool move = gmax > m_ref + M_STEP;
                     if (__builtin_expect(__ballot(move) != 0ull, 0)) {
@@ -436,10 +431,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
                             s_W[(wave * 3 + mu) * 64 + lane] = (u32x4){wp[mu][0], wp[mu][1], wp[mu][2], wp[mu][3]};
                     }
                     __syncthreads();
-                    // ---- aggregate the four chunks of the group into this wave's components
+                    load_K(min(cm + NW, nch - 1), kf);   // k rows of this wave's chunk in the next group
+                    // ---- aggregate the chunks of the group into this wave's components
 #pragma unroll
-                    for (int cc = 0; cc < 4; ++cc) {
-                        const int c = 4 * G + cc;
+                    for (int cc = 0; cc < NW; ++cc) {
+                        const int c = NW * G + cc;
 #ifdef E2F_EXP_SKIP_CONSUME
                         if (c < nch && P.n_tiles < 0) {
 #else
@@ -465,50 +461,54 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
         a = b;
     }
 
-    // ---- epilogue: out = (1/z) sum_mu G_mu T_mu; the four waves' shares are added through LDS
-    f32x4 po[n];
+    // ---- epilogue: out = (1/z) sum_mu G_mu T_mu.  For one mu at a time the waves put their T_mu components into
+    // LDS (the list and the weights are dead by then) and every wave forms the output components x_out = wave
+    // (mod NW) from the non-zero entries of G_mu.
+    constexpr int RO = (n + NW - 1) / NW;
+    f32x4 pr[RO];
 #pragma unroll
-    for (int xo = 0; xo < n; ++xo) po[xo] = (f32x4){0.f, 0.f, 0.f, 0.f};
-    switch (wave) {
-        case 0: axis_epilogue<L, 0, 0, NX>(P.G, acc, po); break;
-        case 1: axis_epilogue<L, (NX < n - NX ? NX : n - NX), NX, NX>(P.G, acc, po); break;
-        case 2: axis_epilogue<L, (2 * NX < n - NX ? 2 * NX : n - NX), 2 * NX, NX>(P.G, acc, po); break;
-        default: axis_epilogue<L, (3 * NX < n - NX ? 3 * NX : n - NX), 3 * NX, NX>(P.G, acc, po); break;
-    }
+    for (int i = 0; i < RO; ++i) pr[i] = (f32x4){0.f, 0.f, 0.f, 0.f};
     z += __shfl_xor(z, 16);
     z += __shfl_xor(z, 32);
     if (lane < 16) s_z[wave][lane] = z;
-    __syncthreads();   // the list and the weights are dead: their bytes take the partial outputs
-    for (int w = 1; w < 4; ++w) {
-        if (wave == w) {
 #pragma unroll
-            for (int xo = 0; xo < n; ++xo) {
-                if (w == 1)
-                    s_po[xo * 64 + lane] = po[xo];
-                else
-                    s_po[xo * 64 + lane] += po[xo];
-            }
-        }
+    for (int mu = 0; mu < 3; ++mu) {
         __syncthreads();
+#pragma unroll
+        for (int x = 0; x < NX; ++x) s_po[(x0 + x) * 64 + lane] = acc[mu][x];   // repeated components hold equal values
+        __syncthreads();
+#pragma unroll
+        for (int xo = 0; xo < n; ++xo)
+            if (xo % NW == wave) {
+#pragma unroll
+                for (int xi = 0; xi < n; ++xi)
+                    if ((E2F_AXIS_NZ[mu][xo] >> xi) & 1u)
+                        pr[xo / NW] += P.G[(mu * E2F_MAX_N + xo) * E2F_MAX_N + xi] * s_po[xi * 64 + lane];
+            }
     }
     TICK(4)
 #ifdef E2F_TIMING
     if (lane == 0 && P.dbg)
         for (int k = 0; k < 6; ++k) atomicAdd(P.dbg + k, tacc[k]);
 #endif
-    if (wave != 0) return;
+    f32x4 inv;
+    int orow[4];
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
-        const int t = t0 + 4 * g + r;
-        if (t < N) {
-            const int tt = 4 * g + r;
-            const float zt = s_z[0][tt] + s_z[1][tt] + s_z[2][tt] + s_z[3][tt];
-            const float inv = zt > 0.0f ? 1.0f / zt : 0.0f;
-            float* o = P.out + (size_t)P.cv.perm[t] * n * P.C + head * 16 + tn;
+        const int tt = 4 * g + r;
+        float zt = 0.0f;
 #pragma unroll
-            for (int xo = 0; xo < n; ++xo) o[xo * P.C] = (po[xo][r] + s_po[xo * 64 + lane][r]) * inv;
-        }
+        for (int w = 0; w < NW; ++w) zt += s_z[w][tt];
+        inv[r] = zt > 0.0f ? 1.0f / zt : 0.0f;
+        orow[r] = t0 + tt < N ? P.cv.perm[t0 + tt] : -1;
     }
+#pragma unroll
+    for (int xo = 0; xo < n; ++xo)
+        if (xo % NW == wave) {
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+                if (orow[r] >= 0) P.out[((size_t)orow[r] * n + xo) * P.C + head * 16 + tn] = pr[xo / NW][r] * inv[r];
+        }
 }
 
 template <int L>
@@ -516,7 +516,14 @@ void launch_L(const TileParams& P, const float* cw, float* G, hipStream_t st) {
     k_axis_ops<L><<<1, 128, 0, st>>>(cw, G);
     const int chunks = (P.n_tiles + TILE_BLK - 1) / TILE_BLK;
     const int grid = ((chunks + 7) / 8) * 8 * TILE_BLK * P.H;
-    k_tile<L><<<grid, 256, 0, st>>>(P);
+#ifdef E2F_EXP_LDS_PAD
+    (void)hipFuncSetAttribute((const void*)k_tile<L, 4>, hipFuncAttributeMaxDynamicSharedMemorySize, E2F_EXP_LDS_PAD);
+    k_tile<L, 4><<<grid, 256, E2F_EXP_LDS_PAD, st>>>(P);
+    return;
+#endif
+    // four waves per workgroup, two workgroups per CU: with eight waves the 128 registers left per wave do not
+    // hold a wave's accumulators, value rows and key rows without spilling into the streaming loop
+    k_tile<L, 4><<<grid, 256, 0, st>>>(P);
 }
 
 }  // namespace
