@@ -54,6 +54,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-materialized", action="store_true")
+    ap.add_argument("--no-factorized", action="store_true")
     ap.add_argument("--workload", default="scaling", help="scaling | large | small | tiny | box<N>")
     ap.add_argument("--sweep", action="store_true",
                     help="also time the Large-N boxes (20k, 50k, 100k atoms) and fit peak activation bytes against N")
@@ -115,24 +116,40 @@ def main():
     fwd_ms = (time.perf_counter() - t0) * 1e3 / args.steps
 
     attn_ms = stage_ms["attention"]
-    achieved = E * f_edge / (attn_ms * 1e-3) / 1e12 if attn_ms > 0 else 0.0
-    on_mfma = (cfg["dtype"] == "bf16" and cfg["C"] // cfg["H"] == 16 and cfg["lf"] == 1 and cfg["L"] >= 1
-               and cfg["H"] in (1, 2, 4, 8) and os.environ.get("E2F_ATTENTION") != "valu")
-    # formal bound of the attention kernel: max(HBM time, MFMA time of the dense pieces, plain-ALU time of the rest)
+    bf16 = cfg["dtype"] == "bf16"
+    pick = os.environ.get("E2F_ATTENTION")
+    mc_ok = bf16 and cfg["C"] // cfg["H"] == 16 and cfg["L"] >= 1 and pick != "valu"
+    if mc_ok and cfg["lf"] == 1 and cfg["C"] in (32, 64, 128) and pick != "pair":
+        kernel = "k_tile"
+    elif mc_ok and cfg["lf"] in (1, 2) and cfg["H"] in (1, 2, 4, 8):
+        kernel = "k_fused_mfma"
+    else:
+        kernel = "k_fused_valu"
+    # Roofs of the attention kernel from the algorithmic work of the method (per pair: logits, rotate in, re-index,
+    # rotate back, weighted accumulate): HBM time of the rows it must touch once, matrix-core time of the dense
+    # pieces, plain-ALU time of the rest.  The largest of the three binds; `frac` is that time over the measured one.
     Lm, Cc = cfg["L"], cfg["C"]
     n = (Lm + 1) ** 2
     S2 = sum((2 * l + 1) ** 2 for l in range(Lm + 1))
     f_dense = E * (2 * (Lm + 1) * Cc + 4 * S2 * Cc)
     f_rest = E * f_edge - f_dense
-    esz = 2 if cfg["dtype"] == "bf16" else 4
+    esz = 2 if bf16 else 4
     hbm_bytes = N * (16 + 2 * (Lm + 1) * Cc * 4 + n * Cc * esz + n * Cc * 4)
-    t_roof_ms = max(hbm_bytes / 8e12, f_dense / (2.5e15 if esz == 2 else 157.3e12), f_rest / 157.3e12) * 1e3
-    roofline = {"bound": "alu", "kernel": "k_fused_mfma" if on_mfma else "k_fused_valu",
-                "achieved": round(achieved, 3), "peak": PEAK_ALU_TFLOPS,
-                "unit": "TFLOP/s", "frac": round(achieved / PEAK_ALU_TFLOPS, 4), "traffic": read_traffic(),
-                "kernel_ms": round(attn_ms, 4), "flops_per_launch": E * f_edge, "pairs_per_launch": E,
-                "stage_ms": {k: round(v, 4) for k, v in stage_ms.items()},
-                "t_roof_ms": round(t_roof_ms, 4), "frac_of_t_roof": round(t_roof_ms / attn_ms, 4) if attn_ms > 0 else 0.0}
+    peak_mfma = 2500.0 if bf16 else PEAK_ALU_TFLOPS
+    roofs = {"hbm": (hbm_bytes / 8e12, hbm_bytes / 1e9, 8000.0, "GB/s"),
+             "mfma": (f_dense / (peak_mfma * 1e12), f_dense / 1e12, peak_mfma, "TFLOP/s"),
+             "alu": (f_rest / (PEAK_ALU_TFLOPS * 1e12), f_rest / 1e12, PEAK_ALU_TFLOPS, "TFLOP/s")}
+    bound = max(roofs, key=lambda k: roofs[k][0])
+    t_roof, work, peak, unit = roofs[bound]
+    achieved = work / (attn_ms * 1e-3) if attn_ms > 0 else 0.0
+    roofline = {"bound": bound, "kernel": kernel, "achieved": round(achieved, 3), "peak": peak, "unit": unit,
+                "frac": round(achieved / peak, 4), "traffic": read_traffic(),
+                "kernel_ms": round(attn_ms, 4), "pairs_per_launch": E,
+                "algorithmic_flops_per_launch": E * f_edge,
+                "algorithmic_tflops": round(E * f_edge / (attn_ms * 1e-3) / 1e12, 3) if attn_ms > 0 else 0.0,
+                "work_of_bound_per_launch": work * (1e9 if bound == "hbm" else 1e12),
+                "roof_ms": {k: round(v[0] * 1e3, 4) for k, v in roofs.items()},
+                "stage_ms": {k: round(v, 4) for k, v in stage_ms.items()}}
 
     result = {
         "metric": "atoms/sec of fused equivariant attention forward (cells + projections + attention)",
@@ -151,6 +168,8 @@ def main():
 
     # the paper's own factorized pipeline (node-level products around Algorithm 1) on the same inputs
     try:
+        if args.no_factorized:
+            raise B.E2fError(0, "skipped")
         out_f = torch.empty_like(P.out)
         for _ in range(3):
             P.forward_factorized(out_f)

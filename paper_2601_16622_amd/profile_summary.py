@@ -35,14 +35,16 @@ def pmc(fetch_db, write_db, copy_bytes):
     print(f"copy of {copy_bytes} bytes: FETCH_SIZE reads {fetch[copy_name][2]:.1f} KiB (scale {f_scale:.3f}), "
           f"WRITE_SIZE reads {write[copy_name][2]:.1f} KiB (scale {w_scale:.3f})")
     print(f"{'dispatches':>10} {'fetch_MB':>12} {'write_MB':>12}  kernel (scaled, per dispatch)")
+    marked = False
     for name in sorted(fetch, key=lambda k: -fetch[k][1]):
         if name.startswith("void at::") or name == copy_name:
             continue
         f = fetch[name][1] * f_scale * 1024 / 1e6
         w = write.get(name, (0, 0, 0))[1] * w_scale * 1024 / 1e6
         print(f"{fetch[name][0]:10d} {f:12.2f} {w:12.2f}  {name[:100]}")
-        if "k_fused" in name:
+        if not marked and ("k_tile" in name or "k_fused" in name):   # the attention kernel of the timed path
             print(f"traffic_bytes_per_launch: {(f + w) * 1e6:.0f}")
+            marked = True
 
 
 if __name__ == "__main__":
