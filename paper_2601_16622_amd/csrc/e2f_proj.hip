@@ -5,6 +5,9 @@
 // tiles; for every order m it multiplies the 16 x C slab of h by W^T on the matrix cores and, for q and k,
 // accumulates the element-wise product of the two projections over m, so Q1,Q2,K1,K2 never leave registers.
 // k_project_simple is a plain one-thread-per-output version used by the materialized baseline.
+#include <stdlib.h>
+#include <string.h>
+
 #include "e2f_device.h"
 
 namespace {
@@ -531,6 +534,159 @@ __global__ __launch_bounds__(64 * WG_WAVES) void k_project_wg(E2fCellsView cv, c
     }
 }
 
+// Shared-slab projection for the layout of the tile attention kernel.  One workgroup owns (up to SH_TPW tiles of 16
+// atoms, one degree l) and all output channels: wave ct holds the five 16 x C weight tiles of that degree for output
+// channels 16 ct .. 16 ct + 15 as MFMA A operands (fetched once per workgroup); one more wave does nothing but fetch
+// the next (atom tile, order) slab of h into LDS, where all the other waves read it as their B operand.  Every h row
+// is fetched once (the per-channel-tile kernels above fetch it C/16 times) and a weight tile once per 64 atoms.  The
+// fetching wave stores nothing and the computing waves load nothing inside the stream, so no wait ever covers a
+// store and the outputs go straight from registers to memory: q and k of the degree after a tile's last order
+// (binary16, 8 bytes per lane), v after a 16 x 16 transpose through a private 512-byte LDS patch (bf16, the four slots
+// of a (component, channel) per lane).  Workgroups of the highest degree (most orders) are launched first.
+constexpr int SH_TPW = 16;   // most tiles a workgroup takes; the launcher picks 4, 8 or 16 from the problem size
+template <int C>
+__global__ __launch_bounds__(64 * (C / 16 + 1)) void k_project_sh(E2fCellsView cv, const uint16_t* __restrict__ h,
+                                                                 const uint16_t* __restrict__ WQ1,
+                                                                 const uint16_t* __restrict__ WQ2,
+                                                                 const uint16_t* __restrict__ WK1,
+                                                                 const uint16_t* __restrict__ WK2,
+                                                                 const uint16_t* __restrict__ WV, int L, int n_groups,
+                                                                 int tpw, WgGroupOut go) {
+    typedef Frag<uint16_t> F;
+    typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+    typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+    typedef _Float16 h16x4 __attribute__((ext_vector_type(4)));
+    constexpr int NS = C / F::KSTEP, NCT = C / 16, ROW = C + 8, NLD = C / 32;   // NLD 16-byte loads per lane and slab
+    __shared__ __attribute__((aligned(16))) uint16_t s_x[2][16 * ROW];
+    __shared__ __attribute__((aligned(8))) uint16_t s_t[NCT][256];
+    const int N = cv.N, n = (L + 1) * (L + 1), n_tiles = (N + 15) / 16, N4 = (N + 3) / 4 * 4;
+    const int l = L - (int)blockIdx.x / n_groups, nl = 2 * l + 1;
+    const int tile0 = ((int)blockIdx.x % n_groups) * tpw, nt = min(tpw, n_tiles - tile0);
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, j = lane & 15, g = lane >> 4;
+    const int n_steps = nt * nl;   // step = local tile * nl + order
+
+    if (wave == NCT) {
+        // ---- the fetching wave: lane = (atom a of the tile, quarter of its row)
+        const int a = lane >> 2, part = lane & 3;
+        int atom_of[SH_TPW];
+#pragma unroll
+        for (int x = 0; x < SH_TPW; ++x) atom_of[x] = cv.perm[min((tile0 + min(x, nt - 1)) * 16 + a, N - 1)];
+        auto issue = [&](int st, u32x4 (&r)[NLD]) {
+            st = min(st, n_steps - 1);
+            const int lt = st / nl, m = st - lt * nl;
+            int atom = atom_of[0];
+#pragma unroll
+            for (int x = 1; x < SH_TPW; ++x) atom = lt == x ? atom_of[x] : atom;
+            const uint16_t* row = h + ((size_t)atom * n + l * l + m) * C + part * (C / 4);
+#pragma unroll
+            for (int i = 0; i < NLD; ++i) r[i] = *reinterpret_cast<const u32x4*>(row + 8 * i);
+        };
+        auto put = [&](int buf, const u32x4 (&r)[NLD]) {
+            uint16_t* d = s_x[buf] + a * ROW + part * (C / 4);
+#pragma unroll
+            for (int i = 0; i < NLD; ++i) *reinterpret_cast<u32x4*>(d + 8 * i) = r[i];
+        };
+        // slab st + 1 is written to LDS while the others work on slab st; its registers then take slab st + 1 + PD,
+        // so PD slabs are in flight at any time
+        constexpr int PD = 6;
+        u32x4 r[PD][NLD];
+#pragma unroll
+        for (int u = 0; u < PD; ++u) issue(u, r[u]);
+        put(0, r[0]);
+        issue(PD, r[0]);
+        __syncthreads();
+        for (int s0 = 0; s0 < n_steps; s0 += PD) {
+#pragma unroll
+            for (int u = 0; u < PD; ++u) {
+                const int st = s0 + u;   // slab st + 1 lives in r[(u + 1) % PD]
+                if (st < n_steps) {
+                    put((st + 1) & 1, r[(u + 1) % PD]);
+                    issue(st + 1 + PD, r[(u + 1) % PD]);
+                    __syncthreads();
+                }
+            }
+        }
+        return;
+    }
+
+    // ---- the computing waves
+    const int ct = wave;
+    F::type Wf[5][NS];
+    {   // weights of the degree; they must have arrived before the stream starts, so that inside it the wave's
+        // memory counter only ever holds stores, which nothing waits for
+        const size_t wrow = ((size_t)l * C + (ct * 16 + j)) * C;
+#pragma unroll
+        for (int S = 0; S < NS; ++S) {
+            Wf[0][S] = F::load(WQ1 + wrow, S, g);
+            Wf[1][S] = F::load(WQ2 + wrow, S, g);
+            Wf[2][S] = F::load(WK1 + wrow, S, g);
+            Wf[3][S] = F::load(WK2 + wrow, S, g);
+            Wf[4][S] = F::load(WV + wrow, S, g);
+        }
+#pragma unroll
+        for (int w = 0; w < 5; ++w)
+#pragma unroll
+            for (int S = 0; S < NS; ++S) asm volatile("" ::"v"(__builtin_bit_cast(u32x4, Wf[w][S])));
+    }
+    f32x4 qacc = {0.f, 0.f, 0.f, 0.f}, kacc = {0.f, 0.f, 0.f, 0.f};
+    const int DK = (L + 1) * 16;
+    __syncthreads();
+    int st = 0;
+    for (int lt = 0; lt < nt; ++lt)
+        for (int m = 0; m < nl; ++m, ++st) {
+            const uint16_t* xrow = s_x[st & 1] + j * ROW;
+            f32x4 p[5];
+#pragma unroll
+            for (int w = 0; w < 5; ++w) p[w] = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int S = 0; S < NS; ++S) {
+                const F::type X = F::load(xrow, S, g);
+#pragma unroll
+                for (int w = 0; w < 5; ++w) p[w] = F::mma(Wf[w][S], X, p[w]);
+            }
+            qacc += p[0] * p[1];
+            kacc += p[2] * p[3];
+            // accumulator layout: lane (g, j) holds output channels 4g..4g+3 of atom j
+            const int slot = (tile0 + lt) * 16 + j;
+            {   // v: [channel][atom] patch, then one (channel, group of four slots) per lane
+                uint16_t* patch = s_t[ct];
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+                    patch[(4 * g + r) * 16 + j] = slot < N ? e2f::float_to_bf16_bits(p[4][r]) : (uint16_t)0;
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+                __builtin_amdgcn_wave_barrier();
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+                const int ch = lane >> 2, G = lane & 3;
+                const u32x2 unit = *reinterpret_cast<const u32x2*>(patch + ch * 16 + 4 * G);
+                const int grp = (tile0 + lt) * 4 + G;
+                if (grp * 4 < N)
+                    *reinterpret_cast<u32x2*>(go.v4 + (((size_t)grp * NCT + ct) * n + l * l + m) * 64 + ch * 4) = unit;
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+                __builtin_amdgcn_wave_barrier();
+            }
+            if (m == nl - 1) {   // last order of this tile: q and k of the degree go out
+                h16x4 qv, kv;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    qv[r] = (_Float16)(qacc[r] * go.qscale);
+                    kv[r] = (_Float16)(slot < N ? kacc[r] : 0.0f);
+                }
+                const size_t dst = ((size_t)slot * NCT + ct) * go.DKP + l * 16 + 4 * g;
+                if (slot < N) *reinterpret_cast<h16x4*>(go.q16 + dst) = qv;
+                if (slot < N4) *reinterpret_cast<h16x4*>(go.k16 + dst) = kv;
+                if (l == L && go.DKP > DK) {   // padding features read as zero
+                    const h16x4 zero = {(_Float16)0.0f, (_Float16)0.0f, (_Float16)0.0f, (_Float16)0.0f};
+                    const size_t dz = ((size_t)slot * NCT + ct) * go.DKP + DK + 4 * g;
+                    if (slot < N) *reinterpret_cast<h16x4*>(go.q16 + dz) = zero;
+                    if (slot < N4) *reinterpret_cast<h16x4*>(go.k16 + dz) = zero;
+                }
+                qacc = (f32x4){0.f, 0.f, 0.f, 0.f};
+                kacc = (f32x4){0.f, 0.f, 0.f, 0.f};
+            }
+            __syncthreads();
+        }
+}
+
 // Plain version: block = one sorted slot, thread = one output channel; fp32 outputs.
 template <typename T>
 __global__ void k_project_simple(E2fCellsView cv, const T* __restrict__ h, const T* __restrict__ WQ1,
@@ -634,7 +790,16 @@ bool launch_wg(const e2f_ctx* ctx, const E2fCellsView& cv, const void* h, const 
         go.q16 = ws.q16; go.k16 = ws.k16; go.v4 = ws.v4;
         go.qscale = ctx->tau * 1.44269504088896341f;   // logits in base-2 units
         go.DKP = ((L + 1) * 16 + 31) / 32 * 32;
-        if (v_layout == 2)
+        static const bool use_sh = [] { const char* e = getenv("E2F_PROJECT"); return !(e && strcmp(e, "wg") == 0); }();
+        if (v_layout == 2 && use_sh) {
+            // more tiles per workgroup fetch the weights less often; keep a few workgroups per CU
+            int tpw = SH_TPW;
+            while (tpw > 4 && (n_tiles + tpw - 1) / tpw * (L + 1) < 384) tpw >>= 1;
+            const int n_groups = (n_tiles + tpw - 1) / tpw;
+            k_project_sh<C><<<n_groups * (L + 1), 64 * (C / 16 + 1), 0, st>>>(
+                cv, (const uint16_t*)h, (const uint16_t*)w->WQ1, (const uint16_t*)w->WQ2, (const uint16_t*)w->WK1,
+                (const uint16_t*)w->WK2, (const uint16_t*)w->WV, L, n_groups, tpw, go);
+        } else if (v_layout == 2)
             k_project_wg<C, 2><<<blocks, 64 * WG_WAVES, 0, st>>>(cv, (const uint16_t*)h, (const uint16_t*)w->WQ1,
                                                                 (const uint16_t*)w->WQ2, (const uint16_t*)w->WK1,
                                                                 (const uint16_t*)w->WK2, (const uint16_t*)w->WV, L, roles,
