@@ -132,12 +132,8 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(E2F_TIL
     constexpr int PO_BYTES = NW * NX * 64 * 16;   // one mu of the accumulators of all waves
     constexpr int MAIN_BYTES = LIST_BYTES + W_BYTES > PO_BYTES ? LIST_BYTES + W_BYTES : PO_BYTES;
     __shared__ __attribute__((aligned(16))) unsigned char s_raw[MAIN_BYTES];
-#ifdef E2F_EXP_LDS_PAD
-    extern __shared__ float s_padding[];   // occupancy experiment: dynamic LDS so that fewer workgroups fit a CU
-    s_padding[threadIdx.x] = (float)threadIdx.x;
-    if (s_padding[(threadIdx.x * 7) % (64 * NW)] == -1.0f) P.out[0] = 0.0f;
-#endif
     __shared__ __attribute__((aligned(16))) uint16_t s_q[16 * DKP];
+    __shared__ float s_G[3 * E2F_MAX_N * E2F_MAX_N];   // the axis operators, read by the epilogue
     __shared__ float s_cmax[NW][16];
     __shared__ float s_z[NW][16];
     __shared__ int s_cnt[NW];
@@ -181,6 +177,11 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(E2F_TIL
     const float c_u = 2.0f * P.rbf_gamma * P.rbf_step * 1.44269504088896341f;
     const float c_g = -P.rbf_gamma * 1.44269504088896341f;
 
+    for (int i = threadIdx.x; i < 3 * E2F_MAX_N * E2F_MAX_N; i += 64 * NW) s_G[i] = P.G[i];
+    // rows of the output that this lane will store (targets 4g..4g+3), fetched early
+    int orow[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) orow[r] = t0 + 4 * g + r < N ? P.cv.perm[t0 + 4 * g + r] : -1;
     // q of the 16 targets for this head -> LDS (3 KB); every group re-reads its B operands from there
     for (int u = threadIdx.x; u < 16 * (DKP / 8); u += 64 * NW) {
         const int tq = u / (DKP / 8), f8 = u % (DKP / 8);
@@ -309,11 +310,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(E2F_TIL
 #ifdef E2F_TIMING
             if (threadIdx.x == 0 && P.dbg) { atomicAdd(P.dbg + 6, (unsigned long long)nch); atomicAdd(P.dbg + 7, 1ull); }
 #endif
-#ifdef E2F_EXP_SKIP_LOOP
-            if (false) {
-#else
             if (ngr > 0) {
-#endif
                 auto load_K = [&](int c, f16x8 (&kf)[2][KS]) {
 #pragma unroll
                     for (int mt = 0; mt < 2; ++mt) {
@@ -436,11 +433,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(E2F_TIL
 #pragma unroll
                     for (int cc = 0; cc < NW; ++cc) {
                         const int c = NW * G + cc;
-#ifdef E2F_EXP_SKIP_CONSUME
-                        if (c < nch && P.n_tiles < 0) {
-#else
                         if (c < nch) {
-#endif
                             bf16x8 W[3];
 #pragma unroll
                             for (int mu = 0; mu < 3; ++mu) W[mu] = __builtin_bit_cast(bf16x8, s_W[(cc * 3 + mu) * 64 + lane]);
@@ -483,7 +476,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(E2F_TIL
 #pragma unroll
                 for (int xi = 0; xi < n; ++xi)
                     if ((E2F_AXIS_NZ[mu][xo] >> xi) & 1u)
-                        pr[xo / NW] += P.G[(mu * E2F_MAX_N + xo) * E2F_MAX_N + xi] * s_po[xi * 64 + lane];
+                        pr[xo / NW] += s_G[(mu * E2F_MAX_N + xo) * E2F_MAX_N + xi] * s_po[xi * 64 + lane];
             }
     }
     TICK(4)
@@ -492,7 +485,6 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(E2F_TIL
         for (int k = 0; k < 6; ++k) atomicAdd(P.dbg + k, tacc[k]);
 #endif
     f32x4 inv;
-    int orow[4];
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
         const int tt = 4 * g + r;
@@ -500,7 +492,6 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(E2F_TIL
 #pragma unroll
         for (int w = 0; w < NW; ++w) zt += s_z[w][tt];
         inv[r] = zt > 0.0f ? 1.0f / zt : 0.0f;
-        orow[r] = t0 + tt < N ? P.cv.perm[t0 + tt] : -1;
     }
 #pragma unroll
     for (int xo = 0; xo < n; ++xo)
@@ -516,11 +507,6 @@ void launch_L(const TileParams& P, const float* cw, float* G, hipStream_t st) {
     k_axis_ops<L><<<1, 128, 0, st>>>(cw, G);
     const int chunks = (P.n_tiles + TILE_BLK - 1) / TILE_BLK;
     const int grid = ((chunks + 7) / 8) * 8 * TILE_BLK * P.H;
-#ifdef E2F_EXP_LDS_PAD
-    (void)hipFuncSetAttribute((const void*)k_tile<L, 4>, hipFuncAttributeMaxDynamicSharedMemorySize, E2F_EXP_LDS_PAD);
-    k_tile<L, 4><<<grid, 256, E2F_EXP_LDS_PAD, st>>>(P);
-    return;
-#endif
     // four waves per workgroup, two workgroups per CU: with eight waves the 128 registers left per wave do not
     // hold a wave's accumulators, value rows and key rows without spilling into the streaming loop
     k_tile<L, 4><<<grid, 256, 0, st>>>(P);
