@@ -41,7 +41,7 @@ size_t cells_ws_layout(int32_t N, int32_t S, void* ws, e2f_cells* c) {
         off += e2f_align_up(bytes);
         return p;
     };
-    char* grid = take((size_t)(S > 0 ? S : 1) * sizeof(E2fSegGrid));
+    char* grid = take((size_t)((S > 0 ? S : 1) + 1) * sizeof(E2fSegGrid));   // one more: the cells-in-use sentinel
     char* cell_start = take((size_t)(max_cells + 1) * 4);
     char* perm = take((size_t)N * 4);
     char* scell = take((size_t)N * 4);

@@ -36,16 +36,38 @@ __global__ void k_cells_bbox(const float* __restrict__ pos, const int32_t* __res
         atom_seg[a] = s;
         x = pos[3 * a]; y = pos[3 * a + 1]; z = pos[3 * a + 2];
     }
-    // one set of atomics per wave when the whole wave sits in one segment
-    const int s0 = __shfl(s, 0);
+    // One set of atomics per workgroup when all of it sits in one segment (the common case: few, large segments),
+    // else one per wave that does, else one per atom.
+    __shared__ float s_box[16][6];
+    __shared__ int s_seg[16];
+    const int s0 = __shfl(s, 0), wave = threadIdx.x >> 6, n_waves = (blockDim.x + 63) >> 6;
     const bool uniform = __all(live && s == s0);
+    float mnx = x, mny = y, mnz = z, mxx = x, mxy = y, mxz = z;
     if (uniform) {
-        float mnx = x, mny = y, mnz = z, mxx = x, mxy = y, mxz = z;
         for (int off = 32; off > 0; off >>= 1) {
             mnx = fminf(mnx, __shfl_xor(mnx, off)); mny = fminf(mny, __shfl_xor(mny, off));
             mnz = fminf(mnz, __shfl_xor(mnz, off)); mxx = fmaxf(mxx, __shfl_xor(mxx, off));
             mxy = fmaxf(mxy, __shfl_xor(mxy, off)); mxz = fmaxf(mxz, __shfl_xor(mxz, off));
         }
+    }
+    if ((threadIdx.x & 63) == 0) {
+        s_seg[wave] = uniform ? s0 : -1;
+        s_box[wave][0] = mnx; s_box[wave][1] = mny; s_box[wave][2] = mnz;
+        s_box[wave][3] = mxx; s_box[wave][4] = mxy; s_box[wave][5] = mxz;
+    }
+    __syncthreads();
+    bool block_uniform = s_seg[0] >= 0;
+    for (int w = 1; w < n_waves; ++w) block_uniform = block_uniform && s_seg[w] == s_seg[0];
+    if (block_uniform) {
+        if (threadIdx.x < 6) {
+            float v = s_box[0][threadIdx.x];
+            for (int w = 1; w < n_waves; ++w) v = threadIdx.x < 3 ? fminf(v, s_box[w][threadIdx.x]) : fmaxf(v, s_box[w][threadIdx.x]);
+            if (threadIdx.x < 3)
+                atomicMin(&bbox[s_seg[0] * 6 + threadIdx.x], float_to_ordered(v));
+            else
+                atomicMax(&bbox[s_seg[0] * 6 + threadIdx.x], float_to_ordered(v));
+        }
+    } else if (uniform) {
         if ((threadIdx.x & 63) == 0) {
             atomicMin(&bbox[s * 6 + 0], float_to_ordered(mnx)); atomicMin(&bbox[s * 6 + 1], float_to_ordered(mny));
             atomicMin(&bbox[s * 6 + 2], float_to_ordered(mnz)); atomicMax(&bbox[s * 6 + 3], float_to_ordered(mxx));
@@ -117,6 +139,7 @@ __global__ void k_cells_grid(const int32_t* __restrict__ bbox, const int32_t* __
         if (threadIdx.x == blockDim.x - 1) s_carry = carry + incl;
         __syncthreads();
     }
+    if (threadIdx.x == 0) grid[S].base = s_carry;   // cells in use: what the scan of the counts has to cover
 }
 
 __global__ void k_cells_assign(const float* __restrict__ pos, const int32_t* __restrict__ atom_seg,
@@ -143,8 +166,9 @@ __global__ void k_cells_assign(const float* __restrict__ pos, const int32_t* __r
 // One block: in-place inclusive scan of data[0..n) (data[0] is 0, data[c+1] the count of cell c), which turns
 // the counts into first-slot offsets.  Every thread sums one contiguous chunk, the chunk sums are scanned across
 // the block, and a second sweep writes the running totals.
-__global__ void k_cells_scan(int32_t* __restrict__ data, int n) {
+__global__ void k_cells_scan(int32_t* __restrict__ data, const E2fSegGrid* __restrict__ grid, int S) {
     __shared__ int s_part[1024];
+    const int n = grid[S].base + 1;   // cells in use + 1; the counts beyond are zero and never read
     const int chunk = (n + (int)blockDim.x - 1) / (int)blockDim.x;
     const int b = min((int)threadIdx.x * chunk, n), e = min(b + chunk, n);
     int sum = 0;
@@ -233,13 +257,13 @@ e2f_status e2f_launch_build_cells(const e2f_ctx* ctx, e2f_cells* c, const float*
     int32_t* cell_start = const_cast<int32_t*>(c->view.cell_start);
     const int n_init = c->max_cells + 1 > S * 6 ? c->max_cells + 1 : S * 6;
     k_cells_init<<<(n_init + tb - 1) / tb, tb, 0, st>>>(c->bbox, S, cell_start, c->cell_fill, c->max_cells);
-    k_cells_bbox<<<(N + tb - 1) / tb, tb, 0, st>>>(pos, seg_offsets, N, S, c->atom_seg, c->bbox);
+    k_cells_bbox<<<(N + 1023) / 1024, 1024, 0, st>>>(pos, seg_offsets, N, S, c->atom_seg, c->bbox);
     // edge a hair above the cutoff: the binary32 predicate can accept a pair whose exact |dx| exceeds the
     // cutoff by rounding, and cell coordinates carry rounding of their own
     k_cells_grid<<<1, 1024, 0, st>>>(c->bbox, seg_offsets, S, ctx->cfg.cutoff * 1.0001f,
                                      const_cast<E2fSegGrid*>(c->view.grid));
     k_cells_assign<<<(N + tb - 1) / tb, tb, 0, st>>>(pos, c->atom_seg, c->view.grid, N, c->atom_cell, c->atom_sub, cell_start + 1);
-    k_cells_scan<<<1, 1024, 0, st>>>(cell_start, c->max_cells + 1);
+    k_cells_scan<<<1, 1024, 0, st>>>(cell_start, c->view.grid, S);
     k_cells_scatter<<<(N + tb - 1) / tb, tb, 0, st>>>(c->atom_cell, cell_start, N, c->cell_fill, c->tmp_slot);
     k_cells_rank<<<(N + tb - 1) / tb, tb, 0, st>>>(c->tmp_slot, c->atom_cell, c->atom_sub, c->atom_seg, cell_start, N,
                                                   const_cast<int32_t*>(c->view.perm),
