@@ -215,6 +215,17 @@ def main():
                                   "kind": "oracle",
                                   "sample": f"{n_t} of {N} target atoms of the same workload, fp64 dense-CG route, "
                                             f"{dt:.1f} s wall"}
+        # the same oracle on one thread, a smaller sample of targets
+        all_threads = oracle.num_threads()
+        n_1 = min(N, 400)
+        t_1 = np.random.default_rng(1).choice(N, n_1, replace=False).astype(np.int32)
+        oracle.set_num_threads(1)
+        t0 = time.perf_counter()
+        oracle.attn_forward(cfg, wl["pos"], wl["h"], wl["seg"], wl["weights"], targets=t_1, nbr=nbr)
+        dt1 = time.perf_counter() - t0
+        oracle.set_num_threads(all_threads)
+        result["cpu_baseline_1thread"] = {"value": round(n_1 / dt1, 1), "unit": "atoms/s", "cores": 1, "kind": "oracle",
+                                          "sample": f"{n_1} of {N} target atoms, {dt1:.1f} s wall"}
     P.close()
 
     if args.tp:

@@ -64,6 +64,8 @@ def lib():
         L.e2fo_attn_forward.restype = ctypes.c_int
         L.e2fo_num_threads.argtypes = []
         L.e2fo_num_threads.restype = ctypes.c_int
+        L.e2fo_set_num_threads.argtypes = [ctypes.c_int]
+        L.e2fo_set_num_threads.restype = None
         _lib = L
     return _lib
 
@@ -78,6 +80,11 @@ def _f64(a):
 
 def num_threads():
     return lib().e2fo_num_threads()
+
+
+def set_num_threads(n):
+    """Thread count of the oracle's loops over target atoms (timing aid only; results do not depend on it)."""
+    lib().e2fo_set_num_threads(int(n))
 
 
 def solid_harmonics(l, r):

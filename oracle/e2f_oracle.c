@@ -659,6 +659,9 @@ int e2fo_attn_forward(const e2fo_config *cfg, const double *pos, const double *h
 #ifdef _OPENMP
 #include <omp.h>
 int e2fo_num_threads(void) { return omp_get_max_threads(); }
+/* Thread count of the loops over target atoms (timing aid: the benchmark reports the oracle on all cores and on one). */
+void e2fo_set_num_threads(int n) { if (n > 0) omp_set_num_threads(n); }
 #else
 int e2fo_num_threads(void) { return 1; }
+void e2fo_set_num_threads(int n) { (void)n; }
 #endif

@@ -4,6 +4,7 @@
     python -m paper_2601_16622_amd.profile_summary pmc    <fetch_results.db> <write_results.db> <copy_bytes>
 
 `trace` prints per-kernel call counts and mean durations (what `rocprofv3 --kernel-trace --stats` collects).
+`counters` prints the mean of every collected counter for the kernels whose name contains a pattern.
 `pmc` prints FETCH_SIZE / WRITE_SIZE per kernel (KiB per dispatch), scaled by what the same counters read for the
 plain device copy of <copy_bytes> bytes that `bench.py --copy-calibration` runs in the same process.
 """
@@ -47,8 +48,25 @@ def pmc(fetch_db, write_db, copy_bytes):
             marked = True
 
 
+def counters(db, pattern):
+    """Mean value per dispatch of every counter collected in this run, for kernels whose name contains `pattern`."""
+    con = sqlite3.connect(db)
+    rows = con.execute("select kernel_name, counter_name, avg(value), count(*) from counters_collection "
+                       "group by kernel_name, counter_name").fetchall()
+    seen = {}
+    for name, counter, value, n in rows:
+        if pattern in name:
+            seen.setdefault(name, []).append((counter, value, n))
+    for name, items in seen.items():
+        print(name[:110])
+        for counter, value, n in sorted(items):
+            print(f"    {counter:<32} {value:16.6g}   (mean over {n} dispatches)")
+
+
 if __name__ == "__main__":
     if sys.argv[1] == "trace":
         trace(sys.argv[2])
+    elif sys.argv[1] == "counters":
+        counters(sys.argv[2], sys.argv[3])
     else:
         pmc(sys.argv[2], sys.argv[3], int(sys.argv[4]))
