@@ -186,6 +186,30 @@ def main():
     except B.E2fError as e:
         result["factorized"] = {"error": str(e)}
 
+    # neighbour cap (max_neighbors of the paper's model table is 32) and the padded-table form of the call
+    if not args.no_factorized:
+        def timed(fn, reps=20):
+            for _ in range(3):
+                fn()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(reps):
+                fn()
+            torch.cuda.synchronize()
+            return (time.perf_counter() - t0) * 1e3 / reps
+        out_c = torch.empty_like(P.out)
+        capped = {}
+        for K in (32, 64):
+            ms = timed(lambda: P.forward_capped(K, out_c))
+            capped[str(K)] = {"forward_ms": round(ms, 4), "atoms_per_s": round(N / (ms * 1e-3), 1)}
+        table, count = P.neighbor_table(32)
+        build_ms = timed(lambda: B.e2f_build_neighbor_table(P.ctx, P.cells, P.pos, 32, table, count), reps=10)
+        ms = timed(lambda: P.forward_table(table, out_c), reps=10)
+        result["capped"] = capped
+        result["table"] = {"K": 32, "build_ms": round(build_ms, 4), "forward_ms": round(ms, 4),
+                           "pairs": int(count.sum().item()),
+                           "max_abs_diff_vs_capped": float((out_c - P.forward_capped(32, torch.empty_like(P.out))).abs().max())}
+
     if not args.no_materialized:
         try:
             out_m = torch.empty_like(P.out)

@@ -136,6 +136,36 @@ e2f_status e2f_attn_forward_materialized(e2f_ctx *ctx, const e2f_cells *cells, c
                                          size_t *peak_bytes_out);
 
 /*
+ * Neighbour cap (the max_neighbors setting of the paper's model table): the same operator as e2f_attn_forward with
+ * N(i) restricted to the max_neighbors nearest atoms inside the cutoff (distance compared through the binary32 d^2 of
+ * the cutoff predicate, ties to the lower atom index).  The thresholds are found by a radix select on the GPU inside
+ * the call and kept in two more int32 [N] arrays at the end of the workspace; all three attention kernels apply them.
+ * max_neighbors <= 0: E2F_ERR_INVALID_ARG.  Otherwise as e2f_attn_forward.
+ */
+size_t e2f_attn_capped_workspace_bytes(const e2f_ctx *ctx, int32_t N);
+e2f_status e2f_attn_forward_capped(e2f_ctx *ctx, const e2f_cells *cells, const float *pos, const void *h,
+                                   const int32_t *seg_offsets, int32_t N, int32_t S, const e2f_weights *w,
+                                   int32_t max_neighbors, float *out, void *ws, size_t ws_bytes, void *hip_stream);
+
+/*
+ * Padded neighbour table, the input form of Algorithm 1 (Sec. 3.4: a padded N x K table of neighbour indices).
+ * e2f_build_neighbor_table fills table[i][0 .. count[i]) (device, int32 [N][K], caller's atom numbering) with the at
+ * most K nearest atoms of atom i inside the cutoff (same selection as the cap above, order within a row unspecified
+ * but deterministic) and the rest of the row with -1; count (device int32 [N]) may be null.
+ * e2f_attn_forward_table evaluates the operator with N(i) = the atoms listed in row i (entries < 0, entries equal to
+ * i and entries at zero distance are skipped; the cutoff is not re-applied, so the rows should hold atoms inside
+ * it; entries must be atoms of the same call).  The pair geometry is still built from pos inside the kernel.
+ * Workspace: e2f_attn_table_workspace_bytes.  Both allocate nothing and do not synchronise.
+ */
+e2f_status e2f_build_neighbor_table(e2f_ctx *ctx, const e2f_cells *cells, const float *pos, int32_t N, int32_t K,
+                                    int32_t *table, int32_t *count, void *hip_stream);
+size_t e2f_attn_table_workspace_bytes(const e2f_ctx *ctx, int32_t N);
+e2f_status e2f_attn_forward_table(e2f_ctx *ctx, const e2f_cells *cells, const float *pos, const void *h,
+                                  const int32_t *seg_offsets, int32_t N, int32_t S, const e2f_weights *w,
+                                  const int32_t *table, int32_t K, float *out, void *ws, size_t ws_bytes,
+                                  void *hip_stream);
+
+/*
  * The paper's factorized node-centric pipeline for lf = 1 (Eq. e2former_final with l = 1; Sec. 3.2, three-stage data
  * flow; Sec. 3.4 Algorithm 1): source terms h'_j = v_j (x) R(r_j - o) by node-level EAAS, Algorithm 1 streaming over
  * the precomputed rows [h'_j ; v_j] with scalar weights alpha_ij only, target coupling A1_i - A0_i (x) R(r_i - o).

@@ -189,3 +189,23 @@ def attn_forward(cfg, pos, h, seg_offsets, weights, targets=None, message_mode="
     if rc != 0:
         raise ValueError("oracle rejected the configuration")
     return out
+
+
+def cap_neighbors(pos, offsets, idx, K):
+    """Neighbour cap (the max_neighbors setting of the paper's model table): of every atom's neighbours keep the K
+    nearest.  Distances are compared through the binary32 d^2 of the cutoff predicate ((dx*dx + dy*dy) + dz*dz, every
+    operation rounded to binary32), ties go to the lower atom index.  Returns (offsets, idx), rows in atom order."""
+    p = np.asarray(pos, dtype=np.float32)
+    new_off = np.zeros(len(offsets), dtype=np.int64)
+    rows = []
+    for i in range(len(offsets) - 1):
+        nb = np.asarray(idx[offsets[i]:offsets[i + 1]], dtype=np.int64)
+        if len(nb) > K:
+            d = p[nb] - p[i]
+            d2 = (d[:, 0] * d[:, 0] + d[:, 1] * d[:, 1]) + d[:, 2] * d[:, 2]
+            assert d2.dtype == np.float32
+            keep = np.lexsort((nb, d2))[:K]
+            nb = np.sort(nb[keep])
+        rows.append(nb.astype(np.int32))
+        new_off[i + 1] = new_off[i] + len(nb)
+    return new_off, (np.concatenate(rows) if rows else np.zeros(0, dtype=np.int32)).astype(np.int32)

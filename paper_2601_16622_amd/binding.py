@@ -18,7 +18,9 @@ E2F_F32, E2F_BF16 = 0, 1
 EXPORTS = ["e2f_status_string", "e2f_create", "e2f_destroy", "e2f_cells_workspace_bytes", "e2f_build_cells",
            "e2f_cells_destroy", "e2f_count_neighbors", "e2f_list_neighbors", "e2f_attn_workspace_bytes",
            "e2f_attn_forward", "e2f_attn_forward_materialized", "e2f_profile_begin", "e2f_profile_end",
-           "e2f_eaas_tensor_product", "e2f_attn_factorized_workspace_bytes", "e2f_attn_forward_factorized"]
+           "e2f_eaas_tensor_product", "e2f_attn_factorized_workspace_bytes", "e2f_attn_forward_factorized",
+           "e2f_attn_capped_workspace_bytes", "e2f_attn_forward_capped", "e2f_build_neighbor_table",
+           "e2f_attn_table_workspace_bytes", "e2f_attn_forward_table"]
 STAGES = ("prepare", "project", "attention")
 
 
@@ -76,6 +78,16 @@ def load():
     L.e2f_attn_factorized_workspace_bytes.restype = sz
     L.e2f_attn_forward_factorized.argtypes = [vp, vp, vp, vp, vp, i32, i32, ctypes.POINTER(Weights), vp, vp, sz, vp]
     L.e2f_attn_forward_factorized.restype = ctypes.c_int
+    L.e2f_attn_capped_workspace_bytes.argtypes = [vp, i32]
+    L.e2f_attn_capped_workspace_bytes.restype = sz
+    L.e2f_attn_forward_capped.argtypes = [vp, vp, vp, vp, vp, i32, i32, ctypes.POINTER(Weights), i32, vp, vp, sz, vp]
+    L.e2f_attn_forward_capped.restype = ctypes.c_int
+    L.e2f_build_neighbor_table.argtypes = [vp, vp, vp, i32, i32, vp, vp, vp]
+    L.e2f_build_neighbor_table.restype = ctypes.c_int
+    L.e2f_attn_table_workspace_bytes.argtypes = [vp, i32]
+    L.e2f_attn_table_workspace_bytes.restype = sz
+    L.e2f_attn_forward_table.argtypes = [vp, vp, vp, vp, vp, i32, i32, ctypes.POINTER(Weights), vp, i32, vp, vp, sz, vp]
+    L.e2f_attn_forward_table.restype = ctypes.c_int
     L.e2f_eaas_tensor_product.argtypes = [vp, vp, vp, vp, vp, i32, vp]
     L.e2f_eaas_tensor_product.restype = ctypes.c_int
     L.e2f_profile_begin.argtypes = [vp, i32]
@@ -157,6 +169,36 @@ def e2f_attn_forward(ctx, cells, pos, h, seg_offsets, weights, out, ws):
                                    _ptr(out), _ptr(ws), ws.numel(), _stream()), "e2f_attn_forward")
 
 
+def e2f_attn_capped_workspace_bytes(ctx, N):
+    return load().e2f_attn_capped_workspace_bytes(ctx, N)
+
+
+def e2f_attn_forward_capped(ctx, cells, pos, h, seg_offsets, weights, max_neighbors, out, ws):
+    N, S = pos.shape[0], seg_offsets.shape[0] - 1
+    wt = _weights(weights)
+    _check(load().e2f_attn_forward_capped(ctx, cells, _ptr(pos), _ptr(h), _ptr(seg_offsets), N, S, ctypes.byref(wt),
+                                          int(max_neighbors), _ptr(out), _ptr(ws), ws.numel(), _stream()),
+           "e2f_attn_forward_capped")
+
+
+def e2f_build_neighbor_table(ctx, cells, pos, K, table, count=None):
+    _check(load().e2f_build_neighbor_table(ctx, cells, _ptr(pos), pos.shape[0], int(K), _ptr(table),
+                                           _ptr(count) if count is not None else None, _stream()),
+           "e2f_build_neighbor_table")
+
+
+def e2f_attn_table_workspace_bytes(ctx, N):
+    return load().e2f_attn_table_workspace_bytes(ctx, N)
+
+
+def e2f_attn_forward_table(ctx, cells, pos, h, seg_offsets, weights, table, K, out, ws):
+    N, S = pos.shape[0], seg_offsets.shape[0] - 1
+    wt = _weights(weights)
+    _check(load().e2f_attn_forward_table(ctx, cells, _ptr(pos), _ptr(h), _ptr(seg_offsets), N, S, ctypes.byref(wt),
+                                         _ptr(table), int(K), _ptr(out), _ptr(ws), ws.numel(), _stream()),
+           "e2f_attn_forward_table")
+
+
 def e2f_attn_factorized_workspace_bytes(ctx, N):
     return load().e2f_attn_factorized_workspace_bytes(ctx, N)
 
@@ -234,6 +276,34 @@ class Problem:
     def forward(self):
         e2f_attn_forward(self.ctx, self.cells, self.pos, self.h, self.seg, self.weights, self.out, self.attn_ws)
         return self.out
+
+    def _scratch(self, name, need):
+        import torch
+        buf = getattr(self, name, None)
+        if buf is None or buf.numel() < need:
+            buf = torch.empty(max(need, 256), dtype=torch.uint8, device=self.device)
+            setattr(self, name, buf)
+        return buf
+
+    def forward_capped(self, max_neighbors, out=None):
+        out = self.out if out is None else out
+        ws = self._scratch("cap_ws", e2f_attn_capped_workspace_bytes(self.ctx, self.N))
+        e2f_attn_forward_capped(self.ctx, self.cells, self.pos, self.h, self.seg, self.weights, max_neighbors, out, ws)
+        return out
+
+    def neighbor_table(self, K):
+        """(table [N][K] int32, count [N] int32) on the device."""
+        import torch
+        table = torch.empty((max(self.N, 1), K), dtype=torch.int32, device=self.device)
+        count = torch.empty((max(self.N, 1),), dtype=torch.int32, device=self.device)
+        e2f_build_neighbor_table(self.ctx, self.cells, self.pos, K, table, count)
+        return table, count
+
+    def forward_table(self, table, out=None):
+        out = self.out if out is None else out
+        ws = self._scratch("table_ws", e2f_attn_table_workspace_bytes(self.ctx, self.N))
+        e2f_attn_forward_table(self.ctx, self.cells, self.pos, self.h, self.seg, self.weights, table, table.shape[1], out, ws)
+        return out
 
     def forward_factorized(self, out=None):
         import torch

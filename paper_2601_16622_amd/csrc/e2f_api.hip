@@ -121,6 +121,8 @@ E2fAttnWs e2f_attn_ws_layout(const e2f_ctx* ctx, int32_t N, void* ws, int v_layo
     }
     L.cw = (float*)take((size_t)E2F_MAX_N * E2F_NP * 4);
     L.wbT = (float*)take((size_t)ctx->cfg.B * ctx->cfg.H * 4);
+    L.cap_d2 = nullptr;
+    L.cap_idx = nullptr;
     L.bytes = off;
     return L;
 }
@@ -289,21 +291,36 @@ size_t e2f_attn_workspace_bytes(const e2f_ctx* ctx, int32_t N) {
     return e2f_attn_ws_layout(ctx, N, nullptr, e2f_v_layout(ctx)).bytes;
 }
 
-e2f_status e2f_attn_forward(e2f_ctx* ctx, const e2f_cells* cells, const float* pos, const void* h,
-                            const int32_t* seg_offsets, int32_t N, int32_t S, const e2f_weights* w, float* out,
-                            void* ws, size_t ws_bytes, void* hip_stream) {
+// The fused call, optionally with a neighbour cap K > 0 (threshold keys in two more [N] arrays after the workspace)
+// or over the caller's padded table.
+static e2f_status forward_impl(e2f_ctx* ctx, const e2f_cells* cells, const float* pos, const void* h,
+                               const int32_t* seg_offsets, int32_t N, int32_t S, const e2f_weights* w, float* out,
+                               void* ws, size_t ws_bytes, void* hip_stream, int32_t cap_K, const int32_t* table,
+                               int32_t table_K) {
     e2f_status rc = check_forward_args(ctx, cells, pos, h, seg_offsets, N, S, w, out, ws, ws_bytes);
     if (rc != E2F_OK || N == 0) return rc;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
-    const E2fAttnWs L = e2f_attn_ws_layout(ctx, N, ws, e2f_v_layout(ctx));
+    // the table form runs on the ALU kernel, which reads the plain layout
+    const int v_layout = table ? 0 : e2f_v_layout(ctx);
+    E2fAttnWs L = e2f_attn_ws_layout(ctx, N, ws, v_layout);
+    if (cap_K > 0) {
+        if (ws_bytes < L.bytes + 2 * e2f_align_up((size_t)N * 4)) return E2F_ERR_WORKSPACE_TOO_SMALL;
+        uint32_t* cd = reinterpret_cast<uint32_t*>(static_cast<char*>(ws) + L.bytes);
+        int32_t* ci = reinterpret_cast<int32_t*>(static_cast<char*>(ws) + L.bytes + e2f_align_up((size_t)N * 4));
+        if ((rc = e2f_launch_select_neighbors(ctx, cells->view, pos, cap_K, cd, ci, nullptr, nullptr, st)) != E2F_OK)
+            return rc;
+        L.cap_d2 = cd;
+        L.cap_idx = ci;
+    }
     hipEvent_t* ev = (ctx->prof_events && ctx->prof_calls < ctx->prof_capacity)
                          ? ctx->prof_events + ctx->prof_calls * (E2F_N_STAGES + 1) : nullptr;
     if (ev) E2F_HIP_CHECK(hipEventRecord(ev[0], st));
     if ((rc = e2f_launch_prepare(ctx, cells->view, pos, w, L, st)) != E2F_OK) return rc;
     if (ev) E2F_HIP_CHECK(hipEventRecord(ev[1], st));
-    if ((rc = e2f_launch_project_mfma(ctx, cells->view, h, w, L, e2f_v_layout(ctx), st)) != E2F_OK) return rc;
+    if ((rc = e2f_launch_project_mfma(ctx, cells->view, h, w, L, v_layout, st)) != E2F_OK) return rc;
     if (ev) E2F_HIP_CHECK(hipEventRecord(ev[2], st));
-    rc = ctx->use_tile_attn   ? e2f_launch_tile(ctx, cells->view, L, out, st)
+    rc = table                ? e2f_launch_fused_table(ctx, cells->view, w, L, table, table_K, out, st)
+         : ctx->use_tile_attn ? e2f_launch_tile(ctx, cells->view, L, out, st)
          : ctx->use_mfma_attn ? e2f_launch_fused_mfma(ctx, cells->view, w, L, out, st)
                               : e2f_launch_fused(ctx, cells->view, w, L, out, st);
     if (rc != E2F_OK) return rc;
@@ -312,6 +329,47 @@ e2f_status e2f_attn_forward(e2f_ctx* ctx, const e2f_cells* cells, const float* p
         ctx->prof_calls++;
     }
     return E2F_OK;
+}
+
+e2f_status e2f_attn_forward(e2f_ctx* ctx, const e2f_cells* cells, const float* pos, const void* h,
+                            const int32_t* seg_offsets, int32_t N, int32_t S, const e2f_weights* w, float* out,
+                            void* ws, size_t ws_bytes, void* hip_stream) {
+    return forward_impl(ctx, cells, pos, h, seg_offsets, N, S, w, out, ws, ws_bytes, hip_stream, 0, nullptr, 0);
+}
+
+size_t e2f_attn_capped_workspace_bytes(const e2f_ctx* ctx, int32_t N) {
+    if (!ctx || N < 0) return 0;
+    return e2f_attn_ws_layout(ctx, N, nullptr, e2f_v_layout(ctx)).bytes + 2 * e2f_align_up((size_t)N * 4);
+}
+
+e2f_status e2f_attn_forward_capped(e2f_ctx* ctx, const e2f_cells* cells, const float* pos, const void* h,
+                                   const int32_t* seg_offsets, int32_t N, int32_t S, const e2f_weights* w,
+                                   int32_t max_neighbors, float* out, void* ws, size_t ws_bytes, void* hip_stream) {
+    if (max_neighbors <= 0) return E2F_ERR_INVALID_ARG;
+    return forward_impl(ctx, cells, pos, h, seg_offsets, N, S, w, out, ws, ws_bytes, hip_stream, max_neighbors, nullptr, 0);
+}
+
+e2f_status e2f_build_neighbor_table(e2f_ctx* ctx, const e2f_cells* cells, const float* pos, int32_t N, int32_t K,
+                                    int32_t* table, int32_t* count, void* hip_stream) {
+    if (!ctx || !cells || N != cells->view.N || K <= 0) return E2F_ERR_INVALID_ARG;
+    if (N > 0 && (!pos || !table || pos != cells->pos)) return E2F_ERR_INVALID_ARG;
+    return e2f_launch_select_neighbors(ctx, cells->view, pos, K, nullptr, nullptr, table, count,
+                                       static_cast<hipStream_t>(hip_stream));
+}
+
+size_t e2f_attn_table_workspace_bytes(const e2f_ctx* ctx, int32_t N) {
+    if (!ctx || N < 0) return 0;
+    const size_t a = e2f_attn_ws_layout(ctx, N, nullptr, 0).bytes, b = e2f_attn_workspace_bytes(ctx, N);
+    return a > b ? a : b;
+}
+
+e2f_status e2f_attn_forward_table(e2f_ctx* ctx, const e2f_cells* cells, const float* pos, const void* h,
+                                  const int32_t* seg_offsets, int32_t N, int32_t S, const e2f_weights* w,
+                                  const int32_t* table, int32_t K, float* out, void* ws, size_t ws_bytes,
+                                  void* hip_stream) {
+    if (K <= 0 || (N > 0 && !table)) return E2F_ERR_INVALID_ARG;
+    if (ctx && ws_bytes < e2f_attn_table_workspace_bytes(ctx, N)) return E2F_ERR_WORKSPACE_TOO_SMALL;
+    return forward_impl(ctx, cells, pos, h, seg_offsets, N, S, w, out, ws, ws_bytes, hip_stream, 0, table, K);
 }
 
 static E2fFactWs fact_ws_layout(const e2f_ctx* ctx, int32_t N, void* ws, size_t attn_bytes) {

@@ -247,6 +247,95 @@ __global__ __launch_bounds__(64) void k_neighbors(E2fCellsView cv, const float* 
     if (!LIST && lane == 0) degree[ai] = cnt;
 }
 
+// Neighbour cap: one wave per target finds the K-th smallest key (bits of d^2, atom index) among the target's
+// neighbours inside the cutoff by an 8-bit radix select over the 64-bit keys (one stencil walk per digit, a
+// 256-bin histogram in LDS; no limit on the number of neighbours), then writes the threshold key and / or the
+// table row of the selected atoms (in cell order, -1 padded).  Keys are unique, so exactly min(K, degree) atoms pass.
+__global__ __launch_bounds__(64) void k_select_neighbors(E2fCellsView cv, const float* __restrict__ pos, float rc2,
+                                                         int K, uint32_t* __restrict__ cap_d2,
+                                                         int32_t* __restrict__ cap_idx, int32_t* __restrict__ table,
+                                                         int32_t* __restrict__ count) {
+    __shared__ int s_hist[256];
+    const int t = blockIdx.x, lane = threadIdx.x;
+    const int ai = cv.perm[t];
+    const float xi = pos[3 * ai], yi = pos[3 * ai + 1], zi = pos[3 * ai + 2];
+    int lo[9], hi[9];
+    e2f::stencil_rows(cv, t, lo, hi);
+    // walk(f): f(ok, key, atom) for every candidate of this lane, all lanes in step
+    auto walk = [&](auto&& f) {
+        for (int r = 0; r < 9; ++r)
+            for (int base = lo[r]; base < hi[r]; base += 64) {
+                const int j = base + lane;
+                bool ok = false;
+                int aj = 0;
+                unsigned long long key = ~0ull;
+                if (j < hi[r] && j != t) {
+                    aj = cv.perm[j];
+                    const float d2 = e2f::dist2_exact(xi, yi, zi, pos[3 * aj], pos[3 * aj + 1], pos[3 * aj + 2]);
+                    ok = e2f::is_neighbor(d2, rc2);
+                    key = ((unsigned long long)__float_as_uint(d2) << 32) | (unsigned int)aj;
+                }
+                f(ok, key, aj);
+            }
+    };
+    int total = 0;
+    walk([&](bool ok, unsigned long long, int) { total += __popcll(__ballot(ok)); });
+    unsigned long long thr = ~0ull;   // no cap needed: every neighbour passes
+    if (total > K) {
+        unsigned long long prefix = 0ull;
+        int want = K;   // rank (1-based) of the key looked for among the keys that share the prefix
+        for (int shift = 56; shift >= 0; shift -= 8) {
+            for (int b = lane; b < 256; b += 64) s_hist[b] = 0;
+            __syncthreads();
+            walk([&](bool ok, unsigned long long key, int) {
+                const bool same = shift == 56 || (key >> (shift + 8)) == (prefix >> (shift + 8));
+                if (ok && same) atomicAdd(&s_hist[(int)((key >> shift) & 255ull)], 1);
+            });
+            __syncthreads();
+            // lane l owns bins 4l..4l+3; find the bin where the running count reaches `want`
+            const int h0 = s_hist[4 * lane], h1 = s_hist[4 * lane + 1], h2 = s_hist[4 * lane + 2], h3 = s_hist[4 * lane + 3];
+            int incl = h0 + h1 + h2 + h3;
+            for (int off = 1; off < 64; off <<= 1) {
+                const int v = __shfl_up(incl, off);
+                if (lane >= off) incl += v;
+            }
+            const int before = incl - (h0 + h1 + h2 + h3);
+            const bool mine = before < want && want <= incl;
+            int bin = 0, below = 0;
+            if (mine) {
+                int c = before;
+                if (want <= c + h0) { bin = 4 * lane; below = c; }
+                else if (want <= c + h0 + h1) { bin = 4 * lane + 1; below = c + h0; }
+                else if (want <= c + h0 + h1 + h2) { bin = 4 * lane + 2; below = c + h0 + h1; }
+                else { bin = 4 * lane + 3; below = c + h0 + h1 + h2; }
+            }
+            const int src = __ffsll((long long)__ballot(mine)) - 1;   // exactly one lane
+            bin = __shfl(bin, src);
+            below = __shfl(below, src);
+            prefix |= (unsigned long long)bin << shift;
+            want -= below;
+            __syncthreads();
+        }
+        thr = prefix;
+    }
+    if (lane == 0) {
+        if (cap_d2) cap_d2[t] = (uint32_t)(thr >> 32);
+        if (cap_idx) cap_idx[t] = (thr == ~0ull) ? INT_MAX : (int32_t)(thr & 0xffffffffull);
+        if (count) count[ai] = total < K ? total : K;
+    }
+    if (table) {
+        int32_t* row = table + (size_t)ai * K;
+        int n_out = 0;
+        walk([&](bool ok, unsigned long long key, int aj) {
+            const bool take = ok && key <= thr;
+            const unsigned long long mask = __ballot(take);
+            if (take) row[n_out + __popcll(mask & ((1ull << lane) - 1ull))] = aj;
+            n_out += __popcll(mask);
+        });
+        for (int x = n_out + lane; x < K; x += 64) row[x] = -1;
+    }
+}
+
 }  // namespace
 
 e2f_status e2f_launch_build_cells(const e2f_ctx* ctx, e2f_cells* c, const float* pos, const int32_t* seg_offsets,
@@ -286,6 +375,15 @@ e2f_status e2f_launch_list_neighbors(const e2f_ctx* ctx, const E2fCellsView& cv,
                                      const int64_t* offsets, int32_t* idx, hipStream_t st) {
     if (cv.N == 0) return E2F_OK;
     k_neighbors<true><<<cv.N, 64, 0, st>>>(cv, pos, ctx->rc2, nullptr, offsets, idx);
+    E2F_HIP_CHECK(hipGetLastError());
+    return E2F_OK;
+}
+
+e2f_status e2f_launch_select_neighbors(const e2f_ctx* ctx, const E2fCellsView& cv, const float* pos, int32_t K,
+                                       uint32_t* cap_d2, int32_t* cap_idx, int32_t* table, int32_t* count,
+                                       hipStream_t st) {
+    if (cv.N == 0) return E2F_OK;
+    k_select_neighbors<<<cv.N, 64, 0, st>>>(cv, pos, ctx->rc2, K, cap_d2, cap_idx, table, count);
     E2F_HIP_CHECK(hipGetLastError());
     return E2F_OK;
 }

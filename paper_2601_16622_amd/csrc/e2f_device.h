@@ -27,6 +27,15 @@ __device__ __forceinline__ float dist2_exact(float xi, float yi, float zi, float
 
 __device__ __forceinline__ bool is_neighbor(float d2, float rc2) { return d2 < rc2 && d2 > 0.0f; }
 
+// Neighbour cap (the max_neighbors setting of the paper's model table): with a cap K, atom j counts for target i
+// only if the pair's key (bits of d^2, atom index of j) is not above the target's threshold key, the K-th smallest
+// key among its neighbours inside the cutoff (nearest first, ties to the lower atom index).  Without a cap the
+// threshold is (0xffffffff, INT_MAX), above every key.  `w` is the w component of a sorted position: the atom index.
+__device__ __forceinline__ bool under_cap(float d2, float w, uint32_t cap_d2, int cap_idx) {
+    const uint32_t b = __float_as_uint(d2);
+    return b < cap_d2 || (b == cap_d2 && __float_as_int(w) <= cap_idx);
+}
+
 // The 27-cell stencil of a target as 9 contiguous runs of sorted slots (cells along x are adjacent in the
 // sorted order).  Runs that fall outside the segment's grid come back empty.
 __device__ __forceinline__ void stencil_rows(const E2fCellsView& cv, int slot, int (&lo)[9], int (&hi)[9]) {

@@ -8,6 +8,7 @@
 //   all lanes       logits of the chunk (q.k reduced over the lanes of a head), chunk maximum, one rescale
 //                   of the running (mu, z, A) per chunk, then per pair: A += e^{s-mu} phi D^T P D v_j
 // Nothing per pair is written to global memory; out_i = A/z is stored once, in the caller's atom order.
+#include <limits.h>
 #include <stdlib.h>
 
 #include "e2f_device.h"
@@ -22,6 +23,10 @@ struct FusedParams {
     const void* v;
     const float* cw;
     const float* Wb;
+    const uint32_t* cap_d2;   // neighbour cap thresholds per sorted slot, or null
+    const int32_t* cap_idx;
+    const int32_t* table;     // TABLE kernels: padded neighbour table [N][K] in the caller's atom order, -1 = empty
+    int K;
     float* out;
     int C, H, B, Ch;
     float tau, rc2, cutoff, rbf_step, rbf_gamma;
@@ -30,7 +35,9 @@ struct FusedParams {
 constexpr int PB = 16;    // pairs per chunk
 constexpr int CAP = 192;  // capacity of the neighbour list in LDS
 
-template <int L, int LF, int CPL, typename VT>
+// TABLE: the neighbours come from the caller's padded table (the input form of Algorithm 1) instead of the cell walk;
+// the pair geometry is still built from the positions.
+template <int L, int LF, int CPL, typename VT, bool TABLE>
 __global__ __launch_bounds__(64) void k_fused_valu(FusedParams P) {
     constexpr int n = (L + 1) * (L + 1);
     constexpr int DS = e2f::d_offset(L + 1);
@@ -49,6 +56,8 @@ __global__ __launch_bounds__(64) void k_fused_valu(FusedParams P) {
     const int head = c0 / P.Ch;
     const int lanes_per_head = P.Ch / CPL;
     const float4 pi = P.spos[t];
+    const uint32_t capd = P.cap_d2 ? P.cap_d2[t] : 0xffffffffu;
+    const int capi = P.cap_idx ? P.cap_idx[t] : INT_MAX;
 
     float q[L + 1][CPL];
 #pragma unroll
@@ -68,10 +77,26 @@ __global__ __launch_bounds__(64) void k_fused_valu(FusedParams P) {
 
     int row = 0, base = lo[0];
     bool rows_done = false;
+    const int32_t* trow = TABLE ? P.table + (size_t)P.cv.perm[t] * P.K : nullptr;
+    int tb = 0;
     while (true) {
         // ---- fill the list
         int cnt = 0;
-        while (!rows_done && cnt + 64 <= CAP) {
+        while (TABLE && !rows_done && cnt + 64 <= CAP) {
+            if (tb >= P.K) { rows_done = true; break; }
+            const int aj = tb + lane < P.K ? trow[tb + lane] : -1;
+            const int j = aj >= 0 ? P.cv.atom_slot[aj] : -1;
+            bool ok = false;
+            if (j >= 0 && j != t) {
+                const float4 pj = P.spos[j];
+                ok = e2f::dist2_exact(pi.x, pi.y, pi.z, pj.x, pj.y, pj.z) > 0.0f;
+            }
+            const unsigned long long mask = __ballot(ok);
+            if (ok) s_list[cnt + __popcll(mask & ((1ull << lane) - 1ull))] = j;
+            cnt += __popcll(mask);
+            tb += 64;
+        }
+        while (!TABLE && !rows_done && cnt + 64 <= CAP) {
             if (base >= hi[row]) {
                 ++row;
                 if (row == 9) { rows_done = true; break; }
@@ -82,7 +107,8 @@ __global__ __launch_bounds__(64) void k_fused_valu(FusedParams P) {
             bool ok = false;
             if (j < hi[row] && j != t) {
                 const float4 pj = P.spos[j];
-                ok = e2f::is_neighbor(e2f::dist2_exact(pi.x, pi.y, pi.z, pj.x, pj.y, pj.z), P.rc2);
+                const float d2 = e2f::dist2_exact(pi.x, pi.y, pi.z, pj.x, pj.y, pj.z);
+                ok = e2f::is_neighbor(d2, P.rc2) && e2f::under_cap(d2, pj.w, capd, capi);
             }
             const unsigned long long mask = __ballot(ok);
             if (ok) s_list[cnt + __popcll(mask & ((1ull << lane) - 1ull))] = j;
@@ -170,10 +196,16 @@ __global__ __launch_bounds__(64) void k_fused_valu(FusedParams P) {
 
 template <int L, int LF, int CPL>
 void launch_valu_dtype(const e2f_ctx* ctx, const FusedParams& P, hipStream_t st) {
-    if (ctx->cfg.feat_dtype == E2F_BF16)
-        k_fused_valu<L, LF, CPL, uint16_t><<<e2f::xcd_grid(P.cv.N), 64, 0, st>>>(P);
+    const int grid = e2f::xcd_grid(P.cv.N);
+    if (P.table) {
+        if (ctx->cfg.feat_dtype == E2F_BF16)
+            k_fused_valu<L, LF, CPL, uint16_t, true><<<grid, 64, 0, st>>>(P);
+        else
+            k_fused_valu<L, LF, CPL, float, true><<<grid, 64, 0, st>>>(P);
+    } else if (ctx->cfg.feat_dtype == E2F_BF16)
+        k_fused_valu<L, LF, CPL, uint16_t, false><<<grid, 64, 0, st>>>(P);
     else
-        k_fused_valu<L, LF, CPL, float><<<e2f::xcd_grid(P.cv.N), 64, 0, st>>>(P);
+        k_fused_valu<L, LF, CPL, float, false><<<grid, 64, 0, st>>>(P);
 }
 
 template <int L, int LF>
@@ -199,12 +231,13 @@ bool launch_valu_lf(const e2f_ctx* ctx, const FusedParams& P, hipStream_t st) {
 
 }  // namespace
 
-e2f_status e2f_launch_fused(const e2f_ctx* ctx, const E2fCellsView& cv, const e2f_weights* w, const E2fAttnWs& ws,
-                            float* out, hipStream_t st) {
+static e2f_status launch_valu(const e2f_ctx* ctx, const E2fCellsView& cv, const e2f_weights* w, const E2fAttnWs& ws,
+                              const int32_t* table, int32_t K, float* out, hipStream_t st) {
     if (cv.N == 0) return E2F_OK;
     FusedParams P;
     P.cv = cv;
     P.spos = ws.spos; P.q = ws.q; P.k = ws.k; P.v = ws.v; P.cw = ws.cw; P.Wb = w->Wb; P.out = out;
+    P.cap_d2 = ws.cap_d2; P.cap_idx = ws.cap_idx; P.table = table; P.K = K;
     P.C = ctx->cfg.C; P.H = ctx->cfg.H; P.B = ctx->cfg.B; P.Ch = ctx->Ch;
     P.tau = ctx->tau; P.rc2 = ctx->rc2; P.cutoff = ctx->cfg.cutoff; P.rbf_step = ctx->rbf_step; P.rbf_gamma = ctx->rbf_gamma;
     bool ok = false;
@@ -218,4 +251,14 @@ e2f_status e2f_launch_fused(const e2f_ctx* ctx, const E2fCellsView& cv, const e2
     if (!ok) return E2F_ERR_UNSUPPORTED;
     E2F_HIP_CHECK(hipGetLastError());
     return E2F_OK;
+}
+
+e2f_status e2f_launch_fused(const e2f_ctx* ctx, const E2fCellsView& cv, const e2f_weights* w, const E2fAttnWs& ws,
+                            float* out, hipStream_t st) {
+    return launch_valu(ctx, cv, w, ws, nullptr, 0, out, st);
+}
+
+e2f_status e2f_launch_fused_table(const e2f_ctx* ctx, const E2fCellsView& cv, const e2f_weights* w, const E2fAttnWs& ws,
+                                  const int32_t* table, int32_t K, float* out, hipStream_t st) {
+    return launch_valu(ctx, cv, w, ws, table, K, out, st);
 }

@@ -25,6 +25,8 @@
 #include <stdio.h>
 #include <stdlib.h>
 
+#include <limits.h>
+
 #include "e2f_device.h"
 
 namespace {
@@ -43,6 +45,8 @@ struct MfmaParams {
     const uint16_t* vt;  // [slot][H][NT][16 channels][16 tile rows] bf16
     const float* cw;
     const float* WbT;  // [B][H]
+    const uint32_t* cap_d2;   // neighbour cap thresholds per sorted slot, or null
+    const int32_t* cap_idx;
     float* out;
     int B, lf;
     float tau, rc2, cutoff, rbf_step, rbf_gamma;
@@ -99,6 +103,8 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) void
     if (t < 0) return;  // padding block of the XCD map (whole wave)
     const int lane = threadIdx.x, i = lane & 15, g = lane >> 4;
     const float4 pi = P.spos[t];
+    const uint32_t capd = P.cap_d2 ? P.cap_d2[t] : 0xffffffffu;
+    const int capi = P.cap_idx ? P.cap_idx[t] : INT_MAX;
     for (int x = lane; x < (L + 1) * (L + 1) * E2F_NP; x += 64) s_cw[x] = P.cw[x];
     __syncthreads();
 
@@ -190,8 +196,9 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) void
             }
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
-                const bool ok = jj[u] >= 0 && jj[u] != t &&
-                                e2f::is_neighbor(e2f::dist2_exact(pi.x, pi.y, pi.z, pj[u].x, pj[u].y, pj[u].z), P.rc2);
+                const float d2 = e2f::dist2_exact(pi.x, pi.y, pi.z, pj[u].x, pj[u].y, pj[u].z);
+                const bool ok = jj[u] >= 0 && jj[u] != t && e2f::is_neighbor(d2, P.rc2) &&
+                                e2f::under_cap(d2, pj[u].w, capd, capi);
                 const unsigned long long mask = __ballot(ok);
                 if (ok) s_list[cnt + __popcll(mask & ((1ull << lane) - 1ull))] = jj[u];
                 cnt += __popcll(mask);
@@ -418,6 +425,7 @@ e2f_status e2f_launch_fused_mfma(const e2f_ctx* ctx, const E2fCellsView& cv, con
     MfmaParams P;
     P.cv = cv;
     P.spos = ws.spos; P.q = ws.q; P.k = ws.k; P.vt = (const uint16_t*)ws.v; P.cw = ws.cw; P.WbT = ws.wbT; P.out = out;
+    P.cap_d2 = ws.cap_d2; P.cap_idx = ws.cap_idx;
     P.B = ctx->cfg.B;
     P.lf = ctx->cfg.lf;
     P.dbg = nullptr;

@@ -69,6 +69,9 @@ struct E2fAttnWs {
     void* v;        // [N][n][C] sorted order, float or bf16 (follows feat_dtype)
     float* cw;      // [n][E2F_NP] P coefficients times path weights
     float* wbT;     // [B][H] radial bias weights, transposed
+    // neighbour cap: threshold key of every sorted slot (null when the call has no cap); see under_cap()
+    const uint32_t* cap_d2;
+    const int32_t* cap_idx;
     // layout of the tile attention kernel (v_layout 2; q, k, v above are then unused)
     uint16_t* q16;       // [N][H][DKP] binary16, q * tau * log2(e)
     uint16_t* k16;       // [4*ceil(N/4)][H][DKP] binary16
@@ -117,6 +120,13 @@ e2f_status e2f_launch_fused(const e2f_ctx* ctx, const E2fCellsView& cv, const e2
 e2f_status e2f_launch_tensor_product(const e2f_ctx* ctx, const void* h, const float* r, const float* w_path, float* out,
                                      int32_t T, hipStream_t st);
 bool e2f_fused_mfma_supported(const e2f_ctx* ctx);
+// K-th smallest neighbour key of every atom (threshold arrays in sorted-slot order) and / or the padded table of
+// the at most K nearest neighbours in the caller's atom order; any of the outputs may be null.
+e2f_status e2f_launch_select_neighbors(const e2f_ctx* ctx, const E2fCellsView& cv, const float* pos, int32_t K,
+                                       uint32_t* cap_d2, int32_t* cap_idx, int32_t* table, int32_t* count,
+                                       hipStream_t st);
+e2f_status e2f_launch_fused_table(const e2f_ctx* ctx, const E2fCellsView& cv, const e2f_weights* w, const E2fAttnWs& ws,
+                                  const int32_t* table, int32_t K, float* out, hipStream_t st);
 bool e2f_tile_supported(const e2f_ctx* ctx);
 e2f_status e2f_launch_tile(const e2f_ctx* ctx, const E2fCellsView& cv, const E2fAttnWs& ws, float* out, hipStream_t st);
 e2f_status e2f_launch_fused_mfma(const e2f_ctx* ctx, const E2fCellsView& cv, const e2f_weights* w, const E2fAttnWs& ws,

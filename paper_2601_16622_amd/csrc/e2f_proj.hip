@@ -19,7 +19,7 @@ struct CoefTable {
     float c[E2F_MAX_N][E2F_NP];
 };
 
-// spos[slot] = position of the atom in that slot; cw[comp][t] = P coefficient times its path weight.
+// spos[slot] = position of the atom in that slot (w carries its index in the caller's order); cw[comp][t] = P coefficient times its path weight.
 __global__ void k_prepare(E2fCellsView cv, const float* __restrict__ pos, const float* __restrict__ w_path, int L,
                           int lf, CoefTable tab, float4* __restrict__ spos, float* __restrict__ cw,
                           const float* __restrict__ Wb, int H, int B, float* __restrict__ wbT) {
@@ -27,7 +27,7 @@ __global__ void k_prepare(E2fCellsView cv, const float* __restrict__ pos, const 
     if (t < H * B) wbT[(t % B) * H + t / B] = Wb[t];
     if (t < cv.N) {
         const int a = cv.perm[t];
-        spos[t] = make_float4(pos[3 * a], pos[3 * a + 1], pos[3 * a + 2], 0.0f);
+        spos[t] = make_float4(pos[3 * a], pos[3 * a + 1], pos[3 * a + 2], __int_as_float(a));   // w: the atom index
     }
     const int n = (L + 1) * (L + 1);
     if (t < n * E2F_NP) {

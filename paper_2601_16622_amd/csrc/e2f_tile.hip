@@ -18,6 +18,7 @@
 // The logits come out as S^T[candidate row 4g+r][target i] for two 16-candidate halves; read as the A operand of the
 // aggregation the same registers are W[target i][k = 8g + r'] with k -> (first half, row 4g+r') for r' < 4 and
 // (second half, row 4g+r'-4) otherwise, and the V operand is loaded in that same order of k.
+#include <limits.h>
 #include <stdio.h>
 #include <stdlib.h>
 
@@ -47,6 +48,8 @@ struct TileParams {
     const uint16_t *q16, *k16, *v4;
     const float* G;
     const float* WbT;
+    const uint32_t* cap_d2;   // neighbour cap thresholds per sorted slot, or null
+    const int32_t* cap_idx;
     float* out;
     int C, H, B, n_tiles;
     float rc2, cutoff, rbf_step, rbf_gamma;
@@ -156,6 +159,8 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(E2F_TIL
     const int t0 = tile * 16, nt = min(16, N - t0);
     const int tslot = min(t0 + tn, N - 1);
     const float4 tp = P.spos[tslot];
+    const uint32_t capd = P.cap_d2 ? P.cap_d2[tslot] : 0xffffffffu;
+    const int capi = P.cap_idx ? P.cap_idx[tslot] : INT_MAX;
     const int tseg = P.cv.sseg[tslot];
     int tcx, trow;
     {
@@ -361,7 +366,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(E2F_TIL
                             const float d2 = e2f::dist2_exact(tp.x, tp.y, tp.z, pc.x, pc.y, pc.z);
                             // (bitwise on purpose: the eight candidates are evaluated side by side)
                             const bool ok = (((e >> r) & 1) != 0) & t_active & ((4 * (e >> 4) + r) != t0 + tn) &
-                                            (d2 < P.rc2) & (d2 > 0.0f);
+                                            (d2 < P.rc2) & (d2 > 0.0f) & e2f::under_cap(d2, pc.w, capd, capi);
                             const float d = __builtin_amdgcn_sqrtf(d2);
                             const float uu = __builtin_amdgcn_exp2f(c_u * d);
                             float poly = cb[7];
@@ -525,6 +530,7 @@ e2f_status e2f_launch_tile(const e2f_ctx* ctx, const E2fCellsView& cv, const E2f
     TileParams P;
     P.cv = cv;
     P.spos = ws.spos; P.q16 = ws.q16; P.k16 = ws.k16; P.v4 = ws.v4; P.G = ws.G; P.WbT = ws.wbT;
+    P.cap_d2 = ws.cap_d2; P.cap_idx = ws.cap_idx;
     P.out = out;
     P.C = ctx->cfg.C; P.H = ctx->cfg.H; P.B = ctx->cfg.B; P.n_tiles = (cv.N + 15) / 16;
     P.rc2 = ctx->rc2; P.cutoff = ctx->cfg.cutoff; P.rbf_step = ctx->rbf_step; P.rbf_gamma = ctx->rbf_gamma;

@@ -115,6 +115,28 @@ def test_factorized_entry_point_sizes_and_limits(lib):
             B.e2f_destroy(ctx)
 
 
+def test_cap_and_table_entry_points_reject_bad_arguments(lib):
+    ctx = B.e2f_create(1, 16, 2, 8, 1, 5.0, "f32")
+    try:
+        cells = ctypes.c_void_p()
+        null = ctypes.c_void_p(0)
+        assert lib.e2f_build_cells(ctx, null, null, 0, 0, null, 0, ctypes.byref(cells), null) == 0
+        w = B.Weights(*([0] * 7))
+        # an empty problem is fine; a cap or a table width of zero is not; a null table with atoms is not
+        assert lib.e2f_attn_forward_capped(ctx, cells, null, null, null, 0, 0, ctypes.byref(w), 8, null, null, 0, null) == 0
+        assert lib.e2f_attn_forward_capped(ctx, cells, null, null, null, 0, 0, ctypes.byref(w), 0, null, null, 0, null) == 1
+        assert lib.e2f_attn_forward_table(ctx, cells, null, null, null, 0, 0, ctypes.byref(w), null, 0, null, null, 0, null) == 1
+        assert lib.e2f_attn_forward_table(ctx, cells, null, null, null, 5, 1, ctypes.byref(w), null, 4, null, null, 0, null) == 1
+        assert lib.e2f_build_neighbor_table(ctx, cells, null, 0, 0, null, null, null) == 1
+        assert lib.e2f_build_neighbor_table(ctx, cells, null, 3, 4, null, null, null) == 1   # N does not match the cells
+        n = 10_000
+        assert B.e2f_attn_capped_workspace_bytes(ctx, n) - B.e2f_attn_workspace_bytes(ctx, n) == 2 * ((n * 4 + 255) // 256 * 256)
+        assert B.e2f_attn_table_workspace_bytes(ctx, n) >= B.e2f_attn_workspace_bytes(ctx, n)
+        lib.e2f_cells_destroy(cells)
+    finally:
+        B.e2f_destroy(ctx)
+
+
 def test_axis_operator_pattern_matches_the_dense_definition():
     """The compile-time sparsity pattern of the three axis operators G_mu = (.) (x) R^(1)(e_mu) used by the tile kernel
     is exactly the non-zero pattern of the oracle's dense Clebsch-Gordan message for r = e_mu (216 entries, L_max = 4)."""

@@ -148,6 +148,110 @@ def test_each_attention_kernel_matches_the_oracle(torch_cuda, name, kernel, monk
     run_case(torch_cuda, wl, tg, check_materialized=False, message_mode="eaas")
 
 
+def _capped_case(torch, wl, K):
+    """(Problem, oracle neighbour lists capped to the K nearest, oracle output for them)."""
+    import oracle as O
+    from paper_2601_16622_amd import binding as B
+    cfg = wl["cfg"]
+    P = B.Problem(wl)
+    P.build_cells()
+    offs, idx = O.neighbor_list(wl["pos"], wl["seg"], np.float32(cfg["cutoff"]), use_cells=False)
+    c_offs, c_idx = O.cap_neighbors(wl["pos"], offs, idx, K)
+    ref = O.attn_forward(cfg, wl["pos"], wl["h"], wl["seg"], wl["weights"], nbr=(c_offs, c_idx), message_mode="eaas")
+    return P, (offs, idx), (c_offs, c_idx), ref
+
+
+@pytest.mark.parametrize("K", [5, 16])
+def test_neighbor_table_holds_the_k_nearest(torch_cuda, K):
+    """e2f_build_neighbor_table against the oracle's selection rule: same set in every row (order within a row is free),
+    same counts, -1 padding; segments, a ragged last row and atoms with fewer than K neighbours included."""
+    wl = _custom(11, 700, 1, 32, 2, 4, 1, "f32", cutoff=3.2, side=13.0, seg=[0, 3, 4, 350, 700])
+    P, (offs, idx), (c_offs, c_idx), _ = _capped_case(torch_cuda, wl, K)
+    try:
+        table, count = P.neighbor_table(K)
+        torch_cuda.cuda.synchronize()
+        table, count = table.cpu().numpy(), count.cpu().numpy()
+        deg = np.diff(offs)
+        assert np.array_equal(count, np.minimum(deg, K))
+        assert (deg > K).any() and (deg < K).any()
+        for i in range(P.N):
+            row = table[i]
+            assert np.array_equal(np.sort(row[:count[i]]), c_idx[c_offs[i]:c_offs[i + 1]]), i
+            assert (row[count[i]:] == -1).all()
+    finally:
+        P.close()
+
+
+@pytest.mark.parametrize("kernel", ["tile", "pair", "valu"])
+def test_capped_forward_matches_the_oracle(torch_cuda, kernel, monkeypatch):
+    """max_neighbors = 12 (about a third of the mean degree) through each attention kernel."""
+    monkeypatch.setenv("E2F_ATTENTION", kernel)
+    wl = _custom(12, 500, 3, 64, 4, 6, 1, "bf16", cutoff=4.0, side=11.0, seg=[0, 200, 500])
+    P, _, _, ref = _capped_case(torch_cuda, wl, 12)
+    try:
+        P.out.fill_(float("nan"))
+        P.forward_capped(12)
+        torch_cuda.cuda.synchronize()
+        got = P.out.cpu().numpy().astype(np.float64)
+        assert rel_l2(got, ref) <= TOL["bf16"]
+        P.forward()   # and the cap really changes the result
+        torch_cuda.cuda.synchronize()
+        assert rel_l2(P.out.cpu().numpy().astype(np.float64), ref) > 0.05
+    finally:
+        P.close()
+
+
+def test_capped_forward_fp32_and_no_effect_above_the_degree(torch_cuda):
+    wl = _custom(13, 300, 2, 32, 2, 8, 1, "f32", cutoff=3.5, side=9.0)
+    P, (offs, _), _, ref = _capped_case(torch_cuda, wl, 7)
+    try:
+        P.forward_capped(7)
+        torch_cuda.cuda.synchronize()
+        assert rel_l2(P.out.cpu().numpy().astype(np.float64), ref) <= TOL["f32"]
+        full = P.forward().clone()
+        P.forward_capped(int(np.diff(offs).max()))   # a cap at the largest degree changes nothing
+        torch_cuda.cuda.synchronize()
+        assert torch_cuda.equal(full, P.out)
+    finally:
+        P.close()
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_forward_over_a_padded_table(torch_cuda, dtype):
+    """e2f_attn_forward_table: the library's own table, and a hand-made one (a random subset of the true neighbours in
+    shuffled order, with holes, a self entry and repeated padding) against the oracle run on the same lists."""
+    import oracle as O
+    wl = _custom(14, 260, 2, 32, 2, 8, 1, dtype, cutoff=3.5, side=8.5, seg=[0, 100, 260])
+    K = 16
+    P, (offs, idx), (c_offs, c_idx), ref = _capped_case(torch_cuda, wl, K)
+    try:
+        table, _ = P.neighbor_table(K)
+        out = torch_cuda.full_like(P.out, float("nan"))
+        P.forward_table(table, out)
+        torch_cuda.cuda.synchronize()
+        assert rel_l2(out.cpu().numpy().astype(np.float64), ref) <= TOL[dtype]
+        rng = np.random.default_rng(5)
+        hand = -np.ones((P.N, K + 3), dtype=np.int32)
+        rows, h_off = [], np.zeros(P.N + 1, dtype=np.int64)
+        for i in range(P.N):
+            nb = idx[offs[i]:offs[i + 1]]
+            pick = rng.permutation(nb)[:rng.integers(0, min(len(nb), K) + 1)]
+            slots = rng.permutation(K + 3)[:len(pick)]
+            hand[i, slots] = pick
+            free = np.setdiff1d(np.arange(K + 3), slots)
+            hand[i, free[0]] = i            # a self entry is ignored
+            rows.append(np.sort(pick).astype(np.int32))
+            h_off[i + 1] = h_off[i] + len(pick)
+        h_idx = np.concatenate(rows).astype(np.int32)
+        cfg = wl["cfg"]
+        ref2 = O.attn_forward(cfg, wl["pos"], wl["h"], wl["seg"], wl["weights"], nbr=(h_off, h_idx), message_mode="eaas")
+        P.forward_table(torch_cuda.from_numpy(hand).to(P.device), out)
+        torch_cuda.cuda.synchronize()
+        assert rel_l2(out.cpu().numpy().astype(np.float64), ref2) <= TOL[dtype]
+    finally:
+        P.close()
+
+
 def test_isolated_atoms_and_crowded_cells(torch_cuda):
     """Atoms with no neighbour give zeros; a target with more neighbours than one LDS list holds still matches."""
     from paper_2601_16622_amd import workloads as W
