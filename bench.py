@@ -280,8 +280,11 @@ def main():
     if args.sweep:
         rows = [{"N": N, "forward_ms": round(fwd_ms, 4), "step_ms": round(ms_per_step, 4),
                  "peak_activation_bytes": result["peak_activation_bytes"], "pairs": E}]
-        for n_atoms in (20_000, 50_000, 100_000):
-            wl2 = W.box(n_atoms, 0)
+        fcc_rows = []
+        # boxes of the Large-N regime, then the FCC-subsample systems of the paper's inference-scaling experiment
+        for kind, n_atoms in (("box", 20_000), ("box", 50_000), ("box", 100_000),
+                              ("fcc", 1_000), ("fcc", 10_000), ("fcc", 50_000), ("fcc", 100_000)):
+            wl2 = W.box(n_atoms, 0) if kind == "box" else W.fcc_subsample(n_atoms, 0)
             P2 = B.Problem(wl2, "cuda:0")
             for _ in range(3):
                 P2.build_cells()
@@ -299,10 +302,26 @@ def main():
             torch.cuda.synchronize()
             fwd2 = (time.perf_counter() - t0) * 1e2
             deg2, _, _ = P2.neighbors()
-            rows.append({"N": n_atoms, "forward_ms": round(fwd2, 4), "step_ms": round(step2, 4),
-                         "peak_activation_bytes": P2.activation_bytes(), "pairs": int(deg2.sum())})
+            row = {"N": n_atoms, "forward_ms": round(fwd2, 4), "step_ms": round(step2, 4),
+                   "peak_activation_bytes": P2.activation_bytes(), "pairs": int(deg2.sum())}
+            if kind == "fcc":   # with the model's max_neighbors = 32 as well
+                outc = torch.empty_like(P2.out)
+                for _ in range(3):
+                    P2.forward_capped(32, outc)
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                for _ in range(10):
+                    P2.forward_capped(32, outc)
+                torch.cuda.synchronize()
+                row["forward_capped32_ms"] = round((time.perf_counter() - t0) * 1e2, 4)
+                row["atoms_per_s"] = round(n_atoms / (step2 * 1e-3), 1)
+                fcc_rows.append(row)
+            else:
+                rows.append(row)
             P2.close()
             del P2, wl2
+        result["fcc_subsample"] = {"rows": fcc_rows, "recipe": "FCC supercell a=3.8 A, N sites drawn without replacement, "
+                                                               "cutoff 6 A, no periodic images"}
         xs = np.array([r["N"] for r in rows], dtype=np.float64)
         ys = np.array([r["peak_activation_bytes"] for r in rows], dtype=np.float64)
         slope, icpt = np.polyfit(xs, ys, 1)

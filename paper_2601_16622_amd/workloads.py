@@ -147,6 +147,23 @@ def box(n_atoms, seed=0, L=4, C=128, H=8, B=8, cutoff=6.0, dtype="bf16", density
     return _pack(cfg, [dart_throw_box(rng, n_atoms, side)], rng)
 
 
+def fcc_subsample(n_atoms, seed=0, a=3.8, L=4, C=128, H=8, B=8, cutoff=6.0, dtype="bf16"):
+    """The system recipe of the paper's inference-scaling experiment (App. "System generation"): the smallest cubic
+    FCC supercell with lattice constant a that holds n_atoms sites, n_atoms of them drawn without replacement; no
+    periodic images.  A full lattice has 54 sites inside 6 A of a site (12 + 6 + 24 + 12); many pairs are exactly
+    equidistant, which exercises the tie rule of the neighbour cap."""
+    rng = np.random.default_rng(seed)
+    cfg = dict(L=L, C=C, H=H, B=B, lf=1, cutoff=cutoff, dtype=dtype)
+    nc = 1
+    while 4 * nc ** 3 < n_atoms:
+        nc += 1
+    cell = np.stack(np.meshgrid(np.arange(nc), np.arange(nc), np.arange(nc), indexing="ij"), -1).reshape(-1, 3)
+    basis = np.array([[0.0, 0.0, 0.0], [0.0, 0.5, 0.5], [0.5, 0.0, 0.5], [0.5, 0.5, 0.0]])
+    sites = ((cell[:, None, :] + basis[None, :, :]) * a).reshape(-1, 3)
+    keep = rng.choice(len(sites), n_atoms, replace=False)
+    return _pack(cfg, [sites[np.sort(keep)].astype(np.float32)], rng)
+
+
 def scaling_point(seed=0):
     return box(10_000, seed)
 
@@ -162,4 +179,6 @@ def by_name(name, seed=0):
         return scaling_point(seed)
     if name.startswith("box"):
         return box(int(name[3:]), seed)
+    if name.startswith("fcc"):
+        return fcc_subsample(int(name[3:]), seed)
     raise KeyError(name)

@@ -201,6 +201,23 @@ def test_capped_forward_matches_the_oracle(torch_cuda, kernel, monkeypatch):
         P.close()
 
 
+def test_fcc_lattice_with_equidistant_neighbours(torch_cuda):
+    """Sites of an FCC lattice (the paper's scaling systems): shells of exactly equidistant neighbours, pair vectors
+    along the axes and face diagonals (poles of the aligning rotation); full neighbourhoods and a cap that cuts
+    through a shell, where only the index tie rule decides."""
+    from paper_2601_16622_amd import workloads as W
+    wl = W.fcc_subsample(600, 0, L=2, C=64, H=4, dtype="bf16")
+    run_case(torch_cuda, wl, check_materialized=True, message_mode="eaas")
+    P, (offs, _), _, ref = _capped_case(torch_cuda, wl, 20)   # the third shell (24 sites) is cut
+    try:
+        assert np.diff(offs).max() > 40
+        P.forward_capped(20)
+        torch_cuda.cuda.synchronize()
+        assert rel_l2(P.out.cpu().numpy().astype(np.float64), ref) <= TOL["bf16"]
+    finally:
+        P.close()
+
+
 def test_capped_forward_fp32_and_no_effect_above_the_degree(torch_cuda):
     wl = _custom(13, 300, 2, 32, 2, 8, 1, "f32", cutoff=3.5, side=9.0)
     P, (offs, _), _, ref = _capped_case(torch_cuda, wl, 7)
