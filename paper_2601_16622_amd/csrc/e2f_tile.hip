@@ -132,7 +132,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(E2F_TIL
     constexpr int DK = (L + 1) * 16, KS = (DK + 31) / 32, DKP = KS * 32;
     // LDS: the list and the weights while streaming; the same bytes hold the partial outputs at the end
     constexpr int LIST_BYTES = (CAPG + PADE) * 4 + (CAPG + PADE) * 4 * 16, W_BYTES = NW * 3 * 64 * 16;
-    constexpr int PO_BYTES = NW * NX * 64 * 16;   // one mu of the accumulators of all waves
+    constexpr int PO_BYTES = n * 64 * 16;   // one mu of the accumulators of all waves
     constexpr int MAIN_BYTES = LIST_BYTES + W_BYTES > PO_BYTES ? LIST_BYTES + W_BYTES : PO_BYTES;
     __shared__ __attribute__((aligned(16))) unsigned char s_raw[MAIN_BYTES];
     __shared__ __attribute__((aligned(16))) uint16_t s_q[16 * DKP];
@@ -148,9 +148,10 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(E2F_TIL
     int tile, head;
     if (!tile_xcd_remap(blockIdx.x, P.n_tiles, P.H, tile, head)) return;   // whole workgroup
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, tn = lane & 15, g = lane >> 4;
-    // first component of this wave; the last wave is shifted back so that all hold NX real components (it repeats
-    // a few of its neighbour's and leaves them out of the epilogue)
-    const int x0 = min(wave * NX, n - NX);
+    // components [x0, x0 + nxw) belong to this wave: n / NW each, the first n % NW waves one more (NX is the largest)
+    const int nxw = n / NW + (wave < n % NW ? 1 : 0);
+    const int x0 = wave * (n / NW) + min(wave, n % NW);
+    const bool last_x = nxw == NX;   // whether this wave uses accumulator slot NX - 1
 #ifdef E2F_TIMING
     unsigned long long tacc[6] = {0, 0, 0, 0, 0, 0};
     unsigned long long tprev = __builtin_amdgcn_s_memtime();
@@ -243,7 +244,11 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(E2F_TIL
             by0 = fminf(by0, __shfl_xor(by0, off)); by1 = fmaxf(by1, __shfl_xor(by1, off));
             bz0 = fminf(bz0, __shfl_xor(bz0, off)); bz1 = fmaxf(bz1, __shfl_xor(bz1, off));
         }
-        const float prune2 = P.rc2 * 1.001f;
+        // with a neighbour cap no target of the pass reaches beyond its threshold distance
+        float reach2 = t_active ? (capd == 0xffffffffu ? P.rc2 : fminf(P.rc2, __uint_as_float(capd))) : 0.0f;
+#pragma unroll
+        for (int off = 1; off < 16; off <<= 1) reach2 = fmaxf(reach2, __shfl_xor(reach2, off));
+        const float prune2 = reach2 * 1.001f;
 
         const int total = pre[9];
         for (int fbase = 0; fbase < total; fbase += 256) {
@@ -336,7 +341,8 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(E2F_TIL
                 u32x2 va[NX], vb[NX];
                 load_K(min(wave, nch - 1), kf);
 #pragma unroll
-                for (int x = 0; x < NX; ++x) load_V(0, x, va[x], vb[x]);
+                for (int x = 0; x < NX; ++x)
+                    if (x < NX - 1 || last_x) load_V(0, x, va[x], vb[x]);
                 TICK(2)
                 for (int G = 0; G < ngr; ++G) {
                     // ---- logits, pair geometry and cutoff mask of this wave's chunk
@@ -444,12 +450,13 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(E2F_TIL
                             for (int mu = 0; mu < 3; ++mu) W[mu] = __builtin_bit_cast(bf16x8, s_W[(cc * 3 + mu) * 64 + lane]);
                             const int cnext = min(c + 1, nch - 1);
 #pragma unroll
-                            for (int x = 0; x < NX; ++x) {
-                                const bf16x8 bv = __builtin_bit_cast(bf16x8, __builtin_shufflevector(va[x], vb[x], 0, 1, 2, 3));
+                            for (int x = 0; x < NX; ++x)
+                                if (x < NX - 1 || last_x) {   // (wave-uniform)
+                                    const bf16x8 bv = __builtin_bit_cast(bf16x8, __builtin_shufflevector(va[x], vb[x], 0, 1, 2, 3));
 #pragma unroll
-                                for (int mu = 0; mu < 3; ++mu) acc[mu][x] = mfma(W[mu], bv, acc[mu][x]);
-                                load_V(cnext, x, va[x], vb[x]);
-                            }
+                                    for (int mu = 0; mu < 3; ++mu) acc[mu][x] = mfma(W[mu], bv, acc[mu][x]);
+                                    load_V(cnext, x, va[x], vb[x]);
+                                }
                         }
                     }
                 }
@@ -473,7 +480,8 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(E2F_TIL
     for (int mu = 0; mu < 3; ++mu) {
         __syncthreads();
 #pragma unroll
-        for (int x = 0; x < NX; ++x) s_po[(x0 + x) * 64 + lane] = acc[mu][x];   // repeated components hold equal values
+        for (int x = 0; x < NX; ++x)
+            if (x < NX - 1 || last_x) s_po[(x0 + x) * 64 + lane] = acc[mu][x];
         __syncthreads();
 #pragma unroll
         for (int xo = 0; xo < n; ++xo)
