@@ -248,8 +248,9 @@ __global__ __launch_bounds__(64) void k_neighbors(E2fCellsView cv, const float* 
 }
 
 // Neighbour cap: one wave per target finds the K-th smallest key (bits of d^2, atom index) among the target's
-// neighbours inside the cutoff by an 8-bit radix select over the 64-bit keys (one stencil walk per digit, a
-// 256-bin histogram in LDS; no limit on the number of neighbours), then writes the threshold key and / or the
+// neighbours inside the cutoff by an 8-bit radix select over the 64-bit keys (a 256-bin histogram in LDS per digit;
+// the keys are kept in LDS after one stencil walk, or, beyond 512 neighbours, the stencil is walked once per digit,
+// so there is no limit on their number), then writes the threshold key and / or the
 // table row of the selected atoms (in cell order, -1 padded).  Keys are unique, so exactly min(K, degree) atoms pass.
 __global__ __launch_bounds__(64) void k_select_neighbors(E2fCellsView cv, const float* __restrict__ pos, float rc2,
                                                          int K, uint32_t* __restrict__ cap_d2,
@@ -278,8 +279,29 @@ __global__ __launch_bounds__(64) void k_select_neighbors(E2fCellsView cv, const 
                 f(ok, key, aj);
             }
     };
+    // first walk: count the neighbours and keep their keys in LDS while they fit (they do in any physical system)
+    constexpr int KEEP = 512;
+    __shared__ unsigned long long s_key[KEEP];
     int total = 0;
-    walk([&](bool ok, unsigned long long, int) { total += __popcll(__ballot(ok)); });
+    walk([&](bool ok, unsigned long long key, int) {
+        const unsigned long long mask = __ballot(ok);
+        const int at = total + __popcll(mask & ((1ull << lane) - 1ull));
+        if (ok && at < KEEP) s_key[at] = key;
+        total += __popcll(mask);
+    });
+    __syncthreads();
+    const bool in_lds = total <= KEEP;
+    // keys(f): f(ok, key) over all neighbour keys, from LDS or by walking the stencil again
+    auto keys = [&](auto&& f) {
+        if (in_lds) {
+            for (int base = 0; base < total; base += 64) {
+                const bool ok = base + lane < total;
+                f(ok, ok ? s_key[base + lane] : ~0ull);
+            }
+        } else {
+            walk([&](bool ok, unsigned long long key, int) { f(ok, key); });
+        }
+    };
     unsigned long long thr = ~0ull;   // no cap needed: every neighbour passes
     if (total > K) {
         unsigned long long prefix = 0ull;
@@ -287,7 +309,7 @@ __global__ __launch_bounds__(64) void k_select_neighbors(E2fCellsView cv, const 
         for (int shift = 56; shift >= 0; shift -= 8) {
             for (int b = lane; b < 256; b += 64) s_hist[b] = 0;
             __syncthreads();
-            walk([&](bool ok, unsigned long long key, int) {
+            keys([&](bool ok, unsigned long long key) {
                 const bool same = shift == 56 || (key >> (shift + 8)) == (prefix >> (shift + 8));
                 if (ok && same) atomicAdd(&s_hist[(int)((key >> shift) & 255ull)], 1);
             });

@@ -182,6 +182,27 @@ def test_neighbor_table_holds_the_k_nearest(torch_cuda, K):
         P.close()
 
 
+def test_neighbor_table_with_more_neighbours_than_the_selection_keeps_on_chip(torch_cuda):
+    """700 atoms inside one cutoff sphere: every atom has 699 neighbours, above the 512 keys the selection kernel keeps
+    in LDS, so the per-digit stencil walk is used."""
+    from paper_2601_16622_amd import workloads as W
+    rng = np.random.default_rng(21)
+    cfg = dict(L=1, C=32, H=2, B=4, lf=1, cutoff=9.0, dtype="f32")
+    wl = W._pack(cfg, [rng.uniform(0.0, 5.0, size=(700, 3)).astype(np.float32)], rng, elements=False)
+    K = 40
+    P, (offs, idx), (c_offs, c_idx), _ = _capped_case(torch_cuda, wl, K)
+    try:
+        assert np.diff(offs).min() > 512
+        table, count = P.neighbor_table(K)
+        torch_cuda.cuda.synchronize()
+        table, count = table.cpu().numpy(), count.cpu().numpy()
+        assert (count == K).all()
+        for i in range(P.N):
+            assert np.array_equal(np.sort(table[i]), c_idx[c_offs[i]:c_offs[i + 1]]), i
+    finally:
+        P.close()
+
+
 @pytest.mark.parametrize("kernel", ["tile", "pair", "valu"])
 def test_capped_forward_matches_the_oracle(torch_cuda, kernel, monkeypatch):
     """max_neighbors = 12 (about a third of the mean degree) through each attention kernel."""
