@@ -8,6 +8,8 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <type_traits>
+
 #include "e2f_device.h"
 
 namespace {
@@ -730,15 +732,24 @@ bool launch_mfma(const e2f_ctx* ctx, const E2fCellsView& cv, const void* h, cons
         // orders m held in registers at once: bounded by the A fragments (C/KSTEP registers-quads per order)
         constexpr int MG = sizeof(T) == 2 ? (C <= 128 ? 9 : 4) : (C <= 64 ? 9 : (C <= 128 ? 5 : 2));
         constexpr int CT = (C / 16) % 4 == 0 ? 4 : ((C / 16) % 2 == 0 ? 2 : 1);
-        const dim3 grid((cv.N + 15) / 16, ctx->cfg.L_max + 1, C / 16 / CT);
-        if (tiled)
-            k_project_mfma<T, C, MG, CT, true><<<grid, 64, 0, st>>>(cv, (const T*)h, (const T*)w->WQ1, (const T*)w->WQ2,
-                                                                   (const T*)w->WK1, (const T*)w->WK2, (const T*)w->WV,
-                                                                   ctx->cfg.L_max, ws.q, ws.k, (T*)ws.v);
+        // few atoms: one channel tile per wave gives CT times the waves (each h slab is then fetched C/16 times)
+        const int waves_ct = (cv.N + 15) / 16 * (ctx->cfg.L_max + 1) * (C / 16 / CT);
+        auto go = [&](auto ct_tag) {
+            constexpr int ct = decltype(ct_tag)::value;
+            const dim3 grid((cv.N + 15) / 16, ctx->cfg.L_max + 1, C / 16 / ct);
+            if (tiled)
+                k_project_mfma<T, C, MG, ct, true><<<grid, 64, 0, st>>>(cv, (const T*)h, (const T*)w->WQ1, (const T*)w->WQ2,
+                                                                       (const T*)w->WK1, (const T*)w->WK2, (const T*)w->WV,
+                                                                       ctx->cfg.L_max, ws.q, ws.k, (T*)ws.v);
+            else
+                k_project_mfma<T, C, MG, ct, false><<<grid, 64, 0, st>>>(cv, (const T*)h, (const T*)w->WQ1, (const T*)w->WQ2,
+                                                                        (const T*)w->WK1, (const T*)w->WK2, (const T*)w->WV,
+                                                                        ctx->cfg.L_max, ws.q, ws.k, (T*)ws.v);
+        };
+        if (CT > 1 && waves_ct < 4096)
+            go(std::integral_constant<int, 1>{});
         else
-            k_project_mfma<T, C, MG, CT, false><<<grid, 64, 0, st>>>(cv, (const T*)h, (const T*)w->WQ1, (const T*)w->WQ2,
-                                                                    (const T*)w->WK1, (const T*)w->WK2, (const T*)w->WV,
-                                                                    ctx->cfg.L_max, ws.q, ws.k, (T*)ws.v);
+            go(std::integral_constant<int, CT>{});
         return true;
     }
 }
