@@ -166,6 +166,30 @@ def main():
         "roofline": roofline,
     }
 
+    # the same step replayed from a captured graph (the calls allocate nothing and never synchronise)
+    try:
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            step()
+            side.synchronize()
+            with torch.cuda.graph(graph, stream=side):
+                step()
+        torch.cuda.synchronize()
+        for _ in range(3):
+            graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        g_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+        result["graph_replay"] = {"ms_per_step": round(g_ms, 4), "atoms_per_s": round(N / (g_ms * 1e-3), 1)}
+        del graph
+    except Exception as e:   # noqa: BLE001 - a capture problem must not take the benchmark line away
+        result["graph_replay"] = {"error": str(e)[:200]}
+
     # the paper's own factorized pipeline (node-level products around Algorithm 1) on the same inputs
     try:
         if args.no_factorized:

@@ -335,6 +335,49 @@ def test_result_is_deterministic_and_order_equivariant(torch_cuda):
     P2.close()
 
 
+@pytest.mark.parametrize("name", ["tiny", "odd_bf16"])
+def test_step_replays_from_a_captured_graph(torch_cuda, name):
+    """e2f_build_cells + e2f_attn_forward allocate nothing, never synchronise and clear their counters with kernels, so a
+    step can be captured into a graph; every replay (with eager work and synchronisations in between, and with the
+    positions changed before the last one) gives the bits of the eager call."""
+    from paper_2601_16622_amd import binding as B, workloads as W
+    torch = torch_cuda
+    wl = W.tiny(3) if name == "tiny" else _custom(31, 333, 2, 64, 4, 5, 1, "bf16", cutoff=3.5, side=9.0, seg=[0, 150, 333])
+    P = B.Problem(wl)
+    try:
+        def step():
+            P.build_cells()
+            P.forward()
+        step()
+        torch.cuda.synchronize()
+        eager = P.out.clone()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            step()   # warm-up on the capture stream
+            side.synchronize()
+            with torch.cuda.graph(graph, stream=side):
+                step()
+        torch.cuda.synchronize()
+        for rep in range(3):
+            P.out.fill_(float("nan"))
+            _ = (P.h.float() * 2).sum().item()   # eager work and a synchronisation between replays
+            graph.replay()
+            torch.cuda.synchronize()
+            assert torch.equal(P.out, eager), rep
+        # new positions in the same buffers: the replay follows them (cells are rebuilt inside the graph)
+        P.pos.add_(torch.randn_like(P.pos) * 0.05)
+        graph.replay()
+        torch.cuda.synchronize()
+        replayed = P.out.clone()
+        step()
+        torch.cuda.synchronize()
+        assert torch.equal(P.out, replayed)
+    finally:
+        P.close()
+
+
 def test_fused_activation_memory_is_linear_and_below_the_baseline(torch_cuda):
     from paper_2601_16622_amd import binding as B, workloads as W
     wl = W.box(3000, seed=4)
