@@ -359,6 +359,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(E2F_TIL
                             for (int ks = 0; ks < KS; ++ks) S[mt] = mfma(kf[mt][ks], qf[ks], S[mt]);
                         }
                     }
+                    load_K(min(cm + NW, nch - 1), kf);   // k rows of this wave's chunk in the next group
                     float s2[8], gate[8];
                     float cmax = -INFINITY;
 #pragma unroll
@@ -439,7 +440,6 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(E2F_TIL
                             s_W[(wave * 3 + mu) * 64 + lane] = (u32x4){wp[mu][0], wp[mu][1], wp[mu][2], wp[mu][3]};
                     }
                     __syncthreads();
-                    load_K(min(cm + NW, nch - 1), kf);   // k rows of this wave's chunk in the next group
                     // ---- aggregate the chunks of the group into this wave's components
 #pragma unroll
                     for (int cc = 0; cc < NW; ++cc) {
