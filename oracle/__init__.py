@@ -60,7 +60,8 @@ def lib():
         L.e2fo_free.argtypes = [ctypes.c_void_p]
         L.e2fo_free.restype = None
         L.e2fo_attn_forward.argtypes = [ctypes.POINTER(_Config), dp, dp, ctypes.c_int, dp, dp, dp, dp, dp, dp, dp,
-                                        lp, ip, ip, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_double, dp]
+                                        lp, ip, dp, ip, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_double,
+                                        dp]
         L.e2fo_attn_forward.restype = ctypes.c_int
         L.e2fo_num_threads.argtypes = []
         L.e2fo_num_threads.restype = ctypes.c_int
@@ -157,11 +158,100 @@ def neighbor_list(pos, seg_offsets, cutoff, use_cells=False):
     return offsets, idx
 
 
+def wrap_positions(pos, seg_offsets, box):
+    """Coordinates folded into the periodic box, in binary32 with every operation rounded:
+    q = floor(x * inv), inv = 1/len rounded to binary32;  w = x - len*q;  w < 0: w += len;  w >= len: w -= len.
+    box is float [S][3], the edge lengths of every segment's orthorhombic box; an entry <= 0 leaves that axis open.
+    Periodic boundaries are not part of the paper's operator (it takes the pair vectors as given); this is the
+    convention of this build, used for the bulk simulations of the paper's Sec. 4.3."""
+    p = np.array(pos, dtype=np.float32)
+    box = np.asarray(box, dtype=np.float32).reshape(-1, 3)
+    seg = np.asarray(seg_offsets)
+    for s in range(len(seg) - 1):
+        a0, a1 = int(seg[s]), int(seg[s + 1])
+        for k in range(3):
+            ln = np.float32(box[s, k])
+            if not ln > 0:
+                continue
+            inv = np.float32(1.0) / ln
+            x = p[a0:a1, k]
+            q = np.floor(x * inv)
+            w = x - ln * q
+            w = np.where(w < 0, w + ln, w)
+            w = np.where(w >= ln, w - ln, w)
+            assert w.dtype == np.float32
+            p[a0:a1, k] = w
+    return p
+
+
+def neighbor_list_periodic(pos, seg_offsets, cutoff, box):
+    """Neighbour sets under periodic boundaries by brute force over all pairs of a segment.  With w the folded
+    coordinates (wrap_positions), the image of j seen from i along a periodic axis of length len is
+    w_j + s*len with s = +1 if w_i - w_j > len/2, s = -1 if w_j - w_i > len/2, else 0 (binary32); the predicate is
+    the binary32 one of the open case on the image position fl(w_j + s*len).  Every periodic edge length must be at
+    least three cutoffs, so at most one image of an atom lies within the cutoff.
+    Returns (offsets int64 [N+1], idx int32 [E] sorted within a row, shift int8 [E][3])."""
+    w = wrap_positions(pos, seg_offsets, box)
+    box = np.asarray(box, dtype=np.float32).reshape(-1, 3)
+    seg = np.asarray(seg_offsets)
+    N = w.shape[0]
+    rc2 = np.float32(cutoff) * np.float32(cutoff)
+    offsets = np.zeros(N + 1, dtype=np.int64)
+    rows_idx, rows_shift = [], []
+    for s in range(len(seg) - 1):
+        a0, a1 = int(seg[s]), int(seg[s + 1])
+        ws = w[a0:a1]
+        for i in range(a0, a1):
+            d = []
+            sh = np.zeros((a1 - a0, 3), dtype=np.int8)
+            for k in range(3):
+                ln = np.float32(box[s, k])
+                xj = ws[:, k]
+                if ln > 0:
+                    half = ln * np.float32(0.5)
+                    sk = np.where(w[i, k] - xj > half, 1, np.where(xj - w[i, k] > half, -1, 0)).astype(np.int8)
+                    sh[:, k] = sk
+                    xj = xj + sk.astype(np.float32) * ln
+                d.append(xj - w[i, k])
+            d2 = (d[0] * d[0] + d[1] * d[1]) + d[2] * d[2]
+            assert d2.dtype == np.float32
+            ok = (d2 < rc2) & (d2 > 0)
+            ok[i - a0] = False
+            nb = np.nonzero(ok)[0]
+            rows_idx.append((nb + a0).astype(np.int32))
+            rows_shift.append(sh[nb])
+            offsets[i + 1] = offsets[i] + len(nb)
+    idx = np.concatenate(rows_idx) if rows_idx else np.zeros(0, dtype=np.int32)
+    shift = np.concatenate(rows_shift) if rows_shift else np.zeros((0, 3), dtype=np.int8)
+    return offsets, idx.astype(np.int32), shift.astype(np.int8)
+
+
+def edge_translations(seg_offsets, box, offsets, shift):
+    """Lattice translation of every edge's neighbour image, float64 [E][3]: shift * box of the edge's segment."""
+    box = np.asarray(box, dtype=np.float32).reshape(-1, 3).astype(np.float64)
+    seg = np.asarray(seg_offsets)
+    N = len(offsets) - 1
+    atom_seg = np.repeat(np.arange(len(seg) - 1), np.diff(seg))
+    edge_atom = np.repeat(np.arange(N), np.diff(offsets))
+    return shift.astype(np.float64) * np.maximum(box[atom_seg[edge_atom]], 0.0)
+
+
 def attn_forward(cfg, pos, h, seg_offsets, weights, targets=None, message_mode="dense", softmax_mode="twopass",
-                 use_cells=False, chi=0.0, nbr=None):
+                 use_cells=False, chi=0.0, nbr=None, box=None):
     """The operator.  cfg: dict(L, C, H, B, lf, cutoff); weights: dict(WQ1, WQ2, WK1, WK2, WV [L+1][C][C],
-    Wb [H][B], w_path [L+1][L+1]); returns float64 [n_targets][(L+1)^2][C]."""
+    Wb [H][B], w_path [L+1][L+1]); returns float64 [n_targets][(L+1)^2][C].
+    box: None, or float [S][3] periodic edge lengths (see neighbor_list_periodic); nbr is then the triple that
+    function returns, and the pair vectors are r_ij = (w_j + shift*box) - w_i on the folded coordinates w."""
     c = _Config(cfg["L"], cfg["C"], cfg["H"], cfg["B"], cfg["lf"], float(np.float32(cfg["cutoff"])))
+    edge_shift = None
+    if box is not None:
+        if nbr is None:
+            nbr = neighbor_list_periodic(pos, seg_offsets, np.float32(cfg["cutoff"]), box)
+        edge_shift = np.ascontiguousarray(edge_translations(seg_offsets, box, nbr[0], nbr[2]))
+        if edge_shift.size == 0:
+            edge_shift = np.zeros((1, 3))
+        pos = wrap_positions(pos, seg_offsets, box)
+        nbr = (nbr[0], nbr[1])
     pos = _f64(pos)
     h = _f64(h)
     N = pos.shape[0]
@@ -184,28 +274,41 @@ def attn_forward(cfg, pos, h, seg_offsets, weights, targets=None, message_mode="
     rc = lib().e2fo_attn_forward(ctypes.byref(c), _d(pos), _d(h), N,
                                  _d(W["WQ1"]), _d(W["WQ2"]), _d(W["WK1"]), _d(W["WK2"]), _d(W["WV"]), _d(W["Wb"]),
                                  _d(W["w_path"]), offsets.ctypes.data_as(ctypes.POINTER(ctypes.c_int64)),
-                                 idx.ctypes.data_as(ip), tptr, nt, 0 if message_mode == "dense" else 1,
+                                 idx.ctypes.data_as(ip),
+                                 _d(edge_shift) if edge_shift is not None else ctypes.POINTER(ctypes.c_double)(),
+                                 tptr, nt, 0 if message_mode == "dense" else 1,
                                  0 if softmax_mode == "twopass" else 1, float(chi), _d(out))
     if rc != 0:
         raise ValueError("oracle rejected the configuration")
     return out
 
 
-def cap_neighbors(pos, offsets, idx, K):
+def cap_neighbors(pos, offsets, idx, K, translation=None):
     """Neighbour cap (the max_neighbors setting of the paper's model table): of every atom's neighbours keep the K
     nearest.  Distances are compared through the binary32 d^2 of the cutoff predicate ((dx*dx + dy*dy) + dz*dz, every
-    operation rounded to binary32), ties go to the lower atom index.  Returns (offsets, idx), rows in atom order."""
+    operation rounded to binary32), ties go to the lower atom index.  Returns (offsets, idx), rows in atom order.
+    translation: None, or [E][3] lattice translations of the neighbours' periodic images (pos is then the folded
+    positions); a third array, the kept edges' positions in the input list, is returned as well."""
     p = np.asarray(pos, dtype=np.float32)
     new_off = np.zeros(len(offsets), dtype=np.int64)
-    rows = []
+    rows, kept = [], []
     for i in range(len(offsets) - 1):
         nb = np.asarray(idx[offsets[i]:offsets[i + 1]], dtype=np.int64)
+        where = np.arange(offsets[i], offsets[i + 1])
         if len(nb) > K:
-            d = p[nb] - p[i]
+            pj = p[nb]
+            if translation is not None:
+                pj = pj + np.asarray(translation[offsets[i]:offsets[i + 1]], dtype=np.float32)
+            d = pj - p[i]
             d2 = (d[:, 0] * d[:, 0] + d[:, 1] * d[:, 1]) + d[:, 2] * d[:, 2]
             assert d2.dtype == np.float32
             keep = np.lexsort((nb, d2))[:K]
-            nb = np.sort(nb[keep])
+            keep = keep[np.argsort(nb[keep])]
+            nb, where = nb[keep], where[keep]
         rows.append(nb.astype(np.int32))
+        kept.append(where)
         new_off[i + 1] = new_off[i] + len(nb)
-    return new_off, (np.concatenate(rows) if rows else np.zeros(0, dtype=np.int32)).astype(np.int32)
+    new_idx = (np.concatenate(rows) if rows else np.zeros(0, dtype=np.int32)).astype(np.int32)
+    if translation is None:
+        return new_off, new_idx
+    return new_off, new_idx, (np.concatenate(kept) if kept else np.zeros(0, dtype=np.int64)).astype(np.int64)

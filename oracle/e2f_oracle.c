@@ -495,14 +495,18 @@ static void project(const e2fo_config *cfg, const double *W, const double *h_ato
  *   WQ1,WQ2,WK1,WK2,WV double[L+1][C][C] (out channel, in channel); Wb double[H][B];
  *   w_path double[L+1][L+1] indexed [li][lo];
  *   nbr_offsets/nbr_idx: CSR neighbour lists from e2fo_neighbor_list;
+ *   edge_shift: NULL, or double[E][3] beside nbr_idx: the lattice translation of the neighbour's periodic image,
+ *     r_ij = (pos[j] + edge_shift[e]) - pos[i]  (periodic boundaries; not in the paper, which states the operator
+ *     for pair vectors r_ij as given);
  *   message_mode 0 = dense CG contraction, 1 = EAAS (gauge angle chi);
  *   softmax_mode 0 = two-pass softmax, 1 = streaming recurrences of Algorithm 1;
  *   out double[n_targets][n][C].
  */
 int e2fo_attn_forward(const e2fo_config *cfg, const double *pos, const double *h, int N, const double *WQ1,
                       const double *WQ2, const double *WK1, const double *WK2, const double *WV, const double *Wb,
-                      const double *w_path, const int64_t *nbr_offsets, const int32_t *nbr_idx, const int32_t *targets,
-                      int n_targets, int message_mode, int softmax_mode, double chi, double *out) {
+                      const double *w_path, const int64_t *nbr_offsets, const int32_t *nbr_idx,
+                      const double *edge_shift, const int32_t *targets, int n_targets, int message_mode,
+                      int softmax_mode, double chi, double *out) {
     int L = cfg->L, C = cfg->C, H = cfg->H, B = cfg->B, lf = cfg->lf;
     if (L < 0 || L > E2FO_MAX_L || lf < 0 || lf > E2FO_MAX_L || C <= 0 || H <= 0 || C % H != 0 || B <= 0) return 1;
     int n = (L + 1) * (L + 1);
@@ -573,7 +577,8 @@ int e2fo_attn_forward(const e2fo_config *cfg, const double *pos, const double *h
             for (int e = 0; e < K; ++e) {
                 int j = nbr_idx[e0 + e];
                 double r[3];
-                for (int x = 0; x < 3; ++x) r[x] = pos[3 * j + x] - pos[3 * i + x];
+                for (int x = 0; x < 3; ++x)
+                    r[x] = (pos[3 * j + x] + (edge_shift ? edge_shift[3 * (e0 + e) + x] : 0.0)) - pos[3 * i + x];
                 double d = sqrt(r[0] * r[0] + r[1] * r[1] + r[2] * r[2]);
                 for (int x = 0; x < 3; ++x) rij[3 * e + x] = r[x];
                 gate[e] = radial_gate(d, cfg->cutoff);

@@ -164,6 +164,59 @@ def fcc_subsample(n_atoms, seed=0, a=3.8, L=4, C=128, H=8, B=8, cutoff=6.0, dtyp
     return _pack(cfg, [sites[np.sort(keep)].astype(np.float32)], rng)
 
 
+def periodic_boxes(n_atoms=(600,), seed=0, L=4, C=128, H=8, B=8, cutoff=6.0, dtype="bf16", density=0.1, open_axes=()):
+    """Periodic systems (bulk simulation cells, as in the paper's condensed-phase runs, Sec. 4.3): one orthorhombic
+    box per segment at the given number density, edge lengths in the ratio 1 : 1.1 : 0.95, atoms thrown so that
+    periodic images keep the minimum separation too; coordinates are then displaced by whole box lengths for a
+    tenth of the atoms, so callers see coordinates outside [0, len) as an MD run produces them.  Axes listed in
+    open_axes are not periodic (a slab).  The dict carries "box": float32 [S][3], 0 on an open axis."""
+    rng = np.random.default_rng(seed)
+    cfg = dict(L=L, C=C, H=H, B=B, lf=1, cutoff=cutoff, dtype=dtype)
+    pos_list, boxes = [], []
+    for n in n_atoms:
+        base = (n / density / (1.1 * 0.95)) ** (1.0 / 3.0)
+        lens = np.array([base, 1.1 * base, 0.95 * base]).astype(np.float32)
+        lens = np.maximum(lens, np.float32(3.0 * cutoff * 1.001))
+        grid = _Grid(0.9)
+        pts = np.empty((n, 3))
+        k = 0
+        while k < n:
+            for u in rng.uniform(0.0, 1.0, size=(max(256, n - k), 3)):
+                p = 0.45 + u * (lens - 0.9)
+                if grid.ok(p):
+                    grid.add(p)
+                    pts[k] = p
+                    k += 1
+                    if k == n:
+                        break
+        moved = rng.random(n) < 0.1
+        hop = rng.integers(-2, 3, size=(n, 3)) * lens[None, :]
+        for ax in open_axes:
+            hop[:, ax] = 0.0
+        pts = pts + np.where(moved[:, None], hop, 0.0)
+        bx = lens.copy()
+        for ax in open_axes:
+            bx[ax] = 0.0
+        pos_list.append(pts.astype(np.float32))
+        boxes.append(bx)
+    out = _pack(cfg, pos_list, rng)
+    out["box"] = np.stack(boxes).astype(np.float32)
+    return out
+
+
+def periodic_fcc(nc=5, seed=0, a=3.8, L=4, C=128, H=8, B=8, cutoff=6.0, dtype="bf16"):
+    """A full periodic FCC crystal of nc^3 conventional cells (lattice constant a): every atom has the same
+    environment, 54 neighbours inside 6 A for a = 3.8 (shells of 12, 6, 24 and 12; the next shell is at 6.008)."""
+    rng = np.random.default_rng(seed)
+    cfg = dict(L=L, C=C, H=H, B=B, lf=1, cutoff=cutoff, dtype=dtype)
+    cell = np.stack(np.meshgrid(np.arange(nc), np.arange(nc), np.arange(nc), indexing="ij"), -1).reshape(-1, 3)
+    basis = np.array([[0.0, 0.0, 0.0], [0.0, 0.5, 0.5], [0.5, 0.0, 0.5], [0.5, 0.5, 0.0]])
+    sites = ((cell[:, None, :] + basis[None, :, :]) * a).reshape(-1, 3)
+    out = _pack(cfg, [sites.astype(np.float32)], rng)
+    out["box"] = np.full((1, 3), nc * a, dtype=np.float32)
+    return out
+
+
 def scaling_point(seed=0):
     return box(10_000, seed)
 
@@ -181,4 +234,6 @@ def by_name(name, seed=0):
         return box(int(name[3:]), seed)
     if name.startswith("fcc"):
         return fcc_subsample(int(name[3:]), seed)
+    if name.startswith("pbox"):
+        return periodic_boxes((int(name[4:]),), seed)
     raise KeyError(name)
