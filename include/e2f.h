@@ -96,6 +96,26 @@ e2f_status e2f_build_cells(e2f_ctx *ctx, const float *pos, const int32_t *seg_of
 void e2f_cells_destroy(e2f_cells *cells);
 
 /*
+ * Cell lists under periodic boundaries (for bulk simulation cells such as the periodic water runs of Sec. 4.3; the
+ * paper states the operator for given pair vectors and does not define the convention, which is this library's):
+ *   box   host float [S][3]: edge lengths of every segment's orthorhombic box; an entry <= 0 (or NaN) leaves that
+ *         axis open, NULL means no periodic axis anywhere (the call is then e2f_build_cells).  Read before the call
+ *         returns.
+ * On a periodic axis of length len a coordinate x counts as w = x - len*floor(x * (1/len)), every operation rounded
+ * to binary32 and one correction step into [0, len), so callers need not fold coordinates themselves.  Atom j is
+ * seen from atom i at its nearest image w_j + s*len, s in {-1, 0, 1}; the neighbour predicate and the pair vector
+ * r_ij of the operator use fl(w_j + s*len) - w_i per axis.  Every periodic edge must be at least three cell edges
+ * (3 * 1.0001 * cutoff), so that an atom has at most one image inside the cutoff: E2F_ERR_UNSUPPORTED otherwise
+ * (also for an infinite length).  The cells of a periodic axis tile the box exactly.
+ * Cell lists built here are accepted by e2f_count_neighbors, e2f_list_neighbors, e2f_build_neighbor_table,
+ * e2f_attn_forward and e2f_attn_forward_capped; the materialized baseline, the factorized pipeline (its node-level
+ * terms assume one position per atom, Eq. e2former_final) and the table form return E2F_ERR_UNSUPPORTED for them.
+ * Everything else as e2f_build_cells.
+ */
+e2f_status e2f_build_cells_periodic(e2f_ctx *ctx, const float *pos, const int32_t *seg_offsets, int32_t N, int32_t S,
+                                    const float *box, void *ws, size_t ws_bytes, e2f_cells **cells, void *hip_stream);
+
+/*
  * Neighbour sets as the kernels see them, for checking against a reference (test entry points).
  *   degree   device int32 [N]: |N(i)| for every atom, in the caller's atom order
  *   offsets  device int64 [N+1]: exclusive prefix sum of degree

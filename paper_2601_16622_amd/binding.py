@@ -20,7 +20,7 @@ EXPORTS = ["e2f_status_string", "e2f_create", "e2f_destroy", "e2f_cells_workspac
            "e2f_attn_forward", "e2f_attn_forward_materialized", "e2f_profile_begin", "e2f_profile_end",
            "e2f_eaas_tensor_product", "e2f_attn_factorized_workspace_bytes", "e2f_attn_forward_factorized",
            "e2f_attn_capped_workspace_bytes", "e2f_attn_forward_capped", "e2f_build_neighbor_table",
-           "e2f_attn_table_workspace_bytes", "e2f_attn_forward_table"]
+           "e2f_attn_table_workspace_bytes", "e2f_attn_forward_table", "e2f_build_cells_periodic"]
 STAGES = ("prepare", "project", "attention")
 
 
@@ -61,6 +61,8 @@ def load():
     L.e2f_cells_workspace_bytes.restype = sz
     L.e2f_build_cells.argtypes = [vp, vp, vp, i32, i32, vp, sz, ctypes.POINTER(vp), vp]
     L.e2f_build_cells.restype = ctypes.c_int
+    L.e2f_build_cells_periodic.argtypes = [vp, vp, vp, i32, i32, vp, vp, sz, ctypes.POINTER(vp), vp]
+    L.e2f_build_cells_periodic.restype = ctypes.c_int
     L.e2f_cells_destroy.argtypes = [vp]
     L.e2f_cells_destroy.restype = None
     L.e2f_count_neighbors.argtypes = [vp, vp, vp, i32, vp, vp]
@@ -137,6 +139,19 @@ def e2f_build_cells(ctx, pos, seg_offsets, ws):
     cells = ctypes.c_void_p()
     _check(load().e2f_build_cells(ctx, _ptr(pos), _ptr(seg_offsets), N, S, _ptr(ws), ws.numel(), ctypes.byref(cells),
                                   _stream()), "e2f_build_cells")
+    return cells
+
+
+def e2f_build_cells_periodic(ctx, pos, seg_offsets, box, ws):
+    """As e2f_build_cells, with box a host float32 array [S][3] of periodic edge lengths (<= 0: open axis) or None."""
+    N, S = pos.shape[0], seg_offsets.shape[0] - 1
+    cells = ctypes.c_void_p()
+    if box is not None:
+        box = np.ascontiguousarray(box, dtype=np.float32)
+        assert box.shape == (S, 3)
+    bptr = ctypes.c_void_p(box.ctypes.data) if box is not None else ctypes.c_void_p()
+    _check(load().e2f_build_cells_periodic(ctx, _ptr(pos), _ptr(seg_offsets), N, S, bptr, _ptr(ws), ws.numel(),
+                                           ctypes.byref(cells), _stream()), "e2f_build_cells_periodic")
     return cells
 
 
@@ -266,11 +281,16 @@ class Problem:
                                    device=self.device)
         self.out = torch.empty((self.N, self.n, cfg["C"]), dtype=torch.float32, device=self.device)
         self.cells = None
+        self.box = wl.get("box")   # host float32 [S][3] of periodic edge lengths, or None
 
     def build_cells(self):
         if self.cells is not None:
             e2f_cells_destroy(self.cells)
-        self.cells = e2f_build_cells(self.ctx, self.pos, self.seg, self.cells_ws)
+            self.cells = None
+        if self.box is not None:
+            self.cells = e2f_build_cells_periodic(self.ctx, self.pos, self.seg, self.box, self.cells_ws)
+        else:
+            self.cells = e2f_build_cells(self.ctx, self.pos, self.seg, self.cells_ws)
         return self.cells
 
     def forward(self):

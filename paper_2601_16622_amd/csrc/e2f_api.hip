@@ -53,7 +53,11 @@ size_t cells_ws_layout(int32_t N, int32_t S, void* ws, e2f_cells* c) {
     char* cell_fill = take((size_t)max_cells * 4);
     char* tmp_slot = take((size_t)N * 4);
     char* atom_sub = take((size_t)N * 4);
+    char* box = take((size_t)(S > 0 ? S : 1) * 6 * 4);
     if (c) {
+        c->box = (float*)box;
+        c->host_box = nullptr;
+        c->view.periodic = 0;
         c->view.grid = (const E2fSegGrid*)grid;
         c->view.cell_start = (const int32_t*)cell_start;
         c->view.perm = (const int32_t*)perm;
@@ -252,7 +256,21 @@ size_t e2f_cells_workspace_bytes(const e2f_ctx* ctx, int32_t N, int32_t S) {
 
 e2f_status e2f_build_cells(e2f_ctx* ctx, const float* pos, const int32_t* seg_offsets, int32_t N, int32_t S, void* ws,
                            size_t ws_bytes, e2f_cells** cells, void* hip_stream) {
+    return e2f_build_cells_periodic(ctx, pos, seg_offsets, N, S, nullptr, ws, ws_bytes, cells, hip_stream);
+}
+
+e2f_status e2f_build_cells_periodic(e2f_ctx* ctx, const float* pos, const int32_t* seg_offsets, int32_t N, int32_t S,
+                                    const float* box, void* ws, size_t ws_bytes, e2f_cells** cells,
+                                    void* hip_stream) {
     if (!ctx || !cells || N < 0 || S < 0) return E2F_ERR_INVALID_ARG;
+    bool periodic = false;
+    if (box)
+        for (int64_t i = 0; i < (int64_t)3 * S; ++i) {
+            if (!(box[i] > 0.0f)) continue;   // open axis (also NaN)
+            // three cells along a periodic axis: an atom then has at most one image inside the cutoff
+            if (isinf(box[i]) || box[i] < 3.0f * e2f_cell_edge(ctx->cfg.cutoff)) return E2F_ERR_UNSUPPORTED;
+            periodic = true;
+        }
     if (N > 0 && (S < 1 || !pos || !seg_offsets || !ws)) return E2F_ERR_INVALID_ARG;
     if ((int64_t)27 * S + (int64_t)2 * N + 1 > 0x7fffffff) return E2F_ERR_UNSUPPORTED;
     if (N > 0 && !aligned256(ws)) return E2F_ERR_INVALID_ARG;
@@ -261,16 +279,39 @@ e2f_status e2f_build_cells(e2f_ctx* ctx, const float* pos, const int32_t* seg_of
     if (!c) return E2F_ERR_OOM;
     cells_ws_layout(N, S, ws, c);
     c->pos = pos;
+    if (periodic && N > 0) {
+        c->host_box = new (std::nothrow) float[(size_t)6 * S];
+        if (!c->host_box) {
+            delete c;
+            return E2F_ERR_OOM;
+        }
+        for (int32_t s = 0; s < S; ++s)
+            for (int k = 0; k < 3; ++k) {
+                const float len = box[3 * s + k] > 0.0f ? box[3 * s + k] : 0.0f;
+                c->host_box[6 * s + k] = len;
+                c->host_box[6 * s + 3 + k] = len > 0.0f ? 1.0f / len : 0.0f;
+            }
+        c->view.periodic = 1;
+        if (hipMemcpyAsync(c->box, c->host_box, sizeof(float) * 6 * S, hipMemcpyHostToDevice,
+                           static_cast<hipStream_t>(hip_stream)) != hipSuccess) {
+            e2f_cells_destroy(c);
+            return E2F_ERR_HIP;
+        }
+    }
     const e2f_status rc = e2f_launch_build_cells(ctx, c, pos, seg_offsets, static_cast<hipStream_t>(hip_stream));
     if (rc != E2F_OK) {
-        delete c;
+        e2f_cells_destroy(c);
         return rc;
     }
     *cells = c;
     return E2F_OK;
 }
 
-void e2f_cells_destroy(e2f_cells* cells) { delete cells; }
+void e2f_cells_destroy(e2f_cells* cells) {
+    if (!cells) return;
+    delete[] cells->host_box;
+    delete cells;
+}
 
 e2f_status e2f_count_neighbors(e2f_ctx* ctx, const e2f_cells* cells, const float* pos, int32_t N, int32_t* degree,
                                void* hip_stream) {
@@ -300,6 +341,11 @@ static e2f_status forward_impl(e2f_ctx* ctx, const e2f_cells* cells, const float
     e2f_status rc = check_forward_args(ctx, cells, pos, h, seg_offsets, N, S, w, out, ws, ws_bytes);
     if (rc != E2F_OK || N == 0) return rc;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    if (cells->view.periodic) {
+        // Images are followed by the tile kernel and the ALU kernel.  The table names atoms, not images, and the
+        // per-pair matrix-core kernel (bf16 shapes outside the tile kernel's) does not carry the translations.
+        if (table || (!ctx->use_tile_attn && ctx->use_mfma_attn)) return E2F_ERR_UNSUPPORTED;
+    }
     // the table form runs on the ALU kernel, which reads the plain layout
     const int v_layout = table ? 0 : e2f_v_layout(ctx);
     E2fAttnWs L = e2f_attn_ws_layout(ctx, N, ws, v_layout);
@@ -401,6 +447,8 @@ e2f_status e2f_attn_forward_factorized(e2f_ctx* ctx, const e2f_cells* cells, con
     // same argument checks as the fused call, against this call's own workspace size
     e2f_status rc = check_forward_args(ctx, cells, pos, h, seg_offsets, N, S, w, out, ws, (size_t)-1);
     if (rc != E2F_OK || N == 0) return rc;
+    // the node-level source and target terms take one position per atom; images would need one per pair
+    if (cells->view.periodic) return E2F_ERR_UNSUPPORTED;
     if (ws_bytes < e2f_attn_factorized_workspace_bytes(ctx, N)) return E2F_ERR_WORKSPACE_TOO_SMALL;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     const E2fAttnWs L = e2f_attn_ws_layout(ctx, N, ws, 0);
@@ -425,6 +473,7 @@ e2f_status e2f_attn_forward_materialized(e2f_ctx* ctx, const e2f_cells* cells, c
     if (edges_out) *edges_out = 0;
     if (peak_bytes_out) *peak_bytes_out = 0;
     if (rc != E2F_OK || N == 0) return rc;
+    if (cells->view.periodic) return E2F_ERR_UNSUPPORTED;   // the edge list carries no images
     const E2fAttnWs L = e2f_attn_ws_layout(ctx, N, ws, e2f_v_layout(ctx));
     return e2f_run_materialized(ctx, cells->view, pos, h, w, L, out, static_cast<hipStream_t>(hip_stream), edges_out,
                                 peak_bytes_out);

@@ -82,8 +82,9 @@ __global__ void k_cells_bbox(const float* __restrict__ pos, const int32_t* __res
 
 // One block: grid of every segment (edge doubled until the segment stays within its cell budget of
 // 27 + 2 * atoms, so the total never exceeds the workspace), then an exclusive scan of the cell counts.
+// A periodic axis (box length > 0) gets floor(length / edge) >= 3 cells that tile the box exactly, origin 0.
 __global__ void k_cells_grid(const int32_t* __restrict__ bbox, const int32_t* __restrict__ seg_offsets, int S,
-                             float edge0, E2fSegGrid* __restrict__ grid) {
+                             float edge0, const float* __restrict__ box, E2fSegGrid* __restrict__ grid) {
     __shared__ int s_part[1024];
     __shared__ int s_carry;
     if (threadIdx.x == 0) s_carry = 0;
@@ -91,10 +92,16 @@ __global__ void k_cells_grid(const int32_t* __restrict__ bbox, const int32_t* __
     for (int s0 = 0; s0 < S; s0 += blockDim.x) {
         const int s = s0 + threadIdx.x;
         int cells = 0;
-        E2fSegGrid g = {0.f, 0.f, 0.f, 1.f, 1, 1, 1, 0};
+        E2fSegGrid g = {0.f, 0.f, 0.f, 1.f, 1.f, 1.f, 1, 1, 1, 0, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
         if (s < S) {
             const int ns = seg_offsets[s + 1] - seg_offsets[s];
             cells = 1;  // an empty segment keeps one empty cell
+            // box: [S][6], lengths (0 = open axis) and their reciprocals as the host rounded them
+            const float lx = box ? box[6 * s] : 0.0f, ly = box ? box[6 * s + 1] : 0.0f, lz = box ? box[6 * s + 2] : 0.0f;
+            g.lx = lx; g.ly = ly; g.lz = lz;
+            g.rx = box ? box[6 * s + 3] : 0.0f;
+            g.ry = box ? box[6 * s + 4] : 0.0f;
+            g.rz = box ? box[6 * s + 5] : 0.0f;
             if (ns > 0) {
                 const float mnx = ordered_to_float(bbox[s * 6 + 0]), mny = ordered_to_float(bbox[s * 6 + 1]);
                 const float mnz = ordered_to_float(bbox[s * 6 + 2]), mxx = ordered_to_float(bbox[s * 6 + 3]);
@@ -103,10 +110,14 @@ __global__ void k_cells_grid(const int32_t* __restrict__ bbox, const int32_t* __
                 float edge = edge0;
                 long long nx = 1, ny = 1, nz = 1;
                 bool fits = false;
+                auto cells_along = [&](float len, float extent) -> long long {
+                    const long long whole = (long long)floorf((len > 0.0f ? len : extent) / edge);
+                    return len > 0.0f ? (whole > 3 ? whole : 3) : whole + 1;   // (27 cells always fit the budget)
+                };
                 for (int it = 0; it < 200 && !fits; ++it) {  // bounded: edge overflows to inf long before
-                    nx = (long long)floorf((mxx - mnx) / edge) + 1;
-                    ny = (long long)floorf((mxy - mny) / edge) + 1;
-                    nz = (long long)floorf((mxz - mnz) / edge) + 1;
+                    nx = cells_along(lx, mxx - mnx);
+                    ny = cells_along(ly, mxy - mny);
+                    nz = cells_along(lz, mxz - mnz);
                     fits = nx >= 1 && ny >= 1 && nz >= 1 && nx <= budget && ny <= budget && nz <= budget &&
                            nx * ny * nz <= budget;
                     if (!fits) edge *= 2.0f;
@@ -115,7 +126,12 @@ __global__ void k_cells_grid(const int32_t* __restrict__ bbox, const int32_t* __
                     nx = ny = nz = 1;
                     edge = edge0;
                 }
-                g.ox = mnx; g.oy = mny; g.oz = mnz; g.inv_edge = 1.0f / edge;
+                g.ox = lx > 0.0f ? 0.0f : mnx;
+                g.oy = ly > 0.0f ? 0.0f : mny;
+                g.oz = lz > 0.0f ? 0.0f : mnz;
+                g.ix = lx > 0.0f ? (float)nx / lx : 1.0f / edge;
+                g.iy = ly > 0.0f ? (float)ny / ly : 1.0f / edge;
+                g.iz = lz > 0.0f ? (float)nz / lz : 1.0f / edge;
                 g.nx = (int)nx; g.ny = (int)ny; g.nz = (int)nz;
                 cells = (int)(nx * ny * nz);
             }
@@ -148,8 +164,9 @@ __global__ void k_cells_assign(const float* __restrict__ pos, const int32_t* __r
     const int a = blockIdx.x * blockDim.x + threadIdx.x;
     if (a >= N) return;
     const E2fSegGrid g = grid[atom_seg[a]];
-    const float fx = (pos[3 * a] - g.ox) * g.inv_edge, fy = (pos[3 * a + 1] - g.oy) * g.inv_edge;
-    const float fz = (pos[3 * a + 2] - g.oz) * g.inv_edge;
+    const float fx = (e2f::fold_coord(pos[3 * a], g.lx, g.rx) - g.ox) * g.ix;
+    const float fy = (e2f::fold_coord(pos[3 * a + 1], g.ly, g.ry) - g.oy) * g.iy;
+    const float fz = (e2f::fold_coord(pos[3 * a + 2], g.lz, g.rz) - g.oz) * g.iz;
     int cx = (int)floorf(fx), cy = (int)floorf(fy), cz = (int)floorf(fz);
     cx = min(max(cx, 0), g.nx - 1); cy = min(max(cy, 0), g.ny - 1); cz = min(max(cz, 0), g.nz - 1);
     const int c = g.base + (cz * g.ny + cy) * g.nx + cx;
@@ -220,25 +237,44 @@ __global__ void k_cells_rank(const int32_t* __restrict__ tmp_slot, const int32_t
 }
 
 // One wave per target: walk the 27-cell stencil 64 candidates at a time.
-template <bool LIST>
+// Position of an atom as the predicate sees it: folded into the segment's box on periodic axes.
+template <bool PBC>
+__device__ __forceinline__ void atom_position(const float* __restrict__ pos, int atom, const E2fSegGrid& g, float& x,
+                                              float& y, float& z) {
+    x = pos[3 * atom];
+    y = pos[3 * atom + 1];
+    z = pos[3 * atom + 2];
+    if (PBC) {
+        x = e2f::fold_coord(x, g.lx, g.rx);
+        y = e2f::fold_coord(y, g.ly, g.ry);
+        z = e2f::fold_coord(z, g.lz, g.rz);
+    }
+}
+
+template <bool LIST, bool PBC>
 __global__ __launch_bounds__(64) void k_neighbors(E2fCellsView cv, const float* __restrict__ pos, float rc2,
                                                   int32_t* __restrict__ degree, const int64_t* __restrict__ offsets,
                                                   int32_t* __restrict__ idx) {
     const int t = blockIdx.x, lane = threadIdx.x;
     const int ai = cv.perm[t];
-    const float xi = pos[3 * ai], yi = pos[3 * ai + 1], zi = pos[3 * ai + 2];
-    int lo[9], hi[9];
-    e2f::stencil_rows(cv, t, lo, hi);
+    const E2fSegGrid g = cv.grid[cv.sseg[t]];
+    float xi, yi, zi;
+    atom_position<PBC>(pos, ai, g, xi, yi, zi);
+    e2f::Stencil<PBC> st;
+    st.init(cv, t);
     int cnt = 0;
     const int64_t out0 = LIST ? offsets[ai] : 0;
-    for (int r = 0; r < 9; ++r)
-        for (int base = lo[r]; base < hi[r]; base += 64) {
+    for (int r = 0; r < e2f::Stencil<PBC>::NR; ++r)
+        for (int base = st.lo[r]; base < st.hi[r]; base += 64) {
             const int j = base + lane;
             bool ok = false;
             int aj = 0;
-            if (j < hi[r] && j != t) {
+            if (j < st.hi[r] && j != t) {
                 aj = cv.perm[j];
-                ok = e2f::is_neighbor(e2f::dist2_exact(xi, yi, zi, pos[3 * aj], pos[3 * aj + 1], pos[3 * aj + 2]), rc2);
+                float xj, yj, zj;
+                atom_position<PBC>(pos, aj, g, xj, yj, zj);
+                ok = e2f::is_neighbor(e2f::dist2_exact(xi, yi, zi, xj + st.shift_x(r), yj + st.shift_y(r),
+                                                       zj + st.shift_z(r)), rc2);
             }
             const unsigned long long mask = __ballot(ok);
             if (LIST && ok) idx[out0 + cnt + __popcll(mask & ((1ull << lane) - 1ull))] = aj;
@@ -252,6 +288,7 @@ __global__ __launch_bounds__(64) void k_neighbors(E2fCellsView cv, const float* 
 // the keys are kept in LDS after one stencil walk, or, beyond 512 neighbours, the stencil is walked once per digit,
 // so there is no limit on their number), then writes the threshold key and / or the
 // table row of the selected atoms (in cell order, -1 padded).  Keys are unique, so exactly min(K, degree) atoms pass.
+template <bool PBC>
 __global__ __launch_bounds__(64) void k_select_neighbors(E2fCellsView cv, const float* __restrict__ pos, float rc2,
                                                          int K, uint32_t* __restrict__ cap_d2,
                                                          int32_t* __restrict__ cap_idx, int32_t* __restrict__ table,
@@ -259,20 +296,25 @@ __global__ __launch_bounds__(64) void k_select_neighbors(E2fCellsView cv, const 
     __shared__ int s_hist[256];
     const int t = blockIdx.x, lane = threadIdx.x;
     const int ai = cv.perm[t];
-    const float xi = pos[3 * ai], yi = pos[3 * ai + 1], zi = pos[3 * ai + 2];
-    int lo[9], hi[9];
-    e2f::stencil_rows(cv, t, lo, hi);
+    const E2fSegGrid g = cv.grid[cv.sseg[t]];
+    float xi, yi, zi;
+    atom_position<PBC>(pos, ai, g, xi, yi, zi);
+    e2f::Stencil<PBC> st;
+    st.init(cv, t);
     // walk(f): f(ok, key, atom) for every candidate of this lane, all lanes in step
     auto walk = [&](auto&& f) {
-        for (int r = 0; r < 9; ++r)
-            for (int base = lo[r]; base < hi[r]; base += 64) {
+        for (int r = 0; r < e2f::Stencil<PBC>::NR; ++r)
+            for (int base = st.lo[r]; base < st.hi[r]; base += 64) {
                 const int j = base + lane;
                 bool ok = false;
                 int aj = 0;
                 unsigned long long key = ~0ull;
-                if (j < hi[r] && j != t) {
+                if (j < st.hi[r] && j != t) {
                     aj = cv.perm[j];
-                    const float d2 = e2f::dist2_exact(xi, yi, zi, pos[3 * aj], pos[3 * aj + 1], pos[3 * aj + 2]);
+                    float xj, yj, zj;
+                    atom_position<PBC>(pos, aj, g, xj, yj, zj);
+                    const float d2 = e2f::dist2_exact(xi, yi, zi, xj + st.shift_x(r), yj + st.shift_y(r),
+                                                      zj + st.shift_z(r));
                     ok = e2f::is_neighbor(d2, rc2);
                     key = ((unsigned long long)__float_as_uint(d2) << 32) | (unsigned int)aj;
                 }
@@ -371,8 +413,8 @@ e2f_status e2f_launch_build_cells(const e2f_ctx* ctx, e2f_cells* c, const float*
     k_cells_bbox<<<(N + 1023) / 1024, 1024, 0, st>>>(pos, seg_offsets, N, S, c->atom_seg, c->bbox);
     // edge a hair above the cutoff: the binary32 predicate can accept a pair whose exact |dx| exceeds the
     // cutoff by rounding, and cell coordinates carry rounding of their own
-    k_cells_grid<<<1, 1024, 0, st>>>(c->bbox, seg_offsets, S, ctx->cfg.cutoff * 1.0001f,
-                                     const_cast<E2fSegGrid*>(c->view.grid));
+    k_cells_grid<<<1, 1024, 0, st>>>(c->bbox, seg_offsets, S, e2f_cell_edge(ctx->cfg.cutoff),
+                                     c->view.periodic ? c->box : nullptr, const_cast<E2fSegGrid*>(c->view.grid));
     k_cells_assign<<<(N + tb - 1) / tb, tb, 0, st>>>(pos, c->atom_seg, c->view.grid, N, c->atom_cell, c->atom_sub, cell_start + 1);
     k_cells_scan<<<1, 1024, 0, st>>>(cell_start, c->view.grid, S);
     k_cells_scatter<<<(N + tb - 1) / tb, tb, 0, st>>>(c->atom_cell, cell_start, N, c->cell_fill, c->tmp_slot);
@@ -388,7 +430,8 @@ e2f_status e2f_launch_build_cells(const e2f_ctx* ctx, e2f_cells* c, const float*
 e2f_status e2f_launch_count_neighbors(const e2f_ctx* ctx, const E2fCellsView& cv, const float* pos, int32_t* degree,
                                       hipStream_t st) {
     if (cv.N == 0) return E2F_OK;
-    k_neighbors<false><<<cv.N, 64, 0, st>>>(cv, pos, ctx->rc2, degree, nullptr, nullptr);
+    if (cv.periodic) k_neighbors<false, true><<<cv.N, 64, 0, st>>>(cv, pos, ctx->rc2, degree, nullptr, nullptr);
+    else k_neighbors<false, false><<<cv.N, 64, 0, st>>>(cv, pos, ctx->rc2, degree, nullptr, nullptr);
     E2F_HIP_CHECK(hipGetLastError());
     return E2F_OK;
 }
@@ -396,7 +439,8 @@ e2f_status e2f_launch_count_neighbors(const e2f_ctx* ctx, const E2fCellsView& cv
 e2f_status e2f_launch_list_neighbors(const e2f_ctx* ctx, const E2fCellsView& cv, const float* pos,
                                      const int64_t* offsets, int32_t* idx, hipStream_t st) {
     if (cv.N == 0) return E2F_OK;
-    k_neighbors<true><<<cv.N, 64, 0, st>>>(cv, pos, ctx->rc2, nullptr, offsets, idx);
+    if (cv.periodic) k_neighbors<true, true><<<cv.N, 64, 0, st>>>(cv, pos, ctx->rc2, nullptr, offsets, idx);
+    else k_neighbors<true, false><<<cv.N, 64, 0, st>>>(cv, pos, ctx->rc2, nullptr, offsets, idx);
     E2F_HIP_CHECK(hipGetLastError());
     return E2F_OK;
 }
@@ -405,7 +449,8 @@ e2f_status e2f_launch_select_neighbors(const e2f_ctx* ctx, const E2fCellsView& c
                                        uint32_t* cap_d2, int32_t* cap_idx, int32_t* table, int32_t* count,
                                        hipStream_t st) {
     if (cv.N == 0) return E2F_OK;
-    k_select_neighbors<<<cv.N, 64, 0, st>>>(cv, pos, ctx->rc2, K, cap_d2, cap_idx, table, count);
+    if (cv.periodic) k_select_neighbors<true><<<cv.N, 64, 0, st>>>(cv, pos, ctx->rc2, K, cap_d2, cap_idx, table, count);
+    else k_select_neighbors<false><<<cv.N, 64, 0, st>>>(cv, pos, ctx->rc2, K, cap_d2, cap_idx, table, count);
     E2F_HIP_CHECK(hipGetLastError());
     return E2F_OK;
 }

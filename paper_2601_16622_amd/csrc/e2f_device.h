@@ -36,26 +36,78 @@ __device__ __forceinline__ bool under_cap(float d2, float w, uint32_t cap_d2, in
     return b < cap_d2 || (b == cap_d2 && __float_as_int(w) <= cap_idx);
 }
 
-// The 27-cell stencil of a target as 9 contiguous runs of sorted slots (cells along x are adjacent in the
-// sorted order).  Runs that fall outside the segment's grid come back empty.
+// Coordinate folded into a periodic box of length len (inv = 1/len rounded to binary32), every operation rounded
+// to binary32: q = floor(x inv), w = x - len q, then one correction step into [0, len).  len == 0: open axis.
+__device__ __forceinline__ float fold_coord(float x, float len, float inv) {
+#pragma clang fp contract(off)
+    if (!(len > 0.0f)) return x;
+    const float q = floorf(x * inv);
+    const float t = len * q;
+    float w = x - t;
+    if (w < 0.0f) w = w + len;
+    if (w >= len) w = w - len;
+    return w;
+}
+
+// Runs of sorted slots that hold a target's candidates: without periodic axes the 27-cell stencil as 9 rows
+// (cells along x are adjacent in the sorted order); with them 18 runs, where run 9 + r is the cell of row r
+// that lies across a periodic x face (empty if the target's cell does not touch one).  Rows outside an open
+// grid come back empty.  Candidates of run r are seen at their position plus shift(r), a lattice translation.
+template <bool PBC>
+struct Stencil {
+    static constexpr int NR = PBC ? 18 : 9;
+    int lo[NR], hi[NR];
+    float sxe, sy[3], sz[3];   // translations: of the extra runs along x, of the rows per y and z offset
+
+    __device__ __forceinline__ void init(const E2fCellsView& cv, int slot) {
+        const E2fSegGrid g = cv.grid[cv.sseg[slot]];
+        const int local = cv.scell[slot] - g.base;
+        const int cx = local % g.nx;
+        const int cy = (local / g.nx) % g.ny;
+        const int cz = local / (g.nx * g.ny);
+        const int x0 = max(cx - 1, 0), x1 = min(cx + 1, g.nx - 1);
+        int xe = -1;   // the cell across the x face
+        sxe = 0.0f;
+        if (PBC && g.lx > 0.0f) {
+            if (cx == 0) { xe = g.nx - 1; sxe = -g.lx; }
+            else if (cx == g.nx - 1) { xe = 0; sxe = g.lx; }
+        }
+#pragma unroll
+        for (int d = 0; d < 3; ++d) { sy[d] = 0.0f; sz[d] = 0.0f; }
+#pragma unroll
+        for (int r = 0; r < 9; ++r) {
+            int y = cy + (r % 3) - 1, z = cz + (r / 3) - 1;
+            if (PBC && g.ly > 0.0f) {
+                if (y < 0) { y += g.ny; sy[r % 3] = -g.ly; }
+                else if (y >= g.ny) { y -= g.ny; sy[r % 3] = g.ly; }
+            }
+            if (PBC && g.lz > 0.0f) {
+                if (z < 0) { z += g.nz; sz[r / 3] = -g.lz; }
+                else if (z >= g.nz) { z -= g.nz; sz[r / 3] = g.lz; }
+            }
+            const bool inside = y >= 0 && y < g.ny && z >= 0 && z < g.nz;
+            const int row = g.base + (z * g.ny + y) * g.nx;
+            lo[r] = inside ? cv.cell_start[row + x0] : 0;
+            hi[r] = inside ? cv.cell_start[row + x1 + 1] : 0;
+            if (PBC) {
+                lo[9 + r] = inside && xe >= 0 ? cv.cell_start[row + xe] : 0;
+                hi[9 + r] = inside && xe >= 0 ? cv.cell_start[row + xe + 1] : 0;
+            }
+        }
+    }
+    __device__ __forceinline__ float shift_x(int r) const { return PBC && r >= 9 ? sxe : 0.0f; }
+    __device__ __forceinline__ float shift_y(int r) const { return PBC ? sy[(r % 9) % 3] : 0.0f; }
+    __device__ __forceinline__ float shift_z(int r) const { return PBC ? sz[(r % 9) / 3] : 0.0f; }
+};
+
+// The open-boundary stencil as plain arrays.
 __device__ __forceinline__ void stencil_rows(const E2fCellsView& cv, int slot, int (&lo)[9], int (&hi)[9]) {
-    const E2fSegGrid g = cv.grid[cv.sseg[slot]];
-    const int local = cv.scell[slot] - g.base;
-    const int cx = local % g.nx;
-    const int cy = (local / g.nx) % g.ny;
-    const int cz = local / (g.nx * g.ny);
-    const int x0 = max(cx - 1, 0), x1 = min(cx + 1, g.nx - 1);
+    Stencil<false> s;
+    s.init(cv, slot);
 #pragma unroll
     for (int r = 0; r < 9; ++r) {
-        const int y = cy + (r % 3) - 1, z = cz + (r / 3) - 1;
-        if (y < 0 || y >= g.ny || z < 0 || z >= g.nz) {
-            lo[r] = 0;
-            hi[r] = 0;
-        } else {
-            const int row = g.base + (z * g.ny + y) * g.nx;
-            lo[r] = cv.cell_start[row + x0];
-            hi[r] = cv.cell_start[row + x1 + 1];
-        }
+        lo[r] = s.lo[r];
+        hi[r] = s.hi[r];
     }
 }
 

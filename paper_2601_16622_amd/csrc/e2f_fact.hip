@@ -19,8 +19,7 @@ constexpr int FCAP = 320;
 
 __device__ __forceinline__ float3 seg_origin(const E2fCellsView& cv, int slot) {
     const E2fSegGrid g = cv.grid[cv.sseg[slot]];
-    const float e = 1.0f / g.inv_edge;
-    return make_float3(g.ox + 0.5f * e * g.nx, g.oy + 0.5f * e * g.ny, g.oz + 0.5f * e * g.nz);
+    return make_float3(g.ox + 0.5f * g.nx / g.ix, g.oy + 0.5f * g.ny / g.iy, g.oz + 0.5f * g.nz / g.iz);
 }
 
 // Node-level EAAS product with r = spos[slot] - o for FPB consecutive slots per wave.

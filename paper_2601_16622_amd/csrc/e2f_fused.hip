@@ -72,10 +72,12 @@ __global__ __launch_bounds__(64) void k_fused_valu(FusedParams P) {
         for (int u = 0; u < CPL; ++u) A[x][u] = 0.0f;
     float mu = -INFINITY, z = 0.0f;
 
-    int lo[9], hi[9];
-    e2f::stencil_rows(P.cv, t, lo, hi);
+    // (the 18-run form also serves open boundaries: its extra runs are empty and every translation is zero)
+    e2f::Stencil<true> st;
+    st.init(P.cv, t);
+    constexpr int RUN_SHIFT = 26;   // a list entry is slot | run << 26; the launcher checks N < 2^26
 
-    int row = 0, base = lo[0];
+    int row = 0, base = st.lo[0];
     bool rows_done = false;
     const int32_t* trow = TABLE ? P.table + (size_t)P.cv.perm[t] * P.K : nullptr;
     int tb = 0;
@@ -97,21 +99,22 @@ __global__ __launch_bounds__(64) void k_fused_valu(FusedParams P) {
             tb += 64;
         }
         while (!TABLE && !rows_done && cnt + 64 <= CAP) {
-            if (base >= hi[row]) {
+            if (base >= st.hi[row]) {
                 ++row;
-                if (row == 9) { rows_done = true; break; }
-                base = lo[row];
+                if (row == 18) { rows_done = true; break; }
+                base = st.lo[row];
                 continue;
             }
             const int j = base + lane;
             bool ok = false;
-            if (j < hi[row] && j != t) {
+            if (j < st.hi[row] && j != t) {
                 const float4 pj = P.spos[j];
-                const float d2 = e2f::dist2_exact(pi.x, pi.y, pi.z, pj.x, pj.y, pj.z);
+                const float d2 = e2f::dist2_exact(pi.x, pi.y, pi.z, pj.x + st.shift_x(row), pj.y + st.shift_y(row),
+                                                  pj.z + st.shift_z(row));
                 ok = e2f::is_neighbor(d2, P.rc2) && e2f::under_cap(d2, pj.w, capd, capi);
             }
             const unsigned long long mask = __ballot(ok);
-            if (ok) s_list[cnt + __popcll(mask & ((1ull << lane) - 1ull))] = j;
+            if (ok) s_list[cnt + __popcll(mask & ((1ull << lane) - 1ull))] = j | (row << RUN_SHIFT);
             cnt += __popcll(mask);
             base += 64;
         }
@@ -120,9 +123,10 @@ __global__ __launch_bounds__(64) void k_fused_valu(FusedParams P) {
         for (int p0 = 0; p0 < cnt; p0 += PB) {
             const int np = min(PB, cnt - p0);
             if (lane < np) {
-                const int j = s_list[p0 + lane];
+                const int e = s_list[p0 + lane], j = e & ((1 << RUN_SHIFT) - 1), run = e >> RUN_SHIFT;
                 const float4 pj = P.spos[j];
-                const float dx = pj.x - pi.x, dy = pj.y - pi.y, dz = pj.z - pi.z;
+                const float dx = (pj.x + st.shift_x(run)) - pi.x, dy = (pj.y + st.shift_y(run)) - pi.y;
+                const float dz = (pj.z + st.shift_z(run)) - pi.z;
                 const float d = sqrtf(dx * dx + dy * dy + dz * dz);
                 if constexpr (LF != 0) e2f::align_D<L>(dx, dy, dz, d, s_D + lane * DSP);
                 for (int hh = 0; hh < H; ++hh) {
@@ -140,7 +144,7 @@ __global__ __launch_bounds__(64) void k_fused_valu(FusedParams P) {
             for (int p = 0; p < PB; ++p) {
                 s_arr[p] = -INFINITY;
                 if (p < np) {
-                    const int j = s_list[p0 + p];
+                    const int j = s_list[p0 + p] & ((1 << RUN_SHIFT) - 1);
                     const float* kj = P.k + (size_t)j * (L + 1) * C + c0;
                     float dot = 0.0f;
 #pragma unroll
@@ -170,7 +174,7 @@ __global__ __launch_bounds__(64) void k_fused_valu(FusedParams P) {
                 const float pe = __expf(sp - mu);
                 z += pe;
                 const float wgt = pe * s_wgt[p];
-                const int j = s_list[p0 + p];
+                const int j = s_list[p0 + p] & ((1 << RUN_SHIFT) - 1);
                 const VT* vj = (const VT*)P.v + (size_t)j * n * C + c0;
                 float vin[n][CPL];
 #pragma unroll
@@ -234,6 +238,7 @@ bool launch_valu_lf(const e2f_ctx* ctx, const FusedParams& P, hipStream_t st) {
 static e2f_status launch_valu(const e2f_ctx* ctx, const E2fCellsView& cv, const e2f_weights* w, const E2fAttnWs& ws,
                               const int32_t* table, int32_t K, float* out, hipStream_t st) {
     if (cv.N == 0) return E2F_OK;
+    if (cv.N >= (1 << 26)) return E2F_ERR_UNSUPPORTED;   // list entries carry the run in their top bits
     FusedParams P;
     P.cv = cv;
     P.spos = ws.spos; P.q = ws.q; P.k = ws.k; P.v = ws.v; P.cw = ws.cw; P.Wb = w->Wb; P.out = out;

@@ -13,9 +13,14 @@
 #define E2F_NP (2 * E2F_MAX_LF + 1)  // coupling paths per output degree: l_in = l_out - lf + k, k = 0..2 lf
 
 // Per-segment uniform grid: cell (x,y,z) of the segment has global id base + (z*ny + y)*nx + x.
+// A periodic axis has box length l* > 0 (r* = 1/l* rounded to binary32), origin 0 and at least 3 cells that
+// tile the box exactly; an open axis has l* = 0 and cells laid over the bounding box.
 struct E2fSegGrid {
-    float ox, oy, oz, inv_edge;
+    float ox, oy, oz;
+    float ix, iy, iz;   // 1 / cell edge per axis
     int32_t nx, ny, nz, base;
+    float lx, ly, lz;
+    float rx, ry, rz;
 };
 
 // Device view of a cell list (all pointers into the caller's cells workspace).
@@ -27,6 +32,7 @@ struct E2fCellsView {
     const int32_t* sseg;        // [N] segment of the atom in each sorted slot
     const int32_t* atom_slot;   // [N] caller's atom index -> sorted slot
     int32_t N, S;
+    int32_t periodic;           // whether any segment has a periodic axis (selects the kernels that follow images)
 };
 
 struct e2f_cells {
@@ -38,8 +44,10 @@ struct e2f_cells {
     int32_t* cell_fill;  // [max_cells]
     int32_t* tmp_slot;   // [N]
     int32_t* atom_sub;   // [N] position of the atom inside its cell: Morton index over 4x4x4 sub-cells
+    float* box;          // [S][6] on the device: periodic box lengths (0 = open axis), then their reciprocals
     int32_t max_cells;
     const float* pos;    // the positions the list was built from (identity check only)
+    float* host_box;     // [S][6] copy of the periodic boxes that the upload reads (owned; nullptr without any)
 };
 
 struct e2f_ctx {
@@ -92,6 +100,9 @@ struct E2fFactWs {
 };
 
 static inline size_t e2f_align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
+// Cell edge: a hair above the cutoff, since the binary32 predicate can accept a pair whose exact |dx| exceeds the
+// cutoff by rounding, and cell coordinates carry rounding of their own.
+static inline float e2f_cell_edge(float cutoff) { return cutoff * 1.0001f; }
 
 #define E2F_HIP_CHECK(expr)                      \
     do {                                         \

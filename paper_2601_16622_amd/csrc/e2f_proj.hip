@@ -29,7 +29,14 @@ __global__ void k_prepare(E2fCellsView cv, const float* __restrict__ pos, const 
     if (t < H * B) wbT[(t % B) * H + t / B] = Wb[t];
     if (t < cv.N) {
         const int a = cv.perm[t];
-        spos[t] = make_float4(pos[3 * a], pos[3 * a + 1], pos[3 * a + 2], __int_as_float(a));   // w: the atom index
+        float x = pos[3 * a], y = pos[3 * a + 1], z = pos[3 * a + 2];
+        if (cv.periodic) {   // folded into the segment's box on its periodic axes
+            const E2fSegGrid g = cv.grid[cv.sseg[t]];
+            x = e2f::fold_coord(x, g.lx, g.rx);
+            y = e2f::fold_coord(y, g.ly, g.ry);
+            z = e2f::fold_coord(z, g.lz, g.rz);
+        }
+        spos[t] = make_float4(x, y, z, __int_as_float(a));   // w: the atom index
     }
     const int n = (L + 1) * (L + 1);
     if (t < n * E2F_NP) {

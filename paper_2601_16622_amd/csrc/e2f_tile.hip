@@ -124,7 +124,8 @@ __global__ void k_axis_ops(const float* __restrict__ cw, float* __restrict__ G) 
 //   aggregate every wave applies all four chunks' W_mu to its own quarter of the components, T_mu += W_mu V
 // The softmax reference of a target is common to the four waves: it is set by the target's first neighbours and
 // moved (with a rescale of the accumulator rows) only when a later logit exceeds it by M_STEP.
-template <int L, int NW>
+// PBC: whether segments can have periodic axes (the candidate runs then include the images across the faces).
+template <int L, int NW, bool PBC>
 __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(E2F_TILE_OCC(NW), E2F_TILE_OCC(NW)))) void k_tile(TileParams P) {
     constexpr int n = (L + 1) * (L + 1), NX = (n + NW - 1) / NW;
     constexpr int PADE = 8 * NW;        // the list is padded to whole groups of NW chunks
@@ -213,25 +214,48 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(E2F_TIL
         const int b = stop ? __builtin_ctz(stop) : nt;
         const bool t_active = tn >= a && tn < b;
         const int cxa = __builtin_amdgcn_readlane(tcx, a), cxb = __builtin_amdgcn_readlane(tcx, b - 1);
-        int lo[9], hi[9], pre[10];
+        // Runs of sorted slots that hold the pass's candidates: rows 0..8 are the stencil rows over the cells
+        // [cxa - 1, cxb + 1]; with periodic boundaries runs 9..17 are the rows' last cell seen across the low x
+        // face and runs 18..26 their first cell seen across the high x face, and rows that leave the grid along a
+        // periodic y or z come back in from the other side.  Candidates of a run are seen at their position plus
+        // the run's lattice translation.
+        constexpr int NR = PBC ? 27 : 9;
+        int lo[NR], hi[NR], pre[NR + 1];
+        float sxl = 0.0f, sxh = 0.0f, sy[3] = {0.0f, 0.0f, 0.0f}, sz[3] = {0.0f, 0.0f, 0.0f};
         {
             const E2fSegGrid G = P.cv.grid[seg_a];
             const int cy = row_a % G.ny, cz = row_a / G.ny;
             const int xa = max(cxa - 1, 0), xb = min(cxb + 1, G.nx - 1);
-            pre[0] = 0;
+            int xl = -1, xh = -1;
+            if (PBC && G.lx > 0.0f) {
+                if (cxa == 0) { xl = G.nx - 1; sxl = -G.lx; }
+                if (cxb == G.nx - 1) { xh = 0; sxh = G.lx; }
+            }
 #pragma unroll
             for (int r = 0; r < 9; ++r) {
-                const int y = cy + (r % 3) - 1, zc = cz + (r / 3) - 1;
-                if (y < 0 || y >= G.ny || zc < 0 || zc >= G.nz) {
-                    lo[r] = 0;
-                    hi[r] = 0;
-                } else {
-                    const int row = G.base + (zc * G.ny + y) * G.nx;
-                    lo[r] = P.cv.cell_start[row + xa];
-                    hi[r] = P.cv.cell_start[row + xb + 1];
+                int y = cy + (r % 3) - 1, zc = cz + (r / 3) - 1;
+                if (PBC && G.ly > 0.0f) {
+                    if (y < 0) { y += G.ny; sy[r % 3] = -G.ly; }
+                    else if (y >= G.ny) { y -= G.ny; sy[r % 3] = G.ly; }
                 }
-                pre[r + 1] = pre[r] + (hi[r] > lo[r] ? ((hi[r] + 3) >> 2) - (lo[r] >> 2) : 0);
+                if (PBC && G.lz > 0.0f) {
+                    if (zc < 0) { zc += G.nz; sz[r / 3] = -G.lz; }
+                    else if (zc >= G.nz) { zc -= G.nz; sz[r / 3] = G.lz; }
+                }
+                const bool inside = y >= 0 && y < G.ny && zc >= 0 && zc < G.nz;
+                const int row = G.base + (zc * G.ny + y) * G.nx;
+                lo[r] = inside ? P.cv.cell_start[row + xa] : 0;
+                hi[r] = inside ? P.cv.cell_start[row + xb + 1] : 0;
+                if (PBC) {
+                    lo[9 + r] = inside && xl >= 0 ? P.cv.cell_start[row + xl] : 0;
+                    hi[9 + r] = inside && xl >= 0 ? P.cv.cell_start[row + xl + 1] : 0;
+                    lo[18 + r] = inside && xh >= 0 ? P.cv.cell_start[row + xh] : 0;
+                    hi[18 + r] = inside && xh >= 0 ? P.cv.cell_start[row + xh + 1] : 0;
+                }
             }
+            pre[0] = 0;
+#pragma unroll
+            for (int r = 0; r < NR; ++r) pre[r + 1] = pre[r] + (hi[r] > lo[r] ? ((hi[r] + 3) >> 2) - (lo[r] >> 2) : 0);
         }
         // bounding box of the pass's targets: a candidate group is kept if one of its slots can be within the
         // cutoff of the box (pruning only; the predicate itself is evaluated per pair below)
@@ -250,7 +274,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(E2F_TIL
         for (int off = 1; off < 16; off <<= 1) reach2 = fmaxf(reach2, __shfl_xor(reach2, off));
         const float prune2 = reach2 * 1.001f;
 
-        const int total = pre[9];
+        const int total = pre[NR];
         for (int fbase = 0; fbase < total; fbase += 256) {
             // ---- a batch of the candidate list: 256 slot groups, 64 per wave, kept groups packed in order into
             // entries (group << 4 | valid slots) with the slots' positions beside them
@@ -266,17 +290,28 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(E2F_TIL
                 for (int u = 0; u < LU; ++u) {
                     const int fg = fbase + 16 * LU * wave + 16 * u + (ln >> 2);
                     int gq = -1, rlo = 0, rhi = 0;
+                    float shx = 0.0f, shy = 0.0f, shz = 0.0f;
 #pragma unroll
-                    for (int r = 0; r < 9; ++r)
+                    for (int r = 0; r < NR; ++r)
                         if (fg >= pre[r] && fg < pre[r + 1]) {
                             gq = (lo[r] >> 2) + fg - pre[r];
                             rlo = lo[r];
                             rhi = hi[r];
+                            if (PBC) {
+                                shx = r >= 18 ? sxh : (r >= 9 ? sxl : 0.0f);
+                                shy = sy[(r % 9) % 3];
+                                shz = sz[(r % 9) / 3];
+                            }
                         }
                     const int slot = 4 * gq + (ln & 3);
                     grp[u] = gq;
                     valid[u] = gq >= 0 && slot >= rlo && slot < rhi;
                     pj[u] = P.spos[valid[u] ? slot : tslot];
+                    if (PBC) {   // the image this run sees (the translation is exact; the sum rounds to binary32)
+                        pj[u].x += shx;
+                        pj[u].y += shy;
+                        pj[u].z += shz;
+                    }
                 }
                 int mine = 0;
 #pragma unroll
@@ -522,7 +557,8 @@ void launch_L(const TileParams& P, const float* cw, float* G, hipStream_t st) {
     const int grid = ((chunks + 7) / 8) * 8 * TILE_BLK * P.H;
     // four waves per workgroup, two workgroups per CU: with eight waves the 128 registers left per wave do not
     // hold a wave's accumulators, value rows and key rows without spilling into the streaming loop
-    k_tile<L, 4><<<grid, 256, 0, st>>>(P);
+    if (P.cv.periodic) k_tile<L, 4, true><<<grid, 256, 0, st>>>(P);
+    else k_tile<L, 4, false><<<grid, 256, 0, st>>>(P);
 }
 
 }  // namespace
