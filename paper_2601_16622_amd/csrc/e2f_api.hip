@@ -341,11 +341,7 @@ static e2f_status forward_impl(e2f_ctx* ctx, const e2f_cells* cells, const float
     e2f_status rc = check_forward_args(ctx, cells, pos, h, seg_offsets, N, S, w, out, ws, ws_bytes);
     if (rc != E2F_OK || N == 0) return rc;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
-    if (cells->view.periodic) {
-        // Images are followed by the tile kernel and the ALU kernel.  The table names atoms, not images, and the
-        // per-pair matrix-core kernel (bf16 shapes outside the tile kernel's) does not carry the translations.
-        if (table || (!ctx->use_tile_attn && ctx->use_mfma_attn)) return E2F_ERR_UNSUPPORTED;
-    }
+    if (cells->view.periodic && table) return E2F_ERR_UNSUPPORTED;   // the table names atoms, not images
     // the table form runs on the ALU kernel, which reads the plain layout
     const int v_layout = table ? 0 : e2f_v_layout(ctx);
     E2fAttnWs L = e2f_attn_ws_layout(ctx, N, ws, v_layout);

@@ -100,6 +100,34 @@ struct Stencil {
     __device__ __forceinline__ float shift_z(int r) const { return PBC ? sz[(r % 9) / 3] : 0.0f; }
 };
 
+// Run r of the 18-run stencil on its own (for kernels that keep the runs in a table, one lane per run):
+// first and last sorted slot and the lattice translation of its candidates.
+__device__ __forceinline__ void stencil_run(const E2fCellsView& cv, int slot, int r, int& lo, int& hi, float4& sh) {
+    const E2fSegGrid g = cv.grid[cv.sseg[slot]];
+    const int local = cv.scell[slot] - g.base;
+    const int cx = local % g.nx, rr = r % 9;
+    int y = (local / g.nx) % g.ny + (rr % 3) - 1, z = local / (g.nx * g.ny) + (rr / 3) - 1;
+    sh = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+    if (g.ly > 0.0f) {
+        if (y < 0) { y += g.ny; sh.y = -g.ly; }
+        else if (y >= g.ny) { y -= g.ny; sh.y = g.ly; }
+    }
+    if (g.lz > 0.0f) {
+        if (z < 0) { z += g.nz; sh.z = -g.lz; }
+        else if (z >= g.nz) { z -= g.nz; sh.z = g.lz; }
+    }
+    bool have = y >= 0 && y < g.ny && z >= 0 && z < g.nz;
+    int x_first = max(cx - 1, 0), x_last = min(cx + 1, g.nx - 1);
+    if (r >= 9) {   // the cell across a periodic x face
+        have = have && g.lx > 0.0f && (cx == 0 || cx == g.nx - 1);
+        x_first = x_last = cx == 0 ? g.nx - 1 : 0;
+        sh.x = cx == 0 ? -g.lx : g.lx;
+    }
+    const int row = g.base + (z * g.ny + y) * g.nx;
+    lo = have ? cv.cell_start[row + x_first] : 0;
+    hi = have ? cv.cell_start[row + x_last + 1] : 0;
+}
+
 // The open-boundary stencil as plain arrays.
 __device__ __forceinline__ void stencil_rows(const E2fCellsView& cv, int slot, int (&lo)[9], int (&hi)[9]) {
     Stencil<false> s;

@@ -85,7 +85,12 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) void
     constexpr int NT = HAS_HI ? 2 : 1;
     constexpr int T0 = HAS_HI ? 0 : 1;                // first tile in use
     constexpr int C = 16 * H;
-    __shared__ int s_list[CAPM];
+    __shared__ int s_list[CAPM];   // entries: slot | run << RUN_SHIFT
+    // the target's 18 candidate runs (9 stencil rows, then their cells across a periodic x face): first slot,
+    // candidates before the run, lattice translation
+    __shared__ int s_rlo[32], s_rpre[32];
+    __shared__ float4 s_rsh[32];
+    constexpr int RUN_SHIFT = 26;    // the launcher checks N < 2^26
     __shared__ float s_D[SC * DST];
     __shared__ float s_bias[SC * H];
     __shared__ float s_wgt[SC];
@@ -163,36 +168,49 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) void
         for (int T = 0; T < NT; ++T) acc[h][T] = (f32x4){0.f, 0.f, 0.f, 0.f};
     float mu = -INFINITY, z = 0.0f;
 
-    // The 9 stencil runs as one candidate range [0, pre[9]): candidate c lies in run r when pre[r] <= c < pre[r+1].
-    int lo[9], pre[10];
-    {
-        int hi[9];
-        e2f::stencil_rows(P.cv, t, lo, hi);
-        pre[0] = 0;
+    // The runs as one candidate range [0, n_cand): candidate c lies in the last run r with s_rpre[r] <= c.
+    if (lane < 18) {
+        int rlo, rhi;
+        float4 sh;
+        e2f::stencil_run(P.cv, t, lane, rlo, rhi, sh);
+        int inc = rhi - rlo;   // -> inclusive scan over the runs
 #pragma unroll
-        for (int r = 0; r < 9; ++r) pre[r + 1] = pre[r] + (hi[r] - lo[r]);
+        for (int off = 1; off < 32; off <<= 1) {
+            const int up = __shfl_up(inc, off);
+            if (lane >= off) inc += up;
+        }
+        s_rlo[lane] = rlo;
+        s_rsh[lane] = sh;
+        s_rpre[lane + 1] = inc;
+        if (lane == 0) s_rpre[0] = 0;
+        if (lane < 13) s_rpre[19 + lane] = INT_MAX;   // stops of the search
+    } else if (lane < 32) {
+        s_rsh[lane] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
     }
-    const int n_cand = pre[9];
+    __syncthreads();
+    const int n_cand = s_rpre[18];
     int cbase = 0;
     while (true) {
         // ---- fill the list: 4 x 64 candidates per step, their positions requested together
         int cnt = 0;
         while (cbase < n_cand && cnt + 256 <= CAPM) {
-            int jj[4];
+            int jj[4], run[4];
             float4 pj[4];
-            // keep the lane id opaque here: otherwise every (lane - pre[r]) is hoisted out of the loop into its
-            // own register and the kernel spills
-            int ln = lane;
-            asm volatile("" : "+v"(ln));
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
-                const int c = cbase + 64 * u + ln;
-                int j = -1;
+                const int c = cbase + 64 * u + lane;
+                int r = 0;
 #pragma unroll
-                for (int r = 0; r < 9; ++r)
-                    if (c >= pre[r] && c < pre[r + 1]) j = lo[r] + c - pre[r];
+                for (int step = 16; step >= 1; step >>= 1)
+                    if (s_rpre[r + step] <= c) r += step;
+                const int j = c < n_cand ? s_rlo[r] + c - s_rpre[r] : -1;
                 jj[u] = j;
+                run[u] = r;
                 pj[u] = P.spos[j >= 0 ? j : t];
+                const float4 sh = s_rsh[r & 31];   // the image this run sees (zero without periodic axes)
+                pj[u].x += sh.x;
+                pj[u].y += sh.y;
+                pj[u].z += sh.z;
             }
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
@@ -200,7 +218,7 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) void
                 const bool ok = jj[u] >= 0 && jj[u] != t && e2f::is_neighbor(d2, P.rc2) &&
                                 e2f::under_cap(d2, pj[u].w, capd, capi);
                 const unsigned long long mask = __ballot(ok);
-                if (ok) s_list[cnt + __popcll(mask & ((1ull << lane) - 1ull))] = jj[u];
+                if (ok) s_list[cnt + __popcll(mask & ((1ull << lane) - 1ull))] = jj[u] | (run[u] << RUN_SHIFT);
                 cnt += __popcll(mask);
             }
             cbase += 256;
@@ -212,9 +230,9 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) void
             const int np = min(SC, cnt - p0);
             // ---- lanes = pairs: Wigner blocks (fp32), radial bias, gate
             if (lane < np) {
-                const int j = s_list[p0 + lane];
-                const float4 pj = P.spos[j];
-                const float dx = pj.x - pi.x, dy = pj.y - pi.y, dz = pj.z - pi.z;
+                const int e = s_list[p0 + lane], j = e & ((1 << RUN_SHIFT) - 1);
+                const float4 pj = P.spos[j], sh = s_rsh[e >> RUN_SHIFT];
+                const float dx = (pj.x + sh.x) - pi.x, dy = (pj.y + sh.y) - pi.y, dz = (pj.z + sh.z) - pi.z;
                 const float d = sqrtf(dx * dx + dy * dy + dz * dz);
                 e2f::align_D<L>(dx, dy, dz, d, s_D + lane * DST);
                 s_D[lane * DST + ZERO] = 0.0f;
@@ -247,7 +265,7 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) void
                 float2 kk[8][L + 1];
 #pragma unroll
                 for (int u = 0; u < 8; ++u) {
-                    const int j = s_list[p0 + min(pb + u, np - 1)];
+                    const int j = s_list[p0 + min(pb + u, np - 1)] & ((1 << RUN_SHIFT) - 1);
                     const float* kj = P.k + (size_t)j * (L + 1) * C + c0;
 #pragma unroll
                     for (int l = 0; l <= L; ++l) kk[u][l] = *reinterpret_cast<const float2*>(kj + l * C);
@@ -285,7 +303,7 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) void
             // Value rows live in one register set: as soon as head h of pair p has gone through its MFMAs, its
             // registers are refilled with head h of pair p+1, so every load has almost a whole pair of work to land.
             auto v_ptr = [&](int p) {
-                const int j = s_list[p0 + p];
+                const int j = s_list[p0 + p] & ((1 << RUN_SHIFT) - 1);
                 return P.vt + (size_t)j * H * NT * 256 + i * 16 + 4 * g;
             };
             // The operator of one pair, G = D^T P D, as bf16 A operands per output tile.
@@ -422,6 +440,7 @@ bool e2f_fused_mfma_supported(const e2f_ctx* ctx) {
 e2f_status e2f_launch_fused_mfma(const e2f_ctx* ctx, const E2fCellsView& cv, const e2f_weights* w, const E2fAttnWs& ws,
                                  float* out, hipStream_t st) {
     if (cv.N == 0) return E2F_OK;
+    if (cv.N >= (1 << 26)) return E2F_ERR_UNSUPPORTED;   // list entries carry the run in their top bits
     MfmaParams P;
     P.cv = cv;
     P.spos = ws.spos; P.q = ws.q; P.k = ws.k; P.vt = (const uint16_t*)ws.v; P.cw = ws.cw; P.WbT = ws.wbT; P.out = out;

@@ -141,6 +141,10 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(E2F_TIL
     __shared__ float s_cmax[NW][16];
     __shared__ float s_z[NW][16];
     __shared__ int s_cnt[NW];
+    // periodic boundaries: the pass's candidate runs (first and last slot, slot groups before the run, translation)
+    constexpr int NRUN = PBC ? 27 : 9;
+    __shared__ int s_rlo[32], s_rhi[32], s_rpre[32];
+    __shared__ float4 s_rsh[PBC ? 32 : 1];
     int* s_ent = reinterpret_cast<int*>(s_raw);
     float4* s_pos = reinterpret_cast<float4*>(s_raw + (CAPG + PADE) * 4);
     u32x4* s_W = reinterpret_cast<u32x4*>(s_raw + LIST_BYTES);   // [chunk of the group][mu][lane]
@@ -215,47 +219,56 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(E2F_TIL
         const bool t_active = tn >= a && tn < b;
         const int cxa = __builtin_amdgcn_readlane(tcx, a), cxb = __builtin_amdgcn_readlane(tcx, b - 1);
         // Runs of sorted slots that hold the pass's candidates: rows 0..8 are the stencil rows over the cells
-        // [cxa - 1, cxb + 1]; with periodic boundaries runs 9..17 are the rows' last cell seen across the low x
-        // face and runs 18..26 their first cell seen across the high x face, and rows that leave the grid along a
-        // periodic y or z come back in from the other side.  Candidates of a run are seen at their position plus
-        // the run's lattice translation.
-        constexpr int NR = PBC ? 27 : 9;
-        int lo[NR], hi[NR], pre[NR + 1];
-        float sxl = 0.0f, sxh = 0.0f, sy[3] = {0.0f, 0.0f, 0.0f}, sz[3] = {0.0f, 0.0f, 0.0f};
+        // [cxa - 1, cxb + 1].  With periodic boundaries there are 27: runs 9..17 are the rows' last cell seen across
+        // the low x face, runs 18..26 their first cell seen across the high x face, and rows that leave the grid
+        // along a periodic y or z come back in from the other side; candidates of a run are seen at their position
+        // plus the run's lattice translation.  The runs are a table in LDS, one thread per run (in registers they
+        // push the kernel's value rows into scratch).
+        int total;
         {
-            const E2fSegGrid G = P.cv.grid[seg_a];
-            const int cy = row_a % G.ny, cz = row_a / G.ny;
-            const int xa = max(cxa - 1, 0), xb = min(cxb + 1, G.nx - 1);
-            int xl = -1, xh = -1;
-            if (PBC && G.lx > 0.0f) {
-                if (cxa == 0) { xl = G.nx - 1; sxl = -G.lx; }
-                if (cxb == G.nx - 1) { xh = 0; sxh = G.lx; }
-            }
-#pragma unroll
-            for (int r = 0; r < 9; ++r) {
-                int y = cy + (r % 3) - 1, zc = cz + (r / 3) - 1;
+            __syncthreads();   // every wave has finished with the previous pass's table
+            if (threadIdx.x < NRUN) {
+                const int r = threadIdx.x, rr = r % 9, kind = r / 9;
+                const E2fSegGrid G = P.cv.grid[seg_a];
+                int y = row_a % G.ny + (rr % 3) - 1, zc = row_a / G.ny + (rr / 3) - 1;
+                float shx = 0.0f, shy = 0.0f, shz = 0.0f;
                 if (PBC && G.ly > 0.0f) {
-                    if (y < 0) { y += G.ny; sy[r % 3] = -G.ly; }
-                    else if (y >= G.ny) { y -= G.ny; sy[r % 3] = G.ly; }
+                    if (y < 0) { y += G.ny; shy = -G.ly; }
+                    else if (y >= G.ny) { y -= G.ny; shy = G.ly; }
                 }
                 if (PBC && G.lz > 0.0f) {
-                    if (zc < 0) { zc += G.nz; sz[r / 3] = -G.lz; }
-                    else if (zc >= G.nz) { zc -= G.nz; sz[r / 3] = G.lz; }
+                    if (zc < 0) { zc += G.nz; shz = -G.lz; }
+                    else if (zc >= G.nz) { zc -= G.nz; shz = G.lz; }
                 }
-                const bool inside = y >= 0 && y < G.ny && zc >= 0 && zc < G.nz;
+                bool have = y >= 0 && y < G.ny && zc >= 0 && zc < G.nz;
+                int x_first = max(cxa - 1, 0), x_last = min(cxb + 1, G.nx - 1);
+                if (kind == 1) {
+                    have = have && G.lx > 0.0f && cxa == 0;
+                    x_first = x_last = G.nx - 1;
+                    shx = -G.lx;
+                } else if (kind == 2) {
+                    have = have && G.lx > 0.0f && cxb == G.nx - 1;
+                    x_first = x_last = 0;
+                    shx = G.lx;
+                }
                 const int row = G.base + (zc * G.ny + y) * G.nx;
-                lo[r] = inside ? P.cv.cell_start[row + xa] : 0;
-                hi[r] = inside ? P.cv.cell_start[row + xb + 1] : 0;
-                if (PBC) {
-                    lo[9 + r] = inside && xl >= 0 ? P.cv.cell_start[row + xl] : 0;
-                    hi[9 + r] = inside && xl >= 0 ? P.cv.cell_start[row + xl + 1] : 0;
-                    lo[18 + r] = inside && xh >= 0 ? P.cv.cell_start[row + xh] : 0;
-                    hi[18 + r] = inside && xh >= 0 ? P.cv.cell_start[row + xh + 1] : 0;
-                }
-            }
-            pre[0] = 0;
+                const int rlo = have ? P.cv.cell_start[row + x_first] : 0;
+                const int rhi = have ? P.cv.cell_start[row + x_last + 1] : 0;
+                int inc = rhi > rlo ? ((rhi + 3) >> 2) - (rlo >> 2) : 0;   // -> inclusive scan over the 27 runs
 #pragma unroll
-            for (int r = 0; r < NR; ++r) pre[r + 1] = pre[r] + (hi[r] > lo[r] ? ((hi[r] + 3) >> 2) - (lo[r] >> 2) : 0);
+                for (int off = 1; off < 32; off <<= 1) {
+                    const int up = __shfl_up(inc, off);
+                    if (r >= off) inc += up;
+                }
+                s_rlo[r] = rlo;
+                s_rhi[r] = rhi;
+                s_rpre[r + 1] = inc;
+                if (PBC) s_rsh[r] = make_float4(shx, shy, shz, 0.0f);
+                if (r == 0) s_rpre[0] = 0;
+                if (r < 32 - (NRUN + 1)) s_rpre[NRUN + 1 + r] = INT_MAX;   // stops of the search below
+            }
+            __syncthreads();
+            total = s_rpre[NRUN];
         }
         // bounding box of the pass's targets: a candidate group is kept if one of its slots can be within the
         // cutoff of the box (pruning only; the predicate itself is evaluated per pair below)
@@ -274,7 +287,6 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(E2F_TIL
         for (int off = 1; off < 16; off <<= 1) reach2 = fmaxf(reach2, __shfl_xor(reach2, off));
         const float prune2 = reach2 * 1.001f;
 
-        const int total = pre[NR];
         for (int fbase = 0; fbase < total; fbase += 256) {
             // ---- a batch of the candidate list: 256 slot groups, 64 per wave, kept groups packed in order into
             // entries (group << 4 | valid slots) with the slots' positions beside them
@@ -283,34 +295,33 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(E2F_TIL
             unsigned long long leaders[LU];
             float4 pj[LU];
             {
-                int ln = lane;
-                asm volatile("" : "+v"(ln));   // keeps (lane - pre[r]) from being hoisted out of the loop
+                const int ln = lane;
                 bool valid[LU];
 #pragma unroll
                 for (int u = 0; u < LU; ++u) {
                     const int fg = fbase + 16 * LU * wave + 16 * u + (ln >> 2);
                     int gq = -1, rlo = 0, rhi = 0;
-                    float shx = 0.0f, shy = 0.0f, shz = 0.0f;
+                    float4 sh = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+                    {
+                        int r = 0;   // the last run that starts at or before fg (empty runs start where the next does)
 #pragma unroll
-                    for (int r = 0; r < NR; ++r)
-                        if (fg >= pre[r] && fg < pre[r + 1]) {
-                            gq = (lo[r] >> 2) + fg - pre[r];
-                            rlo = lo[r];
-                            rhi = hi[r];
-                            if (PBC) {
-                                shx = r >= 18 ? sxh : (r >= 9 ? sxl : 0.0f);
-                                shy = sy[(r % 9) % 3];
-                                shz = sz[(r % 9) / 3];
-                            }
+                        for (int step = (PBC ? 16 : 8); step >= 1; step >>= 1)   // reaches entry 31 or 15
+                            if (s_rpre[r + step] <= fg) r += step;
+                        if (fg < total) {
+                            rlo = s_rlo[r];
+                            rhi = s_rhi[r];
+                            gq = (rlo >> 2) + fg - s_rpre[r];
+                            if (PBC) sh = s_rsh[r];
                         }
+                    }
                     const int slot = 4 * gq + (ln & 3);
                     grp[u] = gq;
                     valid[u] = gq >= 0 && slot >= rlo && slot < rhi;
                     pj[u] = P.spos[valid[u] ? slot : tslot];
                     if (PBC) {   // the image this run sees (the translation is exact; the sum rounds to binary32)
-                        pj[u].x += shx;
-                        pj[u].y += shy;
-                        pj[u].z += shz;
+                        pj[u].x += sh.x;
+                        pj[u].y += sh.y;
+                        pj[u].z += sh.z;
                     }
                 }
                 int mine = 0;

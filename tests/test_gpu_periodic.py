@@ -69,7 +69,7 @@ def run_periodic(torch, wl, targets=None, cap=None):
         P.close()
 
 
-@pytest.mark.parametrize("kernel", ["tile", "valu"])
+@pytest.mark.parametrize("kernel", ["tile", "pair", "valu"])
 def test_two_periodic_boxes_bf16(torch_cuda, kernel, monkeypatch):
     """Two boxes of different size in one batch, coordinates partly outside [0, len), tiles that span faces."""
     from paper_2601_16622_amd import workloads as W
@@ -86,10 +86,12 @@ def test_periodic_box_at_the_benchmark_shape_sampled(torch_cuda):
     run_periodic(torch_cuda, wl, targets=tg)
 
 
-def test_periodic_fp32_all_degrees_of_the_filter(torch_cuda):
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_periodic_all_degrees_of_the_filter(torch_cuda, dtype):
+    """lf = 1 and 2; in bf16 the degree-2 filter runs on the per-pair matrix-core kernel."""
     from paper_2601_16622_amd import workloads as W
     for lf in (1, 2):
-        wl = W.periodic_boxes((260, 150, 1), seed=3 + lf, L=2, C=32, H=2, B=6, cutoff=4.0, dtype="f32")
+        wl = W.periodic_boxes((260, 150, 1), seed=3 + lf, L=2, C=32, H=2, B=6, cutoff=4.0, dtype=dtype)
         wl["cfg"]["lf"] = lf
         run_periodic(torch_cuda, wl)
 
