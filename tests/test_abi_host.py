@@ -86,6 +86,30 @@ def test_entry_points_reject_bad_arguments_before_launching(lib):
         B.e2f_destroy(ctx)
 
 
+def test_periodic_cells_validate_the_box_on_the_host(lib):
+    """A periodic edge must hold three cell edges (3 * 1.0001 * cutoff) and be finite; entries <= 0 or NaN mean an
+    open axis.  All of this is decided before anything is launched."""
+    ctx = B.e2f_create(1, 16, 2, 8, 1, 5.0, "f32")
+    try:
+        cells = ctypes.c_void_p()
+        null, fake = ctypes.c_void_p(0), ctypes.c_void_p(4096)
+
+        def build(box, N=4, ws=fake, ws_bytes=16):
+            b = np.ascontiguousarray(box, dtype=np.float32)
+            return lib.e2f_build_cells_periodic(ctx, fake, fake, N, 1, ctypes.c_void_p(b.ctypes.data), ws, ws_bytes,
+                                                ctypes.byref(cells), null)
+        assert build([[15.0, 40.0, 40.0]]) == 2            # 15 < 15.0015
+        assert build([[40.0, 40.0, np.inf]]) == 2
+        assert build([[15.002, 0.0, -3.0]]) == 3           # valid box: the next check (workspace size) answers
+        assert build([[np.nan, 0.0, 0.0]]) == 3            # no periodic axis at all
+        assert build([[15.002, 15.002, 15.002]], ws=ctypes.c_void_p(4096 + 8), ws_bytes=1 << 20) == 1
+        # NULL box: the open-boundary call
+        assert lib.e2f_build_cells_periodic(ctx, null, null, 0, 0, null, null, 0, ctypes.byref(cells), null) == 0
+        lib.e2f_cells_destroy(cells)
+    finally:
+        B.e2f_destroy(ctx)
+
+
 def test_factorized_entry_point_sizes_and_limits(lib):
     """Three more fp32 [N][n][C] arrays on top of the untiled attention workspace; lf != 1 and head widths that are
     not a power of two <= 64 are refused before anything is launched."""
