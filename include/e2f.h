@@ -199,6 +199,30 @@ e2f_status e2f_attn_forward_factorized(e2f_ctx *ctx, const e2f_cells *cells, con
                                        float *out, void *ws, size_t ws_bytes, void *hip_stream);
 
 /*
+ * Backward pass of e2f_attn_forward for the degree-1 filter.  The paper gives the forward pass only (Algorithm 1);
+ * this is its derivative by the same rules: pair quantities are recomputed from positions, q, k, v and two per-atom
+ * softmax statistics, nothing per pair is stored, every atom's sums are formed by the workgroup that owns the atom.
+ * With L = sum(out * grad_out) for the neighbour sets of the forward call held fixed:
+ *   out       device float [N][(L_max+1)^2][C]: the result of e2f_attn_forward for the same arguments
+ *   grad_out  device float [N][(L_max+1)^2][C]: dL/d out
+ *   grad_pos  device float [N][3]: dL/d pos (forces are its negative), fully overwritten
+ *   grad_q    device float [N][L_max+1][C]: dL/d q, q the invariants of Eq. qk (before the 1/sqrt(d_k) scaling)
+ *   grad_k    device float [N][L_max+1][C]: dL/d k likewise
+ *   grad_v    device float [N][(L_max+1)^2][C]: dL/d v, v = W_V h (all three in the caller's atom order, fully
+ *             overwritten; the gradients with respect to h and the projection weights follow from them by the chain
+ *             rule through the l-wise linear maps, which is plain matrix work and not part of this call)
+ *   ws        device, at least e2f_attn_backward_workspace_bytes(ctx, N) bytes, 256-byte aligned
+ * Cell lists from e2f_build_cells and e2f_build_cells_periodic are accepted.  E2F_ERR_UNSUPPORTED: lf != 1, or a
+ * head width C/H that is not a power of two <= 64.  A neighbour cap has no backward form here (the capped
+ * neighbour relation is not symmetric).  Allocates nothing, does not synchronise.  Otherwise as e2f_attn_forward.
+ */
+size_t e2f_attn_backward_workspace_bytes(const e2f_ctx *ctx, int32_t N);
+e2f_status e2f_attn_backward(e2f_ctx *ctx, const e2f_cells *cells, const float *pos, const void *h,
+                             const int32_t *seg_offsets, int32_t N, int32_t S, const e2f_weights *w, const float *out,
+                             const float *grad_out, float *grad_pos, float *grad_q, float *grad_k, float *grad_v,
+                             void *ws, size_t ws_bytes, void *hip_stream);
+
+/*
  * Stand-alone EAAS tensor product (Sec. 3.3, Prop. EAAS; the operation of the paper's tensor-product timing table):
  * out[t] = h[t] (x) R^(lf)(r[t]) for t = 0..T-1, channel-wise with path weights, evaluated as rotate into the frame
  * of r[t], re-index with P, rotate back.  Uses L_max, C, lf and feat_dtype of the context.

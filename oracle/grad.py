@@ -24,9 +24,26 @@ def _edges(offsets, idx):
     return torch.from_numpy(tgt.astype(np.int64)), torch.from_numpy(np.asarray(idx, dtype=np.int64))
 
 
-def forward_torch(cfg, pos, h, weights, nbr, translation=None):
+def project_qkv(cfg, h, weights):
+    """q, k [N][L+1][C] (the invariants of Eq. qk, unscaled) and v [N][n][C] from the l-wise projections."""
+    L = cfg["L"]
+
+    def project(W):   # [L+1][C][C] (out, in) applied l-wise
+        blocks = [torch.einsum("oc,nmc->nmo", W[l], h[:, l * l:(l + 1) ** 2]) for l in range(L + 1)]
+        return torch.cat(blocks, dim=1)
+
+    def invariant(a, b):   # sum over m inside every degree: [N][L+1][C]
+        return torch.stack([(a[:, l * l:(l + 1) ** 2] * b[:, l * l:(l + 1) ** 2]).sum(1) for l in range(L + 1)], 1)
+
+    q = invariant(project(weights["WQ1"]), project(weights["WQ2"]))
+    k = invariant(project(weights["WK1"]), project(weights["WK2"]))
+    return q, k, project(weights["WV"])
+
+
+def forward_torch(cfg, pos, h, weights, nbr, translation=None, qkv=None):
     """The operator on torch float64 tensors (pos [N][3], h [N][n][C], weights as in oracle.attn_forward; any of them
     may require grad).  nbr = (offsets, idx) CSR lists, translation = None or [E][3] lattice translations.
+    qkv: None, or (q, k, v) tensors to use in place of the projections of h (to differentiate with respect to them).
     Returns out [N][n][C]."""
     L, C, H, B, lf = cfg["L"], cfg["C"], cfg["H"], cfg["B"], cfg["lf"]
     if lf != 1:
@@ -38,16 +55,7 @@ def forward_torch(cfg, pos, h, weights, nbr, translation=None):
     E = ti.shape[0]
     f64 = torch.float64
 
-    def project(W):   # [L+1][C][C] (out, in) applied l-wise
-        blocks = [torch.einsum("oc,nmc->nmo", W[l], h[:, l * l:(l + 1) ** 2]) for l in range(L + 1)]
-        return torch.cat(blocks, dim=1)
-
-    def invariant(a, b):   # sum over m inside every degree: [N][L+1][C]
-        return torch.stack([(a[:, l * l:(l + 1) ** 2] * b[:, l * l:(l + 1) ** 2]).sum(1) for l in range(L + 1)], 1)
-
-    q = invariant(project(weights["WQ1"]), project(weights["WQ2"]))
-    k = invariant(project(weights["WK1"]), project(weights["WK2"]))
-    v = project(weights["WV"])
+    q, k, v = project_qkv(cfg, h, weights) if qkv is None else qkv
     out = torch.zeros((N, n, C), dtype=f64)
     if E == 0:
         return out + 0.0 * (q.sum() + k.sum() + v.sum())
@@ -95,17 +103,24 @@ def forward_torch(cfg, pos, h, weights, nbr, translation=None):
 
 
 def attn_backward(cfg, pos, h, weights, nbr, grad_out, translation=None, wrt=("pos", "h")):
-    """Gradients of sum(out * grad_out) with respect to the named inputs ("pos", "h", or a weight name).
+    """Gradients of sum(out * grad_out) with respect to the named inputs: "pos", "h", a weight name, or "q", "k",
+    "v" (the projections of h taken as independent variables; not together with "h" or projection weights).
     Returns (out, {name: gradient}) as float64 numpy arrays."""
     tp = torch.tensor(np.asarray(pos, dtype=np.float64), requires_grad="pos" in wrt)
     th = torch.tensor(np.asarray(h, dtype=np.float64), requires_grad="h" in wrt)
     tw = {kk: torch.tensor(np.asarray(vv, dtype=np.float64), requires_grad=kk in wrt) for kk, vv in weights.items()}
-    out = forward_torch(cfg, tp, th, tw, nbr, translation)
+    qkv = None
+    if any(name in wrt for name in ("q", "k", "v")):
+        with torch.no_grad():
+            qkv = project_qkv(cfg, th, tw)
+        qkv = tuple(t.clone().requires_grad_(name in wrt) for t, name in zip(qkv, ("q", "k", "v")))
+    out = forward_torch(cfg, tp, th, tw, nbr, translation, qkv)
     loss = (out * torch.as_tensor(np.asarray(grad_out, dtype=np.float64))).sum()
     if wrt:
         loss.backward()
     grads = {}
     for name in wrt:
-        t = tp if name == "pos" else th if name == "h" else tw[name]
+        t = (tp if name == "pos" else th if name == "h" else qkv["qkv".index(name)] if name in ("q", "k", "v")
+             else tw[name])
         grads[name] = (t.grad if t.grad is not None else torch.zeros_like(t)).numpy()
     return out.detach().numpy(), grads

@@ -20,7 +20,8 @@ EXPORTS = ["e2f_status_string", "e2f_create", "e2f_destroy", "e2f_cells_workspac
            "e2f_attn_forward", "e2f_attn_forward_materialized", "e2f_profile_begin", "e2f_profile_end",
            "e2f_eaas_tensor_product", "e2f_attn_factorized_workspace_bytes", "e2f_attn_forward_factorized",
            "e2f_attn_capped_workspace_bytes", "e2f_attn_forward_capped", "e2f_build_neighbor_table",
-           "e2f_attn_table_workspace_bytes", "e2f_attn_forward_table", "e2f_build_cells_periodic"]
+           "e2f_attn_table_workspace_bytes", "e2f_attn_forward_table", "e2f_build_cells_periodic",
+           "e2f_attn_backward_workspace_bytes", "e2f_attn_backward"]
 STAGES = ("prepare", "project", "attention")
 
 
@@ -90,6 +91,11 @@ def load():
     L.e2f_attn_table_workspace_bytes.restype = sz
     L.e2f_attn_forward_table.argtypes = [vp, vp, vp, vp, vp, i32, i32, ctypes.POINTER(Weights), vp, i32, vp, vp, sz, vp]
     L.e2f_attn_forward_table.restype = ctypes.c_int
+    L.e2f_attn_backward_workspace_bytes.argtypes = [vp, i32]
+    L.e2f_attn_backward_workspace_bytes.restype = sz
+    L.e2f_attn_backward.argtypes = [vp, vp, vp, vp, vp, i32, i32, ctypes.POINTER(Weights), vp, vp, vp, vp, vp, vp, vp,
+                                    sz, vp]
+    L.e2f_attn_backward.restype = ctypes.c_int
     L.e2f_eaas_tensor_product.argtypes = [vp, vp, vp, vp, vp, i32, vp]
     L.e2f_eaas_tensor_product.restype = ctypes.c_int
     L.e2f_profile_begin.argtypes = [vp, i32]
@@ -225,6 +231,18 @@ def e2f_attn_forward_factorized(ctx, cells, pos, h, seg_offsets, weights, out, w
                                               _ptr(out), _ptr(ws), ws.numel(), _stream()), "e2f_attn_forward_factorized")
 
 
+def e2f_attn_backward_workspace_bytes(ctx, N):
+    return load().e2f_attn_backward_workspace_bytes(ctx, N)
+
+
+def e2f_attn_backward(ctx, cells, pos, h, seg_offsets, weights, out, grad_out, grad_pos, grad_q, grad_k, grad_v, ws):
+    N, S = pos.shape[0], seg_offsets.shape[0] - 1
+    w = _weights(weights)
+    _check(load().e2f_attn_backward(ctx, cells, _ptr(pos), _ptr(h), _ptr(seg_offsets), N, S, ctypes.byref(w), _ptr(out),
+                                    _ptr(grad_out), _ptr(grad_pos), _ptr(grad_q), _ptr(grad_k), _ptr(grad_v),
+                                    _ptr(ws), ws.numel(), _stream()), "e2f_attn_backward")
+
+
 def e2f_attn_forward_materialized(ctx, cells, pos, h, seg_offsets, weights, out, ws):
     """Returns (n_edges, peak_bytes_allocated_inside)."""
     N, S = pos.shape[0], seg_offsets.shape[0] - 1
@@ -333,6 +351,20 @@ class Problem:
             self.fact_ws = torch.empty(max(need, 256), dtype=torch.uint8, device=self.device)
         e2f_attn_forward_factorized(self.ctx, self.cells, self.pos, self.h, self.seg, self.weights, out, self.fact_ws)
         return out
+
+    def backward(self, grad_out, out=None):
+        """Gradients of sum(out * grad_out): (grad_pos [N][3], grad_q, grad_k [N][L+1][C], grad_v [N][n][C])."""
+        import torch
+        out = self.out if out is None else out
+        ws = self._scratch("bwd_ws", e2f_attn_backward_workspace_bytes(self.ctx, self.N))
+        L1 = self.cfg["L"] + 1
+        gp = torch.empty((self.N, 3), dtype=torch.float32, device=self.device)
+        gq = torch.empty((self.N, L1, self.cfg["C"]), dtype=torch.float32, device=self.device)
+        gk = torch.empty_like(gq)
+        gv = torch.empty((self.N, self.n, self.cfg["C"]), dtype=torch.float32, device=self.device)
+        e2f_attn_backward(self.ctx, self.cells, self.pos, self.h, self.seg, self.weights, out, grad_out, gp, gq, gk, gv,
+                          ws)
+        return gp, gq, gk, gv
 
     def forward_materialized(self, out=None):
         out = self.out if out is None else out

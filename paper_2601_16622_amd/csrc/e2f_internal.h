@@ -91,6 +91,14 @@ struct E2fAttnWs {
 E2fAttnWs e2f_attn_ws_layout(const e2f_ctx* ctx, int32_t N, void* ws, int v_layout);
 static inline int e2f_v_layout(const e2f_ctx* ctx) { return ctx->use_tile_attn ? 2 : (ctx->use_mfma_attn ? 1 : 0); }
 
+// Extra buffers of the backward pass, placed after the attention workspace (untiled v).
+struct E2fBwdWs {
+    float* lse;  // [N][H] log of the softmax normaliser per sorted slot and head
+    float* Dn;   // [N][H] <dL/d out_i, out_i> per head
+    float* G;    // [3][25][25] axis operators of the degree-1 filter
+    size_t bytes;
+};
+
 // Extra O(N) buffers of the factorized pipeline, placed after the attention workspace (untiled v).
 struct E2fFactWs {
     float* hp;   // [N][n][C] source terms h'
@@ -139,6 +147,13 @@ e2f_status e2f_launch_select_neighbors(const e2f_ctx* ctx, const E2fCellsView& c
 e2f_status e2f_launch_fused_table(const e2f_ctx* ctx, const E2fCellsView& cv, const e2f_weights* w, const E2fAttnWs& ws,
                                   const int32_t* table, int32_t K, float* out, hipStream_t st);
 bool e2f_tile_supported(const e2f_ctx* ctx);
+// G[mu][x_out][x_in], mu = x, y, z: the degree-1 filter's message for a unit pair vector along mu, from the path
+// coefficients cw (tile attention kernel, backward pass).
+e2f_status e2f_launch_axis_ops(const e2f_ctx* ctx, const float* cw, float* G, hipStream_t st);
+bool e2f_backward_supported(const e2f_ctx* ctx);
+e2f_status e2f_launch_backward(const e2f_ctx* ctx, const E2fCellsView& cv, const e2f_weights* w, const E2fAttnWs& ws,
+                               const E2fBwdWs& bw, const float* out, const float* grad_out, float* grad_pos,
+                               float* grad_q, float* grad_k, float* grad_v, hipStream_t st);
 e2f_status e2f_launch_tile(const e2f_ctx* ctx, const E2fCellsView& cv, const E2fAttnWs& ws, float* out, hipStream_t st);
 e2f_status e2f_launch_fused_mfma(const e2f_ctx* ctx, const E2fCellsView& cv, const e2f_weights* w, const E2fAttnWs& ws,
                                  float* out, hipStream_t st);

@@ -574,6 +574,18 @@ void launch_L(const TileParams& P, const float* cw, float* G, hipStream_t st) {
 
 }  // namespace
 
+e2f_status e2f_launch_axis_ops(const e2f_ctx* ctx, const float* cw, float* G, hipStream_t st) {
+    switch (ctx->cfg.L_max) {
+        case 1: k_axis_ops<1><<<1, 128, 0, st>>>(cw, G); break;
+        case 2: k_axis_ops<2><<<1, 128, 0, st>>>(cw, G); break;
+        case 3: k_axis_ops<3><<<1, 128, 0, st>>>(cw, G); break;
+        case 4: k_axis_ops<4><<<1, 128, 0, st>>>(cw, G); break;
+        default: return E2F_ERR_UNSUPPORTED;
+    }
+    E2F_HIP_CHECK(hipGetLastError());
+    return E2F_OK;
+}
+
 bool e2f_tile_supported(const e2f_ctx* ctx) {
     const int C = ctx->cfg.C;
     return ctx->cfg.feat_dtype == E2F_BF16 && ctx->cfg.lf == 1 && ctx->Ch == 16 && ctx->cfg.L_max >= 1 &&

@@ -1,0 +1,110 @@
+"""GPU parity of e2f_attn_backward against the gradient reference (the operator's definition under float64 autograd,
+oracle/grad.py), element by element, through the C-ABI: gradients with respect to positions and to q, k, v."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": 1e-4, "bf16": 2e-2}
+
+
+@pytest.fixture(scope="module")
+def torch_cuda():
+    import torch
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    from paper_2601_16622_amd import binding as B
+    B.load()   # fails loudly if the HIP library was not built
+    return torch
+
+
+def rel_l2(a, b):
+    nb = np.linalg.norm(b)
+    return float(np.linalg.norm(a - b) / nb) if nb > 0 else float(np.linalg.norm(a - b))
+
+
+def run_backward(torch, wl, seed=0):
+    import oracle as O
+    from oracle import grad as G
+    from paper_2601_16622_amd import binding as B
+    cfg = wl["cfg"]
+    ocfg = {k: cfg[k] for k in ("L", "C", "H", "B", "lf", "cutoff")}
+    box = wl.get("box")
+    if box is None:
+        nbr = O.neighbor_list(wl["pos"], wl["seg"], np.float32(cfg["cutoff"]))
+        pos64, tr = wl["pos"].astype(np.float64), None
+    else:
+        full = O.neighbor_list_periodic(wl["pos"], wl["seg"], np.float32(cfg["cutoff"]), box)
+        nbr = (full[0], full[1])
+        tr = O.edge_translations(wl["seg"], box, full[0], full[2])
+        pos64 = O.wrap_positions(wl["pos"], wl["seg"], box).astype(np.float64)
+        assert full[2].any()
+    go = np.random.default_rng(seed).normal(size=wl["h"].shape).astype(np.float32)
+    ref_out, ref = G.attn_backward(ocfg, pos64, wl["h"], wl["weights"], nbr, go, translation=tr,
+                                   wrt=("pos", "q", "k", "v"))
+    P = B.Problem(wl)
+    try:
+        P.build_cells()
+        P.forward()
+        torch.cuda.synchronize()
+        assert rel_l2(P.out.cpu().numpy().astype(np.float64), ref_out) <= TOL[cfg["dtype"]]
+        g = torch.from_numpy(go).to(P.device)
+        got = [x.cpu().numpy().astype(np.float64) for x in P.backward(g)]
+        torch.cuda.synchronize()
+        errs = {}
+        for name, arr in zip(("pos", "q", "k", "v"), got):
+            assert np.isfinite(arr).all(), name
+            assert np.abs(ref[name]).max() > 1e-6, name
+            errs[name] = rel_l2(arr, ref[name])
+            assert errs[name] <= TOL[cfg["dtype"]], (name, errs)
+        # translation invariance: the position gradients of every segment sum to zero
+        for s in range(len(wl["seg"]) - 1):
+            seg = slice(wl["seg"][s], wl["seg"][s + 1])
+            assert np.abs(got[0][seg].sum(0)).max() <= 1e-3 * max(1.0, np.abs(got[0][seg]).max())
+        return errs
+    finally:
+        P.close()
+
+
+def custom(seed, sizes, L, C, H, B, dtype, cutoff, side):
+    from paper_2601_16622_amd import workloads as W
+    rng = np.random.default_rng(seed)
+    cfg = dict(L=L, C=C, H=H, B=B, lf=1, cutoff=cutoff, dtype=dtype)
+    pos = [W.dart_throw_box(rng, n, side, origin=rng.uniform(-5, 5, 3)) for n in sizes]
+    return W._pack(cfg, pos, rng, elements=False)
+
+
+@pytest.mark.parametrize("L,C,H", [(1, 16, 2), (2, 32, 2), (3, 64, 1)])
+def test_backward_fp32(torch_cuda, L, C, H):
+    """Several segments, a single-atom segment (no neighbours: zero gradients), head widths 8, 16 and 64."""
+    wl = custom(10 + L, (150, 1, 90), L, C, H, 6, "f32", 3.5, 9.0)
+    run_backward(torch_cuda, wl)
+
+
+def test_backward_bf16_at_the_benchmark_shape(torch_cuda):
+    """L = 4, C = 128, 8 heads, bf16 features; more neighbours than one batch of the list holds."""
+    wl = custom(20, (260,), 4, 128, 8, 8, "bf16", 6.0, 10.0)
+    import oracle as O
+    off, _ = O.neighbor_list(wl["pos"], wl["seg"], np.float32(6.0))
+    assert np.diff(off).max() > 128
+    run_backward(torch_cuda, wl)
+
+
+def test_backward_periodic(torch_cuda):
+    from paper_2601_16622_amd import workloads as W
+    wl = W.periodic_boxes((220, 120), seed=5, L=2, C=32, H=2, B=6, cutoff=4.0, dtype="f32")
+    run_backward(torch_cuda, wl)
+
+
+def test_backward_rejects_what_it_does_not_cover(torch_cuda):
+    from paper_2601_16622_amd import binding as B
+    wl = custom(30, (60,), 2, 32, 2, 4, "f32", 3.5, 7.0)
+    wl["cfg"]["lf"] = 2
+    P = B.Problem(wl)
+    try:
+        P.build_cells()
+        P.forward()
+        with pytest.raises(B.E2fError) as e:
+            P.backward(torch_cuda.zeros_like(P.out))
+        assert e.value.code == 2
+    finally:
+        P.close()

@@ -79,3 +79,21 @@ def test_periodic_translations_enter_the_pair_vectors():
     ref = O.attn_forward(cfg, pos, h, seg, w, box=box, nbr=nbr)
     np.testing.assert_allclose(out, ref, atol=1e-12)
     np.testing.assert_allclose(g["pos"].sum(0), 0.0, atol=1e-10)
+
+
+def test_gradients_with_respect_to_q_k_v_chain_to_the_gradient_with_respect_to_h():
+    """dL/dh assembled by hand from dL/dq, dL/dk, dL/dv through the l-wise maps equals autograd's dL/dh."""
+    cfg, pos, seg, h, w, nbr, go = case(4, L=2, C=4, H=2, per_seg=9)
+    _, g = G.attn_backward(cfg, pos, h, w, nbr, go, wrt=("q", "k", "v"))
+    _, gh = G.attn_backward(cfg, pos, h, w, nbr, go, wrt=("h",))
+    L = cfg["L"]
+    dh = np.zeros_like(h)
+    for l in range(L + 1):
+        blk = slice(l * l, (l + 1) ** 2)
+        x = h[:, blk]                                               # [N][2l+1][C]
+        for W1, W2, gq in ((w["WQ1"][l], w["WQ2"][l], g["q"][:, l]), (w["WK1"][l], w["WK2"][l], g["k"][:, l])):
+            a1, a2 = x @ W1.T, x @ W2.T
+            dh[:, blk] += (gq[:, None, :] * a2) @ W1 + (gq[:, None, :] * a1) @ W2
+        dh[:, blk] += g["v"][:, blk] @ w["WV"][l]
+    assert np.abs(gh["h"]).max() > 1e-3
+    np.testing.assert_allclose(dh, gh["h"], atol=1e-12)
