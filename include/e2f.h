@@ -209,8 +209,11 @@ e2f_status e2f_attn_forward_factorized(e2f_ctx *ctx, const e2f_cells *cells, con
  *   grad_q    device float [N][L_max+1][C]: dL/d q, q the invariants of Eq. qk (before the 1/sqrt(d_k) scaling)
  *   grad_k    device float [N][L_max+1][C]: dL/d k likewise
  *   grad_v    device float [N][(L_max+1)^2][C]: dL/d v, v = W_V h (all three in the caller's atom order, fully
- *             overwritten; the gradients with respect to h and the projection weights follow from them by the chain
- *             rule through the l-wise linear maps, which is plain matrix work and not part of this call)
+ *             overwritten)
+ *   grad_h    device float [N][(L_max+1)^2][C] or NULL: dL/d h, by the chain rule from the three above through the
+ *             l-wise linear maps of Eq. qk (what an earlier layer, or a force evaluation through several layers,
+ *             needs); skipped when NULL.  The gradients with respect to the projection weights are sums over atoms
+ *             of outer products of the same quantities and are not formed here.
  *   ws        device, at least e2f_attn_backward_workspace_bytes(ctx, N) bytes, 256-byte aligned
  * Cell lists from e2f_build_cells and e2f_build_cells_periodic are accepted.  E2F_ERR_UNSUPPORTED: lf != 1, or a
  * head width C/H that is not a power of two <= 64.  A neighbour cap has no backward form here (the capped
@@ -220,7 +223,7 @@ size_t e2f_attn_backward_workspace_bytes(const e2f_ctx *ctx, int32_t N);
 e2f_status e2f_attn_backward(e2f_ctx *ctx, const e2f_cells *cells, const float *pos, const void *h,
                              const int32_t *seg_offsets, int32_t N, int32_t S, const e2f_weights *w, const float *out,
                              const float *grad_out, float *grad_pos, float *grad_q, float *grad_k, float *grad_v,
-                             void *ws, size_t ws_bytes, void *hip_stream);
+                             float *grad_h, void *ws, size_t ws_bytes, void *hip_stream);
 
 /*
  * Stand-alone EAAS tensor product (Sec. 3.3, Prop. EAAS; the operation of the paper's tensor-product timing table):

@@ -477,7 +477,7 @@ size_t e2f_attn_backward_workspace_bytes(const e2f_ctx* ctx, int32_t N) {
 e2f_status e2f_attn_backward(e2f_ctx* ctx, const e2f_cells* cells, const float* pos, const void* h,
                              const int32_t* seg_offsets, int32_t N, int32_t S, const e2f_weights* w, const float* out,
                              const float* grad_out, float* grad_pos, float* grad_q, float* grad_k, float* grad_v,
-                             void* ws, size_t ws_bytes, void* hip_stream) {
+                             float* grad_h, void* ws, size_t ws_bytes, void* hip_stream) {
     if (!ctx) return E2F_ERR_INVALID_ARG;
     if (!e2f_backward_supported(ctx)) return E2F_ERR_UNSUPPORTED;
     // same argument checks as the fused call (out is read here), against this call's own workspace size
@@ -490,7 +490,8 @@ e2f_status e2f_attn_backward(e2f_ctx* ctx, const e2f_cells* cells, const float* 
     const E2fBwdWs Bw = bwd_ws_layout(ctx, N, ws, L.bytes);
     if ((rc = e2f_launch_prepare(ctx, cells->view, pos, w, L, st)) != E2F_OK) return rc;
     if ((rc = e2f_launch_project_mfma(ctx, cells->view, h, w, L, 0, st)) != E2F_OK) return rc;
-    return e2f_launch_backward(ctx, cells->view, w, L, Bw, out, grad_out, grad_pos, grad_q, grad_k, grad_v, st);
+    return e2f_launch_backward(ctx, cells->view, w, L, Bw, out, grad_out, grad_pos, grad_q, grad_k, grad_v, h, grad_h,
+                               st);
 }
 
 e2f_status e2f_eaas_tensor_product(e2f_ctx* ctx, const void* h, const float* r, const float* w_path, float* out,

@@ -62,8 +62,10 @@ struct ListWalk {
     }
 };
 
+// The workgroup then evaluates what depends on the distance alone, once per pair instead of once per channel:
+// s_rad[e] = (phi, dphi/dd, d, -) and s_bias[e * H + h] = (b_h(d), db_h/dd).
 __device__ __forceinline__ int next_batch(const BwdParams& P, ListWalk& w, int t, const float4& pi, int* s_list,
-                                          float4* s_pos, int* s_ctl) {
+                                          float4* s_pos, float4* s_rad, float2* s_bias, int* s_ctl) {
     __syncthreads();   // the previous batch has been consumed
     if (threadIdx.x < 64) {
         const int lane = threadIdx.x;
@@ -100,38 +102,48 @@ __device__ __forceinline__ int next_batch(const BwdParams& P, ListWalk& w, int t
         }
     }
     __syncthreads();
-    return s_ctl[0];
-}
-
-// Radial bias of a head and its derivative with respect to the distance.
-__device__ __forceinline__ void radial_bias(const BwdParams& P, int head, float d, float& b, float& db) {
-    b = 0.0f;
-    db = 0.0f;
-    for (int i = 0; i < P.B; ++i) {
-        const float x = d - (float)i * P.rbf_step;
-        const float g = P.Wb[head * P.B + i] * __expf(-P.rbf_gamma * x * x);
-        b += g;
-        db += -2.0f * P.rbf_gamma * x * g;
+    const int cnt = s_ctl[0];
+    // what depends on the distance alone, spread over the whole workgroup: one (pair, head) item per thread and step
+    for (int it = threadIdx.x; it < cnt * P.H; it += blockDim.x) {
+        const int e = it / P.H, hh = it % P.H;
+        const float4 pj = s_pos[e];
+        const float rx = pj.x - pi.x, ry = pj.y - pi.y, rz = pj.z - pi.z;
+        const float d = sqrtf(rx * rx + ry * ry + rz * rz);
+        if (hh == 0) {
+            const float arg = 3.14159265358979f * d / P.cutoff;   // in [0, pi]
+            s_rad[e] = make_float4(0.5f * (1.0f + __cosf(arg)), -0.5f * 3.14159265358979f / P.cutoff * __sinf(arg), d, 0.0f);
+        }
+        float b = 0.0f, db = 0.0f;
+        for (int i = 0; i < P.B; ++i) {
+            const float x = d - (float)i * P.rbf_step;
+            const float g = P.Wb[hh * P.B + i] * __expf(-P.rbf_gamma * x * x);
+            b += g;
+            db += -2.0f * P.rbf_gamma * x * g;
+        }
+        s_bias[it] = make_float2(b, db);
     }
+    __syncthreads();
+    return cnt;
 }
 
-// u_mu = sum_{xo, xi} G_mu[xo][xi] A[xo] B[xi] over the non-zero pattern of the axis operators.
-template <int L>
-__device__ __forceinline__ void axis_bilinear(const float (&A)[(L + 1) * (L + 1)], const float (&B)[(L + 1) * (L + 1)],
-                                              const float* s_G, float (&u)[3]) {
+// Node-level products with the axis operators, once per atom: T[mu] = G_mu^T a (TRANSPOSE) or G_mu a.
+template <int L, bool TRANSPOSE>
+__device__ __forceinline__ void axis_apply(const float (&a)[(L + 1) * (L + 1)], const float* s_G,
+                                           float (&T)[3][(L + 1) * (L + 1)]) {
     constexpr int n = (L + 1) * (L + 1);
 #pragma unroll
     for (int mu = 0; mu < 3; ++mu) {
-        float acc = 0.0f;
 #pragma unroll
-        for (int xo = 0; xo < n; ++xo) {
-            float inner = 0.0f;
+        for (int x = 0; x < n; ++x) T[mu][x] = 0.0f;
+#pragma unroll
+        for (int xo = 0; xo < n; ++xo)
 #pragma unroll
             for (int xi = 0; xi < n; ++xi)
-                if ((E2F_AXIS_NZ[mu][xo] >> xi) & 1u) inner += s_G[(mu * E2F_MAX_N + xo) * E2F_MAX_N + xi] * B[xi];
-            acc += A[xo] * inner;
-        }
-        u[mu] = acc;
+                if ((E2F_AXIS_NZ[mu][xo] >> xi) & 1u) {
+                    const float gv = s_G[(mu * E2F_MAX_N + xo) * E2F_MAX_N + xi];
+                    if (TRANSPOSE) T[mu][xi] += gv * a[xo];
+                    else T[mu][xo] += gv * a[xi];
+                }
     }
 }
 
@@ -140,9 +152,11 @@ template <int L>
 __global__ __launch_bounds__(256) void k_bwd_stats(BwdParams P) {
     constexpr int n = (L + 1) * (L + 1);
     __shared__ int s_list[BCAP];
-    __shared__ float4 s_pos[BCAP];
+    __shared__ float4 s_pos[BCAP], s_rad[BCAP];
+    extern __shared__ float2 s_bias[];   // [BCAP][H]
     __shared__ int s_ctl[2];
-    const int t = blockIdx.x, C = P.C;
+    const int t = e2f::xcd_remap(blockIdx.x, P.cv.N), C = P.C;
+    if (t < 0) return;
     const bool live = (int)threadIdx.x < C;        // workgroups have at least one full wave: the list walk needs it
     const int c = live ? threadIdx.x : 0, head = c / P.Ch;
     const int a = P.cv.perm[t];
@@ -157,19 +171,14 @@ __global__ __launch_bounds__(256) void k_bwd_stats(BwdParams P) {
     ListWalk w;
     w.init(P.cv, t);
     while (true) {
-        const int cnt = next_batch(P, w, t, pi, s_list, s_pos, s_ctl);
+        const int cnt = next_batch(P, w, t, pi, s_list, s_pos, s_rad, s_bias, s_ctl);
         for (int e = 0; e < cnt; ++e) {
             const int j = s_list[e];
-            const float4 pj = s_pos[e];
-            const float rx = pj.x - pi.x, ry = pj.y - pi.y, rz = pj.z - pi.z;
-            const float d = sqrtf(rx * rx + ry * ry + rz * rz);
             float dot = 0.0f;
 #pragma unroll
             for (int l = 0; l <= L; ++l) dot += qv[l] * P.k[((size_t)j * (L + 1) + l) * C + c];
             dot = head_sum(dot, P.Ch);
-            float b, db;
-            radial_bias(P, head, d, b, db);
-            const float s = dot * P.tau + b;
+            const float s = dot * P.tau + s_bias[e * P.H + head].x;
             const float mn = fmaxf(m, s);
             z = z * __expf(m - mn) + __expf(s - mn);
             m = mn;
@@ -187,11 +196,13 @@ template <int L, typename VT>
 __global__ __launch_bounds__(256) void k_bwd_target(BwdParams P) {
     constexpr int n = (L + 1) * (L + 1);
     __shared__ int s_list[BCAP];
-    __shared__ float4 s_pos[BCAP];
+    __shared__ float4 s_pos[BCAP], s_rad[BCAP];
+    extern __shared__ float2 s_bias[];   // [BCAP][H]
     __shared__ int s_ctl[2];
     __shared__ float s_G[3 * E2F_MAX_N * E2F_MAX_N];
     __shared__ float s_gp[E2F_MAX_H][3];
-    const int t = blockIdx.x, C = P.C;
+    const int t = e2f::xcd_remap(blockIdx.x, P.cv.N), C = P.C;
+    if (t < 0) return;
     const bool live = (int)threadIdx.x < C;        // workgroups have at least one full wave: the list walk needs it
     const int c = live ? threadIdx.x : 0, head = c / P.Ch;
     const int a = P.cv.perm[t];
@@ -209,37 +220,41 @@ __global__ __launch_bounds__(256) void k_bwd_target(BwdParams P) {
     float gx = 0.0f, gy = 0.0f, gz = 0.0f;   // sum_j dL/dr_ij of this head
     ListWalk w;
     w.init(P.cv, t);
+    __syncthreads();
+    float gt[3][n];   // G_mu^T g_i: u_mu = <g_i, G_mu v_j> = <gt_mu, v_j>
+    axis_apply<L, true>(g, s_G, gt);
     while (true) {
-        const int cnt = next_batch(P, w, t, pi, s_list, s_pos, s_ctl);   // (the first barrier also covers s_G)
+        const int cnt = next_batch(P, w, t, pi, s_list, s_pos, s_rad, s_bias, s_ctl);
         for (int e = 0; e < cnt; ++e) {
             const int j = s_list[e];
             const float4 pj = s_pos[e];
             const float rx = pj.x - pi.x, ry = pj.y - pi.y, rz = pj.z - pi.z;
-            const float d = sqrtf(rx * rx + ry * ry + rz * rz);
+            const float4 rad = s_rad[e];
+            const float2 bb = s_bias[e * P.H + head];
             float kv[L + 1], dot = 0.0f;
 #pragma unroll
             for (int l = 0; l <= L; ++l) {
                 kv[l] = P.k[((size_t)j * (L + 1) + l) * C + c];
                 dot += qv[l] * kv[l];
             }
-            float vj[n];
+            float u[3] = {0.0f, 0.0f, 0.0f};
 #pragma unroll
-            for (int x = 0; x < n; ++x) vj[x] = e2f::load_as_float<VT>((const VT*)P.v + ((size_t)j * n + x) * C + c);
-            float u[3];
-            axis_bilinear<L>(g, vj, s_G, u);
+            for (int x = 0; x < n; ++x) {
+                const float vx = e2f::load_as_float<VT>((const VT*)P.v + ((size_t)j * n + x) * C + c);
+                u[0] += gt[0][x] * vx;
+                u[1] += gt[1][x] * vx;
+                u[2] += gt[2][x] * vx;
+            }
             dot = head_sum(dot, P.Ch);
             u[0] = head_sum(u[0], P.Ch);
             u[1] = head_sum(u[1], P.Ch);
             u[2] = head_sum(u[2], P.Ch);
-            float b, db;
-            radial_bias(P, head, d, b, db);
-            const float p = __expf(dot * P.tau + b - lse);
-            const float phi = e2f::radial_gate(d, P.cutoff);
-            const float dphi = -0.5f * 3.14159265358979f / P.cutoff * __sinf(3.14159265358979f * d / P.cutoff);
+            const float p = __expf(dot * P.tau + bb.x - lse);
+            const float phi = rad.x, dphi = rad.y;
             const float wsum = rx * u[0] + ry * u[1] + rz * u[2];
             const float ds = p * (phi * wsum - Dn);
             const float alpha = p * phi;
-            const float dd = (ds * db + p * wsum * dphi) / d;
+            const float dd = (ds * bb.y + p * wsum * dphi) / rad.z;
 #pragma unroll
             for (int l = 0; l <= L; ++l) dq[l] += P.tau * ds * kv[l];
             gx += alpha * u[0] + dd * rx;
@@ -271,11 +286,13 @@ template <int L, typename VT>
 __global__ __launch_bounds__(256) void k_bwd_source(BwdParams P) {
     constexpr int n = (L + 1) * (L + 1);
     __shared__ int s_list[BCAP];
-    __shared__ float4 s_pos[BCAP];
+    __shared__ float4 s_pos[BCAP], s_rad[BCAP];
+    extern __shared__ float2 s_bias[];   // [BCAP][H]
     __shared__ int s_ctl[2];
     __shared__ float s_G[3 * E2F_MAX_N * E2F_MAX_N];
     __shared__ float s_gp[E2F_MAX_H][3];
-    const int t = blockIdx.x, C = P.C;
+    const int t = e2f::xcd_remap(blockIdx.x, P.cv.N), C = P.C;
+    if (t < 0) return;
     const bool live = (int)threadIdx.x < C;        // workgroups have at least one full wave: the list walk needs it
     const int c = live ? threadIdx.x : 0, head = c / P.Ch;
     const int a = P.cv.perm[t];
@@ -295,14 +312,18 @@ __global__ __launch_bounds__(256) void k_bwd_source(BwdParams P) {
     float gx = 0.0f, gy = 0.0f, gz = 0.0f;   // sum_i dL/dr_ij of this head
     ListWalk w;
     w.init(P.cv, t);
+    __syncthreads();
+    float Gv[3][n];   // G_mu v_j: u_mu = <g_i, G_mu v_j>
+    axis_apply<L, false>(vj, s_G, Gv);
     while (true) {
-        const int cnt = next_batch(P, w, t, pj, s_list, s_pos, s_ctl);
+        const int cnt = next_batch(P, w, t, pj, s_list, s_pos, s_rad, s_bias, s_ctl);
         for (int e = 0; e < cnt; ++e) {
             const int i = s_list[e];           // the target, seen from j at its image s_pos[e]
             const float4 pim = s_pos[e];
             const int ai = __float_as_int(pim.w);
             const float rx = pj.x - pim.x, ry = pj.y - pim.y, rz = pj.z - pim.z;   // r_ij = pos_j - pos_i
-            const float d = sqrtf(rx * rx + ry * ry + rz * rz);
+            const float4 rad = s_rad[e];
+            const float2 bb = s_bias[e * P.H + head];
             float qv[L + 1], dot = 0.0f;
 #pragma unroll
             for (int l = 0; l <= L; ++l) {
@@ -310,23 +331,24 @@ __global__ __launch_bounds__(256) void k_bwd_source(BwdParams P) {
                 dot += qv[l] * kv[l];
             }
             float g[n];
+            float u[3] = {0.0f, 0.0f, 0.0f};
 #pragma unroll
-            for (int x = 0; x < n; ++x) g[x] = P.gout[((size_t)ai * n + x) * C + c];
-            float u[3];
-            axis_bilinear<L>(g, vj, s_G, u);
+            for (int x = 0; x < n; ++x) {
+                g[x] = P.gout[((size_t)ai * n + x) * C + c];
+                u[0] += Gv[0][x] * g[x];
+                u[1] += Gv[1][x] * g[x];
+                u[2] += Gv[2][x] * g[x];
+            }
             dot = head_sum(dot, P.Ch);
             u[0] = head_sum(u[0], P.Ch);
             u[1] = head_sum(u[1], P.Ch);
             u[2] = head_sum(u[2], P.Ch);
-            float b, db;
-            radial_bias(P, head, d, b, db);
-            const float p = __expf(dot * P.tau + b - P.lse[(size_t)i * P.H + head]);
-            const float phi = e2f::radial_gate(d, P.cutoff);
-            const float dphi = -0.5f * 3.14159265358979f / P.cutoff * __sinf(3.14159265358979f * d / P.cutoff);
+            const float p = __expf(dot * P.tau + bb.x - P.lse[(size_t)i * P.H + head]);
+            const float phi = rad.x, dphi = rad.y;
             const float wsum = rx * u[0] + ry * u[1] + rz * u[2];
             const float ds = p * (phi * wsum - P.Dn[(size_t)i * P.H + head]);
             const float alpha = p * phi;
-            const float dd = (ds * db + p * wsum * dphi) / d;
+            const float dd = (ds * bb.y + p * wsum * dphi) / rad.z;
 #pragma unroll
             for (int l = 0; l <= L; ++l) dk[l] += P.tau * ds * qv[l];
             const float ax = alpha * rx, ay = alpha * ry, az = alpha * rz;
@@ -375,16 +397,124 @@ __global__ __launch_bounds__(256) void k_bwd_source(BwdParams P) {
     }
 }
 
+// ---- chain rule through the l-wise linear maps: dL/dh from dL/dq, dL/dk, dL/dv (all in the caller's atom order).
+// With a1 = W_Q1 x, a2 = W_Q2 x for a row x = h[atom][l, m] and q[l] = sum_m a1 a2 (Eq. qk):
+//     dx = W_Q1^T (dq[l] a2) + W_Q2^T (dq[l] a1) + the same with K + W_V^T dv[l, m].
+// One workgroup per 8 atoms, one thread per channel: the thread forms its output channel of the four forward
+// products (its own weight rows, the 8 rows x broadcast from LDS), then its input channel of the five transposed
+// products (weight columns, coalesced across the workgroup).  Plain vector-ALU matrix work, fp32 accumulation.
+template <typename T>
+__device__ __forceinline__ void load8(const T* p, float (&o)[8]);
+template <>
+__device__ __forceinline__ void load8<float>(const float* p, float (&o)[8]) {
+    const float4 a = *reinterpret_cast<const float4*>(p), b = *reinterpret_cast<const float4*>(p + 4);
+    o[0] = a.x; o[1] = a.y; o[2] = a.z; o[3] = a.w; o[4] = b.x; o[5] = b.y; o[6] = b.z; o[7] = b.w;
+}
+template <>
+__device__ __forceinline__ void load8<uint16_t>(const uint16_t* p, float (&o)[8]) {
+    const uint4 a = *reinterpret_cast<const uint4*>(p);
+    const uint32_t wv[4] = {a.x, a.y, a.z, a.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        o[2 * i] = __uint_as_float(wv[i] << 16);
+        o[2 * i + 1] = __uint_as_float(wv[i] & 0xffff0000u);
+    }
+}
+
+constexpr int PTA = 8;   // atoms per workgroup of the projection backward: every weight element read serves 8 rows
+
+template <typename T>
+__global__ __launch_bounds__(256) void k_bwd_project(const T* __restrict__ h, const T* __restrict__ WQ1,
+                                                     const T* __restrict__ WQ2, const T* __restrict__ WK1,
+                                                     const T* __restrict__ WK2, const T* __restrict__ WV,
+                                                     const float* __restrict__ gq, const float* __restrict__ gk,
+                                                     const float* __restrict__ gv, float* __restrict__ gh, int L, int C,
+                                                     int N) {
+    extern __shared__ float4 sm4[];   // x[C][PTA], then t[5][C][PTA]
+    float* s_x = reinterpret_cast<float*>(sm4);
+    float* s_t = s_x + C * PTA;
+    const int a0 = blockIdx.x * PTA, c = threadIdx.x, n = (L + 1) * (L + 1);
+    int atom[PTA];
+#pragma unroll
+    for (int ta = 0; ta < PTA; ++ta) atom[ta] = min(a0 + ta, N - 1);   // a short last group repeats its last atom
+    for (int l = 0; l <= L; ++l) {
+        const size_t wo = (size_t)l * C * C;
+        float dqv[PTA], dkv[PTA];
+#pragma unroll
+        for (int ta = 0; ta < PTA; ++ta) {
+            dqv[ta] = gq[((size_t)atom[ta] * (L + 1) + l) * C + c];
+            dkv[ta] = gk[((size_t)atom[ta] * (L + 1) + l) * C + c];
+        }
+        for (int m = 0; m < 2 * l + 1; ++m) {
+            const int comp = l * l + m;
+#pragma unroll
+            for (int ta = 0; ta < PTA; ++ta) s_x[c * PTA + ta] = e2f::load_as_float<T>(h + ((size_t)atom[ta] * n + comp) * C + c);
+            __syncthreads();
+            float acc4[4][PTA];
+#pragma unroll
+            for (int k = 0; k < 4; ++k)
+#pragma unroll
+                for (int ta = 0; ta < PTA; ++ta) acc4[k][ta] = 0.0f;
+            for (int ci = 0; ci < C; ci += 8) {
+                float w[4][8];
+                load8<T>(WQ1 + wo + (size_t)c * C + ci, w[0]);
+                load8<T>(WQ2 + wo + (size_t)c * C + ci, w[1]);
+                load8<T>(WK1 + wo + (size_t)c * C + ci, w[2]);
+                load8<T>(WK2 + wo + (size_t)c * C + ci, w[3]);
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const float4 xa = *reinterpret_cast<const float4*>(s_x + (ci + u) * PTA);
+                    const float4 xb = *reinterpret_cast<const float4*>(s_x + (ci + u) * PTA + 4);
+                    const float xs[PTA] = {xa.x, xa.y, xa.z, xa.w, xb.x, xb.y, xb.z, xb.w};
+#pragma unroll
+                    for (int k = 0; k < 4; ++k)
+#pragma unroll
+                        for (int ta = 0; ta < PTA; ++ta) acc4[k][ta] += w[k][u] * xs[ta];
+                }
+            }
+#pragma unroll
+            for (int ta = 0; ta < PTA; ++ta) {
+                s_t[(0 * C + c) * PTA + ta] = dqv[ta] * acc4[1][ta];
+                s_t[(1 * C + c) * PTA + ta] = dqv[ta] * acc4[0][ta];
+                s_t[(2 * C + c) * PTA + ta] = dkv[ta] * acc4[3][ta];
+                s_t[(3 * C + c) * PTA + ta] = dkv[ta] * acc4[2][ta];
+                s_t[(4 * C + c) * PTA + ta] = gv[((size_t)atom[ta] * n + comp) * C + c];
+            }
+            __syncthreads();
+            float dx[PTA];
+#pragma unroll
+            for (int ta = 0; ta < PTA; ++ta) dx[ta] = 0.0f;
+            for (int co = 0; co < C; ++co) {
+                const size_t wi = wo + (size_t)co * C + c;
+                const float wk[5] = {e2f::load_as_float<T>(WQ1 + wi), e2f::load_as_float<T>(WQ2 + wi),
+                                     e2f::load_as_float<T>(WK1 + wi), e2f::load_as_float<T>(WK2 + wi),
+                                     e2f::load_as_float<T>(WV + wi)};
+#pragma unroll
+                for (int k = 0; k < 5; ++k) {
+                    const float4 ta4 = *reinterpret_cast<const float4*>(s_t + (k * C + co) * PTA);
+                    const float4 tb4 = *reinterpret_cast<const float4*>(s_t + (k * C + co) * PTA + 4);
+                    dx[0] += wk[k] * ta4.x; dx[1] += wk[k] * ta4.y; dx[2] += wk[k] * ta4.z; dx[3] += wk[k] * ta4.w;
+                    dx[4] += wk[k] * tb4.x; dx[5] += wk[k] * tb4.y; dx[6] += wk[k] * tb4.z; dx[7] += wk[k] * tb4.w;
+                }
+            }
+#pragma unroll
+            for (int ta = 0; ta < PTA; ++ta)
+                if (a0 + ta < N) gh[((size_t)(a0 + ta) * n + comp) * C + c] = dx[ta];
+            __syncthreads();
+        }
+    }
+}
+
 template <int L>
 void launch_L(const e2f_ctx* ctx, const BwdParams& P, hipStream_t st) {
     const int N = P.cv.N, C = P.C < 64 ? 64 : P.C;
-    k_bwd_stats<L><<<N, C, 0, st>>>(P);
+    k_bwd_stats<L><<<e2f::xcd_grid(N), C, (size_t)BCAP * P.H * sizeof(float2), st>>>(P);
     if (ctx->cfg.feat_dtype == E2F_BF16) {
-        k_bwd_target<L, uint16_t><<<N, C, 0, st>>>(P);
-        k_bwd_source<L, uint16_t><<<N, C, 0, st>>>(P);
+        k_bwd_target<L, uint16_t><<<e2f::xcd_grid(N), C, (size_t)BCAP * P.H * sizeof(float2), st>>>(P);
+        k_bwd_source<L, uint16_t><<<e2f::xcd_grid(N), C, (size_t)BCAP * P.H * sizeof(float2), st>>>(P);
     } else {
-        k_bwd_target<L, float><<<N, C, 0, st>>>(P);
-        k_bwd_source<L, float><<<N, C, 0, st>>>(P);
+        k_bwd_target<L, float><<<e2f::xcd_grid(N), C, (size_t)BCAP * P.H * sizeof(float2), st>>>(P);
+        k_bwd_source<L, float><<<e2f::xcd_grid(N), C, (size_t)BCAP * P.H * sizeof(float2), st>>>(P);
     }
 }
 
@@ -397,7 +527,8 @@ bool e2f_backward_supported(const e2f_ctx* ctx) {
 
 e2f_status e2f_launch_backward(const e2f_ctx* ctx, const E2fCellsView& cv, const e2f_weights* w, const E2fAttnWs& ws,
                                const E2fBwdWs& bw, const float* out, const float* grad_out, float* grad_pos,
-                               float* grad_q, float* grad_k, float* grad_v, hipStream_t st) {
+                               float* grad_q, float* grad_k, float* grad_v, const void* h, float* grad_h,
+                               hipStream_t st) {
     if (cv.N == 0) return E2F_OK;
     BwdParams P;
     P.cv = cv;
@@ -414,6 +545,19 @@ e2f_status e2f_launch_backward(const e2f_ctx* ctx, const E2fCellsView& cv, const
         case 3: launch_L<3>(ctx, P, st); break;
         case 4: launch_L<4>(ctx, P, st); break;
         default: return E2F_ERR_UNSUPPORTED;
+    }
+    if (grad_h) {
+        const int C = P.C, L = ctx->cfg.L_max;
+        const size_t shm = (size_t)6 * C * PTA * sizeof(float);
+        const int groups = (cv.N + PTA - 1) / PTA;
+        if (ctx->cfg.feat_dtype == E2F_BF16)
+            k_bwd_project<uint16_t><<<groups, C, shm, st>>>((const uint16_t*)h, (const uint16_t*)w->WQ1, (const uint16_t*)w->WQ2,
+                                                          (const uint16_t*)w->WK1, (const uint16_t*)w->WK2,
+                                                          (const uint16_t*)w->WV, grad_q, grad_k, grad_v, grad_h, L, C, cv.N);
+        else
+            k_bwd_project<float><<<groups, C, shm, st>>>((const float*)h, (const float*)w->WQ1, (const float*)w->WQ2,
+                                                       (const float*)w->WK1, (const float*)w->WK2, (const float*)w->WV,
+                                                       grad_q, grad_k, grad_v, grad_h, L, C, cv.N);
     }
     E2F_HIP_CHECK(hipGetLastError());
     return E2F_OK;

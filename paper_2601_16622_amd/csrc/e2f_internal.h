@@ -153,7 +153,8 @@ e2f_status e2f_launch_axis_ops(const e2f_ctx* ctx, const float* cw, float* G, hi
 bool e2f_backward_supported(const e2f_ctx* ctx);
 e2f_status e2f_launch_backward(const e2f_ctx* ctx, const E2fCellsView& cv, const e2f_weights* w, const E2fAttnWs& ws,
                                const E2fBwdWs& bw, const float* out, const float* grad_out, float* grad_pos,
-                               float* grad_q, float* grad_k, float* grad_v, hipStream_t st);
+                               float* grad_q, float* grad_k, float* grad_v, const void* h, float* grad_h,
+                               hipStream_t st);
 e2f_status e2f_launch_tile(const e2f_ctx* ctx, const E2fCellsView& cv, const E2fAttnWs& ws, float* out, hipStream_t st);
 e2f_status e2f_launch_fused_mfma(const e2f_ctx* ctx, const E2fCellsView& cv, const e2f_weights* w, const E2fAttnWs& ws,
                                  float* out, hipStream_t st);

@@ -1,5 +1,5 @@
 """GPU parity of e2f_attn_backward against the gradient reference (the operator's definition under float64 autograd,
-oracle/grad.py), element by element, through the C-ABI: gradients with respect to positions and to q, k, v."""
+oracle/grad.py), element by element, through the C-ABI: gradients with respect to positions, to q, k, v and to h."""
 import numpy as np
 import pytest
 
@@ -41,6 +41,8 @@ def run_backward(torch, wl, seed=0):
     go = np.random.default_rng(seed).normal(size=wl["h"].shape).astype(np.float32)
     ref_out, ref = G.attn_backward(ocfg, pos64, wl["h"], wl["weights"], nbr, go, translation=tr,
                                    wrt=("pos", "q", "k", "v"))
+    _, ref_h = G.attn_backward(ocfg, pos64, wl["h"], wl["weights"], nbr, go, translation=tr, wrt=("h",))
+    ref["h"] = ref_h["h"]
     P = B.Problem(wl)
     try:
         P.build_cells()
@@ -51,7 +53,7 @@ def run_backward(torch, wl, seed=0):
         got = [x.cpu().numpy().astype(np.float64) for x in P.backward(g)]
         torch.cuda.synchronize()
         errs = {}
-        for name, arr in zip(("pos", "q", "k", "v"), got):
+        for name, arr in zip(("pos", "q", "k", "v", "h"), got):
             assert np.isfinite(arr).all(), name
             assert np.abs(ref[name]).max() > 1e-6, name
             errs[name] = rel_l2(arr, ref[name])
