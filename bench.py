@@ -248,6 +248,18 @@ def main():
         finally:
             Pp.close()
 
+        # backward pass of the fused call (positions, q, k, v, h), same workload
+        try:
+            g_out = torch.randn_like(P.out)
+            P.forward()
+            bwd_ms = timed(lambda: P.backward(g_out), reps=10)
+            bwd_core_ms = timed(lambda: P.backward(g_out, with_h=False), reps=10)
+            result["backward"] = {"ms": round(bwd_ms, 4), "ms_without_grad_h": round(bwd_core_ms, 4),
+                                  "over_forward": round(bwd_ms / fwd_ms, 2),
+                                  "workspace_bytes": int(B.e2f_attn_backward_workspace_bytes(P.ctx, N))}
+        except B.E2fError as e:
+            result["backward"] = {"error": str(e)}
+
     if not args.no_materialized:
         try:
             out_m = torch.empty_like(P.out)
