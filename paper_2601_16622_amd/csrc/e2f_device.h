@@ -33,7 +33,8 @@ __device__ __forceinline__ bool is_neighbor(float d2, float rc2) { return d2 < r
 // threshold is (0xffffffff, INT_MAX), above every key.  `w` is the w component of a sorted position: the atom index.
 __device__ __forceinline__ bool under_cap(float d2, float w, uint32_t cap_d2, int cap_idx) {
     const uint32_t b = __float_as_uint(d2);
-    return b < cap_d2 || (b == cap_d2 && __float_as_int(w) <= cap_idx);
+    // (bitwise on purpose: callers evaluate several candidates side by side and must stay in one basic block)
+    return (b < cap_d2) | ((b == cap_d2) & (__float_as_int(w) <= cap_idx));
 }
 
 // Coordinate folded into a periodic box of length len (inv = 1/len rounded to binary32), every operation rounded

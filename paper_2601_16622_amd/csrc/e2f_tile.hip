@@ -425,7 +425,10 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(E2F_TIL
                             float poly = cb[7];
 #pragma unroll
                             for (int bb = 6; bb >= 0; --bb) poly = poly * uu + cb[bb];
-                            const float bias = __builtin_amdgcn_exp2f(c_g * d2) * poly;
+                            float bias = __builtin_amdgcn_exp2f(c_g * d2) * poly;
+                            // (evaluated for every candidate, not under its predicate: otherwise each of the eight
+                            // candidates becomes a basic block of its own and their LDS reads are issued one by one)
+                            asm("" : "+v"(bias));
                             s2[u] = ok ? S[mt][r] + bias : -INFINITY;
                             gate[u] = e2f::radial_gate(d, P.cutoff);
                             cmax = fmaxf(cmax, s2[u]);
