@@ -22,6 +22,8 @@
 #include <stdio.h>
 #include <stdlib.h>
 
+#include <type_traits>
+
 #include "e2f_axis_pattern.h"
 #include "e2f_device.h"
 
@@ -517,51 +519,78 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(E2F_TIL
 
     // ---- epilogue: out = (1/z) sum_mu G_mu T_mu.  For one mu at a time the waves put their T_mu components into
     // LDS (the list and the weights are dead by then) and every wave forms the output components x_out = wave
-    // (mod NW) from the non-zero entries of G_mu.
-    constexpr int RO = (n + NW - 1) / NW;
-    f32x4 pr[RO];
-#pragma unroll
-    for (int i = 0; i < RO; ++i) pr[i] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    // (mod NW) from the non-zero entries of G_mu.  The code exists once per wave index, so that the components a
+    // wave owns and the sparsity pattern are compile-time facts and each step is straight-line code.
     z += __shfl_xor(z, 16);
     z += __shfl_xor(z, 32);
     if (lane < 16) s_z[wave][lane] = z;
+    auto finish = [&](auto wv_tag) {
+        constexpr int WV = decltype(wv_tag)::value;
+        constexpr int RO = (n - WV + NW - 1) / NW;                      // components WV, WV + NW, ...
+        constexpr int X0 = WV * (n / NW) + (WV < n % NW ? WV : n % NW);  // this wave's accumulator components
+        constexpr int NXW = n / NW + (WV < n % NW ? 1 : 0);
+        f32x4 pr[RO];
 #pragma unroll
-    for (int mu = 0; mu < 3; ++mu) {
-        __syncthreads();
+        for (int i = 0; i < RO; ++i) pr[i] = (f32x4){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int x = 0; x < NX; ++x)
-            if (x < NX - 1 || last_x) s_po[(x0 + x) * 64 + lane] = acc[mu][x];
-        __syncthreads();
+        for (int mu = 0; mu < 3; ++mu) {
+            __syncthreads();
 #pragma unroll
-        for (int xo = 0; xo < n; ++xo)
-            if (xo % NW == wave) {
+            for (int x = 0; x < NXW; ++x) s_po[(X0 + x) * 64 + lane] = acc[mu][x];
+            __syncthreads();
+#pragma unroll
+            for (int i = 0; i < RO; ++i) {
 #pragma unroll
                 for (int xi = 0; xi < n; ++xi)
-                    if ((E2F_AXIS_NZ[mu][xo] >> xi) & 1u)
-                        pr[xo / NW] += s_G[(mu * E2F_MAX_N + xo) * E2F_MAX_N + xi] * s_po[xi * 64 + lane];
+                    if ((E2F_AXIS_NZ[mu][WV + NW * i] >> xi) & 1u)
+                        pr[i] += s_G[(mu * E2F_MAX_N + WV + NW * i) * E2F_MAX_N + xi] * s_po[xi * 64 + lane];
             }
+        }
+        TICK(4)
+        f32x4 inv;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int tt = 4 * g + r;
+            float zt = 0.0f;
+#pragma unroll
+            for (int w = 0; w < NW; ++w) zt += s_z[w][tt];
+            inv[r] = zt > 0.0f ? 1.0f / zt : 0.0f;
+        }
+        // rows of the output: one base pointer per target row, components C floats apart
+        float* orp[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) orp[r] = P.out + (size_t)max(orow[r], 0) * n * P.C + head * 16 + tn;
+        const size_t cstride = (size_t)P.C;
+        if (nt == 16) {   // (uniform) every row exists: no per-row test
+#pragma unroll
+            for (int i = 0; i < RO; ++i)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) orp[r][(WV + NW * i) * cstride] = pr[i][r] * inv[r];
+        } else {
+#pragma unroll
+            for (int i = 0; i < RO; ++i)
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+                    if (orow[r] >= 0) orp[r][(WV + NW * i) * cstride] = pr[i][r] * inv[r];
+        }
+    };
+    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+    if (wave_u == 0) finish(std::integral_constant<int, 0>{});
+    if (wave_u == 1) finish(std::integral_constant<int, 1>{});
+    if constexpr (NW > 2) {
+        if (wave_u == 2) finish(std::integral_constant<int, 2>{});
+        if (wave_u == 3) finish(std::integral_constant<int, 3>{});
     }
-    TICK(4)
+    if constexpr (NW > 4) {
+        if (wave_u == 4) finish(std::integral_constant<int, 4>{});
+        if (wave_u == 5) finish(std::integral_constant<int, 5>{});
+        if (wave_u == 6) finish(std::integral_constant<int, 6>{});
+        if (wave_u == 7) finish(std::integral_constant<int, 7>{});
+    }
 #ifdef E2F_TIMING
     if (lane == 0 && P.dbg)
         for (int k = 0; k < 6; ++k) atomicAdd(P.dbg + k, tacc[k]);
 #endif
-    f32x4 inv;
-#pragma unroll
-    for (int r = 0; r < 4; ++r) {
-        const int tt = 4 * g + r;
-        float zt = 0.0f;
-#pragma unroll
-        for (int w = 0; w < NW; ++w) zt += s_z[w][tt];
-        inv[r] = zt > 0.0f ? 1.0f / zt : 0.0f;
-    }
-#pragma unroll
-    for (int xo = 0; xo < n; ++xo)
-        if (xo % NW == wave) {
-#pragma unroll
-            for (int r = 0; r < 4; ++r)
-                if (orow[r] >= 0) P.out[((size_t)orow[r] * n + xo) * P.C + head * 16 + tn] = pr[xo / NW][r] * inv[r];
-        }
 }
 
 template <int L>
