@@ -54,7 +54,9 @@ size_t cells_ws_layout(int32_t N, int32_t S, void* ws, e2f_cells* c) {
     char* tmp_slot = take((size_t)N * 4);
     char* atom_sub = take((size_t)N * 4);
     char* box = take((size_t)(S > 0 ? S : 1) * 6 * 4);
+    char* sinfo = take((size_t)N * 2 * sizeof(int4));
     if (c) {
+        c->view.sinfo = (const int4*)sinfo;
         c->box = (float*)box;
         c->host_box = nullptr;
         c->view.periodic = 0;

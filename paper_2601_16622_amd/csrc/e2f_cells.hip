@@ -217,8 +217,9 @@ __global__ void k_cells_scatter(const int32_t* __restrict__ atom_cell, const int
 // index) makes the final order independent of that.
 __global__ void k_cells_rank(const int32_t* __restrict__ tmp_slot, const int32_t* __restrict__ atom_cell,
                              const int32_t* __restrict__ atom_sub, const int32_t* __restrict__ atom_seg, const int32_t* __restrict__ cell_start, int N,
-                             int32_t* __restrict__ perm, int32_t* __restrict__ scell, int32_t* __restrict__ sseg,
-                             int32_t* __restrict__ atom_slot) {
+                             const E2fSegGrid* __restrict__ grid, int32_t* __restrict__ perm,
+                             int32_t* __restrict__ scell, int32_t* __restrict__ sseg, int32_t* __restrict__ atom_slot,
+                             int4* __restrict__ sinfo) {
     const int t = blockIdx.x * blockDim.x + threadIdx.x;
     if (t >= N) return;
     const int a = tmp_slot[t];
@@ -234,6 +235,10 @@ __global__ void k_cells_rank(const int32_t* __restrict__ tmp_slot, const int32_t
     scell[b + rank] = c;
     sseg[b + rank] = atom_seg[a];
     atom_slot[a] = b + rank;
+    const E2fSegGrid g = grid[atom_seg[a]];
+    const int local = c - g.base;
+    sinfo[2 * (b + rank)] = make_int4(atom_seg[a], local % g.nx, (local / g.nx) % g.ny, local / (g.nx * g.ny));
+    sinfo[2 * (b + rank) + 1] = make_int4(g.nx, g.ny, g.nz, g.base);
 }
 
 // One wave per target: walk the 27-cell stencil 64 candidates at a time.
@@ -419,10 +424,11 @@ e2f_status e2f_launch_build_cells(const e2f_ctx* ctx, e2f_cells* c, const float*
     k_cells_scan<<<1, 1024, 0, st>>>(cell_start, c->view.grid, S);
     k_cells_scatter<<<(N + tb - 1) / tb, tb, 0, st>>>(c->atom_cell, cell_start, N, c->cell_fill, c->tmp_slot);
     k_cells_rank<<<(N + tb - 1) / tb, tb, 0, st>>>(c->tmp_slot, c->atom_cell, c->atom_sub, c->atom_seg, cell_start, N,
-                                                  const_cast<int32_t*>(c->view.perm),
+                                                  c->view.grid, const_cast<int32_t*>(c->view.perm),
                                                   const_cast<int32_t*>(c->view.scell),
                                                   const_cast<int32_t*>(c->view.sseg),
-                                                  const_cast<int32_t*>(c->view.atom_slot));
+                                                  const_cast<int32_t*>(c->view.atom_slot),
+                                                  const_cast<int4*>(c->view.sinfo));
     E2F_HIP_CHECK(hipGetLastError());
     return E2F_OK;
 }

@@ -31,6 +31,8 @@ struct E2fCellsView {
     const int32_t* scell;       // [N] global cell id of the atom in each sorted slot
     const int32_t* sseg;        // [N] segment of the atom in each sorted slot
     const int32_t* atom_slot;   // [N] caller's atom index -> sorted slot
+    const int4* sinfo;          // [N][2] per sorted slot: (segment, cell x, cell y, cell z), (nx, ny, nz, first cell id)
+                                // of its grid: what a target needs to find its stencil without reading the grid
     int32_t N, S;
     int32_t periodic;           // whether any segment has a periodic axis (selects the kernels that follow images)
 };

@@ -169,14 +169,9 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(E2F_TIL
     const float4 tp = P.spos[tslot];
     const uint32_t capd = P.cap_d2 ? P.cap_d2[tslot] : 0xffffffffu;
     const int capi = P.cap_idx ? P.cap_idx[tslot] : INT_MAX;
-    const int tseg = P.cv.sseg[tslot];
-    int tcx, trow;
-    {
-        const E2fSegGrid tg = P.cv.grid[tseg];
-        const int loc = P.cv.scell[tslot] - tg.base;
-        tcx = loc % tg.nx;
-        trow = loc / tg.nx;
-    }
+    // the target's segment, cell and grid shape in one record (no dependent read of the grid)
+    const int4 ti0 = P.cv.sinfo[2 * tslot], ti1 = P.cv.sinfo[2 * tslot + 1];
+    const int tseg = ti0.x, tcx = ti0.y, trow = ti0.w * ti1.y + ti0.z;   // row of cells: cz * ny + cy
 
     // radial bias of this head as a polynomial in u = e^{2 gamma step d}:  b(d) = e^{-gamma d^2} sum_b cb[b] u^b,
     // cb[b] = Wb[h][b] e^{-gamma (b step)^2} (log2 e folded in)
@@ -229,9 +224,21 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(E2F_TIL
         int total;
         {
             __syncthreads();   // every wave has finished with the previous pass's table
+            // shape of the pass's grid from the first target's record; box lengths (periodic only) from the grid
+            struct { int nx, ny, nz, base; float lx, ly, lz; } G;
+            G.nx = __builtin_amdgcn_readlane(ti1.x, a);
+            G.ny = __builtin_amdgcn_readlane(ti1.y, a);
+            G.nz = __builtin_amdgcn_readlane(ti1.z, a);
+            G.base = __builtin_amdgcn_readlane(ti1.w, a);
+            G.lx = G.ly = G.lz = 0.0f;
+            if (PBC) {
+                const E2fSegGrid gs = P.cv.grid[seg_a];
+                G.lx = gs.lx;
+                G.ly = gs.ly;
+                G.lz = gs.lz;
+            }
             if (threadIdx.x < NRUN) {
                 const int r = threadIdx.x, rr = r % 9, kind = r / 9;
-                const E2fSegGrid G = P.cv.grid[seg_a];
                 int y = row_a % G.ny + (rr % 3) - 1, zc = row_a / G.ny + (rr / 3) - 1;
                 float shx = 0.0f, shy = 0.0f, shz = 0.0f;
                 if (PBC && G.ly > 0.0f) {
