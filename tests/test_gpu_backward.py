@@ -110,3 +110,53 @@ def test_backward_rejects_what_it_does_not_cover(torch_cuda):
         assert e.value.code == 2
     finally:
         P.close()
+
+
+def test_backward_scaling_point_sampled(torch_cuda):
+    """The 10 000-atom box the benchmark times, bf16, same launch configuration: dL/dpos and dL/dh of sampled atoms
+    against the gradient reference.  The gradient with respect to atom a involves only the outputs of a and of its
+    neighbours, so the reference runs on those targets (with their complete neighbourhoods) alone."""
+    import oracle as O
+    from oracle import grad as G
+    from paper_2601_16622_amd import binding as B
+    from paper_2601_16622_amd import workloads as W
+    wl = W.scaling_point(0)
+    cfg = wl["cfg"]
+    ocfg = {k: cfg[k] for k in ("L", "C", "H", "B", "lf", "cutoff")}
+    N = wl["pos"].shape[0]
+    off, idx = O.neighbor_list(wl["pos"], wl["seg"], np.float32(cfg["cutoff"]), use_cells=True)
+    go = np.random.default_rng(7).normal(size=wl["h"].shape).astype(np.float32)
+    P = B.Problem(wl)
+    try:
+        P.build_cells()
+        P.forward()
+        gp, _, _, _, gh = P.backward(torch_cuda.from_numpy(go).to(P.device))
+        torch_cuda.cuda.synchronize()
+        gp, gh = gp.cpu().numpy().astype(np.float64), gh.cpu().numpy().astype(np.float64)
+    finally:
+        P.close()
+    assert np.isfinite(gp).all() and np.isfinite(gh).all()
+    assert np.abs(gp.sum(0)).max() <= 1e-3 * np.abs(gp).max() * np.sqrt(N)   # translation invariance
+    deg = np.diff(off)
+    picks = np.random.default_rng(8).choice(np.nonzero((deg > 20) & (deg < 110))[0], 5, replace=False)
+    ref_p, got_p, ref_h, got_h = [], [], [], []
+    for a in picks:
+        targets = np.concatenate([[a], idx[off[a]:off[a + 1]]])
+        atoms = np.unique(np.concatenate([targets] + [idx[off[i]:off[i + 1]] for i in targets]))
+        local = -np.ones(N, dtype=np.int64)
+        local[atoms] = np.arange(len(atoms))
+        sub_off = np.zeros(len(atoms) + 1, dtype=np.int64)
+        rows = [np.zeros(0, dtype=np.int32)] * len(atoms)
+        for i in targets:
+            rows[local[i]] = local[idx[off[i]:off[i + 1]]].astype(np.int32)
+        sub_off[1:] = np.cumsum([len(r) for r in rows])
+        sub_go = np.zeros((len(atoms),) + go.shape[1:], dtype=np.float64)
+        sub_go[local[targets]] = go[targets]
+        _, g = G.attn_backward(ocfg, wl["pos"][atoms].astype(np.float64), wl["h"][atoms], wl["weights"],
+                               (sub_off, np.concatenate(rows)), sub_go, wrt=("pos", "h"))
+        ref_p.append(g["pos"][local[a]])
+        got_p.append(gp[a])
+        ref_h.append(g["h"][local[a]])
+        got_h.append(gh[a])
+    assert rel_l2(np.stack(got_p), np.stack(ref_p)) <= TOL["bf16"]
+    assert rel_l2(np.stack(got_h), np.stack(ref_h)) <= TOL["bf16"]
