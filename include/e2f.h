@@ -26,9 +26,11 @@
  *
  * Memory: every pointer marked "device" is GPU memory owned by the caller; the library never frees it.
  * Pointers marked "host" are ordinary process memory.  All work is enqueued on the HIP stream passed in
- * (a hipStream_t cast to void*; NULL is the default stream).  e2f_build_cells and e2f_attn_forward
- * allocate no device memory and do not synchronise with the host; e2f_attn_forward_materialized,
- * e2f_count_neighbors and e2f_list_neighbors are measurement/test entry points that may do both.
+ * (a hipStream_t cast to void*; NULL is the default stream).  e2f_build_cells, e2f_attn_forward, its capped, table
+ * and factorized forms, e2f_build_neighbor_table and e2f_attn_backward allocate no device memory and do not
+ * synchronise with the host (e2f_build_cells_periodic enqueues one small host-to-device copy of the boxes from a
+ * buffer the cells handle owns); e2f_attn_forward_materialized, e2f_count_neighbors and e2f_list_neighbors are
+ * measurement/test entry points that may do both.
  * Errors are reported through the return code; no entry point aborts or throws.  Arguments are checked
  * before anything is launched.
  */
