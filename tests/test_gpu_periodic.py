@@ -104,6 +104,15 @@ def test_slab_and_wire(torch_cuda, open_axes):
     run_periodic(torch_cuda, wl)
 
 
+def test_periodic_and_open_segments_in_one_batch(torch_cuda):
+    """A periodic box next to an open cluster (all three box entries zero) and an empty segment between them."""
+    from paper_2601_16622_amd import workloads as W
+    wl = W.periodic_boxes((420, 260), seed=11, L=2, C=64, H=4, cutoff=5.0, dtype="bf16")
+    wl["seg"] = np.array([0, 420, 420, 680], dtype=np.int32)
+    wl["box"] = np.stack([wl["box"][0], np.zeros(3, dtype=np.float32), np.zeros(3, dtype=np.float32)])
+    run_periodic(torch_cuda, wl)
+
+
 def test_full_fcc_crystal(torch_cuda):
     """Every atom of the periodic crystal has the 54 neighbours of the closed form; many exactly equidistant pairs
     and pair vectors along the axes."""
