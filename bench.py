@@ -20,7 +20,7 @@ import numpy as np
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
-# MI355X published peaks used for the roofline (see DESIGN.md): fp32 vector 157.3 TFLOP/s
+# MI355X published peaks used for the roofline: fp32 vector 157.3 TFLOP/s
 # (256 CUs x 4 SIMDs x 16 lanes x 2 (packed) x 2 (FMA) x 2.4 GHz), bf16 dense MFMA 2.5 PFLOP/s, HBM 8 TB/s.
 PEAK_ALU_TFLOPS = 157.3
 
