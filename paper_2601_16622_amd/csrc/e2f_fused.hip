@@ -156,7 +156,7 @@ __global__ __launch_bounds__(64) void k_fused_valu(FusedParams P) {
                     cmax = fmaxf(cmax, s_arr[p]);
                 }
             }
-            // one rescale of the running state per chunk (Algorithm 1, lines mu', z, A, taken chunk-wise)
+            // one rescale of the running state per chunk (the updates of mu, z and A in Algorithm 1, taken chunk-wise)
             const float mu_new = fmaxf(mu, cmax);
             const float scale = __expf(mu - mu_new);  // 0 on the first chunk (mu = -inf)
             z *= scale;
