@@ -94,7 +94,7 @@ def load():
     L.e2f_attn_backward_workspace_bytes.argtypes = [vp, i32]
     L.e2f_attn_backward_workspace_bytes.restype = sz
     L.e2f_attn_backward.argtypes = [vp, vp, vp, vp, vp, i32, i32, ctypes.POINTER(Weights), vp, vp, vp, vp, vp, vp, vp,
-                                    vp, sz, vp]
+                                    vp, vp, vp, sz, vp]
     L.e2f_attn_backward.restype = ctypes.c_int
     L.e2f_eaas_tensor_product.argtypes = [vp, vp, vp, vp, vp, i32, vp]
     L.e2f_eaas_tensor_product.restype = ctypes.c_int
@@ -236,13 +236,15 @@ def e2f_attn_backward_workspace_bytes(ctx, N):
 
 
 def e2f_attn_backward(ctx, cells, pos, h, seg_offsets, weights, out, grad_out, grad_pos, grad_q, grad_k, grad_v, grad_h,
-                      ws):
+                      ws, grad_Wb=None, grad_w_path=None):
     N, S = pos.shape[0], seg_offsets.shape[0] - 1
     w = _weights(weights)
     _check(load().e2f_attn_backward(ctx, cells, _ptr(pos), _ptr(h), _ptr(seg_offsets), N, S, ctypes.byref(w), _ptr(out),
                                     _ptr(grad_out), _ptr(grad_pos), _ptr(grad_q), _ptr(grad_k), _ptr(grad_v),
-                                    _ptr(grad_h) if grad_h is not None else ctypes.c_void_p(), _ptr(ws), ws.numel(),
-                                    _stream()), "e2f_attn_backward")
+                                    _ptr(grad_h) if grad_h is not None else ctypes.c_void_p(),
+                                    _ptr(grad_Wb) if grad_Wb is not None else ctypes.c_void_p(),
+                                    _ptr(grad_w_path) if grad_w_path is not None else ctypes.c_void_p(),
+                                    _ptr(ws), ws.numel(), _stream()), "e2f_attn_backward")
 
 
 def e2f_attn_forward_materialized(ctx, cells, pos, h, seg_offsets, weights, out, ws):
@@ -354,9 +356,9 @@ class Problem:
         e2f_attn_forward_factorized(self.ctx, self.cells, self.pos, self.h, self.seg, self.weights, out, self.fact_ws)
         return out
 
-    def backward(self, grad_out, out=None, with_h=True):
+    def backward(self, grad_out, out=None, with_h=True, with_weights=False):
         """Gradients of sum(out * grad_out): (grad_pos [N][3], grad_q, grad_k [N][L+1][C], grad_v [N][n][C],
-        grad_h [N][n][C] or None)."""
+        grad_h [N][n][C] or None); with_weights appends (grad_Wb [H][B], grad_w_path [L+1][L+1])."""
         import torch
         out = self.out if out is None else out
         ws = self._scratch("bwd_ws", e2f_attn_backward_workspace_bytes(self.ctx, self.N))
@@ -366,9 +368,13 @@ class Problem:
         gk = torch.empty_like(gq)
         gv = torch.empty((self.N, self.n, self.cfg["C"]), dtype=torch.float32, device=self.device)
         gh = torch.empty_like(gv) if with_h else None
+        gwb = gwp = None
+        if with_weights:
+            gwb = torch.empty((self.cfg["H"], self.cfg["B"]), dtype=torch.float32, device=self.device)
+            gwp = torch.empty((L1, L1), dtype=torch.float32, device=self.device)
         e2f_attn_backward(self.ctx, self.cells, self.pos, self.h, self.seg, self.weights, out, grad_out, gp, gq, gk, gv,
-                          gh, ws)
-        return gp, gq, gk, gv, gh
+                          gh, ws, gwb, gwp)
+        return (gp, gq, gk, gv, gh, gwb, gwp) if with_weights else (gp, gq, gk, gv, gh)
 
     def forward_materialized(self, out=None):
         out = self.out if out is None else out

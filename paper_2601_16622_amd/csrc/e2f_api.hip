@@ -467,6 +467,10 @@ static E2fBwdWs bwd_ws_layout(const e2f_ctx* ctx, int32_t N, void* ws, size_t at
     Bw.lse = (float*)take((size_t)N * ctx->cfg.H * 4);
     Bw.Dn = (float*)take((size_t)N * ctx->cfg.H * 4);
     Bw.G = (float*)take((size_t)3 * E2F_MAX_N * E2F_MAX_N * 4);
+    Bw.cw_unit = (float*)take((size_t)E2F_MAX_N * E2F_NP * 4);
+    Bw.Gu = (float*)take((size_t)3 * E2F_MAX_N * E2F_MAX_N * 4);
+    Bw.pWb = (float*)take((size_t)N * ctx->cfg.H * ctx->cfg.B * 4);
+    Bw.pwp = (float*)take((size_t)N * 32 * 4);
     Bw.bytes = off;
     return Bw;
 }
@@ -479,7 +483,8 @@ size_t e2f_attn_backward_workspace_bytes(const e2f_ctx* ctx, int32_t N) {
 e2f_status e2f_attn_backward(e2f_ctx* ctx, const e2f_cells* cells, const float* pos, const void* h,
                              const int32_t* seg_offsets, int32_t N, int32_t S, const e2f_weights* w, const float* out,
                              const float* grad_out, float* grad_pos, float* grad_q, float* grad_k, float* grad_v,
-                             float* grad_h, void* ws, size_t ws_bytes, void* hip_stream) {
+                             float* grad_h, float* grad_Wb, float* grad_w_path, void* ws, size_t ws_bytes,
+                             void* hip_stream) {
     if (!ctx) return E2F_ERR_INVALID_ARG;
     if (!e2f_backward_supported(ctx)) return E2F_ERR_UNSUPPORTED;
     // same argument checks as the fused call (out is read here), against this call's own workspace size
@@ -493,7 +498,7 @@ e2f_status e2f_attn_backward(e2f_ctx* ctx, const e2f_cells* cells, const float* 
     if ((rc = e2f_launch_prepare(ctx, cells->view, pos, w, L, st)) != E2F_OK) return rc;
     if ((rc = e2f_launch_project_mfma(ctx, cells->view, h, w, L, 0, st)) != E2F_OK) return rc;
     return e2f_launch_backward(ctx, cells->view, w, L, Bw, out, grad_out, grad_pos, grad_q, grad_k, grad_v, h, grad_h,
-                               st);
+                               grad_Wb, grad_w_path, st);
 }
 
 e2f_status e2f_eaas_tensor_product(e2f_ctx* ctx, const void* h, const float* r, const float* w_path, float* out,

@@ -21,6 +21,8 @@
 namespace {
 
 constexpr int BCAP = 128;   // neighbours per batch of the list
+constexpr int WP_BINS = 32;  // row length of the per-atom path-weight partials ((L_max + 1)^2 <= 25 used)
+constexpr int WB_PER_THREAD = 8;   // radial basis functions per thread of a head in the dWb sums: B <= 8 * C/H
 
 struct BwdParams {
     E2fCellsView cv;
@@ -38,6 +40,10 @@ struct BwdParams {
     float* gq;            // [N][L+1][C] caller's order
     float* gk;
     float* gv;            // [N][n][C] caller's order
+    // gradients of the attention's own weights (null unless asked for): per-atom partial sums, reduced afterwards
+    const float* Gu;      // [3][25][25] axis operators with unit path weights
+    float* pWb;           // [N][H][B]
+    float* pwp;           // [N][WP_BINS], bin li * (L_max + 1) + lo
     int C, H, B, Ch;
     float tau, rc2, cutoff, rbf_step, rbf_gamma;
 };
@@ -191,8 +197,14 @@ __global__ __launch_bounds__(256) void k_bwd_stats(BwdParams P) {
     }
 }
 
-// ---- what an atom owns as a target i: dq_i and -sum_j dL/dr_ij
-template <int L, typename VT>
+// Degree of component x (index l*l + l + m).
+__host__ __device__ constexpr int degree_of(int x) { return x >= 16 ? 4 : x >= 9 ? 3 : x >= 4 ? 2 : x >= 1 ? 1 : 0; }
+
+// ---- what an atom owns as a target i: dq_i and -sum_j dL/dr_ij; with WGRAD also its partial sums of
+//   dL/dWb[h][b]       = sum_j ds_ij,h exp(-gamma (d_ij - mu_b)^2)
+//   dL/dw_path[li][lo] = sum_mu sum_{xo in lo, xi in li} <g_i[xo], Gu_mu[xo][xi] T_mu[xi]>,  T_mu = sum_j alpha_ij r_mu v_j
+// (the message is linear in the path weights: G_mu[xo][xi] = w_path[li(xi)][lo(xo)] Gu_mu[xo][xi]).
+template <int L, typename VT, bool WGRAD>
 __global__ __launch_bounds__(256) void k_bwd_target(BwdParams P) {
     constexpr int n = (L + 1) * (L + 1);
     __shared__ int s_list[BCAP];
@@ -223,6 +235,15 @@ __global__ __launch_bounds__(256) void k_bwd_target(BwdParams P) {
     __syncthreads();
     float gt[3][n];   // G_mu^T g_i: u_mu = <g_i, G_mu v_j> = <gt_mu, v_j>
     axis_apply<L, true>(g, s_G, gt);
+    float accWb[WGRAD ? WB_PER_THREAD : 1], Tm[WGRAD ? 3 : 1][WGRAD ? n : 1];
+    if (WGRAD) {
+#pragma unroll
+        for (int i = 0; i < WB_PER_THREAD; ++i) accWb[i] = 0.0f;
+#pragma unroll
+        for (int mu = 0; mu < 3; ++mu)
+#pragma unroll
+            for (int x = 0; x < n; ++x) Tm[mu][x] = 0.0f;
+    }
     while (true) {
         const int cnt = next_batch(P, w, t, pi, s_list, s_pos, s_rad, s_bias, s_ctl);
         for (int e = 0; e < cnt; ++e) {
@@ -238,25 +259,39 @@ __global__ __launch_bounds__(256) void k_bwd_target(BwdParams P) {
                 dot += qv[l] * kv[l];
             }
             float u[3] = {0.0f, 0.0f, 0.0f};
+            dot = head_sum(dot, P.Ch);
+            const float p = __expf(dot * P.tau + bb.x - lse);
+            const float phi = rad.x, dphi = rad.y;
 #pragma unroll
             for (int x = 0; x < n; ++x) {
                 const float vx = e2f::load_as_float<VT>((const VT*)P.v + ((size_t)j * n + x) * C + c);
                 u[0] += gt[0][x] * vx;
                 u[1] += gt[1][x] * vx;
                 u[2] += gt[2][x] * vx;
+                if (WGRAD) {
+                    const float av = p * phi * vx;
+                    Tm[0][x] += av * rx;
+                    Tm[1][x] += av * ry;
+                    Tm[2][x] += av * rz;
+                }
             }
-            dot = head_sum(dot, P.Ch);
             u[0] = head_sum(u[0], P.Ch);
             u[1] = head_sum(u[1], P.Ch);
             u[2] = head_sum(u[2], P.Ch);
-            const float p = __expf(dot * P.tau + bb.x - lse);
-            const float phi = rad.x, dphi = rad.y;
             const float wsum = rx * u[0] + ry * u[1] + rz * u[2];
             const float ds = p * (phi * wsum - Dn);
             const float alpha = p * phi;
             const float dd = (ds * bb.y + p * wsum * dphi) / rad.z;
 #pragma unroll
             for (int l = 0; l <= L; ++l) dq[l] += P.tau * ds * kv[l];
+            if (WGRAD) {   // the head's threads share its basis functions: thread ci takes b = ci, ci + Ch, ...
+#pragma unroll
+                for (int i = 0; i < WB_PER_THREAD; ++i) {
+                    const int b = c % P.Ch + i * P.Ch;
+                    const float xb = rad.z - (float)b * P.rbf_step;
+                    if (b < P.B) accWb[i] += ds * __expf(-P.rbf_gamma * xb * xb);
+                }
+            }
             gx += alpha * u[0] + dd * rx;
             gy += alpha * u[1] + dd * ry;
             gz += alpha * u[2] + dd * rz;
@@ -279,6 +314,60 @@ __global__ __launch_bounds__(256) void k_bwd_target(BwdParams P) {
         for (int hh = 0; hh < P.H; ++hh) s += s_gp[hh][c];
         P.gpos[(size_t)a * 3 + c] = -s;
     }
+    if (WGRAD) {
+        if (live) {
+#pragma unroll
+            for (int i = 0; i < WB_PER_THREAD; ++i) {
+                const int b = c % P.Ch + i * P.Ch;
+                if (b < P.B) P.pWb[((size_t)a * P.H + head) * P.B + b] = accWb[i];
+            }
+        }
+        // path weights: bins per thread, then summed over the channels in a fixed order
+        __syncthreads();
+        for (int i = threadIdx.x; i < 3 * E2F_MAX_N * E2F_MAX_N; i += blockDim.x) s_G[i] = P.Gu[i];
+        __syncthreads();
+        float bins[(L + 1) * (L + 1)];
+#pragma unroll
+        for (int i = 0; i < (L + 1) * (L + 1); ++i) bins[i] = 0.0f;
+#pragma unroll
+        for (int mu = 0; mu < 3; ++mu)
+#pragma unroll
+            for (int xo = 0; xo < n; ++xo)
+#pragma unroll
+                for (int xi = 0; xi < n; ++xi)
+                    if ((E2F_AXIS_NZ[mu][xo] >> xi) & 1u)
+                        bins[degree_of(xi) * (L + 1) + degree_of(xo)] +=
+                            g[xo] * s_G[(mu * E2F_MAX_N + xo) * E2F_MAX_N + xi] * Tm[mu][xi];
+        float* s_red = reinterpret_cast<float*>(s_bias);   // [(L+1)^2][C]: the list batches are done
+        __syncthreads();
+        if (live) {
+#pragma unroll
+            for (int i = 0; i < (L + 1) * (L + 1); ++i) s_red[i * C + c] = bins[i];
+        }
+        __syncthreads();
+        if ((int)threadIdx.x < WP_BINS) {
+            float s = 0.0f;
+            if ((int)threadIdx.x < (L + 1) * (L + 1))
+                for (int cc = 0; cc < C; ++cc) s += s_red[threadIdx.x * C + cc];
+            P.pwp[(size_t)a * WP_BINS + threadIdx.x] = s;
+        }
+    }
+}
+
+// Sum of the per-atom partials, one workgroup per output element, in a fixed order.
+__global__ __launch_bounds__(256) void k_reduce_partials(const float* __restrict__ part, int N, int stride, int M,
+                                                         float* __restrict__ out) {
+    __shared__ float s_acc[256];
+    const int m = blockIdx.x;
+    float s = 0.0f;
+    for (int a = threadIdx.x; a < N; a += 256) s += part[(size_t)a * stride + m];
+    s_acc[threadIdx.x] = s;
+    __syncthreads();
+    for (int off = 128; off > 0; off >>= 1) {
+        if ((int)threadIdx.x < off) s_acc[threadIdx.x] += s_acc[threadIdx.x + off];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0 && m < M) out[m] = s_acc[0];
 }
 
 // ---- what an atom owns as a source j: dk_j, dv_j and +sum_i dL/dr_ij (added to the target kernel's share)
@@ -505,17 +594,22 @@ __global__ __launch_bounds__(256) void k_bwd_project(const T* __restrict__ h, co
     }
 }
 
+template <int L, typename VT>
+void launch_LV(const BwdParams& P, hipStream_t st) {
+    const int N = P.cv.N, C = P.C < 64 ? 64 : P.C;
+    const size_t shm = (size_t)BCAP * P.H * sizeof(float2);
+    // with weight gradients the same bytes later hold the [(L+1)^2][C] channel sums of the path-weight bins
+    const size_t shm_w = shm > (size_t)(L + 1) * (L + 1) * P.C * 4 ? shm : (size_t)(L + 1) * (L + 1) * P.C * 4;
+    k_bwd_stats<L><<<e2f::xcd_grid(N), C, shm, st>>>(P);
+    if (P.pWb) k_bwd_target<L, VT, true><<<e2f::xcd_grid(N), C, shm_w, st>>>(P);
+    else k_bwd_target<L, VT, false><<<e2f::xcd_grid(N), C, shm, st>>>(P);
+    k_bwd_source<L, VT><<<e2f::xcd_grid(N), C, shm, st>>>(P);
+}
+
 template <int L>
 void launch_L(const e2f_ctx* ctx, const BwdParams& P, hipStream_t st) {
-    const int N = P.cv.N, C = P.C < 64 ? 64 : P.C;
-    k_bwd_stats<L><<<e2f::xcd_grid(N), C, (size_t)BCAP * P.H * sizeof(float2), st>>>(P);
-    if (ctx->cfg.feat_dtype == E2F_BF16) {
-        k_bwd_target<L, uint16_t><<<e2f::xcd_grid(N), C, (size_t)BCAP * P.H * sizeof(float2), st>>>(P);
-        k_bwd_source<L, uint16_t><<<e2f::xcd_grid(N), C, (size_t)BCAP * P.H * sizeof(float2), st>>>(P);
-    } else {
-        k_bwd_target<L, float><<<e2f::xcd_grid(N), C, (size_t)BCAP * P.H * sizeof(float2), st>>>(P);
-        k_bwd_source<L, float><<<e2f::xcd_grid(N), C, (size_t)BCAP * P.H * sizeof(float2), st>>>(P);
-    }
+    if (ctx->cfg.feat_dtype == E2F_BF16) launch_LV<L, uint16_t>(P, st);
+    else launch_LV<L, float>(P, st);
 }
 
 }  // namespace
@@ -528,8 +622,10 @@ bool e2f_backward_supported(const e2f_ctx* ctx) {
 e2f_status e2f_launch_backward(const e2f_ctx* ctx, const E2fCellsView& cv, const e2f_weights* w, const E2fAttnWs& ws,
                                const E2fBwdWs& bw, const float* out, const float* grad_out, float* grad_pos,
                                float* grad_q, float* grad_k, float* grad_v, const void* h, float* grad_h,
-                               hipStream_t st) {
+                               float* grad_Wb, float* grad_w_path, hipStream_t st) {
     if (cv.N == 0) return E2F_OK;
+    const bool wgrad = grad_Wb || grad_w_path;
+    if (wgrad && ctx->cfg.B > WB_PER_THREAD * ctx->Ch) return E2F_ERR_UNSUPPORTED;
     BwdParams P;
     P.cv = cv;
     P.spos = ws.spos; P.q = ws.q; P.k = ws.k; P.v = ws.v; P.G = bw.G; P.Wb = w->Wb;
@@ -539,12 +635,23 @@ e2f_status e2f_launch_backward(const e2f_ctx* ctx, const E2fCellsView& cv, const
     P.tau = ctx->tau; P.rc2 = ctx->rc2; P.cutoff = ctx->cfg.cutoff; P.rbf_step = ctx->rbf_step; P.rbf_gamma = ctx->rbf_gamma;
     e2f_status rc = e2f_launch_axis_ops(ctx, ws.cw, bw.G, st);
     if (rc != E2F_OK) return rc;
+    P.Gu = nullptr; P.pWb = nullptr; P.pwp = nullptr;
+    if (wgrad) {
+        if ((rc = e2f_launch_unit_cw(ctx, bw.cw_unit, st)) != E2F_OK) return rc;
+        if ((rc = e2f_launch_axis_ops(ctx, bw.cw_unit, bw.Gu, st)) != E2F_OK) return rc;
+        P.Gu = bw.Gu; P.pWb = bw.pWb; P.pwp = bw.pwp;
+    }
     switch (ctx->cfg.L_max) {
         case 1: launch_L<1>(ctx, P, st); break;
         case 2: launch_L<2>(ctx, P, st); break;
         case 3: launch_L<3>(ctx, P, st); break;
         case 4: launch_L<4>(ctx, P, st); break;
         default: return E2F_ERR_UNSUPPORTED;
+    }
+    if (wgrad) {
+        const int L1 = ctx->cfg.L_max + 1, HB = ctx->cfg.H * ctx->cfg.B;
+        if (grad_Wb) k_reduce_partials<<<HB, 256, 0, st>>>(bw.pWb, cv.N, HB, HB, grad_Wb);
+        if (grad_w_path) k_reduce_partials<<<L1 * L1, 256, 0, st>>>(bw.pwp, cv.N, WP_BINS, L1 * L1, grad_w_path);
     }
     if (grad_h) {
         const int C = P.C, L = ctx->cfg.L_max;

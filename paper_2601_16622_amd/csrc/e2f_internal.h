@@ -98,6 +98,11 @@ struct E2fBwdWs {
     float* lse;  // [N][H] log of the softmax normaliser per sorted slot and head
     float* Dn;   // [N][H] <dL/d out_i, out_i> per head
     float* G;    // [3][25][25] axis operators of the degree-1 filter
+    // for the gradients of Wb and w_path: unit-weight path coefficients and axis operators, per-atom partial sums
+    float* cw_unit;  // [n][E2F_NP]
+    float* Gu;       // [3][25][25]
+    float* pWb;      // [N][H][B]
+    float* pwp;      // [N][32]
     size_t bytes;
 };
 
@@ -156,7 +161,9 @@ bool e2f_backward_supported(const e2f_ctx* ctx);
 e2f_status e2f_launch_backward(const e2f_ctx* ctx, const E2fCellsView& cv, const e2f_weights* w, const E2fAttnWs& ws,
                                const E2fBwdWs& bw, const float* out, const float* grad_out, float* grad_pos,
                                float* grad_q, float* grad_k, float* grad_v, const void* h, float* grad_h,
-                               hipStream_t st);
+                               float* grad_Wb, float* grad_w_path, hipStream_t st);
+// cw[comp][t] = P coefficient with every path weight one.
+e2f_status e2f_launch_unit_cw(const e2f_ctx* ctx, float* cw, hipStream_t st);
 e2f_status e2f_launch_tile(const e2f_ctx* ctx, const E2fCellsView& cv, const E2fAttnWs& ws, float* out, hipStream_t st);
 e2f_status e2f_launch_fused_mfma(const e2f_ctx* ctx, const E2fCellsView& cv, const e2f_weights* w, const E2fAttnWs& ws,
                                  float* out, hipStream_t st);

@@ -50,6 +50,18 @@ __global__ void k_prepare(E2fCellsView cv, const float* __restrict__ pos, const 
     }
 }
 
+// cw[comp][t] = P coefficient of the path into comp with every path weight one (w_path gradients).
+__global__ void k_unit_cw(int L, int lf, CoefTable tab, float* __restrict__ cw) {
+    const int t = blockIdx.x * blockDim.x + threadIdx.x;
+    const int n = (L + 1) * (L + 1);
+    if (t >= n * E2F_NP) return;
+    const int comp = t / E2F_NP, kk = t % E2F_NP;
+    int lo = 0;
+    while ((lo + 1) * (lo + 1) <= comp) ++lo;
+    const int li = lo - lf + kk;
+    cw[t] = (kk <= 2 * lf && li >= 0 && li <= L) ? tab.c[comp][kk] : 0.0f;
+}
+
 template <typename T>
 struct Frag;
 // bf16: v_mfma_f32_16x16x32_bf16, lane (i = lane%16, g = lane/16) supplies A[i][32S + 8g + 0..7] and
@@ -877,6 +889,15 @@ e2f_status e2f_launch_prepare(const e2f_ctx* ctx, const E2fCellsView& cv, const 
     if (ctx->cfg.H * ctx->cfg.B > work) work = ctx->cfg.H * ctx->cfg.B;
     k_prepare<<<(work + 255) / 256, 256, 0, st>>>(cv, pos, w->w_path, ctx->cfg.L_max, ctx->cfg.lf, tab, ws.spos, ws.cw,
                                                  w->Wb, ctx->cfg.H, ctx->cfg.B, ws.wbT);
+    E2F_HIP_CHECK(hipGetLastError());
+    return E2F_OK;
+}
+
+e2f_status e2f_launch_unit_cw(const e2f_ctx* ctx, float* cw, hipStream_t st) {
+    CoefTable tab;
+    for (int x = 0; x < E2F_MAX_N; ++x)
+        for (int t = 0; t < E2F_NP; ++t) tab.c[x][t] = ctx->coefP[x][t];
+    k_unit_cw<<<1, 256, 0, st>>>(ctx->cfg.L_max, ctx->cfg.lf, tab, cw);
     E2F_HIP_CHECK(hipGetLastError());
     return E2F_OK;
 }

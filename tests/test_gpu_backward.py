@@ -41,8 +41,9 @@ def run_backward(torch, wl, seed=0):
     go = np.random.default_rng(seed).normal(size=wl["h"].shape).astype(np.float32)
     ref_out, ref = G.attn_backward(ocfg, pos64, wl["h"], wl["weights"], nbr, go, translation=tr,
                                    wrt=("pos", "q", "k", "v"))
-    _, ref_h = G.attn_backward(ocfg, pos64, wl["h"], wl["weights"], nbr, go, translation=tr, wrt=("h",))
-    ref["h"] = ref_h["h"]
+    _, ref_h = G.attn_backward(ocfg, pos64, wl["h"], wl["weights"], nbr, go, translation=tr,
+                               wrt=("h", "Wb", "w_path"))
+    ref.update(ref_h)
     P = B.Problem(wl)
     try:
         P.build_cells()
@@ -50,10 +51,13 @@ def run_backward(torch, wl, seed=0):
         torch.cuda.synchronize()
         assert rel_l2(P.out.cpu().numpy().astype(np.float64), ref_out) <= TOL[cfg["dtype"]]
         g = torch.from_numpy(go).to(P.device)
-        got = [x.cpu().numpy().astype(np.float64) for x in P.backward(g)]
+        got = [x.cpu().numpy().astype(np.float64) for x in P.backward(g, with_weights=True)]
         torch.cuda.synchronize()
+        plain = P.backward(g)   # without the weight gradients the other outputs are the same numbers
+        for x, y in zip(plain, P.backward(g, with_weights=True)):
+            assert torch.equal(x, y)
         errs = {}
-        for name, arr in zip(("pos", "q", "k", "v", "h"), got):
+        for name, arr in zip(("pos", "q", "k", "v", "h", "Wb", "w_path"), got):
             assert np.isfinite(arr).all(), name
             assert np.abs(ref[name]).max() > 1e-6, name
             errs[name] = rel_l2(arr, ref[name])
