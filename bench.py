@@ -256,9 +256,11 @@ def main():
             bwd_core_ms = timed(lambda: P.backward(g_out, with_h=False), reps=10)
             bwd_w_ms = timed(lambda: P.backward(g_out, with_weights=True), reps=10)
             result["backward"] = {"ms": round(bwd_ms, 4), "ms_without_grad_h": round(bwd_core_ms, 4),
-                                  "ms_with_grad_Wb_w_path": round(bwd_w_ms, 4),
+                                  "ms_with_weight_gradients": round(bwd_w_ms, 4),
                                   "over_forward": round(bwd_ms / fwd_ms, 2),
-                                  "workspace_bytes": int(B.e2f_attn_backward_workspace_bytes(P.ctx, N))}
+                                  "workspace_bytes": int(B.e2f_attn_backward_workspace_bytes(P.ctx, N)),
+                                  "workspace_bytes_with_weight_gradients":
+                                      int(B.e2f_attn_backward_weights_workspace_bytes(P.ctx, N))}
         except B.E2fError as e:
             result["backward"] = {"error": str(e)}
 

@@ -214,23 +214,25 @@ e2f_status e2f_attn_forward_factorized(e2f_ctx *ctx, const e2f_cells *cells, con
  *             overwritten)
  *   grad_h    device float [N][(L_max+1)^2][C] or NULL: dL/d h, by the chain rule from the three above through the
  *             l-wise linear maps of Eq. qk (what an earlier layer, or a force evaluation through several layers,
- *             needs); skipped when NULL.  The gradients with respect to the five projection matrices are sums over
- *             atoms of outer products of grad_q, grad_k, grad_v with the projections of h (dense matrix products any
- *             BLAS forms from these outputs) and are not formed here.
+ *             needs); skipped when NULL.
  *   grad_Wb      device float [H][B] or NULL: dL/d Wb (radial bias weights), fully overwritten
  *   grad_w_path  device float [L_max+1][L_max+1] or NULL: dL/d w_path, fully overwritten (zero off the allowed paths);
  *             either of the two needs B <= 8 * C/H (E2F_ERR_UNSUPPORTED otherwise) and makes the call slower
+ *   grad_W    device float [5][L_max+1][C][C] or NULL: dL/d WQ1, WQ2, WK1, WK2, WV in this order (out channel, in
+ *             channel), fully overwritten; needs the larger workspace e2f_attn_backward_weights_workspace_bytes(ctx, N)
+ *             (five more [N][(L_max+1)^2][C] float arrays of row factors and 32 partial sums of the result)
  *   ws        device, at least e2f_attn_backward_workspace_bytes(ctx, N) bytes, 256-byte aligned
  * Cell lists from e2f_build_cells and e2f_build_cells_periodic are accepted.  E2F_ERR_UNSUPPORTED: lf != 1, or a
  * head width C/H that is not a power of two <= 64.  A neighbour cap has no backward form here (the capped
  * neighbour relation is not symmetric).  Allocates nothing, does not synchronise.  Otherwise as e2f_attn_forward.
  */
 size_t e2f_attn_backward_workspace_bytes(const e2f_ctx *ctx, int32_t N);
+size_t e2f_attn_backward_weights_workspace_bytes(const e2f_ctx *ctx, int32_t N);
 e2f_status e2f_attn_backward(e2f_ctx *ctx, const e2f_cells *cells, const float *pos, const void *h,
                              const int32_t *seg_offsets, int32_t N, int32_t S, const e2f_weights *w, const float *out,
                              const float *grad_out, float *grad_pos, float *grad_q, float *grad_k, float *grad_v,
-                             float *grad_h, float *grad_Wb, float *grad_w_path, void *ws, size_t ws_bytes,
-                             void *hip_stream);
+                             float *grad_h, float *grad_Wb, float *grad_w_path, float *grad_W, void *ws,
+                             size_t ws_bytes, void *hip_stream);
 
 /*
  * Stand-alone EAAS tensor product (Sec. 3.3, Prop. EAAS; the operation of the paper's tensor-product timing table):

@@ -21,7 +21,8 @@ EXPORTS = ["e2f_status_string", "e2f_create", "e2f_destroy", "e2f_cells_workspac
            "e2f_eaas_tensor_product", "e2f_attn_factorized_workspace_bytes", "e2f_attn_forward_factorized",
            "e2f_attn_capped_workspace_bytes", "e2f_attn_forward_capped", "e2f_build_neighbor_table",
            "e2f_attn_table_workspace_bytes", "e2f_attn_forward_table", "e2f_build_cells_periodic",
-           "e2f_attn_backward_workspace_bytes", "e2f_attn_backward"]
+           "e2f_attn_backward_workspace_bytes", "e2f_attn_backward",
+           "e2f_attn_backward_weights_workspace_bytes"]
 STAGES = ("prepare", "project", "attention")
 
 
@@ -93,8 +94,10 @@ def load():
     L.e2f_attn_forward_table.restype = ctypes.c_int
     L.e2f_attn_backward_workspace_bytes.argtypes = [vp, i32]
     L.e2f_attn_backward_workspace_bytes.restype = sz
+    L.e2f_attn_backward_weights_workspace_bytes.argtypes = [vp, i32]
+    L.e2f_attn_backward_weights_workspace_bytes.restype = sz
     L.e2f_attn_backward.argtypes = [vp, vp, vp, vp, vp, i32, i32, ctypes.POINTER(Weights), vp, vp, vp, vp, vp, vp, vp,
-                                    vp, vp, vp, sz, vp]
+                                    vp, vp, vp, vp, sz, vp]
     L.e2f_attn_backward.restype = ctypes.c_int
     L.e2f_eaas_tensor_product.argtypes = [vp, vp, vp, vp, vp, i32, vp]
     L.e2f_eaas_tensor_product.restype = ctypes.c_int
@@ -235,8 +238,12 @@ def e2f_attn_backward_workspace_bytes(ctx, N):
     return load().e2f_attn_backward_workspace_bytes(ctx, N)
 
 
+def e2f_attn_backward_weights_workspace_bytes(ctx, N):
+    return load().e2f_attn_backward_weights_workspace_bytes(ctx, N)
+
+
 def e2f_attn_backward(ctx, cells, pos, h, seg_offsets, weights, out, grad_out, grad_pos, grad_q, grad_k, grad_v, grad_h,
-                      ws, grad_Wb=None, grad_w_path=None):
+                      ws, grad_Wb=None, grad_w_path=None, grad_W=None):
     N, S = pos.shape[0], seg_offsets.shape[0] - 1
     w = _weights(weights)
     _check(load().e2f_attn_backward(ctx, cells, _ptr(pos), _ptr(h), _ptr(seg_offsets), N, S, ctypes.byref(w), _ptr(out),
@@ -244,6 +251,7 @@ def e2f_attn_backward(ctx, cells, pos, h, seg_offsets, weights, out, grad_out, g
                                     _ptr(grad_h) if grad_h is not None else ctypes.c_void_p(),
                                     _ptr(grad_Wb) if grad_Wb is not None else ctypes.c_void_p(),
                                     _ptr(grad_w_path) if grad_w_path is not None else ctypes.c_void_p(),
+                                    _ptr(grad_W) if grad_W is not None else ctypes.c_void_p(),
                                     _ptr(ws), ws.numel(), _stream()), "e2f_attn_backward")
 
 
@@ -358,23 +366,27 @@ class Problem:
 
     def backward(self, grad_out, out=None, with_h=True, with_weights=False):
         """Gradients of sum(out * grad_out): (grad_pos [N][3], grad_q, grad_k [N][L+1][C], grad_v [N][n][C],
-        grad_h [N][n][C] or None); with_weights appends (grad_Wb [H][B], grad_w_path [L+1][L+1])."""
+        grad_h [N][n][C] or None); with_weights appends (grad_Wb [H][B], grad_w_path [L+1][L+1],
+        grad_W [5][L+1][C][C])."""
         import torch
         out = self.out if out is None else out
-        ws = self._scratch("bwd_ws", e2f_attn_backward_workspace_bytes(self.ctx, self.N))
+        need = (e2f_attn_backward_weights_workspace_bytes if with_weights else e2f_attn_backward_workspace_bytes)(self.ctx, self.N)
+        ws = self._scratch("bwd_ws", need)
         L1 = self.cfg["L"] + 1
         gp = torch.empty((self.N, 3), dtype=torch.float32, device=self.device)
         gq = torch.empty((self.N, L1, self.cfg["C"]), dtype=torch.float32, device=self.device)
         gk = torch.empty_like(gq)
         gv = torch.empty((self.N, self.n, self.cfg["C"]), dtype=torch.float32, device=self.device)
         gh = torch.empty_like(gv) if with_h else None
-        gwb = gwp = None
+        gwb = gwp = gw = None
         if with_weights:
+            C = self.cfg["C"]
             gwb = torch.empty((self.cfg["H"], self.cfg["B"]), dtype=torch.float32, device=self.device)
             gwp = torch.empty((L1, L1), dtype=torch.float32, device=self.device)
+            gw = torch.empty((5, L1, C, C), dtype=torch.float32, device=self.device)
         e2f_attn_backward(self.ctx, self.cells, self.pos, self.h, self.seg, self.weights, out, grad_out, gp, gq, gk, gv,
-                          gh, ws, gwb, gwp)
-        return (gp, gq, gk, gv, gh, gwb, gwp) if with_weights else (gp, gq, gk, gv, gh)
+                          gh, ws, gwb, gwp, gw)
+        return (gp, gq, gk, gv, gh, gwb, gwp, gw) if with_weights else (gp, gq, gk, gv, gh)
 
     def forward_materialized(self, out=None):
         out = self.out if out is None else out

@@ -456,7 +456,7 @@ e2f_status e2f_attn_forward_factorized(e2f_ctx* ctx, const e2f_cells* cells, con
     return e2f_launch_factorized(ctx, cells->view, L, F, out, st);
 }
 
-static E2fBwdWs bwd_ws_layout(const e2f_ctx* ctx, int32_t N, void* ws, size_t attn_bytes) {
+static E2fBwdWs bwd_ws_layout(const e2f_ctx* ctx, int32_t N, void* ws, size_t attn_bytes, bool with_W) {
     E2fBwdWs Bw;
     size_t off = attn_bytes;
     auto take = [&](size_t bytes) {
@@ -471,19 +471,30 @@ static E2fBwdWs bwd_ws_layout(const e2f_ctx* ctx, int32_t N, void* ws, size_t at
     Bw.Gu = (float*)take((size_t)3 * E2F_MAX_N * E2F_MAX_N * 4);
     Bw.pWb = (float*)take((size_t)N * ctx->cfg.H * ctx->cfg.B * 4);
     Bw.pwp = (float*)take((size_t)N * 32 * 4);
+    Bw.tbuf = Bw.wpart = nullptr;
+    if (with_W) {
+        const size_t C = ctx->cfg.C, L1 = ctx->cfg.L_max + 1;
+        Bw.tbuf = (float*)take((size_t)5 * N * ctx->n * C * 4);
+        Bw.wpart = (float*)take((size_t)32 * 5 * L1 * C * C * 4);
+    }
     Bw.bytes = off;
     return Bw;
 }
 
 size_t e2f_attn_backward_workspace_bytes(const e2f_ctx* ctx, int32_t N) {
     if (!ctx || N < 0) return 0;
-    return bwd_ws_layout(ctx, N, nullptr, e2f_attn_ws_layout(ctx, N, nullptr, 0).bytes).bytes;
+    return bwd_ws_layout(ctx, N, nullptr, e2f_attn_ws_layout(ctx, N, nullptr, 0).bytes, false).bytes;
+}
+
+size_t e2f_attn_backward_weights_workspace_bytes(const e2f_ctx* ctx, int32_t N) {
+    if (!ctx || N < 0) return 0;
+    return bwd_ws_layout(ctx, N, nullptr, e2f_attn_ws_layout(ctx, N, nullptr, 0).bytes, true).bytes;
 }
 
 e2f_status e2f_attn_backward(e2f_ctx* ctx, const e2f_cells* cells, const float* pos, const void* h,
                              const int32_t* seg_offsets, int32_t N, int32_t S, const e2f_weights* w, const float* out,
                              const float* grad_out, float* grad_pos, float* grad_q, float* grad_k, float* grad_v,
-                             float* grad_h, float* grad_Wb, float* grad_w_path, void* ws, size_t ws_bytes,
+                             float* grad_h, float* grad_Wb, float* grad_w_path, float* grad_W, void* ws, size_t ws_bytes,
                              void* hip_stream) {
     if (!ctx) return E2F_ERR_INVALID_ARG;
     if (!e2f_backward_supported(ctx)) return E2F_ERR_UNSUPPORTED;
@@ -491,14 +502,15 @@ e2f_status e2f_attn_backward(e2f_ctx* ctx, const e2f_cells* cells, const float* 
     e2f_status rc = check_forward_args(ctx, cells, pos, h, seg_offsets, N, S, w, const_cast<float*>(out), ws, (size_t)-1);
     if (rc != E2F_OK || N == 0) return rc;
     if (!grad_out || !grad_pos || !grad_q || !grad_k || !grad_v) return E2F_ERR_INVALID_ARG;
-    if (ws_bytes < e2f_attn_backward_workspace_bytes(ctx, N)) return E2F_ERR_WORKSPACE_TOO_SMALL;
+    if (ws_bytes < (grad_W ? e2f_attn_backward_weights_workspace_bytes(ctx, N) : e2f_attn_backward_workspace_bytes(ctx, N)))
+        return E2F_ERR_WORKSPACE_TOO_SMALL;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     const E2fAttnWs L = e2f_attn_ws_layout(ctx, N, ws, 0);
-    const E2fBwdWs Bw = bwd_ws_layout(ctx, N, ws, L.bytes);
+    const E2fBwdWs Bw = bwd_ws_layout(ctx, N, ws, L.bytes, grad_W != nullptr);
     if ((rc = e2f_launch_prepare(ctx, cells->view, pos, w, L, st)) != E2F_OK) return rc;
     if ((rc = e2f_launch_project_mfma(ctx, cells->view, h, w, L, 0, st)) != E2F_OK) return rc;
     return e2f_launch_backward(ctx, cells->view, w, L, Bw, out, grad_out, grad_pos, grad_q, grad_k, grad_v, h, grad_h,
-                               grad_Wb, grad_w_path, st);
+                               grad_Wb, grad_w_path, grad_W, st);
 }
 
 e2f_status e2f_eaas_tensor_product(e2f_ctx* ctx, const void* h, const float* r, const float* w_path, float* out,

@@ -517,8 +517,8 @@ __global__ __launch_bounds__(256) void k_bwd_project(const T* __restrict__ h, co
                                                      const T* __restrict__ WQ2, const T* __restrict__ WK1,
                                                      const T* __restrict__ WK2, const T* __restrict__ WV,
                                                      const float* __restrict__ gq, const float* __restrict__ gk,
-                                                     const float* __restrict__ gv, float* __restrict__ gh, int L, int C,
-                                                     int N) {
+                                                     const float* __restrict__ gv, float* __restrict__ gh,
+                                                     float* __restrict__ tbuf, int L, int C, int N) {
     extern __shared__ float4 sm4[];   // x[C][PTA], then t[5][C][PTA]
     float* s_x = reinterpret_cast<float*>(sm4);
     float* s_t = s_x + C * PTA;
@@ -570,6 +570,18 @@ __global__ __launch_bounds__(256) void k_bwd_project(const T* __restrict__ h, co
                 s_t[(4 * C + c) * PTA + ta] = gv[((size_t)atom[ta] * n + comp) * C + c];
             }
             __syncthreads();
+            if (tbuf) {   // the five row factors of the weight gradients: dW_k[l] = sum over rows of t_k (x) x
+#pragma unroll
+                for (int k = 0; k < 5; ++k)
+#pragma unroll
+                    for (int ta = 0; ta < PTA; ++ta)
+                        if (a0 + ta < N)
+                            tbuf[((size_t)k * N + a0 + ta) * n * C + (size_t)comp * C + c] = s_t[(k * C + c) * PTA + ta];
+            }
+            if (!gh) {   // (uniform) only the row factors were asked for
+                __syncthreads();
+                continue;
+            }
             float dx[PTA];
 #pragma unroll
             for (int ta = 0; ta < PTA; ++ta) dx[ta] = 0.0f;
@@ -592,6 +604,50 @@ __global__ __launch_bounds__(256) void k_bwd_project(const T* __restrict__ h, co
             __syncthreads();
         }
     }
+}
+
+// ---- gradients of the five projection matrices: dW_k[l][co][ci] = sum over atoms a and orders m of
+// t_k[a][l, m][co] * h[a][l, m][ci], with the row factors t_k that k_bwd_project leaves in the workspace.  One
+// workgroup per (chunk of atoms, degree, tile of 16 output channels), one thread per input channel; the factors of
+// a row are the same for the whole workgroup and come through the scalar unit.  Partial sums per chunk are added
+// up afterwards in a fixed order.
+constexpr int WG_CHUNKS = 32;
+template <typename T>
+__global__ __launch_bounds__(256) void k_bwd_wgrad(const T* __restrict__ h, const float* __restrict__ tbuf, int L, int C,
+                                                   int N, float* __restrict__ part) {
+    const int chunk = blockIdx.x, l = blockIdx.y, co0 = blockIdx.z * 16, ci = threadIdx.x;
+    const int n = (L + 1) * (L + 1);
+    const int per = (N + WG_CHUNKS - 1) / WG_CHUNKS, a_lo = chunk * per, a_hi = min(N, a_lo + per);
+    float acc[5][16];
+#pragma unroll
+    for (int k = 0; k < 5; ++k)
+#pragma unroll
+        for (int j = 0; j < 16; ++j) acc[k][j] = 0.0f;
+    for (int a = a_lo; a < a_hi; ++a)
+        for (int m = 0; m < 2 * l + 1; ++m) {
+            const size_t row = ((size_t)a * n + l * l + m) * C;
+            const float x = e2f::load_as_float<T>(h + row + ci);
+#pragma unroll
+            for (int k = 0; k < 5; ++k) {
+                const float* __restrict__ tk = tbuf + (size_t)k * N * n * C + row + co0;   // uniform address
+#pragma unroll
+                for (int j = 0; j < 16; ++j) acc[k][j] += tk[j] * x;
+            }
+        }
+    // part[chunk][k][l][co][ci]
+#pragma unroll
+    for (int k = 0; k < 5; ++k)
+#pragma unroll
+        for (int j = 0; j < 16; ++j)
+            part[((((size_t)chunk * 5 + k) * (L + 1) + l) * C + co0 + j) * C + ci] = acc[k][j];
+}
+
+__global__ void k_sum_chunks(const float* __restrict__ part, size_t M, int chunks, float* __restrict__ out) {
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= M) return;
+    float s = 0.0f;
+    for (int c = 0; c < chunks; ++c) s += part[(size_t)c * M + i];
+    out[i] = s;
 }
 
 template <int L, typename VT>
@@ -622,7 +678,7 @@ bool e2f_backward_supported(const e2f_ctx* ctx) {
 e2f_status e2f_launch_backward(const e2f_ctx* ctx, const E2fCellsView& cv, const e2f_weights* w, const E2fAttnWs& ws,
                                const E2fBwdWs& bw, const float* out, const float* grad_out, float* grad_pos,
                                float* grad_q, float* grad_k, float* grad_v, const void* h, float* grad_h,
-                               float* grad_Wb, float* grad_w_path, hipStream_t st) {
+                               float* grad_Wb, float* grad_w_path, float* grad_W, hipStream_t st) {
     if (cv.N == 0) return E2F_OK;
     const bool wgrad = grad_Wb || grad_w_path;
     if (wgrad && ctx->cfg.B > WB_PER_THREAD * ctx->Ch) return E2F_ERR_UNSUPPORTED;
@@ -653,18 +709,26 @@ e2f_status e2f_launch_backward(const e2f_ctx* ctx, const E2fCellsView& cv, const
         if (grad_Wb) k_reduce_partials<<<HB, 256, 0, st>>>(bw.pWb, cv.N, HB, HB, grad_Wb);
         if (grad_w_path) k_reduce_partials<<<L1 * L1, 256, 0, st>>>(bw.pwp, cv.N, WP_BINS, L1 * L1, grad_w_path);
     }
-    if (grad_h) {
+    if (grad_h || grad_W) {
         const int C = P.C, L = ctx->cfg.L_max;
         const size_t shm = (size_t)6 * C * PTA * sizeof(float);
         const int groups = (cv.N + PTA - 1) / PTA;
-        if (ctx->cfg.feat_dtype == E2F_BF16)
+        float* tbuf = grad_W ? bw.tbuf : nullptr;
+        const dim3 wgrid(WG_CHUNKS, L + 1, C / 16);
+        const size_t M = (size_t)5 * (L + 1) * C * C;
+        if (ctx->cfg.feat_dtype == E2F_BF16) {
             k_bwd_project<uint16_t><<<groups, C, shm, st>>>((const uint16_t*)h, (const uint16_t*)w->WQ1, (const uint16_t*)w->WQ2,
                                                           (const uint16_t*)w->WK1, (const uint16_t*)w->WK2,
-                                                          (const uint16_t*)w->WV, grad_q, grad_k, grad_v, grad_h, L, C, cv.N);
-        else
+                                                          (const uint16_t*)w->WV, grad_q, grad_k, grad_v, grad_h, tbuf, L, C,
+                                                          cv.N);
+            if (grad_W) k_bwd_wgrad<uint16_t><<<wgrid, C, 0, st>>>((const uint16_t*)h, tbuf, L, C, cv.N, bw.wpart);
+        } else {
             k_bwd_project<float><<<groups, C, shm, st>>>((const float*)h, (const float*)w->WQ1, (const float*)w->WQ2,
                                                        (const float*)w->WK1, (const float*)w->WK2, (const float*)w->WV,
-                                                       grad_q, grad_k, grad_v, grad_h, L, C, cv.N);
+                                                       grad_q, grad_k, grad_v, grad_h, tbuf, L, C, cv.N);
+            if (grad_W) k_bwd_wgrad<float><<<wgrid, C, 0, st>>>((const float*)h, tbuf, L, C, cv.N, bw.wpart);
+        }
+        if (grad_W) k_sum_chunks<<<(unsigned)((M + 255) / 256), 256, 0, st>>>(bw.wpart, M, WG_CHUNKS, grad_W);
     }
     E2F_HIP_CHECK(hipGetLastError());
     return E2F_OK;

@@ -103,6 +103,9 @@ struct E2fBwdWs {
     float* Gu;       // [3][25][25]
     float* pWb;      // [N][H][B]
     float* pwp;      // [N][32]
+    // for the gradients of the projection matrices (only in the larger workspace of that form of the call)
+    float* tbuf;     // [5][N][n][C] row factors
+    float* wpart;    // [32 chunks][5][L+1][C][C] partial sums
     size_t bytes;
 };
 
@@ -161,7 +164,7 @@ bool e2f_backward_supported(const e2f_ctx* ctx);
 e2f_status e2f_launch_backward(const e2f_ctx* ctx, const E2fCellsView& cv, const e2f_weights* w, const E2fAttnWs& ws,
                                const E2fBwdWs& bw, const float* out, const float* grad_out, float* grad_pos,
                                float* grad_q, float* grad_k, float* grad_v, const void* h, float* grad_h,
-                               float* grad_Wb, float* grad_w_path, hipStream_t st);
+                               float* grad_Wb, float* grad_w_path, float* grad_W, hipStream_t st);
 // cw[comp][t] = P coefficient with every path weight one.
 e2f_status e2f_launch_unit_cw(const e2f_ctx* ctx, float* cw, hipStream_t st);
 e2f_status e2f_launch_tile(const e2f_ctx* ctx, const E2fCellsView& cv, const E2fAttnWs& ws, float* out, hipStream_t st);

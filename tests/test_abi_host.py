@@ -148,6 +148,9 @@ def test_backward_entry_point_sizes_and_limits(lib):
         per_atom = 16 + 2 * 5 * 128 * 4 + 25 * 128 * 2 + 2 * 8 * 4 + 8 * 8 * 4 + 32 * 4
         assert abs((s[1] - s[0]) - 10_000 * per_atom) <= 4096
         assert B.e2f_attn_backward_workspace_bytes(ctx, -1) == 0
+        sw = [B.e2f_attn_backward_weights_workspace_bytes(ctx, N) for N in (10_000, 20_000)]
+        assert abs((sw[1] - sw[0]) - 10_000 * (per_atom + 5 * 25 * 128 * 4)) <= 4096
+        assert sw[0] - s[0] >= 5 * 10_000 * 25 * 128 * 4 + 32 * 5 * 5 * 128 * 128 * 4
         cells = ctypes.c_void_p()
         null = ctypes.c_void_p(0)
         assert lib.e2f_build_cells(ctx, null, null, 0, 0, null, 0, ctypes.byref(cells), null) == 0
@@ -155,7 +158,7 @@ def test_backward_entry_point_sizes_and_limits(lib):
 
         def call(N, S, ptr):
             return lib.e2f_attn_backward(ctx, cells, ptr, ptr, ptr, N, S, ctypes.byref(w), ptr, ptr, ptr, ptr, ptr, ptr,
-                                         null, null, null, ptr, 0, null)
+                                         null, null, null, null, ptr, 0, null)
         assert call(0, 0, null) == 0
         assert call(5, 1, null) == 1
         lib.e2f_cells_destroy(cells)
@@ -168,7 +171,7 @@ def test_backward_entry_point_sizes_and_limits(lib):
         try:
             w = B.Weights(*([0] * 7))
             assert lib.e2f_attn_backward(ctx, None, None, None, None, 0, 0, ctypes.byref(w), None, None, None, None, None,
-                                         None, None, None, None, None, 0, None) == 2
+                                         None, None, None, None, None, None, 0, None) == 2
         finally:
             B.e2f_destroy(ctx)
 

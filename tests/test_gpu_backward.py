@@ -42,8 +42,9 @@ def run_backward(torch, wl, seed=0):
     ref_out, ref = G.attn_backward(ocfg, pos64, wl["h"], wl["weights"], nbr, go, translation=tr,
                                    wrt=("pos", "q", "k", "v"))
     _, ref_h = G.attn_backward(ocfg, pos64, wl["h"], wl["weights"], nbr, go, translation=tr,
-                               wrt=("h", "Wb", "w_path"))
+                               wrt=("h", "Wb", "w_path", "WQ1", "WQ2", "WK1", "WK2", "WV"))
     ref.update(ref_h)
+    ref["W"] = np.stack([ref[k] for k in ("WQ1", "WQ2", "WK1", "WK2", "WV")])
     P = B.Problem(wl)
     try:
         P.build_cells()
@@ -57,7 +58,7 @@ def run_backward(torch, wl, seed=0):
         for x, y in zip(plain, P.backward(g, with_weights=True)):
             assert torch.equal(x, y)
         errs = {}
-        for name, arr in zip(("pos", "q", "k", "v", "h", "Wb", "w_path"), got):
+        for name, arr in zip(("pos", "q", "k", "v", "h", "Wb", "w_path", "W"), got):
             assert np.isfinite(arr).all(), name
             assert np.abs(ref[name]).max() > 1e-6, name
             errs[name] = rel_l2(arr, ref[name])
