@@ -220,7 +220,7 @@ e2f_status e2f_attn_forward_factorized(e2f_ctx *ctx, const e2f_cells *cells, con
  *             either of the two needs B <= 8 * C/H (E2F_ERR_UNSUPPORTED otherwise) and makes the call slower
  *   grad_W    device float [5][L_max+1][C][C] or NULL: dL/d WQ1, WQ2, WK1, WK2, WV in this order (out channel, in
  *             channel), fully overwritten; needs the larger workspace e2f_attn_backward_weights_workspace_bytes(ctx, N)
- *             (five more [N][(L_max+1)^2][C] float arrays of row factors and 32 partial sums of the result)
+ *             (five more [N][(L_max+1)^2][C] float arrays of row factors and partial sums of the result)
  *   ws        device, at least e2f_attn_backward_workspace_bytes(ctx, N) bytes, 256-byte aligned
  * Cell lists from e2f_build_cells and e2f_build_cells_periodic are accepted.  E2F_ERR_UNSUPPORTED: lf != 1, or a
  * head width C/H that is not a power of two <= 64.  A neighbour cap has no backward form here (the capped

@@ -475,7 +475,7 @@ static E2fBwdWs bwd_ws_layout(const e2f_ctx* ctx, int32_t N, void* ws, size_t at
     if (with_W) {
         const size_t C = ctx->cfg.C, L1 = ctx->cfg.L_max + 1;
         Bw.tbuf = (float*)take((size_t)5 * N * ctx->n * C * 4);
-        Bw.wpart = (float*)take((size_t)32 * 5 * L1 * C * C * 4);
+        Bw.wpart = (float*)take((size_t)8 * L1 * L1 * 5 * C * C * 4);   // 8 (L_max+1)^2 slices of partial sums
     }
     Bw.bytes = off;
     return Bw;

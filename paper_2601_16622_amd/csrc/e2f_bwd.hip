@@ -201,11 +201,9 @@ __global__ __launch_bounds__(256) void k_bwd_stats(BwdParams P) {
 __host__ __device__ constexpr int degree_of(int x) { return x >= 16 ? 4 : x >= 9 ? 3 : x >= 4 ? 2 : x >= 1 ? 1 : 0; }
 
 // ---- what an atom owns as a target i: dq_i and -sum_j dL/dr_ij; with WGRAD also its partial sums of
-//   dL/dWb[h][b]       = sum_j ds_ij,h exp(-gamma (d_ij - mu_b)^2)
-//   dL/dw_path[li][lo] = sum_mu sum_{xo in lo, xi in li} <g_i[xo], Gu_mu[xo][xi] T_mu[xi]>,  T_mu = sum_j alpha_ij r_mu v_j
-// (the message is linear in the path weights: G_mu[xo][xi] = w_path[li(xi)][lo(xo)] Gu_mu[xo][xi]).
+//   dL/dWb[h][b] = sum_j ds_ij,h exp(-gamma (d_ij - mu_b)^2)
 template <int L, typename VT, bool WGRAD>
-__global__ __launch_bounds__(256) void k_bwd_target(BwdParams P) {
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void k_bwd_target(BwdParams P) {
     constexpr int n = (L + 1) * (L + 1);
     __shared__ int s_list[BCAP];
     __shared__ float4 s_pos[BCAP], s_rad[BCAP];
@@ -235,14 +233,10 @@ __global__ __launch_bounds__(256) void k_bwd_target(BwdParams P) {
     __syncthreads();
     float gt[3][n];   // G_mu^T g_i: u_mu = <g_i, G_mu v_j> = <gt_mu, v_j>
     axis_apply<L, true>(g, s_G, gt);
-    float accWb[WGRAD ? WB_PER_THREAD : 1], Tm[WGRAD ? 3 : 1][WGRAD ? n : 1];
+    float accWb[WGRAD ? WB_PER_THREAD : 1];
     if (WGRAD) {
 #pragma unroll
         for (int i = 0; i < WB_PER_THREAD; ++i) accWb[i] = 0.0f;
-#pragma unroll
-        for (int mu = 0; mu < 3; ++mu)
-#pragma unroll
-            for (int x = 0; x < n; ++x) Tm[mu][x] = 0.0f;
     }
     while (true) {
         const int cnt = next_batch(P, w, t, pi, s_list, s_pos, s_rad, s_bias, s_ctl);
@@ -268,12 +262,6 @@ __global__ __launch_bounds__(256) void k_bwd_target(BwdParams P) {
                 u[0] += gt[0][x] * vx;
                 u[1] += gt[1][x] * vx;
                 u[2] += gt[2][x] * vx;
-                if (WGRAD) {
-                    const float av = p * phi * vx;
-                    Tm[0][x] += av * rx;
-                    Tm[1][x] += av * ry;
-                    Tm[2][x] += av * rz;
-                }
             }
             u[0] = head_sum(u[0], P.Ch);
             u[1] = head_sum(u[1], P.Ch);
@@ -322,35 +310,6 @@ __global__ __launch_bounds__(256) void k_bwd_target(BwdParams P) {
                 if (b < P.B) P.pWb[((size_t)a * P.H + head) * P.B + b] = accWb[i];
             }
         }
-        // path weights: bins per thread, then summed over the channels in a fixed order
-        __syncthreads();
-        for (int i = threadIdx.x; i < 3 * E2F_MAX_N * E2F_MAX_N; i += blockDim.x) s_G[i] = P.Gu[i];
-        __syncthreads();
-        float bins[(L + 1) * (L + 1)];
-#pragma unroll
-        for (int i = 0; i < (L + 1) * (L + 1); ++i) bins[i] = 0.0f;
-#pragma unroll
-        for (int mu = 0; mu < 3; ++mu)
-#pragma unroll
-            for (int xo = 0; xo < n; ++xo)
-#pragma unroll
-                for (int xi = 0; xi < n; ++xi)
-                    if ((E2F_AXIS_NZ[mu][xo] >> xi) & 1u)
-                        bins[degree_of(xi) * (L + 1) + degree_of(xo)] +=
-                            g[xo] * s_G[(mu * E2F_MAX_N + xo) * E2F_MAX_N + xi] * Tm[mu][xi];
-        float* s_red = reinterpret_cast<float*>(s_bias);   // [(L+1)^2][C]: the list batches are done
-        __syncthreads();
-        if (live) {
-#pragma unroll
-            for (int i = 0; i < (L + 1) * (L + 1); ++i) s_red[i * C + c] = bins[i];
-        }
-        __syncthreads();
-        if ((int)threadIdx.x < WP_BINS) {
-            float s = 0.0f;
-            if ((int)threadIdx.x < (L + 1) * (L + 1))
-                for (int cc = 0; cc < C; ++cc) s += s_red[threadIdx.x * C + cc];
-            P.pwp[(size_t)a * WP_BINS + threadIdx.x] = s;
-        }
     }
 }
 
@@ -370,9 +329,13 @@ __global__ __launch_bounds__(256) void k_reduce_partials(const float* __restrict
     if (threadIdx.x == 0 && m < M) out[m] = s_acc[0];
 }
 
-// ---- what an atom owns as a source j: dk_j, dv_j and +sum_i dL/dr_ij (added to the target kernel's share)
-template <int L, typename VT>
-__global__ __launch_bounds__(256) void k_bwd_source(BwdParams P) {
+// ---- what an atom owns as a source j: dk_j, dv_j and +sum_i dL/dr_ij (added to the target kernel's share); with
+// WGRAD also its partial sums of the path-weight gradient.  The message is linear in the path weights,
+// G_mu[xo][xi] = w_path[li(xi)][lo(xo)] Gu_mu[xo][xi] with the unit-weight operators Gu, so with the sums
+// Y_mu = sum_i alpha_ij r_mu g_i that this kernel forms anyway
+//   dL/dw_path[li][lo] = sum_j sum_mu sum_{xo in lo, xi in li} Y_mu[xo] Gu_mu[xo][xi] v_j[xi].
+template <int L, typename VT, bool WGRAD>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k_bwd_source(BwdParams P) {
     constexpr int n = (L + 1) * (L + 1);
     __shared__ int s_list[BCAP];
     __shared__ float4 s_pos[BCAP], s_rad[BCAP];
@@ -483,6 +446,38 @@ __global__ __launch_bounds__(256) void k_bwd_source(BwdParams P) {
         float s = 0.0f;
         for (int hh = 0; hh < P.H; ++hh) s += s_gp[hh][c];
         P.gpos[(size_t)a * 3 + c] += s;   // the target kernel wrote this atom's other share before
+    }
+    if (WGRAD) {
+        // bins per thread, then summed over the channels in a fixed order
+        __syncthreads();
+        for (int i = threadIdx.x; i < 3 * E2F_MAX_N * E2F_MAX_N; i += blockDim.x) s_G[i] = P.Gu[i];
+        __syncthreads();
+        float bins[(L + 1) * (L + 1)], vr[n];   // (the value row is read again: keeping it through the loop costs registers)
+#pragma unroll
+        for (int i = 0; i < (L + 1) * (L + 1); ++i) bins[i] = 0.0f;
+#pragma unroll
+        for (int x = 0; x < n; ++x) vr[x] = e2f::load_as_float<VT>((const VT*)P.v + ((size_t)t * n + x) * C + c);
+#pragma unroll
+        for (int mu = 0; mu < 3; ++mu)
+#pragma unroll
+            for (int xo = 0; xo < n; ++xo)
+#pragma unroll
+                for (int xi = 0; xi < n; ++xi)
+                    if ((E2F_AXIS_NZ[mu][xo] >> xi) & 1u)
+                        bins[degree_of(xi) * (L + 1) + degree_of(xo)] +=
+                            Y[mu][xo] * s_G[(mu * E2F_MAX_N + xo) * E2F_MAX_N + xi] * vr[xi];
+        float* s_red = reinterpret_cast<float*>(s_bias);   // [(L+1)^2][C]: the list batches are done
+        if (live) {
+#pragma unroll
+            for (int i = 0; i < (L + 1) * (L + 1); ++i) s_red[i * C + c] = bins[i];
+        }
+        __syncthreads();
+        if ((int)threadIdx.x < WP_BINS) {
+            float s = 0.0f;
+            if ((int)threadIdx.x < (L + 1) * (L + 1))
+                for (int cc = 0; cc < C; ++cc) s += s_red[threadIdx.x * C + cc];
+            P.pwp[(size_t)a * WP_BINS + threadIdx.x] = s;
+        }
     }
 }
 
@@ -609,44 +604,76 @@ __global__ __launch_bounds__(256) void k_bwd_project(const T* __restrict__ h, co
 // ---- gradients of the five projection matrices: dW_k[l][co][ci] = sum over atoms a and orders m of
 // t_k[a][l, m][co] * h[a][l, m][ci], with the row factors t_k that k_bwd_project leaves in the workspace.  One
 // workgroup per (chunk of atoms, degree, tile of 16 output channels), one thread per input channel; the factors of
-// a row are the same for the whole workgroup and come through the scalar unit.  Partial sums per chunk are added
-// up afterwards in a fixed order.
-constexpr int WG_CHUNKS = 32;
+// 16 rows at a time are staged in LDS and read from there by all threads at once.  Partial sums per chunk are
+// added up afterwards in a fixed order.
+constexpr int WG_SPLIT = 8;   // degree l is cut into WG_SPLIT * (2l+1) chunks of atoms: every workgroup gets N / WG_SPLIT rows
+constexpr int WG_ROWS = 16;   // rows staged in LDS per step
 template <typename T>
 __global__ __launch_bounds__(256) void k_bwd_wgrad(const T* __restrict__ h, const float* __restrict__ tbuf, int L, int C,
                                                    int N, float* __restrict__ part) {
-    const int chunk = blockIdx.x, l = blockIdx.y, co0 = blockIdx.z * 16, ci = threadIdx.x;
-    const int n = (L + 1) * (L + 1);
-    const int per = (N + WG_CHUNKS - 1) / WG_CHUNKS, a_lo = chunk * per, a_hi = min(N, a_lo + per);
+    __shared__ __attribute__((aligned(16))) float s_t[WG_ROWS][5][16];
+    // slice s of the partial sums: degree l = floor(sqrt(s / WG_SPLIT)), chunk s - WG_SPLIT * l^2 of WG_SPLIT * (2l+1)
+    const int slice = blockIdx.x, co0 = blockIdx.y * 16, ci = threadIdx.x;
+    int l = 0;
+    while (WG_SPLIT * (l + 1) * (l + 1) <= slice) ++l;
+    const int n = (L + 1) * (L + 1), nl = 2 * l + 1;
+    const int chunk = slice - WG_SPLIT * l * l, chunks = WG_SPLIT * nl;
+    const int per = (N + chunks - 1) / chunks, a_lo = chunk * per, a_hi = min(N, a_lo + per);
+    const int rows = max(a_hi - a_lo, 0) * nl;   // row r of the chunk: atom a_lo + r / nl, order r % nl
+    const size_t kstride = (size_t)N * n * C;
     float acc[5][16];
 #pragma unroll
     for (int k = 0; k < 5; ++k)
 #pragma unroll
         for (int j = 0; j < 16; ++j) acc[k][j] = 0.0f;
-    for (int a = a_lo; a < a_hi; ++a)
-        for (int m = 0; m < 2 * l + 1; ++m) {
-            const size_t row = ((size_t)a * n + l * l + m) * C;
-            const float x = e2f::load_as_float<T>(h + row + ci);
+    for (int r0 = 0; r0 < rows; r0 += WG_ROWS) {
+        const int nr = min(WG_ROWS, rows - r0);
+        __syncthreads();   // the previous rows have been consumed
+        for (int e = threadIdx.x; e < nr * 80; e += blockDim.x) {
+            const int rr = e / 80, k = (e % 80) / 16, jj = e % 16;
+            const int r = r0 + rr;
+            const size_t row = ((size_t)(a_lo + r / nl) * n + l * l + r % nl) * C;
+            s_t[rr][k][jj] = tbuf[k * kstride + row + co0 + jj];
+        }
+        float x[WG_ROWS];
 #pragma unroll
-            for (int k = 0; k < 5; ++k) {
-                const float* __restrict__ tk = tbuf + (size_t)k * N * n * C + row + co0;   // uniform address
+        for (int rr = 0; rr < WG_ROWS; ++rr) {
+            const int r = r0 + min(rr, nr - 1);
+            x[rr] = e2f::load_as_float<T>(h + ((size_t)(a_lo + r / nl) * n + l * l + r % nl) * C + ci);
+        }
+        __syncthreads();
 #pragma unroll
-                for (int j = 0; j < 16; ++j) acc[k][j] += tk[j] * x;
+        for (int rr = 0; rr < WG_ROWS; ++rr) {
+            if (rr < nr) {
+#pragma unroll
+                for (int k = 0; k < 5; ++k)
+#pragma unroll
+                    for (int j4 = 0; j4 < 4; ++j4) {
+                        const float4 tv = *reinterpret_cast<const float4*>(&s_t[rr][k][4 * j4]);
+                        acc[k][4 * j4] += tv.x * x[rr];
+                        acc[k][4 * j4 + 1] += tv.y * x[rr];
+                        acc[k][4 * j4 + 2] += tv.z * x[rr];
+                        acc[k][4 * j4 + 3] += tv.w * x[rr];
+                    }
             }
         }
-    // part[chunk][k][l][co][ci]
+    }
+    // part[slice][k][co][ci]
 #pragma unroll
     for (int k = 0; k < 5; ++k)
 #pragma unroll
-        for (int j = 0; j < 16; ++j)
-            part[((((size_t)chunk * 5 + k) * (L + 1) + l) * C + co0 + j) * C + ci] = acc[k][j];
+        for (int j = 0; j < 16; ++j) part[(((size_t)slice * 5 + k) * C + co0 + j) * C + ci] = acc[k][j];
 }
 
-__global__ void k_sum_chunks(const float* __restrict__ part, size_t M, int chunks, float* __restrict__ out) {
+// out[k][l][co][ci] = sum over the slices of degree l, in a fixed order.
+__global__ void k_sum_chunks(const float* __restrict__ part, int L, int C, float* __restrict__ out) {
+    const size_t CC = (size_t)C * C, M = (size_t)5 * (L + 1) * CC;
     const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= M) return;
+    const int k = (int)(i / ((L + 1) * CC)), l = (int)((i / CC) % (L + 1));
+    const size_t e = i % CC;
     float s = 0.0f;
-    for (int c = 0; c < chunks; ++c) s += part[(size_t)c * M + i];
+    for (int c = 0; c < WG_SPLIT * (2 * l + 1); ++c) s += part[((size_t)(WG_SPLIT * l * l + c) * 5 + k) * CC + e];
     out[i] = s;
 }
 
@@ -657,9 +684,13 @@ void launch_LV(const BwdParams& P, hipStream_t st) {
     // with weight gradients the same bytes later hold the [(L+1)^2][C] channel sums of the path-weight bins
     const size_t shm_w = shm > (size_t)(L + 1) * (L + 1) * P.C * 4 ? shm : (size_t)(L + 1) * (L + 1) * P.C * 4;
     k_bwd_stats<L><<<e2f::xcd_grid(N), C, shm, st>>>(P);
-    if (P.pWb) k_bwd_target<L, VT, true><<<e2f::xcd_grid(N), C, shm_w, st>>>(P);
-    else k_bwd_target<L, VT, false><<<e2f::xcd_grid(N), C, shm, st>>>(P);
-    k_bwd_source<L, VT><<<e2f::xcd_grid(N), C, shm, st>>>(P);
+    if (P.pWb) {
+        k_bwd_target<L, VT, true><<<e2f::xcd_grid(N), C, shm, st>>>(P);
+        k_bwd_source<L, VT, true><<<e2f::xcd_grid(N), C, shm_w, st>>>(P);
+    } else {
+        k_bwd_target<L, VT, false><<<e2f::xcd_grid(N), C, shm, st>>>(P);
+        k_bwd_source<L, VT, false><<<e2f::xcd_grid(N), C, shm, st>>>(P);
+    }
 }
 
 template <int L>
@@ -714,7 +745,7 @@ e2f_status e2f_launch_backward(const e2f_ctx* ctx, const E2fCellsView& cv, const
         const size_t shm = (size_t)6 * C * PTA * sizeof(float);
         const int groups = (cv.N + PTA - 1) / PTA;
         float* tbuf = grad_W ? bw.tbuf : nullptr;
-        const dim3 wgrid(WG_CHUNKS, L + 1, C / 16);
+        const dim3 wgrid(WG_SPLIT * (L + 1) * (L + 1), C / 16);
         const size_t M = (size_t)5 * (L + 1) * C * C;
         if (ctx->cfg.feat_dtype == E2F_BF16) {
             k_bwd_project<uint16_t><<<groups, C, shm, st>>>((const uint16_t*)h, (const uint16_t*)w->WQ1, (const uint16_t*)w->WQ2,
@@ -728,7 +759,7 @@ e2f_status e2f_launch_backward(const e2f_ctx* ctx, const E2fCellsView& cv, const
                                                        grad_q, grad_k, grad_v, grad_h, tbuf, L, C, cv.N);
             if (grad_W) k_bwd_wgrad<float><<<wgrid, C, 0, st>>>((const float*)h, tbuf, L, C, cv.N, bw.wpart);
         }
-        if (grad_W) k_sum_chunks<<<(unsigned)((M + 255) / 256), 256, 0, st>>>(bw.wpart, M, WG_CHUNKS, grad_W);
+        if (grad_W) k_sum_chunks<<<(unsigned)((M + 255) / 256), 256, 0, st>>>(bw.wpart, L, C, grad_W);
     }
     E2F_HIP_CHECK(hipGetLastError());
     return E2F_OK;

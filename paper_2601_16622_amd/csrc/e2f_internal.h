@@ -105,7 +105,7 @@ struct E2fBwdWs {
     float* pwp;      // [N][32]
     // for the gradients of the projection matrices (only in the larger workspace of that form of the call)
     float* tbuf;     // [5][N][n][C] row factors
-    float* wpart;    // [32 chunks][5][L+1][C][C] partial sums
+    float* wpart;    // [8 (L+1)^2 slices][5][C][C] partial sums
     size_t bytes;
 };
 
