@@ -12,8 +12,8 @@
 // D^T P D for the three axis frames, path weights included) are applied once per target in the epilogue, using
 // only their non-zero entries.  Nothing per pair is written to global memory.
 //
-// One wave owns (tile, head, half of the component pairs); the two halves of a head form a workgroup and add
-// their partial outputs through LDS.  Register layout notes (v_mfma_f32_16x16x32_bf16, lane = 16 g + i):
+// A workgroup of four waves owns (tile, head); each wave scores a quarter of the candidate chunks and accumulates a
+// quarter of the components (see k_tile below).  Register layout notes (v_mfma_f32_16x16x32_bf16, lane = 16 g + i):
 //   A operand: lane holds A[i][8g..8g+7]; B operand: lane holds B[8g..8g+7][i]; result: lane holds C[4g..4g+3][i].
 // The logits come out as S^T[candidate row 4g+r][target i] for two 16-candidate halves; read as the A operand of the
 // aggregation the same registers are W[target i][k = 8g + r'] with k -> (first half, row 4g+r') for r' < 4 and
@@ -120,7 +120,8 @@ __global__ void k_axis_ops(const float* __restrict__ cw, float* __restrict__ G) 
 
 // One workgroup of NW waves per (tile of 16 targets, head).  The waves share the candidate list and the softmax
 // weights through LDS and split the rest:
-//   list      each wave scans a quarter of the stencil's slot groups; the kept groups are packed in order
+//   list      each wave scans a quarter of the stencil's slot groups and keeps those with a slot within reach of a
+//             target; the kept groups are packed in order
 //   weights   chunks of 32 candidates are taken four at a time; wave w computes the logits (matrix cores), the pair
 //             geometry and the weights W_mu of chunk 4G + w and publishes them (3 KB per chunk)
 //   aggregate every wave applies all four chunks' W_mu to its own quarter of the components, T_mu += W_mu V
