@@ -61,7 +61,7 @@ def lib():
         L.e2fo_free.restype = None
         L.e2fo_attn_forward.argtypes = [ctypes.POINTER(_Config), dp, dp, ctypes.c_int, dp, dp, dp, dp, dp, dp, dp,
                                         lp, ip, dp, ip, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_double,
-                                        dp]
+                                        ctypes.c_int, dp]
         L.e2fo_attn_forward.restype = ctypes.c_int
         L.e2fo_num_threads.argtypes = []
         L.e2fo_num_threads.restype = ctypes.c_int
@@ -237,11 +237,15 @@ def edge_translations(seg_offsets, box, offsets, shift):
 
 
 def attn_forward(cfg, pos, h, seg_offsets, weights, targets=None, message_mode="dense", softmax_mode="twopass",
-                 use_cells=False, chi=0.0, nbr=None, box=None):
+                 use_cells=False, chi=0.0, nbr=None, box=None, score_mode="kernel_score"):
     """The operator.  cfg: dict(L, C, H, B, lf, cutoff); weights: dict(WQ1, WQ2, WK1, WK2, WV [L+1][C][C],
     Wb [H][B], w_path [L+1][L+1]); returns float64 [n_targets][(L+1)^2][C].
     box: None, or float [S][3] periodic edge lengths (see neighbor_list_periodic); nbr is then the triple that
-    function returns, and the pair vectors are r_ij = (w_j + shift*box) - w_i on the folded coordinates w."""
+    function returns, and the pair vectors are r_ij = (w_j + shift*box) - w_i on the folded coordinates w.
+    score_mode: "kernel_score" (Eq. kernel_score) or "nonlinear" (the logit with the non-linear pair feature of
+    Eqs. app-nonlin-fea / app-nonlin-alpha, in the reading stated at e2fo_attn_forward)."""
+    if score_mode not in ("kernel_score", "nonlinear"):
+        raise ValueError("unknown score_mode")
     c = _Config(cfg["L"], cfg["C"], cfg["H"], cfg["B"], cfg["lf"], float(np.float32(cfg["cutoff"])))
     edge_shift = None
     if box is not None:
@@ -277,7 +281,8 @@ def attn_forward(cfg, pos, h, seg_offsets, weights, targets=None, message_mode="
                                  idx.ctypes.data_as(ip),
                                  _d(edge_shift) if edge_shift is not None else ctypes.POINTER(ctypes.c_double)(),
                                  tptr, nt, 0 if message_mode == "dense" else 1,
-                                 0 if softmax_mode == "twopass" else 1, float(chi), _d(out))
+                                 0 if softmax_mode == "twopass" else 1, float(chi),
+                                 1 if score_mode == "nonlinear" else 0, _d(out))
     if rc != 0:
         raise ValueError("oracle rejected the configuration")
     return out

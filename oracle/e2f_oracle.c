@@ -500,13 +500,20 @@ static void project(const e2fo_config *cfg, const double *W, const double *h_ato
  *     for pair vectors r_ij as given);
  *   message_mode 0 = dense CG contraction, 1 = EAAS (gauge angle chi);
  *   softmax_mode 0 = two-pass softmax, 1 = streaming recurrences of Algorithm 1;
+ *   score_mode 0 = the logit of Eq. kernel_score, s = tau q.k + b;
+ *     1 = the logit with the non-linear pair feature of App. "Role of Non-linearity" (Eqs. app-nonlin-fea,
+ *     app-nonlin-alpha), in this reading of it:  with Y^(l) the real harmonics of the unit pair vector, Q = W_Q1 h_i and
+ *     V = W_V h_j, the product "within each angular order" is the invariant  a[l][c] = sum_m Q[l,m,c] Y^(l)_m  and
+ *     b[l][c] = sum_m V[l,m,c] Y^(l)_m  (any pointwise sigma of an invariant keeps the operator equivariant),
+ *     Fea = sigma(a || b) with sigma(x) = x / (1 + e^-x), and the triple product contracts q_i, k_j and both halves of
+ *     Fea over (l, channel of the head):  s = tau sum_{l,c} q[l][c] k[l][c] (sigma(a[l][c]) + sigma(b[l][c])) + b_h(d);
  *   out double[n_targets][n][C].
  */
 int e2fo_attn_forward(const e2fo_config *cfg, const double *pos, const double *h, int N, const double *WQ1,
                       const double *WQ2, const double *WK1, const double *WK2, const double *WV, const double *Wb,
                       const double *w_path, const int64_t *nbr_offsets, const int32_t *nbr_idx,
                       const double *edge_shift, const int32_t *targets, int n_targets, int message_mode,
-                      int softmax_mode, double chi, double *out) {
+                      int softmax_mode, double chi, int score_mode, double *out) {
     int L = cfg->L, C = cfg->C, H = cfg->H, B = cfg->B, lf = cfg->lf;
     if (L < 0 || L > E2FO_MAX_L || lf < 0 || lf > E2FO_MAX_L || C <= 0 || H <= 0 || C % H != 0 || B <= 0) return 1;
     int n = (L + 1) * (L + 1);
@@ -526,6 +533,7 @@ int e2fo_attn_forward(const e2fo_config *cfg, const double *pos, const double *h
     double *q = (double *)calloc((size_t)N * (L + 1) * C, sizeof(double));
     double *k = (double *)calloc((size_t)N * (L + 1) * C, sizeof(double));
     double *v = (double *)calloc((size_t)N * n * C, sizeof(double));
+    double *q1 = score_mode == 1 ? (double *)calloc((size_t)N * n * C, sizeof(double)) : NULL;   /* W_Q1 h of the targets */
 #pragma omp parallel
     {
         double *p1 = (double *)malloc(sizeof(double) * n * C);
@@ -536,6 +544,7 @@ int e2fo_attn_forward(const e2fo_config *cfg, const double *pos, const double *h
             if (need_q[a]) {
                 project(cfg, WQ1, ha, p1);
                 project(cfg, WQ2, ha, p2);
+                if (q1) memcpy(q1 + (size_t)a * n * C, p1, sizeof(double) * n * C);
                 for (int l = 0; l <= L; ++l)
                     for (int c = 0; c < C; ++c) {
                         double acc = 0.0;
@@ -563,6 +572,7 @@ int e2fo_attn_forward(const e2fo_config *cfg, const double *pos, const double *h
     {
         double *g = (double *)malloc(sizeof(double) * B);
         double *msg = (double *)malloc(sizeof(double) * n * C);
+        double *Y = (double *)malloc(sizeof(double) * n);
 #pragma omp for schedule(dynamic, 4)
         for (int t = 0; t < nt; ++t) {
             int i = targets ? targets[t] : t;
@@ -583,11 +593,25 @@ int e2fo_attn_forward(const e2fo_config *cfg, const double *pos, const double *h
                 for (int x = 0; x < 3; ++x) rij[3 * e + x] = r[x];
                 gate[e] = radial_gate(d, cfg->cutoff);
                 radial_basis(d, cfg->cutoff, B, g);
+                if (score_mode == 1) {
+                    double rhat[3] = {r[0] / d, r[1] / d, r[2] / d};
+                    for (int l = 0; l <= L; ++l) e2fo_solid_harmonics(l, rhat, Y + l * l);
+                }
                 for (int hh = 0; hh < H; ++hh) {
                     double dot = 0.0;
                     for (int l = 0; l <= L; ++l)
-                        for (int c = hh * Ch; c < (hh + 1) * Ch; ++c)
-                            dot += q[((size_t)i * (L + 1) + l) * C + c] * k[((size_t)j * (L + 1) + l) * C + c];
+                        for (int c = hh * Ch; c < (hh + 1) * Ch; ++c) {
+                            double fea = 1.0;
+                            if (score_mode == 1) {
+                                double a = 0.0, b = 0.0;
+                                for (int m = 0; m < 2 * l + 1; ++m) {
+                                    a += q1[((size_t)i * n + l * l + m) * C + c] * Y[l * l + m];
+                                    b += v[((size_t)j * n + l * l + m) * C + c] * Y[l * l + m];
+                                }
+                                fea = a / (1.0 + exp(-a)) + b / (1.0 + exp(-b));
+                            }
+                            dot += q[((size_t)i * (L + 1) + l) * C + c] * k[((size_t)j * (L + 1) + l) * C + c] * fea;
+                        }
                     double bias = 0.0;
                     for (int b = 0; b < B; ++b) bias += Wb[hh * B + b] * g[b];
                     s[e * H + hh] = tau * dot + bias;
@@ -650,7 +674,9 @@ int e2fo_attn_forward(const e2fo_config *cfg, const double *pos, const double *h
         }
         free(g);
         free(msg);
+        free(Y);
     }
+    free(q1);
     tables_free(&tab);
     free(need_q);
     free(need_kv);
