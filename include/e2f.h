@@ -188,6 +188,23 @@ e2f_status e2f_attn_forward_table(e2f_ctx *ctx, const e2f_cells *cells, const fl
                                   void *hip_stream);
 
 /*
+ * The fused call with the non-linear pair feature in the logit (App. "Role of Non-linearity", Eqs. app-nonlin-fea and
+ * app-nonlin-alpha; the tp_type QKdotS_alpha of the hyper-parameter table).  The paper gives the feature only in
+ * outline; this library computes, with Y^(l) the real harmonics of the unit pair vector (Racah normalisation),
+ * Q = W_Q1 h_i and V = W_V h_j,
+ *     a[l][c] = sum_m Q[l,m,c] Y^(l)_m,  b[l][c] = sum_m V[l,m,c] Y^(l)_m,  sigma(x) = x / (1 + e^-x),
+ *     s_ij,h  = (1/sqrt(d_k)) sum_{l, c in head h} q_i[l][c] k_j[l][c] (sigma(a[l][c]) + sigma(b[l][c])) + b_h(d_ij),
+ * and softmax, gate and message exactly as e2f_attn_forward.  Same arguments; open and periodic cells; lf = 0, 1, 2.
+ * Workspace: e2f_attn_nonlinear_workspace_bytes (the plain-layout attention workspace plus one [N][(L_max+1)^2][C]
+ * array of the feature type), O(N).  Requires C <= 128.  Allocates nothing, does not synchronise.
+ * Errors: as e2f_attn_forward; E2F_ERR_UNSUPPORTED for C > 128.
+ */
+size_t e2f_attn_nonlinear_workspace_bytes(const e2f_ctx *ctx, int32_t N);
+e2f_status e2f_attn_forward_nonlinear(e2f_ctx *ctx, const e2f_cells *cells, const float *pos, const void *h,
+                                      const int32_t *seg_offsets, int32_t N, int32_t S, const e2f_weights *w,
+                                      float *out, void *ws, size_t ws_bytes, void *hip_stream);
+
+/*
  * The paper's factorized node-centric pipeline for lf = 1 (Eq. e2former_final with l = 1; Sec. 3.2, three-stage data
  * flow; Sec. 3.4 Algorithm 1): source terms h'_j = v_j (x) R(r_j - o) by node-level EAAS, Algorithm 1 streaming over
  * the precomputed rows [h'_j ; v_j] with scalar weights alpha_ij only, target coupling A1_i - A0_i (x) R(r_i - o).

@@ -22,7 +22,8 @@ EXPORTS = ["e2f_status_string", "e2f_create", "e2f_destroy", "e2f_cells_workspac
            "e2f_attn_capped_workspace_bytes", "e2f_attn_forward_capped", "e2f_build_neighbor_table",
            "e2f_attn_table_workspace_bytes", "e2f_attn_forward_table", "e2f_build_cells_periodic",
            "e2f_attn_backward_workspace_bytes", "e2f_attn_backward",
-           "e2f_attn_backward_weights_workspace_bytes"]
+           "e2f_attn_backward_weights_workspace_bytes", "e2f_attn_nonlinear_workspace_bytes",
+           "e2f_attn_forward_nonlinear"]
 STAGES = ("prepare", "project", "attention")
 
 
@@ -82,6 +83,10 @@ def load():
     L.e2f_attn_factorized_workspace_bytes.restype = sz
     L.e2f_attn_forward_factorized.argtypes = [vp, vp, vp, vp, vp, i32, i32, ctypes.POINTER(Weights), vp, vp, sz, vp]
     L.e2f_attn_forward_factorized.restype = ctypes.c_int
+    L.e2f_attn_nonlinear_workspace_bytes.argtypes = [vp, i32]
+    L.e2f_attn_nonlinear_workspace_bytes.restype = sz
+    L.e2f_attn_forward_nonlinear.argtypes = [vp, vp, vp, vp, vp, i32, i32, ctypes.POINTER(Weights), vp, vp, sz, vp]
+    L.e2f_attn_forward_nonlinear.restype = ctypes.c_int
     L.e2f_attn_capped_workspace_bytes.argtypes = [vp, i32]
     L.e2f_attn_capped_workspace_bytes.restype = sz
     L.e2f_attn_forward_capped.argtypes = [vp, vp, vp, vp, vp, i32, i32, ctypes.POINTER(Weights), i32, vp, vp, sz, vp]
@@ -223,6 +228,17 @@ def e2f_attn_forward_table(ctx, cells, pos, h, seg_offsets, weights, table, K, o
            "e2f_attn_forward_table")
 
 
+def e2f_attn_nonlinear_workspace_bytes(ctx, N):
+    return load().e2f_attn_nonlinear_workspace_bytes(ctx, N)
+
+
+def e2f_attn_forward_nonlinear(ctx, cells, pos, h, seg_offsets, weights, out, ws):
+    N, S = pos.shape[0], seg_offsets.shape[0] - 1
+    wt = _weights(weights)
+    _check(load().e2f_attn_forward_nonlinear(ctx, cells, _ptr(pos), _ptr(h), _ptr(seg_offsets), N, S, ctypes.byref(wt),
+                                             _ptr(out), _ptr(ws), ws.numel(), _stream()), "e2f_attn_forward_nonlinear")
+
+
 def e2f_attn_factorized_workspace_bytes(ctx, N):
     return load().e2f_attn_factorized_workspace_bytes(ctx, N)
 
@@ -353,6 +369,12 @@ class Problem:
         out = self.out if out is None else out
         ws = self._scratch("table_ws", e2f_attn_table_workspace_bytes(self.ctx, self.N))
         e2f_attn_forward_table(self.ctx, self.cells, self.pos, self.h, self.seg, self.weights, table, table.shape[1], out, ws)
+        return out
+
+    def forward_nonlinear(self, out=None):
+        out = self.out if out is None else out
+        ws = self._scratch("nonlinear_ws", e2f_attn_nonlinear_workspace_bytes(self.ctx, self.N))
+        e2f_attn_forward_nonlinear(self.ctx, self.cells, self.pos, self.h, self.seg, self.weights, out, ws)
         return out
 
     def forward_factorized(self, out=None):

@@ -456,6 +456,39 @@ e2f_status e2f_attn_forward_factorized(e2f_ctx* ctx, const e2f_cells* cells, con
     return e2f_launch_factorized(ctx, cells->view, L, F, out, st);
 }
 
+// q1 = W_Q1 h in v's plain layout, after the attention workspace
+static size_t nonlinear_q1_bytes(const e2f_ctx* ctx, int32_t N) {
+    return e2f_align_up((size_t)N * ctx->n * ctx->cfg.C * (ctx->cfg.feat_dtype == E2F_BF16 ? 2 : 4));
+}
+
+size_t e2f_attn_nonlinear_workspace_bytes(const e2f_ctx* ctx, int32_t N) {
+    if (!ctx || N < 0) return 0;
+    return e2f_attn_ws_layout(ctx, N, nullptr, 0).bytes + nonlinear_q1_bytes(ctx, N);
+}
+
+e2f_status e2f_attn_forward_nonlinear(e2f_ctx* ctx, const e2f_cells* cells, const float* pos, const void* h,
+                                      const int32_t* seg_offsets, int32_t N, int32_t S, const e2f_weights* w,
+                                      float* out, void* ws, size_t ws_bytes, void* hip_stream) {
+    if (!ctx) return E2F_ERR_INVALID_ARG;
+    if (!e2f_nonlinear_supported(ctx)) return E2F_ERR_UNSUPPORTED;
+    e2f_status rc = check_forward_args(ctx, cells, pos, h, seg_offsets, N, S, w, out, ws, (size_t)-1);
+    if (rc != E2F_OK || N == 0) return rc;
+    if (ws_bytes < e2f_attn_nonlinear_workspace_bytes(ctx, N)) return E2F_ERR_WORKSPACE_TOO_SMALL;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    const E2fAttnWs L = e2f_attn_ws_layout(ctx, N, ws, 0);
+    void* q1 = static_cast<char*>(ws) + L.bytes;
+    if ((rc = e2f_launch_prepare(ctx, cells->view, pos, w, L, st)) != E2F_OK) return rc;
+    // W_Q1 h of every atom: the projection kernel once more, with W_Q1 in the value's place (it rewrites q and k
+    // with the same numbers; the second run below leaves them in place with the values)
+    e2f_weights wq = *w;
+    wq.WV = w->WQ1;
+    E2fAttnWs Lq = L;
+    Lq.v = q1;
+    if ((rc = e2f_launch_project_mfma(ctx, cells->view, h, &wq, Lq, 0, st)) != E2F_OK) return rc;
+    if ((rc = e2f_launch_project_mfma(ctx, cells->view, h, w, L, 0, st)) != E2F_OK) return rc;
+    return e2f_launch_fused_nonlinear(ctx, cells->view, w, L, q1, out, st);
+}
+
 static E2fBwdWs bwd_ws_layout(const e2f_ctx* ctx, int32_t N, void* ws, size_t attn_bytes, bool with_W) {
     E2fBwdWs Bw;
     size_t off = attn_bytes;

@@ -146,6 +146,10 @@ e2f_status e2f_launch_project_simple(const e2f_ctx* ctx, const E2fCellsView& cv,
                                      float* q, float* k, float* v, hipStream_t st);
 e2f_status e2f_launch_fused(const e2f_ctx* ctx, const E2fCellsView& cv, const e2f_weights* w, const E2fAttnWs& ws,
                             float* out, hipStream_t st);
+// The fused call with the non-linear pair feature in the logit; q1 = W_Q1 h in v's plain layout and type.
+bool e2f_nonlinear_supported(const e2f_ctx* ctx);
+e2f_status e2f_launch_fused_nonlinear(const e2f_ctx* ctx, const E2fCellsView& cv, const e2f_weights* w,
+                                      const E2fAttnWs& ws, const void* q1, float* out, hipStream_t st);
 e2f_status e2f_launch_tensor_product(const e2f_ctx* ctx, const void* h, const float* r, const float* w_path, float* out,
                                      int32_t T, hipStream_t st);
 bool e2f_fused_mfma_supported(const e2f_ctx* ctx);
