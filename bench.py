@@ -264,6 +264,14 @@ def main():
         except B.E2fError as e:
             result["backward"] = {"error": str(e)}
 
+        # the logit with the non-linear pair feature (vector-ALU kernel), same workload
+        try:
+            nl_ms = timed(lambda: P.forward_nonlinear(out_c), reps=5)
+            result["nonlinear_score"] = {"forward_ms": round(nl_ms, 4), "atoms_per_s": round(N / (nl_ms * 1e-3), 1),
+                                         "workspace_bytes": int(B.e2f_attn_nonlinear_workspace_bytes(P.ctx, N))}
+        except B.E2fError as e:
+            result["nonlinear_score"] = {"error": str(e)}
+
     if not args.no_materialized:
         try:
             out_m = torch.empty_like(P.out)
