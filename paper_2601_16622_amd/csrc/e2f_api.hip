@@ -110,6 +110,9 @@ E2fAttnWs e2f_attn_ws_layout(const e2f_ctx* ctx, int32_t N, void* ws, int v_layo
     L.v = nullptr;
     L.q16 = L.k16 = L.v4 = nullptr;
     L.G = nullptr;
+    L.lists_hdr = nullptr;
+    L.lists_ent = nullptr;
+    L.lists_pos = nullptr;
     if (v_layout == 2) {
         const size_t H = ctx->cfg.H, DKP = ((size_t)(ctx->cfg.L_max + 1) * 16 + 31) / 32 * 32;
         const size_t N4 = ((size_t)N + 3) / 4 * 4;
@@ -117,6 +120,10 @@ E2fAttnWs e2f_attn_ws_layout(const e2f_ctx* ctx, int32_t N, void* ws, int v_layo
         L.k16 = (uint16_t*)take(N4 * H * DKP * 2);
         L.v4 = (uint16_t*)take(N4 / 4 * H * ctx->n * 64 * 2);
         L.G = (float*)take((size_t)3 * E2F_MAX_N * E2F_MAX_N * 4);
+        const size_t n_tiles = ((size_t)N + 15) / 16;
+        L.lists_hdr = (int4*)take(n_tiles * sizeof(int4));
+        L.lists_ent = (int*)take(n_tiles * E2F_TILE_LCAP * 4);
+        L.lists_pos = (float4*)take(n_tiles * E2F_TILE_LCAP * 4 * sizeof(float4));
     } else {
         L.q = (float*)take((size_t)N * (ctx->cfg.L_max + 1) * ctx->cfg.C * 4);
         L.k = (float*)take((size_t)N * (ctx->cfg.L_max + 1) * ctx->cfg.C * 4);

@@ -87,8 +87,13 @@ struct E2fAttnWs {
     uint16_t* k16;       // [4*ceil(N/4)][H][DKP] binary16
     uint16_t* v4;        // [ceil(N/4)][H][n][16 channels][4 slots] bf16
     float* G;            // [3][25][25] axis operators of the degree-1 filter
+    // candidate lists of the tile kernel, one per tile of 16 sorted slots (see TileParams)
+    int4* lists_hdr;     // [ceil(N/16)]
+    int* lists_ent;      // [ceil(N/16)][E2F_TILE_LCAP]
+    float4* lists_pos;   // [ceil(N/16)][E2F_TILE_LCAP][4]
     size_t bytes;
 };
+#define E2F_TILE_LCAP 192
 // v_layout: 0 plain [N][n][C], 1 component tiles of the per-pair MFMA kernel, 2 slot groups of the tile kernel
 E2fAttnWs e2f_attn_ws_layout(const e2f_ctx* ctx, int32_t N, void* ws, int v_layout);
 static inline int e2f_v_layout(const e2f_ctx* ctx) { return ctx->use_tile_attn ? 2 : (ctx->use_mfma_attn ? 1 : 0); }

@@ -38,6 +38,8 @@ typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 
 constexpr int CAPG = 256;      // candidate groups (of four slots) held in LDS per batch
+constexpr int LCAP = E2F_TILE_LCAP;   // entries of a precomputed list; longer lists are built in the kernel
+static_assert(LCAP <= CAPG, "a precomputed list must fit the list area in LDS");
 constexpr int TILE_BLK = 16;   // consecutive tiles whose (tile, head) items form one XCD chunk, head-major
 #ifndef E2F_TILE_OCC
 #define E2F_TILE_OCC(NW) ((NW) / 2)
@@ -53,6 +55,13 @@ struct TileParams {
     const uint32_t* cap_d2;   // neighbour cap thresholds per sorted slot, or null
     const int32_t* cap_idx;
     float* out;
+    // candidate lists built once per tile for all heads, or null: header (entries or -1 = build the list in the
+    // kernel; pass of every target, 4 bits each), entries, positions of the entries' four slots (images included)
+    int4* lists_hdr;
+    int* lists_ent;
+    float4* lists_pos;
+    const float* cw;   // the list kernel's first workgroup forms the axis operators instead: G_out from cw
+    float* G_out;
     int C, H, B, n_tiles;
     float rc2, cutoff, rbf_step, rbf_gamma;
 #ifdef E2F_TIMING
@@ -100,9 +109,8 @@ __device__ __forceinline__ bool tile_xcd_remap(int bid, int n_tiles, int H, int&
 
 // The three axis operators, column by column: G[mu][x_out][x_in] = (e_{x_in} (x) R^(1)(e_mu))[x_out].
 template <int L>
-__global__ void k_axis_ops(const float* __restrict__ cw, float* __restrict__ G) {
+__device__ __forceinline__ void axis_ops(const float* __restrict__ cw, float* __restrict__ G, int tid) {
     constexpr int n = (L + 1) * (L + 1), DS = e2f::d_offset(L + 1);
-    const int tid = threadIdx.x;
     if (tid >= 3 * n) return;
     const int mu = tid / n, xi = tid % n;
     float D[DS];
@@ -117,6 +125,10 @@ __global__ void k_axis_ops(const float* __restrict__ cw, float* __restrict__ G) 
 #pragma unroll
     for (int xo = 0; xo < n; ++xo) G[(mu * E2F_MAX_N + xo) * E2F_MAX_N + xi] = acc[xo][0];
 }
+template <int L>
+__global__ void k_axis_ops(const float* __restrict__ cw, float* __restrict__ G) {
+    axis_ops<L>(cw, G, threadIdx.x);
+}
 
 // One workgroup of NW waves per (tile of 16 targets, head).  The waves share the candidate list and the softmax
 // weights through LDS and split the rest:
@@ -128,7 +140,11 @@ __global__ void k_axis_ops(const float* __restrict__ cw, float* __restrict__ G) 
 // The softmax reference of a target is common to the four waves: it is set by the target's first neighbours and
 // moved (with a rescale of the accumulator rows) only when a later logit exceeds it by M_STEP.
 // PBC: whether segments can have periodic axes (the candidate runs then include the images across the faces).
-template <int L, int NW, bool PBC>
+// MODE 0: lists built here, per (tile, head).  MODE 1: one workgroup per tile only builds the tile's list and writes it
+// out (no head, no streaming): the passes' lists one after the other, every entry tagged with its pass, so that a
+// candidate counts only for the targets of the pass that found it.  MODE 2: reads the list MODE 1 left (the H heads
+// of a tile share it), and builds it here when that one did not fit its LCAP entries.
+template <int L, int NW, bool PBC, int MODE>
 __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(E2F_TILE_OCC(NW), E2F_TILE_OCC(NW)))) void k_tile(TileParams P) {
     constexpr int n = (L + 1) * (L + 1), NX = (n + NW - 1) / NW;
     constexpr int PADE = 8 * NW;        // the list is padded to whole groups of NW chunks
@@ -155,7 +171,16 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(E2F_TIL
     f32x4* s_po = reinterpret_cast<f32x4*>(s_raw);
 
     int tile, head;
-    if (!tile_xcd_remap(blockIdx.x, P.n_tiles, P.H, tile, head)) return;   // whole workgroup
+    if constexpr (MODE == 1) {
+        if (blockIdx.x == 0) {   // (whole workgroup) the first workgroup forms the axis operators instead
+            axis_ops<L>(P.cw, P.G_out, threadIdx.x);
+            return;
+        }
+        tile = blockIdx.x - 1;
+        head = 0;
+    } else {
+        if (!tile_xcd_remap(blockIdx.x, P.n_tiles, P.H, tile, head)) return;   // whole workgroup
+    }
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, tn = lane & 15, g = lane >> 4;
     // components [x0, x0 + nxw) belong to this wave: n / NW each, the first n % NW waves one more (NX is the largest)
     const int nxw = n / NW + (wave < n % NW ? 1 : 0);
@@ -178,8 +203,8 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(E2F_TIL
 
     // radial bias of this head as a polynomial in u = e^{2 gamma step d}:  b(d) = e^{-gamma d^2} sum_b cb[b] u^b,
     // cb[b] = Wb[h][b] e^{-gamma (b step)^2} (log2 e folded in)
-    float cb[8];
-    {
+    float cb[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    if constexpr (MODE != 1) {
         const float bs = (float)lane * P.rbf_step;
         const float mine = lane < P.B ? P.WbT[lane * H + head] * __expf(-P.rbf_gamma * bs * bs) * 1.44269504088896341f : 0.0f;
 #pragma unroll
@@ -188,17 +213,31 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(E2F_TIL
     const float c_u = 2.0f * P.rbf_gamma * P.rbf_step * 1.44269504088896341f;
     const float c_g = -P.rbf_gamma * 1.44269504088896341f;
 
-    for (int i = threadIdx.x; i < 3 * E2F_MAX_N * E2F_MAX_N; i += 64 * NW) s_G[i] = P.G[i];
     // rows of the output that this lane will store (targets 4g..4g+3), fetched early
-    int orow[4];
+    int orow[4] = {-1, -1, -1, -1};
+    if constexpr (MODE != 1) {
+        for (int i = threadIdx.x; i < 3 * E2F_MAX_N * E2F_MAX_N; i += 64 * NW) s_G[i] = P.G[i];
 #pragma unroll
-    for (int r = 0; r < 4; ++r) orow[r] = t0 + 4 * g + r < N ? P.cv.perm[t0 + 4 * g + r] : -1;
-    // q of the 16 targets for this head -> LDS (3 KB); every group re-reads its B operands from there
-    for (int u = threadIdx.x; u < 16 * (DKP / 8); u += 64 * NW) {
-        const int tq = u / (DKP / 8), f8 = u % (DKP / 8);
-        reinterpret_cast<u32x4*>(s_q)[u] =
-            *reinterpret_cast<const u32x4*>(P.q16 + ((size_t)min(t0 + tq, N - 1) * H + head) * DKP + 8 * f8);
+        for (int r = 0; r < 4; ++r) orow[r] = t0 + 4 * g + r < N ? P.cv.perm[t0 + 4 * g + r] : -1;
+        // q of the 16 targets for this head -> LDS (3 KB); every group re-reads its B operands from there
+        for (int u = threadIdx.x; u < 16 * (DKP / 8); u += 64 * NW) {
+            const int tq = u / (DKP / 8), f8 = u % (DKP / 8);
+            reinterpret_cast<u32x4*>(s_q)[u] =
+                *reinterpret_cast<const u32x4*>(P.q16 + ((size_t)min(t0 + tq, N - 1) * H + head) * DKP + 8 * f8);
+        }
     }
+    // MODE 2: the tile's list as the list kernel left it (pre < 0: not there, build it here)
+    // (fetching the whole list area beside the header, so that nothing waits for the count, was slower)
+    int pre = -1, my_pass = -1;
+    if constexpr (MODE == 2) {
+        const int4 hd = P.lists_hdr[tile];
+        pre = hd.x;
+        if (pre >= 0 && tn < nt) my_pass = ((tn < 8 ? hd.y : hd.z) >> (4 * (tn & 7))) & 15;
+    }
+    // MODE 1: entries written so far, whether they still fit, the pass of every target
+    int out_cnt = 0, pidx = 0;
+    bool overflow = false;
+    __shared__ int s_tpass[16];
 
     f32x4 acc[3][NX];
 #pragma unroll
@@ -215,8 +254,10 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(E2F_TIL
         const bool same = tseg == seg_a && trow == row_a && lane >= a && lane < nt;   // lanes 0..15 carry the targets
         const unsigned bits = (unsigned)(__ballot(same) & 0xFFFFull);
         const unsigned stop = ~bits & ((1u << nt) - 1u) & ~((1u << a) - 1u);
-        const int b = stop ? __builtin_ctz(stop) : nt;
+        const int b = pre >= 0 ? nt : (stop ? __builtin_ctz(stop) : nt);   // (a precomputed list covers every pass)
         const bool t_active = tn >= a && tn < b;
+        if (pre < 0) my_pass = t_active ? (MODE == 1 ? pidx : 0) : -1;
+        if (MODE == 1 && t_active && threadIdx.x < 16) s_tpass[threadIdx.x] = pidx;
         const int cxa = __builtin_amdgcn_readlane(tcx, a), cxb = __builtin_amdgcn_readlane(tcx, b - 1);
         // Runs of sorted slots that hold the pass's candidates: rows 0..8 are the stencil rows over the cells
         // [cxa - 1, cxb + 1].  With periodic boundaries there are 27: runs 9..17 are the rows' last cell seen across
@@ -224,8 +265,8 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(E2F_TIL
         // along a periodic y or z come back in from the other side; candidates of a run are seen at their position
         // plus the run's lattice translation.  The runs are a table in LDS, one thread per run (in registers they
         // push the kernel's value rows into scratch).
-        int total;
-        {
+        int total = 1;
+        if (pre < 0) {
             __syncthreads();   // every wave has finished with the previous pass's table
             if (threadIdx.x < 16) {
                 // |p - t|^2 < reach^2 as |q|^2 + q.(-2u) + (|u|^2 - reach^2) < 0 with q = p - o, u = t - o around the
@@ -297,7 +338,15 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(E2F_TIL
 
         for (int fbase = 0; fbase < total; fbase += 256) {
             // ---- a batch of the candidate list: 256 slot groups, 64 per wave, kept groups packed in order into
-            // entries (group << 4 | valid slots) with the slots' positions beside them
+            // entries (group << 8 | pass << 4 | valid slots) with the slots' positions beside them
+            int cnt = 0;
+            if (pre >= 0) {   // (uniform) the list is there: entries and slot positions -> LDS
+                cnt = pre;
+                const int* ge = P.lists_ent + (size_t)tile * LCAP;
+                const float4* gp = P.lists_pos + (size_t)tile * LCAP * 4;
+                for (int i = threadIdx.x; i < cnt; i += 64 * NW) s_ent[i] = ge[i];
+                for (int i = threadIdx.x; i < 4 * cnt; i += 64 * NW) s_pos[i] = gp[i];
+            } else {
             int grp[LU];
             unsigned near4[LU], valid4[LU];
             unsigned long long leaders[LU];
@@ -362,7 +411,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(E2F_TIL
                 if (lane == 0) s_cnt[wave] = mine;
             }
             __syncthreads();   // every wave has finished with the previous list
-            int cnt = 0, e0 = 0;
+            int e0 = 0;
 #pragma unroll
             for (int w = 0; w < NW; ++w) {
                 const int cw_ = s_cnt[w];
@@ -374,10 +423,24 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(E2F_TIL
                 const int sh = lane & ~3;
                 const int e = e0 + __popcll(leaders[u] & ((1ull << sh) - 1ull));
                 if (near4[u] != 0u) {
-                    if ((lane & 3) == 0) s_ent[e] = (grp[u] << 4) | (int)valid4[u];
+                    if ((lane & 3) == 0) s_ent[e] = (int)(((unsigned)grp[u] << 8) | ((MODE == 1 ? (unsigned)pidx : 0u) << 4) | valid4[u]);
                     s_pos[e * 4 + (lane & 3)] = pj[u];
                 }
                 e0 += __popcll(leaders[u]);
+            }
+            }
+            if constexpr (MODE == 1) {
+                // ---- the list kernel: append the batch to the tile's list in memory
+                __syncthreads();
+                if (out_cnt + cnt > LCAP) overflow = true;
+                if (!overflow) {
+                    int* ge = P.lists_ent + (size_t)tile * LCAP + out_cnt;
+                    float4* gp = P.lists_pos + ((size_t)tile * LCAP + out_cnt) * 4;
+                    for (int i = threadIdx.x; i < cnt; i += 64 * NW) ge[i] = s_ent[i];
+                    for (int i = threadIdx.x; i < 4 * cnt; i += 64 * NW) gp[i] = s_pos[i];
+                    out_cnt += cnt;
+                }
+                continue;
             }
             // pad to whole groups of four chunks: entries of group 0 with no valid slot, finite positions
             for (int i = threadIdx.x; i < PADE; i += 64 * NW) s_ent[cnt + i] = 0;
@@ -393,7 +456,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(E2F_TIL
 #pragma unroll
                     for (int mt = 0; mt < 2; ++mt) {
                         const int e = s_ent[8 * c + 4 * mt + (tn >> 2)];
-                        const size_t off = ((size_t)(4 * (e >> 4) + (tn & 3)) * H + head) * DKP + 8 * g;
+                        const size_t off = ((size_t)(4 * ((unsigned)e >> 8) + (tn & 3)) * H + head) * DKP + 8 * g;
 #pragma unroll
                         for (int ks = 0; ks < KS; ++ks) kf[mt][ks] = *reinterpret_cast<const f16x8*>(P.k16 + off + 32 * ks);
                     }
@@ -401,7 +464,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(E2F_TIL
                 // v rows of this wave's component x for the lane's two entries: k = 8g..8g+3 from entry g of the
                 // chunk, 8g+4..8g+7 from entry 4+g
                 auto load_V = [&](int c, int x, u32x2& va, u32x2& vb) {
-                    const int ea = s_ent[8 * c + g] >> 4, eb = s_ent[8 * c + 4 + g] >> 4;
+                    const unsigned ea = (unsigned)s_ent[8 * c + g] >> 8, eb = (unsigned)s_ent[8 * c + 4 + g] >> 8;
                     va = *reinterpret_cast<const u32x2*>(P.v4 + (((size_t)ea * H + head) * n + x0) * 64 + tn * 4 + x * 64);
                     vb = *reinterpret_cast<const u32x2*>(P.v4 + (((size_t)eb * H + head) * n + x0) * 64 + tn * 4 + x * 64);
                 };
@@ -440,7 +503,8 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(E2F_TIL
                             const float4 pc = s_pos[ei * 4 + r];
                             const float d2 = e2f::dist2_exact(tp.x, tp.y, tp.z, pc.x, pc.y, pc.z);
                             // (bitwise on purpose: the eight candidates are evaluated side by side)
-                            const bool ok = (((e >> r) & 1) != 0) & t_active & ((4 * (e >> 4) + r) != t0 + tn) &
+                            const bool ok = (((e >> r) & 1) != 0) & (((e >> 4) & 15) == my_pass) &
+                                            ((int)(4 * ((unsigned)e >> 8) + r) != t0 + tn) &
                                             (d2 < P.rc2) & (d2 > 0.0f) & e2f::under_cap(d2, pc.w, capd, capi);
                             const float d = __builtin_amdgcn_sqrtf(d2);
                             const float uu = __builtin_amdgcn_exp2f(c_u * d);
@@ -535,6 +599,19 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(E2F_TIL
             TICK(3)
         }
         a = b;
+        ++pidx;
+    }
+    if constexpr (MODE == 1) {
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            unsigned lo = 0u, hi = 0u;
+            for (int i = 0; i < 8; ++i) {
+                lo |= (i < nt ? (unsigned)s_tpass[i] : 0u) << (4 * i);
+                hi |= (8 + i < nt ? (unsigned)s_tpass[8 + i] : 0u) << (4 * i);
+            }
+            P.lists_hdr[tile] = make_int4(overflow ? -1 : out_cnt, (int)lo, (int)hi, 0);
+        }
+        return;
     }
 
     // ---- epilogue: out = (1/z) sum_mu G_mu T_mu.  For one mu at a time the waves put their T_mu components into
@@ -615,13 +692,24 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(E2F_TIL
 
 template <int L>
 void launch_L(const TileParams& P, const float* cw, float* G, hipStream_t st) {
-    k_axis_ops<L><<<1, 128, 0, st>>>(cw, G);
+    if (!P.lists_hdr) k_axis_ops<L><<<1, 128, 0, st>>>(cw, G);
     const int chunks = (P.n_tiles + TILE_BLK - 1) / TILE_BLK;
     const int grid = ((chunks + 7) / 8) * 8 * TILE_BLK * P.H;
     // four waves per workgroup, two workgroups per CU: with eight waves the 128 registers left per wave do not
     // hold a wave's accumulators, value rows and key rows without spilling into the streaming loop
-    if (P.cv.periodic) k_tile<L, 4, true><<<grid, 256, 0, st>>>(P);
-    else k_tile<L, 4, false><<<grid, 256, 0, st>>>(P);
+    if (P.lists_hdr) {   // the tiles' candidate lists (and the axis operators) first, then the heads read them
+        if (P.cv.periodic) {
+            k_tile<L, 4, true, 1><<<P.n_tiles + 1, 256, 0, st>>>(P);
+            k_tile<L, 4, true, 2><<<grid, 256, 0, st>>>(P);
+        } else {
+            k_tile<L, 4, false, 1><<<P.n_tiles + 1, 256, 0, st>>>(P);
+            k_tile<L, 4, false, 2><<<grid, 256, 0, st>>>(P);
+        }
+    } else if (P.cv.periodic) {
+        k_tile<L, 4, true, 0><<<grid, 256, 0, st>>>(P);
+    } else {
+        k_tile<L, 4, false, 0><<<grid, 256, 0, st>>>(P);
+    }
 }
 
 }  // namespace
@@ -651,6 +739,13 @@ e2f_status e2f_launch_tile(const e2f_ctx* ctx, const E2fCellsView& cv, const E2f
     P.spos = ws.spos; P.q16 = ws.q16; P.k16 = ws.k16; P.v4 = ws.v4; P.G = ws.G; P.WbT = ws.wbT;
     P.cap_d2 = ws.cap_d2; P.cap_idx = ws.cap_idx;
     P.out = out;
+    const bool lists = ws.lists_hdr && !getenv("E2F_TILE_NO_LISTS");
+    P.lists_hdr = lists ? ws.lists_hdr : nullptr;
+    P.lists_ent = ws.lists_ent;
+    P.lists_pos = ws.lists_pos;
+    P.cw = ws.cw;
+    P.G_out = ws.G;
+    if (cv.N >= (1 << 26)) return E2F_ERR_UNSUPPORTED;   // a list entry keeps the slot group in 24 bits
     P.C = ctx->cfg.C; P.H = ctx->cfg.H; P.B = ctx->cfg.B; P.n_tiles = (cv.N + 15) / 16;
     P.rc2 = ctx->rc2; P.cutoff = ctx->cfg.cutoff; P.rbf_step = ctx->rbf_step; P.rbf_gamma = ctx->rbf_gamma;
 #ifdef E2F_TIMING

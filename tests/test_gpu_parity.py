@@ -335,6 +335,38 @@ def test_result_is_deterministic_and_order_equivariant(torch_cuda):
     P2.close()
 
 
+@pytest.mark.parametrize("name", ["large", "scaling", "pbox2500"])
+def test_shared_candidate_lists_and_lists_built_per_head_agree(torch_cuda, name, monkeypatch):
+    """The tile kernel reads candidate lists built once per tile (all heads) or builds them per (tile, head): the same
+    pairs either way.  The order of the candidates differs, and with it the softmax reference that the bf16 weights
+    are rounded against, so the two agree to bf16 rounding noise (well inside the tolerance against the oracle)."""
+    from paper_2601_16622_amd import binding as B
+    from paper_2601_16622_amd import workloads as W
+    wl = W.by_name(name, 0)
+    P = B.Problem(wl)
+    try:
+        P.build_cells()
+        P.forward()
+        torch_cuda.cuda.synchronize()
+        shared = P.out.clone()
+        monkeypatch.setenv("E2F_TILE_NO_LISTS", "1")
+        P.out.fill_(float("nan"))
+        P.forward()
+        torch_cuda.cuda.synchronize()
+        per_head = P.out
+        assert torch_cuda.isfinite(shared).all() and torch_cuda.isfinite(per_head).all()
+        assert float((shared - per_head).norm() / per_head.norm()) < 5e-3
+        # a neighbour cap prunes the lists with every target's own reach
+        monkeypatch.delenv("E2F_TILE_NO_LISTS")
+        a = P.forward_capped(24, torch_cuda.empty_like(P.out)).clone()
+        monkeypatch.setenv("E2F_TILE_NO_LISTS", "1")
+        b = P.forward_capped(24, torch_cuda.empty_like(P.out))
+        torch_cuda.cuda.synchronize()
+        assert float((a - b).norm() / b.norm()) < 5e-3
+    finally:
+        P.close()
+
+
 @pytest.mark.parametrize("name", ["tiny", "odd_bf16"])
 def test_step_replays_from_a_captured_graph(torch_cuda, name):
     """e2f_build_cells + e2f_attn_forward allocate nothing, never synchronise and clear their counters with kernels, so a
