@@ -690,25 +690,24 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(E2F_TIL
 #endif
 }
 
+// what: 1 the list kernel (with the axis operators), 2 the attention kernel reading the lists, 0 the attention kernel
+// building its lists itself (after the axis-operator kernel)
 template <int L>
-void launch_L(const TileParams& P, const float* cw, float* G, hipStream_t st) {
-    if (!P.lists_hdr) k_axis_ops<L><<<1, 128, 0, st>>>(cw, G);
+void launch_L(const TileParams& P, const float* cw, float* G, int what, hipStream_t st) {
     const int chunks = (P.n_tiles + TILE_BLK - 1) / TILE_BLK;
     const int grid = ((chunks + 7) / 8) * 8 * TILE_BLK * P.H;
     // four waves per workgroup, two workgroups per CU: with eight waves the 128 registers left per wave do not
     // hold a wave's accumulators, value rows and key rows without spilling into the streaming loop
-    if (P.lists_hdr) {   // the tiles' candidate lists (and the axis operators) first, then the heads read them
-        if (P.cv.periodic) {
-            k_tile<L, 4, true, 1><<<P.n_tiles + 1, 256, 0, st>>>(P);
-            k_tile<L, 4, true, 2><<<grid, 256, 0, st>>>(P);
-        } else {
-            k_tile<L, 4, false, 1><<<P.n_tiles + 1, 256, 0, st>>>(P);
-            k_tile<L, 4, false, 2><<<grid, 256, 0, st>>>(P);
-        }
-    } else if (P.cv.periodic) {
-        k_tile<L, 4, true, 0><<<grid, 256, 0, st>>>(P);
+    if (what == 1) {
+        if (P.cv.periodic) k_tile<L, 4, true, 1><<<P.n_tiles + 1, 256, 0, st>>>(P);
+        else k_tile<L, 4, false, 1><<<P.n_tiles + 1, 256, 0, st>>>(P);
+    } else if (what == 2) {
+        if (P.cv.periodic) k_tile<L, 4, true, 2><<<grid, 256, 0, st>>>(P);
+        else k_tile<L, 4, false, 2><<<grid, 256, 0, st>>>(P);
     } else {
-        k_tile<L, 4, false, 0><<<grid, 256, 0, st>>>(P);
+        k_axis_ops<L><<<1, 128, 0, st>>>(cw, G);
+        if (P.cv.periodic) k_tile<L, 4, true, 0><<<grid, 256, 0, st>>>(P);
+        else k_tile<L, 4, false, 0><<<grid, 256, 0, st>>>(P);
     }
 }
 
@@ -732,20 +731,20 @@ bool e2f_tile_supported(const e2f_ctx* ctx) {
            ctx->cfg.B <= 8 && (C == 32 || C == 64 || C == 128);
 }
 
-e2f_status e2f_launch_tile(const e2f_ctx* ctx, const E2fCellsView& cv, const E2fAttnWs& ws, float* out, hipStream_t st) {
+static e2f_status launch_tile(const e2f_ctx* ctx, const E2fCellsView& cv, const E2fAttnWs& ws, float* out, int what,
+                              hipStream_t st) {
     if (cv.N == 0) return E2F_OK;
+    if (cv.N >= (1 << 26)) return E2F_ERR_UNSUPPORTED;   // a list entry keeps the slot group in 24 bits
     TileParams P;
     P.cv = cv;
     P.spos = ws.spos; P.q16 = ws.q16; P.k16 = ws.k16; P.v4 = ws.v4; P.G = ws.G; P.WbT = ws.wbT;
     P.cap_d2 = ws.cap_d2; P.cap_idx = ws.cap_idx;
     P.out = out;
-    const bool lists = ws.lists_hdr && !getenv("E2F_TILE_NO_LISTS");
-    P.lists_hdr = lists ? ws.lists_hdr : nullptr;
+    P.lists_hdr = what == 0 ? nullptr : ws.lists_hdr;
     P.lists_ent = ws.lists_ent;
     P.lists_pos = ws.lists_pos;
     P.cw = ws.cw;
     P.G_out = ws.G;
-    if (cv.N >= (1 << 26)) return E2F_ERR_UNSUPPORTED;   // a list entry keeps the slot group in 24 bits
     P.C = ctx->cfg.C; P.H = ctx->cfg.H; P.B = ctx->cfg.B; P.n_tiles = (cv.N + 15) / 16;
     P.rc2 = ctx->rc2; P.cutoff = ctx->cfg.cutoff; P.rbf_step = ctx->rbf_step; P.rbf_gamma = ctx->rbf_gamma;
 #ifdef E2F_TIMING
@@ -755,12 +754,31 @@ e2f_status e2f_launch_tile(const e2f_ctx* ctx, const E2fCellsView& cv, const E2f
     { unsigned long long hst[8]; (void)hipMemcpy(hst, dbg, 64, hipMemcpyDeviceToHost); if (getenv("E2F_TIMING_PRINT")) fprintf(stderr, "sections(cum) setup %llu list %llu prologue %llu loop %llu epilogue %llu chunks %llu batches %llu\n", hst[0], hst[1], hst[2], hst[3], hst[4], hst[6], hst[7]); }
 #endif
     switch (ctx->cfg.L_max) {
-        case 1: launch_L<1>(P, ws.cw, ws.G, st); break;
-        case 2: launch_L<2>(P, ws.cw, ws.G, st); break;
-        case 3: launch_L<3>(P, ws.cw, ws.G, st); break;
-        case 4: launch_L<4>(P, ws.cw, ws.G, st); break;
+        case 1: launch_L<1>(P, ws.cw, ws.G, what, st); break;
+        case 2: launch_L<2>(P, ws.cw, ws.G, what, st); break;
+        case 3: launch_L<3>(P, ws.cw, ws.G, what, st); break;
+        case 4: launch_L<4>(P, ws.cw, ws.G, what, st); break;
         default: return E2F_ERR_UNSUPPORTED;
     }
     E2F_HIP_CHECK(hipGetLastError());
     return E2F_OK;
+}
+
+// E2F_TILE_NO_LISTS (environment, read at every call): the attention kernel builds its lists per (tile, head).
+bool e2f_tile_uses_lists(const e2f_ctx* ctx, const E2fAttnWs& ws) {
+    return ctx->use_tile_attn && ws.lists_hdr && !getenv("E2F_TILE_NO_LISTS");
+}
+
+e2f_status e2f_launch_tile_lists(const e2f_ctx* ctx, const E2fCellsView& cv, const E2fAttnWs& ws, hipStream_t st) {
+    return launch_tile(ctx, cv, ws, nullptr, 1, st);
+}
+
+e2f_status e2f_launch_tile(const e2f_ctx* ctx, const E2fCellsView& cv, const E2fAttnWs& ws, float* out, hipStream_t st,
+                           bool lists_ready) {
+    if (!e2f_tile_uses_lists(ctx, ws)) return launch_tile(ctx, cv, ws, out, 0, st);
+    if (!lists_ready) {
+        const e2f_status rc = launch_tile(ctx, cv, ws, out, 1, st);
+        if (rc != E2F_OK) return rc;
+    }
+    return launch_tile(ctx, cv, ws, out, 2, st);
 }
