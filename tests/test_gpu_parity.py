@@ -311,6 +311,23 @@ def test_isolated_atoms_and_crowded_cells(torch_cuda):
     P.close()
 
 
+def test_tile_kernel_with_lists_longer_than_the_shared_list_area(torch_cuda):
+    """1500 atoms in a 6 A box (bf16, heads of 16: the tile kernel): central atoms have over 1000 neighbours, so their
+    tiles keep more slot groups than a tile's shared candidate list holds (192 entries) and more than one batch of
+    the list in LDS (256): those tiles build their lists per head, in several batches; a sparse cluster beside them
+    uses the shared lists."""
+    from paper_2601_16622_amd import workloads as W
+    rng = np.random.default_rng(10)
+    cfg = dict(L=1, C=32, H=2, B=8, lf=1, cutoff=4.0, dtype="bf16")
+    crowd = W.dart_throw_box(rng, 1500, 6.0, min_sep=0.3)
+    sparse = W.dart_throw_box(rng, 200, 14.0, origin=(40.0, 0.0, 0.0))
+    wl = W._pack(cfg, [crowd, sparse], rng, elements=False)
+    import oracle as O
+    offs, _ = O.neighbor_list(wl["pos"], wl["seg"], np.float32(4.0))
+    assert np.diff(offs)[:1500].max() > 4 * 256 and np.diff(offs)[1500:].max() < 100
+    run_case(torch_cuda, wl, check_materialized=False)
+
+
 def test_result_is_deterministic_and_order_equivariant(torch_cuda):
     from paper_2601_16622_amd import binding as B, workloads as W
     wl = W.small_molecules(2, n_mol=6)
