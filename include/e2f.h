@@ -196,8 +196,8 @@ e2f_status e2f_attn_forward_table(e2f_ctx *ctx, const e2f_cells *cells, const fl
  *     s_ij,h  = (1/sqrt(d_k)) sum_{l, c in head h} q_i[l][c] k_j[l][c] (sigma(a[l][c]) + sigma(b[l][c])) + b_h(d_ij),
  * and softmax, gate and message exactly as e2f_attn_forward.  Same arguments; open and periodic cells; lf = 0, 1, 2.
  * Workspace: e2f_attn_nonlinear_workspace_bytes (the plain-layout attention workspace plus one [N][(L_max+1)^2][C]
- * array of the feature type), O(N).  Requires C <= 128.  Allocates nothing, does not synchronise.
- * Errors: as e2f_attn_forward; E2F_ERR_UNSUPPORTED for C > 128.
+ * array of the feature type), O(N).  Requires C <= 256 and heads of a power-of-two number of channels, at most 64.
+ * Allocates nothing, does not synchronise.  Errors: as e2f_attn_forward; E2F_ERR_UNSUPPORTED outside those limits.
  */
 size_t e2f_attn_nonlinear_workspace_bytes(const e2f_ctx *ctx, int32_t N);
 e2f_status e2f_attn_forward_nonlinear(e2f_ctx *ctx, const e2f_cells *cells, const float *pos, const void *h,

@@ -6,7 +6,8 @@
 //     s_ij,h  = tau sum_{l, c in h} q_i[l][c] k_j[l][c] (sigma(a[l][c]) + sigma(b[l][c])) + b_h(d_ij)
 // and everything after the logit as in Algorithm 1 (softmax over the neighbours, gate outside, EAAS message).
 //
-// One wave per target atom, lanes over channels (CPL channels per lane), like the ALU form of the fused call.  The
+// One workgroup per target atom, one thread per channel (one or more waves; every wave walks the stencil and reads the
+// pair geometry that the first lanes of each wave build, identically), like the ALU form of the fused call.  The
 // harmonics of the pair direction cost nothing extra: R_ij takes the pair direction to +z, so Y^(l)(r/|r|) is the
 // m = 0 row of the block D^(l)(R_ij) that the message needs anyway.  The value row of a neighbour is read once and
 // serves the feature and the message; the softmax is online per pair (Algorithm 1 as printed).
@@ -36,8 +37,9 @@ constexpr int CAP = 192;  // capacity of the neighbour list in LDS
 
 __device__ __forceinline__ float silu(float x) { return x * __builtin_amdgcn_rcpf(1.0f + __expf(-x)); }
 
-template <int L, int LF, int CPL, typename VT>
-__global__ __launch_bounds__(64) void k_fused_nonlinear(NlParams P) {
+template <int L, int LF, typename VT>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k_fused_nonlinear(NlParams P) {
+    constexpr int CPL = 1;
     constexpr int n = (L + 1) * (L + 1);
     constexpr int DS = e2f::d_offset(L + 1);
     constexpr int DSP = (DS + 3) & ~3;
@@ -46,25 +48,27 @@ __global__ __launch_bounds__(64) void k_fused_nonlinear(NlParams P) {
     __shared__ float s_bias[PB * E2F_MAX_H];
     __shared__ float s_wgt[PB];
 
-    const int t = e2f::xcd_remap(blockIdx.x, P.cv.N), lane = threadIdx.x;
-    if (t < 0) return;  // padding block of the XCD map (whole wave)
+    const int t = e2f::xcd_remap(blockIdx.x, P.cv.N), lane = threadIdx.x & 63;
+    if (t < 0) return;  // padding block of the XCD map (whole workgroup)
     const int C = P.C, H = P.H;
-    const int nlanes = C / CPL;
-    const bool active = lane < nlanes;
-    const int c0 = active ? lane * CPL : 0;  // idle lanes shadow lane 0's loads and store nothing
+    const bool active = (int)threadIdx.x < C;
+    const int c0 = active ? threadIdx.x : 0;  // idle lanes shadow channel 0's loads and store nothing
     const int head = c0 / P.Ch;
-    const int lanes_per_head = P.Ch / CPL;
+    const int lanes_per_head = P.Ch;
     const float4 pi = P.spos[t];
 
-    float q[L + 1][CPL], q1[n][CPL];
+    float q[L + 1][CPL];
 #pragma unroll
     for (int l = 0; l <= L; ++l)
 #pragma unroll
         for (int u = 0; u < CPL; ++u) q[l][u] = P.q[((size_t)t * (L + 1) + l) * C + c0 + u];
+    // the target's query components: in LDS (component-major), not in registers, where they would sit beside the
+    // accumulators, the value row and its rotated copy
+    extern __shared__ float s_q1[];   // [n][threads]
+    const int nthreads = blockDim.x;
 #pragma unroll
     for (int x = 0; x < n; ++x)
-#pragma unroll
-        for (int u = 0; u < CPL; ++u) q1[x][u] = e2f::load_as_float((const VT*)P.q1 + ((size_t)t * n + x) * C + c0 + u);
+        s_q1[x * nthreads + threadIdx.x] = e2f::load_as_float((const VT*)P.q1 + ((size_t)t * n + x) * C + c0);
 
     float A[n][CPL];
 #pragma unroll
@@ -144,7 +148,7 @@ __global__ __launch_bounds__(64) void k_fused_nonlinear(NlParams P) {
                         const float y = Dp[e2f::d_offset(l) + l * (2 * l + 1) + m];
 #pragma unroll
                         for (int u = 0; u < CPL; ++u) {
-                            a[u] += q1[l * l + m][u] * y;
+                            a[u] += s_q1[(l * l + m) * nthreads + threadIdx.x] * y;
                             b[u] += vin[l * l + m][u] * y;
                         }
                     }
@@ -180,38 +184,34 @@ __global__ __launch_bounds__(64) void k_fused_nonlinear(NlParams P) {
     }
 }
 
-template <int L, int LF, int CPL>
-void launch_dtype(const e2f_ctx* ctx, const NlParams& P, hipStream_t st) {
-    const int grid = e2f::xcd_grid(P.cv.N);
-    if (ctx->cfg.feat_dtype == E2F_BF16)
-        k_fused_nonlinear<L, LF, CPL, uint16_t><<<grid, 64, 0, st>>>(P);
-    else
-        k_fused_nonlinear<L, LF, CPL, float><<<grid, 64, 0, st>>>(P);
-}
-
 template <int L, int LF>
-bool launch_cpl(const e2f_ctx* ctx, const NlParams& P, hipStream_t st) {
-    switch (ctx->cpl) {
-        case 1: launch_dtype<L, LF, 1>(ctx, P, st); return true;
-        case 2: launch_dtype<L, LF, 2>(ctx, P, st); return true;
-    }
-    return false;
+bool launch_dtype(const e2f_ctx* ctx, const NlParams& P, hipStream_t st) {
+    const int grid = e2f::xcd_grid(P.cv.N), threads = (P.C + 63) / 64 * 64;
+    const size_t shm = (size_t)(L + 1) * (L + 1) * threads * sizeof(float);
+    if (ctx->cfg.feat_dtype == E2F_BF16)
+        k_fused_nonlinear<L, LF, uint16_t><<<grid, threads, shm, st>>>(P);
+    else
+        k_fused_nonlinear<L, LF, float><<<grid, threads, shm, st>>>(P);
+    return true;
 }
 
 template <int L>
 bool launch_lf(const e2f_ctx* ctx, const NlParams& P, hipStream_t st) {
     switch (ctx->cfg.lf) {
-        case 0: return launch_cpl<L, 0>(ctx, P, st);
-        case 1: return launch_cpl<L, 1>(ctx, P, st);
-        case 2: return launch_cpl<L, 2>(ctx, P, st);
+        case 0: return launch_dtype<L, 0>(ctx, P, st);
+        case 1: return launch_dtype<L, 1>(ctx, P, st);
+        case 2: return launch_dtype<L, 2>(ctx, P, st);
     }
     return false;
 }
 
 }  // namespace
 
-// At most two channels per lane: the target's query components sit in registers beside the accumulators.
-bool e2f_nonlinear_supported(const e2f_ctx* ctx) { return ctx->cpl <= 2; }
+// A head's channels sit in one wave (the logit is reduced by a butterfly over them); at most four waves per target.
+bool e2f_nonlinear_supported(const e2f_ctx* ctx) {
+    const int Ch = ctx->Ch;
+    return ctx->cfg.C <= 256 && Ch <= 64 && (Ch & (Ch - 1)) == 0;
+}
 
 e2f_status e2f_launch_fused_nonlinear(const e2f_ctx* ctx, const E2fCellsView& cv, const e2f_weights* w,
                                       const E2fAttnWs& ws, const void* q1, float* out, hipStream_t st) {

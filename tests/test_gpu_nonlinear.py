@@ -66,8 +66,10 @@ def run_nonlinear(torch, wl, targets=None):
     dict(N=90, L=4, C=64, H=8, B=16, lf=1, dtype="f32"),
     dict(N=120, L=2, C=16, H=1, B=8, lf=1, dtype="f32", seg=[0, 0, 1, 40, 40, 119, 120]),  # empty and 1-atom segments
     dict(N=72, L=4, C=16, H=2, B=8, lf=2, dtype="f32"),        # degree-2 filter
-    dict(N=64, L=4, C=128, H=8, B=8, lf=1, dtype="bf16"),      # two channels per lane
+    dict(N=64, L=4, C=128, H=8, B=8, lf=1, dtype="bf16"),      # two waves per target
     dict(N=64, L=2, C=128, H=4, B=8, lf=2, dtype="f32"),
+    dict(N=33, L=1, C=256, H=8, B=8, lf=1, dtype="bf16"),      # four waves per target
+    dict(N=40, L=2, C=48, H=3, B=8, lf=1, dtype="f32"),        # idle lanes in the only wave
 ])
 def test_shapes_and_filter_degrees(torch_cuda, kw):
     run_nonlinear(torch_cuda, _custom(5, **kw))
@@ -95,7 +97,7 @@ def test_periodic_boxes(torch_cuda):
 
 def test_limits_and_empty_input(torch_cuda):
     from paper_2601_16622_amd import binding as B
-    wl = _custom(5, N=33, L=1, C=256, H=8, B=8, lf=1, dtype="bf16")   # four channels per lane: not built
+    wl = _custom(5, N=33, L=1, C=128, H=1, B=8, lf=1, dtype="bf16")   # a head wider than a wave: not built
     P = B.Problem(wl)
     try:
         P.build_cells()
