@@ -578,7 +578,7 @@ __global__ __launch_bounds__(64 * (C / 16 + 1)) void k_project_sh(E2fCellsView c
     typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
     typedef _Float16 h16x4 __attribute__((ext_vector_type(4)));
     constexpr int NS = C / F::KSTEP, NCT = C / 16, ROW = C + 8, NLD = C / 32;   // NLD 16-byte loads per lane and slab
-    __shared__ __attribute__((aligned(16))) uint16_t s_x[2][16 * ROW];
+    __shared__ __attribute__((aligned(16))) uint16_t s_x[4][16 * ROW];   // slab st in buffer st mod 4
     __shared__ __attribute__((aligned(8))) uint16_t s_t[NCT][256];
     const int N = cv.N, n = (L + 1) * (L + 1), n_tiles = (N + 15) / 16, N4 = (N + 3) / 4 * 4;
     const int l = L - (int)blockIdx.x / n_groups, nl = 2 * l + 1;
@@ -607,22 +607,28 @@ __global__ __launch_bounds__(64 * (C / 16 + 1)) void k_project_sh(E2fCellsView c
 #pragma unroll
             for (int i = 0; i < NLD; ++i) *reinterpret_cast<u32x4*>(d + 8 * i) = r[i];
         };
-        // slab st + 1 is written to LDS while the others work on slab st; its registers then take slab st + 1 + PD,
-        // so PD slabs are in flight at any time
+        // The computing waves take two slabs per step (st, st + 1: two independent chains of matrix products, one
+        // barrier).  Slabs st + 2 and st + 3 are written to LDS meanwhile (four buffers); slab k travels in r[k mod PD],
+        // whose registers then take slab k + PD, so PD slabs are in flight at any time.
         constexpr int PD = 6;
+        static_assert(PD % 2 == 0, "slabs are handed over in pairs");
         u32x4 r[PD][NLD];
 #pragma unroll
         for (int u = 0; u < PD; ++u) issue(u, r[u]);
         put(0, r[0]);
         issue(PD, r[0]);
+        put(1, r[1]);
+        issue(PD + 1, r[1]);
         __syncthreads();
         for (int s0 = 0; s0 < n_steps; s0 += PD) {
 #pragma unroll
-            for (int u = 0; u < PD; ++u) {
-                const int st = s0 + u;   // slab st + 1 lives in r[(u + 1) % PD]
+            for (int u = 0; u < PD; u += 2) {
+                const int st = s0 + u;
                 if (st < n_steps) {
-                    put((st + 1) & 1, r[(u + 1) % PD]);
-                    issue(st + 1 + PD, r[(u + 1) % PD]);
+                    put((st + 2) & 3, r[(u + 2) % PD]);
+                    issue(st + 2 + PD, r[(u + 2) % PD]);
+                    put((st + 3) & 3, r[(u + 3) % PD]);
+                    issue(st + 3 + PD, r[(u + 3) % PD]);
                     __syncthreads();
                 }
             }
@@ -652,60 +658,69 @@ __global__ __launch_bounds__(64 * (C / 16 + 1)) void k_project_sh(E2fCellsView c
     f32x4 qacc = {0.f, 0.f, 0.f, 0.f}, kacc = {0.f, 0.f, 0.f, 0.f};
     const int DK = (L + 1) * 16;
     __syncthreads();
-    int st = 0;
-    for (int lt = 0; lt < nt; ++lt)
-        for (int m = 0; m < nl; ++m, ++st) {
-            const uint16_t* xrow = s_x[st & 1] + j * ROW;
-            f32x4 p[5];
+    // what follows the matrix products of one slab (local tile lt, order m)
+    auto finish_slab = [&](int st, const f32x4 (&p)[5]) {
+        const int lt = st / nl, m = st - lt * nl;
+        qacc += p[0] * p[1];
+        kacc += p[2] * p[3];
+        // accumulator layout: lane (g, j) holds output channels 4g..4g+3 of atom j
+        const int slot = (tile0 + lt) * 16 + j;
+        {   // v: [channel][atom] patch, then one (channel, group of four slots) per lane
+            uint16_t* patch = s_t[ct];
 #pragma unroll
-            for (int w = 0; w < 5; ++w) p[w] = (f32x4){0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int S = 0; S < NS; ++S) {
-                const F::type X = F::load(xrow, S, g);
-#pragma unroll
-                for (int w = 0; w < 5; ++w) p[w] = F::mma(Wf[w][S], X, p[w]);
-            }
-            qacc += p[0] * p[1];
-            kacc += p[2] * p[3];
-            // accumulator layout: lane (g, j) holds output channels 4g..4g+3 of atom j
-            const int slot = (tile0 + lt) * 16 + j;
-            {   // v: [channel][atom] patch, then one (channel, group of four slots) per lane
-                uint16_t* patch = s_t[ct];
-#pragma unroll
-                for (int r = 0; r < 4; ++r)
-                    patch[(4 * g + r) * 16 + j] = slot < N ? e2f::float_to_bf16_bits(p[4][r]) : (uint16_t)0;
-                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-                __builtin_amdgcn_wave_barrier();
-                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
-                const int ch = lane >> 2, G = lane & 3;
-                const u32x2 unit = *reinterpret_cast<const u32x2*>(patch + ch * 16 + 4 * G);
-                const int grp = (tile0 + lt) * 4 + G;
-                if (grp * 4 < N)
-                    *reinterpret_cast<u32x2*>(go.v4 + (((size_t)grp * NCT + ct) * n + l * l + m) * 64 + ch * 4) = unit;
-                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-                __builtin_amdgcn_wave_barrier();
-            }
-            if (m == nl - 1) {   // last order of this tile: q and k of the degree go out
-                h16x4 qv, kv;
-#pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    qv[r] = (_Float16)(qacc[r] * go.qscale);
-                    kv[r] = (_Float16)(slot < N ? kacc[r] : 0.0f);
-                }
-                const size_t dst = ((size_t)slot * NCT + ct) * go.DKP + l * 16 + 4 * g;
-                if (slot < N) *reinterpret_cast<h16x4*>(go.q16 + dst) = qv;
-                if (slot < N4) *reinterpret_cast<h16x4*>(go.k16 + dst) = kv;
-                if (l == L && go.DKP > DK) {   // padding features read as zero
-                    const h16x4 zero = {(_Float16)0.0f, (_Float16)0.0f, (_Float16)0.0f, (_Float16)0.0f};
-                    const size_t dz = ((size_t)slot * NCT + ct) * go.DKP + DK + 4 * g;
-                    if (slot < N) *reinterpret_cast<h16x4*>(go.q16 + dz) = zero;
-                    if (slot < N4) *reinterpret_cast<h16x4*>(go.k16 + dz) = zero;
-                }
-                qacc = (f32x4){0.f, 0.f, 0.f, 0.f};
-                kacc = (f32x4){0.f, 0.f, 0.f, 0.f};
-            }
-            __syncthreads();
+            for (int r = 0; r < 4; ++r)
+                patch[(4 * g + r) * 16 + j] = slot < N ? e2f::float_to_bf16_bits(p[4][r]) : (uint16_t)0;
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+            const int ch = lane >> 2, G = lane & 3;
+            const u32x2 unit = *reinterpret_cast<const u32x2*>(patch + ch * 16 + 4 * G);
+            const int grp = (tile0 + lt) * 4 + G;
+            if (grp * 4 < N)
+                *reinterpret_cast<u32x2*>(go.v4 + (((size_t)grp * NCT + ct) * n + l * l + m) * 64 + ch * 4) = unit;
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+            __builtin_amdgcn_wave_barrier();
         }
+        if (m == nl - 1) {   // last order of this tile: q and k of the degree go out
+            h16x4 qv, kv;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                qv[r] = (_Float16)(qacc[r] * go.qscale);
+                kv[r] = (_Float16)(slot < N ? kacc[r] : 0.0f);
+            }
+            const size_t dst = ((size_t)slot * NCT + ct) * go.DKP + l * 16 + 4 * g;
+            if (slot < N) *reinterpret_cast<h16x4*>(go.q16 + dst) = qv;
+            if (slot < N4) *reinterpret_cast<h16x4*>(go.k16 + dst) = kv;
+            if (l == L && go.DKP > DK) {   // padding features read as zero
+                const h16x4 zero = {(_Float16)0.0f, (_Float16)0.0f, (_Float16)0.0f, (_Float16)0.0f};
+                const size_t dz = ((size_t)slot * NCT + ct) * go.DKP + DK + 4 * g;
+                if (slot < N) *reinterpret_cast<h16x4*>(go.q16 + dz) = zero;
+                if (slot < N4) *reinterpret_cast<h16x4*>(go.k16 + dz) = zero;
+            }
+            qacc = (f32x4){0.f, 0.f, 0.f, 0.f};
+            kacc = (f32x4){0.f, 0.f, 0.f, 0.f};
+        }
+    };
+    for (int st = 0; st < n_steps; st += 2) {
+        // two slabs per step: their products are independent chains, interleaved
+        const uint16_t* xa = s_x[st & 3] + j * ROW;
+        const uint16_t* xb = s_x[(st + 1) & 3] + j * ROW;   // (past the last slab: a copy of it, not used)
+        f32x4 pa[5], pb[5];
+#pragma unroll
+        for (int w = 0; w < 5; ++w) pa[w] = pb[w] = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int S = 0; S < NS; ++S) {
+            const F::type Xa = F::load(xa, S, g), Xb = F::load(xb, S, g);
+#pragma unroll
+            for (int w = 0; w < 5; ++w) {
+                pa[w] = F::mma(Wf[w][S], Xa, pa[w]);
+                pb[w] = F::mma(Wf[w][S], Xb, pb[w]);
+            }
+        }
+        finish_slab(st, pa);
+        if (st + 1 < n_steps) finish_slab(st + 1, pb);
+        __syncthreads();
+    }
 }
 
 // Plain version: block = one sorted slot, thread = one output channel; fp32 outputs.
