@@ -580,6 +580,7 @@ __global__ __launch_bounds__(64 * (C / 16 + 1)) void k_project_sh(E2fCellsView c
     constexpr int NS = C / F::KSTEP, NCT = C / 16, ROW = C + 8, NLD = C / 32;   // NLD 16-byte loads per lane and slab
     __shared__ __attribute__((aligned(16))) uint16_t s_x[4][16 * ROW];   // slab st in buffer st mod 4
     __shared__ __attribute__((aligned(8))) uint16_t s_t[NCT][256];
+    __shared__ int s_atom[SH_TPW * 16];   // fetching wave: atom of every row of the workgroup's tiles
     const int N = cv.N, n = (L + 1) * (L + 1), n_tiles = (N + 15) / 16, N4 = (N + 3) / 4 * 4;
     const int l = L - (int)blockIdx.x / n_groups, nl = 2 * l + 1;
     const int tile0 = ((int)blockIdx.x % n_groups) * tpw, nt = min(tpw, n_tiles - tile0);
@@ -588,16 +589,18 @@ __global__ __launch_bounds__(64 * (C / 16 + 1)) void k_project_sh(E2fCellsView c
 
     if (wave == NCT) {
         // ---- the fetching wave: lane = (atom a of the tile, quarter of its row)
+        // The atoms of the workgroup's tiles go through LDS: indexed by the local tile in registers they end up in
+        // scratch memory, whose loads share the memory counter with the slab loads and are the youngest of them, so
+        // that waiting for an atom index drained every slab in flight.
         const int a = lane >> 2, part = lane & 3;
-        int atom_of[SH_TPW];
-#pragma unroll
-        for (int x = 0; x < SH_TPW; ++x) atom_of[x] = cv.perm[min((tile0 + min(x, nt - 1)) * 16 + a, N - 1)];
+        for (int x = part; x < SH_TPW; x += 4) s_atom[x * 16 + a] = cv.perm[min((tile0 + min(x, nt - 1)) * 16 + a, N - 1)];
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
         auto issue = [&](int st, u32x4 (&r)[NLD]) {
             st = min(st, n_steps - 1);
             const int lt = st / nl, m = st - lt * nl;
-            int atom = atom_of[0];
-#pragma unroll
-            for (int x = 1; x < SH_TPW; ++x) atom = lt == x ? atom_of[x] : atom;
+            const int atom = s_atom[lt * 16 + a];
             const uint16_t* row = h + ((size_t)atom * n + l * l + m) * C + part * (C / 4);
 #pragma unroll
             for (int i = 0; i < NLD; ++i) r[i] = *reinterpret_cast<const u32x4*>(row + 8 * i);
