@@ -119,7 +119,7 @@ E2fAttnWs e2f_attn_ws_layout(const e2f_ctx* ctx, int32_t N, void* ws, int v_layo
         L.q16 = (uint16_t*)take((size_t)N * H * DKP * 2);
         L.k16 = (uint16_t*)take(N4 * H * DKP * 2);
         L.v4 = (uint16_t*)take(N4 / 4 * H * ctx->n * 64 * 2);
-        L.G = (float*)take((size_t)3 * E2F_MAX_N * E2F_MAX_N * 4);
+        L.G = (float*)take((size_t)(3 * E2F_MAX_N * E2F_MAX_N + 256) * 4);   // full form, then the packed non-zeros
         const size_t n_tiles = ((size_t)N + 15) / 16;
         L.lists_hdr = (int4*)take(n_tiles * sizeof(int4));
         L.lists_ent = (int*)take(n_tiles * E2F_TILE_LCAP * 4);

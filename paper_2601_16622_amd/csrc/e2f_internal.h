@@ -86,7 +86,7 @@ struct E2fAttnWs {
     uint16_t* q16;       // [N][H][DKP] binary16, q * tau * log2(e)
     uint16_t* k16;       // [4*ceil(N/4)][H][DKP] binary16
     uint16_t* v4;        // [ceil(N/4)][H][n][16 channels][4 slots] bf16
-    float* G;            // [3][25][25] axis operators of the degree-1 filter
+    float* G;            // [3][25][25] axis operators of the degree-1 filter, then their 216 pattern entries packed
     // candidate lists of the tile kernel, one per tile of 16 sorted slots (see TileParams)
     int4* lists_hdr;     // [ceil(N/16)]
     int* lists_ent;      // [ceil(N/16)][E2F_TILE_LCAP]
