@@ -140,6 +140,36 @@ def test_factorized_entry_point_sizes_and_limits(lib):
             B.e2f_destroy(ctx)
 
 
+def test_nonlinear_entry_point_sizes_and_limits(lib):
+    """The plain-layout attention workspace plus W_Q1 h as one more [N][n][C] array of the feature type; heads wider
+    than a wave are refused before anything is launched."""
+    ctx = B.e2f_create(4, 128, 8, 8, 1, 6.0, "bf16")
+    try:
+        s = [B.e2f_attn_nonlinear_workspace_bytes(ctx, N) for N in (10_000, 20_000)]
+        per_atom = 16 + 2 * 5 * 128 * 4 + 2 * 25 * 128 * 2
+        assert abs((s[1] - s[0]) - 10_000 * per_atom) <= 4096
+        assert B.e2f_attn_nonlinear_workspace_bytes(ctx, -1) == 0
+        cells = ctypes.c_void_p()
+        null = ctypes.c_void_p(0)
+        assert lib.e2f_build_cells(ctx, null, null, 0, 0, null, 0, ctypes.byref(cells), null) == 0
+        w = B.Weights(*([0] * 7))
+        assert lib.e2f_attn_forward_nonlinear(ctx, cells, null, null, null, 0, 0, ctypes.byref(w), null, null, 0, null) == 0
+        assert lib.e2f_attn_forward_nonlinear(ctx, cells, null, null, null, 5, 1, ctypes.byref(w), null, null, 0, null) == 1
+        assert lib.e2f_attn_forward_nonlinear(None, cells, null, null, null, 0, 0, ctypes.byref(w), null, null, 0, null) == 1
+        lib.e2f_cells_destroy(cells)
+    finally:
+        B.e2f_destroy(ctx)
+    for kw in (dict(C=128, H=1), dict(C=256, H=2)):
+        a = dict(L_max=2, C=64, H=4, B=8, lf=1)
+        a.update(kw)
+        ctx = B.e2f_create(a["L_max"], a["C"], a["H"], a["B"], a["lf"], 5.0, "f32")
+        try:
+            w = B.Weights(*([0] * 7))
+            assert lib.e2f_attn_forward_nonlinear(ctx, None, None, None, None, 0, 0, ctypes.byref(w), None, None, 0, None) == 2
+        finally:
+            B.e2f_destroy(ctx)
+
+
 def test_backward_entry_point_sizes_and_limits(lib):
     """Two [N][H] statistics arrays and the axis operators on top of the untiled attention workspace; the degree-1
     filter and power-of-two head widths up to 64 only; an empty problem is valid; null gradients are not."""
