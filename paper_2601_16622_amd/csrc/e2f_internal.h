@@ -176,12 +176,7 @@ e2f_status e2f_launch_backward(const e2f_ctx* ctx, const E2fCellsView& cv, const
                                float* grad_Wb, float* grad_w_path, float* grad_W, hipStream_t st);
 // cw[comp][t] = P coefficient with every path weight one.
 e2f_status e2f_launch_unit_cw(const e2f_ctx* ctx, float* cw, hipStream_t st);
-// lists_ready: e2f_launch_tile_lists has been enqueued before (on any stream that st has joined); otherwise the call
-// builds what it needs itself.
-e2f_status e2f_launch_tile(const e2f_ctx* ctx, const E2fCellsView& cv, const E2fAttnWs& ws, float* out, hipStream_t st,
-                           bool lists_ready = false);
-bool e2f_tile_uses_lists(const e2f_ctx* ctx, const E2fAttnWs& ws);
-e2f_status e2f_launch_tile_lists(const e2f_ctx* ctx, const E2fCellsView& cv, const E2fAttnWs& ws, hipStream_t st);
+e2f_status e2f_launch_tile(const e2f_ctx* ctx, const E2fCellsView& cv, const E2fAttnWs& ws, float* out, hipStream_t st);
 e2f_status e2f_launch_fused_mfma(const e2f_ctx* ctx, const E2fCellsView& cv, const e2f_weights* w, const E2fAttnWs& ws,
                                  float* out, hipStream_t st);
 e2f_status e2f_run_materialized(const e2f_ctx* ctx, const E2fCellsView& cv, const float* pos, const void* h,

@@ -784,21 +784,11 @@ static e2f_status launch_tile(const e2f_ctx* ctx, const E2fCellsView& cv, const 
     return E2F_OK;
 }
 
-// E2F_TILE_NO_LISTS (environment, read at every call): the attention kernel builds its lists per (tile, head).
-bool e2f_tile_uses_lists(const e2f_ctx* ctx, const E2fAttnWs& ws) {
-    return ctx->use_tile_attn && ws.lists_hdr && !getenv("E2F_TILE_NO_LISTS");
-}
-
-e2f_status e2f_launch_tile_lists(const e2f_ctx* ctx, const E2fCellsView& cv, const E2fAttnWs& ws, hipStream_t st) {
-    return launch_tile(ctx, cv, ws, nullptr, 1, st);
-}
-
-e2f_status e2f_launch_tile(const e2f_ctx* ctx, const E2fCellsView& cv, const E2fAttnWs& ws, float* out, hipStream_t st,
-                           bool lists_ready) {
-    if (!e2f_tile_uses_lists(ctx, ws)) return launch_tile(ctx, cv, ws, out, 0, st);
-    if (!lists_ready) {
-        const e2f_status rc = launch_tile(ctx, cv, ws, out, 1, st);
-        if (rc != E2F_OK) return rc;
-    }
+// E2F_TILE_NO_LISTS (environment, read at every call, for A/B timing and tests): the attention kernel builds its lists
+// per (tile, head) instead of reading the ones the list kernel leaves per tile.
+e2f_status e2f_launch_tile(const e2f_ctx* ctx, const E2fCellsView& cv, const E2fAttnWs& ws, float* out, hipStream_t st) {
+    if (!ws.lists_hdr || getenv("E2F_TILE_NO_LISTS")) return launch_tile(ctx, cv, ws, out, 0, st);
+    const e2f_status rc = launch_tile(ctx, cv, ws, out, 1, st);
+    if (rc != E2F_OK) return rc;
     return launch_tile(ctx, cv, ws, out, 2, st);
 }
