@@ -22,7 +22,10 @@ sys.path.insert(0, ROOT)
 
 # MI355X published peaks used for the roofline: fp32 vector 157.3 TFLOP/s
 # (256 CUs x 4 SIMDs x 16 lanes x 2 (packed) x 2 (FMA) x 2.4 GHz), bf16 dense MFMA 2.5 PFLOP/s, HBM 8 TB/s.
+# This build compiles with packed fp32 switched off, so what its vector code can reach is the plain-FMA figure.
 PEAK_ALU_TFLOPS = 157.3
+PEAK_ALU_PLAIN_FMA_TFLOPS = 78.6
+TOL = {"f32": 1e-4, "bf16": 2e-2}   # relative L2 against the fp64 oracle; one atom's own row: five times that
 
 
 def flop_model(cfg, N, E):
@@ -38,13 +41,42 @@ def flop_model(cfg, N, E):
     return f_node, f_edge, N * f_node + E * f_edge
 
 
+TRAFFIC_FILE = "profiles/fused_attention_scaling10k_pmc.txt"
+COUNTER_FILE = "profiles/tile_attention_scaling10k_counters.txt"
+
+
 def read_traffic():
-    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 counter summary, if any."""
-    path = os.path.join(ROOT, "profiles", "fused_attention_scaling10k_pmc.txt")
+    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 counter summary, if any (the counters
+    need a profiler run of their own; this run does not measure them)."""
+    path = os.path.join(ROOT, TRAFFIC_FILE)
     if not os.path.exists(path):
         return None
     m = re.search(r"traffic_bytes_per_launch:\s*([0-9.eE+]+)", open(path).read())
     return float(m.group(1)) if m else None
+
+
+def read_counters(kernel_pattern):
+    """SQ counters of one kernel from the committed rocprofv3 summary: {counter: mean per dispatch}."""
+    path = os.path.join(ROOT, COUNTER_FILE)
+    if not os.path.exists(path):
+        return {}
+    out, on = {}, False
+    for line in open(path):
+        if line.startswith("#"):
+            continue
+        if not line.startswith(" "):
+            on = kernel_pattern in line
+        elif on:
+            parts = line.split()
+            if parts[0].startswith("SQ_"):
+                out[parts[0]] = float(parts[1])
+    return out
+
+
+def atom_errors(got, ref):
+    d = np.linalg.norm((got - ref).reshape(ref.shape[0], -1), axis=1)
+    r = np.linalg.norm(ref.reshape(ref.shape[0], -1), axis=1)
+    return np.where(r > 0, d / np.where(r > 0, r, 1.0), d)
 
 
 def main():
@@ -94,13 +126,20 @@ def main():
         step()
     torch.cuda.synchronize()
     B.e2f_profile_begin(P.ctx, args.steps)
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]   # on the launch stream (current)
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    ev[0].record()
+    for i in range(args.steps):
         step()
+        ev[i + 1].record()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
+    timed_out = P.out.clone()   # the output of the timed region's last step: checked against the oracle below
+    per_call = B.e2f_profile_read(P.ctx, args.steps)
     stage_ms, calls = B.e2f_profile_end(P.ctx)
     ms_per_step = (t1 - t0) * 1e3 / args.steps
+    step_ms_median = float(np.median([ev[i].elapsed_time(ev[i + 1]) for i in range(args.steps)]))
+    attn_ms_median = float(np.median([c["attention"] for c in per_call])) if per_call else 0.0
     deg, _, _ = P.neighbors()
     E = int(deg.sum())
     f_node, f_edge, f_alg = flop_model(cfg, N, E)
@@ -117,9 +156,8 @@ def main():
 
     attn_ms = stage_ms["attention"]
     bf16 = cfg["dtype"] == "bf16"
-    pick = os.environ.get("E2F_ATTENTION")
-    mc_ok = bf16 and cfg["C"] // cfg["H"] == 16 and cfg["L"] >= 1 and pick != "valu"
-    if mc_ok and cfg["lf"] == 1 and cfg["C"] in (32, 64, 128) and pick != "pair":
+    mc_ok = bf16 and cfg["C"] // cfg["H"] == 16 and cfg["L"] >= 1
+    if mc_ok and cfg["lf"] == 1 and cfg["C"] in (32, 64, 128):
         kernel = "k_tile"
     elif mc_ok and cfg["lf"] in (1, 2) and cfg["H"] in (1, 2, 4, 8):
         kernel = "k_fused_mfma"
@@ -144,17 +182,38 @@ def main():
     achieved = work / (attn_ms * 1e-3) if attn_ms > 0 else 0.0
     roofline = {"bound": bound, "kernel": kernel, "achieved": round(achieved, 3), "peak": peak, "unit": unit,
                 "frac": round(achieved / peak, 4), "traffic": read_traffic(),
-                "kernel_ms": round(attn_ms, 4), "pairs_per_launch": E,
+                "traffic_source": TRAFFIC_FILE + " (rocprofv3 FETCH_SIZE + WRITE_SIZE runs; not measured in this run)",
+                "kernel_ms": round(attn_ms, 4), "kernel_ms_median": round(attn_ms_median, 4),
+                "achieved_is": "the method's per-pair work of the bound (model) over the measured time of the "
+                               "attention stage, not executed instructions",
+                "pairs_per_launch": E,
                 "algorithmic_flops_per_launch": E * f_edge,
                 "algorithmic_tflops": round(E * f_edge / (attn_ms * 1e-3) / 1e12, 3) if attn_ms > 0 else 0.0,
                 "work_of_bound_per_launch": work * (1e9 if bound == "hbm" else 1e12),
                 "roof_ms": {k: round(v[0] * 1e3, 4) for k, v in roofs.items()},
                 "stage_ms": {k: round(v, 4) for k, v in stage_ms.items()}}
+    if bound == "alu":
+        roofline["frac_of_plain_fma_peak"] = round(achieved / PEAK_ALU_PLAIN_FMA_TFLOPS, 4)
+    if kernel == "k_tile":
+        # what the kernel executes (matrix-core instructions over all candidate slots, masked ones included), from the
+        # committed counter summary of the same workload
+        sq = read_counters("k_tile<4, 4, false, 2>")
+        useful = E * cfg["H"] * (2 * (Lm + 1) * 16 + 3 * n * 16 * 2)
+        if sq.get("SQ_INSTS_MFMA"):
+            roofline["executed"] = {
+                "source": COUNTER_FILE,
+                "mfma_instructions": sq["SQ_INSTS_MFMA"], "mfma_flops_issued": sq["SQ_INSTS_MFMA"] * 16384,
+                "mfma_flops_useful": useful, "valu_instructions": sq.get("SQ_INSTS_VALU"),
+                # SIMD cycles the pipes were busy (the counter file's figures) over the SIMD cycles of this run's
+                # kernel time (1024 SIMDs at 2.4 GHz)
+                "valu_active_frac": round(sq.get("SQ_ACTIVE_INST_VALU", 0.0) * 4 / (attn_ms * 2.4e6 * 1024), 3),
+                "mfma_busy_frac": round(sq.get("SQ_VALU_MFMA_BUSY_CYCLES", 0.0) / (attn_ms * 2.4e6 * 1024), 3)}
 
     result = {
         "metric": "atoms/sec of fused equivariant attention forward (cells + projections + attention)",
         "value": round(N / (ms_per_step * 1e-3), 1), "unit": "atoms/s", "n_gpus": 1, "steps": args.steps,
-        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "ms_per_step_median_of_events": round(step_ms_median, 4), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16" if cfg["dtype"] == "bf16" else "f32", "data": "synthetic",
         "config": {"workload": f"{args.workload}: N={N} atoms, E={E} directed pairs, cutoff {cfg['cutoff']} A, "
                                f"L_max={cfg['L']}, C={cfg['C']}, H={cfg['H']}, B={cfg['B']}, lf={cfg['lf']}, "
@@ -277,14 +336,22 @@ def main():
             out_m = torch.empty_like(P.out)
             P.forward_materialized(out_m)
             torch.cuda.synchronize()
-            t0 = time.perf_counter()
             reps = 3
+            B.e2f_profile_begin(P.ctx, reps)
+            t0 = time.perf_counter()
             for _ in range(reps):
                 _, peak = P.forward_materialized(out_m)
             torch.cuda.synchronize()
             mat_ms = (time.perf_counter() - t0) * 1e3 / reps
-            result["materialized"] = {"ms": round(mat_ms, 3), "peak_bytes": int(peak) + P.activation_bytes(),
-                                      "fused_speedup": round(mat_ms / fwd_ms, 2),
+            # the baseline's kernels alone (HIP events inside the call: node-level kernels + edge kernels, without the
+            # allocation of the edge tensors and the host synchronisation between them), and the whole call
+            mat_stage, _ = B.e2f_profile_end(P.ctx)
+            mat_kernels = mat_stage["prepare"] + mat_stage["attention"]
+            result["materialized"] = {"ms_kernels": round(mat_kernels, 3), "ms_call": round(mat_ms, 3),
+                                      "ms_alloc_and_sync": round(mat_stage["project"], 3),
+                                      "peak_bytes": int(peak) + P.activation_bytes(),
+                                      "fused_speedup": round(mat_kernels / fwd_ms, 2),
+                                      "fused_speedup_is": "materialized kernels / fused forward (kernels only)",
                                       "memory_ratio": round((peak + P.activation_bytes()) / P.activation_bytes(), 1)}
         except B.E2fError as e:
             result["materialized"] = {"error": str(e)}
@@ -295,8 +362,19 @@ def main():
         n_t = min(N, 10_000)
         targets = None if n_t == N else np.random.default_rng(0).choice(N, n_t, replace=False).astype(np.int32)
         t0 = time.perf_counter()
-        oracle.attn_forward(cfg, wl["pos"], wl["h"], wl["seg"], wl["weights"], targets=targets, nbr=nbr)
+        ref = oracle.attn_forward(cfg, wl["pos"], wl["h"], wl["seg"], wl["weights"], targets=targets, nbr=nbr)
         dt = time.perf_counter() - t0
+        # the output of the timed region against what the oracle just computed, over the same targets
+        got = timed_out.cpu().numpy().astype(np.float64)
+        got = got if targets is None else got[targets]
+        per_atom = atom_errors(got, ref)
+        tol = TOL["bf16" if bf16 else "f32"]
+        parity = {"rel_l2": float(np.linalg.norm(got - ref) / np.linalg.norm(ref)),
+                  "max_atom_rel_err": float(per_atom.max()), "worst_atom": int(np.argmax(per_atom)),
+                  "targets": int(ref.shape[0]), "tolerance": tol, "atom_tolerance": 5 * tol,
+                  "finite": bool(np.isfinite(got).all())}
+        parity["ok"] = bool(parity["finite"] and parity["rel_l2"] <= tol and parity["max_atom_rel_err"] <= 5 * tol)
+        result["parity"] = parity
         result["cpu_baseline"] = {"value": round(n_t / dt, 1), "unit": "atoms/s", "cores": oracle.num_threads(),
                                   "kind": "oracle",
                                   "sample": f"{n_t} of {N} target atoms of the same workload, fp64 dense-CG route, "
@@ -391,6 +469,9 @@ def main():
         result["large_n"] = {"rows": rows, "bytes_per_atom": round(float(slope), 2), "intercept_bytes": round(float(icpt), 1),
                              "r2": round(float(r2), 8)}
     print(json.dumps(result))
+    if result.get("parity") is not None and not result["parity"]["ok"]:
+        print("bench.py: the timed output does not match the oracle: %r" % (result["parity"],), file=sys.stderr)
+        sys.exit(1)
 
 
 if __name__ == "__main__":

@@ -29,8 +29,8 @@
  * (a hipStream_t cast to void*; NULL is the default stream).  e2f_build_cells, e2f_attn_forward, its capped, table
  * and factorized forms, e2f_build_neighbor_table and e2f_attn_backward allocate no device memory and do not
  * synchronise with the host (e2f_build_cells_periodic enqueues one small host-to-device copy of the boxes from a
- * buffer the cells handle owns); e2f_attn_forward_materialized, e2f_count_neighbors and e2f_list_neighbors are
- * measurement/test entry points that may do both.
+ * buffer the cells handle owns); e2f_attn_forward_materialized and e2f_count_edges are measurement/test entry points
+ * that do both.
  * Errors are reported through the return code; no entry point aborts or throws.  Arguments are checked
  * before anything is launched.
  */
@@ -58,6 +58,25 @@ typedef enum {
 
 typedef enum { E2F_F32 = 0, E2F_BF16 = 1 } e2f_dtype;
 
+/*
+ * Which kernel runs the attention stage (Sec. 3.4, Algorithm 1).  All give the same result up to rounding.
+ *   AUTO  the fastest form that supports the configuration (the order below)
+ *   TILE  16 targets x 32 candidates on the matrix cores, degree-1 filter through its linear factorization
+ *         (Eq. e2former_final at l = 1); heads of 16 channels, lf = 1.  With bf16 features q and k are kept in
+ *         binary16 (values beyond +-65504 are clamped: use PAIR for features that are not normalised)
+ *   PAIR  one wave per target, the aligning rotation and P evaluated per pair (Sec. 3.3), operators applied on the
+ *         matrix cores; bf16 features, heads of 16 channels, lf = 1 or 2; q and k in fp32
+ *   VALU  the same per-pair form on the vector ALUs; every configuration
+ * A choice the configuration does not support makes e2f_create return E2F_ERR_UNSUPPORTED.
+ */
+typedef enum { E2F_ATTN_AUTO = 0, E2F_ATTN_TILE = 1, E2F_ATTN_PAIR = 2, E2F_ATTN_VALU = 3 } e2f_attn_kernel;
+
+/* e2f_config.flags (for A/B measurements and tests; 0 is the fast setting) */
+enum {
+    E2F_FLAG_TILE_LISTS_PER_HEAD = 1, /* tile kernel: build the candidate lists per (tile, head), not once per tile */
+    E2F_FLAG_PROJECT_PER_CHANNEL_TILE = 2 /* projections of the tile layout by the per-channel-tile kernel */
+};
+
 typedef struct {
     int32_t L_max;      /* highest degree, 0..4 */
     int32_t C;          /* channels per degree; multiple of 16; C <= 64 or C a multiple of 64, C <= 256 */
@@ -66,6 +85,8 @@ typedef struct {
     int32_t lf;         /* degree of the geometric filter R^(lf)(r_ij): 0, 1 or 2 (lf <= L_max unless 0) */
     float cutoff;       /* > 0 */
     int32_t feat_dtype; /* e2f_dtype of h and of the five projection matrices */
+    int32_t attention;  /* e2f_attn_kernel */
+    int32_t flags;      /* E2F_FLAG_* */
 } e2f_config;
 
 typedef struct {
@@ -127,6 +148,15 @@ e2f_status e2f_count_neighbors(e2f_ctx *ctx, const e2f_cells *cells, const float
                                void *hip_stream);
 e2f_status e2f_list_neighbors(e2f_ctx *ctx, const e2f_cells *cells, const float *pos, int32_t N, const int64_t *offsets,
                               int32_t *idx, void *hip_stream);
+/*
+ * Number of directed pairs E = sum_i |N(i)| (the edge count of the materialize-per-edge regime, App. A) together with
+ * the degrees: e2f_count_neighbors, then the sum on the host.
+ *   n_edges  host int64, written on E2F_OK
+ *   degree   device int32 [N], required (the call has no memory of its own to count into)
+ * Synchronises with the host (one device-to-host copy of the degrees).
+ */
+e2f_status e2f_count_edges(e2f_ctx *ctx, const e2f_cells *cells, const float *pos, int32_t N, int64_t *n_edges,
+                           int32_t *degree, void *hip_stream);
 
 /*
  * The fused forward pass (Sec. 3.4, Algorithm 1, with pair geometry, the edge-frame rotation and the EAAS
@@ -274,6 +304,11 @@ e2f_status e2f_eaas_tensor_product(e2f_ctx *ctx, const void *h, const float *r, 
  */
 enum { E2F_STAGE_PREPARE = 0, E2F_STAGE_PROJECT = 1, E2F_STAGE_ATTENTION = 2, E2F_N_STAGES = 3 };
 e2f_status e2f_profile_begin(e2f_ctx *ctx, int32_t max_calls);
+/* Per-call stage durations of the calls recorded so far: call_ms host float [capacity][E2F_N_STAGES] (milliseconds),
+ * *calls = rows written.  Waits for those calls' events; profiling stays on.  e2f_attn_forward_materialized records
+ * too: stage 0 its node-level kernels, stage 1 the host synchronisation and allocation in between, stage 2 its edge
+ * kernels. */
+e2f_status e2f_profile_read(e2f_ctx *ctx, float *call_ms, int32_t capacity, int32_t *calls);
 e2f_status e2f_profile_end(e2f_ctx *ctx, float *stage_ms, int32_t *calls);
 
 #ifdef __cplusplus

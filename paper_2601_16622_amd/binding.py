@@ -14,6 +14,8 @@ LIB_PATH = os.path.join(_HERE, "csrc", "libe2f.so")
 
 E2F_OK = 0
 E2F_F32, E2F_BF16 = 0, 1
+ATTENTION = {"auto": 0, "tile": 1, "pair": 2, "valu": 3}   # e2f_attn_kernel
+E2F_FLAG_TILE_LISTS_PER_HEAD, E2F_FLAG_PROJECT_PER_CHANNEL_TILE = 1, 2
 
 EXPORTS = ["e2f_status_string", "e2f_create", "e2f_destroy", "e2f_cells_workspace_bytes", "e2f_build_cells",
            "e2f_cells_destroy", "e2f_count_neighbors", "e2f_list_neighbors", "e2f_attn_workspace_bytes",
@@ -23,13 +25,14 @@ EXPORTS = ["e2f_status_string", "e2f_create", "e2f_destroy", "e2f_cells_workspac
            "e2f_attn_table_workspace_bytes", "e2f_attn_forward_table", "e2f_build_cells_periodic",
            "e2f_attn_backward_workspace_bytes", "e2f_attn_backward",
            "e2f_attn_backward_weights_workspace_bytes", "e2f_attn_nonlinear_workspace_bytes",
-           "e2f_attn_forward_nonlinear"]
+           "e2f_attn_forward_nonlinear", "e2f_count_edges", "e2f_profile_read"]
 STAGES = ("prepare", "project", "attention")
 
 
 class Config(ctypes.Structure):
     _fields_ = [("L_max", ctypes.c_int32), ("C", ctypes.c_int32), ("H", ctypes.c_int32), ("B", ctypes.c_int32),
-                ("lf", ctypes.c_int32), ("cutoff", ctypes.c_float), ("feat_dtype", ctypes.c_int32)]
+                ("lf", ctypes.c_int32), ("cutoff", ctypes.c_float), ("feat_dtype", ctypes.c_int32),
+                ("attention", ctypes.c_int32), ("flags", ctypes.c_int32)]
 
 
 class Weights(ctypes.Structure):
@@ -72,6 +75,10 @@ def load():
     L.e2f_count_neighbors.restype = ctypes.c_int
     L.e2f_list_neighbors.argtypes = [vp, vp, vp, i32, vp, vp, vp]
     L.e2f_list_neighbors.restype = ctypes.c_int
+    L.e2f_count_edges.argtypes = [vp, vp, vp, i32, ctypes.POINTER(ctypes.c_int64), vp, vp]
+    L.e2f_count_edges.restype = ctypes.c_int
+    L.e2f_profile_read.argtypes = [vp, ctypes.POINTER(ctypes.c_float), i32, ctypes.POINTER(i32)]
+    L.e2f_profile_read.restype = ctypes.c_int
     L.e2f_attn_workspace_bytes.argtypes = [vp, i32]
     L.e2f_attn_workspace_bytes.restype = sz
     L.e2f_attn_forward.argtypes = [vp, vp, vp, vp, vp, i32, i32, ctypes.POINTER(Weights), vp, vp, sz, vp]
@@ -132,8 +139,9 @@ def _ptr(t):
     return ctypes.c_void_p(t.data_ptr() if t is not None and t.numel() > 0 else 0)
 
 
-def e2f_create(L_max, C, H, B, lf, cutoff, feat_dtype):
-    cfg = Config(L_max, C, H, B, lf, float(cutoff), E2F_BF16 if feat_dtype in ("bf16", E2F_BF16) else E2F_F32)
+def e2f_create(L_max, C, H, B, lf, cutoff, feat_dtype, attention="auto", flags=0):
+    cfg = Config(L_max, C, H, B, lf, float(cutoff), E2F_BF16 if feat_dtype in ("bf16", E2F_BF16) else E2F_F32,
+                 ATTENTION.get(attention, attention), int(flags))
     ctx = ctypes.c_void_p()
     _check(load().e2f_create(ctypes.byref(cfg), ctypes.byref(ctx)), "e2f_create")
     return ctx
@@ -176,6 +184,14 @@ def e2f_cells_destroy(cells):
 def e2f_count_neighbors(ctx, cells, pos, degree):
     _check(load().e2f_count_neighbors(ctx, cells, _ptr(pos), pos.shape[0], _ptr(degree), _stream()),
            "e2f_count_neighbors")
+
+
+def e2f_count_edges(ctx, cells, pos, degree):
+    """Returns E; degree (device int32 [N]) receives the neighbour counts."""
+    E = ctypes.c_int64(0)
+    _check(load().e2f_count_edges(ctx, cells, _ptr(pos), pos.shape[0], ctypes.byref(E), _ptr(degree), _stream()),
+           "e2f_count_edges")
+    return E.value
 
 
 def e2f_list_neighbors(ctx, cells, pos, offsets, idx):
@@ -293,6 +309,14 @@ def e2f_profile_begin(ctx, max_calls):
     _check(load().e2f_profile_begin(ctx, max_calls), "e2f_profile_begin")
 
 
+def e2f_profile_read(ctx, capacity):
+    """Per-call stage times so far: list of {stage: ms}."""
+    buf = (ctypes.c_float * (capacity * len(STAGES)))()
+    calls = ctypes.c_int32(0)
+    _check(load().e2f_profile_read(ctx, buf, capacity, ctypes.byref(calls)), "e2f_profile_read")
+    return [{k: float(buf[c * len(STAGES) + i]) for i, k in enumerate(STAGES)} for c in range(calls.value)]
+
+
 def e2f_profile_end(ctx):
     """Returns ({stage: mean ms}, calls)."""
     ms = (ctypes.c_float * len(STAGES))()
@@ -304,7 +328,7 @@ def e2f_profile_end(ctx):
 class Problem:
     """Device-resident copy of one workload (see workloads.py) plus the library objects needed to run it."""
 
-    def __init__(self, wl, device="cuda:0"):
+    def __init__(self, wl, device="cuda:0", attention="auto", flags=0):
         import torch
         cfg = wl["cfg"]
         self.cfg = cfg
@@ -320,7 +344,8 @@ class Problem:
         for k, v in wl["weights"].items():
             t = torch.from_numpy(np.ascontiguousarray(v, dtype=np.float32)).to(self.device)
             self.weights[k] = (t.to(fdt) if k.startswith("W") and k != "Wb" else t).contiguous()
-        self.ctx = e2f_create(cfg["L"], cfg["C"], cfg["H"], cfg["B"], cfg["lf"], cfg["cutoff"], cfg["dtype"])
+        self.ctx = e2f_create(cfg["L"], cfg["C"], cfg["H"], cfg["B"], cfg["lf"], cfg["cutoff"], cfg["dtype"],
+                              attention, flags)
         self.cells_ws = torch.empty(max(e2f_cells_workspace_bytes(self.ctx, self.N, self.S), 256), dtype=torch.uint8,
                                     device=self.device)
         self.attn_ws = torch.empty(max(e2f_attn_workspace_bytes(self.ctx, self.N), 256), dtype=torch.uint8,

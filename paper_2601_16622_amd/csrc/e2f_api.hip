@@ -160,6 +160,8 @@ e2f_status e2f_create(const e2f_config* cfg, e2f_ctx** ctx_out) {
     if (!(cfg->cutoff > 0.0f) || !isfinite(cfg->cutoff)) return E2F_ERR_INVALID_ARG;
     if (cfg->C % cfg->H != 0) return E2F_ERR_INVALID_ARG;
     if (cfg->feat_dtype != E2F_F32 && cfg->feat_dtype != E2F_BF16) return E2F_ERR_INVALID_ARG;
+    if (cfg->attention < E2F_ATTN_AUTO || cfg->attention > E2F_ATTN_VALU) return E2F_ERR_INVALID_ARG;
+    if (cfg->flags & ~(E2F_FLAG_TILE_LISTS_PER_HEAD | E2F_FLAG_PROJECT_PER_CHANNEL_TILE)) return E2F_ERR_INVALID_ARG;
     if (cfg->lf > cfg->L_max && cfg->lf != 0) return E2F_ERR_INVALID_ARG;
     if (cfg->L_max > E2F_MAX_L || cfg->lf > E2F_MAX_LF || cfg->H > E2F_MAX_H) return E2F_ERR_UNSUPPORTED;
     // channel tiling of the kernels: 16-wide MFMA tiles (32-deep for bf16), lanes over channels in the fused kernel
@@ -196,12 +198,15 @@ e2f_status e2f_create(const e2f_config* cfg, e2f_ctx** ctx_out) {
                 c->coefP[comp][kk] = (float)((kk % 2) ? (m > 0 ? cg : (m < 0 ? -cg : 0.0)) : cg);
             }
         }
-    // Attention kernel: the tile kernel where it applies, else the per-pair matrix-core kernel, else the ALU kernel.
-    // E2F_ATTENTION=valu | pair | tile in the environment narrows the choice (for A/B timing).
-    const char* pick = getenv("E2F_ATTENTION");
-    const bool only_valu = pick && strcmp(pick, "valu") == 0, only_pair = pick && strcmp(pick, "pair") == 0;
-    c->use_tile_attn = e2f_tile_supported(c) && !only_valu && !only_pair;
-    c->use_mfma_attn = !c->use_tile_attn && e2f_fused_mfma_supported(c) && !only_valu;
+    // Attention kernel: the tile kernel where it applies, else the per-pair matrix-core kernel, else the ALU kernel,
+    // unless the configuration names one.
+    const int pick = cfg->attention;
+    c->use_tile_attn = e2f_tile_supported(c) && (pick == E2F_ATTN_AUTO || pick == E2F_ATTN_TILE);
+    c->use_mfma_attn = !c->use_tile_attn && e2f_fused_mfma_supported(c) && (pick == E2F_ATTN_AUTO || pick == E2F_ATTN_PAIR);
+    if ((pick == E2F_ATTN_TILE && !c->use_tile_attn) || (pick == E2F_ATTN_PAIR && !c->use_mfma_attn)) {
+        delete c;
+        return E2F_ERR_UNSUPPORTED;
+    }
     c->prof_events = nullptr;
     c->prof_capacity = 0;
     c->prof_calls = 0;
@@ -232,6 +237,18 @@ e2f_status e2f_profile_begin(e2f_ctx* ctx, int32_t max_calls) {
     ctx->prof_events = ev;
     ctx->prof_capacity = max_calls;
     ctx->prof_calls = 0;
+    return E2F_OK;
+}
+
+e2f_status e2f_profile_read(e2f_ctx* ctx, float* call_ms, int32_t capacity, int32_t* calls) {
+    if (!ctx || !call_ms || !calls || capacity < 0 || !ctx->prof_events) return E2F_ERR_INVALID_ARG;
+    const int nc = ctx->prof_calls < capacity ? ctx->prof_calls : capacity;
+    for (int c = 0; c < nc; ++c) {
+        hipEvent_t* ev = ctx->prof_events + c * (E2F_N_STAGES + 1);
+        E2F_HIP_CHECK(hipEventSynchronize(ev[E2F_N_STAGES]));
+        for (int s = 0; s < E2F_N_STAGES; ++s) E2F_HIP_CHECK(hipEventElapsedTime(&call_ms[c * E2F_N_STAGES + s], ev[s], ev[s + 1]));
+    }
+    *calls = nc;
     return E2F_OK;
 }
 
@@ -327,6 +344,27 @@ e2f_status e2f_count_neighbors(e2f_ctx* ctx, const e2f_cells* cells, const float
     if (!ctx || !cells || N != cells->view.N) return E2F_ERR_INVALID_ARG;
     if (N > 0 && (!pos || !degree || pos != cells->pos)) return E2F_ERR_INVALID_ARG;
     return e2f_launch_count_neighbors(ctx, cells->view, pos, degree, static_cast<hipStream_t>(hip_stream));
+}
+
+e2f_status e2f_count_edges(e2f_ctx* ctx, const e2f_cells* cells, const float* pos, int32_t N, int64_t* n_edges,
+                           int32_t* degree, void* hip_stream) {
+    if (!n_edges) return E2F_ERR_INVALID_ARG;
+    *n_edges = 0;
+    e2f_status rc = e2f_count_neighbors(ctx, cells, pos, N, degree, hip_stream);
+    if (rc != E2F_OK || N == 0) return rc;
+    int32_t* host = new (std::nothrow) int32_t[(size_t)N];
+    if (!host) return E2F_ERR_OOM;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    if (hipMemcpyAsync(host, degree, (size_t)N * 4, hipMemcpyDeviceToHost, st) != hipSuccess ||
+        hipStreamSynchronize(st) != hipSuccess) {
+        delete[] host;
+        return E2F_ERR_HIP;
+    }
+    int64_t sum = 0;
+    for (int32_t i = 0; i < N; ++i) sum += host[i];
+    delete[] host;
+    *n_edges = sum;
+    return E2F_OK;
 }
 
 e2f_status e2f_list_neighbors(e2f_ctx* ctx, const e2f_cells* cells, const float* pos, int32_t N, const int64_t* offsets,
@@ -570,8 +608,12 @@ e2f_status e2f_attn_forward_materialized(e2f_ctx* ctx, const e2f_cells* cells, c
     if (rc != E2F_OK || N == 0) return rc;
     if (cells->view.periodic) return E2F_ERR_UNSUPPORTED;   // the edge list carries no images
     const E2fAttnWs L = e2f_attn_ws_layout(ctx, N, ws, e2f_v_layout(ctx));
-    return e2f_run_materialized(ctx, cells->view, pos, h, w, L, out, static_cast<hipStream_t>(hip_stream), edges_out,
-                                peak_bytes_out);
+    hipEvent_t* ev = (ctx->prof_events && ctx->prof_calls < ctx->prof_capacity)
+                         ? ctx->prof_events + ctx->prof_calls * (E2F_N_STAGES + 1) : nullptr;
+    rc = e2f_run_materialized(ctx, cells->view, pos, h, w, L, out, static_cast<hipStream_t>(hip_stream), edges_out,
+                              peak_bytes_out, ev);
+    if (rc == E2F_OK && ev) ctx->prof_calls++;
+    return rc;
 }
 
 }  // extern "C"

@@ -22,8 +22,6 @@
 // pairs compute the fp32 Wigner blocks, radial bias and gate into LDS (uniform code, no divergence).  Every
 // lane then assembles its own A-operand fragments of D1 and M for one pair at a time from those blocks, using
 // per-lane tables of LDS offsets and P coefficients built once at kernel start.
-#include <stdio.h>
-#include <stdlib.h>
 
 #include <limits.h>
 
@@ -50,7 +48,6 @@ struct MfmaParams {
     float* out;
     int B, lf;
     float tau, rc2, cutoff, rbf_step, rbf_gamma;
-    unsigned long long* dbg;
 };
 
 constexpr int SC = 32;     // pairs per super-chunk
@@ -97,13 +94,6 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) void
     __shared__ float s_s[SC * H];
     __shared__ float s_cw[E2F_MAX_N * E2F_NP];
 
-#ifdef E2F_TIMING
-    unsigned long long tacc[6] = {0, 0, 0, 0, 0, 0};
-    unsigned long long tprev = __builtin_amdgcn_s_memtime();
-#define TICK(k) { unsigned long long now_ = __builtin_amdgcn_s_memtime(); tacc[k] += now_ - tprev; tprev = now_; }
-#else
-#define TICK(k)
-#endif
     const int t = e2f::xcd_remap(blockIdx.x, P.cv.N);
     if (t < 0) return;  // padding block of the XCD map (whole wave)
     const int lane = threadIdx.x, i = lane & 15, g = lane >> 4;
@@ -225,7 +215,6 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) void
         }
         const bool rows_done = cbase >= n_cand;
         __syncthreads();
-        TICK(0)
         for (int p0 = 0; p0 < cnt; p0 += SC) {
             const int np = min(SC, cnt - p0);
             // ---- lanes = pairs: Wigner blocks (fp32), radial bias, gate
@@ -249,7 +238,6 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) void
                 s_wgt[lane] = e2f::radial_gate(d, P.cutoff) * (P.lf == 2 ? d * d : d);
             }
             __syncthreads();
-            TICK(1)
             // ---- pass 1: logits of the super-chunk (Eq. kernel_score) and their maximum per head
             float cmax = -INFINITY;
             // the query row is re-read per super-chunk (cache hit) instead of living in registers across pass 2
@@ -285,7 +273,6 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) void
                     }
                 }
             }
-            TICK(2)
             // ---- one rescale of (mu, z, A) per super-chunk
             const float mu_new = fmaxf(mu, cmax);
             const float scale = __expf(mu - mu_new);
@@ -298,7 +285,6 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) void
                 for (int T = 0; T < NT; ++T) acc[h][T] *= sc;
             }
             __syncthreads();
-            TICK(3)
             // ---- pass 2: per pair, assemble the fragments, then 4 MFMAs per head
             // Value rows live in one register set: as soon as head h of pair p has gone through its MFMAs, its
             // registers are refilled with head h of pair p+1, so every load has almost a whole pair of work to land.
@@ -392,7 +378,6 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) void
                 }
             }
             __syncthreads();
-            TICK(4)
         }
         if (rows_done) break;
     }
@@ -411,11 +396,6 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) void
                 if (tile_row_to_lm(T0 + T, 4 * g + r, L, l, m)) o[(l * l + l + m) * C + 16 * h + i] = acc[h][T][r] * zi;
             }
     }
-#ifdef E2F_TIMING
-    TICK(5)
-    if (lane == 0 && P.dbg)
-        for (int k = 0; k < 6; ++k) atomicAdd(P.dbg + k, tacc[k]);
-#endif
 }
 
 template <int L>
@@ -447,13 +427,6 @@ e2f_status e2f_launch_fused_mfma(const e2f_ctx* ctx, const E2fCellsView& cv, con
     P.cap_d2 = ws.cap_d2; P.cap_idx = ws.cap_idx;
     P.B = ctx->cfg.B;
     P.lf = ctx->cfg.lf;
-    P.dbg = nullptr;
-#ifdef E2F_TIMING
-    static unsigned long long* dbg = nullptr;
-    if (!dbg) { (void)hipMalloc((void**)&dbg, 64); (void)hipMemset(dbg, 0, 64); }
-    P.dbg = dbg;
-    { unsigned long long hst[6]; (void)hipMemcpy(hst, dbg, 48, hipMemcpyDeviceToHost); if (getenv("E2F_TIMING_PRINT")) fprintf(stderr, "sections(cum) fill %llu geom %llu pass1 %llu rescale %llu pass2 %llu epi %llu\n", hst[0], hst[1], hst[2], hst[3], hst[4], hst[5]); }
-#endif
     P.tau = ctx->tau; P.rc2 = ctx->rc2; P.cutoff = ctx->cfg.cutoff; P.rbf_step = ctx->rbf_step; P.rbf_gamma = ctx->rbf_gamma;
     bool ok = false;
     switch (ctx->cfg.L_max) {

@@ -181,4 +181,4 @@ e2f_status e2f_launch_fused_mfma(const e2f_ctx* ctx, const E2fCellsView& cv, con
                                  float* out, hipStream_t st);
 e2f_status e2f_run_materialized(const e2f_ctx* ctx, const E2fCellsView& cv, const float* pos, const void* h,
                                 const e2f_weights* w, const E2fAttnWs& ws, float* out, hipStream_t st,
-                                size_t* edges_out, size_t* peak_bytes_out);
+                                size_t* edges_out, size_t* peak_bytes_out, hipEvent_t* ev);

@@ -170,7 +170,7 @@ __global__ void k_edge_reduce(E2fCellsView cv, const int64_t* __restrict__ eoff,
 
 template <int L, int LF>
 e2f_status run(const e2f_ctx* ctx, const E2fCellsView& cv, const void* h, const e2f_weights* w, const E2fAttnWs& ws,
-               float* out, hipStream_t st, size_t* edges_out, size_t* peak_bytes_out) {
+               float* out, hipStream_t st, size_t* edges_out, size_t* peak_bytes_out, hipEvent_t* ev) {
     const int N = cv.N, C = ctx->cfg.C, H = ctx->cfg.H, n = ctx->n;
     constexpr int DS = e2f::d_offset(L + 1), DSP = (DS + 3) & ~3;
     const int row = (L + 1) * C;
@@ -186,10 +186,14 @@ e2f_status run(const e2f_ctx* ctx, const E2fCellsView& cv, const void* h, const 
     int32_t* degree = (int32_t*)p; p += e2f_align_up((size_t)N * 4);
     int64_t* eoff = (int64_t*)p;
 
+    // with profiling on: stage 0 = node-level kernels, stage 1 = host synchronisation and allocation of the edge
+    // tensors, stage 2 = the edge kernels
+    if (ev) (void)hipEventRecord(ev[0], st);
     e2f_status rc = e2f_launch_project_simple(ctx, cv, h, w, q, k, v, st);
     if (rc != E2F_OK) { (void)hipFree(node); return rc; }
     k_edge_walk<<<N, 64, 0, st>>>(cv, ws.spos, ctx->rc2, degree, nullptr, nullptr, nullptr);
     k_scan_degree<<<1, 1024, 0, st>>>(degree, N, eoff);
+    if (ev) (void)hipEventRecord(ev[1], st);
     int64_t E = 0;
     if (hipMemcpyAsync(&E, eoff + N, sizeof(int64_t), hipMemcpyDeviceToHost, st) != hipSuccess ||
         hipStreamSynchronize(st) != hipSuccess) {
@@ -222,6 +226,7 @@ e2f_status run(const e2f_ctx* ctx, const E2fCellsView& cv, const void* h, const 
     eb.msg = (float*)p;
 
     const int tb = 256;
+    if (ev) (void)hipEventRecord(ev[2], st);
     if (E > 0) {
         k_edge_walk<<<N, 64, 0, st>>>(cv, ws.spos, ctx->rc2, nullptr, eoff, eb.src, eb.dst);
         k_edge_geometry<L, LF><<<(unsigned)((E + tb - 1) / tb), tb, 0, st>>>(
@@ -234,6 +239,7 @@ e2f_status run(const e2f_ctx* ctx, const E2fCellsView& cv, const void* h, const 
         k_edge_message<L, LF><<<(unsigned)((E * C + tb - 1) / tb), tb, 0, st>>>(E, eb.dst, v, eb.D, ws.cw, C, eb.msg);
     }
     k_edge_reduce<<<N, 256, 0, st>>>(cv, eoff, eb.alpha, eb.msg, n, C, H, ctx->Ch, out);
+    if (ev) (void)hipEventRecord(ev[3], st);
     hipError_t err = hipGetLastError();
     if (err == hipSuccess) err = hipStreamSynchronize(st);
     (void)hipFree(edge);
@@ -243,11 +249,11 @@ e2f_status run(const e2f_ctx* ctx, const E2fCellsView& cv, const void* h, const 
 
 template <int L>
 e2f_status run_lf(const e2f_ctx* ctx, const E2fCellsView& cv, const void* h, const e2f_weights* w, const E2fAttnWs& ws,
-                  float* out, hipStream_t st, size_t* edges_out, size_t* peak_bytes_out) {
+                  float* out, hipStream_t st, size_t* edges_out, size_t* peak_bytes_out, hipEvent_t* ev) {
     switch (ctx->cfg.lf) {
-        case 0: return run<L, 0>(ctx, cv, h, w, ws, out, st, edges_out, peak_bytes_out);
-        case 1: return run<L, 1>(ctx, cv, h, w, ws, out, st, edges_out, peak_bytes_out);
-        case 2: return run<L, 2>(ctx, cv, h, w, ws, out, st, edges_out, peak_bytes_out);
+        case 0: return run<L, 0>(ctx, cv, h, w, ws, out, st, edges_out, peak_bytes_out, ev);
+        case 1: return run<L, 1>(ctx, cv, h, w, ws, out, st, edges_out, peak_bytes_out, ev);
+        case 2: return run<L, 2>(ctx, cv, h, w, ws, out, st, edges_out, peak_bytes_out, ev);
     }
     return E2F_ERR_UNSUPPORTED;
 }
@@ -256,18 +262,18 @@ e2f_status run_lf(const e2f_ctx* ctx, const E2fCellsView& cv, const void* h, con
 
 e2f_status e2f_run_materialized(const e2f_ctx* ctx, const E2fCellsView& cv, const float* pos, const void* h,
                                 const e2f_weights* w, const E2fAttnWs& ws, float* out, hipStream_t st,
-                                size_t* edges_out, size_t* peak_bytes_out) {
+                                size_t* edges_out, size_t* peak_bytes_out, hipEvent_t* ev) {
     if (edges_out) *edges_out = 0;
     if (peak_bytes_out) *peak_bytes_out = 0;
     if (cv.N == 0) return E2F_OK;
     e2f_status rc = e2f_launch_prepare(ctx, cv, pos, w, ws, st);
     if (rc != E2F_OK) return rc;
     switch (ctx->cfg.L_max) {
-        case 0: return run_lf<0>(ctx, cv, h, w, ws, out, st, edges_out, peak_bytes_out);
-        case 1: return run_lf<1>(ctx, cv, h, w, ws, out, st, edges_out, peak_bytes_out);
-        case 2: return run_lf<2>(ctx, cv, h, w, ws, out, st, edges_out, peak_bytes_out);
-        case 3: return run_lf<3>(ctx, cv, h, w, ws, out, st, edges_out, peak_bytes_out);
-        case 4: return run_lf<4>(ctx, cv, h, w, ws, out, st, edges_out, peak_bytes_out);
+        case 0: return run_lf<0>(ctx, cv, h, w, ws, out, st, edges_out, peak_bytes_out, ev);
+        case 1: return run_lf<1>(ctx, cv, h, w, ws, out, st, edges_out, peak_bytes_out, ev);
+        case 2: return run_lf<2>(ctx, cv, h, w, ws, out, st, edges_out, peak_bytes_out, ev);
+        case 3: return run_lf<3>(ctx, cv, h, w, ws, out, st, edges_out, peak_bytes_out, ev);
+        case 4: return run_lf<4>(ctx, cv, h, w, ws, out, st, edges_out, peak_bytes_out, ev);
     }
     return E2F_ERR_UNSUPPORTED;
 }

@@ -14,6 +14,12 @@
 
 namespace {
 
+// binary16 keeps |x| <= 65504: the invariants of Eq. qk are quadratic in the features, so un-normalised inputs can leave
+// that range; they saturate instead of becoming infinite (an infinite logit would turn the softmax into NaN).  NaN stays.
+__device__ __forceinline__ _Float16 to_f16_sat(float x) {
+    return (_Float16)__builtin_amdgcn_fmed3f(x, -65504.0f, 65504.0f);
+}
+
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
@@ -528,8 +534,8 @@ __global__ __launch_bounds__(64 * WG_WAVES) void k_project_wg(E2fCellsView cv, c
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
                 const bool real = a < n_atoms && f0 + i < DK;
-                qv[i] = (_Float16)(real ? s_q[a * (E2F_MAX_L + 1) * 16 + f0 + i] * go.qscale : 0.0f);
-                kv[i] = (_Float16)(real ? s_k[a * (E2F_MAX_L + 1) * 16 + f0 + i] : 0.0f);
+                qv[i] = to_f16_sat(real ? s_q[a * (E2F_MAX_L + 1) * 16 + f0 + i] * go.qscale : 0.0f);
+                kv[i] = to_f16_sat(real ? s_k[a * (E2F_MAX_L + 1) * 16 + f0 + i] : 0.0f);
             }
             const size_t dst = (slot * NCT + ct) * go.DKP + f0;
             *reinterpret_cast<h16x8*>(go.k16 + dst) = kv;
@@ -688,8 +694,8 @@ __global__ __launch_bounds__(64 * (C / 16 + 1)) void k_project_sh(E2fCellsView c
             h16x4 qv, kv;
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
-                qv[r] = (_Float16)(qacc[r] * go.qscale);
-                kv[r] = (_Float16)(slot < N ? kacc[r] : 0.0f);
+                qv[r] = to_f16_sat(qacc[r] * go.qscale);
+                kv[r] = to_f16_sat(slot < N ? kacc[r] : 0.0f);
             }
             const size_t dst = ((size_t)slot * NCT + ct) * go.DKP + l * 16 + 4 * g;
             if (slot < N) *reinterpret_cast<h16x4*>(go.q16 + dst) = qv;
@@ -838,7 +844,7 @@ bool launch_wg(const e2f_ctx* ctx, const E2fCellsView& cv, const void* h, const 
         go.q16 = ws.q16; go.k16 = ws.k16; go.v4 = ws.v4;
         go.qscale = ctx->tau * 1.44269504088896341f;   // logits in base-2 units
         go.DKP = ((L + 1) * 16 + 31) / 32 * 32;
-        static const bool use_sh = [] { const char* e = getenv("E2F_PROJECT"); return !(e && strcmp(e, "wg") == 0); }();
+        const bool use_sh = !(ctx->cfg.flags & E2F_FLAG_PROJECT_PER_CHANNEL_TILE);
         if (v_layout == 2 && use_sh) {
             // more tiles per workgroup fetch the weights less often; keep a few workgroups per CU
             int tpw = SH_TPW;

@@ -19,8 +19,6 @@
 // aggregation the same registers are W[target i][k = 8g + r'] with k -> (first half, row 4g+r') for r' < 4 and
 // (second half, row 4g+r'-4) otherwise, and the V operand is loaded in that same order of k.
 #include <limits.h>
-#include <stdio.h>
-#include <stdlib.h>
 
 #include <type_traits>
 
@@ -64,16 +62,7 @@ struct TileParams {
     float* G_out;
     int C, H, B, n_tiles;
     float rc2, cutoff, rbf_step, rbf_gamma;
-#ifdef E2F_TIMING
-    unsigned long long* dbg;
-#endif
 };
-
-#ifdef E2F_TIMING
-#define TICK(k) { unsigned long long now_ = __builtin_amdgcn_s_memtime(); tacc[k] += now_ - tprev; tprev = now_; }
-#else
-#define TICK(k)
-#endif
 
 __device__ __forceinline__ float read_lane(float x, int src_lane) {
     return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, x), src_lane));
@@ -206,10 +195,6 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(E2F_TIL
     const int nxw = n / NW + (wave < n % NW ? 1 : 0);
     const int x0 = wave * (n / NW) + min(wave, n % NW);
     const bool last_x = nxw == NX;   // whether this wave uses accumulator slot NX - 1
-#ifdef E2F_TIMING
-    unsigned long long tacc[6] = {0, 0, 0, 0, 0, 0};
-    unsigned long long tprev = __builtin_amdgcn_s_memtime();
-#endif
     const int N = P.cv.N, H = P.H;
     const int t0 = tile * 16, nt = min(16, N - t0);
     const int tslot = min(t0 + tn, N - 1);
@@ -266,7 +251,6 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(E2F_TIL
         for (int x = 0; x < NX; ++x) acc[mu][x] = (f32x4){0.f, 0.f, 0.f, 0.f};
     float m_ref = -INFINITY, z = 0.0f;
 
-    TICK(0)
     int a = 0;
     while (a < nt) {
         // ---- a pass: the targets [a, b) of the tile that share a row of cells (same segment, same y and z cell)
@@ -466,11 +450,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(E2F_TIL
             for (int i = threadIdx.x; i < PADE; i += 64 * NW) s_ent[cnt + i] = 0;
             for (int i = threadIdx.x; i < PADE * 4; i += 64 * NW) s_pos[cnt * 4 + i] = tp;
             __syncthreads();
-            TICK(1)
             const int nch = (cnt + 7) >> 3, ngr = (nch + NW - 1) / NW;
-#ifdef E2F_TIMING
-            if (threadIdx.x == 0 && P.dbg) { atomicAdd(P.dbg + 6, (unsigned long long)nch); atomicAdd(P.dbg + 7, 1ull); }
-#endif
             if (ngr > 0) {
                 auto load_K = [&](int c, f16x8 (&kf)[2][KS]) {
 #pragma unroll
@@ -494,7 +474,6 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(E2F_TIL
 #pragma unroll
                 for (int x = 0; x < NX; ++x)
                     if (x < NX - 1 || last_x) load_V(0, x, va[x], vb[x]);
-                TICK(2)
                 for (int G = 0; G < ngr; ++G) {
                     // ---- logits, pair geometry and cutoff mask of this wave's chunk
                     const int cm = NW * G + wave;
@@ -616,7 +595,6 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(E2F_TIL
                     }
                 }
             }
-            TICK(3)
         }
         a = b;
         ++pidx;
@@ -663,7 +641,6 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(E2F_TIL
                         pr[i] += s_G[AXIS_INDEX.v[mu][WV + NW * i][xi]] * s_po[xi * 64 + lane];
             }
         }
-        TICK(4)
         f32x4 inv;
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
@@ -704,10 +681,6 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(E2F_TIL
         if (wave_u == 6) finish(std::integral_constant<int, 6>{});
         if (wave_u == 7) finish(std::integral_constant<int, 7>{});
     }
-#ifdef E2F_TIMING
-    if (lane == 0 && P.dbg)
-        for (int k = 0; k < 6; ++k) atomicAdd(P.dbg + k, tacc[k]);
-#endif
 }
 
 // what: 1 the list kernel (with the axis operators), 2 the attention kernel reading the lists, 0 the attention kernel
@@ -767,12 +740,6 @@ static e2f_status launch_tile(const e2f_ctx* ctx, const E2fCellsView& cv, const 
     P.G_out = ws.G;
     P.C = ctx->cfg.C; P.H = ctx->cfg.H; P.B = ctx->cfg.B; P.n_tiles = (cv.N + 15) / 16;
     P.rc2 = ctx->rc2; P.cutoff = ctx->cfg.cutoff; P.rbf_step = ctx->rbf_step; P.rbf_gamma = ctx->rbf_gamma;
-#ifdef E2F_TIMING
-    static unsigned long long* dbg = nullptr;
-    if (!dbg) { (void)hipMalloc((void**)&dbg, 64); (void)hipMemset(dbg, 0, 64); }
-    P.dbg = dbg;
-    { unsigned long long hst[8]; (void)hipMemcpy(hst, dbg, 64, hipMemcpyDeviceToHost); if (getenv("E2F_TIMING_PRINT")) fprintf(stderr, "sections(cum) setup %llu list %llu prologue %llu loop %llu epilogue %llu chunks %llu batches %llu\n", hst[0], hst[1], hst[2], hst[3], hst[4], hst[6], hst[7]); }
-#endif
     switch (ctx->cfg.L_max) {
         case 1: launch_L<1>(P, ws.cw, ws.G, what, st); break;
         case 2: launch_L<2>(P, ws.cw, ws.G, what, st); break;
@@ -784,10 +751,10 @@ static e2f_status launch_tile(const e2f_ctx* ctx, const E2fCellsView& cv, const 
     return E2F_OK;
 }
 
-// E2F_TILE_NO_LISTS (environment, read at every call, for A/B timing and tests): the attention kernel builds its lists
-// per (tile, head) instead of reading the ones the list kernel leaves per tile.
+// With E2F_FLAG_TILE_LISTS_PER_HEAD in the configuration the attention kernel builds its lists per (tile, head)
+// instead of reading the ones the list kernel leaves per tile (for A/B timing and tests).
 e2f_status e2f_launch_tile(const e2f_ctx* ctx, const E2fCellsView& cv, const E2fAttnWs& ws, float* out, hipStream_t st) {
-    if (!ws.lists_hdr || getenv("E2F_TILE_NO_LISTS")) return launch_tile(ctx, cv, ws, out, 0, st);
+    if (!ws.lists_hdr || (ctx->cfg.flags & E2F_FLAG_TILE_LISTS_PER_HEAD)) return launch_tile(ctx, cv, ws, out, 0, st);
     const e2f_status rc = launch_tile(ctx, cv, ws, out, 1, st);
     if (rc != E2F_OK) return rc;
     return launch_tile(ctx, cv, ws, out, 2, st);

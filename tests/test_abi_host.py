@@ -38,11 +38,14 @@ def test_status_strings(lib):
     (dict(L_max=-1), 1), (dict(C=0), 1), (dict(H=3), 1), (dict(B=0), 1), (dict(cutoff=0.0), 1),
     (dict(cutoff=float("nan")), 1), (dict(feat_dtype=7), 1), (dict(L_max=0, lf=1), 1),
     (dict(L_max=5), 2), (dict(lf=3, L_max=4), 2), (dict(lf=2, L_max=1), 1), (dict(C=24, H=2), 2), (dict(C=320, H=8), 2), (dict(C=16, H=2, feat_dtype=1), 2),
+    (dict(attention=4), 1), (dict(attention=-1), 1), (dict(flags=64), 1),
+    (dict(attention=1), 2),                 # the tile kernel wants heads of 16 channels and bf16 or fp32 features it supports
+    (dict(attention=2, feat_dtype=0), 2),   # the per-pair matrix-core kernel wants bf16 features
 ])
 def test_create_rejects_bad_configurations(lib, kw, code):
-    base = dict(L_max=2, C=128, H=8, B=8, lf=1, cutoff=5.0, feat_dtype=0)
+    base = dict(L_max=2, C=128, H=8, B=8, lf=1, cutoff=5.0, feat_dtype=0, attention=0, flags=0)
     base.update(kw)
-    cfg = B.Config(*[base[k] for k in ("L_max", "C", "H", "B", "lf", "cutoff", "feat_dtype")])
+    cfg = B.Config(*[base[k] for k in ("L_max", "C", "H", "B", "lf", "cutoff", "feat_dtype", "attention", "flags")])
     ctx = ctypes.c_void_p()
     assert lib.e2f_create(ctypes.byref(cfg), ctypes.byref(ctx)) == code
     assert not ctx.value

@@ -26,12 +26,12 @@ def oracle_cfg(wl):
     return {k: wl["cfg"][k] for k in ("L", "C", "H", "B", "lf", "cutoff")}
 
 
-def run_periodic(torch, wl, targets=None, cap=None):
+def run_periodic(torch, wl, targets=None, cap=None, attention="auto"):
     """Neighbour sets exactly, forward within the tolerance of the dtype; returns the relative L2 error."""
     import oracle as O
     from paper_2601_16622_amd import binding as B
     cfg = wl["cfg"]
-    P = B.Problem(wl)
+    P = B.Problem(wl, attention=attention)
     try:
         P.build_cells()
         deg, offs, idx = P.neighbors()
@@ -70,12 +70,11 @@ def run_periodic(torch, wl, targets=None, cap=None):
 
 
 @pytest.mark.parametrize("kernel", ["tile", "pair", "valu"])
-def test_two_periodic_boxes_bf16(torch_cuda, kernel, monkeypatch):
+def test_two_periodic_boxes_bf16(torch_cuda, kernel):
     """Two boxes of different size in one batch, coordinates partly outside [0, len), tiles that span faces."""
     from paper_2601_16622_amd import workloads as W
-    monkeypatch.setenv("E2F_ATTENTION", kernel)
     wl = W.periodic_boxes((700, 420), seed=1, L=2, C=64, H=4, B=8, cutoff=5.0, dtype="bf16")
-    run_periodic(torch_cuda, wl)
+    run_periodic(torch_cuda, wl, attention=kernel)
 
 
 def test_periodic_box_at_the_benchmark_shape_sampled(torch_cuda):
