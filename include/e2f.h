@@ -53,7 +53,8 @@ typedef enum {
     E2F_ERR_UNSUPPORTED = 2,         /* valid in principle, not implemented (e.g. L_max > 4, lf > 2) */
     E2F_ERR_WORKSPACE_TOO_SMALL = 3, /* ws_bytes below the value the matching *_workspace_bytes returns */
     E2F_ERR_HIP = 4,                 /* a HIP runtime call failed */
-    E2F_ERR_OOM = 5                  /* device allocation failed (materialized baseline only) */
+    E2F_ERR_OOM = 5,                 /* device allocation failed (materialized baseline only) */
+    E2F_ERR_SCRATCH_EXCEEDED = 6     /* e2f_attn_forward_static: the problem needs more than E2F_STATIC_SCRATCH_BYTES */
 } e2f_status;
 
 typedef enum { E2F_F32 = 0, E2F_BF16 = 1 } e2f_dtype;
@@ -173,6 +174,25 @@ size_t e2f_attn_workspace_bytes(const e2f_ctx *ctx, int32_t N);
 e2f_status e2f_attn_forward(e2f_ctx *ctx, const e2f_cells *cells, const float *pos, const void *h,
                             const int32_t *seg_offsets, int32_t N, int32_t S, const e2f_weights *w, float *out,
                             void *ws, size_t ws_bytes, void *hip_stream);
+
+/*
+ * e2f_attn_forward for callers that cannot allocate device memory or hand over a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments without ws / ws_bytes, same kernels,
+ * same result bit for bit; the workspace is a fixed array of E2F_STATIC_SCRATCH_BYTES bytes of device memory that
+ * belongs to the loaded library (every GPU the library runs on holds its own copy until the process ends).
+ *   - e2f_attn_workspace_bytes(ctx, N) must not exceed E2F_STATIC_SCRATCH_BYTES (about 3 200 atoms at L_max = 4,
+ *     C = 128, bf16): E2F_ERR_SCRATCH_EXCEEDED otherwise, before anything is launched.
+ *   - The device that hip_stream belongs to must be the current device.  The first call on a device looks up the
+ *     array's address there (hipGetSymbolAddress; no allocation): make that first call outside a graph capture.
+ *   - All calls on one GPU share the one array and it keeps the last call's contents.  Nothing in it has to be
+ *     cleared between calls, but two calls that overlap in time on one GPU (different streams, or graphs replayed
+ *     side by side) race on it: serialise them.
+ * Calls no hipMalloc / hipFree and no allocating library routine; does not synchronise.  Errors as e2f_attn_forward.
+ */
+#define E2F_STATIC_SCRATCH_BYTES (32u << 20)
+e2f_status e2f_attn_forward_static(e2f_ctx *ctx, const e2f_cells *cells, const float *pos, const void *h,
+                                   const int32_t *seg_offsets, int32_t N, int32_t S, const e2f_weights *w, float *out,
+                                   void *hip_stream);
 
 /*
  * Edge-centric baseline with the same result: builds the edge list and writes per-edge tensors (geometry,

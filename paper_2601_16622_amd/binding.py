@@ -25,7 +25,9 @@ EXPORTS = ["e2f_status_string", "e2f_create", "e2f_destroy", "e2f_cells_workspac
            "e2f_attn_table_workspace_bytes", "e2f_attn_forward_table", "e2f_build_cells_periodic",
            "e2f_attn_backward_workspace_bytes", "e2f_attn_backward",
            "e2f_attn_backward_weights_workspace_bytes", "e2f_attn_nonlinear_workspace_bytes",
-           "e2f_attn_forward_nonlinear", "e2f_count_edges", "e2f_profile_read"]
+           "e2f_attn_forward_nonlinear", "e2f_count_edges", "e2f_profile_read",
+           "e2f_attn_forward_static"]
+STATIC_SCRATCH_BYTES = 32 << 20   # E2F_STATIC_SCRATCH_BYTES
 STAGES = ("prepare", "project", "attention")
 
 
@@ -83,6 +85,8 @@ def load():
     L.e2f_attn_workspace_bytes.restype = sz
     L.e2f_attn_forward.argtypes = [vp, vp, vp, vp, vp, i32, i32, ctypes.POINTER(Weights), vp, vp, sz, vp]
     L.e2f_attn_forward.restype = ctypes.c_int
+    L.e2f_attn_forward_static.argtypes = [vp, vp, vp, vp, vp, i32, i32, ctypes.POINTER(Weights), vp, vp]
+    L.e2f_attn_forward_static.restype = ctypes.c_int
     L.e2f_attn_forward_materialized.argtypes = [vp, vp, vp, vp, vp, i32, i32, ctypes.POINTER(Weights), vp, vp, sz, vp,
                                                 ctypes.POINTER(sz), ctypes.POINTER(sz)]
     L.e2f_attn_forward_materialized.restype = ctypes.c_int
@@ -212,6 +216,13 @@ def e2f_attn_forward(ctx, cells, pos, h, seg_offsets, weights, out, ws):
     wt = _weights(weights)
     _check(load().e2f_attn_forward(ctx, cells, _ptr(pos), _ptr(h), _ptr(seg_offsets), N, S, ctypes.byref(wt),
                                    _ptr(out), _ptr(ws), ws.numel(), _stream()), "e2f_attn_forward")
+
+
+def e2f_attn_forward_static(ctx, cells, pos, h, seg_offsets, weights, out):
+    N, S = pos.shape[0], seg_offsets.shape[0] - 1
+    wt = _weights(weights)
+    _check(load().e2f_attn_forward_static(ctx, cells, _ptr(pos), _ptr(h), _ptr(seg_offsets), N, S, ctypes.byref(wt),
+                                          _ptr(out), _stream()), "e2f_attn_forward_static")
 
 
 def e2f_attn_capped_workspace_bytes(ctx, N):
@@ -367,6 +378,11 @@ class Problem:
     def forward(self):
         e2f_attn_forward(self.ctx, self.cells, self.pos, self.h, self.seg, self.weights, self.out, self.attn_ws)
         return self.out
+
+    def forward_static(self, out=None):
+        out = self.out if out is None else out
+        e2f_attn_forward_static(self.ctx, self.cells, self.pos, self.h, self.seg, self.weights, out)
+        return out
 
     def _scratch(self, name, need):
         import torch

@@ -2,11 +2,36 @@
 #include <math.h>
 #include <stdlib.h>
 #include <string.h>
+#include <mutex>
 #include <new>
 
 #include "e2f_internal.h"
 
+// Workspace of e2f_attn_forward_static: device memory that belongs to the loaded library, one copy per GPU.  In host
+// code this name only stands for the symbol; the address on a device comes from hipGetSymbolAddress (static_scratch).
+static __device__ __align__(256) unsigned char scratch[E2F_STATIC_SCRATCH_BYTES];
+
 namespace {
+
+constexpr int MAX_DEVICES = 64;
+void* g_scratch_ptr[MAX_DEVICES];   // device address of `scratch` on every GPU that has asked for it
+std::mutex g_scratch_mutex;
+
+// Address of the current device's copy of `scratch` (looked up once per device, with that device current).
+e2f_status static_scratch(void** ptr) {
+    int dev = -1;
+    E2F_HIP_CHECK(hipGetDevice(&dev));
+    if (dev < 0 || dev >= MAX_DEVICES) return E2F_ERR_UNSUPPORTED;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        E2F_HIP_CHECK(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p) return E2F_ERR_HIP;
+        g_scratch_ptr[dev] = p;
+    }
+    *ptr = g_scratch_ptr[dev];
+    return E2F_OK;
+}
 
 bool aligned256(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 255u) == 0; }
 
@@ -150,6 +175,7 @@ const char* e2f_status_string(e2f_status s) {
         case E2F_ERR_WORKSPACE_TOO_SMALL: return "workspace too small";
         case E2F_ERR_HIP: return "HIP runtime error";
         case E2F_ERR_OOM: return "out of device memory";
+        case E2F_ERR_SCRATCH_EXCEEDED: return "problem exceeds the library's static scratch (E2F_STATIC_SCRATCH_BYTES)";
     }
     return "unknown status";
 }
@@ -424,6 +450,22 @@ e2f_status e2f_attn_forward(e2f_ctx* ctx, const e2f_cells* cells, const float* p
                             const int32_t* seg_offsets, int32_t N, int32_t S, const e2f_weights* w, float* out,
                             void* ws, size_t ws_bytes, void* hip_stream) {
     return forward_impl(ctx, cells, pos, h, seg_offsets, N, S, w, out, ws, ws_bytes, hip_stream, 0, nullptr, 0);
+}
+
+e2f_status e2f_attn_forward_static(e2f_ctx* ctx, const e2f_cells* cells, const float* pos, const void* h,
+                                   const int32_t* seg_offsets, int32_t N, int32_t S, const e2f_weights* w, float* out,
+                                   void* hip_stream) {
+    if (!ctx || N < 0) return E2F_ERR_INVALID_ARG;
+    if (e2f_attn_workspace_bytes(ctx, N) > (size_t)E2F_STATIC_SCRATCH_BYTES) return E2F_ERR_SCRATCH_EXCEEDED;
+    void* ws = nullptr;
+    if (N > 0) {
+        const e2f_status rc = static_scratch(&ws);
+        if (rc != E2F_OK) return rc;
+    }
+    // Nothing in the workspace has to start at zero: every stage writes all that the next one reads (padding rows of
+    // k and v and the tiles' list headers included), so what an earlier, larger call left behind is never read.
+    return forward_impl(ctx, cells, pos, h, seg_offsets, N, S, w, out, ws, (size_t)E2F_STATIC_SCRATCH_BYTES, hip_stream, 0,
+                        nullptr, 0);
 }
 
 size_t e2f_attn_capped_workspace_bytes(const e2f_ctx* ctx, int32_t N) {

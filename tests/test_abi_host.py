@@ -30,8 +30,8 @@ def test_every_declared_symbol_is_exported(lib):
 
 
 def test_status_strings(lib):
-    texts = {B.status_string(c) for c in range(6)}
-    assert len(texts) == 6 and "ok" in texts
+    texts = {B.status_string(c) for c in range(7)}
+    assert len(texts) == 7 and "ok" in texts
 
 
 @pytest.mark.parametrize("kw,code", [
