@@ -228,12 +228,48 @@ __device__ __forceinline__ void align_D(float dx, float dy, float dz, float d, f
 }
 
 // Radial pieces of Eq. attn: gate phi(d) and the Gaussian basis value g_b(d).
+// phi(d) = (1 + cos(pi d / cutoff)) / 2.  The hardware cosine takes its argument in revolutions, so the argument is
+// d times 1/(2 cutoff), a factor that does not depend on the pair (no division per pair).
 __device__ __forceinline__ float radial_gate(float d, float cutoff) {
-    return 0.5f * (1.0f + __cosf(3.14159265358979323846f * d / cutoff));
+    return 0.5f + 0.5f * __builtin_amdgcn_cosf(d * (0.5f / cutoff));
 }
 __device__ __forceinline__ float radial_basis(float d, int b, float step, float gamma) {
     const float t = d - (float)b * step;
     return __expf(-gamma * t * t);
+}
+
+// Value rows of the tile attention kernel: per (group of four slots, head) a block of n * 64 bf16.  The n components are
+// split among the four waves of a workgroup (n / 4 each, the first n % 4 waves one more, contiguous ranges); inside a
+// wave's range an odd first component stands alone as [16 channels][4 slots] and the others go in pairs as
+// [16 channels][2 components][4 slots], so that a lane fetches the four slots of two components with one 16-byte
+// load (a vector memory instruction costs the same whether it moves 8 or 16 bytes per lane).  Returns the offset, in
+// bf16 elements, of (component x, channel ch, first slot) inside the block.
+__host__ __device__ __forceinline__ int v4_offset(int n, int x, int ch) {
+    const int q = n / 4, rem = n % 4;
+    int w = 0, x0 = 0, nxw = q + (rem > 0 ? 1 : 0);
+    while (x >= x0 + nxw) {
+        x0 += nxw;
+        ++w;
+        nxw = q + (w < rem ? 1 : 0);
+    }
+    const int odd = nxw & 1;
+    int local = x - x0;
+    if (odd && local == 0) return x0 * 64 + ch * 4;
+    local -= odd;
+    return x0 * 64 + odd * 64 + (local >> 1) * 128 + ch * 8 + (local & 1) * 4;
+}
+// 0: component x stands alone in that layout, 1: it is the first of a pair, 2: the second.
+__host__ __device__ __forceinline__ int v4_role(int n, int x) {
+    const int q = n / 4, rem = n % 4;
+    int w = 0, x0 = 0, nxw = q + (rem > 0 ? 1 : 0);
+    while (x >= x0 + nxw) {
+        x0 += nxw;
+        ++w;
+        nxw = q + (w < rem ? 1 : 0);
+    }
+    const int odd = nxw & 1, local = x - x0;
+    if (odd && local == 0) return 0;
+    return 1 + ((local - odd) & 1);
 }
 
 __device__ __forceinline__ float bf16_bits_to_float(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }

@@ -30,9 +30,10 @@ struct CoefTable {
 // spos[slot] = position of the atom in that slot (w carries its index in the caller's order); cw[comp][t] = P coefficient times its path weight.
 __global__ void k_prepare(E2fCellsView cv, const float* __restrict__ pos, const float* __restrict__ w_path, int L,
                           int lf, CoefTable tab, float4* __restrict__ spos, float* __restrict__ cw,
-                          const float* __restrict__ Wb, int H, int B, float* __restrict__ wbT) {
+                          const float* __restrict__ Wb, int H, int B, float* __restrict__ wbT, int* __restrict__ ovf) {
     const int t = blockIdx.x * blockDim.x + threadIdx.x;
     if (t < H * B) wbT[(t % B) * H + t / B] = Wb[t];
+    if (t == 0 && ovf) ovf[0] = 0;   // no tile of the tile kernel has overflowed its candidate list yet
     if (t < cv.N) {
         const int a = cv.perm[t];
         float x = pos[3 * a], y = pos[3 * a + 1], z = pos[3 * a + 2];
@@ -517,12 +518,14 @@ __global__ __launch_bounds__(64 * WG_WAVES) void k_project_wg(E2fCellsView cv, c
                     const int a = 4 * gl + i;
                     val[4 * s2 + i] = a < n_atoms ? s_v[((a * 2 + T) * 16 + ch + s2) * 16 + pos] : (uint16_t)0;
                 }
-            uint4 pk;
-            pk.x = val[0] | ((uint32_t)val[1] << 16);
-            pk.y = val[2] | ((uint32_t)val[3] << 16);
-            pk.z = val[4] | ((uint32_t)val[5] << 16);
-            pk.w = val[6] | ((uint32_t)val[7] << 16);
-            *reinterpret_cast<uint4*>(go.v4 + ((((size_t)tile0 * 4 + gl) * NCT + ct) * n + comp) * 64 + ch * 4) = pk;
+            uint2 pk0, pk1;   // the four slots of (comp, ch) and of (comp, ch + 1)
+            pk0.x = val[0] | ((uint32_t)val[1] << 16);
+            pk0.y = val[2] | ((uint32_t)val[3] << 16);
+            pk1.x = val[4] | ((uint32_t)val[5] << 16);
+            pk1.y = val[6] | ((uint32_t)val[7] << 16);
+            uint16_t* blk = go.v4 + (((size_t)tile0 * 4 + gl) * NCT + ct) * n * 64;
+            *reinterpret_cast<uint2*>(blk + e2f::v4_offset(n, comp, ch)) = pk0;
+            *reinterpret_cast<uint2*>(blk + e2f::v4_offset(n, comp, ch + 1)) = pk1;
         }
         // q, k: 16-byte units of eight features (feature = l*16 + channel) in binary16
         const int u_per = go.DKP >> 3, DK = (L + 1) * 16;
@@ -586,12 +589,19 @@ __global__ __launch_bounds__(64 * (C / 16 + 1)) void k_project_sh(E2fCellsView c
     constexpr int NS = C / F::KSTEP, NCT = C / 16, ROW = C + 8, NLD = C / 32;   // NLD 16-byte loads per lane and slab
     __shared__ __attribute__((aligned(16))) uint16_t s_x[4][16 * ROW];   // slab st in buffer st mod 4
     __shared__ __attribute__((aligned(8))) uint16_t s_t[NCT][256];
+    __shared__ int s_vst[2 * E2F_MAX_L + 1];   // where the value rows of order m go (see below)
     __shared__ int s_atom[SH_TPW * 16];   // fetching wave: atom of every row of the workgroup's tiles
     const int N = cv.N, n = (L + 1) * (L + 1), n_tiles = (N + 15) / 16, N4 = (N + 3) / 4 * 4;
     const int l = L - (int)blockIdx.x / n_groups, nl = 2 * l + 1;
     const int tile0 = ((int)blockIdx.x % n_groups) * tpw, nt = min(tpw, n_tiles - tile0);
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, j = lane & 15, g = lane >> 4;
     const int n_steps = nt * nl;   // step = local tile * nl + order
+    // Where the value rows of component l*l + m go in the layout of e2f::v4_offset: (offset of channel 0) << 4 | number
+    // of elements from one channel to the next (4 for a lone component, 8 inside a pair).
+    if ((int)threadIdx.x < nl) {
+        const int x = l * l + (int)threadIdx.x;
+        s_vst[threadIdx.x] = (e2f::v4_offset(n, x, 0) << 4) | (e2f::v4_role(n, x) == 0 ? 4 : 8);
+    }
 
     if (wave == NCT) {
         // ---- the fetching wave: lane = (atom a of the tile, quarter of its row)
@@ -675,6 +685,7 @@ __global__ __launch_bounds__(64 * (C / 16 + 1)) void k_project_sh(E2fCellsView c
         // accumulator layout: lane (g, j) holds output channels 4g..4g+3 of atom j
         const int slot = (tile0 + lt) * 16 + j;
         {   // v: [channel][atom] patch, then one (channel, group of four slots) per lane
+            const int vst = s_vst[m];   // (offset of channel 0) << 4 | elements between channels
             uint16_t* patch = s_t[ct];
 #pragma unroll
             for (int r = 0; r < 4; ++r)
@@ -684,9 +695,10 @@ __global__ __launch_bounds__(64 * (C / 16 + 1)) void k_project_sh(E2fCellsView c
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
             const int ch = lane >> 2, G = lane & 3;
             const u32x2 unit = *reinterpret_cast<const u32x2*>(patch + ch * 16 + 4 * G);
-            const int grp = (tile0 + lt) * 4 + G;
-            if (grp * 4 < N)
-                *reinterpret_cast<u32x2*>(go.v4 + (((size_t)grp * NCT + ct) * n + l * l + m) * 64 + ch * 4) = unit;
+            // the tile's part of the address is the same for the whole wave, the lane's part fits 32 bits
+            uint16_t* tile_v = go.v4 + (size_t)(tile0 + lt) * 4 * NCT * n * 64;
+            const unsigned lane_v = (unsigned)((G * NCT + ct) * n * 64 + (vst >> 4) + ch * (vst & 15));
+            if (((tile0 + lt) * 4 + G) * 4 < N) *reinterpret_cast<u32x2*>(tile_v + lane_v) = unit;
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
             __builtin_amdgcn_wave_barrier();
         }
@@ -912,7 +924,7 @@ e2f_status e2f_launch_prepare(const e2f_ctx* ctx, const E2fCellsView& cv, const 
     int work = cv.N > ctx->n * E2F_NP ? cv.N : ctx->n * E2F_NP;
     if (ctx->cfg.H * ctx->cfg.B > work) work = ctx->cfg.H * ctx->cfg.B;
     k_prepare<<<(work + 255) / 256, 256, 0, st>>>(cv, pos, w->w_path, ctx->cfg.L_max, ctx->cfg.lf, tab, ws.spos, ws.cw,
-                                                 w->Wb, ctx->cfg.H, ctx->cfg.B, ws.wbT);
+                                                 w->Wb, ctx->cfg.H, ctx->cfg.B, ws.wbT, ws.lists_ovf);
     E2F_HIP_CHECK(hipGetLastError());
     return E2F_OK;
 }

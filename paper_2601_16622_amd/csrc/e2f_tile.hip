@@ -44,6 +44,33 @@ constexpr int TILE_BLK = 16;   // consecutive tiles whose (tile, head) items for
 #endif
 constexpr float M_STEP = 20.0f; // the softmax reference moves when a logit exceeds it by this much (base-2 units)
 
+// Registers for the value rows of one chunk: the wave's single component (8 bytes per entry) and NP pairs of
+// components (16 bytes per entry), for the lane's two list entries a and b.
+template <int NP>
+struct VRows {
+    u32x2 sa, sb;
+    u32x4 pa[NP > 0 ? NP : 1], pb[NP > 0 ? NP : 1];
+    __device__ __forceinline__ void load_single(const uint16_t* a, const uint16_t* b) {
+        sa = *reinterpret_cast<const u32x2*>(a);
+        sb = *reinterpret_cast<const u32x2*>(b);
+    }
+    // a, b: the first pair's 16 bytes of this lane's channel; pairs are 128 elements apart
+    __device__ __forceinline__ void load_pair(int p, const uint16_t* a, const uint16_t* b) {
+        pa[p] = *reinterpret_cast<const u32x4*>(a + p * 128);
+        pb[p] = *reinterpret_cast<const u32x4*>(b + p * 128);
+    }
+    // B operands (32 candidates x 16 channels; this lane: 8 candidates of its channel)
+    __device__ __forceinline__ bf16x8 single() const {
+        return __builtin_bit_cast(bf16x8, (u32x4){sa[0], sa[1], sb[0], sb[1]});
+    }
+    __device__ __forceinline__ bf16x8 first(int p) const {
+        return __builtin_bit_cast(bf16x8, (u32x4){pa[p][0], pa[p][1], pb[p][0], pb[p][1]});
+    }
+    __device__ __forceinline__ bf16x8 second(int p) const {
+        return __builtin_bit_cast(bf16x8, (u32x4){pa[p][2], pa[p][3], pb[p][2], pb[p][3]});
+    }
+};
+
 struct TileParams {
     E2fCellsView cv;
     const float4* spos;
@@ -58,6 +85,8 @@ struct TileParams {
     int4* lists_hdr;
     int* lists_ent;
     float4* lists_pos;
+    int* lists_ovf;    // [0]: number of tiles whose list did not fit, then their numbers
+    int hpw;           // heads per workgroup of k_tile_heads
     const float* cw;   // the list kernel's first workgroup forms the axis operators instead: G_out from cw
     float* G_out;
     int C, H, B, n_tiles;
@@ -151,10 +180,11 @@ __global__ void k_axis_ops(const float* __restrict__ cw, float* __restrict__ G, 
 // PBC: whether segments can have periodic axes (the candidate runs then include the images across the faces).
 // MODE 0: lists built here, per (tile, head).  MODE 1: one workgroup per tile only builds the tile's list and writes it
 // out (no head, no streaming): the passes' lists one after the other, every entry tagged with its pass, so that a
-// candidate counts only for the targets of the pass that found it.  MODE 2: reads the list MODE 1 left (the H heads
-// of a tile share it), and builds it here when that one did not fit its LCAP entries.
-template <int L, int NW, bool PBC, int MODE>
-__global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(E2F_TILE_OCC(NW), E2F_TILE_OCC(NW)))) void k_tile(TileParams P) {
+// candidate counts only for the targets of the pass that found it (k_tile_heads reads those lists; tiles whose list
+// does not fit LCAP entries come back here in MODE 0 through k_tile_ovf).
+// CAP: whether a neighbour cap is in force (threshold keys per target).
+template <int L, int NW, bool PBC, int MODE, bool CAP>
+__device__ __forceinline__ void tile_item(const TileParams& P, const int tile, const int head) {
     constexpr int n = (L + 1) * (L + 1), NX = (n + NW - 1) / NW;
     constexpr int PADE = 8 * NW;        // the list is padded to whole groups of NW chunks
     constexpr int LU = 64 / NW / 4;     // steps of 16 slot groups per wave and batch (256 groups per batch)
@@ -179,29 +209,23 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(E2F_TIL
     u32x4* s_W = reinterpret_cast<u32x4*>(s_raw + LIST_BYTES);   // [chunk of the group][mu][lane]
     f32x4* s_po = reinterpret_cast<f32x4*>(s_raw);
 
-    int tile, head;
-    if constexpr (MODE == 1) {
-        if (blockIdx.x == 0) {   // (whole workgroup) the first workgroup forms the axis operators instead
-            axis_ops<L>(P.cw, P.G_out, threadIdx.x, true);
-            return;
-        }
-        tile = blockIdx.x - 1;
-        head = 0;
-    } else {
-        if (!tile_xcd_remap(blockIdx.x, P.n_tiles, P.H, tile, head)) return;   // whole workgroup
-    }
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, tn = lane & 15, g = lane >> 4;
-    // components [x0, x0 + nxw) belong to this wave: n / NW each, the first n % NW waves one more (NX is the largest)
+    // components [x0, x0 + nxw) belong to this wave: n / NW each, the first n % NW waves one more (NX is the largest).
+    // Accumulator slot 0 holds the wave's single component (odd nxw), slots 1 + 2p and 2 + 2p its p-th pair.
+    static_assert(NW == 4, "the value rows are laid out for four waves (e2f::v4_offset)");
+    constexpr int NP = NX / 2, NS = 1 + 2 * NP;
+    constexpr bool HAS_ODD = (NX & 1) || (n % NW != 0 && ((NX - 1) & 1));
     const int nxw = n / NW + (wave < n % NW ? 1 : 0);
     const int x0 = wave * (n / NW) + min(wave, n % NW);
-    const bool last_x = nxw == NX;   // whether this wave uses accumulator slot NX - 1
+    const int npair = nxw >> 1;
+    const bool single = (nxw & 1) != 0;
     const int N = P.cv.N, H = P.H;
     const int t0 = tile * 16, nt = min(16, N - t0);
     const int tslot = min(t0 + tn, N - 1);
     const float4 tp = P.spos[tslot];
     const float4 origin = make_float4(read_lane(tp.x, 0), read_lane(tp.y, 0), read_lane(tp.z, 0), 0.0f);
-    const uint32_t capd = P.cap_d2 ? P.cap_d2[tslot] : 0xffffffffu;
-    const int capi = P.cap_idx ? P.cap_idx[tslot] : INT_MAX;
+    const uint32_t capd = CAP ? P.cap_d2[tslot] : 0xffffffffu;
+    const int capi = CAP ? P.cap_idx[tslot] : INT_MAX;
     // the target's segment, cell and grid shape in one record (no dependent read of the grid)
     const int4 ti0 = P.cv.sinfo[2 * tslot], ti1 = P.cv.sinfo[2 * tslot + 1];
     const int tseg = ti0.x, tcx = ti0.y, trow = ti0.w * ti1.y + ti0.z;   // row of cells: cz * ny + cy
@@ -231,25 +255,21 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(E2F_TIL
                 *reinterpret_cast<const u32x4*>(P.q16 + ((size_t)min(t0 + tq, N - 1) * H + head) * DKP + 8 * f8);
         }
     }
-    // MODE 2: the tile's list as the list kernel left it (pre < 0: not there, build it here)
-    // (fetching the whole list area beside the header, so that nothing waits for the count, was slower)
-    int pre = -1, my_pass = -1;
-    if constexpr (MODE == 2) {
-        const int4 hd = P.lists_hdr[tile];
-        pre = hd.x;
-        if (pre >= 0 && tn < nt) my_pass = ((tn < 8 ? hd.y : hd.z) >> (4 * (tn & 7))) & 15;
-    }
+    int my_pass = -1;
     // MODE 1: entries written so far, whether they still fit, the pass of every target
     int out_cnt = 0, pidx = 0;
     bool overflow = false;
     __shared__ int s_tpass[16];
 
-    f32x4 acc[3][NX];
+    f32x4 acc[3][NS];
 #pragma unroll
     for (int mu = 0; mu < 3; ++mu)
 #pragma unroll
-        for (int x = 0; x < NX; ++x) acc[mu][x] = (f32x4){0.f, 0.f, 0.f, 0.f};
-    float m_ref = -INFINITY, z = 0.0f;
+        for (int x = 0; x < NS; ++x) acc[mu][x] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    // Reference of the softmax: M_NONE until the target has met a neighbour.  It is finite, so that a masked logit
+    // (-inf) minus the reference is -inf and its weight 2^-inf = 0 without a select.
+    constexpr float M_NONE = -1.0e30f;
+    float m_ref = M_NONE, z = 0.0f;
 
     int a = 0;
     while (a < nt) {
@@ -258,9 +278,9 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(E2F_TIL
         const bool same = tseg == seg_a && trow == row_a && lane >= a && lane < nt;   // lanes 0..15 carry the targets
         const unsigned bits = (unsigned)(__ballot(same) & 0xFFFFull);
         const unsigned stop = ~bits & ((1u << nt) - 1u) & ~((1u << a) - 1u);
-        const int b = pre >= 0 ? nt : (stop ? __builtin_ctz(stop) : nt);   // (a precomputed list covers every pass)
+        const int b = stop ? __builtin_ctz(stop) : nt;
         const bool t_active = tn >= a && tn < b;
-        if (pre < 0) my_pass = t_active ? (MODE == 1 ? pidx : 0) : -1;
+        my_pass = t_active ? (MODE == 1 ? pidx : 0) : -1;
         if (MODE == 1 && t_active && threadIdx.x < 16) s_tpass[threadIdx.x] = pidx;
         const int cxa = __builtin_amdgcn_readlane(tcx, a), cxb = __builtin_amdgcn_readlane(tcx, b - 1);
         // Runs of sorted slots that hold the pass's candidates: rows 0..8 are the stencil rows over the cells
@@ -270,7 +290,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(E2F_TIL
         // plus the run's lattice translation.  The runs are a table in LDS, one thread per run (in registers they
         // push the kernel's value rows into scratch).
         int total = 1;
-        if (pre < 0) {
+        {
             __syncthreads();   // every wave has finished with the previous pass's table
             if (threadIdx.x < 16) {
                 // |p - t|^2 < reach^2 as |q|^2 + q.(-2u) + (|u|^2 - reach^2) < 0 with q = p - o, u = t - o around the
@@ -344,13 +364,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(E2F_TIL
             // ---- a batch of the candidate list: 256 slot groups, 64 per wave, kept groups packed in order into
             // entries (group << 8 | pass << 4 | valid slots) with the slots' positions beside them
             int cnt = 0;
-            if (pre >= 0) {   // (uniform) the list is there: entries and slot positions -> LDS
-                cnt = pre;
-                const int* ge = P.lists_ent + (size_t)tile * LCAP;
-                const float4* gp = P.lists_pos + (size_t)tile * LCAP * 4;
-                for (int i = threadIdx.x; i < cnt; i += 64 * NW) s_ent[i] = ge[i];
-                for (int i = threadIdx.x; i < 4 * cnt; i += 64 * NW) s_pos[i] = gp[i];
-            } else {
+            {
             int grp[LU];
             unsigned near4[LU], valid4[LU];
             unsigned long long leaders[LU];
@@ -461,19 +475,24 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(E2F_TIL
                         for (int ks = 0; ks < KS; ++ks) kf[mt][ks] = *reinterpret_cast<const f16x8*>(P.k16 + off + 32 * ks);
                     }
                 };
-                // v rows of this wave's component x for the lane's two entries: k = 8g..8g+3 from entry g of the
-                // chunk, 8g+4..8g+7 from entry 4+g
-                auto load_V = [&](int c, int x, u32x2& va, u32x2& vb) {
+                // v rows of this wave's components for the lane's two entries (k = 8g..8g+3 from entry g of the chunk,
+                // 8g+4..8g+7 from entry 4+g): the wave's single component, then its pairs (see e2f::v4_offset)
+                VRows<NP> vr;
+                auto v_base = [&](int c, const uint16_t*& ba, const uint16_t*& bb) {
                     const unsigned ea = (unsigned)s_ent[8 * c + g] >> 8, eb = (unsigned)s_ent[8 * c + 4 + g] >> 8;
-                    va = *reinterpret_cast<const u32x2*>(P.v4 + (((size_t)ea * H + head) * n + x0) * 64 + tn * 4 + x * 64);
-                    vb = *reinterpret_cast<const u32x2*>(P.v4 + (((size_t)eb * H + head) * n + x0) * 64 + tn * 4 + x * 64);
+                    ba = P.v4 + (((size_t)ea * H + head) * n + x0) * 64 + (single ? 64 : 0) + tn * 8;
+                    bb = P.v4 + (((size_t)eb * H + head) * n + x0) * 64 + (single ? 64 : 0) + tn * 8;
                 };
                 f16x8 kf[2][KS];
-                u32x2 va[NX], vb[NX];
                 load_K(min(wave, nch - 1), kf);
+                {
+                    const uint16_t *ba, *bb;
+                    v_base(0, ba, bb);
+                    if (HAS_ODD && single) vr.load_single(ba - 64 - tn * 4, bb - 64 - tn * 4);
 #pragma unroll
-                for (int x = 0; x < NX; ++x)
-                    if (x < NX - 1 || last_x) load_V(0, x, va[x], vb[x]);
+                    for (int p = 0; p < NP; ++p)
+                        if (p < npair) vr.load_pair(p, ba, bb);
+                }
                 for (int G = 0; G < ngr; ++G) {
                     // ---- logits, pair geometry and cutoff mask of this wave's chunk
                     const int cm = NW * G + wave;
@@ -501,10 +520,10 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(E2F_TIL
                             const int u = 4 * mt + r;
                             const float4 pc = s_pos[ei * 4 + r];
                             const float d2 = e2f::dist2_exact(tp.x, tp.y, tp.z, pc.x, pc.y, pc.z);
-                            // (bitwise on purpose: the eight candidates are evaluated side by side)
+                            // (bitwise on purpose: the eight candidates are evaluated side by side; the target itself
+                            // is at distance zero, an image of it at a box length: neither passes)
                             const bool ok = (((e >> r) & 1) != 0) & (((e >> 4) & 15) == my_pass) &
-                                            ((int)(4 * ((unsigned)e >> 8) + r) != t0 + tn) &
-                                            (d2 < P.rc2) & (d2 > 0.0f) & e2f::under_cap(d2, pc.w, capd, capi);
+                                            (d2 < P.rc2) & (d2 > 0.0f) & (!CAP || e2f::under_cap(d2, pc.w, capd, capi));
                             const float d = __builtin_amdgcn_sqrtf(d2);
                             const float uu = __builtin_amdgcn_exp2f(c_u * d);
                             float poly = cb[7];
@@ -527,7 +546,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(E2F_TIL
                     float gmax = s_cmax[0][tn];
 #pragma unroll
                     for (int w = 1; w < NW; ++w) gmax = fmaxf(gmax, s_cmax[w][tn]);
-                    if (m_ref == -INFINITY) m_ref = gmax;   // first neighbours: the accumulator rows are still zero
+                    if (m_ref == M_NONE) m_ref = fmaxf(gmax, M_NONE);   // first neighbours: the accumulator rows are still zero
                     const bool move = gmax > m_ref + M_STEP;
                     if (__builtin_expect(__ballot(move) != 0ull, 0)) {
                         const float f = move ? __builtin_amdgcn_exp2f(m_ref - gmax) : 1.0f;
@@ -541,7 +560,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(E2F_TIL
 #pragma unroll
                         for (int mu = 0; mu < 3; ++mu)
 #pragma unroll
-                            for (int x = 0; x < NX; ++x) {
+                            for (int x = 0; x < NS; ++x) {
                                 f32x4 d = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                                 for (int r = 0; r < 4; ++r)
@@ -557,7 +576,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(E2F_TIL
                             float pg[2], rx[2], ry[2], rz[2];
 #pragma unroll
                             for (int d = 0; d < 2; ++d) {
-                                const float p = s2[u + d] > -INFINITY ? __builtin_amdgcn_exp2f(s2[u + d] - m_ref) : 0.0f;
+                                const float p = __builtin_amdgcn_exp2f(s2[u + d] - m_ref);
                                 z += p;
                                 pg[d] = p * gate[u + d];
                                 const float4 pc = s_pos[(8 * cm + 4 * ((u + d) >> 2) + g) * 4 + ((u + d) & 3)];
@@ -582,14 +601,23 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(E2F_TIL
                             bf16x8 W[3];
 #pragma unroll
                             for (int mu = 0; mu < 3; ++mu) W[mu] = __builtin_bit_cast(bf16x8, s_W[(cc * 3 + mu) * 64 + lane]);
-                            const int cnext = min(c + 1, nch - 1);
+                            const uint16_t *ba, *bb;   // the next chunk's rows replace each operand once it has been used
+                            v_base(min(c + 1, nch - 1), ba, bb);
+                            if (HAS_ODD && single) {   // (wave-uniform)
+                                const bf16x8 bv = vr.single();
 #pragma unroll
-                            for (int x = 0; x < NX; ++x)
-                                if (x < NX - 1 || last_x) {   // (wave-uniform)
-                                    const bf16x8 bv = __builtin_bit_cast(bf16x8, __builtin_shufflevector(va[x], vb[x], 0, 1, 2, 3));
+                                for (int mu = 0; mu < 3; ++mu) acc[mu][0] = mfma(W[mu], bv, acc[mu][0]);
+                                vr.load_single(ba - 64 - tn * 4, bb - 64 - tn * 4);
+                            }
 #pragma unroll
-                                    for (int mu = 0; mu < 3; ++mu) acc[mu][x] = mfma(W[mu], bv, acc[mu][x]);
-                                    load_V(cnext, x, va[x], vb[x]);
+                            for (int p = 0; p < NP; ++p)
+                                if (p < npair) {   // (wave-uniform)
+                                    const bf16x8 b0 = vr.first(p), b1 = vr.second(p);
+#pragma unroll
+                                    for (int mu = 0; mu < 3; ++mu) acc[mu][1 + 2 * p] = mfma(W[mu], b0, acc[mu][1 + 2 * p]);
+#pragma unroll
+                                    for (int mu = 0; mu < 3; ++mu) acc[mu][2 + 2 * p] = mfma(W[mu], b1, acc[mu][2 + 2 * p]);
+                                    vr.load_pair(p, ba, bb);
                                 }
                         }
                     }
@@ -608,6 +636,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(E2F_TIL
                 hi |= (8 + i < nt ? (unsigned)s_tpass[8 + i] : 0u) << (4 * i);
             }
             P.lists_hdr[tile] = make_int4(overflow ? -1 : out_cnt, (int)lo, (int)hi, 0);
+            if (overflow) P.lists_ovf[1 + atomicAdd(P.lists_ovf, 1)] = tile;   // left to k_tile_ovf
         }
         return;
     }
@@ -631,7 +660,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(E2F_TIL
         for (int mu = 0; mu < 3; ++mu) {
             __syncthreads();
 #pragma unroll
-            for (int x = 0; x < NXW; ++x) s_po[(X0 + x) * 64 + lane] = acc[mu][x];
+            for (int x = 0; x < NXW; ++x) s_po[(X0 + x) * 64 + lane] = acc[mu][x + ((NXW & 1) ? 0 : 1)];
             __syncthreads();
 #pragma unroll
             for (int i = 0; i < RO; ++i) {
@@ -683,6 +712,378 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(E2F_TIL
     }
 }
 
+// The attention kernel for tiles whose candidate list the list kernel has left in memory (all but the rare crowded
+// ones).  A workgroup of four waves owns one tile of 16 targets and `hpw` consecutive heads, which it runs one after
+// the other: what belongs to the tile (the targets, their output rows, the candidate list with its slot positions,
+// the axis operators) is fetched once, all of it requested before any of it is used, and stays in LDS for every head;
+// what belongs to a head (its queries, its radial weights, the key and value rows of the first chunks) is requested
+// while the head before it is in its epilogue.  The streaming loop and the epilogue are those of tile_item.
+template <int L, bool CAP>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void k_tile_heads(TileParams P) {
+    constexpr int NW = 4, n = (L + 1) * (L + 1), NX = (n + NW - 1) / NW;
+    constexpr int DK = (L + 1) * 16, KS = (DK + 31) / 32, DKP = KS * 32;
+    constexpr int LENT = LCAP + 8 * NW;   // the list, padded to whole groups of four chunks
+    constexpr int W_BYTES = NW * 3 * 64 * 16, PO_BYTES = n * 64 * 16;
+    __shared__ int s_ent[LENT];
+    __shared__ float4 s_pos[LENT * 4];
+    __shared__ __attribute__((aligned(16))) uint16_t s_q[16 * DKP];
+    __shared__ float s_G[AXIS_NNZ];
+    __shared__ float s_cmax[NW][16];
+    __shared__ float s_z[NW][16];
+    __shared__ int s_orow[16];
+    // the weights while streaming; the same bytes hold one mu of all waves' accumulators in the epilogue
+    __shared__ __attribute__((aligned(16))) unsigned char s_raw[W_BYTES > PO_BYTES ? W_BYTES : PO_BYTES];
+    u32x4* s_W = reinterpret_cast<u32x4*>(s_raw);
+    f32x4* s_po = reinterpret_cast<f32x4*>(s_raw);
+    static_assert(LCAP * 4 == 3 * 256 && LCAP <= 256 && 16 * (DKP / 8) <= 256 && AXIS_NNZ <= 256, "one request per thread");
+
+    const int HG = P.H / P.hpw;
+    int tile, hg;
+    if (!tile_xcd_remap(blockIdx.x, P.n_tiles, HG, tile, hg)) return;   // whole workgroup
+    const int head0 = hg * P.hpw;
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, tn = lane & 15, g = lane >> 4;
+    // (components, accumulator slots and value rows of a wave as in tile_item)
+    constexpr int NP = NX / 2, NS = 1 + 2 * NP;
+    constexpr bool HAS_ODD = (NX & 1) || (n % NW != 0 && ((NX - 1) & 1));
+    const int nxw = n / NW + (wave < n % NW ? 1 : 0);
+    const int x0 = wave * (n / NW) + min(wave, n % NW);
+    const int npair = nxw >> 1;
+    const bool single = (nxw & 1) != 0;
+    const int N = P.cv.N, H = P.H;
+    const int t0 = tile * 16, nt = min(16, N - t0);
+    const int tslot = min(t0 + tn, N - 1);
+
+    // ---- everything the tile needs, requested together
+    const int4 hd = P.lists_hdr[tile];
+    const float4 tp = P.spos[tslot];
+    const uint32_t capd = CAP ? P.cap_d2[tslot] : 0xffffffffu;
+    const int capi = CAP ? P.cap_idx[tslot] : INT_MAX;
+    const int orow_mine = tid < 16 ? (t0 + tid < N ? P.cv.perm[t0 + tid] : -1) : 0;   // output rows of the targets
+    const float g_mine = tid < AXIS_NNZ ? P.G[AXIS_PACKED_AT + tid] : 0.0f;
+    const int ent_mine = tid < LCAP ? P.lists_ent[(size_t)tile * LCAP + tid] : 0;
+    float4 pos_mine[3];
+#pragma unroll
+    for (int j = 0; j < 3; ++j) pos_mine[j] = P.lists_pos[(size_t)tile * LCAP * 4 + tid + 256 * j];
+    // queries (16 targets x DKP binary16 of one head: one 16-byte piece per thread) and radial weights of a head
+    auto fetch_q = [&](int head) -> u32x4 {
+        const int tq = tid / (DKP / 8), f8 = tid % (DKP / 8);
+        return tid < 16 * (DKP / 8)
+                   ? *reinterpret_cast<const u32x4*>(P.q16 + ((size_t)min(t0 + tq, N - 1) * H + head) * DKP + 8 * f8)
+                   : (u32x4){0u, 0u, 0u, 0u};
+    };
+    auto fetch_wb = [&](int head) -> float { return lane < P.B ? P.WbT[lane * H + head] : 0.0f; };
+    u32x4 q_mine = fetch_q(head0);
+    float wb_mine = fetch_wb(head0);
+
+    const int cnt = hd.x;
+    if (cnt < 0) return;   // (whole workgroup) a crowded tile: k_tile_ovf builds its lists per head
+    const int my_pass = tn < nt ? ((tn < 8 ? hd.y : hd.z) >> (4 * (tn & 7))) & 15 : -1;
+    // ---- into LDS; what lies behind the list reads as groups without a valid slot, at a finite position
+    if (tid < LCAP) s_ent[tid] = tid < cnt ? ent_mine : 0;
+    if (tid < LENT - LCAP) s_ent[LCAP + tid] = 0;
+#pragma unroll
+    for (int j = 0; j < 3; ++j) {   // (selected by value, component by component: the compiler would otherwise choose
+        // between the addresses of two register arrays and move both into scratch memory)
+        const bool in_list = ((tid + 256 * j) >> 2) < cnt;
+        s_pos[tid + 256 * j] = make_float4(in_list ? pos_mine[j].x : tp.x, in_list ? pos_mine[j].y : tp.y,
+                                           in_list ? pos_mine[j].z : tp.z, in_list ? pos_mine[j].w : tp.w);
+    }
+    if (tid < (LENT - LCAP) * 4) s_pos[LCAP * 4 + tid] = tp;
+    if (tid < AXIS_NNZ) s_G[tid] = g_mine;
+    if (tid < 16) s_orow[tid] = orow_mine;
+    if (tid < 16 * (DKP / 8)) reinterpret_cast<u32x4*>(s_q)[tid] = q_mine;
+    __syncthreads();
+
+    const int nch = (cnt + 7) >> 3, ngr = (nch + NW - 1) / NW;
+    const float c_u = 2.0f * P.rbf_gamma * P.rbf_step * 1.44269504088896341f;
+    const float c_g = -P.rbf_gamma * 1.44269504088896341f;
+    const float bs = (float)lane * P.rbf_step;
+    const float rbf_mine = __expf(-P.rbf_gamma * bs * bs) * 1.44269504088896341f;
+
+    f16x8 kf[2][KS];
+    VRows<NP> vr;
+    auto load_K = [&](int c, int head) {
+#pragma unroll
+        for (int mt = 0; mt < 2; ++mt) {
+            const int e = s_ent[8 * c + 4 * mt + (tn >> 2)];
+            const size_t off = ((size_t)(4 * ((unsigned)e >> 8) + (tn & 3)) * H + head) * DKP + 8 * g;
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) kf[mt][ks] = *reinterpret_cast<const f16x8*>(P.k16 + off + 32 * ks);
+        }
+    };
+    // v rows of this wave's components for the lane's two entries (k = 8g..8g+3 from entry g of the chunk, 8g+4..8g+7
+    // from entry 4+g): the wave's single component, then its pairs (see e2f::v4_offset)
+    auto v_base = [&](int c, int head, const uint16_t*& ba, const uint16_t*& bb) {
+        const unsigned ea = (unsigned)s_ent[8 * c + g] >> 8, eb = (unsigned)s_ent[8 * c + 4 + g] >> 8;
+        ba = P.v4 + (((size_t)ea * H + head) * n + x0) * 64 + (single ? 64 : 0) + tn * 8;
+        bb = P.v4 + (((size_t)eb * H + head) * n + x0) * 64 + (single ? 64 : 0) + tn * 8;
+    };
+    auto first_rows = [&](int head) {   // the rows the streaming loop starts with
+        if (nch > 0) {
+            load_K(min(wave, nch - 1), head);
+            const uint16_t *ba, *bb;
+            v_base(0, head, ba, bb);
+            if (HAS_ODD && single) vr.load_single(ba - 64 - tn * 4, bb - 64 - tn * 4);
+#pragma unroll
+            for (int p = 0; p < NP; ++p)
+                if (p < npair) vr.load_pair(p, ba, bb);
+        }
+    };
+    first_rows(head0);
+
+    for (int hh = 0; hh < P.hpw; ++hh) {
+        const int head = head0 + hh;
+        // radial bias of this head as a polynomial in u = e^{2 gamma step d}:  b(d) = e^{-gamma d^2} sum_b cb[b] u^b,
+        // cb[b] = Wb[h][b] e^{-gamma (b step)^2} (log2 e folded in)
+        float cb[8];
+        {
+            const float mine = wb_mine * rbf_mine;
+#pragma unroll
+            for (int b = 0; b < 8; ++b) cb[b] = read_lane(mine, b);
+        }
+        f32x4 acc[3][NS];
+#pragma unroll
+        for (int mu = 0; mu < 3; ++mu)
+#pragma unroll
+            for (int x = 0; x < NS; ++x) acc[mu][x] = (f32x4){0.f, 0.f, 0.f, 0.f};
+        constexpr float M_NONE = -1.0e30f;   // finite, so that a masked logit (-inf) gets the weight 2^-inf = 0
+        float m_ref = M_NONE, z = 0.0f;
+
+        for (int G = 0; G < ngr; ++G) {
+            // ---- logits, pair geometry and cutoff mask of this wave's chunk
+            const int cm = NW * G + wave;
+            f32x4 S[2];
+            {
+                f16x8 qf[KS];
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) qf[ks] = *reinterpret_cast<const f16x8*>(s_q + tn * DKP + 32 * ks + 8 * g);
+#pragma unroll
+                for (int mt = 0; mt < 2; ++mt) {
+                    S[mt] = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                    for (int ks = 0; ks < KS; ++ks) S[mt] = mfma(kf[mt][ks], qf[ks], S[mt]);
+                }
+            }
+            load_K(min(cm + NW, nch - 1), head);   // k rows of this wave's chunk in the next group
+            float s2[8], gate[8];
+            float cmax = -INFINITY;
+#pragma unroll
+            for (int mt = 0; mt < 2; ++mt) {
+                const int ei = 8 * cm + 4 * mt + g;
+                const int e = s_ent[ei];
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int u = 4 * mt + r;
+                    const float4 pc = s_pos[ei * 4 + r];
+                    const float d2 = e2f::dist2_exact(tp.x, tp.y, tp.z, pc.x, pc.y, pc.z);
+                    // (bitwise on purpose: the eight candidates are evaluated side by side; the target itself is at
+                    // distance zero, an image of it at a box length: neither passes)
+                    const bool ok = (((e >> r) & 1) != 0) & (((e >> 4) & 15) == my_pass) & (d2 < P.rc2) & (d2 > 0.0f) &
+                                    (!CAP || e2f::under_cap(d2, pc.w, capd, capi));
+                    const float d = __builtin_amdgcn_sqrtf(d2);
+                    const float uu = __builtin_amdgcn_exp2f(c_u * d);
+                    float poly = cb[7];
+#pragma unroll
+                    for (int bb = 6; bb >= 0; --bb) poly = poly * uu + cb[bb];
+                    float bias = __builtin_amdgcn_exp2f(c_g * d2) * poly;
+                    // (evaluated for every candidate, not under its predicate: otherwise each of the eight
+                    // candidates becomes a basic block of its own and their LDS reads are issued one by one)
+                    asm("" : "+v"(bias));
+                    s2[u] = ok ? S[mt][r] + bias : -INFINITY;
+                    gate[u] = e2f::radial_gate(d, P.cutoff);
+                    cmax = fmaxf(cmax, s2[u]);
+                }
+            }
+            cmax = fmaxf(cmax, __shfl_xor(cmax, 16));
+            cmax = fmaxf(cmax, __shfl_xor(cmax, 32));
+            if (lane < 16) s_cmax[wave][lane] = cmax;
+            __syncthreads();
+            // ---- the group's largest logit per target, the same in all four waves
+            float gmax = s_cmax[0][tn];
+#pragma unroll
+            for (int w = 1; w < NW; ++w) gmax = fmaxf(gmax, s_cmax[w][tn]);
+            if (m_ref == M_NONE) m_ref = fmaxf(gmax, M_NONE);   // first neighbours: the accumulator rows are still zero
+            const bool move = gmax > m_ref + M_STEP;
+            if (__builtin_expect(__ballot(move) != 0ull, 0)) {
+                const float f = move ? __builtin_amdgcn_exp2f(m_ref - gmax) : 1.0f;
+                m_ref = move ? gmax : m_ref;
+                z *= f;
+                // Rows of the accumulators are targets: T <- diag(f) T on the matrix cores in fp32.  Slice r pairs
+                // A_r[i][g] = f_i [i == 4g + r] with B_r[g][j] = T[4g + r][j], register r of lane (j, g).
+                float ar[4];
+#pragma unroll
+                for (int r = 0; r < 4; ++r) ar[r] = tn == 4 * g + r ? f : 0.0f;
+#pragma unroll
+                for (int mu = 0; mu < 3; ++mu)
+#pragma unroll
+                    for (int x = 0; x < NS; ++x) {
+                        f32x4 d = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) d = __builtin_amdgcn_mfma_f32_16x16x4f32(ar[r], acc[mu][x][r], d, 0, 0, 0);
+                        acc[mu][x] = d;
+                    }
+            }
+            // ---- weights of this wave's chunk -> LDS
+            {
+                uint32_t wp[3][4];
+#pragma unroll
+                for (int u = 0; u < 8; u += 2) {
+                    float pg[2], rx[2], ry[2], rz[2];
+#pragma unroll
+                    for (int d = 0; d < 2; ++d) {
+                        const float p = __builtin_amdgcn_exp2f(s2[u + d] - m_ref);
+                        z += p;
+                        pg[d] = p * gate[u + d];
+                        const float4 pc = s_pos[(8 * cm + 4 * ((u + d) >> 2) + g) * 4 + ((u + d) & 3)];
+                        rx[d] = pc.x - tp.x;
+                        ry[d] = pc.y - tp.y;
+                        rz[d] = pc.z - tp.z;
+                    }
+                    wp[0][u >> 1] = pack_bf16(pg[0] * rx[0], pg[1] * rx[1]);
+                    wp[1][u >> 1] = pack_bf16(pg[0] * ry[0], pg[1] * ry[1]);
+                    wp[2][u >> 1] = pack_bf16(pg[0] * rz[0], pg[1] * rz[1]);
+                }
+#pragma unroll
+                for (int mu = 0; mu < 3; ++mu)
+                    s_W[(wave * 3 + mu) * 64 + lane] = (u32x4){wp[mu][0], wp[mu][1], wp[mu][2], wp[mu][3]};
+            }
+            __syncthreads();
+            // ---- aggregate the chunks of the group into this wave's components
+#pragma unroll
+            for (int cc = 0; cc < NW; ++cc) {
+                const int c = NW * G + cc;
+                if (c < nch) {
+                    bf16x8 W[3];
+#pragma unroll
+                    for (int mu = 0; mu < 3; ++mu) W[mu] = __builtin_bit_cast(bf16x8, s_W[(cc * 3 + mu) * 64 + lane]);
+                    const uint16_t *ba, *bb;   // the next chunk's rows replace each operand once it has been used
+                    v_base(min(c + 1, nch - 1), head, ba, bb);
+                    if (HAS_ODD && single) {   // (wave-uniform)
+                        const bf16x8 bv = vr.single();
+#pragma unroll
+                        for (int mu = 0; mu < 3; ++mu) acc[mu][0] = mfma(W[mu], bv, acc[mu][0]);
+                        vr.load_single(ba - 64 - tn * 4, bb - 64 - tn * 4);
+                    }
+#pragma unroll
+                    for (int p = 0; p < NP; ++p)
+                        if (p < npair) {   // (wave-uniform)
+                            const bf16x8 b0 = vr.first(p), b1 = vr.second(p);
+#pragma unroll
+                            for (int mu = 0; mu < 3; ++mu) acc[mu][1 + 2 * p] = mfma(W[mu], b0, acc[mu][1 + 2 * p]);
+#pragma unroll
+                            for (int mu = 0; mu < 3; ++mu) acc[mu][2 + 2 * p] = mfma(W[mu], b1, acc[mu][2 + 2 * p]);
+                            vr.load_pair(p, ba, bb);
+                        }
+                }
+            }
+        }
+
+        // ---- the next head's queries, radial weights and first rows are on their way during this head's epilogue
+        const bool more = hh + 1 < P.hpw;
+        if (more) {
+            q_mine = fetch_q(head + 1);
+            wb_mine = fetch_wb(head + 1);
+            first_rows(head + 1);
+        }
+        // ---- epilogue: out = (1/z) sum_mu G_mu T_mu.  For one mu at a time the waves put their T_mu components into
+        // LDS and every wave forms the output components x_out = wave (mod NW) from the non-zero entries of G_mu.  The
+        // code exists once per wave index, so that a wave's components and the pattern are compile-time facts.
+        z += __shfl_xor(z, 16);
+        z += __shfl_xor(z, 32);
+        if (lane < 16) s_z[wave][lane] = z;
+        auto finish = [&](auto wv_tag) {
+            constexpr int WV = decltype(wv_tag)::value;
+            constexpr int RO = (n - WV + NW - 1) / NW;                      // components WV, WV + NW, ...
+            constexpr int X0 = WV * (n / NW) + (WV < n % NW ? WV : n % NW);  // this wave's accumulator components
+            constexpr int NXW = n / NW + (WV < n % NW ? 1 : 0);
+            f32x4 pr[RO];
+#pragma unroll
+            for (int i = 0; i < RO; ++i) pr[i] = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int mu = 0; mu < 3; ++mu) {
+                __syncthreads();
+#pragma unroll
+                for (int x = 0; x < NXW; ++x) s_po[(X0 + x) * 64 + lane] = acc[mu][x + ((NXW & 1) ? 0 : 1)];
+                __syncthreads();
+#pragma unroll
+                for (int i = 0; i < RO; ++i) {
+#pragma unroll
+                    for (int xi = 0; xi < n; ++xi)
+                        if ((E2F_AXIS_NZ[mu][WV + NW * i] >> xi) & 1u)
+                            pr[i] += s_G[AXIS_INDEX.v[mu][WV + NW * i][xi]] * s_po[xi * 64 + lane];
+                }
+            }
+            f32x4 inv;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int tt = 4 * g + r;
+                float zt = 0.0f;
+#pragma unroll
+                for (int w = 0; w < NW; ++w) zt += s_z[w][tt];
+                inv[r] = zt > 0.0f ? 1.0f / zt : 0.0f;
+            }
+            // rows of the output: one base pointer per target row, components C floats apart
+            int orow[4];
+            float* orp[4];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                orow[r] = s_orow[4 * g + r];
+                orp[r] = P.out + (size_t)max(orow[r], 0) * n * P.C + head * 16 + tn;
+            }
+            const size_t cstride = (size_t)P.C;
+            if (nt == 16) {   // (uniform) every row exists: no per-row test
+#pragma unroll
+                for (int i = 0; i < RO; ++i)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) orp[r][(WV + NW * i) * cstride] = pr[i][r] * inv[r];
+            } else {
+#pragma unroll
+                for (int i = 0; i < RO; ++i)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r)
+                        if (orow[r] >= 0) orp[r][(WV + NW * i) * cstride] = pr[i][r] * inv[r];
+            }
+        };
+        const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+        if (wave_u == 0) finish(std::integral_constant<int, 0>{});
+        if (wave_u == 1) finish(std::integral_constant<int, 1>{});
+        if (wave_u == 2) finish(std::integral_constant<int, 2>{});
+        if (wave_u == 3) finish(std::integral_constant<int, 3>{});
+        if (more) {
+            // (every wave has left the streaming loop: the epilogue's barriers lie in between)
+            if (tid < 16 * (DKP / 8)) reinterpret_cast<u32x4*>(s_q)[tid] = q_mine;
+            __syncthreads();   // the new queries are in place; the partial outputs have been read
+        }
+    }
+}
+
+template <int L, int NW, bool PBC, int MODE, bool CAP>
+__global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(E2F_TILE_OCC(NW), E2F_TILE_OCC(NW)))) void k_tile(TileParams P) {
+    int tile, head;
+    if constexpr (MODE == 1) {
+        if (blockIdx.x == 0) {   // (whole workgroup) the first workgroup forms the axis operators instead
+            axis_ops<L>(P.cw, P.G_out, threadIdx.x, true);
+            return;
+        }
+        tile = blockIdx.x - 1;
+        head = 0;
+    } else {
+        if (!tile_xcd_remap(blockIdx.x, P.n_tiles, P.H, tile, head)) return;   // whole workgroup
+    }
+    tile_item<L, NW, PBC, MODE, CAP>(P, tile, head);
+}
+
+// The tiles whose candidate list did not fit the shared list area (the list kernel left their numbers in lists_ovf):
+// a fixed, small grid walks the (tile, head) items, each building its lists itself.  Usually there is none.
+template <int L, int NW, bool PBC, bool CAP>
+__global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(E2F_TILE_OCC(NW), E2F_TILE_OCC(NW)))) void k_tile_ovf(TileParams P) {
+    const int items = P.lists_ovf[0] * P.H;
+    for (int it = blockIdx.x; it < items; it += gridDim.x) {
+        tile_item<L, NW, PBC, 0, CAP>(P, P.lists_ovf[1 + it / P.H], it % P.H);
+        __syncthreads();   // the next item reuses the shared arrays
+    }
+}
+
 // what: 1 the list kernel (with the axis operators), 2 the attention kernel reading the lists, 0 the attention kernel
 // building its lists itself (after the axis-operator kernel)
 template <int L>
@@ -691,17 +1092,23 @@ void launch_L(const TileParams& P, const float* cw, float* G, int what, hipStrea
     const int grid = ((chunks + 7) / 8) * 8 * TILE_BLK * P.H;
     // four waves per workgroup, two workgroups per CU: with eight waves the 128 registers left per wave do not
     // hold a wave's accumulators, value rows and key rows without spilling into the streaming loop
-    if (what == 1) {
-        if (P.cv.periodic) k_tile<L, 4, true, 1><<<P.n_tiles + 1, 256, 0, st>>>(P);
-        else k_tile<L, 4, false, 1><<<P.n_tiles + 1, 256, 0, st>>>(P);
-    } else if (what == 2) {
-        if (P.cv.periodic) k_tile<L, 4, true, 2><<<grid, 256, 0, st>>>(P);
-        else k_tile<L, 4, false, 2><<<grid, 256, 0, st>>>(P);
-    } else {
-        k_axis_ops<L><<<1, 128, 0, st>>>(cw, G, true);
-        if (P.cv.periodic) k_tile<L, 4, true, 0><<<grid, 256, 0, st>>>(P);
-        else k_tile<L, 4, false, 0><<<grid, 256, 0, st>>>(P);
-    }
+    const bool cap = P.cap_d2 != nullptr;
+    auto go = [&](auto pbc, auto capped) {
+        constexpr bool PBC = decltype(pbc)::value, CAP = decltype(capped)::value;
+        if (what == 1) {
+            k_tile<L, 4, PBC, 1, CAP><<<P.n_tiles + 1, 256, 0, st>>>(P);
+        } else if (what == 2) {
+            const int hg_chunks = (P.n_tiles + TILE_BLK - 1) / TILE_BLK;
+            const int hgrid = ((hg_chunks + 7) / 8) * 8 * TILE_BLK * (P.H / P.hpw);
+            k_tile_heads<L, CAP><<<hgrid, 256, 0, st>>>(P);
+            k_tile_ovf<L, 4, PBC, CAP><<<256, 256, 0, st>>>(P);
+        } else {
+            k_axis_ops<L><<<1, 128, 0, st>>>(cw, G, true);
+            k_tile<L, 4, PBC, 0, CAP><<<grid, 256, 0, st>>>(P);
+        }
+    };
+    if (P.cv.periodic) cap ? go(std::true_type{}, std::true_type{}) : go(std::true_type{}, std::false_type{});
+    else cap ? go(std::false_type{}, std::true_type{}) : go(std::false_type{}, std::false_type{});
 }
 
 }  // namespace
@@ -736,9 +1143,14 @@ static e2f_status launch_tile(const e2f_ctx* ctx, const E2fCellsView& cv, const 
     P.lists_hdr = what == 0 ? nullptr : ws.lists_hdr;
     P.lists_ent = ws.lists_ent;
     P.lists_pos = ws.lists_pos;
+    P.lists_ovf = ws.lists_ovf;
     P.cw = ws.cw;
     P.G_out = ws.G;
     P.C = ctx->cfg.C; P.H = ctx->cfg.H; P.B = ctx->cfg.B; P.n_tiles = (cv.N + 15) / 16;
+    // heads per workgroup of the attention kernel: up to four, as long as about four rounds of workgroups are left
+    // for the chip (measured: two and four heads are 2 % ahead of one at 100 000 atoms, even at 10 000)
+    P.hpw = 1;
+    while (P.hpw < 4 && P.H % (P.hpw * 2) == 0 && (long)P.n_tiles * P.H / (P.hpw * 2) >= 2048) P.hpw *= 2;
     P.rc2 = ctx->rc2; P.cutoff = ctx->cfg.cutoff; P.rbf_step = ctx->rbf_step; P.rbf_gamma = ctx->rbf_gamma;
     switch (ctx->cfg.L_max) {
         case 1: launch_L<1>(P, ws.cw, ws.G, what, st); break;
