@@ -138,7 +138,6 @@ E2fAttnWs e2f_attn_ws_layout(const e2f_ctx* ctx, int32_t N, void* ws, int v_layo
     L.lists_hdr = nullptr;
     L.lists_ent = nullptr;
     L.lists_pos = nullptr;
-    L.lists_ovf = nullptr;
     if (v_layout == 2) {
         const size_t H = ctx->cfg.H, DKP = ((size_t)(ctx->cfg.L_max + 1) * 16 + 31) / 32 * 32;
         const size_t N4 = ((size_t)N + 3) / 4 * 4;
@@ -150,7 +149,6 @@ E2fAttnWs e2f_attn_ws_layout(const e2f_ctx* ctx, int32_t N, void* ws, int v_layo
         L.lists_hdr = (int4*)take(n_tiles * sizeof(int4));
         L.lists_ent = (int*)take(n_tiles * E2F_TILE_LCAP * 4);
         L.lists_pos = (float4*)take(n_tiles * E2F_TILE_LCAP * 4 * sizeof(float4));
-        L.lists_ovf = (int*)take((n_tiles + 1) * 4);
     } else {
         L.q = (float*)take((size_t)N * (ctx->cfg.L_max + 1) * ctx->cfg.C * 4);
         L.k = (float*)take((size_t)N * (ctx->cfg.L_max + 1) * ctx->cfg.C * 4);

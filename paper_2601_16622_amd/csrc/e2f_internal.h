@@ -91,7 +91,6 @@ struct E2fAttnWs {
     int4* lists_hdr;     // [ceil(N/16)]
     int* lists_ent;      // [ceil(N/16)][E2F_TILE_LCAP]
     float4* lists_pos;   // [ceil(N/16)][E2F_TILE_LCAP][4]
-    int* lists_ovf;      // [1 + ceil(N/16)] number of tiles whose list did not fit, then those tiles
     size_t bytes;
 };
 #define E2F_TILE_LCAP 192

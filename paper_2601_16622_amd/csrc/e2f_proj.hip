@@ -30,10 +30,9 @@ struct CoefTable {
 // spos[slot] = position of the atom in that slot (w carries its index in the caller's order); cw[comp][t] = P coefficient times its path weight.
 __global__ void k_prepare(E2fCellsView cv, const float* __restrict__ pos, const float* __restrict__ w_path, int L,
                           int lf, CoefTable tab, float4* __restrict__ spos, float* __restrict__ cw,
-                          const float* __restrict__ Wb, int H, int B, float* __restrict__ wbT, int* __restrict__ ovf) {
+                          const float* __restrict__ Wb, int H, int B, float* __restrict__ wbT) {
     const int t = blockIdx.x * blockDim.x + threadIdx.x;
     if (t < H * B) wbT[(t % B) * H + t / B] = Wb[t];
-    if (t == 0 && ovf) ovf[0] = 0;   // no tile of the tile kernel has overflowed its candidate list yet
     if (t < cv.N) {
         const int a = cv.perm[t];
         float x = pos[3 * a], y = pos[3 * a + 1], z = pos[3 * a + 2];
@@ -924,7 +923,7 @@ e2f_status e2f_launch_prepare(const e2f_ctx* ctx, const E2fCellsView& cv, const 
     int work = cv.N > ctx->n * E2F_NP ? cv.N : ctx->n * E2F_NP;
     if (ctx->cfg.H * ctx->cfg.B > work) work = ctx->cfg.H * ctx->cfg.B;
     k_prepare<<<(work + 255) / 256, 256, 0, st>>>(cv, pos, w->w_path, ctx->cfg.L_max, ctx->cfg.lf, tab, ws.spos, ws.cw,
-                                                 w->Wb, ctx->cfg.H, ctx->cfg.B, ws.wbT, ws.lists_ovf);
+                                                 w->Wb, ctx->cfg.H, ctx->cfg.B, ws.wbT);
     E2F_HIP_CHECK(hipGetLastError());
     return E2F_OK;
 }

@@ -38,7 +38,10 @@ typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 constexpr int CAPG = 256;      // candidate groups (of four slots) held in LDS per batch
 constexpr int LCAP = E2F_TILE_LCAP;   // entries of a precomputed list; longer lists are built in the kernel
 static_assert(LCAP <= CAPG, "a precomputed list must fit the list area in LDS");
-constexpr int TILE_BLK = 16;   // consecutive tiles whose (tile, head) items form one XCD chunk, head-major
+#ifndef E2F_TILE_BLK
+#define E2F_TILE_BLK 16
+#endif
+constexpr int TILE_BLK = E2F_TILE_BLK;   // consecutive tiles whose (tile, head) items form one XCD chunk, head-major
 #ifndef E2F_TILE_OCC
 #define E2F_TILE_OCC(NW) ((NW) / 2)
 #endif
@@ -85,7 +88,6 @@ struct TileParams {
     int4* lists_hdr;
     int* lists_ent;
     float4* lists_pos;
-    int* lists_ovf;    // [0]: number of tiles whose list did not fit, then their numbers
     int hpw;           // heads per workgroup of k_tile_heads
     const float* cw;   // the list kernel's first workgroup forms the axis operators instead: G_out from cw
     float* G_out;
@@ -181,7 +183,7 @@ __global__ void k_axis_ops(const float* __restrict__ cw, float* __restrict__ G, 
 // MODE 0: lists built here, per (tile, head).  MODE 1: one workgroup per tile only builds the tile's list and writes it
 // out (no head, no streaming): the passes' lists one after the other, every entry tagged with its pass, so that a
 // candidate counts only for the targets of the pass that found it (k_tile_heads reads those lists; tiles whose list
-// does not fit LCAP entries come back here in MODE 0 through k_tile_ovf).
+// does not fit LCAP entries are finished by the list kernel's own workgroup, head by head, in MODE 0).
 // CAP: whether a neighbour cap is in force (threshold keys per target).
 template <int L, int NW, bool PBC, int MODE, bool CAP>
 __device__ __forceinline__ void tile_item(const TileParams& P, const int tile, const int head) {
@@ -636,7 +638,23 @@ __device__ __forceinline__ void tile_item(const TileParams& P, const int tile, c
                 hi |= (8 + i < nt ? (unsigned)s_tpass[8 + i] : 0u) << (4 * i);
             }
             P.lists_hdr[tile] = make_int4(overflow ? -1 : out_cnt, (int)lo, (int)hi, 0);
-            if (overflow) P.lists_ovf[1 + atomicAdd(P.lists_ovf, 1)] = tile;   // left to k_tile_ovf
+        }
+        if (overflow) {
+            // (uniform) A crowded tile: its list does not fit the shared area, k_tile_heads will skip it.  This
+            // workgroup runs the tile's heads itself, one after the other, building the lists per head.  The axis
+            // operators of this launch may not be there yet (another workgroup forms them), so it forms its own
+            // copy in the tile's list area, which stays unused.
+            float* own_G = reinterpret_cast<float*>(P.lists_pos + (size_t)tile * LCAP * 4);
+            static_assert((size_t)LCAP * 4 * sizeof(float4) >= (AXIS_PACKED_AT + AXIS_NNZ) * sizeof(float), "room for the operators");
+            axis_ops<L>(P.cw, own_G, threadIdx.x, true);
+            __threadfence_block();
+            __syncthreads();
+            TileParams Q = P;
+            Q.G = own_G;
+            for (int h = 0; h < P.H; ++h) {
+                tile_item<L, NW, PBC, 0, CAP>(Q, tile, h);
+                __syncthreads();   // the next head reuses the shared arrays
+            }
         }
         return;
     }
@@ -776,7 +794,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     float wb_mine = fetch_wb(head0);
 
     const int cnt = hd.x;
-    if (cnt < 0) return;   // (whole workgroup) a crowded tile: k_tile_ovf builds its lists per head
+    if (cnt < 0) return;   // (whole workgroup) a crowded tile: the list kernel has done it, with lists per head
     const int my_pass = tn < nt ? ((tn < 8 ? hd.y : hd.z) >> (4 * (tn & 7))) & 15 : -1;
     // ---- into LDS; what lies behind the list reads as groups without a valid slot, at a finite position
     if (tid < LCAP) s_ent[tid] = tid < cnt ? ent_mine : 0;
@@ -1073,17 +1091,6 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(E2F_TIL
     tile_item<L, NW, PBC, MODE, CAP>(P, tile, head);
 }
 
-// The tiles whose candidate list did not fit the shared list area (the list kernel left their numbers in lists_ovf):
-// a fixed, small grid walks the (tile, head) items, each building its lists itself.  Usually there is none.
-template <int L, int NW, bool PBC, bool CAP>
-__global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(E2F_TILE_OCC(NW), E2F_TILE_OCC(NW)))) void k_tile_ovf(TileParams P) {
-    const int items = P.lists_ovf[0] * P.H;
-    for (int it = blockIdx.x; it < items; it += gridDim.x) {
-        tile_item<L, NW, PBC, 0, CAP>(P, P.lists_ovf[1 + it / P.H], it % P.H);
-        __syncthreads();   // the next item reuses the shared arrays
-    }
-}
-
 // what: 1 the list kernel (with the axis operators), 2 the attention kernel reading the lists, 0 the attention kernel
 // building its lists itself (after the axis-operator kernel)
 template <int L>
@@ -1101,7 +1108,6 @@ void launch_L(const TileParams& P, const float* cw, float* G, int what, hipStrea
             const int hg_chunks = (P.n_tiles + TILE_BLK - 1) / TILE_BLK;
             const int hgrid = ((hg_chunks + 7) / 8) * 8 * TILE_BLK * (P.H / P.hpw);
             k_tile_heads<L, CAP><<<hgrid, 256, 0, st>>>(P);
-            k_tile_ovf<L, 4, PBC, CAP><<<256, 256, 0, st>>>(P);
         } else {
             k_axis_ops<L><<<1, 128, 0, st>>>(cw, G, true);
             k_tile<L, 4, PBC, 0, CAP><<<grid, 256, 0, st>>>(P);
@@ -1143,7 +1149,6 @@ static e2f_status launch_tile(const e2f_ctx* ctx, const E2fCellsView& cv, const 
     P.lists_hdr = what == 0 ? nullptr : ws.lists_hdr;
     P.lists_ent = ws.lists_ent;
     P.lists_pos = ws.lists_pos;
-    P.lists_ovf = ws.lists_ovf;
     P.cw = ws.cw;
     P.G_out = ws.G;
     P.C = ctx->cfg.C; P.H = ctx->cfg.H; P.B = ctx->cfg.B; P.n_tiles = (cv.N + 15) / 16;
