@@ -238,6 +238,13 @@ __device__ __forceinline__ float radial_basis(float d, int b, float step, float 
     return __expf(-gamma * t * t);
 }
 
+// Key rows of the tile attention kernel (binary16, DKP = 32 KS features per head, zero-padded): per (group of four
+// slots, head) a block [KS][4 slots][32 features], so that the 16 lanes that fetch one 32-feature step of a group's
+// four rows read 256 contiguous bytes.  Returns the offset, in elements, of (slot, head, feature f).
+__host__ __device__ __forceinline__ size_t k16_offset(size_t slot, int H, int head, int DKP, int f) {
+    return (((slot >> 2) * H + head) * (DKP >> 5) + (f >> 5)) * 128 + (slot & 3) * 32 + (f & 31);
+}
+
 // Value rows of the tile attention kernel: per (group of four slots, head) a block of n * 64 bf16.  The n components are
 // split among the four waves of a workgroup (n / 4 each, the first n % 4 waves one more, contiguous ranges); inside a
 // wave's range an odd first component stands alone as [16 channels][4 slots] and the others go in pairs as

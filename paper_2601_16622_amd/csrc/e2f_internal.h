@@ -84,8 +84,8 @@ struct E2fAttnWs {
     const int32_t* cap_idx;
     // layout of the tile attention kernel (v_layout 2; q, k, v above are then unused)
     uint16_t* q16;       // [N][H][DKP] binary16, q * tau * log2(e)
-    uint16_t* k16;       // [4*ceil(N/4)][H][DKP] binary16
-    uint16_t* v4;        // [ceil(N/4)][H][n][16 channels][4 slots] bf16
+    uint16_t* k16;       // [ceil(N/4)][H][DKP/32][4 slots][32] binary16 (e2f::k16_offset)
+    uint16_t* v4;        // [ceil(N/4)][H] blocks of n * 64 bf16, components alone or in pairs (e2f::v4_offset)
     float* G;            // [3][25][25] axis operators of the degree-1 filter, then their 216 pattern entries packed
     // candidate lists of the tile kernel, one per tile of 16 sorted slots (see TileParams)
     int4* lists_hdr;     // [ceil(N/16)]

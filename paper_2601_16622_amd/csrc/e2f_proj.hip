@@ -540,7 +540,7 @@ __global__ __launch_bounds__(64 * WG_WAVES) void k_project_wg(E2fCellsView cv, c
                 kv[i] = to_f16_sat(real ? s_k[a * (E2F_MAX_L + 1) * 16 + f0 + i] : 0.0f);
             }
             const size_t dst = (slot * NCT + ct) * go.DKP + f0;
-            *reinterpret_cast<h16x8*>(go.k16 + dst) = kv;
+            *reinterpret_cast<h16x8*>(go.k16 + e2f::k16_offset(slot, NCT, ct, go.DKP, f0)) = kv;
             if (a < n_atoms) *reinterpret_cast<h16x8*>(go.q16 + dst) = qv;
         }
         return;
@@ -710,12 +710,12 @@ __global__ __launch_bounds__(64 * (C / 16 + 1)) void k_project_sh(E2fCellsView c
             }
             const size_t dst = ((size_t)slot * NCT + ct) * go.DKP + l * 16 + 4 * g;
             if (slot < N) *reinterpret_cast<h16x4*>(go.q16 + dst) = qv;
-            if (slot < N4) *reinterpret_cast<h16x4*>(go.k16 + dst) = kv;
+            if (slot < N4) *reinterpret_cast<h16x4*>(go.k16 + e2f::k16_offset(slot, NCT, ct, go.DKP, l * 16 + 4 * g)) = kv;
             if (l == L && go.DKP > DK) {   // padding features read as zero
                 const h16x4 zero = {(_Float16)0.0f, (_Float16)0.0f, (_Float16)0.0f, (_Float16)0.0f};
                 const size_t dz = ((size_t)slot * NCT + ct) * go.DKP + DK + 4 * g;
                 if (slot < N) *reinterpret_cast<h16x4*>(go.q16 + dz) = zero;
-                if (slot < N4) *reinterpret_cast<h16x4*>(go.k16 + dz) = zero;
+                if (slot < N4) *reinterpret_cast<h16x4*>(go.k16 + e2f::k16_offset(slot, NCT, ct, go.DKP, DK + 4 * g)) = zero;
             }
             qacc = (f32x4){0.f, 0.f, 0.f, 0.f};
             kacc = (f32x4){0.f, 0.f, 0.f, 0.f};

@@ -472,9 +472,9 @@ __device__ __forceinline__ void tile_item(const TileParams& P, const int tile, c
 #pragma unroll
                     for (int mt = 0; mt < 2; ++mt) {
                         const int e = s_ent[8 * c + 4 * mt + (tn >> 2)];
-                        const size_t off = ((size_t)(4 * ((unsigned)e >> 8) + (tn & 3)) * H + head) * DKP + 8 * g;
+                        const size_t off = e2f::k16_offset(4 * (size_t)((unsigned)e >> 8) + (tn & 3), H, head, DKP, 8 * g);
 #pragma unroll
-                        for (int ks = 0; ks < KS; ++ks) kf[mt][ks] = *reinterpret_cast<const f16x8*>(P.k16 + off + 32 * ks);
+                        for (int ks = 0; ks < KS; ++ks) kf[mt][ks] = *reinterpret_cast<const f16x8*>(P.k16 + off + 128 * ks);
                     }
                 };
                 // v rows of this wave's components for the lane's two entries (k = 8g..8g+3 from entry g of the chunk,
@@ -824,9 +824,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 #pragma unroll
         for (int mt = 0; mt < 2; ++mt) {
             const int e = s_ent[8 * c + 4 * mt + (tn >> 2)];
-            const size_t off = ((size_t)(4 * ((unsigned)e >> 8) + (tn & 3)) * H + head) * DKP + 8 * g;
+            const size_t off = e2f::k16_offset(4 * (size_t)((unsigned)e >> 8) + (tn & 3), H, head, DKP, 8 * g);
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks) kf[mt][ks] = *reinterpret_cast<const f16x8*>(P.k16 + off + 32 * ks);
+            for (int ks = 0; ks < KS; ++ks) kf[mt][ks] = *reinterpret_cast<const f16x8*>(P.k16 + off + 128 * ks);
         }
     };
     // v rows of this wave's components for the lane's two entries (k = 8g..8g+3 from entry g of the chunk, 8g+4..8g+7
