@@ -158,7 +158,7 @@ def main():
     bf16 = cfg["dtype"] == "bf16"
     mc_ok = bf16 and cfg["C"] // cfg["H"] == 16 and cfg["L"] >= 1
     if mc_ok and cfg["lf"] == 1 and cfg["C"] in (32, 64, 128):
-        kernel = "k_tile"
+        kernel = "k_tile_heads"
     elif mc_ok and cfg["lf"] in (1, 2) and cfg["H"] in (1, 2, 4, 8):
         kernel = "k_fused_mfma"
     else:
@@ -194,10 +194,10 @@ def main():
                 "stage_ms": {k: round(v, 4) for k, v in stage_ms.items()}}
     if bound == "alu":
         roofline["frac_of_plain_fma_peak"] = round(achieved / PEAK_ALU_PLAIN_FMA_TFLOPS, 4)
-    if kernel == "k_tile":
+    if kernel == "k_tile_heads":
         # what the kernel executes (matrix-core instructions over all candidate slots, masked ones included), from the
         # committed counter summary of the same workload
-        sq = read_counters("k_tile<4, 4, false, 2>")
+        sq = read_counters("k_tile_heads<4, false>")
         useful = E * cfg["H"] * (2 * (Lm + 1) * 16 + 3 * n * 16 * 2)
         if sq.get("SQ_INSTS_MFMA"):
             roofline["executed"] = {

@@ -43,7 +43,7 @@ def pmc(fetch_db, write_db, copy_bytes):
         f = fetch[name][1] * f_scale * 1024 / 1e6
         w = write.get(name, (0, 0, 0))[1] * w_scale * 1024 / 1e6
         print(f"{fetch[name][0]:10d} {f:12.2f} {w:12.2f}  {name[:100]}")
-        if not marked and ("k_tile" in name or "k_fused" in name):   # the attention kernel of the timed path
+        if not marked and ("k_tile_heads" in name or "k_fused" in name):   # the attention kernel of the timed path
             print(f"traffic_bytes_per_launch: {(f + w) * 1e6:.0f}")
             marked = True
 
