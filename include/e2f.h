@@ -224,9 +224,11 @@ e2f_status e2f_attn_forward_capped(e2f_ctx *ctx, const e2f_cells *cells, const f
  * e2f_build_neighbor_table fills table[i][0 .. count[i]) (device, int32 [N][K], caller's atom numbering) with the at
  * most K nearest atoms of atom i inside the cutoff (same selection as the cap above, order within a row unspecified
  * but deterministic) and the rest of the row with -1; count (device int32 [N]) may be null.
- * e2f_attn_forward_table evaluates the operator with N(i) = the atoms listed in row i (entries < 0, entries equal to
- * i and entries at zero distance are skipped; the cutoff is not re-applied, so the rows should hold atoms inside
- * it; entries must be atoms of the same call).  The pair geometry is still built from pos inside the kernel.
+ * e2f_attn_forward_table evaluates the operator with N(i) = the atoms listed in row i that lie inside the cutoff
+ * (Sec. 3.4: neighbours within the cutoff; entries < 0, entries equal to i, entries at zero distance and entries at or
+ * beyond the cutoff are skipped; entries must be atoms of the same call and a row must not name an atom twice).  The
+ * pair geometry is still built from pos inside the kernel; where the tile kernel applies, the table becomes a mask on
+ * the tile's candidate list and the call runs on the matrix cores like e2f_attn_forward.
  * Workspace: e2f_attn_table_workspace_bytes.  Both allocate nothing and do not synchronise.
  */
 e2f_status e2f_build_neighbor_table(e2f_ctx *ctx, const e2f_cells *cells, const float *pos, int32_t N, int32_t K,

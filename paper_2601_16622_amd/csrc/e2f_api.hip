@@ -138,6 +138,7 @@ E2fAttnWs e2f_attn_ws_layout(const e2f_ctx* ctx, int32_t N, void* ws, int v_layo
     L.lists_hdr = nullptr;
     L.lists_ent = nullptr;
     L.lists_pos = nullptr;
+    L.lists_mask = nullptr;
     if (v_layout == 2) {
         const size_t H = ctx->cfg.H, DKP = ((size_t)(ctx->cfg.L_max + 1) * 16 + 31) / 32 * 32;
         const size_t N4 = ((size_t)N + 3) / 4 * 4;
@@ -149,6 +150,7 @@ E2fAttnWs e2f_attn_ws_layout(const e2f_ctx* ctx, int32_t N, void* ws, int v_layo
         L.lists_hdr = (int4*)take(n_tiles * sizeof(int4));
         L.lists_ent = (int*)take(n_tiles * E2F_TILE_LCAP * 4);
         L.lists_pos = (float4*)take(n_tiles * E2F_TILE_LCAP * 4 * sizeof(float4));
+        L.lists_mask = (unsigned long long*)take(n_tiles * E2F_TILE_LCAP * 8);
     } else {
         L.q = (float*)take((size_t)N * (ctx->cfg.L_max + 1) * ctx->cfg.C * 4);
         L.k = (float*)take((size_t)N * (ctx->cfg.L_max + 1) * ctx->cfg.C * 4);
@@ -415,8 +417,8 @@ static e2f_status forward_impl(e2f_ctx* ctx, const e2f_cells* cells, const float
     if (rc != E2F_OK || N == 0) return rc;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     if (cells->view.periodic && table) return E2F_ERR_UNSUPPORTED;   // the table names atoms, not images
-    // the table form runs on the ALU kernel, which reads the plain layout
-    const int v_layout = table ? 0 : e2f_v_layout(ctx);
+    // the table form runs on the tile kernel where that applies, else on the ALU kernel, which reads the plain layout
+    const int v_layout = (table && !ctx->use_tile_attn) ? 0 : e2f_v_layout(ctx);
     E2fAttnWs L = e2f_attn_ws_layout(ctx, N, ws, v_layout);
     if (cap_K > 0) {
         if (ws_bytes < L.bytes + 2 * e2f_align_up((size_t)N * 4)) return E2F_ERR_WORKSPACE_TOO_SMALL;
@@ -434,8 +436,8 @@ static e2f_status forward_impl(e2f_ctx* ctx, const e2f_cells* cells, const float
     if (ev) E2F_HIP_CHECK(hipEventRecord(ev[1], st));
     if ((rc = e2f_launch_project_mfma(ctx, cells->view, h, w, L, v_layout, st)) != E2F_OK) return rc;
     if (ev) E2F_HIP_CHECK(hipEventRecord(ev[2], st));
-    rc = table                ? e2f_launch_fused_table(ctx, cells->view, w, L, table, table_K, out, st)
-         : ctx->use_tile_attn ? e2f_launch_tile(ctx, cells->view, L, out, st)
+    rc = ctx->use_tile_attn   ? e2f_launch_tile(ctx, cells->view, L, table, table_K, out, st)
+         : table              ? e2f_launch_fused_table(ctx, cells->view, w, L, table, table_K, out, st)
          : ctx->use_mfma_attn ? e2f_launch_fused_mfma(ctx, cells->view, w, L, out, st)
                               : e2f_launch_fused(ctx, cells->view, w, L, out, st);
     if (rc != E2F_OK) return rc;

@@ -91,7 +91,7 @@ __global__ __launch_bounds__(64) void k_fused_valu(FusedParams P) {
             bool ok = false;
             if (j >= 0 && j != t) {
                 const float4 pj = P.spos[j];
-                ok = e2f::dist2_exact(pi.x, pi.y, pi.z, pj.x, pj.y, pj.z) > 0.0f;
+                ok = e2f::is_neighbor(e2f::dist2_exact(pi.x, pi.y, pi.z, pj.x, pj.y, pj.z), P.rc2);
             }
             const unsigned long long mask = __ballot(ok);
             if (ok) s_list[cnt + __popcll(mask & ((1ull << lane) - 1ull))] = j;

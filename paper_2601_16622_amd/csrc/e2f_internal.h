@@ -91,6 +91,7 @@ struct E2fAttnWs {
     int4* lists_hdr;     // [ceil(N/16)]
     int* lists_ent;      // [ceil(N/16)][E2F_TILE_LCAP]
     float4* lists_pos;   // [ceil(N/16)][E2F_TILE_LCAP][4]
+    unsigned long long* lists_mask;   // [ceil(N/16)][E2F_TILE_LCAP] the (target, slot) pairs of an entry that count
     size_t bytes;
 };
 #define E2F_TILE_LCAP 192
@@ -176,7 +177,9 @@ e2f_status e2f_launch_backward(const e2f_ctx* ctx, const E2fCellsView& cv, const
                                float* grad_Wb, float* grad_w_path, float* grad_W, hipStream_t st);
 // cw[comp][t] = P coefficient with every path weight one.
 e2f_status e2f_launch_unit_cw(const e2f_ctx* ctx, float* cw, hipStream_t st);
-e2f_status e2f_launch_tile(const e2f_ctx* ctx, const E2fCellsView& cv, const E2fAttnWs& ws, float* out, hipStream_t st);
+// table: the caller's padded neighbour table [N][table_K], or null (every atom within the cutoff is a neighbour)
+e2f_status e2f_launch_tile(const e2f_ctx* ctx, const E2fCellsView& cv, const E2fAttnWs& ws, const int32_t* table,
+                           int table_K, float* out, hipStream_t st);
 e2f_status e2f_launch_fused_mfma(const e2f_ctx* ctx, const E2fCellsView& cv, const e2f_weights* w, const E2fAttnWs& ws,
                                  float* out, hipStream_t st);
 e2f_status e2f_run_materialized(const e2f_ctx* ctx, const E2fCellsView& cv, const float* pos, const void* h,

@@ -88,6 +88,11 @@ struct TileParams {
     int4* lists_hdr;
     int* lists_ent;
     float4* lists_pos;
+    unsigned long long* lists_mask;   // per list entry: which (target, slot) pairs count, bit 4 * target + slot
+    // the caller's padded neighbour table [N][table_K] (atom numbers, < 0 = empty), or null: then N(i) is every atom
+    // within the cutoff; with a table it is the listed atoms among those
+    const int32_t* table;
+    int table_K;
     int hpw;           // heads per workgroup of k_tile_heads
     const float* cw;   // the list kernel's first workgroup forms the axis operators instead: G_out from cw
     float* G_out;
@@ -201,6 +206,9 @@ __device__ __forceinline__ void tile_item(const TileParams& P, const int tile, c
     __shared__ float s_cmax[NW][16];
     __shared__ float s_z[NW][16];
     __shared__ int s_cnt[NW];
+    // which (target, slot) pairs of a list entry count, bit 4 * target + slot: the valid slots for every target of the
+    // entry's pass, or, with a neighbour table, the listed atoms
+    __shared__ unsigned long long s_mask[CAPG + PADE];
     __shared__ float4 s_tgt[16];   // the pass's targets: position and squared reach (0: not in this pass)
     // periodic boundaries: the pass's candidate runs (first and last slot, slot groups before the run, translation)
     constexpr int NRUN = PBC ? 27 : 9;
@@ -257,7 +265,6 @@ __device__ __forceinline__ void tile_item(const TileParams& P, const int tile, c
                 *reinterpret_cast<const u32x4*>(P.q16 + ((size_t)min(t0 + tq, N - 1) * H + head) * DKP + 8 * f8);
         }
     }
-    int my_pass = -1;
     // MODE 1: entries written so far, whether they still fit, the pass of every target
     int out_cnt = 0, pidx = 0;
     bool overflow = false;
@@ -282,7 +289,8 @@ __device__ __forceinline__ void tile_item(const TileParams& P, const int tile, c
         const unsigned stop = ~bits & ((1u << nt) - 1u) & ~((1u << a) - 1u);
         const int b = stop ? __builtin_ctz(stop) : nt;
         const bool t_active = tn >= a && tn < b;
-        my_pass = t_active ? (MODE == 1 ? pidx : 0) : -1;
+        // a one in the lowest bit of every target of this pass: times an entry's valid slots it gives the entry's mask
+        const unsigned long long pass_nibbles = 0x1111111111111111ull & ((b == 16 ? ~0ull : (1ull << (4 * b)) - 1ull) & ~((1ull << (4 * a)) - 1ull));
         if (MODE == 1 && t_active && threadIdx.x < 16) s_tpass[threadIdx.x] = pidx;
         const int cxa = __builtin_amdgcn_readlane(tcx, a), cxb = __builtin_amdgcn_readlane(tcx, b - 1);
         // Runs of sorted slots that hold the pass's candidates: rows 0..8 are the stencil rows over the cells
@@ -443,11 +451,33 @@ __device__ __forceinline__ void tile_item(const TileParams& P, const int tile, c
                 const int sh = lane & ~3;
                 const int e = e0 + __popcll(leaders[u] & ((1ull << sh) - 1ull));
                 if (near4[u] != 0u) {
-                    if ((lane & 3) == 0) s_ent[e] = (int)(((unsigned)grp[u] << 8) | ((MODE == 1 ? (unsigned)pidx : 0u) << 4) | valid4[u]);
+                    if ((lane & 3) == 0) {
+                        s_ent[e] = (int)(((unsigned)grp[u] << 8) | ((MODE == 1 ? (unsigned)pidx : 0u) << 4) | valid4[u]);
+                        s_mask[e] = P.table ? 0ull : (unsigned long long)valid4[u] * pass_nibbles;
+                    }
                     s_pos[e * 4 + (lane & 3)] = pj[u];
                 }
                 e0 += __popcll(leaders[u]);
             }
+            }
+            if (P.table) {
+                // ---- neighbour table: the listed atoms of the pass's targets, looked up in the batch (an atom outside
+                // the cutoff has no entry there and is skipped, like an empty table entry or the target itself)
+                __syncthreads();
+                const int K = P.table_K;
+                for (int x = threadIdx.x; x < (b - a) * K; x += 64 * NW) {
+                    const int i = a + x / K;
+                    const int ai = P.cv.perm[t0 + i];
+                    const int nb = P.table[(size_t)ai * K + x % K];
+                    if (nb >= 0 && nb < N && nb != ai) {
+                        const int sj = P.cv.atom_slot[nb];
+                        for (int e = 0; e < cnt; ++e)   // (a group on the border of two runs has an entry in each)
+                            if ((int)((unsigned)s_ent[e] >> 8) == (sj >> 2) && ((s_ent[e] >> (sj & 3)) & 1)) {
+                                atomicOr(&s_mask[e], 1ull << (4 * i + (sj & 3)));
+                                break;
+                            }
+                    }
+                }
             }
             if constexpr (MODE == 1) {
                 // ---- the list kernel: append the batch to the tile's list in memory
@@ -458,12 +488,16 @@ __device__ __forceinline__ void tile_item(const TileParams& P, const int tile, c
                     float4* gp = P.lists_pos + ((size_t)tile * LCAP + out_cnt) * 4;
                     for (int i = threadIdx.x; i < cnt; i += 64 * NW) ge[i] = s_ent[i];
                     for (int i = threadIdx.x; i < 4 * cnt; i += 64 * NW) gp[i] = s_pos[i];
+                    for (int i = threadIdx.x; i < cnt; i += 64 * NW) P.lists_mask[(size_t)tile * LCAP + out_cnt + i] = s_mask[i];
                     out_cnt += cnt;
                 }
                 continue;
             }
             // pad to whole groups of four chunks: entries of group 0 with no valid slot, finite positions
-            for (int i = threadIdx.x; i < PADE; i += 64 * NW) s_ent[cnt + i] = 0;
+            for (int i = threadIdx.x; i < PADE; i += 64 * NW) {
+                s_ent[cnt + i] = 0;
+                s_mask[cnt + i] = 0ull;
+            }
             for (int i = threadIdx.x; i < PADE * 4; i += 64 * NW) s_pos[cnt * 4 + i] = tp;
             __syncthreads();
             const int nch = (cnt + 7) >> 3, ngr = (nch + NW - 1) / NW;
@@ -516,7 +550,7 @@ __device__ __forceinline__ void tile_item(const TileParams& P, const int tile, c
 #pragma unroll
                     for (int mt = 0; mt < 2; ++mt) {
                         const int ei = 8 * cm + 4 * mt + g;
-                        const int e = s_ent[ei];
+                        const unsigned mine4 = (unsigned)(s_mask[ei] >> (4 * tn));   // this target's four slots of the entry
 #pragma unroll
                         for (int r = 0; r < 4; ++r) {
                             const int u = 4 * mt + r;
@@ -524,8 +558,8 @@ __device__ __forceinline__ void tile_item(const TileParams& P, const int tile, c
                             const float d2 = e2f::dist2_exact(tp.x, tp.y, tp.z, pc.x, pc.y, pc.z);
                             // (bitwise on purpose: the eight candidates are evaluated side by side; the target itself
                             // is at distance zero, an image of it at a box length: neither passes)
-                            const bool ok = (((e >> r) & 1) != 0) & (((e >> 4) & 15) == my_pass) &
-                                            (d2 < P.rc2) & (d2 > 0.0f) & (!CAP || e2f::under_cap(d2, pc.w, capd, capi));
+                            const bool ok = (((mine4 >> r) & 1u) != 0u) & (d2 < P.rc2) & (d2 > 0.0f) &
+                                            (!CAP || e2f::under_cap(d2, pc.w, capd, capi));
                             const float d = __builtin_amdgcn_sqrtf(d2);
                             const float uu = __builtin_amdgcn_exp2f(c_u * d);
                             float poly = cb[7];
@@ -743,6 +777,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     constexpr int LENT = LCAP + 8 * NW;   // the list, padded to whole groups of four chunks
     constexpr int W_BYTES = NW * 3 * 64 * 16, PO_BYTES = n * 64 * 16;
     __shared__ int s_ent[LENT];
+    __shared__ unsigned long long s_mask[LENT];
     __shared__ float4 s_pos[LENT * 4];
     __shared__ __attribute__((aligned(16))) uint16_t s_q[16 * DKP];
     __shared__ float s_G[AXIS_NNZ];
@@ -779,6 +814,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     const int orow_mine = tid < 16 ? (t0 + tid < N ? P.cv.perm[t0 + tid] : -1) : 0;   // output rows of the targets
     const float g_mine = tid < AXIS_NNZ ? P.G[AXIS_PACKED_AT + tid] : 0.0f;
     const int ent_mine = tid < LCAP ? P.lists_ent[(size_t)tile * LCAP + tid] : 0;
+    const unsigned long long mask_mine = tid < LCAP ? P.lists_mask[(size_t)tile * LCAP + tid] : 0ull;
     float4 pos_mine[3];
 #pragma unroll
     for (int j = 0; j < 3; ++j) pos_mine[j] = P.lists_pos[(size_t)tile * LCAP * 4 + tid + 256 * j];
@@ -795,10 +831,15 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 
     const int cnt = hd.x;
     if (cnt < 0) return;   // (whole workgroup) a crowded tile: the list kernel has done it, with lists per head
-    const int my_pass = tn < nt ? ((tn < 8 ? hd.y : hd.z) >> (4 * (tn & 7))) & 15 : -1;
     // ---- into LDS; what lies behind the list reads as groups without a valid slot, at a finite position
-    if (tid < LCAP) s_ent[tid] = tid < cnt ? ent_mine : 0;
-    if (tid < LENT - LCAP) s_ent[LCAP + tid] = 0;
+    if (tid < LCAP) {
+        s_ent[tid] = tid < cnt ? ent_mine : 0;
+        s_mask[tid] = tid < cnt ? mask_mine : 0ull;
+    }
+    if (tid < LENT - LCAP) {
+        s_ent[LCAP + tid] = 0;
+        s_mask[LCAP + tid] = 0ull;
+    }
 #pragma unroll
     for (int j = 0; j < 3; ++j) {   // (selected by value, component by component: the compiler would otherwise choose
         // between the addresses of two register arrays and move both into scratch memory)
@@ -888,7 +929,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 #pragma unroll
             for (int mt = 0; mt < 2; ++mt) {
                 const int ei = 8 * cm + 4 * mt + g;
-                const int e = s_ent[ei];
+                const unsigned mine4 = (unsigned)(s_mask[ei] >> (4 * tn));   // this target's four slots of the entry
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
                     const int u = 4 * mt + r;
@@ -896,7 +937,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
                     const float d2 = e2f::dist2_exact(tp.x, tp.y, tp.z, pc.x, pc.y, pc.z);
                     // (bitwise on purpose: the eight candidates are evaluated side by side; the target itself is at
                     // distance zero, an image of it at a box length: neither passes)
-                    const bool ok = (((e >> r) & 1) != 0) & (((e >> 4) & 15) == my_pass) & (d2 < P.rc2) & (d2 > 0.0f) &
+                    const bool ok = (((mine4 >> r) & 1u) != 0u) & (d2 < P.rc2) & (d2 > 0.0f) &
                                     (!CAP || e2f::under_cap(d2, pc.w, capd, capi));
                     const float d = __builtin_amdgcn_sqrtf(d2);
                     const float uu = __builtin_amdgcn_exp2f(c_u * d);
@@ -1137,8 +1178,8 @@ bool e2f_tile_supported(const e2f_ctx* ctx) {
            ctx->cfg.B <= 8 && (C == 32 || C == 64 || C == 128);
 }
 
-static e2f_status launch_tile(const e2f_ctx* ctx, const E2fCellsView& cv, const E2fAttnWs& ws, float* out, int what,
-                              hipStream_t st) {
+static e2f_status launch_tile(const e2f_ctx* ctx, const E2fCellsView& cv, const E2fAttnWs& ws, const int32_t* table,
+                              int table_K, float* out, int what, hipStream_t st) {
     if (cv.N == 0) return E2F_OK;
     if (cv.N >= (1 << 26)) return E2F_ERR_UNSUPPORTED;   // a list entry keeps the slot group in 24 bits
     TileParams P;
@@ -1149,6 +1190,9 @@ static e2f_status launch_tile(const e2f_ctx* ctx, const E2fCellsView& cv, const 
     P.lists_hdr = what == 0 ? nullptr : ws.lists_hdr;
     P.lists_ent = ws.lists_ent;
     P.lists_pos = ws.lists_pos;
+    P.lists_mask = ws.lists_mask;
+    P.table = table;
+    P.table_K = table_K;
     P.cw = ws.cw;
     P.G_out = ws.G;
     P.C = ctx->cfg.C; P.H = ctx->cfg.H; P.B = ctx->cfg.B; P.n_tiles = (cv.N + 15) / 16;
@@ -1170,9 +1214,10 @@ static e2f_status launch_tile(const e2f_ctx* ctx, const E2fCellsView& cv, const 
 
 // With E2F_FLAG_TILE_LISTS_PER_HEAD in the configuration the attention kernel builds its lists per (tile, head)
 // instead of reading the ones the list kernel leaves per tile (for A/B timing and tests).
-e2f_status e2f_launch_tile(const e2f_ctx* ctx, const E2fCellsView& cv, const E2fAttnWs& ws, float* out, hipStream_t st) {
-    if (!ws.lists_hdr || (ctx->cfg.flags & E2F_FLAG_TILE_LISTS_PER_HEAD)) return launch_tile(ctx, cv, ws, out, 0, st);
-    const e2f_status rc = launch_tile(ctx, cv, ws, out, 1, st);
+e2f_status e2f_launch_tile(const e2f_ctx* ctx, const E2fCellsView& cv, const E2fAttnWs& ws, const int32_t* table,
+                           int table_K, float* out, hipStream_t st) {
+    if (!ws.lists_hdr || (ctx->cfg.flags & E2F_FLAG_TILE_LISTS_PER_HEAD)) return launch_tile(ctx, cv, ws, table, table_K, out, 0, st);
+    const e2f_status rc = launch_tile(ctx, cv, ws, table, table_K, out, 1, st);
     if (rc != E2F_OK) return rc;
-    return launch_tile(ctx, cv, ws, out, 2, st);
+    return launch_tile(ctx, cv, ws, table, table_K, out, 2, st);
 }

@@ -57,8 +57,8 @@ def test_workspace_sizes_are_linear_in_N(lib):
         sizes = [B.e2f_attn_workspace_bytes(ctx, N) for N in (10_000, 20_000, 40_000)]
         # per atom (tile kernel): sorted position 16 B, q and k binary16 with 96 features per head (80 padded to a
         # multiple of 32), v bf16 [25][128]; per tile of 16 atoms a candidate list of 192 entries (header 16 B,
-        # entry 4 B, four slot positions 64 B)
-        per_atom = 16 + 2 * 8 * 96 * 2 + 25 * 128 * 2 + (16 + 192 * (4 + 64)) // 16
+        # entry 4 B, four slot positions 64 B, pair mask 8 B)
+        per_atom = 16 + 2 * 8 * 96 * 2 + 25 * 128 * 2 + (16 + 192 * (4 + 64 + 8)) // 16
         assert abs((sizes[1] - sizes[0]) - 10_000 * per_atom) <= 2048
         assert abs((sizes[2] - sizes[1]) - 20_000 * per_atom) <= 2048
         c = [B.e2f_cells_workspace_bytes(ctx, N, 4) for N in (1000, 2000, 3000)]

@@ -118,9 +118,10 @@ def test_backward_rejects_what_it_does_not_cover(torch_cuda):
 
 
 def test_backward_scaling_point_sampled(torch_cuda):
-    """The 10 000-atom box the benchmark times, bf16, same launch configuration: dL/dpos and dL/dh of sampled atoms
-    against the gradient reference.  The gradient with respect to atom a involves only the outputs of a and of its
-    neighbours, so the reference runs on those targets (with their complete neighbourhoods) alone."""
+    """The 10 000-atom box the benchmark times, bf16, same launch configuration: dL/dpos and dL/dh of 120 atoms (a
+    compact cluster that reaches a face of the box, so surface atoms are among them) against the gradient reference.
+    The gradient with respect to atom a involves only the outputs of a and of its neighbours, so the reference runs
+    on those targets (with their complete neighbourhoods) alone, all 120 atoms in one differentiation."""
     import oracle as O
     from oracle import grad as G
     from paper_2601_16622_amd import binding as B
@@ -142,26 +143,28 @@ def test_backward_scaling_point_sampled(torch_cuda):
         P.close()
     assert np.isfinite(gp).all() and np.isfinite(gh).all()
     assert np.abs(gp.sum(0)).max() <= 1e-3 * np.abs(gp).max() * np.sqrt(N)   # translation invariance
-    deg = np.diff(off)
-    picks = np.random.default_rng(8).choice(np.nonzero((deg > 20) & (deg < 110))[0], 5, replace=False)
-    ref_p, got_p, ref_h, got_h = [], [], [], []
-    for a in picks:
-        targets = np.concatenate([[a], idx[off[a]:off[a + 1]]])
-        atoms = np.unique(np.concatenate([targets] + [idx[off[i]:off[i + 1]] for i in targets]))
-        local = -np.ones(N, dtype=np.int64)
-        local[atoms] = np.arange(len(atoms))
-        sub_off = np.zeros(len(atoms) + 1, dtype=np.int64)
-        rows = [np.zeros(0, dtype=np.int32)] * len(atoms)
-        for i in targets:
-            rows[local[i]] = local[idx[off[i]:off[i + 1]]].astype(np.int32)
-        sub_off[1:] = np.cumsum([len(r) for r in rows])
-        sub_go = np.zeros((len(atoms),) + go.shape[1:], dtype=np.float64)
-        sub_go[local[targets]] = go[targets]
-        _, g = G.attn_backward(ocfg, wl["pos"][atoms].astype(np.float64), wl["h"][atoms], wl["weights"],
-                               (sub_off, np.concatenate(rows)), sub_go, wrt=("pos", "h"))
-        ref_p.append(g["pos"][local[a]])
-        got_p.append(gp[a])
-        ref_h.append(g["h"][local[a]])
-        got_h.append(gh[a])
-    assert rel_l2(np.stack(got_p), np.stack(ref_p)) <= TOL["bf16"]
-    assert rel_l2(np.stack(got_h), np.stack(ref_h)) <= TOL["bf16"]
+    pos = wl["pos"].astype(np.float64)
+    centre = np.array([pos[:, 0].min() + 3.0, pos[:, 1].mean(), pos[:, 2].mean()])   # three angstrom inside a face
+    picks = np.argsort(((pos - centre) ** 2).sum(1))[:120]
+    assert (pos[picks, 0] < pos[:, 0].min() + 0.5).any() and np.diff(off)[picks].min() < 60 < np.diff(off)[picks].max()
+    targets = np.unique(np.concatenate([picks] + [idx[off[a]:off[a + 1]] for a in picks]))
+    atoms = np.unique(np.concatenate([targets] + [idx[off[i]:off[i + 1]] for i in targets]))
+    local = -np.ones(N, dtype=np.int64)
+    local[atoms] = np.arange(len(atoms))
+    rows = [np.zeros(0, dtype=np.int32)] * len(atoms)
+    for i in targets:
+        rows[local[i]] = local[idx[off[i]:off[i + 1]]].astype(np.int32)
+    sub_off = np.zeros(len(atoms) + 1, dtype=np.int64)
+    sub_off[1:] = np.cumsum([len(r) for r in rows])
+    sub_go = np.zeros((len(atoms),) + go.shape[1:], dtype=np.float64)
+    sub_go[local[targets]] = go[targets]
+    _, g = G.attn_backward(ocfg, pos[atoms], wl["h"][atoms], wl["weights"], (sub_off, np.concatenate(rows)), sub_go,
+                           wrt=("pos", "h"))
+    ref_p, ref_h = g["pos"][local[picks]], g["h"][local[picks]]
+    assert rel_l2(gp[picks], ref_p) <= TOL["bf16"]
+    assert rel_l2(gh[picks], ref_h) <= TOL["bf16"]
+    # no single atom hides in the norm over all of them
+    for got, ref in ((gp[picks], ref_p), (gh[picks], ref_h)):
+        d = np.linalg.norm((got - ref).reshape(len(picks), -1), axis=1)
+        r = np.linalg.norm(ref.reshape(len(picks), -1), axis=1)
+        assert (d <= 5 * TOL["bf16"] * np.maximum(r, 0.05 * r.mean())).all(), float((d / r).max())

@@ -286,7 +286,9 @@ def test_capped_forward_fp32_and_no_effect_above_the_degree(torch_cuda):
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_forward_over_a_padded_table(torch_cuda, dtype):
     """e2f_attn_forward_table: the library's own table, and a hand-made one (a random subset of the true neighbours in
-    shuffled order, with holes, a self entry and repeated padding) against the oracle run on the same lists."""
+    shuffled order, with holes, a self entry, an atom beyond the cutoff and repeated padding) against the oracle run on
+    the same lists; fp32 features go through the vector-ALU kernel, bf16 ones through the tile kernel (the table as a
+    mask on the tiles' candidate lists)."""
     import oracle as O
     wl = _custom(14, 260, 2, 32, 2, 8, 1, dtype, cutoff=3.5, side=8.5, seg=[0, 100, 260])
     K = 16
@@ -307,6 +309,10 @@ def test_forward_over_a_padded_table(torch_cuda, dtype):
             hand[i, slots] = pick
             free = np.setdiff1d(np.arange(K + 3), slots)
             hand[i, free[0]] = i            # a self entry is ignored
+            s0, s1 = wl["seg"][np.searchsorted(wl["seg"], i, side="right") - 1], wl["seg"][np.searchsorted(wl["seg"], i, side="right")]
+            far = [j for j in range(s0, s1) if j != i and j not in nb]
+            if far:
+                hand[i, free[1]] = far[rng.integers(len(far))]   # and so is an atom outside the cutoff
             rows.append(np.sort(pick).astype(np.int32))
             h_off[i + 1] = h_off[i] + len(pick)
         h_idx = np.concatenate(rows).astype(np.int32)
