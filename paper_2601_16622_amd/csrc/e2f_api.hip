@@ -593,6 +593,8 @@ static E2fBwdWs bwd_ws_layout(const e2f_ctx* ctx, int32_t N, void* ws, size_t at
     Bw.Gu = (float*)take((size_t)3 * E2F_MAX_N * E2F_MAX_N * 4);
     Bw.pWb = (float*)take((size_t)N * ctx->cfg.H * ctx->cfg.B * 4);
     Bw.pwp = (float*)take((size_t)N * 32 * 4);
+    Bw.wT = ctx->cfg.feat_dtype == E2F_BF16
+                ? (uint16_t*)take((size_t)5 * (ctx->cfg.L_max + 1) * ctx->cfg.C * ctx->cfg.C * 2) : nullptr;
     Bw.tbuf = Bw.wpart = nullptr;
     if (with_W) {
         const size_t C = ctx->cfg.C, L1 = ctx->cfg.L_max + 1;

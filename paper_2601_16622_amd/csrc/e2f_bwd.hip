@@ -601,6 +601,117 @@ __global__ __launch_bounds__(256) void k_bwd_project(const T* __restrict__ h, co
     }
 }
 
+// ---- the same chain rule on the matrix cores, for bf16 features and C <= 128.  A workgroup owns 16 consecutive atoms
+// and walks the (degree, order) slabs; wave ct owns output channels 16 ct .. 16 ct + 15 of the forward products and
+// the same input channels of the transposed ones.  Both products are written with the channels as rows and the atoms
+// as columns, (W x)^T = W X^T and dX^T = sum_k W_k^T T_k^T, so that the weights are the A operand (one 16-byte load per
+// fragment, from W for the first and from the transposed copy WT for the second, kept in registers over a degree),
+// a lane ends up with four consecutive channels of one atom (16-byte loads of dq, dk, dv and 16-byte stores of the
+// result) and the row factors t_k cross the waves through LDS as [atom][channel] rows.  The factors are fp32; for the
+// second product each is split into two bf16 (leading part and remainder, 16 significant bits together), so that the
+// result keeps fp32-like accuracy on bf16 matrix instructions.
+__global__ __launch_bounds__(256) void k_transpose_weights(const uint16_t* __restrict__ W0, const uint16_t* __restrict__ W1,
+                                                           const uint16_t* __restrict__ W2, const uint16_t* __restrict__ W3,
+                                                           const uint16_t* __restrict__ W4, int L1, int C,
+                                                           uint16_t* __restrict__ WT) {
+    // WT[k][l][ci][co] = W_k[l][co][ci]; one workgroup per (k, l, 16 x 16 tile)
+    __shared__ uint16_t s[16][17];
+    const int tiles = C / 16, t = blockIdx.x % (tiles * tiles), kl = blockIdx.x / (tiles * tiles);
+    const int k = kl / L1, l = kl % L1, tr = t / tiles, tc = t % tiles;
+    const uint16_t* W = k == 0 ? W0 : k == 1 ? W1 : k == 2 ? W2 : k == 3 ? W3 : W4;
+    const int r = threadIdx.x >> 4, c = threadIdx.x & 15;
+    s[r][c] = W[((size_t)l * C + 16 * tr + r) * C + 16 * tc + c];
+    __syncthreads();
+    WT[(((size_t)k * L1 + l) * C + 16 * tc + r) * C + 16 * tr + c] = s[c][r];
+}
+
+template <int C>
+__global__ __launch_bounds__(64 * (C / 16)) void k_bwd_project_mfma(
+    const uint16_t* __restrict__ h, const uint16_t* __restrict__ WQ1, const uint16_t* __restrict__ WQ2,
+    const uint16_t* __restrict__ WK1, const uint16_t* __restrict__ WK2, const uint16_t* __restrict__ WT,
+    const float* __restrict__ gq, const float* __restrict__ gk, const float* __restrict__ gv, float* __restrict__ gh,
+    float* __restrict__ tbuf, int L, int N) {
+    typedef float f32x4 __attribute__((ext_vector_type(4)));
+    typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+    typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+    typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+    constexpr int NS = C / 32, ROW = C + 8;   // LDS rows of the factors, 16 bytes of padding against bank conflicts
+    __shared__ __attribute__((aligned(16))) uint16_t s_T[5][2][16][ROW];
+    const int ct = threadIdx.x >> 6, lane = threadIdx.x & 63, i = lane & 15, g = lane >> 4;
+    const int n = (L + 1) * (L + 1), a0 = blockIdx.x * 16;
+    const bool real = a0 + i < N;
+    const int atom = min(a0 + i, N - 1);
+    const int ch0 = 16 * ct + 4 * g;   // the four channels this lane holds of its atom
+    auto frag = [](const uint16_t* p) { return __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(p)); };
+    for (int l = 0; l <= L; ++l) {
+        bf16x8 W1[4][NS], W2[5][NS];
+        {
+            const size_t row = ((size_t)l * C + 16 * ct + i) * C + 8 * g;
+            const size_t lstride = (size_t)(L + 1) * C * C;
+#pragma unroll
+            for (int S = 0; S < NS; ++S) {
+                W1[0][S] = frag(WQ1 + row + 32 * S);
+                W1[1][S] = frag(WQ2 + row + 32 * S);
+                W1[2][S] = frag(WK1 + row + 32 * S);
+                W1[3][S] = frag(WK2 + row + 32 * S);
+#pragma unroll
+                for (int k = 0; k < 5; ++k) W2[k][S] = frag(WT + k * lstride + row + 32 * S);
+            }
+        }
+        const f32x4 dq = real ? *reinterpret_cast<const f32x4*>(gq + ((size_t)atom * (L + 1) + l) * C + ch0) : (f32x4){0.f, 0.f, 0.f, 0.f};
+        const f32x4 dk = real ? *reinterpret_cast<const f32x4*>(gk + ((size_t)atom * (L + 1) + l) * C + ch0) : (f32x4){0.f, 0.f, 0.f, 0.f};
+        for (int m = 0; m < 2 * l + 1; ++m) {
+            const int comp = l * l + m;
+            const size_t rowx = ((size_t)atom * n + comp) * C;
+            bf16x8 X[NS];
+#pragma unroll
+            for (int S = 0; S < NS; ++S) X[S] = frag(h + rowx + 32 * S + 8 * g);
+            f32x4 t[5];
+            t[4] = real ? *reinterpret_cast<const f32x4*>(gv + rowx + ch0) : (f32x4){0.f, 0.f, 0.f, 0.f};
+            f32x4 p[4];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                p[k] = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int S = 0; S < NS; ++S) p[k] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(W1[k][S], X[S], p[k], 0, 0, 0);
+            }
+            // p[k][r] = (W_k x)[channel 16 ct + 4 g + r] of atom i
+            t[0] = dq * p[1];
+            t[1] = dq * p[0];
+            t[2] = dk * p[3];
+            t[3] = dk * p[2];
+            if (tbuf && real) {   // the five row factors of the weight gradients: dW_k[l] = sum over rows of t_k (x) x
+#pragma unroll
+                for (int k = 0; k < 5; ++k) *reinterpret_cast<f32x4*>(tbuf + ((size_t)k * N + atom) * n * C + (size_t)comp * C + ch0) = t[k];
+            }
+            if (!gh) continue;   // (uniform) only the row factors were asked for
+#pragma unroll
+            for (int k = 0; k < 5; ++k) {
+                uint16_t hi[4], lo[4];
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    hi[r] = e2f::float_to_bf16_bits(t[k][r]);
+                    lo[r] = e2f::float_to_bf16_bits(t[k][r] - e2f::bf16_bits_to_float(hi[r]));
+                }
+                *reinterpret_cast<u32x2*>(&s_T[k][0][i][ch0]) = (u32x2){hi[0] | ((uint32_t)hi[1] << 16), hi[2] | ((uint32_t)hi[3] << 16)};
+                *reinterpret_cast<u32x2*>(&s_T[k][1][i][ch0]) = (u32x2){lo[0] | ((uint32_t)lo[1] << 16), lo[2] | ((uint32_t)lo[3] << 16)};
+            }
+            __syncthreads();
+            f32x4 d = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int k = 0; k < 5; ++k)
+#pragma unroll
+                for (int S = 0; S < NS; ++S) {
+                    d = __builtin_amdgcn_mfma_f32_16x16x32_bf16(W2[k][S], frag(&s_T[k][0][i][32 * S + 8 * g]), d, 0, 0, 0);
+                    d = __builtin_amdgcn_mfma_f32_16x16x32_bf16(W2[k][S], frag(&s_T[k][1][i][32 * S + 8 * g]), d, 0, 0, 0);
+                }
+            // d[r] = dL/dh[atom i][comp][channel 16 ct + 4 g + r]
+            if (real) *reinterpret_cast<f32x4*>(gh + rowx + ch0) = d;
+            __syncthreads();   // the factors have been read: the next slab may overwrite them
+        }
+    }
+}
+
 // ---- gradients of the five projection matrices: dW_k[l][co][ci] = sum over atoms a and orders m of
 // t_k[a][l, m][co] * h[a][l, m][ci], with the row factors t_k that k_bwd_project leaves in the workspace.  One
 // workgroup per (chunk of atoms, degree, tile of 16 output channels), one thread per input channel; the factors of
@@ -747,7 +858,23 @@ e2f_status e2f_launch_backward(const e2f_ctx* ctx, const E2fCellsView& cv, const
         float* tbuf = grad_W ? bw.tbuf : nullptr;
         const dim3 wgrid(WG_SPLIT * (L + 1) * (L + 1), C / 16);
         const size_t M = (size_t)5 * (L + 1) * C * C;
-        if (ctx->cfg.feat_dtype == E2F_BF16) {
+        if (ctx->cfg.feat_dtype == E2F_BF16 && bw.wT && (C == 32 || C == 64 || C == 128)) {
+            const int t16 = C / 16;
+            k_transpose_weights<<<5 * (L + 1) * t16 * t16, 256, 0, st>>>(
+                (const uint16_t*)w->WQ1, (const uint16_t*)w->WQ2, (const uint16_t*)w->WK1, (const uint16_t*)w->WK2,
+                (const uint16_t*)w->WV, L + 1, C, bw.wT);
+            const int tiles = (cv.N + 15) / 16;
+#define E2F_BWD_PROJECT(CC)                                                                                            \
+    k_bwd_project_mfma<CC><<<tiles, 64 * (CC / 16), 0, st>>>((const uint16_t*)h, (const uint16_t*)w->WQ1,              \
+                                                           (const uint16_t*)w->WQ2, (const uint16_t*)w->WK1,          \
+                                                           (const uint16_t*)w->WK2, bw.wT, grad_q, grad_k, grad_v,    \
+                                                           grad_h, tbuf, L, cv.N)
+            if (C == 32) E2F_BWD_PROJECT(32);
+            else if (C == 64) E2F_BWD_PROJECT(64);
+            else E2F_BWD_PROJECT(128);
+#undef E2F_BWD_PROJECT
+            if (grad_W) k_bwd_wgrad<uint16_t><<<wgrid, C, 0, st>>>((const uint16_t*)h, tbuf, L, C, cv.N, bw.wpart);
+        } else if (ctx->cfg.feat_dtype == E2F_BF16) {
             k_bwd_project<uint16_t><<<groups, C, shm, st>>>((const uint16_t*)h, (const uint16_t*)w->WQ1, (const uint16_t*)w->WQ2,
                                                           (const uint16_t*)w->WK1, (const uint16_t*)w->WK2,
                                                           (const uint16_t*)w->WV, grad_q, grad_k, grad_v, grad_h, tbuf, L, C,

@@ -109,6 +109,7 @@ struct E2fBwdWs {
     float* Gu;       // [3][25][25]
     float* pWb;      // [N][H][B]
     float* pwp;      // [N][32]
+    uint16_t* wT;    // [5][L+1][C in][C out] the projection matrices transposed (bf16 features: chain rule on the matrix cores)
     // for the gradients of the projection matrices (only in the larger workspace of that form of the call)
     float* tbuf;     // [5][N][n][C] row factors
     float* wpart;    // [8 (L+1)^2 slices][5][C][C] partial sums
