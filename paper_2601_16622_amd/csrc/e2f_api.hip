@@ -605,14 +605,30 @@ static E2fBwdWs bwd_ws_layout(const e2f_ctx* ctx, int32_t N, void* ws, size_t at
     return Bw;
 }
 
+// The pair work of the backward pass runs in tile form where the forward pass does (and the call asks for no gradients
+// of Wb or w_path, which only the per-atom kernels form).
+static bool backward_in_tile_form(const e2f_ctx* ctx, bool wgrad) { return ctx->use_tile_attn && !wgrad; }
+
 size_t e2f_attn_backward_workspace_bytes(const e2f_ctx* ctx, int32_t N) {
     if (!ctx || N < 0) return 0;
-    return bwd_ws_layout(ctx, N, nullptr, e2f_attn_ws_layout(ctx, N, nullptr, 0).bytes, false).bytes;
+    size_t bytes = bwd_ws_layout(ctx, N, nullptr, e2f_attn_ws_layout(ctx, N, nullptr, 0).bytes, false).bytes;
+    if (backward_in_tile_form(ctx, false)) {   // either form may run, depending on the gradients asked for
+        const size_t b2 = bwd_ws_layout(ctx, N, nullptr, e2f_attn_ws_layout(ctx, N, nullptr, 2).bytes, false).bytes;
+        const size_t b3 = e2f_bwd_tile_ws_layout(ctx, N, nullptr, b2).bytes;
+        if (b3 > bytes) bytes = b3;
+    }
+    return bytes;
 }
 
 size_t e2f_attn_backward_weights_workspace_bytes(const e2f_ctx* ctx, int32_t N) {
     if (!ctx || N < 0) return 0;
-    return bwd_ws_layout(ctx, N, nullptr, e2f_attn_ws_layout(ctx, N, nullptr, 0).bytes, true).bytes;
+    size_t bytes = bwd_ws_layout(ctx, N, nullptr, e2f_attn_ws_layout(ctx, N, nullptr, 0).bytes, true).bytes;
+    if (backward_in_tile_form(ctx, false)) {
+        const size_t b2 = bwd_ws_layout(ctx, N, nullptr, e2f_attn_ws_layout(ctx, N, nullptr, 2).bytes, true).bytes;
+        const size_t b3 = e2f_bwd_tile_ws_layout(ctx, N, nullptr, b2).bytes;
+        if (b3 > bytes) bytes = b3;
+    }
+    return bytes;
 }
 
 e2f_status e2f_attn_backward(e2f_ctx* ctx, const e2f_cells* cells, const float* pos, const void* h,
@@ -629,12 +645,16 @@ e2f_status e2f_attn_backward(e2f_ctx* ctx, const e2f_cells* cells, const float* 
     if (ws_bytes < (grad_W ? e2f_attn_backward_weights_workspace_bytes(ctx, N) : e2f_attn_backward_workspace_bytes(ctx, N)))
         return E2F_ERR_WORKSPACE_TOO_SMALL;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
-    const E2fAttnWs L = e2f_attn_ws_layout(ctx, N, ws, 0);
+    const bool tile = backward_in_tile_form(ctx, grad_Wb || grad_w_path);
+    const int v_layout = tile ? 2 : 0;
+    const E2fAttnWs L = e2f_attn_ws_layout(ctx, N, ws, v_layout);
     const E2fBwdWs Bw = bwd_ws_layout(ctx, N, ws, L.bytes, grad_W != nullptr);
+    E2fBwdTileWs Tw;
+    if (tile) Tw = e2f_bwd_tile_ws_layout(ctx, N, ws, Bw.bytes);
     if ((rc = e2f_launch_prepare(ctx, cells->view, pos, w, L, st)) != E2F_OK) return rc;
-    if ((rc = e2f_launch_project_mfma(ctx, cells->view, h, w, L, 0, st)) != E2F_OK) return rc;
+    if ((rc = e2f_launch_project_mfma(ctx, cells->view, h, w, L, v_layout, st)) != E2F_OK) return rc;
     return e2f_launch_backward(ctx, cells->view, w, L, Bw, out, grad_out, grad_pos, grad_q, grad_k, grad_v, h, grad_h,
-                               grad_Wb, grad_w_path, grad_W, st);
+                               grad_Wb, grad_w_path, grad_W, tile ? &Tw : nullptr, st);
 }
 
 e2f_status e2f_eaas_tensor_product(e2f_ctx* ctx, const void* h, const float* r, const float* w_path, float* out,

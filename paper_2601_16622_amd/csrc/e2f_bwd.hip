@@ -44,9 +44,61 @@ struct BwdParams {
     const float* Gu;      // [3][25][25] axis operators with unit path weights
     float* pWb;           // [N][H][B]
     float* pwp;           // [N][WP_BINS], bin li * (L_max + 1) + lo
+    // TL instances (the crowded tiles that the tile kernels of e2f_bwd_tile.hip leave out) read the tile layouts
+    // instead of q, k, v, lse and Dn: q rows scaled by tau log2 e and k rows in binary16, value blocks, statistics
+    // in base-2 units
+    const uint16_t *q16, *k16, *v4;
+    float2* stat4;            // [group of 4 slots][H][4] (lse, D)
+    const int4* lists_hdr;    // per tile of 16 slots: x < 0 marks a crowded tile
     int C, H, B, Ch;
     float tau, rc2, cutoff, rbf_step, rbf_gamma;
 };
+
+constexpr float LOG2E = 1.44269504088896341f, LN2 = 0.69314718055994531f;
+
+// Operand access in the plain layouts or (TL) in the layouts of the tile kernels (heads of 16 channels).
+template <int L, bool TL>
+__device__ __forceinline__ float load_q(const BwdParams& P, int t, int l, int c) {
+    if constexpr (TL) {
+        constexpr int DKP = ((L + 1) * 16 + 31) / 32 * 32;
+        return (float)__builtin_bit_cast(_Float16, P.q16[((size_t)t * P.H + (c >> 4)) * DKP + l * 16 + (c & 15)]);
+    } else {
+        return P.q[((size_t)t * (L + 1) + l) * P.C + c];
+    }
+}
+template <int L, bool TL>
+__device__ __forceinline__ float load_k(const BwdParams& P, int j, int l, int c) {
+    if constexpr (TL) {
+        constexpr int DKP = ((L + 1) * 16 + 31) / 32 * 32;
+        return (float)__builtin_bit_cast(_Float16, P.k16[e2f::k16_offset(j, P.H, c >> 4, DKP, l * 16 + (c & 15))]);
+    } else {
+        return P.k[((size_t)j * (L + 1) + l) * P.C + c];
+    }
+}
+template <int L, typename VT, bool TL>
+__device__ __forceinline__ float load_v(const BwdParams& P, int j, int x, int c) {
+    constexpr int n = (L + 1) * (L + 1);
+    if constexpr (TL)
+        return e2f::bf16_bits_to_float(P.v4[((size_t)(j >> 2) * P.H + (c >> 4)) * n * 64 + e2f::v4_offset(n, x, c & 15) + (j & 3)]);
+    else
+        return e2f::load_as_float<VT>((const VT*)P.v + ((size_t)j * n + x) * P.C + c);
+}
+// Softmax weight P_ij from the dot product of the layout's q and k rows, the bias (natural units) and the statistic.
+template <bool TL>
+__device__ __forceinline__ float pair_prob(const BwdParams& P, float dot, float bias, float lse) {
+    if constexpr (TL) return exp2f(dot + bias * LOG2E - lse);
+    else return __expf(dot * P.tau + bias - lse);
+}
+template <bool TL>
+__device__ __forceinline__ float load_lse(const BwdParams& P, int t, int head) {
+    if constexpr (TL) return P.stat4[((size_t)(t >> 2) * P.H + head) * 4 + (t & 3)].x;
+    else return P.lse[(size_t)t * P.H + head];
+}
+template <bool TL>
+__device__ __forceinline__ float load_Dn(const BwdParams& P, int t, int head) {
+    if constexpr (TL) return P.stat4[((size_t)(t >> 2) * P.H + head) * 4 + (t & 3)].y;
+    else return P.Dn[(size_t)t * P.H + head];
+}
 
 // Sum over the Ch threads of a head (Ch a power of two <= 64, heads aligned inside a wave).
 __device__ __forceinline__ float head_sum(float x, int Ch) {
@@ -154,7 +206,7 @@ __device__ __forceinline__ void axis_apply(const float (&a)[(L + 1) * (L + 1)], 
 }
 
 // ---- softmax statistics: lse_i = log sum_j exp(s_ij) and D_i = <g_i, out_i>, per head
-template <int L>
+template <int L, bool TL>
 __global__ __launch_bounds__(256) void k_bwd_stats(BwdParams P) {
     constexpr int n = (L + 1) * (L + 1);
     __shared__ int s_list[BCAP];
@@ -163,13 +215,14 @@ __global__ __launch_bounds__(256) void k_bwd_stats(BwdParams P) {
     __shared__ int s_ctl[2];
     const int t = e2f::xcd_remap(blockIdx.x, P.cv.N), C = P.C;
     if (t < 0) return;
+    if (TL && P.lists_hdr[t >> 4].x >= 0) return;   // (whole workgroup) the tile kernels own this atom
     const bool live = (int)threadIdx.x < C;        // workgroups have at least one full wave: the list walk needs it
     const int c = live ? threadIdx.x : 0, head = c / P.Ch;
     const int a = P.cv.perm[t];
     const float4 pi = P.spos[t];
     float qv[L + 1];
 #pragma unroll
-    for (int l = 0; l <= L; ++l) qv[l] = P.q[((size_t)t * (L + 1) + l) * C + c];
+    for (int l = 0; l <= L; ++l) qv[l] = load_q<L, TL>(P, t, l, c);
     float dsum = 0.0f;
     for (int x = 0; x < n; ++x) dsum += P.gout[((size_t)a * n + x) * C + c] * P.out[((size_t)a * n + x) * C + c];
     dsum = head_sum(dsum, P.Ch);
@@ -182,18 +235,29 @@ __global__ __launch_bounds__(256) void k_bwd_stats(BwdParams P) {
             const int j = s_list[e];
             float dot = 0.0f;
 #pragma unroll
-            for (int l = 0; l <= L; ++l) dot += qv[l] * P.k[((size_t)j * (L + 1) + l) * C + c];
+            for (int l = 0; l <= L; ++l) dot += qv[l] * load_k<L, TL>(P, j, l, c);
             dot = head_sum(dot, P.Ch);
-            const float s = dot * P.tau + s_bias[e * P.H + head].x;
-            const float mn = fmaxf(m, s);
-            z = z * __expf(m - mn) + __expf(s - mn);
-            m = mn;
+            if constexpr (TL) {   // base-2 units, as the tile kernels keep them
+                const float s = dot + s_bias[e * P.H + head].x * LOG2E;
+                const float mn = fmaxf(m, s);
+                z = z * exp2f(m - mn) + exp2f(s - mn);
+                m = mn;
+            } else {
+                const float s = dot * P.tau + s_bias[e * P.H + head].x;
+                const float mn = fmaxf(m, s);
+                z = z * __expf(m - mn) + __expf(s - mn);
+                m = mn;
+            }
         }
         if (s_ctl[1]) break;
     }
     if (live && c % P.Ch == 0) {
-        P.lse[(size_t)t * P.H + head] = z > 0.0f ? m + logf(z) : 0.0f;
-        P.Dn[(size_t)t * P.H + head] = dsum;
+        if constexpr (TL) {
+            P.stat4[((size_t)(t >> 2) * P.H + head) * 4 + (t & 3)] = make_float2(z > 0.0f ? m + log2f(z) : 0.0f, dsum);
+        } else {
+            P.lse[(size_t)t * P.H + head] = z > 0.0f ? m + logf(z) : 0.0f;
+            P.Dn[(size_t)t * P.H + head] = dsum;
+        }
     }
 }
 
@@ -202,7 +266,7 @@ __host__ __device__ constexpr int degree_of(int x) { return x >= 16 ? 4 : x >= 9
 
 // ---- what an atom owns as a target i: dq_i and -sum_j dL/dr_ij; with WGRAD also its partial sums of
 //   dL/dWb[h][b] = sum_j ds_ij,h exp(-gamma (d_ij - mu_b)^2)
-template <int L, typename VT, bool WGRAD>
+template <int L, typename VT, bool WGRAD, bool TL>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void k_bwd_target(BwdParams P) {
     constexpr int n = (L + 1) * (L + 1);
     __shared__ int s_list[BCAP];
@@ -213,6 +277,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void k
     __shared__ float s_gp[E2F_MAX_H][3];
     const int t = e2f::xcd_remap(blockIdx.x, P.cv.N), C = P.C;
     if (t < 0) return;
+    if (TL && P.lists_hdr[t >> 4].x >= 0) return;   // (whole workgroup) the tile kernels own this atom
     const bool live = (int)threadIdx.x < C;        // workgroups have at least one full wave: the list walk needs it
     const int c = live ? threadIdx.x : 0, head = c / P.Ch;
     const int a = P.cv.perm[t];
@@ -221,12 +286,12 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void k
     float qv[L + 1], dq[L + 1], g[n];
 #pragma unroll
     for (int l = 0; l <= L; ++l) {
-        qv[l] = P.q[((size_t)t * (L + 1) + l) * C + c];
+        qv[l] = load_q<L, TL>(P, t, l, c);
         dq[l] = 0.0f;
     }
 #pragma unroll
     for (int x = 0; x < n; ++x) g[x] = P.gout[((size_t)a * n + x) * C + c];
-    const float lse = P.lse[(size_t)t * P.H + head], Dn = P.Dn[(size_t)t * P.H + head];
+    const float lse = load_lse<TL>(P, t, head), Dn = load_Dn<TL>(P, t, head);
     float gx = 0.0f, gy = 0.0f, gz = 0.0f;   // sum_j dL/dr_ij of this head
     ListWalk w;
     w.init(P.cv, t);
@@ -249,16 +314,16 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) void k
             float kv[L + 1], dot = 0.0f;
 #pragma unroll
             for (int l = 0; l <= L; ++l) {
-                kv[l] = P.k[((size_t)j * (L + 1) + l) * C + c];
+                kv[l] = load_k<L, TL>(P, j, l, c);
                 dot += qv[l] * kv[l];
             }
             float u[3] = {0.0f, 0.0f, 0.0f};
             dot = head_sum(dot, P.Ch);
-            const float p = __expf(dot * P.tau + bb.x - lse);
+            const float p = pair_prob<TL>(P, dot, bb.x, lse);
             const float phi = rad.x, dphi = rad.y;
 #pragma unroll
             for (int x = 0; x < n; ++x) {
-                const float vx = e2f::load_as_float<VT>((const VT*)P.v + ((size_t)j * n + x) * C + c);
+                const float vx = load_v<L, VT, TL>(P, j, x, c);
                 u[0] += gt[0][x] * vx;
                 u[1] += gt[1][x] * vx;
                 u[2] += gt[2][x] * vx;
@@ -334,7 +399,7 @@ __global__ __launch_bounds__(256) void k_reduce_partials(const float* __restrict
 // G_mu[xo][xi] = w_path[li(xi)][lo(xo)] Gu_mu[xo][xi] with the unit-weight operators Gu, so with the sums
 // Y_mu = sum_i alpha_ij r_mu g_i that this kernel forms anyway
 //   dL/dw_path[li][lo] = sum_j sum_mu sum_{xo in lo, xi in li} Y_mu[xo] Gu_mu[xo][xi] v_j[xi].
-template <int L, typename VT, bool WGRAD>
+template <int L, typename VT, bool WGRAD, bool TL>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k_bwd_source(BwdParams P) {
     constexpr int n = (L + 1) * (L + 1);
     __shared__ int s_list[BCAP];
@@ -345,6 +410,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k
     __shared__ float s_gp[E2F_MAX_H][3];
     const int t = e2f::xcd_remap(blockIdx.x, P.cv.N), C = P.C;
     if (t < 0) return;
+    if (TL && P.lists_hdr[t >> 4].x >= 0) return;   // (whole workgroup) the tile kernels own this atom
     const bool live = (int)threadIdx.x < C;        // workgroups have at least one full wave: the list walk needs it
     const int c = live ? threadIdx.x : 0, head = c / P.Ch;
     const int a = P.cv.perm[t];
@@ -353,12 +419,12 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k
     float kv[L + 1], dk[L + 1], vj[n], Y[3][n];
 #pragma unroll
     for (int l = 0; l <= L; ++l) {
-        kv[l] = P.k[((size_t)t * (L + 1) + l) * C + c];
+        kv[l] = load_k<L, TL>(P, t, l, c);
         dk[l] = 0.0f;
     }
 #pragma unroll
     for (int x = 0; x < n; ++x) {
-        vj[x] = e2f::load_as_float<VT>((const VT*)P.v + ((size_t)t * n + x) * C + c);
+        vj[x] = load_v<L, VT, TL>(P, t, x, c);
         Y[0][x] = Y[1][x] = Y[2][x] = 0.0f;
     }
     float gx = 0.0f, gy = 0.0f, gz = 0.0f;   // sum_i dL/dr_ij of this head
@@ -379,7 +445,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k
             float qv[L + 1], dot = 0.0f;
 #pragma unroll
             for (int l = 0; l <= L; ++l) {
-                qv[l] = P.q[((size_t)i * (L + 1) + l) * C + c];
+                qv[l] = load_q<L, TL>(P, i, l, c);
                 dot += qv[l] * kv[l];
             }
             float g[n];
@@ -395,14 +461,14 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k
             u[0] = head_sum(u[0], P.Ch);
             u[1] = head_sum(u[1], P.Ch);
             u[2] = head_sum(u[2], P.Ch);
-            const float p = __expf(dot * P.tau + bb.x - P.lse[(size_t)i * P.H + head]);
+            const float p = pair_prob<TL>(P, dot, bb.x, load_lse<TL>(P, i, head));
             const float phi = rad.x, dphi = rad.y;
             const float wsum = rx * u[0] + ry * u[1] + rz * u[2];
-            const float ds = p * (phi * wsum - P.Dn[(size_t)i * P.H + head]);
+            const float ds = p * (phi * wsum - load_Dn<TL>(P, i, head));
             const float alpha = p * phi;
             const float dd = (ds * bb.y + p * wsum * dphi) / rad.z;
 #pragma unroll
-            for (int l = 0; l <= L; ++l) dk[l] += P.tau * ds * qv[l];
+            for (int l = 0; l <= L; ++l) dk[l] += (TL ? LN2 : P.tau) * ds * qv[l];   // (TL: the q rows carry tau log2 e)
             const float ax = alpha * rx, ay = alpha * ry, az = alpha * rz;
 #pragma unroll
             for (int x = 0; x < n; ++x) {
@@ -456,7 +522,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k
 #pragma unroll
         for (int i = 0; i < (L + 1) * (L + 1); ++i) bins[i] = 0.0f;
 #pragma unroll
-        for (int x = 0; x < n; ++x) vr[x] = e2f::load_as_float<VT>((const VT*)P.v + ((size_t)t * n + x) * C + c);
+        for (int x = 0; x < n; ++x) vr[x] = load_v<L, VT, TL>(P, t, x, c);
 #pragma unroll
         for (int mu = 0; mu < 3; ++mu)
 #pragma unroll
@@ -794,13 +860,27 @@ void launch_LV(const BwdParams& P, hipStream_t st) {
     const size_t shm = (size_t)BCAP * P.H * sizeof(float2);
     // with weight gradients the same bytes later hold the [(L+1)^2][C] channel sums of the path-weight bins
     const size_t shm_w = shm > (size_t)(L + 1) * (L + 1) * P.C * 4 ? shm : (size_t)(L + 1) * (L + 1) * P.C * 4;
-    k_bwd_stats<L><<<e2f::xcd_grid(N), C, shm, st>>>(P);
+    k_bwd_stats<L, false><<<e2f::xcd_grid(N), C, shm, st>>>(P);
     if (P.pWb) {
-        k_bwd_target<L, VT, true><<<e2f::xcd_grid(N), C, shm, st>>>(P);
-        k_bwd_source<L, VT, true><<<e2f::xcd_grid(N), C, shm_w, st>>>(P);
+        k_bwd_target<L, VT, true, false><<<e2f::xcd_grid(N), C, shm, st>>>(P);
+        k_bwd_source<L, VT, true, false><<<e2f::xcd_grid(N), C, shm_w, st>>>(P);
     } else {
-        k_bwd_target<L, VT, false><<<e2f::xcd_grid(N), C, shm, st>>>(P);
-        k_bwd_source<L, VT, false><<<e2f::xcd_grid(N), C, shm, st>>>(P);
+        k_bwd_target<L, VT, false, false><<<e2f::xcd_grid(N), C, shm, st>>>(P);
+        k_bwd_source<L, VT, false, false><<<e2f::xcd_grid(N), C, shm, st>>>(P);
+    }
+}
+
+// The per-atom kernels over the tile layouts, for the atoms of crowded tiles only (every other workgroup leaves at
+// once).  `what` 0: the statistics, which the tile kernels of the other tiles read too; 1: the pair kernels.
+template <int L>
+void launch_crowded(const BwdParams& P, int what, hipStream_t st) {
+    const int N = P.cv.N, C = P.C < 64 ? 64 : P.C;
+    const size_t shm = (size_t)BCAP * P.H * sizeof(float2);
+    if (what == 0) {
+        k_bwd_stats<L, true><<<e2f::xcd_grid(N), C, shm, st>>>(P);
+    } else {
+        k_bwd_target<L, uint16_t, false, true><<<e2f::xcd_grid(N), C, shm, st>>>(P);
+        k_bwd_source<L, uint16_t, false, true><<<e2f::xcd_grid(N), C, shm, st>>>(P);
     }
 }
 
@@ -820,26 +900,48 @@ bool e2f_backward_supported(const e2f_ctx* ctx) {
 e2f_status e2f_launch_backward(const e2f_ctx* ctx, const E2fCellsView& cv, const e2f_weights* w, const E2fAttnWs& ws,
                                const E2fBwdWs& bw, const float* out, const float* grad_out, float* grad_pos,
                                float* grad_q, float* grad_k, float* grad_v, const void* h, float* grad_h,
-                               float* grad_Wb, float* grad_w_path, float* grad_W, hipStream_t st) {
+                               float* grad_Wb, float* grad_w_path, float* grad_W, const E2fBwdTileWs* tw,
+                               hipStream_t st) {
     if (cv.N == 0) return E2F_OK;
     const bool wgrad = grad_Wb || grad_w_path;
     if (wgrad && ctx->cfg.B > WB_PER_THREAD * ctx->Ch) return E2F_ERR_UNSUPPORTED;
+    if (tw && wgrad) return E2F_ERR_INVALID_ARG;   // (the tile kernels do not form these sums)
     BwdParams P;
     P.cv = cv;
-    P.spos = ws.spos; P.q = ws.q; P.k = ws.k; P.v = ws.v; P.G = bw.G; P.Wb = w->Wb;
+    P.spos = ws.spos; P.q = ws.q; P.k = ws.k; P.v = ws.v; P.G = tw ? ws.G : bw.G; P.Wb = w->Wb;
     P.out = out; P.gout = grad_out; P.lse = bw.lse; P.Dn = bw.Dn;
     P.gpos = grad_pos; P.gq = grad_q; P.gk = grad_k; P.gv = grad_v;
+    P.q16 = ws.q16; P.k16 = ws.k16; P.v4 = ws.v4;
+    P.stat4 = tw ? reinterpret_cast<float2*>(tw->stat4) : nullptr;
+    P.lists_hdr = ws.lists_hdr;
     P.C = ctx->cfg.C; P.H = ctx->cfg.H; P.B = ctx->cfg.B; P.Ch = ctx->Ch;
     P.tau = ctx->tau; P.rc2 = ctx->rc2; P.cutoff = ctx->cfg.cutoff; P.rbf_step = ctx->rbf_step; P.rbf_gamma = ctx->rbf_gamma;
-    e2f_status rc = e2f_launch_axis_ops(ctx, ws.cw, bw.G, st);
-    if (rc != E2F_OK) return rc;
     P.Gu = nullptr; P.pWb = nullptr; P.pwp = nullptr;
-    if (wgrad) {
+    e2f_status rc;
+    if (tw) {
+        // pair work on the matrix cores, tile by tile; the atoms of crowded tiles (lists that do not fit) go through
+        // the per-atom kernels, which read the same layouts and statistics
+        if ((rc = e2f_launch_tile_lists(ctx, cv, ws, st)) != E2F_OK) return rc;
+        auto crowded = [&](int what) {
+            switch (ctx->cfg.L_max) {
+                case 1: launch_crowded<1>(P, what, st); break;
+                case 2: launch_crowded<2>(P, what, st); break;
+                case 3: launch_crowded<3>(P, what, st); break;
+                default: launch_crowded<4>(P, what, st); break;
+            }
+        };
+        crowded(0);
+        if ((rc = e2f_launch_backward_tile(ctx, cv, ws, *tw, out, grad_out, grad_pos, grad_q, grad_k, grad_v, st)) != E2F_OK)
+            return rc;
+        crowded(1);
+    }
+    if (!tw && (rc = e2f_launch_axis_ops(ctx, ws.cw, bw.G, st)) != E2F_OK) return rc;
+    if (!tw && wgrad) {
         if ((rc = e2f_launch_unit_cw(ctx, bw.cw_unit, st)) != E2F_OK) return rc;
         if ((rc = e2f_launch_axis_ops(ctx, bw.cw_unit, bw.Gu, st)) != E2F_OK) return rc;
         P.Gu = bw.Gu; P.pWb = bw.pWb; P.pwp = bw.pwp;
     }
-    switch (ctx->cfg.L_max) {
+    if (!tw) switch (ctx->cfg.L_max) {
         case 1: launch_L<1>(ctx, P, st); break;
         case 2: launch_L<2>(ctx, P, st); break;
         case 3: launch_L<3>(ctx, P, st); break;

@@ -116,6 +116,18 @@ struct E2fBwdWs {
     size_t bytes;
 };
 
+// Extra buffers of the backward pass's tile kernels (bf16 features, heads of 16 channels), after the ones above: the
+// operands in the layouts the forward pass does not keep, the softmax statistics and partial position gradients.
+struct E2fBwdTileWs {
+    uint16_t* q16g;   // q rows in the grouped layout of k16
+    uint16_t *q4, *k4;   // [group][H][DKP/32][16 features][2 feature tiles][4 slots] bf16
+    uint16_t *vrow, *grow;   // [group][H][steps][4 slots][32] bf16 rows of v and of dL/d out over (component, channel)
+    uint16_t* g4;     // dL/d out in the layout of v4
+    float* stat4;     // [group][H][4 slots][2]: lse (base-2 units), <dL/d out_i, out_i>
+    float* gp_part;   // [2][H][N][3] partial position gradients per side and head group
+    size_t bytes;     // end of the last buffer, counted from the start of the workspace
+};
+
 // Extra O(N) buffers of the factorized pipeline, placed after the attention workspace (untiled v).
 struct E2fFactWs {
     float* hp;   // [N][n][C] source terms h'
@@ -171,11 +183,20 @@ bool e2f_tile_supported(const e2f_ctx* ctx);
 // G[mu][x_out][x_in], mu = x, y, z: the degree-1 filter's message for a unit pair vector along mu, from the path
 // coefficients cw (tile attention kernel, backward pass).
 e2f_status e2f_launch_axis_ops(const e2f_ctx* ctx, const float* cw, float* G, hipStream_t st);
+// Tile form of the backward pass's pair work (e2f_bwd_tile.hip): needs the tile layouts of q, k, v and the candidate
+// lists in `ws`; tiles whose list did not fit are left to the per-atom kernels.
+E2fBwdTileWs e2f_bwd_tile_ws_layout(const e2f_ctx* ctx, int32_t N, void* ws, size_t offset);
+e2f_status e2f_launch_backward_tile(const e2f_ctx* ctx, const E2fCellsView& cv, const E2fAttnWs& ws,
+                                    const E2fBwdTileWs& tw, const float* out, const float* grad_out, float* grad_pos,
+                                    float* grad_q, float* grad_k, float* grad_v, hipStream_t st);
+// The candidate lists of the tile kernels and the axis operators only (a crowded tile gets the header -1 and nothing else).
+e2f_status e2f_launch_tile_lists(const e2f_ctx* ctx, const E2fCellsView& cv, const E2fAttnWs& ws, hipStream_t st);
+// tw: null for the per-atom pair kernels (plain layouts in `ws`), else the tile form (tile layouts in `ws`).
 bool e2f_backward_supported(const e2f_ctx* ctx);
 e2f_status e2f_launch_backward(const e2f_ctx* ctx, const E2fCellsView& cv, const e2f_weights* w, const E2fAttnWs& ws,
                                const E2fBwdWs& bw, const float* out, const float* grad_out, float* grad_pos,
                                float* grad_q, float* grad_k, float* grad_v, const void* h, float* grad_h,
-                               float* grad_Wb, float* grad_w_path, float* grad_W, hipStream_t st);
+                               float* grad_Wb, float* grad_w_path, float* grad_W, const E2fBwdTileWs* tw, hipStream_t st);
 // cw[comp][t] = P coefficient with every path weight one.
 e2f_status e2f_launch_unit_cw(const e2f_ctx* ctx, float* cw, hipStream_t st);
 // table: the caller's padded neighbour table [N][table_K], or null (every atom within the cutoff is a neighbour)

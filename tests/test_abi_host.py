@@ -174,12 +174,26 @@ def test_nonlinear_entry_point_sizes_and_limits(lib):
 
 
 def test_backward_entry_point_sizes_and_limits(lib):
-    """Two [N][H] statistics arrays and the axis operators on top of the untiled attention workspace; the degree-1
-    filter and power-of-two head widths up to 64 only; an empty problem is valid; null gradients are not."""
+    """Per-atom kernels: two [N][H] statistics arrays, the partial sums of the weight gradients and the axis operators
+    on top of the untiled attention workspace.  Tile form (where the forward pass runs on the tile kernels): the tile
+    layouts of q, k, v, the candidate lists, and the operands the forward pass does not keep (q grouped, q and k with
+    four slots per lane, rows of v and dL/d out, dL/d out in v's layout, statistics, partial position gradients).
+    The degree-1 filter and power-of-two head widths up to 64 only; an empty problem is valid; null gradients are not."""
+    stats = 2 * 8 * 4 + 8 * 8 * 4 + 32 * 4
+    per_atom_plain = 16 + 2 * 5 * 128 * 4 + 25 * 128 * 2 + stats
+    qk = 8 * 96 * 2
+    per_atom_tile = (16 + 2 * qk + 8 * 25 * 16 * 2 + (16 + 192 * (4 + 64 + 8)) // 16 + stats
+                     + 3 * qk + 2 * 8 * 416 * 2 + 8 * 25 * 16 * 2 + 8 * 8 + 2 * 8 * 3 * 4)
+    ctx = B.e2f_create(4, 128, 8, 8, 1, 6.0, "bf16", attention="valu")
+    try:
+        s = [B.e2f_attn_backward_workspace_bytes(ctx, N) for N in (10_000, 20_000)]
+        assert abs((s[1] - s[0]) - 10_000 * per_atom_plain) <= 4096
+    finally:
+        B.e2f_destroy(ctx)
     ctx = B.e2f_create(4, 128, 8, 8, 1, 6.0, "bf16")
     try:
         s = [B.e2f_attn_backward_workspace_bytes(ctx, N) for N in (10_000, 20_000)]
-        per_atom = 16 + 2 * 5 * 128 * 4 + 25 * 128 * 2 + 2 * 8 * 4 + 8 * 8 * 4 + 32 * 4
+        per_atom = per_atom_tile
         assert abs((s[1] - s[0]) - 10_000 * per_atom) <= 4096
         assert B.e2f_attn_backward_workspace_bytes(ctx, -1) == 0
         sw = [B.e2f_attn_backward_weights_workspace_bytes(ctx, N) for N in (10_000, 20_000)]

@@ -54,19 +54,35 @@ def run_backward(torch, wl, seed=0):
         g = torch.from_numpy(go).to(P.device)
         got = [x.cpu().numpy().astype(np.float64) for x in P.backward(g, with_weights=True)]
         torch.cuda.synchronize()
-        plain = P.backward(g)   # without the weight gradients the other outputs are the same numbers
-        for x, y in zip(plain, P.backward(g, with_weights=True)):
-            assert torch.equal(x, y)
+        # Without the gradients of Wb and w_path the pair work runs in tile form where the forward pass does (other
+        # kernels, other rounding: checked against the reference on its own); elsewhere it is the same kernels and
+        # the same numbers.
+        plain = P.backward(g)
+        torch.cuda.synchronize()
+        same_kernels = not (cfg["dtype"] == "bf16" and cfg["C"] // cfg["H"] == 16 and cfg["B"] <= 8 and cfg["C"] in (32, 64, 128))
         errs = {}
+        for name, x, y in zip(("pos", "q", "k", "v", "h"), plain, P.backward(g, with_weights=True)):
+            if same_kernels:
+                assert torch.equal(x, y)
+            x = x.cpu().numpy().astype(np.float64)
+            assert np.isfinite(x).all(), name
+            errs["plain " + name] = rel_l2(x, ref[name])
+            assert errs["plain " + name] <= TOL[cfg["dtype"]], (name, errs)
         for name, arr in zip(("pos", "q", "k", "v", "h", "Wb", "w_path", "W"), got):
             assert np.isfinite(arr).all(), name
             assert np.abs(ref[name]).max() > 1e-6, name
             errs[name] = rel_l2(arr, ref[name])
             assert errs[name] <= TOL[cfg["dtype"]], (name, errs)
-        # translation invariance: the position gradients of every segment sum to zero
+        print(errs)
+        plain_pos = plain[0].cpu().numpy().astype(np.float64)
+        # translation invariance: the position gradients of every segment sum to zero.  The per-atom kernels form a
+        # pair's term with the same arithmetic on both of its atoms; the tile kernels round the two sides' operands
+        # differently (G^T g against v, g against G v, in bf16), so there the sum is zero to the tolerance only.
         for s in range(len(wl["seg"]) - 1):
             seg = slice(wl["seg"][s], wl["seg"][s + 1])
-            assert np.abs(got[0][seg].sum(0)).max() <= 1e-3 * max(1.0, np.abs(got[0][seg]).max())
+            for gp, exact in ((got[0][seg], True), (plain_pos[seg], same_kernels)):
+                bound = 1e-3 * max(1.0, np.abs(gp).max()) if exact else TOL[cfg["dtype"]] * max(1.0, np.linalg.norm(gp))
+                assert np.abs(gp.sum(0)).max() <= bound
         return errs
     finally:
         P.close()
@@ -99,6 +115,34 @@ def test_backward_bf16_at_the_benchmark_shape(torch_cuda):
 def test_backward_periodic(torch_cuda):
     from paper_2601_16622_amd import workloads as W
     wl = W.periodic_boxes((220, 120), seed=5, L=2, C=32, H=2, B=6, cutoff=4.0, dtype="f32")
+    run_backward(torch_cuda, wl)
+
+
+def test_backward_tile_form_periodic(torch_cuda):
+    """bf16 features and heads of 16 channels in periodic boxes: the tile kernels of the backward pass with candidate
+    lists that include images (a source sees its targets at the opposite images)."""
+    from paper_2601_16622_amd import workloads as W
+    wl = W.periodic_boxes((300, 150), seed=6, L=2, C=32, H=2, B=8, cutoff=4.0, dtype="bf16")
+    run_backward(torch_cuda, wl)
+
+
+def test_backward_tile_form_with_crowded_tiles(torch_cuda):
+    """1500 atoms in a 6 A cube inside a sparse shell, and a sparse cluster apart: the dense tiles keep more slot groups
+    than a tile's candidate list holds (192 entries; the same recipe as the forward pass's test of long lists) and
+    are left to the per-atom kernels, which read the tile layouts and exchange the softmax statistics with the tile
+    kernels of the sparse tiles around them."""
+    from paper_2601_16622_amd import workloads as W
+    rng = np.random.default_rng(12)
+    cfg = dict(L=1, C=32, H=2, B=8, lf=1, cutoff=4.0, dtype="bf16")
+    mixed = np.concatenate([W.dart_throw_box(rng, 1500, 6.0, min_sep=0.3, origin=(5.0, 5.0, 5.0)),
+                            W.dart_throw_box(rng, 250, 16.0, min_sep=1.5)])
+    sparse = W.dart_throw_box(rng, 200, 14.0, origin=(40.0, 0.0, 0.0))
+    wl = W._pack(cfg, [mixed, sparse], rng, elements=False)
+    import oracle as O
+    offs, _ = O.neighbor_list(wl["pos"], wl["seg"], np.float32(4.0))
+    deg = np.diff(offs)
+    assert deg[:1500].max() > 4 * 256 and deg[1750:].max() < 100
+    assert ((deg[1500:1750] > 100) & (deg[1500:1750] < 600)).any()   # shell atoms that see part of the core
     run_backward(torch_cuda, wl)
 
 
