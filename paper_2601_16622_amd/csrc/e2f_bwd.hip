@@ -702,7 +702,10 @@ __global__ __launch_bounds__(64 * (C / 16)) void k_bwd_project_mfma(
     typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
     typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
     constexpr int NS = C / 32, ROW = C + 8;   // LDS rows of the factors, 16 bytes of padding against bank conflicts
-    __shared__ __attribute__((aligned(16))) uint16_t s_T[5][2][16][ROW];
+    // (two buffers, used in turn: a slab's factors may be written while the slab before it is still being read, so
+    // one barrier per slab is enough)
+    __shared__ __attribute__((aligned(16))) uint16_t s_T[2][5][2][16][ROW];
+    int buf = 0;
     const int ct = threadIdx.x >> 6, lane = threadIdx.x & 63, i = lane & 15, g = lane >> 4;
     const int n = (L + 1) * (L + 1), a0 = blockIdx.x * 16;
     const bool real = a0 + i < N;
@@ -726,14 +729,26 @@ __global__ __launch_bounds__(64 * (C / 16)) void k_bwd_project_mfma(
         }
         const f32x4 dq = real ? *reinterpret_cast<const f32x4*>(gq + ((size_t)atom * (L + 1) + l) * C + ch0) : (f32x4){0.f, 0.f, 0.f, 0.f};
         const f32x4 dk = real ? *reinterpret_cast<const f32x4*>(gk + ((size_t)atom * (L + 1) + l) * C + ch0) : (f32x4){0.f, 0.f, 0.f, 0.f};
+        // the rows of a slab are requested one slab ahead
+        bf16x8 X[NS], Xn[NS];
+        f32x4 gvv, gvn;
+        {
+            const size_t rowx = ((size_t)atom * n + l * l) * C;
+#pragma unroll
+            for (int S = 0; S < NS; ++S) X[S] = frag(h + rowx + 32 * S + 8 * g);
+            gvv = *reinterpret_cast<const f32x4*>(gv + rowx + ch0);
+        }
         for (int m = 0; m < 2 * l + 1; ++m) {
             const int comp = l * l + m;
             const size_t rowx = ((size_t)atom * n + comp) * C;
-            bf16x8 X[NS];
+            {
+                const size_t rown = ((size_t)atom * n + min(comp + 1, n - 1)) * C;
 #pragma unroll
-            for (int S = 0; S < NS; ++S) X[S] = frag(h + rowx + 32 * S + 8 * g);
+                for (int S = 0; S < NS; ++S) Xn[S] = frag(h + rown + 32 * S + 8 * g);
+                gvn = *reinterpret_cast<const f32x4*>(gv + rown + ch0);
+            }
             f32x4 t[5];
-            t[4] = real ? *reinterpret_cast<const f32x4*>(gv + rowx + ch0) : (f32x4){0.f, 0.f, 0.f, 0.f};
+            t[4] = real ? gvv : (f32x4){0.f, 0.f, 0.f, 0.f};
             f32x4 p[4];
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
@@ -750,7 +765,12 @@ __global__ __launch_bounds__(64 * (C / 16)) void k_bwd_project_mfma(
 #pragma unroll
                 for (int k = 0; k < 5; ++k) *reinterpret_cast<f32x4*>(tbuf + ((size_t)k * N + atom) * n * C + (size_t)comp * C + ch0) = t[k];
             }
-            if (!gh) continue;   // (uniform) only the row factors were asked for
+            if (!gh) {   // (uniform) only the row factors were asked for
+#pragma unroll
+                for (int S = 0; S < NS; ++S) X[S] = Xn[S];
+                gvv = gvn;
+                continue;
+            }
 #pragma unroll
             for (int k = 0; k < 5; ++k) {
                 uint16_t hi[4], lo[4];
@@ -759,8 +779,8 @@ __global__ __launch_bounds__(64 * (C / 16)) void k_bwd_project_mfma(
                     hi[r] = e2f::float_to_bf16_bits(t[k][r]);
                     lo[r] = e2f::float_to_bf16_bits(t[k][r] - e2f::bf16_bits_to_float(hi[r]));
                 }
-                *reinterpret_cast<u32x2*>(&s_T[k][0][i][ch0]) = (u32x2){hi[0] | ((uint32_t)hi[1] << 16), hi[2] | ((uint32_t)hi[3] << 16)};
-                *reinterpret_cast<u32x2*>(&s_T[k][1][i][ch0]) = (u32x2){lo[0] | ((uint32_t)lo[1] << 16), lo[2] | ((uint32_t)lo[3] << 16)};
+                *reinterpret_cast<u32x2*>(&s_T[buf][k][0][i][ch0]) = (u32x2){hi[0] | ((uint32_t)hi[1] << 16), hi[2] | ((uint32_t)hi[3] << 16)};
+                *reinterpret_cast<u32x2*>(&s_T[buf][k][1][i][ch0]) = (u32x2){lo[0] | ((uint32_t)lo[1] << 16), lo[2] | ((uint32_t)lo[3] << 16)};
             }
             __syncthreads();
             f32x4 d = {0.f, 0.f, 0.f, 0.f};
@@ -768,12 +788,15 @@ __global__ __launch_bounds__(64 * (C / 16)) void k_bwd_project_mfma(
             for (int k = 0; k < 5; ++k)
 #pragma unroll
                 for (int S = 0; S < NS; ++S) {
-                    d = __builtin_amdgcn_mfma_f32_16x16x32_bf16(W2[k][S], frag(&s_T[k][0][i][32 * S + 8 * g]), d, 0, 0, 0);
-                    d = __builtin_amdgcn_mfma_f32_16x16x32_bf16(W2[k][S], frag(&s_T[k][1][i][32 * S + 8 * g]), d, 0, 0, 0);
+                    d = __builtin_amdgcn_mfma_f32_16x16x32_bf16(W2[k][S], frag(&s_T[buf][k][0][i][32 * S + 8 * g]), d, 0, 0, 0);
+                    d = __builtin_amdgcn_mfma_f32_16x16x32_bf16(W2[k][S], frag(&s_T[buf][k][1][i][32 * S + 8 * g]), d, 0, 0, 0);
                 }
             // d[r] = dL/dh[atom i][comp][channel 16 ct + 4 g + r]
             if (real) *reinterpret_cast<f32x4*>(gh + rowx + ch0) = d;
-            __syncthreads();   // the factors have been read: the next slab may overwrite them
+            buf ^= 1;
+#pragma unroll
+            for (int S = 0; S < NS; ++S) X[S] = Xn[S];
+            gvv = gvn;
         }
     }
 }

@@ -79,7 +79,7 @@ __global__ __launch_bounds__(256) void k_bwd_relayout_qk(BwdTileParams P) {
 }
 
 // ---- relayout: value blocks (four slots of a (component, channel) together) -> rows of (component, channel)
-// One workgroup per group of four sorted slots, thread = (head, component, channel).
+// One workgroup per group of four sorted slots, thread = (head, component, 8 channels): 16-byte stores.
 template <int L>
 __global__ __launch_bounds__(256) void k_bwd_relayout_v(BwdTileParams P) {
     constexpr int n = (L + 1) * (L + 1), VK = n * 16, VS = (VK + 31) / 32, VKP = VS * 32;
@@ -87,22 +87,33 @@ __global__ __launch_bounds__(256) void k_bwd_relayout_v(BwdTileParams P) {
     if ((int)threadIdx.x < n) s_off[threadIdx.x] = e2f::v4_offset(n, threadIdx.x, 0) | (e2f::v4_role(n, threadIdx.x) == 0 ? 0 : 1 << 30);
     __syncthreads();
     const int grp = blockIdx.x, H = P.H;
-    for (int it = threadIdx.x; it < H * VKP; it += 256) {
-        const int head = it / VKP, kk = it % VKP;
-        u32x2 four = {0u, 0u};
+    for (int it = threadIdx.x; it < H * (VKP / 8); it += 256) {
+        const int head = it / (VKP / 8), kk = (it % (VKP / 8)) * 8;
+        u32x2 four[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) four[j] = (u32x2){0u, 0u};
         if (kk < VK) {
             const int x = kk >> 4, ch = kk & 15, o = s_off[x];
-            four = *reinterpret_cast<const u32x2*>(P.v4 + ((size_t)grp * H + head) * n * 64 + (o & 0xffffff) + ch * ((o >> 30) ? 8 : 4));
+            const uint16_t* src = P.v4 + ((size_t)grp * H + head) * n * 64 + (o & 0xffffff) + ch * ((o >> 30) ? 8 : 4);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) four[j] = *reinterpret_cast<const u32x2*>(src + j * ((o >> 30) ? 8 : 4));
         }
         const size_t base = e2f::k16_offset(4 * (size_t)grp, H, head, VKP, kk);
-        P.vrow[base] = (uint16_t)(four[0] & 0xffffu);
-        P.vrow[base + 32] = (uint16_t)(four[0] >> 16);
-        P.vrow[base + 64] = (uint16_t)(four[1] & 0xffffu);
-        P.vrow[base + 96] = (uint16_t)(four[1] >> 16);
+#pragma unroll
+        for (int sl = 0; sl < 4; ++sl) {
+            uint32_t w[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const uint32_t lo = sl < 2 ? four[2 * j][0] : four[2 * j][1], hi = sl < 2 ? four[2 * j + 1][0] : four[2 * j + 1][1];
+                w[j] = (sl & 1) ? (lo >> 16) | (hi & 0xffff0000u) : (lo & 0xffffu) | (hi << 16);
+            }
+            *reinterpret_cast<u32x4*>(P.vrow + base + 32 * sl) = (u32x4){w[0], w[1], w[2], w[3]};
+        }
     }
 }
 
 // ---- relayout: dL/d out (caller's order, fp32) -> bf16 rows and bf16 value-block layout in sorted order
+// One workgroup per group of four sorted slots, thread = (component, 8 channels).
 template <int L>
 __global__ __launch_bounds__(256) void k_bwd_relayout_g(BwdTileParams P) {
     constexpr int n = (L + 1) * (L + 1), VK = n * 16, VS = (VK + 31) / 32, VKP = VS * 32;
@@ -113,18 +124,30 @@ __global__ __launch_bounds__(256) void k_bwd_relayout_g(BwdTileParams P) {
     int atom[4];
 #pragma unroll
     for (int s = 0; s < 4; ++s) atom[s] = 4 * grp + s < N ? P.cv.perm[4 * grp + s] : -1;
-    for (int it = threadIdx.x; it < n * C; it += 256) {
-        const int x = it / C, c = it % C, head = c >> 4, ch = c & 15;
-        uint16_t b[4];
+    for (int it = threadIdx.x; it < n * (C / 8); it += 256) {
+        const int x = it / (C / 8), c = (it % (C / 8)) * 8, head = c >> 4, ch = c & 15;
+        uint16_t b[4][8];
 #pragma unroll
-        for (int s = 0; s < 4; ++s)
-            b[s] = atom[s] >= 0 ? e2f::float_to_bf16_bits(P.gout[((size_t)atom[s] * n + x) * C + c]) : (uint16_t)0;
-        const int o = s_off[x];
-        *reinterpret_cast<u32x2*>(P.g4 + ((size_t)grp * H + head) * n * 64 + (o & 0xffffff) + ch * ((o >> 30) ? 8 : 4)) =
-            (u32x2){b[0] | ((uint32_t)b[1] << 16), b[2] | ((uint32_t)b[3] << 16)};
+        for (int s = 0; s < 4; ++s) {
+            const float* src = P.gout + ((size_t)max(atom[s], 0) * n + x) * C + c;
+            const f32x4 lo = *reinterpret_cast<const f32x4*>(src), hi = *reinterpret_cast<const f32x4*>(src + 4);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                b[s][j] = atom[s] >= 0 ? e2f::float_to_bf16_bits(lo[j]) : (uint16_t)0;
+                b[s][4 + j] = atom[s] >= 0 ? e2f::float_to_bf16_bits(hi[j]) : (uint16_t)0;
+            }
+        }
+        const int o = s_off[x], cs = (o >> 30) ? 8 : 4;
+        uint16_t* d4 = P.g4 + ((size_t)grp * H + head) * n * 64 + (o & 0xffffff) + ch * cs;
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+            *reinterpret_cast<u32x2*>(d4 + j * cs) = (u32x2){b[0][j] | ((uint32_t)b[1][j] << 16), b[2][j] | ((uint32_t)b[3][j] << 16)};
         const size_t base = e2f::k16_offset(4 * (size_t)grp, H, head, VKP, x * 16 + ch);
 #pragma unroll
-        for (int s = 0; s < 4; ++s) P.grow[base + 32 * s] = b[s];
+        for (int s = 0; s < 4; ++s)
+            *reinterpret_cast<u32x4*>(P.grow + base + 32 * s) =
+                (u32x4){b[s][0] | ((uint32_t)b[s][1] << 16), b[s][2] | ((uint32_t)b[s][3] << 16),
+                        b[s][4] | ((uint32_t)b[s][5] << 16), b[s][6] | ((uint32_t)b[s][7] << 16)};
     }
     if (VK < VKP) {   // the rows' padding must be finite: it meets zeros of the other operand
         for (int it = threadIdx.x; it < H * 4 * (VKP - VK); it += 256) {
@@ -210,32 +233,38 @@ __global__ __launch_bounds__(256) void k_bwd_tile_stats(BwdTileParams P) {
         }
         float cb[8];
         bias_coefficients(P, lane, lane < P.B ? P.WbT[lane * H + head] : 0.0f, cb);
-        float dsum = 0.0f;
-        if (datom >= 0) {
+        // <g, out> of this thread's (atom, channel): requested here, summed after the streaming loop
+        float dg[n], dout[n];
 #pragma unroll
-            for (int x = 0; x < n; ++x) {
-                const size_t o = ((size_t)datom * n + x) * C + head * 16 + dch;
-                dsum += P.gout[o] * P.out[o];
-            }
+        for (int x = 0; x < n; ++x) {
+            const size_t o = ((size_t)max(datom, 0) * n + x) * C + head * 16 + dch;
+            dg[x] = P.gout[o];
+            dout[x] = P.out[o];
         }
+        f16x8 kf[2][KS];
+        auto load_K = [&](int c) {
 #pragma unroll
-        for (int off = 1; off < 16; off <<= 1) dsum += __shfl_xor(dsum, off);
-        if (dch == 0) s_D[dt] = dsum;
-        __syncthreads();
+            for (int mt = 0; mt < 2; ++mt) {
+                const int e = s_ent[8 * c + 4 * mt + (tn >> 2)];
+                const size_t off = e2f::k16_offset(4 * (size_t)((unsigned)e >> 8) + (tn & 3), H, head, DKP, 8 * g);
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) kf[mt][ks] = *reinterpret_cast<const f16x8*>(P.k16 + off + 128 * ks);
+            }
+        };
+        if (wave < nch) load_K(wave);
+        __syncthreads();   // s_q is in place
         constexpr float M_NONE = -1.0e30f;
         float m = M_NONE, z = 0.0f;
         for (int c = wave; c < nch; c += NW) {
             f32x4 S[2];
 #pragma unroll
             for (int mt = 0; mt < 2; ++mt) {
-                const int e = s_ent[8 * c + 4 * mt + (tn >> 2)];
-                const size_t off = e2f::k16_offset(4 * (size_t)((unsigned)e >> 8) + (tn & 3), H, head, DKP, 8 * g);
                 S[mt] = (f32x4){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                 for (int ks = 0; ks < KS; ++ks)
-                    S[mt] = mfma(*reinterpret_cast<const f16x8*>(P.k16 + off + 128 * ks),
-                                 *reinterpret_cast<const f16x8*>(s_q + tn * DKP + 32 * ks + 8 * g), S[mt]);
+                    S[mt] = mfma(kf[mt][ks], *reinterpret_cast<const f16x8*>(s_q + tn * DKP + 32 * ks + 8 * g), S[mt]);
             }
+            load_K(min(c + NW, nch - 1));
             float s2[8], cmax = -INFINITY;
 #pragma unroll
             for (int mt = 0; mt < 2; ++mt) {
@@ -272,6 +301,14 @@ __global__ __launch_bounds__(256) void k_bwd_tile_stats(BwdTileParams P) {
         if (lane < 16) {
             s_m[wave][lane] = m;
             s_zz[wave][lane] = z;
+        }
+        {
+            float dsum = 0.0f;
+#pragma unroll
+            for (int x = 0; x < n; ++x) dsum += dg[x] * dout[x];
+#pragma unroll
+            for (int off = 1; off < 16; off <<= 1) dsum += __shfl_xor(dsum, off);
+            if (dch == 0) s_D[dt] = datom >= 0 ? dsum : 0.0f;
         }
         __syncthreads();
         if (tid < 16 && t0 + tid < N) {
@@ -312,8 +349,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     __shared__ unsigned long long s_mask[LENT];
     __shared__ float4 s_pos[LENT * 4];
     __shared__ __attribute__((aligned(16))) uint16_t s_rows[16 * DKP];
-    __shared__ float s_G[AXIS_NNZ];
     __shared__ float s_gp[NW][16][3];
+    __shared__ float s_G[AXIS_NNZ];
     // the tile side of U as B operands [mu][step][lane]; at the end of a head the same bytes hold the waves' dq tiles
     __shared__ __attribute__((aligned(16))) unsigned char s_big[GX_BYTES > RED_BYTES ? GX_BYTES : RED_BYTES];
     u32x4* s_GX = reinterpret_cast<u32x4*>(s_big);
@@ -327,10 +364,12 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     const int N = P.cv.N, H = P.H, C = P.C;
     const int t0 = tile * 16, tslot = min(t0 + tn, N - 1);
     const float4 tp = P.spos[tslot];
-    const float g_mine = tid < AXIS_NNZ ? P.G[AXIS_PACKED_AT + tid] : 0.0f;
+    const float* __restrict__ Gp = P.G + AXIS_PACKED_AT;
+    const float g_mine = tid < AXIS_NNZ ? Gp[tid] : 0.0f;
     const int cnt = load_list(P, tile, tid, tp, s_ent, s_mask, s_pos);
     if (cnt < 0) return;   // (whole workgroup) a crowded tile: done by the per-atom kernels
     if (tid < AXIS_NNZ) s_G[tid] = g_mine;
+    __syncthreads();
     const int nch = (cnt + 7) >> 3;
     const float c_u = 2.0f * P.rbf_gamma * P.rbf_step * LOG2E, c_g = -P.rbf_gamma * LOG2E;
     const float two_gamma = 2.0f * P.rbf_gamma, rev = 0.5f / P.cutoff, dphi_scale = -0.5f * 3.14159265358979f / P.cutoff;
@@ -345,6 +384,32 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 
     for (int hh = 0; hh < P.hpw; ++hh) {
         const int head = hg * P.hpw + hh;
+        // ---- the first chunk's rows are requested before the head's set-up, which hides their latency
+        f16x8 kf[2][KS];
+        bf16x8 X[2][VP];
+        auto load_K = [&](int c) {
+#pragma unroll
+            for (int mt = 0; mt < 2; ++mt) {
+                const int e = s_ent[8 * c + 4 * mt + (tn >> 2)];
+                const size_t off = e2f::k16_offset(4 * (size_t)((unsigned)e >> 8) + (tn & 3), H, head, DKP, 8 * g);
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) kf[mt][ks] = *reinterpret_cast<const f16x8*>(rowsK + off + 128 * ks);
+            }
+        };
+        auto load_X = [&](int c, int first, int count) {
+#pragma unroll
+            for (int mt = 0; mt < 2; ++mt) {
+                const int e = s_ent[8 * c + 4 * mt + (tn >> 2)];
+                const size_t off = e2f::k16_offset(4 * (size_t)((unsigned)e >> 8) + (tn & 3), H, head, VKP, 8 * g);
+#pragma unroll
+                for (int s = 0; s < VP; ++s)
+                    if (s < count) X[mt][s] = *reinterpret_cast<const bf16x8*>(rowsV + off + 128 * (first + s));
+            }
+        };
+        if (wave < nch) {
+            load_K(wave);
+            load_X(wave, 0, VP);
+        }
         // ---- the tile's rows of the logits -> LDS
         if (tid < 16 * (DKP / 8)) {
             const int tq = tid / (DKP / 8), f8 = tid % (DKP / 8), slot = min(t0 + tq, N - 1);
@@ -369,7 +434,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
             for (int mu = 0; mu < 3; ++mu)
 #pragma unroll
                 for (int x = 0; x < n; ++x) o[mu][x] = 0.0f;
-            if (hh == 0) __syncthreads();   // s_G is in place
 #pragma unroll
             for (int mu = 0; mu < 3; ++mu)
 #pragma unroll
@@ -405,31 +469,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
         for (int t = 0; t < NT; ++t) dacc[t] = (f32x4){0.f, 0.f, 0.f, 0.f};
         float gx = 0.0f, gy = 0.0f, gz = 0.0f;
 
-        f16x8 kf[2][KS];
-        bf16x8 X[2][VP];
-        auto load_K = [&](int c) {
-#pragma unroll
-            for (int mt = 0; mt < 2; ++mt) {
-                const int e = s_ent[8 * c + 4 * mt + (tn >> 2)];
-                const size_t off = e2f::k16_offset(4 * (size_t)((unsigned)e >> 8) + (tn & 3), H, head, DKP, 8 * g);
-#pragma unroll
-                for (int ks = 0; ks < KS; ++ks) kf[mt][ks] = *reinterpret_cast<const f16x8*>(rowsK + off + 128 * ks);
-            }
-        };
-        auto load_X = [&](int c, int first, int count) {
-#pragma unroll
-            for (int mt = 0; mt < 2; ++mt) {
-                const int e = s_ent[8 * c + 4 * mt + (tn >> 2)];
-                const size_t off = e2f::k16_offset(4 * (size_t)((unsigned)e >> 8) + (tn & 3), H, head, VKP, 8 * g);
-#pragma unroll
-                for (int s = 0; s < VP; ++s)
-                    if (s < count) X[mt][s] = *reinterpret_cast<const bf16x8*>(rowsV + off + 128 * (first + s));
-            }
-        };
-        if (wave < nch) {
-            load_K(wave);
-            load_X(wave, 0, VP);
-        }
         for (int c = wave; c < nch; c += NW) {
             const int cn = min(c + NW, nch - 1);
             // candidates' statistics (sources) and their rows for the dq product
