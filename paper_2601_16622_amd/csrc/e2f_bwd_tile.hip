@@ -190,17 +190,16 @@ __device__ __forceinline__ int load_list(const BwdTileParams& P, int tile, int t
     return cnt;
 }
 
-// Radial bias of a head as a polynomial in u = e^{2 gamma step d}:  b(d) = e^{-gamma d^2} sum_b cb[b] u^b with
-// cb[b] = Wb[h][b] e^{-gamma (b step)^2} log2 e (base-2 units).  `mine`: Wb[h][lane] for lane < B, else 0.
-__device__ __forceinline__ void bias_coefficients(const BwdTileParams& P, int lane, float mine, float (&cb)[8]) {
-    const float bs = (float)lane * P.rbf_step;
-    const float t = mine * __expf(-P.rbf_gamma * bs * bs) * LOG2E;
+// Coefficients of a head's radial bias (bias_value): `mine` is Wb[h][lane] for lane < B, else 0.
+template <int NB>
+__device__ __forceinline__ void bias_coefficients(const BwdTileParams& P, int lane, float mine, float (&cb)[NB]) {
+    const float t = bias_coefficient<NB>(mine, lane, P.rbf_step, P.rbf_gamma);
 #pragma unroll
-    for (int b = 0; b < 8; ++b) cb[b] = read_lane(t, b);
+    for (int b = 0; b < NB; ++b) cb[b] = read_lane(t, b);
 }
 
 // ---- softmax statistics: lse_i (base-2 units, reference included) and D_i = <g_i, out_i>, per head
-template <int L>
+template <int L, int NB>
 __global__ __launch_bounds__(256) void k_bwd_tile_stats(BwdTileParams P) {
     constexpr int NW = 4, n = (L + 1) * (L + 1);
     constexpr int DK = (L + 1) * 16, KS = (DK + 31) / 32, DKP = KS * 32;
@@ -231,7 +230,7 @@ __global__ __launch_bounds__(256) void k_bwd_tile_stats(BwdTileParams P) {
             reinterpret_cast<u32x4*>(s_q)[tid] =
                 *reinterpret_cast<const u32x4*>(P.q16 + ((size_t)min(t0 + tq, N - 1) * H + head) * DKP + 8 * f8);
         }
-        float cb[8];
+        float cb[NB];
         bias_coefficients(P, lane, lane < P.B ? P.WbT[lane * H + head] : 0.0f, cb);
         // <g, out> of this thread's (atom, channel): requested here, summed after the streaming loop
         float dg[n], dout[n];
@@ -276,11 +275,7 @@ __global__ __launch_bounds__(256) void k_bwd_tile_stats(BwdTileParams P) {
                     const float d2 = e2f::dist2_exact(tp.x, tp.y, tp.z, pc.x, pc.y, pc.z);
                     const bool ok = (((mine4 >> r) & 1u) != 0u) & (d2 < P.rc2) & (d2 > 0.0f);
                     const float d = __builtin_amdgcn_sqrtf(d2);
-                    const float uu = __builtin_amdgcn_exp2f(c_u * d);
-                    float poly = cb[7];
-#pragma unroll
-                    for (int bb = 6; bb >= 0; --bb) poly = poly * uu + cb[bb];
-                    float bias = __builtin_amdgcn_exp2f(c_g * d2) * poly;
+                    float bias = bias_value<NB>(cb, d, d2, c_u, c_g, P.rbf_step);
                     asm("" : "+v"(bias));
                     s2[4 * mt + r] = ok ? S[mt][r] + bias : -INFINITY;
                     cmax = fmaxf(cmax, s2[4 * mt + r]);
@@ -336,7 +331,7 @@ __global__ __launch_bounds__(256) void k_bwd_tile_stats(BwdTileParams P) {
 //   dT   += dS Y4          dS in the logits' register layout is the A operand; Y4 the candidates' k (or q) with the four
 //                          slots of a group per lane
 // and the per-pair scalars in between, one tile atom per lane against 8 candidates.
-template <int L, bool SRC>
+template <int L, bool SRC, int NB>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void k_bwd_tile_pairs(BwdTileParams P) {
     constexpr int NW = 4, n = (L + 1) * (L + 1);
     constexpr int DK = (L + 1) * 16, KS = (DK + 31) / 32, DKP = KS * 32;
@@ -372,7 +367,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     __syncthreads();
     const int nch = (cnt + 7) >> 3;
     const float c_u = 2.0f * P.rbf_gamma * P.rbf_step * LOG2E, c_g = -P.rbf_gamma * LOG2E;
-    const float two_gamma = 2.0f * P.rbf_gamma, rev = 0.5f / P.cutoff, dphi_scale = -0.5f * 3.14159265358979f / P.cutoff;
+    const float rev = 0.5f / P.cutoff, dphi_scale = -0.5f * 3.14159265358979f / P.cutoff;
     // candidate rows of the logits, of U and of the dq product
     const uint16_t* rowsK = SRC ? P.q16g : P.k16;
     const uint16_t* rowsV = SRC ? P.grow : P.vrow;
@@ -458,7 +453,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
                 }
             }
         }
-        float cb[8];
+        float cb[NB];
         bias_coefficients(P, lane, lane < P.B ? P.WbT[lane * H + head] : 0.0f, cb);
         // the tile atom's own statistics (targets); sources read those of the candidates per chunk
         const float2 st_mine = P.stat4[((size_t)(tslot >> 2) * H + head) * 4 + (tslot & 3)];
@@ -528,16 +523,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
                     const float d2 = e2f::dist2_exact(tp.x, tp.y, tp.z, pc.x, pc.y, pc.z);
                     const bool ok = (((mine4 >> r) & 1u) != 0u) & (d2 < P.rc2) & (d2 > 0.0f);
                     const float d = __builtin_amdgcn_sqrtf(d2);
-                    const float uu = __builtin_amdgcn_exp2f(c_u * d), E = __builtin_amdgcn_exp2f(c_g * d2);
-                    float poly = cb[7], dpoly = 0.0f;   // the polynomial and its derivative in u
-#pragma unroll
-                    for (int bb = 6; bb >= 0; --bb) {
-                        dpoly = dpoly * uu + poly;
-                        poly = poly * uu + cb[bb];
-                    }
-                    float bias = E * poly;
-                    // d/dd of the bias in natural units: 2 gamma (step e^{-gamma d^2} u poly'(u) - d b) ln 2
-                    float dbias = two_gamma * (P.rbf_step * E * uu * dpoly - d * bias) * LN2;
+                    float bias, dbias;   // the bias in base-2 units, its derivative in natural units
+                    bias_value_grad<NB>(cb, d, d2, c_u, c_g, P.rbf_step, P.rbf_gamma, bias, dbias);
                     asm("" : "+v"(bias), "+v"(dbias));   // (evaluated for every candidate: one basic block)
                     const float lse = SRC ? (r == 0 ? st[mt][0].x : r == 1 ? st[mt][0].z : r == 2 ? st[mt][1].x : st[mt][1].z) : st_mine.x;
                     p[u] = ok ? __builtin_amdgcn_exp2f(S[mt][r] + bias - lse) : 0.0f;
@@ -646,7 +633,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 // the softmax weights from the stored statistics.  The waves score a chunk each and share the weights through LDS (two
 // buffers, one barrier per group of four chunks); every wave aggregates all four chunks into its quarter of the
 // components.
-template <int L>
+template <int L, int NB>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void k_bwd_tile_dv(BwdTileParams P) {
     constexpr int NW = 4, n = (L + 1) * (L + 1), NX = (n + NW - 1) / NW;
     constexpr int DK = (L + 1) * 16, KS = (DK + 31) / 32, DKP = KS * 32;
@@ -708,7 +695,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
             reinterpret_cast<u32x4*>(s_rows)[tid] =
                 *reinterpret_cast<const u32x4*>(P.k16 + e2f::k16_offset(min(t0 + tq, N - 1), H, head, DKP, 8 * f8));
         }
-        float cb[8];
+        float cb[NB];
         bias_coefficients(P, lane, lane < P.B ? P.WbT[lane * H + head] : 0.0f, cb);
         if (nch > 0) {
             load_K(min(wave, nch - 1), head);
@@ -763,11 +750,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
                         const float d2 = e2f::dist2_exact(tp.x, tp.y, tp.z, pc.x, pc.y, pc.z);
                         const bool ok = (((mine4 >> r) & 1u) != 0u) & (d2 < P.rc2) & (d2 > 0.0f);
                         const float d = __builtin_amdgcn_sqrtf(d2);
-                        const float uu = __builtin_amdgcn_exp2f(c_u * d);
-                        float poly = cb[7];
-#pragma unroll
-                        for (int bb = 6; bb >= 0; --bb) poly = poly * uu + cb[bb];
-                        float bias = __builtin_amdgcn_exp2f(c_g * d2) * poly;
+                        float bias = bias_value<NB>(cb, d, d2, c_u, c_g, P.rbf_step);
                         asm("" : "+v"(bias));
                         const float lse = r == 0 ? st[mt][0].x : r == 1 ? st[mt][0].z : r == 2 ? st[mt][1].x : st[mt][1].z;
                         const float p = ok ? __builtin_amdgcn_exp2f(S[mt][r] + bias - lse) : 0.0f;
@@ -877,10 +860,17 @@ void launch_L(const BwdTileParams& P, hipStream_t st) {
     k_bwd_relayout_qk<L><<<groups, 256, 0, st>>>(P);
     k_bwd_relayout_v<L><<<groups, 256, 0, st>>>(P);
     k_bwd_relayout_g<L><<<groups, 256, 0, st>>>(P);
-    k_bwd_tile_stats<L><<<grid, 256, 0, st>>>(P);
-    k_bwd_tile_pairs<L, false><<<grid, 256, 0, st>>>(P);
-    k_bwd_tile_pairs<L, true><<<grid, 256, 0, st>>>(P);
-    k_bwd_tile_dv<L><<<grid, 256, 0, st>>>(P);
+    if (P.B > 8) {   // (the radial bias polynomial has its coefficients in registers: instances for B <= 8 and B <= 16)
+        k_bwd_tile_stats<L, 16><<<grid, 256, 0, st>>>(P);
+        k_bwd_tile_pairs<L, false, 16><<<grid, 256, 0, st>>>(P);
+        k_bwd_tile_pairs<L, true, 16><<<grid, 256, 0, st>>>(P);
+        k_bwd_tile_dv<L, 16><<<grid, 256, 0, st>>>(P);
+    } else {
+        k_bwd_tile_stats<L, 8><<<grid, 256, 0, st>>>(P);
+        k_bwd_tile_pairs<L, false, 8><<<grid, 256, 0, st>>>(P);
+        k_bwd_tile_pairs<L, true, 8><<<grid, 256, 0, st>>>(P);
+        k_bwd_tile_dv<L, 8><<<grid, 256, 0, st>>>(P);
+    }
     k_bwd_gpos_reduce<<<(N * 3 + 255) / 256, 256, 0, st>>>(P.cv, P.gp_part, 2 * HG, P.lists_hdr, P.gpos);
 }
 

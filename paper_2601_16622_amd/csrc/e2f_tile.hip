@@ -91,7 +91,7 @@ __global__ void k_axis_ops(const float* __restrict__ cw, float* __restrict__ G, 
 // candidate counts only for the targets of the pass that found it (k_tile_heads reads those lists; tiles whose list
 // does not fit LCAP entries are finished by the list kernel's own workgroup, head by head, in MODE 0).
 // CAP: whether a neighbour cap is in force (threshold keys per target).
-template <int L, int NW, bool PBC, int MODE, bool CAP>
+template <int L, int NW, bool PBC, int MODE, bool CAP, int NB>
 __device__ __forceinline__ void tile_item(const TileParams& P, const int tile, const int head) {
     constexpr int n = (L + 1) * (L + 1), NX = (n + NW - 1) / NW;
     constexpr int PADE = 8 * NW;        // the list is padded to whole groups of NW chunks
@@ -141,14 +141,14 @@ __device__ __forceinline__ void tile_item(const TileParams& P, const int tile, c
     const int4 ti0 = P.cv.sinfo[2 * tslot], ti1 = P.cv.sinfo[2 * tslot + 1];
     const int tseg = ti0.x, tcx = ti0.y, trow = ti0.w * ti1.y + ti0.z;   // row of cells: cz * ny + cy
 
-    // radial bias of this head as a polynomial in u = e^{2 gamma step d}:  b(d) = e^{-gamma d^2} sum_b cb[b] u^b,
-    // cb[b] = Wb[h][b] e^{-gamma (b step)^2} (log2 e folded in)
-    float cb[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-    if constexpr (MODE != 1) {
-        const float bs = (float)lane * P.rbf_step;
-        const float mine = lane < P.B ? P.WbT[lane * H + head] * __expf(-P.rbf_gamma * bs * bs) * 1.44269504088896341f : 0.0f;
+    // coefficients of this head's radial bias (bias_value)
+    float cb[NB];
 #pragma unroll
-        for (int b = 0; b < 8; ++b) cb[b] = read_lane(mine, b);
+    for (int b = 0; b < NB; ++b) cb[b] = 0.0f;
+    if constexpr (MODE != 1) {
+        const float mine = lane < P.B ? bias_coefficient<NB>(P.WbT[lane * H + head], lane, P.rbf_step, P.rbf_gamma) : 0.0f;
+#pragma unroll
+        for (int b = 0; b < NB; ++b) cb[b] = read_lane(mine, b);
     }
     const float c_u = 2.0f * P.rbf_gamma * P.rbf_step * 1.44269504088896341f;
     const float c_g = -P.rbf_gamma * 1.44269504088896341f;
@@ -462,11 +462,7 @@ __device__ __forceinline__ void tile_item(const TileParams& P, const int tile, c
                             const bool ok = (((mine4 >> r) & 1u) != 0u) & (d2 < P.rc2) & (d2 > 0.0f) &
                                             (!CAP || e2f::under_cap(d2, pc.w, capd, capi));
                             const float d = __builtin_amdgcn_sqrtf(d2);
-                            const float uu = __builtin_amdgcn_exp2f(c_u * d);
-                            float poly = cb[7];
-#pragma unroll
-                            for (int bb = 6; bb >= 0; --bb) poly = poly * uu + cb[bb];
-                            float bias = __builtin_amdgcn_exp2f(c_g * d2) * poly;
+                            float bias = bias_value<NB>(cb, d, d2, c_u, c_g, P.rbf_step);
                             // (evaluated for every candidate, not under its predicate: otherwise each of the eight
                             // candidates becomes a basic block of its own and their LDS reads are issued one by one)
                             asm("" : "+v"(bias));
@@ -587,7 +583,7 @@ __device__ __forceinline__ void tile_item(const TileParams& P, const int tile, c
             TileParams Q = P;
             Q.G = own_G;
             for (int h = 0; h < P.H; ++h) {
-                tile_item<L, NW, PBC, 0, CAP>(Q, tile, h);
+                tile_item<L, NW, PBC, 0, CAP, NB>(Q, tile, h);
                 __syncthreads();   // the next head reuses the shared arrays
             }
         }
@@ -671,7 +667,7 @@ __device__ __forceinline__ void tile_item(const TileParams& P, const int tile, c
 // the axis operators) is fetched once, all of it requested before any of it is used, and stays in LDS for every head;
 // what belongs to a head (its queries, its radial weights, the key and value rows of the first chunks) is requested
 // while the head before it is in its epilogue.  The streaming loop and the epilogue are those of tile_item.
-template <int L, bool CAP>
+template <int L, bool CAP, int NB>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void k_tile_heads(TileParams P) {
     constexpr int NW = 4, n = (L + 1) * (L + 1), NX = (n + NW - 1) / NW;
     constexpr int DK = (L + 1) * 16, KS = (DK + 31) / 32, DKP = KS * 32;
@@ -757,8 +753,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     const int nch = (cnt + 7) >> 3, ngr = (nch + NW - 1) / NW;
     const float c_u = 2.0f * P.rbf_gamma * P.rbf_step * 1.44269504088896341f;
     const float c_g = -P.rbf_gamma * 1.44269504088896341f;
-    const float bs = (float)lane * P.rbf_step;
-    const float rbf_mine = __expf(-P.rbf_gamma * bs * bs) * 1.44269504088896341f;
+    const float rbf_mine = bias_coefficient<NB>(1.0f, lane, P.rbf_step, P.rbf_gamma);
 
     f16x8 kf[2][KS];
     VRows<NP> vr;
@@ -793,13 +788,12 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 
     for (int hh = 0; hh < P.hpw; ++hh) {
         const int head = head0 + hh;
-        // radial bias of this head as a polynomial in u = e^{2 gamma step d}:  b(d) = e^{-gamma d^2} sum_b cb[b] u^b,
-        // cb[b] = Wb[h][b] e^{-gamma (b step)^2} (log2 e folded in)
-        float cb[8];
+        // coefficients of this head's radial bias (bias_value)
+        float cb[NB];
         {
             const float mine = wb_mine * rbf_mine;
 #pragma unroll
-            for (int b = 0; b < 8; ++b) cb[b] = read_lane(mine, b);
+            for (int b = 0; b < NB; ++b) cb[b] = read_lane(mine, b);
         }
         f32x4 acc[3][NS];
 #pragma unroll
@@ -841,11 +835,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
                     const bool ok = (((mine4 >> r) & 1u) != 0u) & (d2 < P.rc2) & (d2 > 0.0f) &
                                     (!CAP || e2f::under_cap(d2, pc.w, capd, capi));
                     const float d = __builtin_amdgcn_sqrtf(d2);
-                    const float uu = __builtin_amdgcn_exp2f(c_u * d);
-                    float poly = cb[7];
-#pragma unroll
-                    for (int bb = 6; bb >= 0; --bb) poly = poly * uu + cb[bb];
-                    float bias = __builtin_amdgcn_exp2f(c_g * d2) * poly;
+                    float bias = bias_value<NB>(cb, d, d2, c_u, c_g, P.rbf_step);
                     // (evaluated for every candidate, not under its predicate: otherwise each of the eight
                     // candidates becomes a basic block of its own and their LDS reads are issued one by one)
                     asm("" : "+v"(bias));
@@ -1017,7 +1007,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     }
 }
 
-template <int L, int NW, bool PBC, int MODE, bool CAP>
+template <int L, int NW, bool PBC, int MODE, bool CAP, int NB>
 __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(E2F_TILE_OCC(NW), E2F_TILE_OCC(NW)))) void k_tile(TileParams P) {
     int tile, head;
     if constexpr (MODE == 1) {
@@ -1030,7 +1020,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(E2F_TIL
     } else {
         if (!tile_xcd_remap(blockIdx.x, P.n_tiles, P.H, tile, head)) return;   // whole workgroup
     }
-    tile_item<L, NW, PBC, MODE, CAP>(P, tile, head);
+    tile_item<L, NW, PBC, MODE, CAP, NB>(P, tile, head);
 }
 
 // what: 1 the list kernel (with the axis operators), 2 the attention kernel reading the lists, 0 the attention kernel
@@ -1042,17 +1032,27 @@ void launch_L(const TileParams& P, const float* cw, float* G, int what, hipStrea
     // four waves per workgroup, two workgroups per CU: with eight waves the 128 registers left per wave do not
     // hold a wave's accumulators, value rows and key rows without spilling into the streaming loop
     const bool cap = P.cap_d2 != nullptr;
+    // the radial bias is a polynomial of degree B - 1 with its coefficients in registers: instances for B <= 8 and B <= 16
     auto go = [&](auto pbc, auto capped) {
         constexpr bool PBC = decltype(pbc)::value, CAP = decltype(capped)::value;
+        if (P.B > 8) {
+            if (what == 1) k_tile<L, 4, PBC, 1, CAP, 16><<<P.n_tiles + 1, 256, 0, st>>>(P);
+            else if (what == 2) k_tile_heads<L, CAP, 16><<<((chunks + 7) / 8) * 8 * TILE_BLK * (P.H / P.hpw), 256, 0, st>>>(P);
+            else {
+                k_axis_ops<L><<<1, 128, 0, st>>>(cw, G, true);
+                k_tile<L, 4, PBC, 0, CAP, 16><<<grid, 256, 0, st>>>(P);
+            }
+            return;
+        }
         if (what == 1) {
-            k_tile<L, 4, PBC, 1, CAP><<<P.n_tiles + 1, 256, 0, st>>>(P);
+            k_tile<L, 4, PBC, 1, CAP, 8><<<P.n_tiles + 1, 256, 0, st>>>(P);
         } else if (what == 2) {
             const int hg_chunks = (P.n_tiles + TILE_BLK - 1) / TILE_BLK;
             const int hgrid = ((hg_chunks + 7) / 8) * 8 * TILE_BLK * (P.H / P.hpw);
-            k_tile_heads<L, CAP><<<hgrid, 256, 0, st>>>(P);
+            k_tile_heads<L, CAP, 8><<<hgrid, 256, 0, st>>>(P);
         } else {
             k_axis_ops<L><<<1, 128, 0, st>>>(cw, G, true);
-            k_tile<L, 4, PBC, 0, CAP><<<grid, 256, 0, st>>>(P);
+            k_tile<L, 4, PBC, 0, CAP, 8><<<grid, 256, 0, st>>>(P);
         }
     };
     if (P.cv.periodic) cap ? go(std::true_type{}, std::true_type{}) : go(std::true_type{}, std::false_type{});
@@ -1076,7 +1076,7 @@ e2f_status e2f_launch_axis_ops(const e2f_ctx* ctx, const float* cw, float* G, hi
 bool e2f_tile_supported(const e2f_ctx* ctx) {
     const int C = ctx->cfg.C;
     return ctx->cfg.feat_dtype == E2F_BF16 && ctx->cfg.lf == 1 && ctx->Ch == 16 && ctx->cfg.L_max >= 1 &&
-           ctx->cfg.B <= 8 && (C == 32 || C == 64 || C == 128);
+           ctx->cfg.B <= 16 && (C == 32 || C == 64 || C == 128);
 }
 
 static e2f_status launch_tile(const e2f_ctx* ctx, const E2fCellsView& cv, const E2fAttnWs& ws, const int32_t* table,

@@ -72,6 +72,76 @@ __device__ __forceinline__ f32x4 mfma(f16x8 a, f16x8 b, f32x4 c) {
     return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0);
 }
 
+// Radial bias of a head, b(d) = sum_b Wb[b] exp(-gamma (d - b step)^2), in base-2 units, evaluated per pair from NB
+// coefficients that every lane holds (uniform).  Up to 8 basis functions: a polynomial in u = e^{2 gamma step d},
+//     b(d) = e^{-gamma d^2} sum_b cb[b] u^b ,       cb[b] = Wb[b] e^{-gamma (b step)^2} log2 e .
+// Up to 16: u^15 would leave the range of binary32, so the same expansion is taken around the middle basis function
+// m = NB/2, x = d - m step:  b(d) = e^{-gamma x^2} ( sum_{b >= m} cb[b] t^(b-m) + sum_{b < m} cb[b] t^-(m-b) ) with
+// t = e^{2 gamma step x} and cb[b] = Wb[b] e^{-gamma ((b-m) step)^2} log2 e; every power stays below e^60.
+template <int NB>
+__device__ __forceinline__ float bias_coefficient(float wb, int b, float step, float gamma) {
+    const float bs = (float)(b - (NB > 8 ? NB / 2 : 0)) * step;
+    return wb * __expf(-gamma * bs * bs) * 1.44269504088896341f;
+}
+// c_u = 2 gamma step log2 e, c_g = -gamma log2 e
+template <int NB>
+__device__ __forceinline__ float bias_value(const float (&cb)[NB], float d, float d2, float c_u, float c_g, float step) {
+    if constexpr (NB <= 8) {
+        const float uu = __builtin_amdgcn_exp2f(c_u * d);
+        float poly = cb[NB - 1];
+#pragma unroll
+        for (int bb = NB - 2; bb >= 0; --bb) poly = poly * uu + cb[bb];
+        return __builtin_amdgcn_exp2f(c_g * d2) * poly;
+    } else {
+        constexpr int M = NB / 2;
+        const float x = d - (float)M * step;
+        const float t = __builtin_amdgcn_exp2f(c_u * x), ti = __builtin_amdgcn_exp2f(-c_u * x);
+        float hi = cb[NB - 1], lo = cb[0];
+#pragma unroll
+        for (int bb = NB - 2; bb >= M; --bb) hi = hi * t + cb[bb];
+#pragma unroll
+        for (int bb = 1; bb < M; ++bb) lo = lo * ti + cb[bb];
+        return __builtin_amdgcn_exp2f(c_g * x * x) * (hi + lo * ti);
+    }
+}
+// The bias (base-2 units) and its derivative with respect to d in natural units.
+template <int NB>
+__device__ __forceinline__ void bias_value_grad(const float (&cb)[NB], float d, float d2, float c_u, float c_g, float step,
+                                                float gamma, float& bias, float& dbias) {
+    constexpr float LN2 = 0.69314718055994531f;
+    if constexpr (NB <= 8) {
+        const float uu = __builtin_amdgcn_exp2f(c_u * d), E = __builtin_amdgcn_exp2f(c_g * d2);
+        float poly = cb[NB - 1], dpoly = 0.0f;   // the polynomial and its derivative in u
+#pragma unroll
+        for (int bb = NB - 2; bb >= 0; --bb) {
+            dpoly = dpoly * uu + poly;
+            poly = poly * uu + cb[bb];
+        }
+        bias = E * poly;
+        // 2 gamma (step e^{-gamma d^2} u poly'(u) - d b) ln 2
+        dbias = 2.0f * gamma * (step * E * uu * dpoly - d * bias) * LN2;
+    } else {
+        constexpr int M = NB / 2;
+        const float x = d - (float)M * step;
+        const float t = __builtin_amdgcn_exp2f(c_u * x), ti = __builtin_amdgcn_exp2f(-c_u * x), E = __builtin_amdgcn_exp2f(c_g * x * x);
+        float hi = cb[NB - 1], dhi = 0.0f, lo = cb[0], dlo = 0.0f;
+#pragma unroll
+        for (int bb = NB - 2; bb >= M; --bb) {
+            dhi = dhi * t + hi;
+            hi = hi * t + cb[bb];
+        }
+#pragma unroll
+        for (int bb = 1; bb < M; ++bb) {
+            dlo = dlo * ti + lo;
+            lo = lo * ti + cb[bb];
+        }
+        // with Lo(ti) = ti lo(ti):  t d/dt of the bracket = t hi'(t) - ti Lo'(ti) = t hi' - ti (lo + ti lo')
+        const float low = lo * ti;
+        bias = E * (hi + low);
+        dbias = 2.0f * gamma * (step * E * (t * dhi - low - ti * ti * dlo) - x * bias) * LN2;
+    }
+}
+
 // The candidate list in LDS is private to a wave, whose LDS operations complete in order: ordering them in the
 // instruction stream is all that is needed, no workgroup barrier.
 __device__ __forceinline__ void wave_lds_sync() {

@@ -59,7 +59,7 @@ def run_backward(torch, wl, seed=0):
         # the same numbers.
         plain = P.backward(g)
         torch.cuda.synchronize()
-        same_kernels = not (cfg["dtype"] == "bf16" and cfg["C"] // cfg["H"] == 16 and cfg["B"] <= 8 and cfg["C"] in (32, 64, 128))
+        same_kernels = not (cfg["dtype"] == "bf16" and cfg["C"] // cfg["H"] == 16 and cfg["B"] <= 16 and cfg["C"] in (32, 64, 128))
         errs = {}
         for name, x, y in zip(("pos", "q", "k", "v", "h"), plain, P.backward(g, with_weights=True)):
             if same_kernels:
@@ -115,6 +115,12 @@ def test_backward_bf16_at_the_benchmark_shape(torch_cuda):
 def test_backward_periodic(torch_cuda):
     from paper_2601_16622_amd import workloads as W
     wl = W.periodic_boxes((220, 120), seed=5, L=2, C=32, H=2, B=6, cutoff=4.0, dtype="f32")
+    run_backward(torch_cuda, wl)
+
+
+def test_backward_tile_form_with_12_radial_functions(torch_cuda):
+    """The tile kernels' instances for more than 8 radial basis functions (the bias polynomial and its derivative)."""
+    wl = custom(21, (230, 40), 3, 64, 4, 12, "bf16", 4.5, 11.0)
     run_backward(torch_cuda, wl)
 
 

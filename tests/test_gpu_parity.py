@@ -154,13 +154,15 @@ def _custom(seed, N, L, C, H, B, lf, dtype, cutoff=3.0, side=6.0, seg=None):
     dict(N=72, L=4, C=16, H=2, B=8, lf=2, dtype="f32"),        # degree-2 filter, L = 4
     dict(N=90, L=4, C=64, H=4, B=8, lf=2, dtype="bf16"),       # degree-2 filter on the matrix-core path
     dict(N=50, L=2, C=32, H=2, B=8, lf=2, dtype="bf16"),       # degree-2 filter, low tile only
+    dict(N=200, L=4, C=64, H=4, B=16, lf=1, dtype="bf16"),     # tile kernels with 16 radial basis functions
+    dict(N=150, L=2, C=32, H=2, B=11, lf=1, dtype="bf16"),     # ... and with 11
 ])
 def test_other_shapes_and_degenerate_inputs(torch_cuda, kw):
     run_case(torch_cuda, _custom(5, **kw))
 
 
 @pytest.mark.parametrize("kernel", ["tile", "pair", "valu"])
-@pytest.mark.parametrize("name", ["large", "scaling", "odd"])
+@pytest.mark.parametrize("name", ["large", "scaling", "odd", "odd_b13"])
 def test_each_attention_kernel_matches_the_oracle(torch_cuda, name, kernel):
     """The three forms of the attention stage on the same bf16 inputs, selected through the configuration: the tile form
     (16 targets x 32 candidates on the matrix cores, linear factorization of the degree-1 filter; the default where it
@@ -173,7 +175,7 @@ def test_each_attention_kernel_matches_the_oracle(torch_cuda, name, kernel):
         wl = W.scaling_point(0)
         tg = np.random.default_rng(2).choice(10_000, 200, replace=False).astype(np.int32)
     else:
-        wl = _custom(5, 333, 2, 64, 4, 5, 1, "bf16", cutoff=3.5, side=9.0, seg=[0, 7, 8, 150, 333])
+        wl = _custom(5, 333, 2, 64, 4, 13 if name == "odd_b13" else 5, 1, "bf16", cutoff=3.5, side=9.0, seg=[0, 7, 8, 150, 333])
         tg = None
     run_case(torch_cuda, wl, tg, check_materialized=False, message_mode="eaas", attention=kernel)
 
