@@ -13,7 +13,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(CSRC, "libe2f.so")
-SOURCES = ["e2f_api.hip", "e2f_cells.hip", "e2f_proj.hip", "e2f_fused.hip", "e2f_fused_mfma.hip", "e2f_materialized.hip", "e2f_tp.hip", "e2f_fact.hip", "e2f_tile.hip", "e2f_bwd.hip", "e2f_bwd_tile.hip", "e2f_nonlinear.hip"]
+SOURCES = ["e2f_api.hip", "e2f_cells.hip", "e2f_proj.hip", "e2f_fused.hip", "e2f_fused_mfma.hip", "e2f_materialized.hip", "e2f_tp.hip", "e2f_fact.hip", "e2f_tile.hip", "e2f_tile_f32.hip", "e2f_bwd.hip", "e2f_bwd_tile.hip", "e2f_nonlinear.hip"]
 FLAGS = ["-O3", "--offload-arch=gfx950", "-fPIC", "-std=c++17", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 

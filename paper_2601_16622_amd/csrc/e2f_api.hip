@@ -134,6 +134,7 @@ E2fAttnWs e2f_attn_ws_layout(const e2f_ctx* ctx, int32_t N, void* ws, int v_layo
     L.q = L.k = nullptr;
     L.v = nullptr;
     L.q16 = L.k16 = L.v4 = nullptr;
+    L.qf = L.kf = L.vf = nullptr;
     L.G = nullptr;
     L.lists_hdr = nullptr;
     L.lists_ent = nullptr;
@@ -152,6 +153,18 @@ E2fAttnWs e2f_attn_ws_layout(const e2f_ctx* ctx, int32_t N, void* ws, int v_layo
         L.lists_pos = (float4*)take(n_tiles * E2F_TILE_LCAP * 4 * sizeof(float4));
         L.lists_mask = (unsigned long long*)take(n_tiles * E2F_TILE_LCAP * 8);
     } else {
+        if (v_layout == 3) {
+            const size_t H = ctx->cfg.H, DK = (size_t)(ctx->cfg.L_max + 1) * 16, N4 = ((size_t)N + 3) / 4 * 4;
+            L.qf = (float*)take((size_t)N * H * DK * 4);
+            L.kf = (float*)take(N4 * H * DK * 4);
+            L.vf = (float*)take(N4 * H * ctx->n * 16 * 4);
+            L.G = (float*)take((size_t)(3 * E2F_MAX_N * E2F_MAX_N + 256) * 4);
+            const size_t n_tiles = ((size_t)N + 15) / 16;
+            L.lists_hdr = (int4*)take(n_tiles * sizeof(int4));
+            L.lists_ent = (int*)take(n_tiles * E2F_TILE_LCAP * 4);
+            L.lists_pos = (float4*)take(n_tiles * E2F_TILE_LCAP * 4 * sizeof(float4));
+            L.lists_mask = (unsigned long long*)take(n_tiles * E2F_TILE_LCAP * 8);
+        }
         L.q = (float*)take((size_t)N * (ctx->cfg.L_max + 1) * ctx->cfg.C * 4);
         L.k = (float*)take((size_t)N * (ctx->cfg.L_max + 1) * ctx->cfg.C * 4);
         // tiled v of the per-pair MFMA attention kernel: 16-row tiles per head, two tiles when L_max >= 3
@@ -230,8 +243,9 @@ e2f_status e2f_create(const e2f_config* cfg, e2f_ctx** ctx_out) {
     // unless the configuration names one.
     const int pick = cfg->attention;
     c->use_tile_attn = e2f_tile_supported(c) && (pick == E2F_ATTN_AUTO || pick == E2F_ATTN_TILE);
+    c->use_tile_f32 = e2f_tile_f32_supported(c) && (pick == E2F_ATTN_AUTO || pick == E2F_ATTN_TILE);
     c->use_mfma_attn = !c->use_tile_attn && e2f_fused_mfma_supported(c) && (pick == E2F_ATTN_AUTO || pick == E2F_ATTN_PAIR);
-    if ((pick == E2F_ATTN_TILE && !c->use_tile_attn) || (pick == E2F_ATTN_PAIR && !c->use_mfma_attn)) {
+    if ((pick == E2F_ATTN_TILE && !c->use_tile_attn && !c->use_tile_f32) || (pick == E2F_ATTN_PAIR && !c->use_mfma_attn)) {
         delete c;
         return E2F_ERR_UNSUPPORTED;
     }
@@ -418,7 +432,9 @@ static e2f_status forward_impl(e2f_ctx* ctx, const e2f_cells* cells, const float
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     if (cells->view.periodic && table) return E2F_ERR_UNSUPPORTED;   // the table names atoms, not images
     // the table form runs on the tile kernel where that applies, else on the ALU kernel, which reads the plain layout
-    const int v_layout = (table && !ctx->use_tile_attn) ? 0 : e2f_v_layout(ctx);
+    // (the fp32 tile kernel takes neither a cap nor a table: those calls run on the ALU kernel)
+    const bool tile_f32 = ctx->use_tile_f32 && !table && cap_K <= 0;
+    const int v_layout = tile_f32 ? 3 : ((table && !ctx->use_tile_attn) || ctx->use_tile_f32) ? 0 : e2f_v_layout(ctx);
     E2fAttnWs L = e2f_attn_ws_layout(ctx, N, ws, v_layout);
     if (cap_K > 0) {
         if (ws_bytes < L.bytes + 2 * e2f_align_up((size_t)N * 4)) return E2F_ERR_WORKSPACE_TOO_SMALL;
@@ -434,9 +450,15 @@ static e2f_status forward_impl(e2f_ctx* ctx, const e2f_cells* cells, const float
     if (ev) E2F_HIP_CHECK(hipEventRecord(ev[0], st));
     if ((rc = e2f_launch_prepare(ctx, cells->view, pos, w, L, st)) != E2F_OK) return rc;
     if (ev) E2F_HIP_CHECK(hipEventRecord(ev[1], st));
-    if ((rc = e2f_launch_project_mfma(ctx, cells->view, h, w, L, v_layout, st)) != E2F_OK) return rc;
+    if ((rc = e2f_launch_project_mfma(ctx, cells->view, h, w, L, v_layout == 3 ? 0 : v_layout, st)) != E2F_OK) return rc;
     if (ev) E2F_HIP_CHECK(hipEventRecord(ev[2], st));
-    rc = ctx->use_tile_attn   ? e2f_launch_tile(ctx, cells->view, L, table, table_K, out, st)
+    if (tile_f32) {
+        // candidate lists, the fp32 tile kernel for the tiles whose list fits, the ALU kernel for the atoms of the others
+        if ((rc = e2f_launch_tile_lists(ctx, cells->view, L, st)) != E2F_OK) return rc;
+        if ((rc = e2f_launch_tile_f32(ctx, cells->view, L, out, st)) != E2F_OK) return rc;
+    }
+    rc = tile_f32             ? e2f_launch_fused_crowded(ctx, cells->view, w, L, out, st)
+         : ctx->use_tile_attn ? e2f_launch_tile(ctx, cells->view, L, table, table_K, out, st)
          : table              ? e2f_launch_fused_table(ctx, cells->view, w, L, table, table_K, out, st)
          : ctx->use_mfma_attn ? e2f_launch_fused_mfma(ctx, cells->view, w, L, out, st)
                               : e2f_launch_fused(ctx, cells->view, w, L, out, st);

@@ -27,6 +27,7 @@ struct FusedParams {
     const int32_t* cap_idx;
     const int32_t* table;     // TABLE kernels: padded neighbour table [N][K] in the caller's atom order, -1 = empty
     int K;
+    const int4* only_crowded; // or null; else the headers of the tile kernels' lists: only atoms of tiles with x < 0 are done
     float* out;
     int C, H, B, Ch;
     float tau, rc2, cutoff, rbf_step, rbf_gamma;
@@ -49,6 +50,7 @@ __global__ __launch_bounds__(64) void k_fused_valu(FusedParams P) {
 
     const int t = e2f::xcd_remap(blockIdx.x, P.cv.N), lane = threadIdx.x;
     if (t < 0) return;  // padding block of the XCD map (whole wave)
+    if (P.only_crowded && P.only_crowded[t >> 4].x >= 0) return;   // (whole wave) a tile kernel owns this atom
     const int C = P.C, H = P.H;
     const int nlanes = C / CPL;
     const bool active = lane < nlanes;
@@ -236,13 +238,14 @@ bool launch_valu_lf(const e2f_ctx* ctx, const FusedParams& P, hipStream_t st) {
 }  // namespace
 
 static e2f_status launch_valu(const e2f_ctx* ctx, const E2fCellsView& cv, const e2f_weights* w, const E2fAttnWs& ws,
-                              const int32_t* table, int32_t K, float* out, hipStream_t st) {
+                              const int32_t* table, int32_t K, float* out, hipStream_t st, bool crowded_only = false) {
     if (cv.N == 0) return E2F_OK;
     if (cv.N >= (1 << 26)) return E2F_ERR_UNSUPPORTED;   // list entries carry the run in their top bits
     FusedParams P;
     P.cv = cv;
     P.spos = ws.spos; P.q = ws.q; P.k = ws.k; P.v = ws.v; P.cw = ws.cw; P.Wb = w->Wb; P.out = out;
     P.cap_d2 = ws.cap_d2; P.cap_idx = ws.cap_idx; P.table = table; P.K = K;
+    P.only_crowded = crowded_only ? ws.lists_hdr : nullptr;
     P.C = ctx->cfg.C; P.H = ctx->cfg.H; P.B = ctx->cfg.B; P.Ch = ctx->Ch;
     P.tau = ctx->tau; P.rc2 = ctx->rc2; P.cutoff = ctx->cfg.cutoff; P.rbf_step = ctx->rbf_step; P.rbf_gamma = ctx->rbf_gamma;
     bool ok = false;
@@ -261,6 +264,11 @@ static e2f_status launch_valu(const e2f_ctx* ctx, const E2fCellsView& cv, const 
 e2f_status e2f_launch_fused(const e2f_ctx* ctx, const E2fCellsView& cv, const e2f_weights* w, const E2fAttnWs& ws,
                             float* out, hipStream_t st) {
     return launch_valu(ctx, cv, w, ws, nullptr, 0, out, st);
+}
+
+e2f_status e2f_launch_fused_crowded(const e2f_ctx* ctx, const E2fCellsView& cv, const e2f_weights* w, const E2fAttnWs& ws,
+                                    float* out, hipStream_t st) {
+    return launch_valu(ctx, cv, w, ws, nullptr, 0, out, st, true);
 }
 
 e2f_status e2f_launch_fused_table(const e2f_ctx* ctx, const E2fCellsView& cv, const e2f_weights* w, const E2fAttnWs& ws,

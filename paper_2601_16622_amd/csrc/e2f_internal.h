@@ -59,6 +59,7 @@ struct e2f_ctx {
     int32_t cpl;       // channels per lane in the fused kernel
     bool use_mfma_attn;  // per-pair attention on the matrix cores (bf16, heads of 16 channels); v is stored tiled
     bool use_tile_attn;  // tile attention kernel (bf16, heads of 16 channels, lf = 1); q, k, v in its group layout
+    bool use_tile_f32;   // its fp32 form (fp32 features, heads of 16 channels, lf = 1); plain q, k, v plus fp32 tile layouts
     float tau;         // 1/sqrt(d_k)
     float rc2;         // cutoff*cutoff rounded to binary32
     float rbf_gamma;   // (B-1)^2 / (2 cutoff^2)
@@ -92,12 +93,19 @@ struct E2fAttnWs {
     int* lists_ent;      // [ceil(N/16)][E2F_TILE_LCAP]
     float4* lists_pos;   // [ceil(N/16)][E2F_TILE_LCAP][4]
     unsigned long long* lists_mask;   // [ceil(N/16)][E2F_TILE_LCAP] the (target, slot) pairs of an entry that count
+    // layout of the fp32 tile kernel (v_layout 3: beside the plain q, k, v)
+    float* qf;           // [N][H][DK] q * tau * log2(e)
+    float* kf;           // [ceil(N/4)][H][4 slots][DK]
+    float* vf;           // [ceil(N/4)][H][n][16 channels][4 slots]
     size_t bytes;
 };
 #define E2F_TILE_LCAP 192
-// v_layout: 0 plain [N][n][C], 1 component tiles of the per-pair MFMA kernel, 2 slot groups of the tile kernel
+// v_layout: 0 plain [N][n][C], 1 component tiles of the per-pair MFMA kernel, 2 slot groups of the tile kernel,
+// 3 plain plus the fp32 tile kernel's layouts and lists
 E2fAttnWs e2f_attn_ws_layout(const e2f_ctx* ctx, int32_t N, void* ws, int v_layout);
-static inline int e2f_v_layout(const e2f_ctx* ctx) { return ctx->use_tile_attn ? 2 : (ctx->use_mfma_attn ? 1 : 0); }
+static inline int e2f_v_layout(const e2f_ctx* ctx) {
+    return ctx->use_tile_attn ? 2 : ctx->use_tile_f32 ? 3 : (ctx->use_mfma_attn ? 1 : 0);
+}
 
 // Extra buffers of the backward pass, placed after the attention workspace (untiled v).
 struct E2fBwdWs {
@@ -165,6 +173,12 @@ e2f_status e2f_launch_project_simple(const e2f_ctx* ctx, const E2fCellsView& cv,
                                      float* q, float* k, float* v, hipStream_t st);
 e2f_status e2f_launch_fused(const e2f_ctx* ctx, const E2fCellsView& cv, const e2f_weights* w, const E2fAttnWs& ws,
                             float* out, hipStream_t st);
+// The same kernel for the atoms of crowded tiles only (tile headers in ws.lists_hdr, x < 0): every other atom's
+// output row is left as it is.
+e2f_status e2f_launch_fused_crowded(const e2f_ctx* ctx, const E2fCellsView& cv, const e2f_weights* w, const E2fAttnWs& ws,
+                                    float* out, hipStream_t st);
+bool e2f_tile_f32_supported(const e2f_ctx* ctx);
+e2f_status e2f_launch_tile_f32(const e2f_ctx* ctx, const E2fCellsView& cv, const E2fAttnWs& ws, float* out, hipStream_t st);
 // The fused call with the non-linear pair feature in the logit; q1 = W_Q1 h in v's plain layout and type.
 bool e2f_nonlinear_supported(const e2f_ctx* ctx);
 e2f_status e2f_launch_fused_nonlinear(const e2f_ctx* ctx, const E2fCellsView& cv, const e2f_weights* w,

@@ -39,7 +39,8 @@ def test_status_strings(lib):
     (dict(cutoff=float("nan")), 1), (dict(feat_dtype=7), 1), (dict(L_max=0, lf=1), 1),
     (dict(L_max=5), 2), (dict(lf=3, L_max=4), 2), (dict(lf=2, L_max=1), 1), (dict(C=24, H=2), 2), (dict(C=320, H=8), 2), (dict(C=16, H=2, feat_dtype=1), 2),
     (dict(attention=4), 1), (dict(attention=-1), 1), (dict(flags=64), 1),
-    (dict(attention=1), 2),                 # the tile kernel wants heads of 16 channels and bf16 or fp32 features it supports
+    (dict(attention=1, C=64, H=8), 2),      # the tile kernels want heads of 16 channels
+    (dict(attention=1, lf=2), 2),           # ... and the degree-1 filter
     (dict(attention=2, feat_dtype=0), 2),   # the per-pair matrix-core kernel wants bf16 features
 ])
 def test_create_rejects_bad_configurations(lib, kw, code):

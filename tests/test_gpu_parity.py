@@ -101,6 +101,34 @@ def test_scaling_point_every_target(torch_cuda):
     run_case(torch_cuda, wl, tg, message_mode="eaas")
 
 
+def test_fp32_tile_kernel(torch_cuda):
+    """fp32 features with heads of 16 channels run on the fp32 tile kernel (binary32 matrix instruction, the paper's own
+    precision): the scaling point's box and shape in fp32 on 600 sampled targets, tolerance 1e-4; the same call on the
+    vector-ALU kernel agrees; a box whose last tile is partial, with 13 radial functions; a dense
+    core whose tiles do not fit the candidate list and go to the vector-ALU kernel, inside a sparse shell that does."""
+    import oracle as O
+    from paper_2601_16622_amd import binding as B, workloads as W
+    wl = W.box(10_000, 0, dtype="f32")
+    tg = large_n_targets(wl["pos"], 6.0, 400, 5)
+    run_case(torch_cuda, wl, tg, check_materialized=False, message_mode="eaas")
+    outs = []
+    for att in ("tile", "valu"):
+        P = B.Problem(wl, attention=att)
+        P.build_cells()
+        outs.append(P.forward().clone())
+        P.close()
+    torch_cuda.cuda.synchronize()
+    d = (outs[0] - outs[1]).double().norm() / outs[1].double().norm()
+    assert 0 < float(d) <= 1e-5, float(d)   # different kernels, same numbers to rounding
+    run_case(torch_cuda, _custom(7, 333 + 6, 3, 64, 4, 13, 1, "f32", cutoff=3.5, side=9.0, seg=[0, 7, 8, 150, 339]),
+             message_mode="eaas")
+    rng = np.random.default_rng(14)
+    cfg = dict(L=1, C=32, H=2, B=8, lf=1, cutoff=4.0, dtype="f32")
+    mixed = np.concatenate([W.dart_throw_box(rng, 1500, 6.0, min_sep=0.3, origin=(5.0, 5.0, 5.0)),
+                            W.dart_throw_box(rng, 250, 16.0, min_sep=1.5)])
+    run_case(torch_cuda, W._pack(cfg, [mixed], rng, elements=False), check_materialized=False, message_mode="eaas")
+
+
 def large_n_targets(pos, cutoff, n_random, seed):
     """Sampled targets of a big box: random atoms, the atoms of the box's last corner (the last cells of the sorted
     order, so the last tile of 16 slots is among them), and atoms next to the faces (surface cells, few neighbours)."""
@@ -280,7 +308,18 @@ def test_capped_forward_fp32_and_no_effect_above_the_degree(torch_cuda):
         full = P.forward().clone()
         P.forward_capped(int(np.diff(offs).max()))   # a cap at the largest degree changes nothing
         torch_cuda.cuda.synchronize()
-        assert torch_cuda.equal(full, P.out)
+        # (the uncapped call runs on the fp32 tile kernel here, the capped one on the vector-ALU kernel: the same
+        # numbers to rounding; on one kernel, as in the bf16 test of the cap, they are the same bits)
+        assert float((full - P.out).double().norm() / full.double().norm()) <= 1e-5
+        Pv = __import__("paper_2601_16622_amd.binding", fromlist=["Problem"]).Problem(wl, attention="valu")
+        try:
+            Pv.build_cells()
+            full_v = Pv.forward().clone()
+            Pv.forward_capped(int(np.diff(offs).max()))
+            torch_cuda.cuda.synchronize()
+            assert torch_cuda.equal(full_v, Pv.out)
+        finally:
+            Pv.close()
     finally:
         P.close()
 

@@ -85,6 +85,13 @@ def test_periodic_box_at_the_benchmark_shape_sampled(torch_cuda):
     run_periodic(torch_cuda, wl, targets=tg)
 
 
+def test_two_periodic_boxes_fp32_tile_kernel(torch_cuda):
+    """fp32 features and heads of 16 channels: the fp32 tile kernel over candidate lists with images, L_max = 4."""
+    from paper_2601_16622_amd import workloads as W
+    wl = W.periodic_boxes((700, 300), seed=8, L=4, C=64, H=4, B=8, cutoff=5.0, dtype="f32")
+    run_periodic(torch_cuda, wl, attention="tile")
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_periodic_all_degrees_of_the_filter(torch_cuda, dtype):
     """lf = 1 and 2; in bf16 the degree-2 filter runs on the per-pair matrix-core kernel."""
