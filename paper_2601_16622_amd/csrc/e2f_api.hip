@@ -627,9 +627,11 @@ static E2fBwdWs bwd_ws_layout(const e2f_ctx* ctx, int32_t N, void* ws, size_t at
     return Bw;
 }
 
-// The pair work of the backward pass runs in tile form where the forward pass does (and the call asks for no gradients
-// of Wb or w_path, which only the per-atom kernels form).
-static bool backward_in_tile_form(const e2f_ctx* ctx, bool wgrad) { return ctx->use_tile_attn && !wgrad; }
+// The pair work of the backward pass runs in tile form where the forward pass does (with the gradients of Wb and
+// w_path only for up to 8 radial basis functions; beyond that the per-atom kernels form them).
+static bool backward_in_tile_form(const e2f_ctx* ctx, bool wgrad) {
+    return ctx->use_tile_attn && (!wgrad || e2f_backward_tile_weight_gradients_supported(ctx));
+}
 
 size_t e2f_attn_backward_workspace_bytes(const e2f_ctx* ctx, int32_t N) {
     if (!ctx || N < 0) return 0;

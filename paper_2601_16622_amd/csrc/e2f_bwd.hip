@@ -899,8 +899,12 @@ template <int L>
 void launch_crowded(const BwdParams& P, int what, hipStream_t st) {
     const int N = P.cv.N, C = P.C < 64 ? 64 : P.C;
     const size_t shm = (size_t)BCAP * P.H * sizeof(float2);
+    const size_t shm_w = shm > (size_t)(L + 1) * (L + 1) * P.C * 4 ? shm : (size_t)(L + 1) * (L + 1) * P.C * 4;
     if (what == 0) {
         k_bwd_stats<L, true><<<e2f::xcd_grid(N), C, shm, st>>>(P);
+    } else if (P.pWb) {   // with the per-atom partial sums of the weight gradients
+        k_bwd_target<L, uint16_t, true, true><<<e2f::xcd_grid(N), C, shm, st>>>(P);
+        k_bwd_source<L, uint16_t, true, true><<<e2f::xcd_grid(N), C, shm_w, st>>>(P);
     } else {
         k_bwd_target<L, uint16_t, false, true><<<e2f::xcd_grid(N), C, shm, st>>>(P);
         k_bwd_source<L, uint16_t, false, true><<<e2f::xcd_grid(N), C, shm, st>>>(P);
@@ -928,7 +932,7 @@ e2f_status e2f_launch_backward(const e2f_ctx* ctx, const E2fCellsView& cv, const
     if (cv.N == 0) return E2F_OK;
     const bool wgrad = grad_Wb || grad_w_path;
     if (wgrad && ctx->cfg.B > WB_PER_THREAD * ctx->Ch) return E2F_ERR_UNSUPPORTED;
-    if (tw && wgrad) return E2F_ERR_INVALID_ARG;   // (the tile kernels do not form these sums)
+    if (tw && wgrad && !e2f_backward_tile_weight_gradients_supported(ctx)) return E2F_ERR_INVALID_ARG;
     BwdParams P;
     P.cv = cv;
     P.spos = ws.spos; P.q = ws.q; P.k = ws.k; P.v = ws.v; P.G = tw ? ws.G : bw.G; P.Wb = w->Wb;
@@ -941,6 +945,12 @@ e2f_status e2f_launch_backward(const e2f_ctx* ctx, const E2fCellsView& cv, const
     P.tau = ctx->tau; P.rc2 = ctx->rc2; P.cutoff = ctx->cfg.cutoff; P.rbf_step = ctx->rbf_step; P.rbf_gamma = ctx->rbf_gamma;
     P.Gu = nullptr; P.pWb = nullptr; P.pwp = nullptr;
     e2f_status rc;
+    if (wgrad) {   // unit-weight path coefficients and axis operators (full form for the per-atom kernels, packed for the tile kernels)
+        if ((rc = e2f_launch_unit_cw(ctx, bw.cw_unit, st)) != E2F_OK) return rc;
+        if ((rc = e2f_launch_axis_ops(ctx, bw.cw_unit, bw.Gu, st)) != E2F_OK) return rc;
+        if (tw && (rc = e2f_launch_axis_ops(ctx, bw.cw_unit, tw->Gu, st, true)) != E2F_OK) return rc;
+        P.Gu = bw.Gu; P.pWb = bw.pWb; P.pwp = bw.pwp;
+    }
     if (tw) {
         // pair work on the matrix cores, tile by tile; the atoms of crowded tiles (lists that do not fit) go through
         // the per-atom kernels, which read the same layouts and statistics
@@ -954,16 +964,13 @@ e2f_status e2f_launch_backward(const e2f_ctx* ctx, const E2fCellsView& cv, const
             }
         };
         crowded(0);
-        if ((rc = e2f_launch_backward_tile(ctx, cv, ws, *tw, out, grad_out, grad_pos, grad_q, grad_k, grad_v, st)) != E2F_OK)
+        if ((rc = e2f_launch_backward_tile(ctx, cv, ws, *tw, out, grad_out, grad_pos, grad_q, grad_k, grad_v, wgrad, st)) != E2F_OK)
             return rc;
         crowded(1);
+        if (wgrad && (rc = e2f_launch_backward_tile_wsum(ctx, cv, ws, *tw, bw.pWb, bw.pwp, grad_Wb, grad_w_path, st)) != E2F_OK)
+            return rc;
     }
     if (!tw && (rc = e2f_launch_axis_ops(ctx, ws.cw, bw.G, st)) != E2F_OK) return rc;
-    if (!tw && wgrad) {
-        if ((rc = e2f_launch_unit_cw(ctx, bw.cw_unit, st)) != E2F_OK) return rc;
-        if ((rc = e2f_launch_axis_ops(ctx, bw.cw_unit, bw.Gu, st)) != E2F_OK) return rc;
-        P.Gu = bw.Gu; P.pWb = bw.pWb; P.pwp = bw.pwp;
-    }
     if (!tw) switch (ctx->cfg.L_max) {
         case 1: launch_L<1>(ctx, P, st); break;
         case 2: launch_L<2>(ctx, P, st); break;
@@ -971,7 +978,7 @@ e2f_status e2f_launch_backward(const e2f_ctx* ctx, const E2fCellsView& cv, const
         case 4: launch_L<4>(ctx, P, st); break;
         default: return E2F_ERR_UNSUPPORTED;
     }
-    if (wgrad) {
+    if (wgrad && !tw) {
         const int L1 = ctx->cfg.L_max + 1, HB = ctx->cfg.H * ctx->cfg.B;
         if (grad_Wb) k_reduce_partials<<<HB, 256, 0, st>>>(bw.pWb, cv.N, HB, HB, grad_Wb);
         if (grad_w_path) k_reduce_partials<<<L1 * L1, 256, 0, st>>>(bw.pwp, cv.N, WP_BINS, L1 * L1, grad_w_path);

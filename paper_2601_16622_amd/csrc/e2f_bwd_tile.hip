@@ -38,6 +38,11 @@ struct BwdTileParams {
     const float *out, *gout;          // caller's order
     float2* stat4;                    // [group][H][4 slots] (lse in base-2 units, D)
     float* gp_part;                   // [2 sides][head groups][N sorted slots][3]
+    // gradients of the attention's own weights (kernels with WGR): partial sums per tile, and the axis operators
+    // with unit path weights (full form, then packed)
+    float* pWb_t;                     // [tiles][H][B]
+    float* pwp_t;                     // [tiles][head groups][32], bin li * (L_max + 1) + lo
+    const float* Gu;
     float *gq, *gk, *gv, *gpos;       // caller's order
     const int4* lists_hdr;
     const int* lists_ent;
@@ -48,6 +53,8 @@ struct BwdTileParams {
 };
 
 constexpr int LENT = LCAP + 32;   // the list in LDS, padded to whole groups of four chunks
+// Degree of component x (index l*l + l + m).
+constexpr int e2f_degree_of(int x) { return x >= 16 ? 4 : x >= 9 ? 3 : x >= 4 ? 2 : x >= 1 ? 1 : 0; }
 constexpr float LOG2E = 1.44269504088896341f, LN2 = 0.69314718055994531f;
 
 // ---- relayout: q rows -> grouped layout, q and k -> four slots of a feature per lane (bf16)
@@ -331,8 +338,10 @@ __global__ __launch_bounds__(256) void k_bwd_tile_stats(BwdTileParams P) {
 //   dT   += dS Y4          dS in the logits' register layout is the A operand; Y4 the candidates' k (or q) with the four
 //                          slots of a group per lane
 // and the per-pair scalars in between, one tile atom per lane against 8 candidates.
-template <int L, bool SRC, int NB>
+// WGR (target side, B <= 8): also the tile's partial sums of dL/dWb[h][b] = sum_ij ds_ij exp(-gamma (d_ij - b step)^2).
+template <int L, bool SRC, int NB, bool WGR>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void k_bwd_tile_pairs(BwdTileParams P) {
+    static_assert(!WGR || (!SRC && NB <= 8), "the sums over the radial basis are formed on the target side, in the form for B <= 8");
     constexpr int NW = 4, n = (L + 1) * (L + 1);
     constexpr int DK = (L + 1) * 16, KS = (DK + 31) / 32, DKP = KS * 32;
     constexpr int VK = n * 16, VS = (VK + 31) / 32, VKP = VS * 32;
@@ -345,6 +354,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     __shared__ float4 s_pos[LENT * 4];
     __shared__ __attribute__((aligned(16))) uint16_t s_rows[16 * DKP];
     __shared__ float s_gp[NW][16][3];
+    __shared__ float s_wb[NW][8];
     __shared__ float s_G[AXIS_NNZ];
     // the tile side of U as B operands [mu][step][lane]; at the end of a head the same bytes hold the waves' dq tiles
     __shared__ __attribute__((aligned(16))) unsigned char s_big[GX_BYTES > RED_BYTES ? GX_BYTES : RED_BYTES];
@@ -463,6 +473,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 #pragma unroll
         for (int t = 0; t < NT; ++t) dacc[t] = (f32x4){0.f, 0.f, 0.f, 0.f};
         float gx = 0.0f, gy = 0.0f, gz = 0.0f;
+        float wbacc[WGR ? NB : 1];   // per lane: sum over its pairs of ds e^{-gamma d^2} u^b (the factor of b comes at the end)
+        if constexpr (WGR) {
+#pragma unroll
+            for (int b = 0; b < NB; ++b) wbacc[b] = 0.0f;
+        }
 
         for (int c = wave; c < nch; c += NW) {
             const int cn = min(c + NW, nch - 1);
@@ -576,6 +591,16 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
                     gx += alpha * u0 + dd * rx;
                     gy += alpha * u1 + dd * ry;
                     gz += alpha * u2 + dd * rz;
+                    if constexpr (WGR) {
+                        // exp(-gamma (d - b step)^2) = e^{-gamma d^2} u^b e^{-gamma (b step)^2}, u = e^{2 gamma step d}
+                        float t = ds[u] * __builtin_amdgcn_exp2f(c_g * d2);
+                        const float uu = __builtin_amdgcn_exp2f(c_u * (d2 * rd));
+#pragma unroll
+                        for (int b = 0; b < NB; ++b) {
+                            wbacc[b] += t;
+                            t *= uu;
+                        }
+                    }
                 }
             }
             // ---- dq (dk) += dS Y4
@@ -606,6 +631,15 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
             for (int w = 0; w < NW; ++w) s += s_gp[w][t][ax];
             gp_acc += s;
         }
+        if constexpr (WGR) {   // the tile's sums over the radial basis: lanes, then waves, in a fixed order
+#pragma unroll
+            for (int b = 0; b < NB; ++b) {
+                float v = wbacc[b];
+#pragma unroll
+                for (int off = 1; off < 64; off <<= 1) v += __shfl_xor(v, off);
+                if (lane == 0) s_wb[wave][b] = v;
+            }
+        }
         {
             const float scale = SRC ? LN2 : P.tau;   // q rows carry tau log2 e; k rows are plain
             float* dst = SRC ? P.gk : P.gq;
@@ -623,6 +657,13 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
             }
         }
         __syncthreads();   // the next head rewrites s_rows, s_GX and the partials
+        if constexpr (WGR) {
+            if (tid < P.B) {
+                const float bs = (float)tid * P.rbf_step;
+                P.pWb_t[((size_t)tile * H + head) * P.B + tid] =
+                    (s_wb[0][tid] + s_wb[1][tid] + s_wb[2][tid] + s_wb[3][tid]) * __expf(-P.rbf_gamma * bs * bs);
+            }
+        }
     }
     if (tid < 48 && t0 + tid / 3 < N)
         P.gp_part[(((size_t)(SRC ? 1 : 0) * HG + hg) * N + t0 + tid / 3) * 3 + tid % 3] = SRC ? gp_acc : -gp_acc;
@@ -633,7 +674,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 // the softmax weights from the stored statistics.  The waves score a chunk each and share the weights through LDS (two
 // buffers, one barrier per group of four chunks); every wave aggregates all four chunks into its quarter of the
 // components.
-template <int L, int NB>
+// WGR: also the tile's partial sums of the path-weight gradient.  The message is linear in the path weights,
+// G_mu[xo][xi] = w_path[li(xi)][lo(xo)] Gu_mu[xo][xi] with the unit-weight operators Gu, so
+//   dL/dw_path[li][lo] = sum_j sum_mu sum_{xo in lo, xi in li} Y_mu[j][xo] Gu_mu[xo][xi] v_j[xi],
+// formed in the epilogue from the Y_mu that are in LDS there anyway.
+template <int L, int NB, bool WGR>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void k_bwd_tile_dv(BwdTileParams P) {
     constexpr int NW = 4, n = (L + 1) * (L + 1), NX = (n + NW - 1) / NW;
     constexpr int DK = (L + 1) * 16, KS = (DK + 31) / 32, DKP = KS * 32;
@@ -644,6 +689,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     __shared__ float4 s_pos[LENT * 4];
     __shared__ __attribute__((aligned(16))) uint16_t s_rows[16 * DKP];
     __shared__ float s_G[AXIS_NNZ];
+    __shared__ float s_Gu[WGR ? AXIS_NNZ : 1];
+    __shared__ float s_bins[NW][32];
     __shared__ int s_orow[16];
     __shared__ __attribute__((aligned(16))) unsigned char s_raw[W_BYTES > PO_BYTES ? W_BYTES : PO_BYTES];
     u32x4* s_W = reinterpret_cast<u32x4*>(s_raw);
@@ -664,10 +711,15 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     const float4 tp = P.spos[tslot];
     const int orow_mine = tid < 16 ? (t0 + tid < N ? P.cv.perm[t0 + tid] : -1) : 0;
     const float g_mine = tid < AXIS_NNZ ? P.G[AXIS_PACKED_AT + tid] : 0.0f;
+    const float gu_mine = WGR && tid < AXIS_NNZ ? P.Gu[AXIS_PACKED_AT + tid] : 0.0f;
     const int cnt = load_list(P, tile, tid, tp, s_ent, s_mask, s_pos);
     if (cnt < 0) return;   // (whole workgroup) a crowded tile: done by the per-atom kernels
     if (tid < AXIS_NNZ) s_G[tid] = g_mine;
+    if (WGR && tid < AXIS_NNZ) s_Gu[tid] = gu_mine;
     if (tid < 16) s_orow[tid] = orow_mine;
+    float bins[WGR ? (L + 1) * (L + 1) : 1];   // per lane, over this workgroup's heads: bin li * (L + 1) + lo
+#pragma unroll
+    for (int i = 0; i < (WGR ? (L + 1) * (L + 1) : 1); ++i) bins[i] = 0.0f;
     const int nch = (cnt + 7) >> 3, ngr = (nch + NW - 1) / NW;
     const float c_u = 2.0f * P.rbf_gamma * P.rbf_step * LOG2E, c_g = -P.rbf_gamma * LOG2E;
 
@@ -806,6 +858,17 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
             f32x4 pr[RO];
 #pragma unroll
             for (int i = 0; i < RO; ++i) pr[i] = (f32x4){0.f, 0.f, 0.f, 0.f};
+            // (WGR) the value rows of the tile's atoms 4g..4g+3, channel tn, for this wave's components x_in
+            f32x4 vt[WGR ? RO : 1];
+            if constexpr (WGR) {
+                const size_t grp = min((size_t)(t0 >> 2) + g, (size_t)(N - 1) >> 2);
+#pragma unroll
+                for (int i = 0; i < RO; ++i) {
+                    const u32x2 four = *reinterpret_cast<const u32x2*>(P.v4 + (grp * H + head) * n * 64 + e2f::v4_offset(n, WV + NW * i, tn));
+                    vt[i] = (f32x4){__uint_as_float(four[0] << 16), __uint_as_float(four[0] & 0xffff0000u),
+                                    __uint_as_float(four[1] << 16), __uint_as_float(four[1] & 0xffff0000u)};
+                }
+            }
 #pragma unroll
             for (int mu = 0; mu < 3; ++mu) {
                 __syncthreads();
@@ -816,8 +879,15 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
                 for (int i = 0; i < RO; ++i) {
 #pragma unroll
                     for (int xo = 0; xo < n; ++xo)
-                        if ((E2F_AXIS_NZ[mu][xo] >> (WV + NW * i)) & 1u)
-                            pr[i] += s_G[AXIS_INDEX.v[mu][xo][WV + NW * i]] * s_po[xo * 64 + lane];
+                        if ((E2F_AXIS_NZ[mu][xo] >> (WV + NW * i)) & 1u) {
+                            const f32x4 y = s_po[xo * 64 + lane];
+                            pr[i] += s_G[AXIS_INDEX.v[mu][xo][WV + NW * i]] * y;
+                            if constexpr (WGR) {
+                                const int li = e2f_degree_of(WV + NW * i), lo = e2f_degree_of(xo);   // (constants once unrolled)
+                                bins[li * (L + 1) + lo] += s_Gu[AXIS_INDEX.v[mu][xo][WV + NW * i]] *
+                                                           (y[0] * vt[i][0] + y[1] * vt[i][1] + y[2] * vt[i][2] + y[3] * vt[i][3]);
+                            }
+                        }
                 }
             }
 #pragma unroll
@@ -837,7 +907,44 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
         if (wave_u == 3) finish(std::integral_constant<int, 3>{});
         __syncthreads();   // the next head rewrites s_rows and the weight buffers
     }
+    if constexpr (WGR) {   // the tile's bins: lanes, then waves, in a fixed order
+#pragma unroll
+        for (int i = 0; i < (L + 1) * (L + 1); ++i) {
+            float v = bins[i];
+#pragma unroll
+            for (int off = 1; off < 64; off <<= 1) v += __shfl_xor(v, off);
+            if (lane == 0) s_bins[wave][i] = v;
+        }
+        __syncthreads();
+        if (tid < 32)
+            P.pwp_t[((size_t)tile * HG + hg) * 32 + tid] =
+                tid < (L + 1) * (L + 1) ? s_bins[0][tid] + s_bins[1][tid] + s_bins[2][tid] + s_bins[3][tid] : 0.0f;
+    }
     (void)nt;
+}
+
+// Sums of the weight-gradient partials in a fixed order: one workgroup per output element m, over the tiles whose
+// list fitted (rows_per_tile rows each) and over the atoms of the crowded tiles (per-atom kernels' rows).
+__global__ __launch_bounds__(256) void k_bwd_wsum(E2fCellsView cv, const int4* __restrict__ hdr, const float* __restrict__ tile_part,
+                                                  int rows_per_tile, int tile_stride, const float* __restrict__ atom_part,
+                                                  int atom_stride, int n_tiles, int M, float* __restrict__ out) {
+    __shared__ float s_acc[256];
+    const int m = blockIdx.x, N = cv.N;
+    float s = 0.0f;
+    for (int t = threadIdx.x; t < n_tiles; t += 256) {
+        if (hdr[t].x >= 0) {
+            for (int r = 0; r < rows_per_tile; ++r) s += tile_part[((size_t)t * rows_per_tile + r) * tile_stride + m];
+        } else {
+            for (int slot = 16 * t; slot < min(16 * t + 16, N); ++slot) s += atom_part[(size_t)cv.perm[slot] * atom_stride + m];
+        }
+    }
+    s_acc[threadIdx.x] = s;
+    __syncthreads();
+    for (int off = 128; off > 0; off >>= 1) {
+        if ((int)threadIdx.x < off) s_acc[threadIdx.x] += s_acc[threadIdx.x + off];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0 && m < M) out[m] = s_acc[0];
 }
 
 // gpos[atom] = sum of the partial sums of both sides and all head groups, in a fixed order
@@ -853,7 +960,7 @@ __global__ __launch_bounds__(256) void k_bwd_gpos_reduce(E2fCellsView cv, const 
 }
 
 template <int L>
-void launch_L(const BwdTileParams& P, hipStream_t st) {
+void launch_L(const BwdTileParams& P, bool wgrad, hipStream_t st) {
     const int N = P.cv.N, groups = (N + 3) / 4, HG = P.H / P.hpw;
     const int chunks = (P.n_tiles + TILE_BLK - 1) / TILE_BLK;
     const int grid = ((chunks + 7) / 8) * 8 * TILE_BLK * HG;
@@ -862,14 +969,19 @@ void launch_L(const BwdTileParams& P, hipStream_t st) {
     k_bwd_relayout_g<L><<<groups, 256, 0, st>>>(P);
     if (P.B > 8) {   // (the radial bias polynomial has its coefficients in registers: instances for B <= 8 and B <= 16)
         k_bwd_tile_stats<L, 16><<<grid, 256, 0, st>>>(P);
-        k_bwd_tile_pairs<L, false, 16><<<grid, 256, 0, st>>>(P);
-        k_bwd_tile_pairs<L, true, 16><<<grid, 256, 0, st>>>(P);
-        k_bwd_tile_dv<L, 16><<<grid, 256, 0, st>>>(P);
+        k_bwd_tile_pairs<L, false, 16, false><<<grid, 256, 0, st>>>(P);
+        k_bwd_tile_pairs<L, true, 16, false><<<grid, 256, 0, st>>>(P);
+        k_bwd_tile_dv<L, 16, false><<<grid, 256, 0, st>>>(P);
+    } else if (wgrad) {
+        k_bwd_tile_stats<L, 8><<<grid, 256, 0, st>>>(P);
+        k_bwd_tile_pairs<L, false, 8, true><<<grid, 256, 0, st>>>(P);
+        k_bwd_tile_pairs<L, true, 8, false><<<grid, 256, 0, st>>>(P);
+        k_bwd_tile_dv<L, 8, true><<<grid, 256, 0, st>>>(P);
     } else {
         k_bwd_tile_stats<L, 8><<<grid, 256, 0, st>>>(P);
-        k_bwd_tile_pairs<L, false, 8><<<grid, 256, 0, st>>>(P);
-        k_bwd_tile_pairs<L, true, 8><<<grid, 256, 0, st>>>(P);
-        k_bwd_tile_dv<L, 8><<<grid, 256, 0, st>>>(P);
+        k_bwd_tile_pairs<L, false, 8, false><<<grid, 256, 0, st>>>(P);
+        k_bwd_tile_pairs<L, true, 8, false><<<grid, 256, 0, st>>>(P);
+        k_bwd_tile_dv<L, 8, false><<<grid, 256, 0, st>>>(P);
     }
     k_bwd_gpos_reduce<<<(N * 3 + 255) / 256, 256, 0, st>>>(P.cv, P.gp_part, 2 * HG, P.lists_hdr, P.gpos);
 }
@@ -894,21 +1006,30 @@ E2fBwdTileWs e2f_bwd_tile_ws_layout(const e2f_ctx* ctx, int32_t N, void* ws, siz
     T.g4 = (uint16_t*)take(groups * H * n * 64 * 2);
     T.stat4 = (float*)take(groups * 4 * H * 8);
     T.gp_part = (float*)take((size_t)2 * H * N * 3 * 4);
+    const size_t n_tiles = ((size_t)N + 15) / 16;
+    T.pWb_t = (float*)take(n_tiles * H * ctx->cfg.B * 4);
+    T.pwp_t = (float*)take(n_tiles * H * 32 * 4);
+    T.Gu = (float*)take((size_t)(3 * E2F_MAX_N * E2F_MAX_N + 256) * 4);
     T.bytes = off;
     return T;
 }
 
 // The tile kernels of the backward pass for every tile whose candidate list fits; the lists (and the axis operators)
 // must have been written by e2f_launch_tile_lists, q16 / k16 / v4 by the projection in the tile layout.
+bool e2f_backward_tile_weight_gradients_supported(const e2f_ctx* ctx) { return ctx->cfg.B <= 8; }
+
+// wgrad: also the per-tile partial sums of dL/dWb and dL/dw_path (tw.Gu must hold the unit-weight axis operators).
 e2f_status e2f_launch_backward_tile(const e2f_ctx* ctx, const E2fCellsView& cv, const E2fAttnWs& ws,
                                     const E2fBwdTileWs& tw, const float* out, const float* grad_out, float* grad_pos,
-                                    float* grad_q, float* grad_k, float* grad_v, hipStream_t st) {
+                                    float* grad_q, float* grad_k, float* grad_v, bool wgrad, hipStream_t st) {
     if (cv.N == 0) return E2F_OK;
+    if (wgrad && !e2f_backward_tile_weight_gradients_supported(ctx)) return E2F_ERR_UNSUPPORTED;
     BwdTileParams P;
     P.cv = cv;
     P.spos = ws.spos; P.q16 = ws.q16; P.k16 = ws.k16; P.v4 = ws.v4; P.G = ws.G; P.WbT = ws.wbT;
     P.q16g = tw.q16g; P.q4 = tw.q4; P.k4 = tw.k4; P.vrow = tw.vrow; P.grow = tw.grow; P.g4 = tw.g4;
     P.stat4 = reinterpret_cast<float2*>(tw.stat4); P.gp_part = tw.gp_part;
+    P.pWb_t = tw.pWb_t; P.pwp_t = tw.pwp_t; P.Gu = tw.Gu;
     P.out = out; P.gout = grad_out; P.gq = grad_q; P.gk = grad_k; P.gv = grad_v; P.gpos = grad_pos;
     P.lists_hdr = ws.lists_hdr; P.lists_ent = ws.lists_ent; P.lists_pos = ws.lists_pos; P.lists_mask = ws.lists_mask;
     P.C = ctx->cfg.C; P.H = ctx->cfg.H; P.B = ctx->cfg.B; P.n_tiles = (cv.N + 15) / 16;
@@ -916,12 +1037,27 @@ e2f_status e2f_launch_backward_tile(const e2f_ctx* ctx, const E2fCellsView& cv, 
     while (P.hpw < 4 && P.H % (P.hpw * 2) == 0 && (long)P.n_tiles * P.H / (P.hpw * 2) >= 2048) P.hpw *= 2;
     P.tau = ctx->tau; P.rc2 = ctx->rc2; P.cutoff = ctx->cfg.cutoff; P.rbf_step = ctx->rbf_step; P.rbf_gamma = ctx->rbf_gamma;
     switch (ctx->cfg.L_max) {
-        case 1: launch_L<1>(P, st); break;
-        case 2: launch_L<2>(P, st); break;
-        case 3: launch_L<3>(P, st); break;
-        case 4: launch_L<4>(P, st); break;
+        case 1: launch_L<1>(P, wgrad, st); break;
+        case 2: launch_L<2>(P, wgrad, st); break;
+        case 3: launch_L<3>(P, wgrad, st); break;
+        case 4: launch_L<4>(P, wgrad, st); break;
         default: return E2F_ERR_UNSUPPORTED;
     }
+    E2F_HIP_CHECK(hipGetLastError());
+    return E2F_OK;
+}
+
+// Sums of the partials that the tile kernels (per tile) and the per-atom kernels (atoms of crowded tiles) leave.
+e2f_status e2f_launch_backward_tile_wsum(const e2f_ctx* ctx, const E2fCellsView& cv, const E2fAttnWs& ws,
+                                         const E2fBwdTileWs& tw, const float* atom_pWb, const float* atom_pwp,
+                                         float* grad_Wb, float* grad_w_path, hipStream_t st) {
+    if (cv.N == 0) return E2F_OK;
+    const int n_tiles = (cv.N + 15) / 16, HB = ctx->cfg.H * ctx->cfg.B, L1 = ctx->cfg.L_max + 1;
+    int hpw = 1;
+    while (hpw < 4 && ctx->cfg.H % (hpw * 2) == 0 && (long)n_tiles * ctx->cfg.H / (hpw * 2) >= 2048) hpw *= 2;
+    if (grad_Wb) k_bwd_wsum<<<HB, 256, 0, st>>>(cv, ws.lists_hdr, tw.pWb_t, 1, HB, atom_pWb, HB, n_tiles, HB, grad_Wb);
+    if (grad_w_path)
+        k_bwd_wsum<<<L1 * L1, 256, 0, st>>>(cv, ws.lists_hdr, tw.pwp_t, ctx->cfg.H / hpw, 32, atom_pwp, 32, n_tiles, L1 * L1, grad_w_path);
     E2F_HIP_CHECK(hipGetLastError());
     return E2F_OK;
 }

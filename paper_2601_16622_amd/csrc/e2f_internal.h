@@ -133,6 +133,9 @@ struct E2fBwdTileWs {
     uint16_t* g4;     // dL/d out in the layout of v4
     float* stat4;     // [group][H][4 slots][2]: lse (base-2 units), <dL/d out_i, out_i>
     float* gp_part;   // [2][H][N][3] partial position gradients per side and head group
+    float* pWb_t;     // [tiles][H][B] partial sums of dL/dWb per tile
+    float* pwp_t;     // [tiles][H][32] partial sums of dL/dw_path per tile and head group
+    float* Gu;        // axis operators with unit path weights: full form, then packed
     size_t bytes;     // end of the last buffer, counted from the start of the workspace
 };
 
@@ -196,13 +199,17 @@ e2f_status e2f_launch_fused_table(const e2f_ctx* ctx, const E2fCellsView& cv, co
 bool e2f_tile_supported(const e2f_ctx* ctx);
 // G[mu][x_out][x_in], mu = x, y, z: the degree-1 filter's message for a unit pair vector along mu, from the path
 // coefficients cw (tile attention kernel, backward pass).
-e2f_status e2f_launch_axis_ops(const e2f_ctx* ctx, const float* cw, float* G, hipStream_t st);
+e2f_status e2f_launch_axis_ops(const e2f_ctx* ctx, const float* cw, float* G, hipStream_t st, bool packed = false);
 // Tile form of the backward pass's pair work (e2f_bwd_tile.hip): needs the tile layouts of q, k, v and the candidate
 // lists in `ws`; tiles whose list did not fit are left to the per-atom kernels.
 E2fBwdTileWs e2f_bwd_tile_ws_layout(const e2f_ctx* ctx, int32_t N, void* ws, size_t offset);
 e2f_status e2f_launch_backward_tile(const e2f_ctx* ctx, const E2fCellsView& cv, const E2fAttnWs& ws,
                                     const E2fBwdTileWs& tw, const float* out, const float* grad_out, float* grad_pos,
-                                    float* grad_q, float* grad_k, float* grad_v, hipStream_t st);
+                                    float* grad_q, float* grad_k, float* grad_v, bool wgrad, hipStream_t st);
+bool e2f_backward_tile_weight_gradients_supported(const e2f_ctx* ctx);
+e2f_status e2f_launch_backward_tile_wsum(const e2f_ctx* ctx, const E2fCellsView& cv, const E2fAttnWs& ws,
+                                         const E2fBwdTileWs& tw, const float* atom_pWb, const float* atom_pwp,
+                                         float* grad_Wb, float* grad_w_path, hipStream_t st);
 // The candidate lists of the tile kernels and the axis operators only (a crowded tile gets the header -1 and nothing else).
 e2f_status e2f_launch_tile_lists(const e2f_ctx* ctx, const E2fCellsView& cv, const E2fAttnWs& ws, hipStream_t st);
 // tw: null for the per-atom pair kernels (plain layouts in `ws`), else the tile form (tile layouts in `ws`).

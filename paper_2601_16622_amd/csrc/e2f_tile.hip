@@ -1061,12 +1061,13 @@ void launch_L(const TileParams& P, const float* cw, float* G, int what, hipStrea
 
 }  // namespace
 
-e2f_status e2f_launch_axis_ops(const e2f_ctx* ctx, const float* cw, float* G, hipStream_t st) {
+// packed: also the list of the pattern's entries behind the full form (G then holds 3 * 25 * 25 + 216 floats)
+e2f_status e2f_launch_axis_ops(const e2f_ctx* ctx, const float* cw, float* G, hipStream_t st, bool packed) {
     switch (ctx->cfg.L_max) {
-        case 1: k_axis_ops<1><<<1, 128, 0, st>>>(cw, G, false); break;
-        case 2: k_axis_ops<2><<<1, 128, 0, st>>>(cw, G, false); break;
-        case 3: k_axis_ops<3><<<1, 128, 0, st>>>(cw, G, false); break;
-        case 4: k_axis_ops<4><<<1, 128, 0, st>>>(cw, G, false); break;
+        case 1: k_axis_ops<1><<<1, 128, 0, st>>>(cw, G, packed); break;
+        case 2: k_axis_ops<2><<<1, 128, 0, st>>>(cw, G, packed); break;
+        case 3: k_axis_ops<3><<<1, 128, 0, st>>>(cw, G, packed); break;
+        case 4: k_axis_ops<4><<<1, 128, 0, st>>>(cw, G, packed); break;
         default: return E2F_ERR_UNSUPPORTED;
     }
     E2F_HIP_CHECK(hipGetLastError());

@@ -54,9 +54,9 @@ def run_backward(torch, wl, seed=0):
         g = torch.from_numpy(go).to(P.device)
         got = [x.cpu().numpy().astype(np.float64) for x in P.backward(g, with_weights=True)]
         torch.cuda.synchronize()
-        # Without the gradients of Wb and w_path the pair work runs in tile form where the forward pass does (other
-        # kernels, other rounding: checked against the reference on its own); elsewhere it is the same kernels and
-        # the same numbers.
+        # The pair work runs in tile form where the forward pass does (with the gradients of Wb and w_path only up to
+        # 8 radial functions; beyond that asking for them selects the per-atom kernels: other kernels, other rounding,
+        # each checked against the reference on its own); elsewhere it is the same kernels and the same numbers.
         plain = P.backward(g)
         torch.cuda.synchronize()
         same_kernels = not (cfg["dtype"] == "bf16" and cfg["C"] // cfg["H"] == 16 and cfg["B"] <= 16 and cfg["C"] in (32, 64, 128))
@@ -80,7 +80,7 @@ def run_backward(torch, wl, seed=0):
         # differently (G^T g against v, g against G v, in bf16), so there the sum is zero to the tolerance only.
         for s in range(len(wl["seg"]) - 1):
             seg = slice(wl["seg"][s], wl["seg"][s + 1])
-            for gp, exact in ((got[0][seg], True), (plain_pos[seg], same_kernels)):
+            for gp, exact in ((got[0][seg], same_kernels or cfg["B"] > 8), (plain_pos[seg], same_kernels)):
                 bound = 1e-3 * max(1.0, np.abs(gp).max()) if exact else TOL[cfg["dtype"]] * max(1.0, np.linalg.norm(gp))
                 assert np.abs(gp.sum(0)).max() <= bound
         return errs
