@@ -184,7 +184,8 @@ def test_backward_entry_point_sizes_and_limits(lib):
     per_atom_plain = 16 + 2 * 5 * 128 * 4 + 25 * 128 * 2 + stats
     qk = 8 * 96 * 2
     per_atom_tile = (16 + 2 * qk + 8 * 25 * 16 * 2 + (16 + 192 * (4 + 64 + 8)) // 16 + stats
-                     + 3 * qk + 2 * 8 * 416 * 2 + 8 * 25 * 16 * 2 + 8 * 8 + 2 * 8 * 3 * 4)
+                     + 3 * qk + 2 * 8 * 416 * 2 + 8 * 25 * 16 * 2 + 8 * 8 + 2 * 8 * 3 * 4
+                     + (8 * 8 * 4 + 8 * 32 * 4) // 16)   # per tile of 16 atoms: partial sums of dL/dWb and dL/dw_path
     ctx = B.e2f_create(4, 128, 8, 8, 1, 6.0, "bf16", attention="valu")
     try:
         s = [B.e2f_attn_backward_workspace_bytes(ctx, N) for N in (10_000, 20_000)]
