@@ -865,6 +865,116 @@ __global__ __launch_bounds__(256) void k_bwd_wgrad(const T* __restrict__ h, cons
         for (int j = 0; j < 16; ++j) part[(((size_t)slice * 5 + k) * C + co0 + j) * C + ci] = acc[k][j];
 }
 
+// The same sums on the matrix cores for bf16 features: dW_k[co][ci] = sum_rows t_k[row][co] h[row][ci] is a product
+// whose contraction runs over the rows (atoms x orders), the slow index of both arrays, so 32 rows at a time go through
+// LDS in their own order (the factors split into two bf16, leading part and remainder, as in k_bwd_project_mfma) and
+// a lane gathers the 8 rows of its column from there, two bytes at a time (writing them turned instead puts the 16
+// lanes of a row into one bank).  A workgroup owns
+// (slice of rows, 16 output channels) as above, its waves share the C input channels (C / 16 tiles over four waves);
+// the rows of the next step are fetched while the products of this one run.
+template <int C>
+__global__ __launch_bounds__(256) void k_bwd_wgrad_mfma(const uint16_t* __restrict__ h, const float* __restrict__ tbuf, int L,
+                                                        int N, float* __restrict__ part) {
+    typedef float f32x4 __attribute__((ext_vector_type(4)));
+    typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+    typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+    constexpr int R = 32;                         // rows per step
+    constexpr int PA = 5 * 16 + 2, PB = C + 2;    // row pitches in LDS (elements): an odd number of dwords, so that the
+                                                  // four row groups of a gather fall into different banks
+    constexpr int CT = C / 16, TPW = (CT + 3) / 4;   // input-channel tiles, tiles per wave
+    constexpr int NTV = R * 80 / 256;             // factors per thread and step (32 rows x 5 k x 16 channels)
+    constexpr int NHV = (R * C / 8 + 255) / 256;  // 16-byte pieces of the feature rows per thread and step
+    __shared__ uint16_t s_A[2][R][PA];   // [leading part, remainder][row][k * 16 + co]
+    __shared__ uint16_t s_B[R][PB];      // [row][ci]
+    const int slice = blockIdx.x, co0 = blockIdx.y * 16, tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, i = lane & 15, g = lane >> 4;
+    int l = 0;
+    while (WG_SPLIT * (l + 1) * (l + 1) <= slice) ++l;
+    const int n = (L + 1) * (L + 1), nl = 2 * l + 1;
+    const int chunk = slice - WG_SPLIT * l * l, chunks = WG_SPLIT * nl;
+    const int per = (N + chunks - 1) / chunks, a_lo = chunk * per, a_hi = min(N, a_lo + per);
+    const int rows = max(a_hi - a_lo, 0) * nl;   // row r of the chunk: atom a_lo + r / nl, order r % nl
+    const size_t kstride = (size_t)N * n * C;
+    auto row_offset = [&](int r) { return ((size_t)(a_lo + r / nl) * n + l * l + r % nl) * C; };
+    f32x4 acc[5][TPW];
+#pragma unroll
+    for (int k = 0; k < 5; ++k)
+#pragma unroll
+        for (int t = 0; t < TPW; ++t) acc[k][t] = (f32x4){0.f, 0.f, 0.f, 0.f};
+    float tv[NTV];
+    u32x4 hv[NHV];
+    auto fetch = [&](int r0) {   // element e of the factors: row e / 80, k (e % 80) / 16, channel e % 16
+#pragma unroll
+        for (int j = 0; j < NTV; ++j) {
+            const int e = tid + 256 * j, rr = e / 80, k = (e % 80) / 16, jj = e % 16, r = r0 + rr;
+            tv[j] = r < rows ? tbuf[k * kstride + row_offset(r) + co0 + jj] : 0.0f;
+        }
+#pragma unroll
+        for (int j = 0; j < NHV; ++j) {
+            const int e = tid + 256 * j, rr = e / (C / 8), c8 = e % (C / 8), r = r0 + rr;
+            hv[j] = (rr < R && r < rows) ? *reinterpret_cast<const u32x4*>(h + row_offset(r) + 8 * c8) : (u32x4){0u, 0u, 0u, 0u};
+        }
+    };
+    auto turn = [&]() {
+#pragma unroll
+        for (int j = 0; j < NTV; ++j) {
+            const int e = tid + 256 * j, rr = e / 80, k = (e % 80) / 16, jj = e % 16;
+            const uint16_t hi = e2f::float_to_bf16_bits(tv[j]);
+            s_A[0][rr][k * 16 + jj] = hi;
+            s_A[1][rr][k * 16 + jj] = e2f::float_to_bf16_bits(tv[j] - e2f::bf16_bits_to_float(hi));
+        }
+#pragma unroll
+        for (int j = 0; j < NHV; ++j) {
+            const int e = tid + 256 * j, rr = e / (C / 8), c8 = e % (C / 8);
+            if (rr < R) {
+#pragma unroll
+                for (int q = 0; q < 4; ++q) *reinterpret_cast<uint32_t*>(&s_B[rr][8 * c8 + 2 * q]) = hv[j][q];
+            }
+        }
+    };
+    if (rows > 0) fetch(0);
+    for (int r0 = 0; r0 < rows; r0 += R) {
+        __syncthreads();   // the previous step's operands have been read
+        turn();
+        __syncthreads();
+        if (r0 + R < rows) fetch(r0 + R);
+        auto gather = [&](const uint16_t* col, int pitch) {   // rows 8g..8g+7 of one column
+            u32x4 v;
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                v[q] = (uint32_t)col[(8 * g + 2 * q) * pitch] | ((uint32_t)col[(8 * g + 2 * q + 1) * pitch] << 16);
+            return __builtin_bit_cast(bf16x8, v);
+        };
+        bf16x8 A[2][5];
+#pragma unroll
+        for (int hl = 0; hl < 2; ++hl)
+#pragma unroll
+            for (int k = 0; k < 5; ++k) A[hl][k] = gather(&s_A[hl][0][k * 16 + i], PA);
+#pragma unroll
+        for (int t = 0; t < TPW; ++t) {
+            const int ct = wave + 4 * t;
+            if (ct < CT) {   // (wave-uniform)
+                const bf16x8 Bv = gather(&s_B[0][16 * ct + i], PB);
+#pragma unroll
+                for (int k = 0; k < 5; ++k) {
+                    acc[k][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A[0][k], Bv, acc[k][t], 0, 0, 0);
+                    acc[k][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(A[1][k], Bv, acc[k][t], 0, 0, 0);
+                }
+            }
+        }
+    }
+    // part[slice][k][co][ci]: the result lane (i, g) holds rows co = 4g..4g+3 of column ci = i
+#pragma unroll
+    for (int t = 0; t < TPW; ++t) {
+        const int ct = wave + 4 * t;
+        if (ct < CT) {
+#pragma unroll
+            for (int k = 0; k < 5; ++k)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) part[(((size_t)slice * 5 + k) * C + co0 + 4 * g + r) * C + 16 * ct + i] = acc[k][t][r];
+        }
+    }
+}
+
 // out[k][l][co][ci] = sum over the slices of degree l, in a fixed order.
 __global__ void k_sum_chunks(const float* __restrict__ part, int L, int C, float* __restrict__ out) {
     const size_t CC = (size_t)C * C, M = (size_t)5 * (L + 1) * CC;
@@ -1005,7 +1115,11 @@ e2f_status e2f_launch_backward(const e2f_ctx* ctx, const E2fCellsView& cv, const
             else if (C == 64) E2F_BWD_PROJECT(64);
             else E2F_BWD_PROJECT(128);
 #undef E2F_BWD_PROJECT
-            if (grad_W) k_bwd_wgrad<uint16_t><<<wgrid, C, 0, st>>>((const uint16_t*)h, tbuf, L, C, cv.N, bw.wpart);
+            if (grad_W) {
+                if (C == 32) k_bwd_wgrad_mfma<32><<<wgrid, 256, 0, st>>>((const uint16_t*)h, tbuf, L, cv.N, bw.wpart);
+                else if (C == 64) k_bwd_wgrad_mfma<64><<<wgrid, 256, 0, st>>>((const uint16_t*)h, tbuf, L, cv.N, bw.wpart);
+                else k_bwd_wgrad_mfma<128><<<wgrid, 256, 0, st>>>((const uint16_t*)h, tbuf, L, cv.N, bw.wpart);
+            }
         } else if (ctx->cfg.feat_dtype == E2F_BF16) {
             k_bwd_project<uint16_t><<<groups, C, shm, st>>>((const uint16_t*)h, (const uint16_t*)w->WQ1, (const uint16_t*)w->WQ2,
                                                           (const uint16_t*)w->WK1, (const uint16_t*)w->WK2,

@@ -55,6 +55,26 @@ struct BwdTileParams {
 constexpr int LENT = LCAP + 32;   // the list in LDS, padded to whole groups of four chunks
 // Degree of component x (index l*l + l + m).
 constexpr int e2f_degree_of(int x) { return x >= 16 ? 4 : x >= 9 ? 3 : x >= 4 ? 2 : x >= 1 ? 1 : 0; }
+// The non-zero entries of the axis operators grouped by (mu, l_in, l_out): entry = x_out | x_in << 8 | position in the
+// packed list << 16; start[mu][5 l_in + l_out] .. start[mu][5 l_in + l_out + 1] are the entries of one group.
+struct PathTable {
+    uint32_t ent[AXIS_NNZ];
+    int16_t start[3][26];
+    constexpr PathTable() : ent(), start() {
+        int count = 0;
+        for (int mu = 0; mu < 3; ++mu) {
+            for (int bin = 0; bin < 25; ++bin) {
+                start[mu][bin] = (int16_t)count;
+                for (int xo = 0; xo < E2F_MAX_N; ++xo)
+                    for (int xi = 0; xi < E2F_MAX_N; ++xi)
+                        if (e2f_degree_of(xi) == bin / 5 && e2f_degree_of(xo) == bin % 5 && ((E2F_AXIS_NZ[mu][xo] >> xi) & 1u))
+                            ent[count++] = (uint32_t)xo | ((uint32_t)xi << 8) | ((uint32_t)AXIS_INDEX.v[mu][xo][xi] << 16);
+            }
+            start[mu][25] = (int16_t)count;
+        }
+    }
+};
+__device__ constexpr PathTable PATH_TABLE{};
 constexpr float LOG2E = 1.44269504088896341f, LN2 = 0.69314718055994531f;
 
 // ---- relayout: q rows -> grouped layout, q and k -> four slots of a feature per lane (bf16)
@@ -691,6 +711,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     __shared__ float s_G[AXIS_NNZ];
     __shared__ float s_Gu[WGR ? AXIS_NNZ : 1];
     __shared__ float s_bins[NW][32];
+    __shared__ __attribute__((aligned(16))) f32x4 s_vt[WGR ? n * 64 : 1];   // value rows of the tile's atoms, [component][lane]
+    __shared__ uint32_t s_tab[WGR ? AXIS_NNZ : 1];   // PATH_TABLE in LDS (a dependent read from memory per entry otherwise)
+    __shared__ int16_t s_tstart[WGR ? 3 * 26 : 1];
     __shared__ int s_orow[16];
     __shared__ __attribute__((aligned(16))) unsigned char s_raw[W_BYTES > PO_BYTES ? W_BYTES : PO_BYTES];
     u32x4* s_W = reinterpret_cast<u32x4*>(s_raw);
@@ -715,11 +738,13 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     const int cnt = load_list(P, tile, tid, tp, s_ent, s_mask, s_pos);
     if (cnt < 0) return;   // (whole workgroup) a crowded tile: done by the per-atom kernels
     if (tid < AXIS_NNZ) s_G[tid] = g_mine;
-    if (WGR && tid < AXIS_NNZ) s_Gu[tid] = gu_mine;
+    if (WGR && tid < AXIS_NNZ) {
+        s_Gu[tid] = gu_mine;
+        s_tab[tid] = PATH_TABLE.ent[tid];
+        if (tid < 3 * 26) s_tstart[tid] = PATH_TABLE.start[tid / 26][tid % 26];
+    }
     if (tid < 16) s_orow[tid] = orow_mine;
-    float bins[WGR ? (L + 1) * (L + 1) : 1];   // per lane, over this workgroup's heads: bin li * (L + 1) + lo
-#pragma unroll
-    for (int i = 0; i < (WGR ? (L + 1) * (L + 1) : 1); ++i) bins[i] = 0.0f;
+    if (WGR && tid < NW * 32) (&s_bins[0][0])[tid] = 0.0f;   // the waves' bins li * (L + 1) + lo, over this workgroup's heads
     const int nch = (cnt + 7) >> 3, ngr = (nch + NW - 1) / NW;
     const float c_u = 2.0f * P.rbf_gamma * P.rbf_step * LOG2E, c_g = -P.rbf_gamma * LOG2E;
 
@@ -858,17 +883,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
             f32x4 pr[RO];
 #pragma unroll
             for (int i = 0; i < RO; ++i) pr[i] = (f32x4){0.f, 0.f, 0.f, 0.f};
-            // (WGR) the value rows of the tile's atoms 4g..4g+3, channel tn, for this wave's components x_in
-            f32x4 vt[WGR ? RO : 1];
-            if constexpr (WGR) {
-                const size_t grp = min((size_t)(t0 >> 2) + g, (size_t)(N - 1) >> 2);
-#pragma unroll
-                for (int i = 0; i < RO; ++i) {
-                    const u32x2 four = *reinterpret_cast<const u32x2*>(P.v4 + (grp * H + head) * n * 64 + e2f::v4_offset(n, WV + NW * i, tn));
-                    vt[i] = (f32x4){__uint_as_float(four[0] << 16), __uint_as_float(four[0] & 0xffff0000u),
-                                    __uint_as_float(four[1] << 16), __uint_as_float(four[1] & 0xffff0000u)};
-                }
-            }
 #pragma unroll
             for (int mu = 0; mu < 3; ++mu) {
                 __syncthreads();
@@ -879,14 +893,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
                 for (int i = 0; i < RO; ++i) {
 #pragma unroll
                     for (int xo = 0; xo < n; ++xo)
-                        if ((E2F_AXIS_NZ[mu][xo] >> (WV + NW * i)) & 1u) {
-                            const f32x4 y = s_po[xo * 64 + lane];
-                            pr[i] += s_G[AXIS_INDEX.v[mu][xo][WV + NW * i]] * y;
-                            if constexpr (WGR) {
-                                const int li = e2f_degree_of(WV + NW * i), lo = e2f_degree_of(xo);   // (constants once unrolled)
-                                bins[li * (L + 1) + lo] += s_Gu[AXIS_INDEX.v[mu][xo][WV + NW * i]] *
-                                                           (y[0] * vt[i][0] + y[1] * vt[i][1] + y[2] * vt[i][2] + y[3] * vt[i][3]);
-                            }
+                        if ((E2F_AXIS_NZ[mu][xo] >> (WV + NW * i)) & 1u) {   // (one statement; braces kept for the diff)
+                            pr[i] += s_G[AXIS_INDEX.v[mu][xo][WV + NW * i]] * s_po[xo * 64 + lane];
                         }
                 }
             }
@@ -905,17 +913,47 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
         if (wave_u == 1) finish(std::integral_constant<int, 1>{});
         if (wave_u == 2) finish(std::integral_constant<int, 2>{});
         if (wave_u == 3) finish(std::integral_constant<int, 3>{});
+        if constexpr (WGR) {
+            // ---- path-weight bins of this head: sum over the tile's atoms j (rows 4g..4g+3 of a lane), channels (lanes)
+            // and the entries (x_out, x_in) of a group (mu, l_in, l_out) of Y_mu[x_out] Gu_mu[x_out][x_in] v_j[x_in].  A
+            // loop over a table rather than straight-line code: the Y_mu go through LDS once more, one mu at a time.
+            {
+                const size_t grp = min((size_t)(t0 >> 2) + g, (size_t)(N - 1) >> 2);
+                for (int x = wave; x < n; x += NW) {
+                    const u32x2 four = *reinterpret_cast<const u32x2*>(P.v4 + (grp * H + head) * n * 64 + e2f::v4_offset(n, x, tn));
+                    s_vt[x * 64 + lane] = (f32x4){__uint_as_float(four[0] << 16), __uint_as_float(four[0] & 0xffff0000u),
+                                                  __uint_as_float(four[1] << 16), __uint_as_float(four[1] & 0xffff0000u)};
+                }
+            }
+#pragma unroll
+            for (int mu = 0; mu < 3; ++mu) {
+                __syncthreads();
+#pragma unroll
+                for (int sl = 0; sl < NS; ++sl) {   // accumulator slot sl holds component x0 + sl (odd count) or x0 + sl - 1
+                    const int xl = sl - (single ? 0 : 1);
+                    if (xl >= 0 && xl < nxw) s_po[(x0 + xl) * 64 + lane] = acc[mu][sl];
+                }
+                __syncthreads();
+                for (int bin = wave; bin < 25; bin += NW) {
+                    const int li = bin / 5, lo = bin % 5;
+                    const int e0 = s_tstart[mu * 26 + bin], e1 = s_tstart[mu * 26 + bin + 1];
+                    if (li > L || lo > L || e0 == e1) continue;   // (wave-uniform)
+                    float sum = 0.0f;
+#pragma unroll 4
+                    for (int e = e0; e < e1; ++e) {
+                        const uint32_t en = s_tab[e];
+                        const f32x4 y = s_po[(en & 0xffu) * 64 + lane], v = s_vt[((en >> 8) & 0xffu) * 64 + lane];
+                        sum += s_Gu[en >> 16] * (y[0] * v[0] + y[1] * v[1] + y[2] * v[2] + y[3] * v[3]);
+                    }
+#pragma unroll
+                    for (int off = 1; off < 64; off <<= 1) sum += __shfl_xor(sum, off);
+                    if (lane == 0) s_bins[wave][li * (L + 1) + lo] += sum;
+                }
+            }
+        }
         __syncthreads();   // the next head rewrites s_rows and the weight buffers
     }
-    if constexpr (WGR) {   // the tile's bins: lanes, then waves, in a fixed order
-#pragma unroll
-        for (int i = 0; i < (L + 1) * (L + 1); ++i) {
-            float v = bins[i];
-#pragma unroll
-            for (int off = 1; off < 64; off <<= 1) v += __shfl_xor(v, off);
-            if (lane == 0) s_bins[wave][i] = v;
-        }
-        __syncthreads();
+    if constexpr (WGR) {   // the tile's bins: the waves' sums in a fixed order (the last head's barrier lies in between)
         if (tid < 32)
             P.pwp_t[((size_t)tile * HG + hg) * 32 + tid] =
                 tid < (L + 1) * (L + 1) ? s_bins[0][tid] + s_bins[1][tid] + s_bins[2][tid] + s_bins[3][tid] : 0.0f;
