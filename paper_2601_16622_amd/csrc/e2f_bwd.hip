@@ -707,12 +707,14 @@ __global__ __launch_bounds__(64 * (C / 16)) void k_bwd_project_mfma(
     __shared__ __attribute__((aligned(16))) uint16_t s_T[2][5][2][16][ROW];
     int buf = 0;
     const int ct = threadIdx.x >> 6, lane = threadIdx.x & 63, i = lane & 15, g = lane >> 4;
-    const int n = (L + 1) * (L + 1), a0 = blockIdx.x * 16;
+    // one workgroup per (tile of 16 atoms, degree), the highest degree (most slabs) first
+    const int n_tiles = (N + 15) / 16;
+    const int n = (L + 1) * (L + 1), a0 = ((int)blockIdx.x % n_tiles) * 16, l_only = L - (int)blockIdx.x / n_tiles;
     const bool real = a0 + i < N;
     const int atom = min(a0 + i, N - 1);
     const int ch0 = 16 * ct + 4 * g;   // the four channels this lane holds of its atom
     auto frag = [](const uint16_t* p) { return __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(p)); };
-    for (int l = 0; l <= L; ++l) {
+    for (int l = l_only; l <= l_only; ++l) {
         bf16x8 W1[4][NS], W2[5][NS];
         {
             const size_t row = ((size_t)l * C + 16 * ct + i) * C + 8 * g;
@@ -783,14 +785,19 @@ __global__ __launch_bounds__(64 * (C / 16)) void k_bwd_project_mfma(
                 *reinterpret_cast<u32x2*>(&s_T[buf][k][1][i][ch0]) = (u32x2){lo[0] | ((uint32_t)lo[1] << 16), lo[2] | ((uint32_t)lo[3] << 16)};
             }
             __syncthreads();
-            f32x4 d = {0.f, 0.f, 0.f, 0.f};
+            // (four partial sums: one accumulator would chain all 10 C / 32 matrix instructions one after the other)
+            f32x4 dp[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) dp[j] = (f32x4){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int k = 0; k < 5; ++k)
 #pragma unroll
                 for (int S = 0; S < NS; ++S) {
-                    d = __builtin_amdgcn_mfma_f32_16x16x32_bf16(W2[k][S], frag(&s_T[buf][k][0][i][32 * S + 8 * g]), d, 0, 0, 0);
-                    d = __builtin_amdgcn_mfma_f32_16x16x32_bf16(W2[k][S], frag(&s_T[buf][k][1][i][32 * S + 8 * g]), d, 0, 0, 0);
+                    const int j = 2 * (S & 1);
+                    dp[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(W2[k][S], frag(&s_T[buf][k][0][i][32 * S + 8 * g]), dp[j], 0, 0, 0);
+                    dp[j + 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(W2[k][S], frag(&s_T[buf][k][1][i][32 * S + 8 * g]), dp[j + 1], 0, 0, 0);
                 }
+            const f32x4 d = (dp[0] + dp[2]) + (dp[1] + dp[3]);
             // d[r] = dL/dh[atom i][comp][channel 16 ct + 4 g + r]
             if (real) *reinterpret_cast<f32x4*>(gh + rowx + ch0) = d;
             buf ^= 1;
@@ -1107,7 +1114,7 @@ e2f_status e2f_launch_backward(const e2f_ctx* ctx, const E2fCellsView& cv, const
                 (const uint16_t*)w->WV, L + 1, C, bw.wT);
             const int tiles = (cv.N + 15) / 16;
 #define E2F_BWD_PROJECT(CC)                                                                                            \
-    k_bwd_project_mfma<CC><<<tiles, 64 * (CC / 16), 0, st>>>((const uint16_t*)h, (const uint16_t*)w->WQ1,              \
+    k_bwd_project_mfma<CC><<<tiles * (L + 1), 64 * (CC / 16), 0, st>>>((const uint16_t*)h, (const uint16_t*)w->WQ1,              \
                                                            (const uint16_t*)w->WQ2, (const uint16_t*)w->WK1,          \
                                                            (const uint16_t*)w->WK2, bw.wT, grad_q, grad_k, grad_v,    \
                                                            grad_h, tbuf, L, cv.N)
