@@ -1,6 +1,6 @@
 """Turns rocprofv3 result databases into the short text summaries kept under profiles/.
 
-    python -m paper_2601_16622_amd.profile_summary trace  <trace_results.db>
+    python -m paper_2601_16622_amd.profile_summary trace  <trace_results.db> [rows]
     python -m paper_2601_16622_amd.profile_summary pmc    <fetch_results.db> <write_results.db> <copy_bytes>
 
 `trace` prints per-kernel call counts and mean durations (what `rocprofv3 --kernel-trace --stats` collects).
@@ -12,11 +12,11 @@ import sqlite3
 import sys
 
 
-def trace(db):
+def trace(db, rows=14):
     con = sqlite3.connect(db)
     print(f"{'calls':>6} {'mean_us':>12} {'total_ms':>10} {'%':>6}  kernel")
     for name, calls, total, avg, pct in con.execute(
-            "select name, total_calls, total_duration, average, percentage from top_kernels limit 14"):
+            "select name, total_calls, total_duration, average, percentage from top_kernels limit %d" % int(rows)):
         print(f"{calls:6d} {avg:12.2f} {total / 1e3:10.3f} {pct:6.2f}  {name[:110]}")
 
 
@@ -65,7 +65,7 @@ def counters(db, pattern):
 
 if __name__ == "__main__":
     if sys.argv[1] == "trace":
-        trace(sys.argv[2])
+        trace(sys.argv[2], sys.argv[3] if len(sys.argv) > 3 else 14)
     elif sys.argv[1] == "counters":
         counters(sys.argv[2], sys.argv[3])
     else:
