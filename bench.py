@@ -157,7 +157,7 @@ def main():
     attn_ms = stage_ms["attention"]
     bf16 = cfg["dtype"] == "bf16"
     mc_ok = bf16 and cfg["C"] // cfg["H"] == 16 and cfg["L"] >= 1
-    if mc_ok and cfg["lf"] == 1 and cfg["C"] in (32, 64, 128) and cfg["B"] <= 16:
+    if mc_ok and cfg["lf"] == 1 and cfg["C"] in (32, 64, 128, 256) and cfg["B"] <= 16:
         kernel = "k_tile_heads"
     elif mc_ok and cfg["lf"] in (1, 2) and cfg["H"] in (1, 2, 4, 8):
         kernel = "k_fused_mfma"

@@ -152,6 +152,11 @@ E2fAttnWs e2f_attn_ws_layout(const e2f_ctx* ctx, int32_t N, void* ws, int v_layo
         L.lists_ent = (int*)take(n_tiles * E2F_TILE_LCAP * 4);
         L.lists_pos = (float4*)take(n_tiles * E2F_TILE_LCAP * 4 * sizeof(float4));
         L.lists_mask = (unsigned long long*)take(n_tiles * E2F_TILE_LCAP * 8);
+        if (!e2f_tile_layouts_direct(ctx)) {   // the projection's plain layouts, turned into the ones above by a relayout kernel
+            L.q = (float*)take((size_t)N * (ctx->cfg.L_max + 1) * ctx->cfg.C * 4);
+            L.k = (float*)take((size_t)N * (ctx->cfg.L_max + 1) * ctx->cfg.C * 4);
+            L.v = (void*)take((size_t)N * ctx->n * ctx->cfg.C * esz);
+        }
     } else {
         if (v_layout == 3) {
             const size_t H = ctx->cfg.H, DK = (size_t)(ctx->cfg.L_max + 1) * 16, N4 = ((size_t)N + 3) / 4 * 4;

@@ -811,7 +811,7 @@ bool launch_mfma(const e2f_ctx* ctx, const E2fCellsView& cv, const void* h, cons
 template <int C>
 bool launch_ws(const e2f_ctx* ctx, const E2fCellsView& cv, const void* h, const e2f_weights* w, const E2fAttnWs& ws,
                hipStream_t st, bool tiled) {
-    if constexpr (C % 32 != 0 || C > 128) {
+    if constexpr (C % 32 != 0 || C > 256) {
         return false;   // five stationary weight tiles must fit the register file
     } else {
         const int L = ctx->cfg.L_max, n_tiles = (cv.N + 15) / 16;
@@ -894,6 +894,7 @@ bool dispatch_ws(const e2f_ctx* ctx, const E2fCellsView& cv, const void* h, cons
         case 32: return launch_ws<32>(ctx, cv, h, w, ws, st, tiled);
         case 64: return launch_ws<64>(ctx, cv, h, w, ws, st, tiled);
         case 128: return launch_ws<128>(ctx, cv, h, w, ws, st, tiled);
+        case 256: return tiled ? false : launch_ws<256>(ctx, cv, h, w, ws, st, false);
     }
     return false;
 }
@@ -937,12 +938,50 @@ e2f_status e2f_launch_unit_cw(const e2f_ctx* ctx, float* cw, hipStream_t st) {
     return E2F_OK;
 }
 
+// q, k (fp32) and v (bf16) from the plain layouts into the tile kernel's: binary16 q rows scaled for base-2 logits, k rows
+// grouped by four slots, value blocks (e2f::k16_offset, e2f::v4_offset); one workgroup per group of four sorted slots.
+__global__ __launch_bounds__(256) void k_tile_relayout(int N, int L, int C, const float* __restrict__ q, const float* __restrict__ k,
+                                                       const uint16_t* __restrict__ v, float qscale, uint16_t* __restrict__ q16,
+                                                       uint16_t* __restrict__ k16, uint16_t* __restrict__ v4) {
+    __shared__ int s_off[E2F_MAX_N];
+    const int n = (L + 1) * (L + 1), H = C / 16, DK = (L + 1) * 16, DKP = (DK + 31) / 32 * 32, grp = blockIdx.x;
+    if ((int)threadIdx.x < n) s_off[threadIdx.x] = e2f::v4_offset(n, threadIdx.x, 0) | (e2f::v4_role(n, threadIdx.x) == 0 ? 0 : 1 << 30);
+    __syncthreads();
+    for (int it = threadIdx.x; it < 4 * H * DKP; it += 256) {
+        const int s = it / (H * DKP), head = (it / DKP) % H, f = it % DKP, slot = 4 * grp + s;
+        const bool real = slot < N && f < DK;
+        const size_t src = ((size_t)min(slot, N - 1) * (L + 1) + min(f >> 4, L)) * C + head * 16 + (f & 15);
+        const _Float16 kv = to_f16_sat(real ? k[src] : 0.0f);
+        k16[e2f::k16_offset(slot, H, head, DKP, f)] = __builtin_bit_cast(uint16_t, kv);
+        if (slot < N) q16[((size_t)slot * H + head) * DKP + f] = __builtin_bit_cast(uint16_t, to_f16_sat(real ? q[src] * qscale : 0.0f));
+    }
+    for (int it = threadIdx.x; it < n * C; it += 256) {
+        const int x = it / C, c = it % C, o = s_off[x];
+        uint16_t b[4];
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            const int slot = 4 * grp + s;
+            const uint16_t val = v[((size_t)min(slot, N - 1) * n + x) * C + c];
+            b[s] = slot < N ? val : (uint16_t)0;
+        }
+        *reinterpret_cast<uint2*>(v4 + ((size_t)grp * H + (c >> 4)) * n * 64 + (o & 0xffffff) + (c & 15) * ((o >> 30) ? 8 : 4)) =
+            make_uint2(b[0] | ((uint32_t)b[1] << 16), b[2] | ((uint32_t)b[3] << 16));
+    }
+}
+
 e2f_status e2f_launch_project_mfma(const e2f_ctx* ctx, const E2fCellsView& cv, const void* h, const e2f_weights* w,
                                    const E2fAttnWs& ws, int v_layout, hipStream_t st) {
     if (cv.N == 0) return E2F_OK;
     bool ok;
     const bool tiled_v = v_layout == 1;
-    if (v_layout == 2)
+    if (v_layout == 2 && !e2f_tile_layouts_direct(ctx)) {
+        // channel counts the tile-layout projection kernels are not built for: plain layouts, then a relayout
+        if (ctx->cfg.feat_dtype != E2F_BF16 || !ws.q || !ws.k || !ws.v) return E2F_ERR_UNSUPPORTED;
+        ok = dispatch_ws(ctx, cv, h, w, ws, st, false) || dispatch_mfma<uint16_t>(ctx, cv, h, w, ws, st, false);
+        if (ok)
+            k_tile_relayout<<<(cv.N + 3) / 4, 256, 0, st>>>(cv.N, ctx->cfg.L_max, ctx->cfg.C, ws.q, ws.k, (const uint16_t*)ws.v,
+                                                         ctx->tau * 1.44269504088896341f, ws.q16, ws.k16, ws.v4);
+    } else if (v_layout == 2)
         ok = ctx->cfg.feat_dtype == E2F_BF16 && dispatch_wg(ctx, cv, h, w, ws, st, 2);
     else if (ctx->cfg.feat_dtype == E2F_BF16)
         ok = (tiled_v && dispatch_wg(ctx, cv, h, w, ws, st, 1)) || dispatch_ws(ctx, cv, h, w, ws, st, tiled_v) ||

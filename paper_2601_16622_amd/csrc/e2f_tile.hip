@@ -1077,7 +1077,7 @@ e2f_status e2f_launch_axis_ops(const e2f_ctx* ctx, const float* cw, float* G, hi
 bool e2f_tile_supported(const e2f_ctx* ctx) {
     const int C = ctx->cfg.C;
     return ctx->cfg.feat_dtype == E2F_BF16 && ctx->cfg.lf == 1 && ctx->Ch == 16 && ctx->cfg.L_max >= 1 &&
-           ctx->cfg.B <= 16 && (C == 32 || C == 64 || C == 128);
+           ctx->cfg.B <= 16 && (C == 32 || C == 64 || C == 128 || C == 256);   // (a projection exists)
 }
 
 static e2f_status launch_tile(const e2f_ctx* ctx, const E2fCellsView& cv, const E2fAttnWs& ws, const int32_t* table,

@@ -59,7 +59,7 @@ def run_backward(torch, wl, seed=0):
         # each checked against the reference on its own); elsewhere it is the same kernels and the same numbers.
         plain = P.backward(g)
         torch.cuda.synchronize()
-        same_kernels = not (cfg["dtype"] == "bf16" and cfg["C"] // cfg["H"] == 16 and cfg["B"] <= 16 and cfg["C"] in (32, 64, 128))
+        same_kernels = not (cfg["dtype"] == "bf16" and cfg["C"] // cfg["H"] == 16 and cfg["B"] <= 16 and cfg["C"] in (32, 64, 128, 256))
         errs = {}
         for name, x, y in zip(("pos", "q", "k", "v", "h"), plain, P.backward(g, with_weights=True)):
             if same_kernels:
@@ -121,6 +121,13 @@ def test_backward_periodic(torch_cuda):
 def test_backward_tile_form_with_12_radial_functions(torch_cuda):
     """The tile kernels' instances for more than 8 radial basis functions (the bias polynomial and its derivative)."""
     wl = custom(21, (230, 40), 3, 64, 4, 12, "bf16", 4.5, 11.0)
+    run_backward(torch_cuda, wl)
+
+
+def test_backward_tile_form_256_channels(torch_cuda):
+    """A channel count the tile-layout projection is not built for: plain projection, relayout, tile kernels; the chain
+    rule through the projections on the vector-ALU kernel."""
+    wl = custom(22, (200, 60), 2, 256, 16, 8, "bf16", 4.5, 11.0)
     run_backward(torch_cuda, wl)
 
 

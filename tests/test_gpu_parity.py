@@ -184,6 +184,8 @@ def _custom(seed, N, L, C, H, B, lf, dtype, cutoff=3.0, side=6.0, seg=None):
     dict(N=50, L=2, C=32, H=2, B=8, lf=2, dtype="bf16"),       # degree-2 filter, low tile only
     dict(N=200, L=4, C=64, H=4, B=16, lf=1, dtype="bf16"),     # tile kernels with 16 radial basis functions
     dict(N=150, L=2, C=32, H=2, B=11, lf=1, dtype="bf16"),     # ... and with 11
+    dict(N=300, L=4, C=256, H=16, B=8, lf=1, dtype="bf16", side=8.5),    # 256 channels on the tile kernels (plain projection + relayout)
+    dict(N=210, L=2, C=48, H=3, B=8, lf=1, dtype="f32", side=7.0),       # 48 channels in three heads: the fp32 tile kernel
 ])
 def test_other_shapes_and_degenerate_inputs(torch_cuda, kw):
     run_case(torch_cuda, _custom(5, **kw))
