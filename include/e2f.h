@@ -63,8 +63,10 @@ typedef enum { E2F_F32 = 0, E2F_BF16 = 1 } e2f_dtype;
  * Which kernel runs the attention stage (Sec. 3.4, Algorithm 1).  All give the same result up to rounding.
  *   AUTO  the fastest form that supports the configuration (the order below)
  *   TILE  16 targets x 32 candidates on the matrix cores, degree-1 filter through its linear factorization
- *         (Eq. e2former_final at l = 1); heads of 16 channels, lf = 1.  With bf16 features q and k are kept in
- *         binary16 (values beyond +-65504 are clamped: use PAIR for features that are not normalised)
+ *         (Eq. e2former_final at l = 1); heads of 16 channels, lf = 1, at most 16 radial basis functions; bf16
+ *         features with C = 32, 64, 128 or 256, or fp32 features (every product then in binary32).  With bf16
+ *         features q and k are kept in binary16 (values beyond +-65504 are clamped: use PAIR for features that are
+ *         not normalised).  fp32 calls with a neighbour cap or a table run on VALU.
  *   PAIR  one wave per target, the aligning rotation and P evaluated per pair (Sec. 3.3), operators applied on the
  *         matrix cores; bf16 features, heads of 16 channels, lf = 1 or 2; q and k in fp32
  *   VALU  the same per-pair form on the vector ALUs; every configuration
@@ -292,7 +294,10 @@ e2f_status e2f_attn_forward_factorized(e2f_ctx *ctx, const e2f_cells *cells, con
  *             (five more [N][(L_max+1)^2][C] float arrays of row factors and partial sums of the result)
  *   ws        device, at least e2f_attn_backward_workspace_bytes(ctx, N) bytes, 256-byte aligned
  * Cell lists from e2f_build_cells and e2f_build_cells_periodic are accepted.  E2F_ERR_UNSUPPORTED: lf != 1, or a
- * head width C/H that is not a power of two <= 64.  A neighbour cap has no backward form here (the capped
+ * head width C/H that is not a power of two <= 64.  Where the forward pass runs on the bf16 TILE kernel the pair work of
+ * this call runs in the same form on the matrix cores (with grad_Wb / grad_w_path only for B <= 8; beyond that, and for
+ * every other configuration, one workgroup per atom on the vector ALUs); position gradients of a segment then sum to
+ * zero to rounding of the bf16 operands, not to the last bit.  A neighbour cap has no backward form here (the capped
  * neighbour relation is not symmetric).  Allocates nothing, does not synchronise.  Otherwise as e2f_attn_forward.
  */
 size_t e2f_attn_backward_workspace_bytes(const e2f_ctx *ctx, int32_t N);
