@@ -199,7 +199,7 @@ def main():
     if kernel == "k_tile_heads":
         # what the kernel executes (matrix-core instructions over all candidate slots, masked ones included), from the
         # committed counter summary of the same workload
-        sq = read_counters("k_tile_heads<4, false>")
+        sq = read_counters("k_tile_heads<4, false, 8>")
         useful = E * cfg["H"] * (2 * (Lm + 1) * 16 + 3 * n * 16 * 2)
         if sq.get("SQ_INSTS_MFMA"):
             roofline["executed"] = {
