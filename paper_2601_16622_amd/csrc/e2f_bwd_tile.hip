@@ -574,9 +574,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
             load_X(c, 2 * VP, VS - 2 * VP);
             scalars(1);
             u_phase(2 * VP, VS - 2 * VP);
-            load_X(cn, 0, VP);
-            load_K(cn);
-            // the candidates' k (q) rows, four slots of a group per lane, for the dq (dk) product
+            // the candidates' k (q) rows, four slots of a group per lane, for the dq (dk) product; requested before the
+            // next chunk's rows, so that waiting for them (loads complete in order) does not wait for those
             VRows<KS> y4;
             {
                 const unsigned ea = (unsigned)s_ent[8 * c + g] >> 8, eb = (unsigned)s_ent[8 * c + 4 + g] >> 8;
@@ -585,6 +584,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 #pragma unroll
                 for (int pp = 0; pp < KS; ++pp) y4.load_pair(pp, ba, bb);
             }
+            load_X(cn, 0, VP);
+            load_K(cn);
             // ---- ds and the position gradient
             float ds[8];
 #pragma unroll
@@ -1026,6 +1027,15 @@ void launch_L(const BwdTileParams& P, bool wgrad, hipStream_t st) {
 
 }  // namespace
 
+// Heads per workgroup of the tile kernels above: up to four, as long as about eight rounds of workgroups are left for the
+// chip (a head's set-up is not shared between heads here, so fewer, longer workgroups only pay in the tail: measured
+// 1.5 % behind with two heads per workgroup at 10 000 atoms).
+static int e2f_bwd_tile_heads_per_workgroup(int n_tiles, int H) {
+    int hpw = 1;
+    while (hpw < 4 && H % (hpw * 2) == 0 && (long)n_tiles * H / (hpw * 2) >= 4096) hpw *= 2;
+    return hpw;
+}
+
 E2fBwdTileWs e2f_bwd_tile_ws_layout(const e2f_ctx* ctx, int32_t N, void* ws, size_t offset) {
     E2fBwdTileWs T;
     size_t off = offset;
@@ -1071,8 +1081,7 @@ e2f_status e2f_launch_backward_tile(const e2f_ctx* ctx, const E2fCellsView& cv, 
     P.out = out; P.gout = grad_out; P.gq = grad_q; P.gk = grad_k; P.gv = grad_v; P.gpos = grad_pos;
     P.lists_hdr = ws.lists_hdr; P.lists_ent = ws.lists_ent; P.lists_pos = ws.lists_pos; P.lists_mask = ws.lists_mask;
     P.C = ctx->cfg.C; P.H = ctx->cfg.H; P.B = ctx->cfg.B; P.n_tiles = (cv.N + 15) / 16;
-    P.hpw = 1;
-    while (P.hpw < 4 && P.H % (P.hpw * 2) == 0 && (long)P.n_tiles * P.H / (P.hpw * 2) >= 2048) P.hpw *= 2;
+    P.hpw = e2f_bwd_tile_heads_per_workgroup(P.n_tiles, P.H);
     P.tau = ctx->tau; P.rc2 = ctx->rc2; P.cutoff = ctx->cfg.cutoff; P.rbf_step = ctx->rbf_step; P.rbf_gamma = ctx->rbf_gamma;
     switch (ctx->cfg.L_max) {
         case 1: launch_L<1>(P, wgrad, st); break;
@@ -1091,8 +1100,7 @@ e2f_status e2f_launch_backward_tile_wsum(const e2f_ctx* ctx, const E2fCellsView&
                                          float* grad_Wb, float* grad_w_path, hipStream_t st) {
     if (cv.N == 0) return E2F_OK;
     const int n_tiles = (cv.N + 15) / 16, HB = ctx->cfg.H * ctx->cfg.B, L1 = ctx->cfg.L_max + 1;
-    int hpw = 1;
-    while (hpw < 4 && ctx->cfg.H % (hpw * 2) == 0 && (long)n_tiles * ctx->cfg.H / (hpw * 2) >= 2048) hpw *= 2;
+    const int hpw = e2f_bwd_tile_heads_per_workgroup(n_tiles, ctx->cfg.H);
     if (grad_Wb) k_bwd_wsum<<<HB, 256, 0, st>>>(cv, ws.lists_hdr, tw.pWb_t, 1, HB, atom_pWb, HB, n_tiles, HB, grad_Wb);
     if (grad_w_path)
         k_bwd_wsum<<<L1 * L1, 256, 0, st>>>(cv, ws.lists_hdr, tw.pwp_t, ctx->cfg.H / hpw, 32, atom_pwp, 32, n_tiles, L1 * L1, grad_w_path);
