@@ -667,15 +667,17 @@ __global__ __launch_bounds__(256) void k_bwd_project(const T* __restrict__ h, co
     }
 }
 
-// ---- the same chain rule on the matrix cores, for bf16 features and C <= 128.  A workgroup owns 16 consecutive atoms
-// and walks the (degree, order) slabs; wave ct owns output channels 16 ct .. 16 ct + 15 of the forward products and
-// the same input channels of the transposed ones.  Both products are written with the channels as rows and the atoms
-// as columns, (W x)^T = W X^T and dX^T = sum_k W_k^T T_k^T, so that the weights are the A operand (one 16-byte load per
-// fragment, from W for the first and from the transposed copy WT for the second, kept in registers over a degree),
-// a lane ends up with four consecutive channels of one atom (16-byte loads of dq, dk, dv and 16-byte stores of the
-// result) and the row factors t_k cross the waves through LDS as [atom][channel] rows.  The factors are fp32; for the
-// second product each is split into two bf16 (leading part and remainder, 16 significant bits together), so that the
-// result keeps fp32-like accuracy on bf16 matrix instructions.
+// ---- the same chain rule on the matrix cores, for bf16 features and C <= 128.  A workgroup owns one degree and a
+// few consecutive tiles of 16 atoms and walks their (tile, order) slabs with one load of its weights; wave ct owns
+// output channels 16 ct .. 16 ct + 15 of the forward products and the same input channels of the transposed ones.
+// Both products are written with the channels as rows and the atoms as columns, (W x)^T = W X^T and
+// dX^T = sum_k W_k^T T_k^T, so that the weights are the A operand (one 16-byte load per fragment, from W for the first
+// and from the transposed copy WT for the second, kept in registers), a lane ends up with four consecutive channels
+// of one atom (16-byte loads of dq, dk, dv and 16-byte stores of the result) and the row factors t_k cross the waves
+// through LDS as [atom][channel] rows.  The feature rows of a slab are fetched once per workgroup and shared through
+// LDS as well.  The factors are fp32; for the second product each is rounded to bf16, the counterpart of the forward
+// pass rounding the projected values to bf16 (HL = 2 splits each into two bf16 instead, leading part and remainder,
+// 16 significant bits together, at twice the LDS reads and matrix instructions of that product).
 __global__ __launch_bounds__(256) void k_transpose_weights(const uint16_t* __restrict__ W0, const uint16_t* __restrict__ W1,
                                                            const uint16_t* __restrict__ W2, const uint16_t* __restrict__ W3,
                                                            const uint16_t* __restrict__ W4, int L1, int C,
@@ -691,121 +693,214 @@ __global__ __launch_bounds__(256) void k_transpose_weights(const uint16_t* __res
     WT[(((size_t)k * L1 + l) * C + 16 * tc + r) * C + 16 * tr + c] = s[c][r];
 }
 
-template <int C>
+// Which workgroups take which degree: workgroups [first[d], first[d + 1]) own degree L - d (the highest degree, with
+// the most slabs per tile, first) and tiles[d] consecutive tiles of 16 atoms each, so that every workgroup walks about
+// the same number of (tile, order) slabs with one load of its weights.
+constexpr int PROJECT_SLABS = 18;   // slabs a workgroup of k_bwd_project_mfma walks with one load of its weights
+constexpr int PROJECT_SPLIT = 1;    // 1: the row factors as one bf16 each; 2: as two (leading part and remainder)
+struct ProjectMap {
+    int first[E2F_MAX_L + 2];
+    int tiles[E2F_MAX_L + 1];
+};
+
+template <int C, int HL>
 __global__ __launch_bounds__(64 * (C / 16)) void k_bwd_project_mfma(
     const uint16_t* __restrict__ h, const uint16_t* __restrict__ WQ1, const uint16_t* __restrict__ WQ2,
     const uint16_t* __restrict__ WK1, const uint16_t* __restrict__ WK2, const uint16_t* __restrict__ WT,
     const float* __restrict__ gq, const float* __restrict__ gk, const float* __restrict__ gv, float* __restrict__ gh,
-    float* __restrict__ tbuf, int L, int N) {
+    float* __restrict__ tbuf, int L, int N, ProjectMap map) {
     typedef float f32x4 __attribute__((ext_vector_type(4)));
     typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
     typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
     typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
-    constexpr int NS = C / 32, ROW = C + 8;   // LDS rows of the factors, 16 bytes of padding against bank conflicts
-    // (two buffers, used in turn: a slab's factors may be written while the slab before it is still being read, so
-    // one barrier per slab is enough)
-    __shared__ __attribute__((aligned(16))) uint16_t s_T[2][5][2][16][ROW];
-    int buf = 0;
-    const int ct = threadIdx.x >> 6, lane = threadIdx.x & 63, i = lane & 15, g = lane >> 4;
-    // one workgroup per (tile of 16 atoms, degree), the highest degree (most slabs) first
-    const int n_tiles = (N + 15) / 16;
-    const int n = (L + 1) * (L + 1), a0 = ((int)blockIdx.x % n_tiles) * 16, l_only = L - (int)blockIdx.x / n_tiles;
-    const bool real = a0 + i < N;
-    const int atom = min(a0 + i, N - 1);
+    constexpr int NS = C / 32, ROW = C + 8;   // LDS rows of 16 atoms, 16 bytes of padding against bank conflicts
+    constexpr int PD = 3;                     // slabs in flight from memory
+    // Two buffers each, used in turn.  In one pass of the loop a wave runs the second stage of slab s (reads s_T[s & 1]),
+    // the first stage of slab s + 1 (reads s_X[(s + 1) & 1], writes s_T[(s + 1) & 1]) and stores the feature rows of
+    // slab s + 2 (s_X[s & 1]): the two stages of consecutive slabs overlap inside a wave and one barrier per slab is enough.
+    __shared__ __attribute__((aligned(16))) uint16_t s_T[2][5][HL][16][ROW];
+    __shared__ __attribute__((aligned(16))) uint16_t s_X[2][16][ROW];
+    // (the wave's index through readfirstlane, so that the compiler knows it to be the same in all lanes)
+    const int tid = threadIdx.x, ct = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, i = lane & 15, g = lane >> 4;
+    const int n_tiles = (N + 15) / 16, n = (L + 1) * (L + 1);
+    int d = 0;
+    while (d < L && (int)blockIdx.x >= map.first[d + 1]) ++d;
+    const int l = L - d, nl = 2 * l + 1;
+    const int tile0 = ((int)blockIdx.x - map.first[d]) * map.tiles[d];
+    const int n_slabs = (min(n_tiles, tile0 + map.tiles[d]) - tile0) * nl;   // slab s: tile tile0 + s / nl, order s % nl
+    if (n_slabs <= 0) return;
     const int ch0 = 16 * ct + 4 * g;   // the four channels this lane holds of its atom
     auto frag = [](const uint16_t* p) { return __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(p)); };
-    for (int l = l_only; l <= l_only; ++l) {
-        bf16x8 W1[4][NS], W2[5][NS];
-        {
-            const size_t row = ((size_t)l * C + 16 * ct + i) * C + 8 * g;
-            const size_t lstride = (size_t)(L + 1) * C * C;
+    auto pack2 = [](float a, float b) {
+        typedef float f32x2 __attribute__((ext_vector_type(2)));
+        typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+        return __builtin_bit_cast(uint32_t, __builtin_convertvector((f32x2){a, b}, bf16x2));
+    };
+    bf16x8 W1[4][NS], W2[5][NS];
+    {
+        const size_t row = ((size_t)l * C + 16 * ct + i) * C + 8 * g;
+        const size_t lstride = (size_t)(L + 1) * C * C;
 #pragma unroll
-            for (int S = 0; S < NS; ++S) {
-                W1[0][S] = frag(WQ1 + row + 32 * S);
-                W1[1][S] = frag(WQ2 + row + 32 * S);
-                W1[2][S] = frag(WK1 + row + 32 * S);
-                W1[3][S] = frag(WK2 + row + 32 * S);
+        for (int S = 0; S < NS; ++S) {
+            W1[0][S] = frag(WQ1 + row + 32 * S);
+            W1[1][S] = frag(WQ2 + row + 32 * S);
+            W1[2][S] = frag(WK1 + row + 32 * S);
+            W1[3][S] = frag(WK2 + row + 32 * S);
 #pragma unroll
-                for (int k = 0; k < 5; ++k) W2[k][S] = frag(WT + k * lstride + row + 32 * S);
+            for (int k = 0; k < 5; ++k) W2[k][S] = frag(WT + k * lstride + row + 32 * S);
+        }
+    }
+    // What is read of a slab.  The feature rows of its 16 atoms, shared by the waves: thread tid fetches four channels
+    // (xa, xc) of one row, which reach the waves through s_X.  dv for the lane's own atom and channels.  Both are
+    // requested PD slabs before their use, in rings of registers indexed at compile time; dq and dk of a tile (lane's
+    // atom and channels again) are requested when the tile before it starts.
+    const int xa = tid / (C / 4), xc = 4 * (tid % (C / 4));
+    // the four places where the sequence of slabs is walked (requests of x and of dv, first stage, second stage)
+    // each keep (first atom of the tile, order); a cursor stays on the last slab once it gets there
+    struct Cursor {
+        int a0, m;
+    };
+    const int a_last = (tile0 + n_slabs / nl - 1) * 16;
+    auto advance = [&](Cursor& c) {
+        if (c.m + 1 < nl) {
+            ++c.m;
+        } else if (c.a0 < a_last) {
+            c.m = 0;
+            c.a0 += 16;
+        }
+    };
+    Cursor cx = {tile0 * 16, 0}, cv = cx, cf = cx, co = cx;
+    auto fetch_x = [&]() {
+        const u32x2 v = *reinterpret_cast<const u32x2*>(h + ((size_t)min(cx.a0 + xa, N - 1) * n + l * l + cx.m) * C + xc);
+        advance(cx);
+        return v;
+    };
+    auto fetch_dv = [&]() {
+        const f32x4 v = *reinterpret_cast<const f32x4*>(gv + ((size_t)min(cv.a0 + i, N - 1) * n + l * l + cv.m) * C + ch0);
+        advance(cv);
+        return v;
+    };
+    auto fetch_dqk = [&](int a0, f32x4& dq, f32x4& dk) {
+        const size_t at = ((size_t)min(a0 + i, N - 1) * (L + 1) + l) * C + ch0;
+        dq = *reinterpret_cast<const f32x4*>(gq + at);
+        dk = *reinterpret_cast<const f32x4*>(gk + at);
+    };
+    auto store_x = [&](int s, u32x2 v) { *reinterpret_cast<u32x2*>(&s_X[s & 1][xa][xc]) = v; };
+    f32x4 dq, dk, dq_next, dk_next;
+    // first stage of slab s: the four forward products of the slab's rows, then the five row factors
+    // t = (dq (WQ2 x), dq (WQ1 x), dk (WK2 x), dk (WK1 x), dv), to the workspace (fp32) and to LDS (bf16)
+    auto factors = [&](int s, f32x4 dv, bool to_lds) {
+        const int atom = cf.a0 + i, m = cf.m;
+        const bool real = atom < N;
+        if (m == 0) {   // (uniform) a new tile
+            dq = dq_next;
+            dk = dk_next;
+            fetch_dqk(cf.a0 + 16, dq_next, dk_next);
+        }
+        advance(cf);
+        f32x4 p[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) p[k] = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int S = 0; S < NS; ++S) {
+            const bf16x8 X = frag(&s_X[s & 1][i][32 * S + 8 * g]);
+#pragma unroll
+            for (int k = 0; k < 4; ++k) p[k] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(W1[k][S], X, p[k], 0, 0, 0);
+        }
+        // p[k][r] = (W_k x)[channel 16 ct + 4 g + r] of atom i
+        f32x4 t[5];
+        t[0] = dq * p[1];
+        t[1] = dq * p[0];
+        t[2] = dk * p[3];
+        t[3] = dk * p[2];
+        t[4] = dv;
+        if (!real) {
+#pragma unroll
+            for (int k = 0; k < 5; ++k) t[k] = (f32x4){0.f, 0.f, 0.f, 0.f};
+        }
+        if (tbuf && real) {   // the row factors of the weight gradients: dW_k[l] = sum over rows of t_k (x) x
+            const size_t rowx = ((size_t)atom * n + l * l + m) * C;
+#pragma unroll
+            for (int k = 0; k < 5; ++k) *reinterpret_cast<f32x4*>(tbuf + (size_t)k * N * n * C + rowx + ch0) = t[k];
+        }
+        if (!to_lds) return;
+        const int buf = s & 1;
+#pragma unroll
+        for (int k = 0; k < 5; ++k) {
+            const u32x2 hi = {pack2(t[k][0], t[k][1]), pack2(t[k][2], t[k][3])};   // (round to nearest even)
+            *reinterpret_cast<u32x2*>(&s_T[buf][k][0][i][ch0]) = hi;
+            if constexpr (HL == 2) {   // the remainders: 16 significant bits together
+                f32x4 rem;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) rem[r] = t[k][r] - __builtin_bit_cast(float, (r & 1) ? (hi[r >> 1] & 0xffff0000u) : (hi[r >> 1] << 16));
+                *reinterpret_cast<u32x2*>(&s_T[buf][k][HL - 1][i][ch0]) = (u32x2){pack2(rem[0], rem[1]), pack2(rem[2], rem[3])};
             }
         }
-        const f32x4 dq = real ? *reinterpret_cast<const f32x4*>(gq + ((size_t)atom * (L + 1) + l) * C + ch0) : (f32x4){0.f, 0.f, 0.f, 0.f};
-        const f32x4 dk = real ? *reinterpret_cast<const f32x4*>(gk + ((size_t)atom * (L + 1) + l) * C + ch0) : (f32x4){0.f, 0.f, 0.f, 0.f};
-        // the rows of a slab are requested one slab ahead
-        bf16x8 X[NS], Xn[NS];
-        f32x4 gvv, gvn;
-        {
-            const size_t rowx = ((size_t)atom * n + l * l) * C;
+    };
+    // ring slot of slab s: s % PD.  Before pass s of the loop the rings hold x of slabs s + 2 .. s + 4 and dv of
+    // slabs s + 1 .. s + 3; s_X holds x of slabs s and s + 1 and s_T the factors of slab s.
+    u32x2 xr[PD];
+    f32x4 dvr[PD];
+    fetch_dqk(tile0 * 16, dq_next, dk_next);
+    store_x(0, fetch_x());
+    store_x(1, fetch_x());
 #pragma unroll
-            for (int S = 0; S < NS; ++S) X[S] = frag(h + rowx + 32 * S + 8 * g);
-            gvv = *reinterpret_cast<const f32x4*>(gv + rowx + ch0);
-        }
-        for (int m = 0; m < 2 * l + 1; ++m) {
-            const int comp = l * l + m;
-            const size_t rowx = ((size_t)atom * n + comp) * C;
-            {
-                const size_t rown = ((size_t)atom * n + min(comp + 1, n - 1)) * C;
-#pragma unroll
-                for (int S = 0; S < NS; ++S) Xn[S] = frag(h + rown + 32 * S + 8 * g);
-                gvn = *reinterpret_cast<const f32x4*>(gv + rown + ch0);
-            }
-            f32x4 t[5];
-            t[4] = real ? gvv : (f32x4){0.f, 0.f, 0.f, 0.f};
-            f32x4 p[4];
-#pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                p[k] = (f32x4){0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                for (int S = 0; S < NS; ++S) p[k] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(W1[k][S], X[S], p[k], 0, 0, 0);
-            }
-            // p[k][r] = (W_k x)[channel 16 ct + 4 g + r] of atom i
-            t[0] = dq * p[1];
-            t[1] = dq * p[0];
-            t[2] = dk * p[3];
-            t[3] = dk * p[2];
-            if (tbuf && real) {   // the five row factors of the weight gradients: dW_k[l] = sum over rows of t_k (x) x
-#pragma unroll
-                for (int k = 0; k < 5; ++k) *reinterpret_cast<f32x4*>(tbuf + ((size_t)k * N + atom) * n * C + (size_t)comp * C + ch0) = t[k];
-            }
-            if (!gh) {   // (uniform) only the row factors were asked for
-#pragma unroll
-                for (int S = 0; S < NS; ++S) X[S] = Xn[S];
-                gvv = gvn;
-                continue;
-            }
-#pragma unroll
-            for (int k = 0; k < 5; ++k) {
-                uint16_t hi[4], lo[4];
-#pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    hi[r] = e2f::float_to_bf16_bits(t[k][r]);
-                    lo[r] = e2f::float_to_bf16_bits(t[k][r] - e2f::bf16_bits_to_float(hi[r]));
-                }
-                *reinterpret_cast<u32x2*>(&s_T[buf][k][0][i][ch0]) = (u32x2){hi[0] | ((uint32_t)hi[1] << 16), hi[2] | ((uint32_t)hi[3] << 16)};
-                *reinterpret_cast<u32x2*>(&s_T[buf][k][1][i][ch0]) = (u32x2){lo[0] | ((uint32_t)lo[1] << 16), lo[2] | ((uint32_t)lo[3] << 16)};
-            }
-            __syncthreads();
-            // (four partial sums: one accumulator would chain all 10 C / 32 matrix instructions one after the other)
-            f32x4 dp[4];
+    for (int u = 0; u < PD; ++u) {
+        xr[(u + 2) % PD] = fetch_x();
+        dvr[u] = fetch_dv();
+    }
+    __syncthreads();
+    const bool lds = gh != nullptr;   // (uniform) without dL/dh only the row factors are asked for
+    factors(0, dvr[0], lds);
+    dvr[0] = fetch_dv();
+    __syncthreads();
+    // One pass of the loop, for slab s = s0 + u with ring slots known at compile time.  (LAST: a pass of the last,
+    // partial group, which checks whether its slab and the next exist.  The passes of the full groups have no such
+    // branches: the compiler places its waits on the loads by the least number of memory instructions on any path
+    // from a request to its use, and a path that skips passes would make it wait for requests one pass old.)
+    auto pass = [&](int s, int u, bool LAST) __attribute__((always_inline)) {
+        // The first stage of the next slab and the second stage of this one are independent.
+        auto first_stage = [&]() {
+            // the feature rows of slab s + 2 have arrived: into the buffer that slab s used
+            store_x(s + 2, xr[(u + 2) % PD]);
+            xr[(u + 2) % PD] = fetch_x();
+            if (!LAST || s + 1 < n_slabs) factors(s + 1, dvr[(u + 1) % PD], lds);
+            dvr[(u + 1) % PD] = fetch_dv();
+        };
+        auto second_stage = [&]() {
+            if (!lds) return;
+            const int buf = s & 1;
+            // (four partial sums: one accumulator would chain all the matrix instructions one after the other)
+            f32x4 dp[4];   // (only dp[0] and dp[1] in use when HL == 1)
 #pragma unroll
             for (int j = 0; j < 4; ++j) dp[j] = (f32x4){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int k = 0; k < 5; ++k)
 #pragma unroll
-                for (int S = 0; S < NS; ++S) {
-                    const int j = 2 * (S & 1);
-                    dp[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(W2[k][S], frag(&s_T[buf][k][0][i][32 * S + 8 * g]), dp[j], 0, 0, 0);
-                    dp[j + 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(W2[k][S], frag(&s_T[buf][k][1][i][32 * S + 8 * g]), dp[j + 1], 0, 0, 0);
-                }
-            const f32x4 d = (dp[0] + dp[2]) + (dp[1] + dp[3]);
-            // d[r] = dL/dh[atom i][comp][channel 16 ct + 4 g + r]
-            if (real) *reinterpret_cast<f32x4*>(gh + rowx + ch0) = d;
-            buf ^= 1;
+                for (int S = 0; S < NS; ++S)
 #pragma unroll
-            for (int S = 0; S < NS; ++S) X[S] = Xn[S];
-            gvv = gvn;
-        }
+                    for (int hl = 0; hl < HL; ++hl) {
+                        const int j = HL == 2 ? 2 * (S & 1) + hl : (k * NS + S) & 1;
+                        dp[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(W2[k][S], frag(&s_T[buf][k][hl][i][32 * S + 8 * g]), dp[j], 0, 0, 0);
+                    }
+            const f32x4 dx = (dp[0] + dp[2]) + (dp[1] + dp[3]);
+            // dx[r] = dL/dh[atom i][component][channel 16 ct + 4 g + r]
+            const int atom = co.a0 + i;
+            if (atom < N) *reinterpret_cast<f32x4*>(gh + ((size_t)atom * n + l * l + co.m) * C + ch0) = dx;
+            advance(co);
+        };
+        first_stage();
+        second_stage();
+        __syncthreads();
+    };
+    int s0 = 0;
+    for (; s0 + PD < n_slabs; s0 += PD) {
+#pragma unroll
+        for (int u = 0; u < PD; ++u) pass(s0 + u, u, false);
     }
+#pragma unroll
+    for (int u = 0; u < PD; ++u)
+        if (s0 + u < n_slabs) pass(s0 + u, u, true);   // (uniform)
 }
 
 // ---- gradients of the five projection matrices: dW_k[l][co][ci] = sum over atoms a and orders m of
@@ -1113,11 +1208,18 @@ e2f_status e2f_launch_backward(const e2f_ctx* ctx, const E2fCellsView& cv, const
                 (const uint16_t*)w->WQ1, (const uint16_t*)w->WQ2, (const uint16_t*)w->WK1, (const uint16_t*)w->WK2,
                 (const uint16_t*)w->WV, L + 1, C, bw.wT);
             const int tiles = (cv.N + 15) / 16;
+            // tiles per workgroup: about PROJECT_SLABS slabs each, whatever the degree
+            ProjectMap map;
+            map.first[0] = 0;
+            for (int d = 0; d <= L; ++d) {
+                const int nl = 2 * (L - d) + 1;
+                map.tiles[d] = (PROJECT_SLABS + nl - 1) / nl;
+                map.first[d + 1] = map.first[d] + (tiles + map.tiles[d] - 1) / map.tiles[d];
+            }
 #define E2F_BWD_PROJECT(CC)                                                                                            \
-    k_bwd_project_mfma<CC><<<tiles * (L + 1), 64 * (CC / 16), 0, st>>>((const uint16_t*)h, (const uint16_t*)w->WQ1,              \
-                                                           (const uint16_t*)w->WQ2, (const uint16_t*)w->WK1,          \
-                                                           (const uint16_t*)w->WK2, bw.wT, grad_q, grad_k, grad_v,    \
-                                                           grad_h, tbuf, L, cv.N)
+    k_bwd_project_mfma<CC, PROJECT_SPLIT><<<map.first[L + 1], 64 * (CC / 16), 0, st>>>(                                \
+        (const uint16_t*)h, (const uint16_t*)w->WQ1, (const uint16_t*)w->WQ2, (const uint16_t*)w->WK1,                 \
+        (const uint16_t*)w->WK2, bw.wT, grad_q, grad_k, grad_v, grad_h, tbuf, L, cv.N, map)
             if (C == 32) E2F_BWD_PROJECT(32);
             else if (C == 64) E2F_BWD_PROJECT(64);
             else E2F_BWD_PROJECT(128);
