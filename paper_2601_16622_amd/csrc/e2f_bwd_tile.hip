@@ -153,28 +153,27 @@ __global__ __launch_bounds__(256) void k_bwd_relayout_g(BwdTileParams P) {
     for (int s = 0; s < 4; ++s) atom[s] = 4 * grp + s < N ? P.cv.perm[4 * grp + s] : -1;
     for (int it = threadIdx.x; it < n * (C / 8); it += 256) {
         const int x = it / (C / 8), c = (it % (C / 8)) * 8, head = c >> 4, ch = c & 15;
-        uint16_t b[4][8];
+        float v[4][8];   // (rows of absent atoms as zeros)
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
             const float* src = P.gout + ((size_t)max(atom[s], 0) * n + x) * C + c;
             const f32x4 lo = *reinterpret_cast<const f32x4*>(src), hi = *reinterpret_cast<const f32x4*>(src + 4);
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                b[s][j] = atom[s] >= 0 ? e2f::float_to_bf16_bits(lo[j]) : (uint16_t)0;
-                b[s][4 + j] = atom[s] >= 0 ? e2f::float_to_bf16_bits(hi[j]) : (uint16_t)0;
+                v[s][j] = atom[s] >= 0 ? lo[j] : 0.0f;
+                v[s][4 + j] = atom[s] >= 0 ? hi[j] : 0.0f;
             }
         }
         const int o = s_off[x], cs = (o >> 30) ? 8 : 4;
         uint16_t* d4 = P.g4 + ((size_t)grp * H + head) * n * 64 + (o & 0xffffff) + ch * cs;
 #pragma unroll
-        for (int j = 0; j < 8; ++j)
-            *reinterpret_cast<u32x2*>(d4 + j * cs) = (u32x2){b[0][j] | ((uint32_t)b[1][j] << 16), b[2][j] | ((uint32_t)b[3][j] << 16)};
+        for (int j = 0; j < 8; ++j)   // the four slots of a channel side by side
+            *reinterpret_cast<u32x2*>(d4 + j * cs) = (u32x2){pack_bf16(v[0][j], v[1][j]), pack_bf16(v[2][j], v[3][j])};
         const size_t base = e2f::k16_offset(4 * (size_t)grp, H, head, VKP, x * 16 + ch);
 #pragma unroll
-        for (int s = 0; s < 4; ++s)
-            *reinterpret_cast<u32x4*>(P.grow + base + 32 * s) =
-                (u32x4){b[s][0] | ((uint32_t)b[s][1] << 16), b[s][2] | ((uint32_t)b[s][3] << 16),
-                        b[s][4] | ((uint32_t)b[s][5] << 16), b[s][6] | ((uint32_t)b[s][7] << 16)};
+        for (int s = 0; s < 4; ++s)   // eight channels of a slot side by side
+            *reinterpret_cast<u32x4*>(P.grow + base + 32 * s) = (u32x4){pack_bf16(v[s][0], v[s][1]), pack_bf16(v[s][2], v[s][3]),
+                                                                       pack_bf16(v[s][4], v[s][5]), pack_bf16(v[s][6], v[s][7])};
     }
     if (VK < VKP) {   // the rows' padding must be finite: it meets zeros of the other operand
         for (int it = threadIdx.x; it < H * 4 * (VKP - VK); it += 256) {
