@@ -593,7 +593,9 @@ __global__ __launch_bounds__(64 * (C / 16 + 1)) void k_project_sh(E2fCellsView c
     const int N = cv.N, n = (L + 1) * (L + 1), n_tiles = (N + 15) / 16, N4 = (N + 3) / 4 * 4;
     const int l = L - (int)blockIdx.x / n_groups, nl = 2 * l + 1;
     const int tile0 = ((int)blockIdx.x % n_groups) * tpw, nt = min(tpw, n_tiles - tile0);
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, j = lane & 15, g = lane >> 4;
+    // (the wave's index through readfirstlane: the compiler then knows it, and the addresses built from it, to be the
+    // same in all lanes and keeps them in scalar registers)
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63, j = lane & 15, g = lane >> 4;
     const int n_steps = nt * nl;   // step = local tile * nl + order
     // Where the value rows of component l*l + m go in the layout of e2f::v4_offset: (offset of channel 0) << 4 | number
     // of elements from one channel to the next (4 for a lone component, 8 inside a pair).
@@ -638,19 +640,24 @@ __global__ __launch_bounds__(64 * (C / 16 + 1)) void k_project_sh(E2fCellsView c
         put(1, r[1]);
         issue(PD + 1, r[1]);
         __syncthreads();
-        for (int s0 = 0; s0 < n_steps; s0 += PD) {
+        // (the full groups of PD slabs without a check per pair: the compiler sets its waits on the loads by the
+        // fewest memory instructions on any path from a request to its use, and a path that skips pairs would make
+        // it wait for requests one pair old)
+        auto pair = [&](int st, int u) __attribute__((always_inline)) {
+            put((st + 2) & 3, r[(u + 2) % PD]);
+            issue(st + 2 + PD, r[(u + 2) % PD]);
+            put((st + 3) & 3, r[(u + 3) % PD]);
+            issue(st + 3 + PD, r[(u + 3) % PD]);
+            __syncthreads();
+        };
+        int s0 = 0;
+        for (; s0 + PD <= n_steps; s0 += PD) {
 #pragma unroll
-            for (int u = 0; u < PD; u += 2) {
-                const int st = s0 + u;
-                if (st < n_steps) {
-                    put((st + 2) & 3, r[(u + 2) % PD]);
-                    issue(st + 2 + PD, r[(u + 2) % PD]);
-                    put((st + 3) & 3, r[(u + 3) % PD]);
-                    issue(st + 3 + PD, r[(u + 3) % PD]);
-                    __syncthreads();
-                }
-            }
+            for (int u = 0; u < PD; u += 2) pair(s0 + u, u);
         }
+#pragma unroll
+        for (int u = 0; u < PD; u += 2)
+            if (s0 + u < n_steps) pair(s0 + u, u);
         return;
     }
 
@@ -708,14 +715,22 @@ __global__ __launch_bounds__(64 * (C / 16 + 1)) void k_project_sh(E2fCellsView c
                 qv[r] = to_f16_sat(qacc[r] * go.qscale);
                 kv[r] = to_f16_sat(slot < N ? kacc[r] : 0.0f);
             }
-            const size_t dst = ((size_t)slot * NCT + ct) * go.DKP + l * 16 + 4 * g;
-            if (slot < N) *reinterpret_cast<h16x4*>(go.q16 + dst) = qv;
-            if (slot < N4) *reinterpret_cast<h16x4*>(go.k16 + e2f::k16_offset(slot, NCT, ct, go.DKP, l * 16 + 4 * g)) = kv;
+            // Addresses as (the tile's part, the same in all lanes) + (the lane's part, 32 bits), the lane's part
+            // hidden from the optimizer: hoisted out of the loop as 64-bit addresses per lane they were spilled, and
+            // a reload from scratch memory waits for every store in flight.
+            const int KS = go.DKP >> 5;
+            uint16_t* tile_q = go.q16 + (size_t)(tile0 + lt) * 16 * NCT * go.DKP;
+            uint16_t* tile_k = go.k16 + (size_t)(tile0 + lt) * 4 * NCT * KS * 128;
+            unsigned jj = (unsigned)j, g4 = 4u * (unsigned)g;
+            asm volatile("" : "+v"(jj), "+v"(g4));
+            auto lane_q = [&](unsigned f) { return (jj * NCT + ct) * go.DKP + f; };
+            auto lane_k = [&](unsigned f) { return (((jj >> 2) * NCT + ct) * KS + (f >> 5)) * 128 + (jj & 3) * 32 + (f & 31); };
+            if (slot < N) *reinterpret_cast<h16x4*>(tile_q + lane_q(l * 16 + g4)) = qv;
+            if (slot < N4) *reinterpret_cast<h16x4*>(tile_k + lane_k(l * 16 + g4)) = kv;
             if (l == L && go.DKP > DK) {   // padding features read as zero
                 const h16x4 zero = {(_Float16)0.0f, (_Float16)0.0f, (_Float16)0.0f, (_Float16)0.0f};
-                const size_t dz = ((size_t)slot * NCT + ct) * go.DKP + DK + 4 * g;
-                if (slot < N) *reinterpret_cast<h16x4*>(go.q16 + dz) = zero;
-                if (slot < N4) *reinterpret_cast<h16x4*>(go.k16 + e2f::k16_offset(slot, NCT, ct, go.DKP, DK + 4 * g)) = zero;
+                if (slot < N) *reinterpret_cast<h16x4*>(tile_q + lane_q(DK + g4)) = zero;
+                if (slot < N4) *reinterpret_cast<h16x4*>(tile_k + lane_k(DK + g4)) = zero;
             }
             qacc = (f32x4){0.f, 0.f, 0.f, 0.f};
             kacc = (f32x4){0.f, 0.f, 0.f, 0.f};
@@ -857,7 +872,9 @@ bool launch_wg(const e2f_ctx* ctx, const E2fCellsView& cv, const void* h, const 
         go.DKP = ((L + 1) * 16 + 31) / 32 * 32;
         const bool use_sh = !(ctx->cfg.flags & E2F_FLAG_PROJECT_PER_CHANNEL_TILE);
         if (v_layout == 2 && use_sh) {
-            // more tiles per workgroup fetch the weights less often; keep a few workgroups per CU
+            // More tiles per workgroup fetch the weights less often and pay the start of a workgroup's stream less
+            // often; keep a few workgroups per CU.  (Splitting the work into equal numbers of slabs per workgroup,
+            // whatever the degree, measured slower at every size tried: 75 to 105 us against 70 at 10 000 atoms.)
             int tpw = SH_TPW;
             while (tpw > 4 && (n_tiles + tpw - 1) / tpw * (L + 1) < 384) tpw >>= 1;
             const int n_groups = (n_tiles + tpw - 1) / tpw;
