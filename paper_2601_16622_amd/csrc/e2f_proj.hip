@@ -375,6 +375,108 @@ __global__ __launch_bounds__(64) void k_project_ws(E2fCellsView cv, const uint16
     }
 }
 
+// Weight-stationary projection for fp32 features (v_mfma_f32_16x16x4_f32), plain fp32 q, k, v.  The five fp32 weight
+// tiles of one 16-channel output tile are 160 registers at 128 channels, so the work of an (atom tiles, degree) item
+// is split between two kinds of waves: a QK wave keeps the four weight tiles of q and k for one output tile, a V wave
+// the value weights of VT output tiles; both do 4 C / 16 chains of C / 4 matrix instructions per slab.  Each streams
+// the slabs of h itself (PD in flight); the waves of one group of atom tiles go to one XCD, whose L2 serves the rows
+// they share.  Block -> (XCD, group of atom tiles, degree, wave of the item) as in k_project_ws.
+template <int C>
+__global__ __launch_bounds__(64) void k_project_ws_f32(E2fCellsView cv, const float* __restrict__ h,
+                                                       const float* __restrict__ WQ1, const float* __restrict__ WQ2,
+                                                       const float* __restrict__ WK1, const float* __restrict__ WK2,
+                                                       const float* __restrict__ WV, int L, int tpw,
+                                                       float* __restrict__ q, float* __restrict__ k, float* __restrict__ v) {
+    typedef Frag<float> F;
+    constexpr int NS = C / F::KSTEP, NCT = C / 16, VT = 4, NVW = NCT / VT;   // V waves per item
+    static_assert(NCT % VT == 0, "value waves take four output tiles each");
+    const int N = cv.N, n = (L + 1) * (L + 1), n_tiles = (N + 15) / 16;
+    const int per_group = (L + 1) * (NCT + NVW);
+    const int xcd = blockIdx.x & 7, rest = blockIdx.x >> 3;
+    const int group = (rest / per_group) * 8 + xcd, lw = rest % per_group;
+    const int l = lw / (NCT + NVW), wv = lw % (NCT + NVW), nl = 2 * l + 1;
+    const bool value_wave = wv >= NCT;                 // (uniform)
+    const int ct0 = value_wave ? (wv - NCT) * VT : wv;   // first output tile of this wave
+    const int lane = threadIdx.x, j = lane & 15, g = lane >> 4;
+    const int tile0 = group * tpw, tile1 = min(tile0 + tpw, n_tiles);
+    if (tile0 >= tile1) return;
+    // four stationary weight tiles: (WQ1, WQ2, WK1, WK2) of output tile ct0, or WV of output tiles ct0 .. ct0 + 3
+    F::type Wf[4][NS];
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+        const float* W = value_wave ? WV : (t == 0 ? WQ1 : t == 1 ? WQ2 : t == 2 ? WK1 : WK2);
+        const size_t wrow = ((size_t)l * C + ((ct0 + (value_wave ? t : 0)) * 16 + j)) * C;
+#pragma unroll
+        for (int S = 0; S < NS; ++S) Wf[t][S] = F::load(W + wrow, S, g);
+    }
+    auto load_x = [&](int tile, int m, F::type (&X)[NS]) {
+        const int slot = min(tile * 16 + j, N - 1);  // clamped atoms are computed and not stored
+        const float* row = h + ((size_t)cv.perm[slot] * n + l * l + m) * C;
+#pragma unroll
+        for (int S = 0; S < NS; ++S) X[S] = F::load(row, S, g);
+    };
+    {   // the weights have arrived before the stream starts: inside it only the ring's own loads are in flight
+        typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+#pragma unroll
+        for (int t = 0; t < 4; ++t)
+#pragma unroll
+            for (int S = 0; S < NS; ++S) asm volatile("" ::"v"(__builtin_bit_cast(u32x4, Wf[t][S])));
+    }
+    constexpr int PD = 2;
+    const int n_steps = (tile1 - tile0) * nl;
+    F::type X[PD][NS];
+#pragma unroll
+    for (int u = 0; u < PD; ++u) {
+        const int su = min(u, n_steps - 1);
+        load_x(tile0 + su / nl, su % nl, X[u]);
+    }
+    f32x4 qacc = {0.f, 0.f, 0.f, 0.f}, kacc = {0.f, 0.f, 0.f, 0.f};
+    for (int s0 = 0; s0 < n_steps; s0 += PD) {
+#pragma unroll
+        for (int u = 0; u < PD; ++u) {
+            const int st = s0 + u;
+            if (st < n_steps) {
+                const int tile = tile0 + st / nl, m = st % nl;
+                const int slot = tile * 16 + j;
+                // four independent chains, interleaved so that no matrix instruction waits for its predecessor
+                f32x4 p[4];
+#pragma unroll
+                for (int t = 0; t < 4; ++t) p[t] = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int S = 0; S < NS; ++S)
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+#pragma unroll
+                        for (int t = 0; t < 4; ++t)
+                            p[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(Wf[t][S][e], X[u][S][e], p[t], 0, 0, 0);
+                {   // this buffer is free again: request the slab PD steps ahead (clamped to the last step)
+                    const int sn = min(st + PD, n_steps - 1);
+                    load_x(tile0 + sn / nl, sn % nl, X[u]);
+                }
+                // accumulator layout: lane (g, j) holds output channels 4g .. 4g + 3 of atom j
+                if (value_wave) {
+                    if (slot < N) {
+                        float* dst = v + ((size_t)slot * n + l * l + m) * C + ct0 * 16 + 4 * g;
+#pragma unroll
+                        for (int t = 0; t < 4; ++t) *reinterpret_cast<f32x4*>(dst + 16 * t) = p[t];
+                    }
+                } else {
+                    qacc += p[0] * p[1];
+                    kacc += p[2] * p[3];
+                    if (m == nl - 1) {   // last order of this atom tile: q and k of the degree go out
+                        if (slot < N) {
+                            *reinterpret_cast<f32x4*>(q + ((size_t)slot * (L + 1) + l) * C + ct0 * 16 + 4 * g) = qacc;
+                            *reinterpret_cast<f32x4*>(k + ((size_t)slot * (L + 1) + l) * C + ct0 * 16 + 4 * g) = kacc;
+                        }
+                        qacc = (f32x4){0.f, 0.f, 0.f, 0.f};
+                        kacc = (f32x4){0.f, 0.f, 0.f, 0.f};
+                    }
+                }
+            }
+        }
+    }
+}
+
 // Workgroup variant of the weight-stationary projection for the tiled v layout.  Global stores inside the
 // streaming loop would share the wave's memory counter with the prefetched loads and force every wait to drain
 // all of them, so nothing is stored while streaming: three waves split the degrees of one (32 atoms, 16
@@ -847,6 +949,34 @@ bool launch_ws(const e2f_ctx* ctx, const E2fCellsView& cv, const void* h, const 
 }
 
 template <int C>
+bool launch_ws_f32(const e2f_ctx* ctx, const E2fCellsView& cv, const void* h, const e2f_weights* w, const E2fAttnWs& ws,
+                   hipStream_t st) {
+    const int L = ctx->cfg.L_max, n_tiles = (cv.N + 15) / 16;
+    // more tiles per wave fetch the weights less often; keep two rounds of waves for the chip (2048 fit at a time)
+    const int per_group = (L + 1) * (C / 16 + C / 64);
+    int tpw = 4;
+    while (tpw > 1 && (n_tiles + tpw - 1) / tpw * per_group < 4096) tpw >>= 1;
+    const int groups = (n_tiles + tpw - 1) / tpw;
+    const int blocks = ((groups + 7) / 8) * per_group * 8;
+    k_project_ws_f32<C><<<blocks, 64, 0, st>>>(cv, (const float*)h, (const float*)w->WQ1, (const float*)w->WQ2,
+                                               (const float*)w->WK1, (const float*)w->WK2, (const float*)w->WV, L, tpw,
+                                               ws.q, ws.k, (float*)ws.v);
+    return true;
+}
+bool dispatch_ws_f32(const e2f_ctx* ctx, const E2fCellsView& cv, const void* h, const e2f_weights* w, const E2fAttnWs& ws,
+                     hipStream_t st) {
+    // While the features fit the caches the per-tile kernel, which fetches its weights per wave, is a little faster
+    // (0.29 against 0.33 ms at 6000 atoms, 128 channels, L = 4: 77 MB of features); beyond, it falls off (0.93
+    // against 0.42 ms at 8000 atoms, 1.16 against 0.47 at 10 000).
+    if ((long long)cv.N * ctx->n * ctx->cfg.C * 4 < (80ll << 20)) return false;
+    switch (ctx->cfg.C) {
+        case 64: return launch_ws_f32<64>(ctx, cv, h, w, ws, st);
+        case 128: return launch_ws_f32<128>(ctx, cv, h, w, ws, st);
+    }
+    return false;
+}
+
+template <int C>
 bool launch_wg(const e2f_ctx* ctx, const E2fCellsView& cv, const void* h, const e2f_weights* w, const E2fAttnWs& ws,
                hipStream_t st, int v_layout) {
     if constexpr (C % 32 != 0 || C > 128) {
@@ -1004,7 +1134,7 @@ e2f_status e2f_launch_project_mfma(const e2f_ctx* ctx, const E2fCellsView& cv, c
         ok = (tiled_v && dispatch_wg(ctx, cv, h, w, ws, st, 1)) || dispatch_ws(ctx, cv, h, w, ws, st, tiled_v) ||
              dispatch_mfma<uint16_t>(ctx, cv, h, w, ws, st, tiled_v);
     else
-        ok = dispatch_mfma<float>(ctx, cv, h, w, ws, st, false);
+        ok = dispatch_ws_f32(ctx, cv, h, w, ws, st) || dispatch_mfma<float>(ctx, cv, h, w, ws, st, false);
     if (!ok) return E2F_ERR_UNSUPPORTED;
     E2F_HIP_CHECK(hipGetLastError());
     return E2F_OK;

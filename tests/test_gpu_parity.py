@@ -103,8 +103,9 @@ def test_scaling_point_every_target(torch_cuda):
 
 def test_fp32_tile_kernel(torch_cuda):
     """fp32 features with heads of 16 channels run on the fp32 tile kernel (binary32 matrix instruction, the paper's own
-    precision): the scaling point's box and shape in fp32 on 600 sampled targets, tolerance 1e-4; the same call on the
-    vector-ALU kernel agrees; a box whose last tile is partial, with 13 radial functions; a dense
+    precision): the scaling point's box and shape in fp32 on 600 sampled targets, tolerance 1e-4 (128 MB of features:
+    the projection runs on the weight-stationary fp32 kernel, the smaller cases below on the per-tile one); the same
+    call on the vector-ALU kernel agrees; a box whose last tile is partial, with 13 radial functions; a dense
     core whose tiles do not fit the candidate list and go to the vector-ALU kernel, inside a sparse shell that does."""
     import oracle as O
     from paper_2601_16622_amd import binding as B, workloads as W
