@@ -48,7 +48,7 @@ struct BwdTileParams {
     const int* lists_ent;
     const float4* lists_pos;
     const unsigned long long* lists_mask;
-    int C, H, B, n_tiles, hpw;
+    int C, H, B, n_tiles, hpw, blk;   // blk: tiles per XCD chunk (tile_blk)
     float tau, rc2, cutoff, rbf_step, rbf_gamma;
 };
 
@@ -237,7 +237,7 @@ __global__ __launch_bounds__(256) void k_bwd_tile_stats(BwdTileParams P) {
     __shared__ float s_m[NW][16], s_zz[NW][16], s_D[16];
     const int HG = P.H / P.hpw;
     int tile, hg;
-    if (!tile_xcd_remap(blockIdx.x, P.n_tiles, HG, tile, hg)) return;   // whole workgroup
+    if (!tile_xcd_remap(blockIdx.x, P.n_tiles, P.blk, HG, tile, hg)) return;   // whole workgroup
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, tn = lane & 15, g = lane >> 4;
     const int N = P.cv.N, H = P.H, C = P.C;
     const int t0 = tile * 16, tslot = min(t0 + tn, N - 1);
@@ -383,7 +383,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 
     const int HG = P.H / P.hpw;
     int tile, hg;
-    if (!tile_xcd_remap(blockIdx.x, P.n_tiles, HG, tile, hg)) return;   // whole workgroup
+    if (!tile_xcd_remap(blockIdx.x, P.n_tiles, P.blk, HG, tile, hg)) return;   // whole workgroup
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, tn = lane & 15, g = lane >> 4;
     const int N = P.cv.N, H = P.H, C = P.C;
     const int t0 = tile * 16, tslot = min(t0 + tn, N - 1);
@@ -721,7 +721,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 
     const int HG = P.H / P.hpw;
     int tile, hg;
-    if (!tile_xcd_remap(blockIdx.x, P.n_tiles, HG, tile, hg)) return;   // whole workgroup
+    if (!tile_xcd_remap(blockIdx.x, P.n_tiles, P.blk, HG, tile, hg)) return;   // whole workgroup
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, tn = lane & 15, g = lane >> 4;
     constexpr int NP = NX / 2, NS = 1 + 2 * NP;
     constexpr bool HAS_ODD = (NX & 1) || (n % NW != 0 && ((NX - 1) & 1));
@@ -1000,8 +1000,7 @@ __global__ __launch_bounds__(256) void k_bwd_gpos_reduce(E2fCellsView cv, const 
 template <int L>
 void launch_L(const BwdTileParams& P, bool wgrad, hipStream_t st) {
     const int N = P.cv.N, groups = (N + 3) / 4, HG = P.H / P.hpw;
-    const int chunks = (P.n_tiles + TILE_BLK - 1) / TILE_BLK;
-    const int grid = ((chunks + 7) / 8) * 8 * TILE_BLK * HG;
+    const int grid = tile_grid(P.n_tiles, P.blk, HG);
     k_bwd_relayout_qk<L><<<groups, 256, 0, st>>>(P);
     k_bwd_relayout_v<L><<<groups, 256, 0, st>>>(P);
     k_bwd_relayout_g<L><<<groups, 256, 0, st>>>(P);
@@ -1079,7 +1078,7 @@ e2f_status e2f_launch_backward_tile(const e2f_ctx* ctx, const E2fCellsView& cv, 
     P.pWb_t = tw.pWb_t; P.pwp_t = tw.pwp_t; P.Gu = tw.Gu;
     P.out = out; P.gout = grad_out; P.gq = grad_q; P.gk = grad_k; P.gv = grad_v; P.gpos = grad_pos;
     P.lists_hdr = ws.lists_hdr; P.lists_ent = ws.lists_ent; P.lists_pos = ws.lists_pos; P.lists_mask = ws.lists_mask;
-    P.C = ctx->cfg.C; P.H = ctx->cfg.H; P.B = ctx->cfg.B; P.n_tiles = (cv.N + 15) / 16;
+    P.C = ctx->cfg.C; P.H = ctx->cfg.H; P.B = ctx->cfg.B; P.n_tiles = (cv.N + 15) / 16; P.blk = tile_blk(P.n_tiles);
     P.hpw = e2f_bwd_tile_heads_per_workgroup(P.n_tiles, P.H);
     P.tau = ctx->tau; P.rc2 = ctx->rc2; P.cutoff = ctx->cfg.cutoff; P.rbf_step = ctx->rbf_step; P.rbf_gamma = ctx->rbf_gamma;
     switch (ctx->cfg.L_max) {

@@ -45,7 +45,7 @@ struct TileParams {
     int lists_only;    // the list kernel leaves crowded tiles to the caller instead of running their heads itself
     const float* cw;   // the list kernel's first workgroup forms the axis operators instead: G_out from cw
     float* G_out;
-    int C, H, B, n_tiles;
+    int C, H, B, n_tiles, blk;   // blk: tiles per XCD chunk (tile_blk)
     float rc2, cutoff, rbf_step, rbf_gamma;
 };
 
@@ -689,7 +689,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 
     const int HG = P.H / P.hpw;
     int tile, hg;
-    if (!tile_xcd_remap(blockIdx.x, P.n_tiles, HG, tile, hg)) return;   // whole workgroup
+    if (!tile_xcd_remap(blockIdx.x, P.n_tiles, P.blk, HG, tile, hg)) return;   // whole workgroup
     const int head0 = hg * P.hpw;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, tn = lane & 15, g = lane >> 4;
     // (components, accumulator slots and value rows of a wave as in tile_item)
@@ -1018,7 +1018,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(E2F_TIL
         tile = blockIdx.x - 1;
         head = 0;
     } else {
-        if (!tile_xcd_remap(blockIdx.x, P.n_tiles, P.H, tile, head)) return;   // whole workgroup
+        if (!tile_xcd_remap(blockIdx.x, P.n_tiles, P.blk, P.H, tile, head)) return;   // whole workgroup
     }
     tile_item<L, NW, PBC, MODE, CAP, NB>(P, tile, head);
 }
@@ -1027,8 +1027,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(E2F_TIL
 // building its lists itself (after the axis-operator kernel)
 template <int L>
 void launch_L(const TileParams& P, const float* cw, float* G, int what, hipStream_t st) {
-    const int chunks = (P.n_tiles + TILE_BLK - 1) / TILE_BLK;
-    const int grid = ((chunks + 7) / 8) * 8 * TILE_BLK * P.H;
+    const int grid = tile_grid(P.n_tiles, P.blk, P.H);
     // four waves per workgroup, two workgroups per CU: with eight waves the 128 registers left per wave do not
     // hold a wave's accumulators, value rows and key rows without spilling into the streaming loop
     const bool cap = P.cap_d2 != nullptr;
@@ -1037,7 +1036,7 @@ void launch_L(const TileParams& P, const float* cw, float* G, int what, hipStrea
         constexpr bool PBC = decltype(pbc)::value, CAP = decltype(capped)::value;
         if (P.B > 8) {
             if (what == 1) k_tile<L, 4, PBC, 1, CAP, 16><<<P.n_tiles + 1, 256, 0, st>>>(P);
-            else if (what == 2) k_tile_heads<L, CAP, 16><<<((chunks + 7) / 8) * 8 * TILE_BLK * (P.H / P.hpw), 256, 0, st>>>(P);
+            else if (what == 2) k_tile_heads<L, CAP, 16><<<tile_grid(P.n_tiles, P.blk, P.H / P.hpw), 256, 0, st>>>(P);
             else {
                 k_axis_ops<L><<<1, 128, 0, st>>>(cw, G, true);
                 k_tile<L, 4, PBC, 0, CAP, 16><<<grid, 256, 0, st>>>(P);
@@ -1047,9 +1046,7 @@ void launch_L(const TileParams& P, const float* cw, float* G, int what, hipStrea
         if (what == 1) {
             k_tile<L, 4, PBC, 1, CAP, 8><<<P.n_tiles + 1, 256, 0, st>>>(P);
         } else if (what == 2) {
-            const int hg_chunks = (P.n_tiles + TILE_BLK - 1) / TILE_BLK;
-            const int hgrid = ((hg_chunks + 7) / 8) * 8 * TILE_BLK * (P.H / P.hpw);
-            k_tile_heads<L, CAP, 8><<<hgrid, 256, 0, st>>>(P);
+            k_tile_heads<L, CAP, 8><<<tile_grid(P.n_tiles, P.blk, P.H / P.hpw), 256, 0, st>>>(P);
         } else {
             k_axis_ops<L><<<1, 128, 0, st>>>(cw, G, true);
             k_tile<L, 4, PBC, 0, CAP, 8><<<grid, 256, 0, st>>>(P);
@@ -1098,7 +1095,7 @@ static e2f_status launch_tile(const e2f_ctx* ctx, const E2fCellsView& cv, const 
     P.cw = ws.cw;
     P.G_out = ws.G;
     P.lists_only = lists_only ? 1 : 0;
-    P.C = ctx->cfg.C; P.H = ctx->cfg.H; P.B = ctx->cfg.B; P.n_tiles = (cv.N + 15) / 16;
+    P.C = ctx->cfg.C; P.H = ctx->cfg.H; P.B = ctx->cfg.B; P.n_tiles = (cv.N + 15) / 16; P.blk = tile_blk(P.n_tiles);
     // heads per workgroup of the attention kernel: up to four, as long as about four rounds of workgroups are left
     // for the chip (measured: two and four heads are 2 % ahead of one at 100 000 atoms, even at 10 000)
     P.hpw = 1;

@@ -30,7 +30,7 @@ struct TileF32Params {
     const int* lists_ent;
     const float4* lists_pos;
     const unsigned long long* lists_mask;
-    int C, H, B, n_tiles;
+    int C, H, B, n_tiles, blk;   // blk: tiles per XCD chunk (tile_blk)
     float qscale, rc2, cutoff, rbf_step, rbf_gamma;
 };
 
@@ -91,7 +91,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2)))
     constexpr int NPOS = (LENT8 * 4 + NT - 1) / NT;   // slot positions per thread
 
     int tile, head;
-    if (!tile_xcd_remap(blockIdx.x, P.n_tiles, P.H, tile, head)) return;   // whole workgroup
+    if (!tile_xcd_remap(blockIdx.x, P.n_tiles, P.blk, P.H, tile, head)) return;   // whole workgroup
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, tn = lane & 15, g = lane >> 4;
     // components [x0, x0 + nxw) belong to this wave: n / NW each, the first n % NW waves one more
     const int nxw = n / NW + (wave < n % NW ? 1 : 0);
@@ -370,8 +370,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2)))
 
 template <int L>
 void launch_L(const TileF32Params& P, hipStream_t st) {
-    const int chunks = (P.n_tiles + TILE_BLK - 1) / TILE_BLK;
-    const int grid = ((chunks + 7) / 8) * 8 * TILE_BLK * P.H;
+    const int grid = tile_grid(P.n_tiles, P.blk, P.H);
     k_f32_relayout<L><<<(P.cv.N + 3) / 4, 256, 0, st>>>(P);
 #ifndef E2F_F32_NW
 #define E2F_F32_NW 4
@@ -398,7 +397,7 @@ e2f_status e2f_launch_tile_f32(const e2f_ctx* ctx, const E2fCellsView& cv, const
     P.spos = ws.spos; P.q = ws.q; P.k = ws.k; P.v = static_cast<const float*>(ws.v);
     P.qf = ws.qf; P.kf = ws.kf; P.vf = ws.vf; P.G = ws.G; P.WbT = ws.wbT; P.out = out;
     P.lists_hdr = ws.lists_hdr; P.lists_ent = ws.lists_ent; P.lists_pos = ws.lists_pos; P.lists_mask = ws.lists_mask;
-    P.C = ctx->cfg.C; P.H = ctx->cfg.H; P.B = ctx->cfg.B; P.n_tiles = (cv.N + 15) / 16;
+    P.C = ctx->cfg.C; P.H = ctx->cfg.H; P.B = ctx->cfg.B; P.n_tiles = (cv.N + 15) / 16; P.blk = tile_blk(P.n_tiles);
     P.qscale = ctx->tau * 1.44269504088896341f;   // logits in base-2 units
     P.rc2 = ctx->rc2; P.cutoff = ctx->cfg.cutoff; P.rbf_step = ctx->rbf_step; P.rbf_gamma = ctx->rbf_gamma;
     switch (ctx->cfg.L_max) {

@@ -22,10 +22,22 @@ typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 constexpr int CAPG = 256;      // candidate groups (of four slots) held in LDS per batch
 constexpr int LCAP = E2F_TILE_LCAP;   // entries of a precomputed list; longer lists are built in the kernel
 static_assert(LCAP <= CAPG, "a precomputed list must fit the list area in LDS");
-#ifndef E2F_TILE_BLK
-#define E2F_TILE_BLK 16
-#endif
-constexpr int TILE_BLK = E2F_TILE_BLK;   // consecutive tiles whose (tile, head) items form one XCD chunk, head-major
+// Consecutive tiles whose (tile, head) items form one XCD chunk, head-major: the tiles are cut into 8 k chunks of equal
+// size, so that every XCD gets k chunks.  The larger the chunk, the smaller the share of candidate rows that its
+// neighbours on other XCDs fetch as well (L2 fills of the attention kernel at 10 000 atoms: 613 MB with chunks of 16
+// tiles, 508 with 27, 467 with 40, 407 with 79, at the same kernel time; a chunk of about 80 tiles reads about 4 MB of
+// rows per head, the size of an XCD's L2): up to 640 tiles every XCD gets one chunk.  Beyond that size the XCDs run
+// several chunks one after the other and finish at different times, and small chunks are faster (100 000 atoms:
+// 2.36 ms with chunks of 79 tiles, 2.30 with 40, 2.28 with 20): chunks of at most 20 tiles there.
+constexpr int TILE_BLK_ONE = 80, TILE_BLK_MANY = 20;
+inline int tile_blk(int n_tiles) {
+    const int cap = n_tiles <= 8 * TILE_BLK_ONE ? TILE_BLK_ONE : TILE_BLK_MANY;
+    const int k = (n_tiles + 8 * cap - 1) / (8 * cap);
+    const int blk = (n_tiles + 8 * k - 1) / (8 * (k > 0 ? k : 1));
+    return blk > 0 ? blk : 1;
+}
+// workgroups of a launch over (tile, head group) items in that order
+inline int tile_grid(int n_tiles, int blk, int HG) { return ((n_tiles + blk - 1) / blk + 7) / 8 * 8 * blk * HG; }
 #ifndef E2F_TILE_OCC
 #define E2F_TILE_OCC(NW) ((NW) / 2)
 #endif
@@ -149,14 +161,14 @@ __device__ __forceinline__ void wave_lds_sync() {
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
 }
-// Workgroups are dealt to the 8 XCDs round-robin, each XCD with its own L2.  A chunk of TILE_BLK consecutive tiles
+// Workgroups are dealt to the 8 XCDs round-robin, each XCD with its own L2.  A chunk of blk consecutive tiles
 // (neighbours in space) goes to one XCD and is run head by head, so that the workgroups resident on an XCD at any
-// time read the k and v rows of one head over one small region.
-__device__ __forceinline__ bool tile_xcd_remap(int bid, int n_tiles, int H, int& tile, int& head) {
-    const int xcd = bid & 7, idx = bid >> 3, per = TILE_BLK * H;
+// time read the k and v rows of one head over one region.
+__device__ __forceinline__ bool tile_xcd_remap(int bid, int n_tiles, int blk, int H, int& tile, int& head) {
+    const int xcd = bid & 7, idx = bid >> 3, per = blk * H;
     const int chunk = (idx / per) * 8 + xcd, within = idx % per;
-    head = within / TILE_BLK;
-    tile = chunk * TILE_BLK + within % TILE_BLK;
+    head = within / blk;
+    tile = chunk * blk + within % blk;
     return tile < n_tiles;
 }
 
