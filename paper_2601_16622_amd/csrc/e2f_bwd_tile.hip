@@ -1001,21 +1001,26 @@ template <int L>
 void launch_L(const BwdTileParams& P, bool wgrad, hipStream_t st) {
     const int N = P.cv.N, groups = (N + 3) / 4, HG = P.H / P.hpw;
     const int grid = tile_grid(P.n_tiles, P.blk, HG);
+    // the statistics kernel, whose workgroups are short, runs faster on small XCD chunks (0.099 against 0.110 ms at
+    // 10 000 atoms with 20 tiles per chunk instead of 79)
+    BwdTileParams Ps = P;
+    Ps.blk = P.blk < TILE_BLK_MANY ? P.blk : TILE_BLK_MANY;
+    const int grid_s = tile_grid(P.n_tiles, Ps.blk, HG);
     k_bwd_relayout_qk<L><<<groups, 256, 0, st>>>(P);
     k_bwd_relayout_v<L><<<groups, 256, 0, st>>>(P);
     k_bwd_relayout_g<L><<<groups, 256, 0, st>>>(P);
     if (P.B > 8) {   // (the radial bias polynomial has its coefficients in registers: instances for B <= 8 and B <= 16)
-        k_bwd_tile_stats<L, 16><<<grid, 256, 0, st>>>(P);
+        k_bwd_tile_stats<L, 16><<<grid_s, 256, 0, st>>>(Ps);
         k_bwd_tile_pairs<L, false, 16, false><<<grid, 256, 0, st>>>(P);
         k_bwd_tile_pairs<L, true, 16, false><<<grid, 256, 0, st>>>(P);
         k_bwd_tile_dv<L, 16, false><<<grid, 256, 0, st>>>(P);
     } else if (wgrad) {
-        k_bwd_tile_stats<L, 8><<<grid, 256, 0, st>>>(P);
+        k_bwd_tile_stats<L, 8><<<grid_s, 256, 0, st>>>(Ps);
         k_bwd_tile_pairs<L, false, 8, true><<<grid, 256, 0, st>>>(P);
         k_bwd_tile_pairs<L, true, 8, false><<<grid, 256, 0, st>>>(P);
         k_bwd_tile_dv<L, 8, true><<<grid, 256, 0, st>>>(P);
     } else {
-        k_bwd_tile_stats<L, 8><<<grid, 256, 0, st>>>(P);
+        k_bwd_tile_stats<L, 8><<<grid_s, 256, 0, st>>>(Ps);
         k_bwd_tile_pairs<L, false, 8, false><<<grid, 256, 0, st>>>(P);
         k_bwd_tile_pairs<L, true, 8, false><<<grid, 256, 0, st>>>(P);
         k_bwd_tile_dv<L, 8, false><<<grid, 256, 0, st>>>(P);
