@@ -309,70 +309,74 @@ __global__ __launch_bounds__(64) void k_project_ws(E2fCellsView cv, const uint16
     }
     f32x4 qacc = {0.f, 0.f, 0.f, 0.f}, kacc = {0.f, 0.f, 0.f, 0.f};
     float vrun[4][2 * E2F_MAX_L + 1];
-    for (int s0 = 0; s0 < n_steps; s0 += PD) {
+    // (full groups of PD steps without a check per step: the compiler sets its waits on the ring's loads by the fewest
+    // memory instructions on any path from a request to its use, and a path that skips steps would make that one)
+    auto step = [&](int st, int u) __attribute__((always_inline)) {
+        const int tile = tile0 + st / nl, m = st % nl;
+        const int slot = tile * 16 + j;
+        // five independent accumulation chains, interleaved so that no MFMA waits for its predecessor
+        f32x4 p[5];
 #pragma unroll
-        for (int u = 0; u < PD; ++u) {
-            const int st = s0 + u;
-            if (st < n_steps) {
-                const int tile = tile0 + st / nl, m = st % nl;
-                const int slot = tile * 16 + j;
-                // five independent accumulation chains, interleaved so that no MFMA waits for its predecessor
-                f32x4 p[5];
+        for (int w = 0; w < 5; ++w) p[w] = (f32x4){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                for (int w = 0; w < 5; ++w) p[w] = (f32x4){0.f, 0.f, 0.f, 0.f};
+        for (int S = 0; S < NS; ++S)
 #pragma unroll
-                for (int S = 0; S < NS; ++S)
+            for (int w = 0; w < 5; ++w) p[w] = F::mma(Wf[w][S], X[u][S], p[w]);
+        // this buffer is free again: request the slab PD steps ahead (clamped to the last step)
+        {
+            const int sn = min(st + PD, n_steps - 1);
+            load_x(tile0 + sn / nl, sn % nl, X[u]);
+        }
+        qacc += p[0] * p[1];
+        kacc += p[2] * p[3];
+        if constexpr (TILED) {
 #pragma unroll
-                    for (int w = 0; w < 5; ++w) p[w] = F::mma(Wf[w][S], X[u][S], p[w]);
-                // this buffer is free again: request the slab PD steps ahead (clamped to the last step)
-                {
-                    const int sn = min(st + PD, n_steps - 1);
-                    load_x(tile0 + sn / nl, sn % nl, X[u]);
+            for (int mm = 0; mm < 2 * E2F_MAX_L + 1; ++mm)
+                if (mm == m) {
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) vrun[r][mm] = p[4][r];
                 }
-                qacc += p[0] * p[1];
-                kacc += p[2] * p[3];
+        } else if (slot < N) {
+            uint16_t* dst = v + ((size_t)slot * n + l * l + m) * C + ct * 16 + 4 * g;
+            const uint32_t w0 = (uint32_t)e2f::float_to_bf16_bits(p[4][0]) | ((uint32_t)e2f::float_to_bf16_bits(p[4][1]) << 16);
+            const uint32_t w1 = (uint32_t)e2f::float_to_bf16_bits(p[4][2]) | ((uint32_t)e2f::float_to_bf16_bits(p[4][3]) << 16);
+            *reinterpret_cast<uint2*>(dst) = make_uint2(w0, w1);
+        }
+        if (m == nl - 1) {  // last order of this atom tile: q, k (and the tiled v rows) go out
+            if (slot < N) {
+                *reinterpret_cast<f32x4*>(q + ((size_t)slot * (L + 1) + l) * C + ct * 16 + 4 * g) = qacc;
+                *reinterpret_cast<f32x4*>(k + ((size_t)slot * (L + 1) + l) * C + ct * 16 + 4 * g) = kacc;
                 if constexpr (TILED) {
+                    const int NT = L >= 3 ? 2 : 1;
+                    const int TI = l >= 3 ? 0 : NT - 1;
+                    const int pos_l = l == 4 ? 0 : (l == 3 ? 9 : (l == 2 ? 0 : (l == 1 ? 5 : 8)));
 #pragma unroll
-                    for (int mm = 0; mm < 2 * E2F_MAX_L + 1; ++mm)
-                        if (mm == m) {
-#pragma unroll
-                            for (int r = 0; r < 4; ++r) vrun[r][mm] = p[4][r];
+                    for (int r = 0; r < 4; ++r) {
+                        uint16_t* row = v + ((((size_t)slot * NCT + ct) * NT + TI) * 16 + 4 * g + r) * 16;
+                        store_run_bf16<2 * E2F_MAX_L + 1>(row, pos_l, vrun[r], nl);
+                        if (l == 0) {
+                            const float zero[7] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+                            store_run_bf16<7>(row, 9, zero, 7);
                         }
-                } else if (slot < N) {
-                    uint16_t* dst = v + ((size_t)slot * n + l * l + m) * C + ct * 16 + 4 * g;
-                    const uint32_t w0 = (uint32_t)e2f::float_to_bf16_bits(p[4][0]) | ((uint32_t)e2f::float_to_bf16_bits(p[4][1]) << 16);
-                    const uint32_t w1 = (uint32_t)e2f::float_to_bf16_bits(p[4][2]) | ((uint32_t)e2f::float_to_bf16_bits(p[4][3]) << 16);
-                    *reinterpret_cast<uint2*>(dst) = make_uint2(w0, w1);
-                }
-                if (m == nl - 1) {  // last order of this atom tile: q, k (and the tiled v rows) go out
-                    if (slot < N) {
-                        *reinterpret_cast<f32x4*>(q + ((size_t)slot * (L + 1) + l) * C + ct * 16 + 4 * g) = qacc;
-                        *reinterpret_cast<f32x4*>(k + ((size_t)slot * (L + 1) + l) * C + ct * 16 + 4 * g) = kacc;
-                        if constexpr (TILED) {
-                            const int NT = L >= 3 ? 2 : 1;
-                            const int TI = l >= 3 ? 0 : NT - 1;
-                            const int pos_l = l == 4 ? 0 : (l == 3 ? 9 : (l == 2 ? 0 : (l == 1 ? 5 : 8)));
-#pragma unroll
-                            for (int r = 0; r < 4; ++r) {
-                                uint16_t* row = v + ((((size_t)slot * NCT + ct) * NT + TI) * 16 + 4 * g + r) * 16;
-                                store_run_bf16<2 * E2F_MAX_L + 1>(row, pos_l, vrun[r], nl);
-                                if (l == 0) {
-                                    const float zero[7] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-                                    store_run_bf16<7>(row, 9, zero, 7);
-                                }
-                                if (l == 3 && L == 3) {
-                                    const float zero[9] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-                                    store_run_bf16<9>(row, 0, zero, 9);
-                                }
-                            }
+                        if (l == 3 && L == 3) {
+                            const float zero[9] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+                            store_run_bf16<9>(row, 0, zero, 9);
                         }
                     }
-                    qacc = (f32x4){0.f, 0.f, 0.f, 0.f};
-                    kacc = (f32x4){0.f, 0.f, 0.f, 0.f};
                 }
             }
+            qacc = (f32x4){0.f, 0.f, 0.f, 0.f};
+            kacc = (f32x4){0.f, 0.f, 0.f, 0.f};
         }
+    };
+    int s0 = 0;
+    for (; s0 + PD <= n_steps; s0 += PD) {
+#pragma unroll
+        for (int u = 0; u < PD; ++u) step(s0 + u, u);
     }
+#pragma unroll
+    for (int u = 0; u < PD; ++u)
+        if (s0 + u < n_steps) step(s0 + u, u);
 }
 
 // Weight-stationary projection for fp32 features (v_mfma_f32_16x16x4_f32), plain fp32 q, k, v.  The five fp32 weight
@@ -431,50 +435,54 @@ __global__ __launch_bounds__(64) void k_project_ws_f32(E2fCellsView cv, const fl
         load_x(tile0 + su / nl, su % nl, X[u]);
     }
     f32x4 qacc = {0.f, 0.f, 0.f, 0.f}, kacc = {0.f, 0.f, 0.f, 0.f};
-    for (int s0 = 0; s0 < n_steps; s0 += PD) {
+    // (full groups of PD steps without a check per step: the compiler sets its waits on the ring's loads by the fewest
+    // memory instructions on any path from a request to its use, and a path that skips steps would make that one)
+    auto step = [&](int st, int u) __attribute__((always_inline)) {
+        const int tile = tile0 + st / nl, m = st % nl;
+        const int slot = tile * 16 + j;
+        // four independent chains, interleaved so that no matrix instruction waits for its predecessor
+        f32x4 p[4];
 #pragma unroll
-        for (int u = 0; u < PD; ++u) {
-            const int st = s0 + u;
-            if (st < n_steps) {
-                const int tile = tile0 + st / nl, m = st % nl;
-                const int slot = tile * 16 + j;
-                // four independent chains, interleaved so that no matrix instruction waits for its predecessor
-                f32x4 p[4];
+        for (int t = 0; t < 4; ++t) p[t] = (f32x4){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                for (int t = 0; t < 4; ++t) p[t] = (f32x4){0.f, 0.f, 0.f, 0.f};
+        for (int S = 0; S < NS; ++S)
 #pragma unroll
-                for (int S = 0; S < NS; ++S)
+            for (int e = 0; e < 4; ++e)
 #pragma unroll
-                    for (int e = 0; e < 4; ++e)
+                for (int t = 0; t < 4; ++t)
+                    p[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(Wf[t][S][e], X[u][S][e], p[t], 0, 0, 0);
+        {   // this buffer is free again: request the slab PD steps ahead (clamped to the last step)
+            const int sn = min(st + PD, n_steps - 1);
+            load_x(tile0 + sn / nl, sn % nl, X[u]);
+        }
+        // accumulator layout: lane (g, j) holds output channels 4g .. 4g + 3 of atom j
+        if (value_wave) {
+            if (slot < N) {
+                float* dst = v + ((size_t)slot * n + l * l + m) * C + ct0 * 16 + 4 * g;
 #pragma unroll
-                        for (int t = 0; t < 4; ++t)
-                            p[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(Wf[t][S][e], X[u][S][e], p[t], 0, 0, 0);
-                {   // this buffer is free again: request the slab PD steps ahead (clamped to the last step)
-                    const int sn = min(st + PD, n_steps - 1);
-                    load_x(tile0 + sn / nl, sn % nl, X[u]);
+                for (int t = 0; t < 4; ++t) *reinterpret_cast<f32x4*>(dst + 16 * t) = p[t];
+            }
+        } else {
+            qacc += p[0] * p[1];
+            kacc += p[2] * p[3];
+            if (m == nl - 1) {   // last order of this atom tile: q and k of the degree go out
+                if (slot < N) {
+                    *reinterpret_cast<f32x4*>(q + ((size_t)slot * (L + 1) + l) * C + ct0 * 16 + 4 * g) = qacc;
+                    *reinterpret_cast<f32x4*>(k + ((size_t)slot * (L + 1) + l) * C + ct0 * 16 + 4 * g) = kacc;
                 }
-                // accumulator layout: lane (g, j) holds output channels 4g .. 4g + 3 of atom j
-                if (value_wave) {
-                    if (slot < N) {
-                        float* dst = v + ((size_t)slot * n + l * l + m) * C + ct0 * 16 + 4 * g;
-#pragma unroll
-                        for (int t = 0; t < 4; ++t) *reinterpret_cast<f32x4*>(dst + 16 * t) = p[t];
-                    }
-                } else {
-                    qacc += p[0] * p[1];
-                    kacc += p[2] * p[3];
-                    if (m == nl - 1) {   // last order of this atom tile: q and k of the degree go out
-                        if (slot < N) {
-                            *reinterpret_cast<f32x4*>(q + ((size_t)slot * (L + 1) + l) * C + ct0 * 16 + 4 * g) = qacc;
-                            *reinterpret_cast<f32x4*>(k + ((size_t)slot * (L + 1) + l) * C + ct0 * 16 + 4 * g) = kacc;
-                        }
-                        qacc = (f32x4){0.f, 0.f, 0.f, 0.f};
-                        kacc = (f32x4){0.f, 0.f, 0.f, 0.f};
-                    }
-                }
+                qacc = (f32x4){0.f, 0.f, 0.f, 0.f};
+                kacc = (f32x4){0.f, 0.f, 0.f, 0.f};
             }
         }
+    };
+    int s0 = 0;
+    for (; s0 + PD <= n_steps; s0 += PD) {
+#pragma unroll
+        for (int u = 0; u < PD; ++u) step(s0 + u, u);
     }
+#pragma unroll
+    for (int u = 0; u < PD; ++u)
+        if (s0 + u < n_steps) step(s0 + u, u);
 }
 
 // Workgroup variant of the weight-stationary projection for the tiled v layout.  Global stores inside the
