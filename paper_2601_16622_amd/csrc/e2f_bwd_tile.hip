@@ -727,7 +727,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     constexpr bool HAS_ODD = (NX & 1) || (n % NW != 0 && ((NX - 1) & 1));
     const int nxw = n / NW + (wave < n % NW ? 1 : 0);
     const int x0 = wave * (n / NW) + min(wave, n % NW);
-    const int npair = nxw >> 1;
+    static_assert((n / NW) / 2 == NP, "every wave has NP pairs of components (a wave with one component more has it unpaired)");
+    constexpr int npair = NP;
     const bool single = (nxw & 1) != 0;
     const int N = P.cv.N, H = P.H;
     const int t0 = tile * 16, nt = min(16, N - t0), tslot = min(t0 + tn, N - 1);
@@ -778,10 +779,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
             load_K(min(wave, nch - 1), head);
             const uint16_t *ba, *bb;
             v_base(0, head, ba, bb);
-            if (HAS_ODD && single) vr.load_single(ba - 64 - tn * 4, bb - 64 - tn * 4);
 #pragma unroll
             for (int p = 0; p < NP; ++p)
                 if (p < npair) vr.load_pair(p, ba, bb);
+            if (HAS_ODD && single) vr.load_single(ba - 64 - tn * 4, bb - 64 - tn * 4);
         }
         f32x4 acc[3][NS];
 #pragma unroll
@@ -854,12 +855,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
                     for (int mu = 0; mu < 3; ++mu) W[mu] = __builtin_bit_cast(bf16x8, s_W[(((G & 1) * NW + cc) * 3 + mu) * 64 + lane]);
                     const uint16_t *ba, *bb;
                     v_base(min(c + 1, nch - 1), head, ba, bb);
-                    if (HAS_ODD && single) {   // (wave-uniform)
-                        const bf16x8 bv = vr.single();
-#pragma unroll
-                        for (int mu = 0; mu < 3; ++mu) acc[mu][0] = mfma(W[mu], bv, acc[mu][0]);
-                        vr.load_single(ba - 64 - tn * 4, bb - 64 - tn * 4);
-                    }
 #pragma unroll
                     for (int p = 0; p < NP; ++p)
                         if (p < npair) {   // (wave-uniform)
@@ -870,6 +865,12 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
                             for (int mu = 0; mu < 3; ++mu) acc[mu][2 + 2 * p] = mfma(W[mu], b1, acc[mu][2 + 2 * p]);
                             vr.load_pair(p, ba, bb);
                         }
+                    if (HAS_ODD && single) {   // (wave-uniform) the odd component last: see k_tile_heads
+                        const bf16x8 bv = vr.single();
+#pragma unroll
+                        for (int mu = 0; mu < 3; ++mu) acc[mu][0] = mfma(W[mu], bv, acc[mu][0]);
+                        vr.load_single(ba - 64 - tn * 4, bb - 64 - tn * 4);
+                    }
                 }
             }
         }

@@ -128,7 +128,8 @@ __device__ __forceinline__ void tile_item(const TileParams& P, const int tile, c
     constexpr bool HAS_ODD = (NX & 1) || (n % NW != 0 && ((NX - 1) & 1));
     const int nxw = n / NW + (wave < n % NW ? 1 : 0);
     const int x0 = wave * (n / NW) + min(wave, n % NW);
-    const int npair = nxw >> 1;
+    static_assert((n / NW) / 2 == NP, "every wave has NP pairs of components (a wave with one component more has it unpaired)");
+    constexpr int npair = NP;
     const bool single = (nxw & 1) != 0;
     const int N = P.cv.N, H = P.H;
     const int t0 = tile * 16, nt = min(16, N - t0);
@@ -425,10 +426,10 @@ __device__ __forceinline__ void tile_item(const TileParams& P, const int tile, c
                 {
                     const uint16_t *ba, *bb;
                     v_base(0, ba, bb);
-                    if (HAS_ODD && single) vr.load_single(ba - 64 - tn * 4, bb - 64 - tn * 4);
 #pragma unroll
                     for (int p = 0; p < NP; ++p)
                         if (p < npair) vr.load_pair(p, ba, bb);
+                    if (HAS_ODD && single) vr.load_single(ba - 64 - tn * 4, bb - 64 - tn * 4);
                 }
                 for (int G = 0; G < ngr; ++G) {
                     // ---- logits, pair geometry and cutoff mask of this wave's chunk
@@ -536,12 +537,6 @@ __device__ __forceinline__ void tile_item(const TileParams& P, const int tile, c
                             for (int mu = 0; mu < 3; ++mu) W[mu] = __builtin_bit_cast(bf16x8, s_W[(cc * 3 + mu) * 64 + lane]);
                             const uint16_t *ba, *bb;   // the next chunk's rows replace each operand once it has been used
                             v_base(min(c + 1, nch - 1), ba, bb);
-                            if (HAS_ODD && single) {   // (wave-uniform)
-                                const bf16x8 bv = vr.single();
-#pragma unroll
-                                for (int mu = 0; mu < 3; ++mu) acc[mu][0] = mfma(W[mu], bv, acc[mu][0]);
-                                vr.load_single(ba - 64 - tn * 4, bb - 64 - tn * 4);
-                            }
 #pragma unroll
                             for (int p = 0; p < NP; ++p)
                                 if (p < npair) {   // (wave-uniform)
@@ -552,6 +547,12 @@ __device__ __forceinline__ void tile_item(const TileParams& P, const int tile, c
                                     for (int mu = 0; mu < 3; ++mu) acc[mu][2 + 2 * p] = mfma(W[mu], b1, acc[mu][2 + 2 * p]);
                                     vr.load_pair(p, ba, bb);
                                 }
+                            if (HAS_ODD && single) {   // (wave-uniform) the odd component last: see k_tile_heads
+                                const bf16x8 bv = vr.single();
+#pragma unroll
+                                for (int mu = 0; mu < 3; ++mu) acc[mu][0] = mfma(W[mu], bv, acc[mu][0]);
+                                vr.load_single(ba - 64 - tn * 4, bb - 64 - tn * 4);
+                            }
                         }
                     }
                 }
@@ -697,7 +698,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     constexpr bool HAS_ODD = (NX & 1) || (n % NW != 0 && ((NX - 1) & 1));
     const int nxw = n / NW + (wave < n % NW ? 1 : 0);
     const int x0 = wave * (n / NW) + min(wave, n % NW);
-    const int npair = nxw >> 1;
+    static_assert((n / NW) / 2 == NP, "every wave has NP pairs of components (a wave with one component more has it unpaired)");
+    constexpr int npair = NP;
     const bool single = (nxw & 1) != 0;
     const int N = P.cv.N, H = P.H;
     const int t0 = tile * 16, nt = min(16, N - t0);
@@ -778,10 +780,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
             load_K(min(wave, nch - 1), head);
             const uint16_t *ba, *bb;
             v_base(0, head, ba, bb);
-            if (HAS_ODD && single) vr.load_single(ba - 64 - tn * 4, bb - 64 - tn * 4);
 #pragma unroll
             for (int p = 0; p < NP; ++p)
                 if (p < npair) vr.load_pair(p, ba, bb);
+            if (HAS_ODD && single) vr.load_single(ba - 64 - tn * 4, bb - 64 - tn * 4);   // (in the order of their use)
         }
     };
     first_rows(head0);
@@ -908,12 +910,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
                     for (int mu = 0; mu < 3; ++mu) W[mu] = __builtin_bit_cast(bf16x8, s_W[(cc * 3 + mu) * 64 + lane]);
                     const uint16_t *ba, *bb;   // the next chunk's rows replace each operand once it has been used
                     v_base(min(c + 1, nch - 1), head, ba, bb);
-                    if (HAS_ODD && single) {   // (wave-uniform)
-                        const bf16x8 bv = vr.single();
-#pragma unroll
-                        for (int mu = 0; mu < 3; ++mu) acc[mu][0] = mfma(W[mu], bv, acc[mu][0]);
-                        vr.load_single(ba - 64 - tn * 4, bb - 64 - tn * 4);
-                    }
 #pragma unroll
                     for (int p = 0; p < NP; ++p)
                         if (p < npair) {   // (wave-uniform)
@@ -924,6 +920,15 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
                             for (int mu = 0; mu < 3; ++mu) acc[mu][2 + 2 * p] = mfma(W[mu], b1, acc[mu][2 + 2 * p]);
                             vr.load_pair(p, ba, bb);
                         }
+                    // The wave with an odd component takes it last.  The waits on the pairs' rows are the same
+                    // instructions for all waves, counted for the waves without the extra rows; with those rows
+                    // requested first, the wave that has them waited at every chunk for rows it had just asked for.
+                    if (HAS_ODD && single) {   // (wave-uniform)
+                        const bf16x8 bv = vr.single();
+#pragma unroll
+                        for (int mu = 0; mu < 3; ++mu) acc[mu][0] = mfma(W[mu], bv, acc[mu][0]);
+                        vr.load_single(ba - 64 - tn * 4, bb - 64 - tn * 4);
+                    }
                 }
             }
         }
