@@ -197,10 +197,10 @@ e2f_status e2f_launch_select_neighbors(const e2f_ctx* ctx, const E2fCellsView& c
 e2f_status e2f_launch_fused_table(const e2f_ctx* ctx, const E2fCellsView& cv, const e2f_weights* w, const E2fAttnWs& ws,
                                   const int32_t* table, int32_t K, float* out, hipStream_t st);
 bool e2f_tile_supported(const e2f_ctx* ctx);
-// Whether the projection writes the tile kernel's layouts itself (C = 32, 64, 128); for other channel counts it writes
-// the plain layouts and a relayout kernel follows (the workspace then holds both).
+// Whether the projection writes the tile kernel's layouts itself (C = 32, 64, 128, 256); for other channel counts it
+// writes the plain layouts and a relayout kernel follows (the workspace then holds both).
 static inline bool e2f_tile_layouts_direct(const e2f_ctx* ctx) {
-    return ctx->cfg.C == 32 || ctx->cfg.C == 64 || ctx->cfg.C == 128;
+    return ctx->cfg.C == 32 || ctx->cfg.C == 64 || ctx->cfg.C == 128 || ctx->cfg.C == 256;
 }
 // G[mu][x_out][x_in], mu = x, y, z: the degree-1 filter's message for a unit pair vector along mu, from the path
 // coefficients cw (tile attention kernel, backward pass).

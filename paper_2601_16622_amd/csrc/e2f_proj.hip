@@ -683,8 +683,13 @@ __global__ __launch_bounds__(64 * WG_WAVES) void k_project_wg(E2fCellsView cv, c
 // (binary16, 8 bytes per lane), v after a 16 x 16 transpose through a private 512-byte LDS patch (bf16, the four slots
 // of a (component, channel) per lane).  Workgroups of the highest degree (most orders) are launched first.
 constexpr int SH_TPW = 16;   // most tiles a workgroup takes; the launcher picks 4, 8 or 16 from the problem size
-template <int C>
-__global__ __launch_bounds__(64 * (C / 16 + 1)) void k_project_sh(E2fCellsView cv, const uint16_t* __restrict__ h,
+// CW: computing waves per workgroup.  C / 16 of them (all output channels in one workgroup) up to 128 channels; at 256
+// channels a wave's five weight tiles are 160 registers, which leaves room for two waves per SIMD only, so a
+// workgroup has four computing waves (64 output channels) and four workgroups share an (atom tiles, degree) item,
+// each fetching its slabs itself; they are dispatched one after the other onto the same XCD, whose L2 serves the
+// repeated rows.
+template <int C, int CW = C / 16>
+__global__ __launch_bounds__(64 * (CW + 1)) void k_project_sh(E2fCellsView cv, const uint16_t* __restrict__ h,
                                                                  const uint16_t* __restrict__ WQ1,
                                                                  const uint16_t* __restrict__ WQ2,
                                                                  const uint16_t* __restrict__ WK1,
@@ -696,13 +701,26 @@ __global__ __launch_bounds__(64 * (C / 16 + 1)) void k_project_sh(E2fCellsView c
     typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
     typedef _Float16 h16x4 __attribute__((ext_vector_type(4)));
     constexpr int NS = C / F::KSTEP, NCT = C / 16, ROW = C + 8, NLD = C / 32;   // NLD 16-byte loads per lane and slab
+    constexpr int NCG = NCT / CW;   // workgroups per item
+    static_assert(NCT % CW == 0, "whole groups of output tiles");
     __shared__ __attribute__((aligned(16))) uint16_t s_x[4][16 * ROW];   // slab st in buffer st mod 4
-    __shared__ __attribute__((aligned(8))) uint16_t s_t[NCT][256];
+    __shared__ __attribute__((aligned(8))) uint16_t s_t[CW][256];
     __shared__ int s_vst[2 * E2F_MAX_L + 1];   // where the value rows of order m go (see below)
     __shared__ int s_atom[SH_TPW * 16];   // fetching wave: atom of every row of the workgroup's tiles
     const int N = cv.N, n = (L + 1) * (L + 1), n_tiles = (N + 15) / 16, N4 = (N + 3) / 4 * 4;
-    const int l = L - (int)blockIdx.x / n_groups, nl = 2 * l + 1;
-    const int tile0 = ((int)blockIdx.x % n_groups) * tpw, nt = min(tpw, n_tiles - tile0);
+    int l, group, cg = 0;
+    if constexpr (NCG == 1) {
+        l = L - (int)blockIdx.x / n_groups;
+        group = (int)blockIdx.x % n_groups;
+    } else {   // per degree ceil(n_groups / 8) * 8 * NCG workgroups: block -> (XCD, group of atom tiles, channel group)
+        const int per_deg = (n_groups + 7) / 8 * 8 * NCG, idx = (int)blockIdx.x % per_deg;
+        l = L - (int)blockIdx.x / per_deg;
+        group = ((idx >> 3) / NCG) * 8 + (idx & 7);
+        cg = (idx >> 3) % NCG;
+        if (group >= n_groups) return;   // whole workgroup
+    }
+    const int nl = 2 * l + 1;
+    const int tile0 = group * tpw, nt = min(tpw, n_tiles - tile0);
     // (the wave's index through readfirstlane: the compiler then knows it, and the addresses built from it, to be the
     // same in all lanes and keeps them in scalar registers)
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63, j = lane & 15, g = lane >> 4;
@@ -714,7 +732,7 @@ __global__ __launch_bounds__(64 * (C / 16 + 1)) void k_project_sh(E2fCellsView c
         s_vst[threadIdx.x] = (e2f::v4_offset(n, x, 0) << 4) | (e2f::v4_role(n, x) == 0 ? 4 : 8);
     }
 
-    if (wave == NCT) {
+    if (wave == CW) {
         // ---- the fetching wave: lane = (atom a of the tile, quarter of its row)
         // The atoms of the workgroup's tiles go through LDS: indexed by the local tile in registers they end up in
         // scratch memory, whose loads share the memory counter with the slab loads and are the youngest of them, so
@@ -772,7 +790,7 @@ __global__ __launch_bounds__(64 * (C / 16 + 1)) void k_project_sh(E2fCellsView c
     }
 
     // ---- the computing waves
-    const int ct = wave;
+    const int ct = cg * CW + wave;
     F::type Wf[5][NS];
     {   // weights of the degree; they must have arrived before the stream starts, so that inside it the wave's
         // memory counter only ever holds stores, which nothing waits for
@@ -802,7 +820,7 @@ __global__ __launch_bounds__(64 * (C / 16 + 1)) void k_project_sh(E2fCellsView c
         const int slot = (tile0 + lt) * 16 + j;
         {   // v: [channel][atom] patch, then one (channel, group of four slots) per lane
             const int vst = s_vst[m];   // (offset of channel 0) << 4 | elements between channels
-            uint16_t* patch = s_t[ct];
+            uint16_t* patch = s_t[wave];
 #pragma unroll
             for (int r = 0; r < 4; ++r)
                 patch[(4 * g + r) * 16 + j] = slot < N ? e2f::float_to_bf16_bits(p[4][r]) : (uint16_t)0;
@@ -984,6 +1002,23 @@ bool dispatch_ws_f32(const e2f_ctx* ctx, const E2fCellsView& cv, const void* h, 
     return false;
 }
 
+// 256 channels into the tile layouts: four workgroups of four computing waves per (atom tiles, degree).
+bool launch_sh256(const e2f_ctx* ctx, const E2fCellsView& cv, const void* h, const e2f_weights* w, const E2fAttnWs& ws,
+                  hipStream_t st) {
+    const int L = ctx->cfg.L_max, n_tiles = (cv.N + 15) / 16;
+    WgGroupOut go;
+    go.q16 = ws.q16; go.k16 = ws.k16; go.v4 = ws.v4;
+    go.qscale = ctx->tau * 1.44269504088896341f;   // logits in base-2 units
+    go.DKP = ((L + 1) * 16 + 31) / 32 * 32;
+    int tpw = SH_TPW;
+    while (tpw > 4 && (n_tiles + tpw - 1) / tpw * (L + 1) < 384) tpw >>= 1;
+    const int n_groups = (n_tiles + tpw - 1) / tpw;
+    k_project_sh<256, 4><<<(n_groups + 7) / 8 * 8 * 4 * (L + 1), 64 * 5, 0, st>>>(
+        cv, (const uint16_t*)h, (const uint16_t*)w->WQ1, (const uint16_t*)w->WQ2, (const uint16_t*)w->WK1,
+        (const uint16_t*)w->WK2, (const uint16_t*)w->WV, L, n_groups, tpw, go);
+    return true;
+}
+
 template <int C>
 bool launch_wg(const e2f_ctx* ctx, const E2fCellsView& cv, const void* h, const e2f_weights* w, const E2fAttnWs& ws,
                hipStream_t st, int v_layout) {
@@ -1137,7 +1172,7 @@ e2f_status e2f_launch_project_mfma(const e2f_ctx* ctx, const E2fCellsView& cv, c
             k_tile_relayout<<<(cv.N + 3) / 4, 256, 0, st>>>(cv.N, ctx->cfg.L_max, ctx->cfg.C, ws.q, ws.k, (const uint16_t*)ws.v,
                                                          ctx->tau * 1.44269504088896341f, ws.q16, ws.k16, ws.v4);
     } else if (v_layout == 2)
-        ok = ctx->cfg.feat_dtype == E2F_BF16 && dispatch_wg(ctx, cv, h, w, ws, st, 2);
+        ok = ctx->cfg.feat_dtype == E2F_BF16 && (ctx->cfg.C == 256 ? launch_sh256(ctx, cv, h, w, ws, st) : dispatch_wg(ctx, cv, h, w, ws, st, 2));
     else if (ctx->cfg.feat_dtype == E2F_BF16)
         ok = (tiled_v && dispatch_wg(ctx, cv, h, w, ws, st, 1)) || dispatch_ws(ctx, cv, h, w, ws, st, tiled_v) ||
              dispatch_mfma<uint16_t>(ctx, cv, h, w, ws, st, tiled_v);
