@@ -316,9 +316,14 @@ def main():
             bwd_ms = timed(lambda: P.backward(g_out), reps=10)
             bwd_core_ms = timed(lambda: P.backward(g_out, with_h=False), reps=10)
             bwd_w_ms = timed(lambda: P.backward(g_out, with_weights=True), reps=10)
+            # the same call right after a forward pass that ran in its workspace (projections and lists are kept)
+            P.forward(for_backward=True)
+            bwd_saved_ms = timed(lambda: P.backward(g_out, after_forward=True), reps=10)
             result["backward"] = {"ms": round(bwd_ms, 4), "ms_without_grad_h": round(bwd_core_ms, 4),
                                   "ms_with_weight_gradients": round(bwd_w_ms, 4),
+                                  "ms_after_forward": round(bwd_saved_ms, 4),
                                   "over_forward": round(bwd_ms / fwd_ms, 2),
+                                  "after_forward_over_forward": round(bwd_saved_ms / fwd_ms, 2),
                                   "workspace_bytes": int(B.e2f_attn_backward_workspace_bytes(P.ctx, N)),
                                   "workspace_bytes_with_weight_gradients":
                                       int(B.e2f_attn_backward_weights_workspace_bytes(P.ctx, N))}

@@ -307,6 +307,22 @@ e2f_status e2f_attn_backward(e2f_ctx *ctx, const e2f_cells *cells, const float *
                              const float *grad_out, float *grad_pos, float *grad_q, float *grad_k, float *grad_v,
                              float *grad_h, float *grad_Wb, float *grad_w_path, float *grad_W, void *ws,
                              size_t ws_bytes, void *hip_stream);
+/*
+ * The same backward pass for a caller that has just run the forward pass and kept its workspace, as a training step
+ * does (Sec. "Model invocation and force modes": energies first, forces by differentiating them): the projected q, k, v
+ * and the candidate lists that e2f_attn_forward left in ws are read instead of being computed again.  Arguments and
+ * results as e2f_attn_backward.  The caller guarantees that ws is the buffer (of at least this call's workspace size)
+ * that the last e2f_attn_forward on this stream wrote, for the same ctx, cells, pos, h, seg_offsets and w, and that
+ * nothing has written to it since; the capped and table forms of the forward pass do not qualify.  Nothing of this
+ * can be checked here: with a workspace that holds anything else the gradients are wrong, not an error.  Where the
+ * backward pass does not run in the tile form (see above) there is nothing to reuse and the call is e2f_attn_backward.
+ */
+e2f_status e2f_attn_backward_after_forward(e2f_ctx *ctx, const e2f_cells *cells, const float *pos, const void *h,
+                                           const int32_t *seg_offsets, int32_t N, int32_t S, const e2f_weights *w,
+                                           const float *out, const float *grad_out, float *grad_pos, float *grad_q,
+                                           float *grad_k, float *grad_v, float *grad_h, float *grad_Wb,
+                                           float *grad_w_path, float *grad_W, void *ws, size_t ws_bytes,
+                                           void *hip_stream);
 
 /*
  * Stand-alone EAAS tensor product (Sec. 3.3, Prop. EAAS; the operation of the paper's tensor-product timing table):

@@ -23,7 +23,7 @@ EXPORTS = ["e2f_status_string", "e2f_create", "e2f_destroy", "e2f_cells_workspac
            "e2f_eaas_tensor_product", "e2f_attn_factorized_workspace_bytes", "e2f_attn_forward_factorized",
            "e2f_attn_capped_workspace_bytes", "e2f_attn_forward_capped", "e2f_build_neighbor_table",
            "e2f_attn_table_workspace_bytes", "e2f_attn_forward_table", "e2f_build_cells_periodic",
-           "e2f_attn_backward_workspace_bytes", "e2f_attn_backward",
+           "e2f_attn_backward_workspace_bytes", "e2f_attn_backward", "e2f_attn_backward_after_forward",
            "e2f_attn_backward_weights_workspace_bytes", "e2f_attn_nonlinear_workspace_bytes",
            "e2f_attn_forward_nonlinear", "e2f_count_edges", "e2f_profile_read",
            "e2f_attn_forward_static"]
@@ -115,6 +115,8 @@ def load():
     L.e2f_attn_backward.argtypes = [vp, vp, vp, vp, vp, i32, i32, ctypes.POINTER(Weights), vp, vp, vp, vp, vp, vp, vp,
                                     vp, vp, vp, vp, sz, vp]
     L.e2f_attn_backward.restype = ctypes.c_int
+    L.e2f_attn_backward_after_forward.argtypes = L.e2f_attn_backward.argtypes
+    L.e2f_attn_backward_after_forward.restype = ctypes.c_int
     L.e2f_eaas_tensor_product.argtypes = [vp, vp, vp, vp, vp, i32, vp]
     L.e2f_eaas_tensor_product.restype = ctypes.c_int
     L.e2f_profile_begin.argtypes = [vp, i32]
@@ -285,17 +287,24 @@ def e2f_attn_backward_weights_workspace_bytes(ctx, N):
     return load().e2f_attn_backward_weights_workspace_bytes(ctx, N)
 
 
+def e2f_attn_backward_after_forward(ctx, cells, pos, h, seg_offsets, weights, out, grad_out, grad_pos, grad_q, grad_k,
+                                    grad_v, grad_h, ws, grad_Wb=None, grad_w_path=None, grad_W=None):
+    """ws: the workspace that the last e2f_attn_forward call for the same arguments wrote (see include/e2f.h)."""
+    return e2f_attn_backward(ctx, cells, pos, h, seg_offsets, weights, out, grad_out, grad_pos, grad_q, grad_k, grad_v,
+                             grad_h, ws, grad_Wb, grad_w_path, grad_W, entry="e2f_attn_backward_after_forward")
+
+
 def e2f_attn_backward(ctx, cells, pos, h, seg_offsets, weights, out, grad_out, grad_pos, grad_q, grad_k, grad_v, grad_h,
-                      ws, grad_Wb=None, grad_w_path=None, grad_W=None):
+                      ws, grad_Wb=None, grad_w_path=None, grad_W=None, entry="e2f_attn_backward"):
     N, S = pos.shape[0], seg_offsets.shape[0] - 1
     w = _weights(weights)
-    _check(load().e2f_attn_backward(ctx, cells, _ptr(pos), _ptr(h), _ptr(seg_offsets), N, S, ctypes.byref(w), _ptr(out),
+    _check(getattr(load(), entry)(ctx, cells, _ptr(pos), _ptr(h), _ptr(seg_offsets), N, S, ctypes.byref(w), _ptr(out),
                                     _ptr(grad_out), _ptr(grad_pos), _ptr(grad_q), _ptr(grad_k), _ptr(grad_v),
                                     _ptr(grad_h) if grad_h is not None else ctypes.c_void_p(),
                                     _ptr(grad_Wb) if grad_Wb is not None else ctypes.c_void_p(),
                                     _ptr(grad_w_path) if grad_w_path is not None else ctypes.c_void_p(),
                                     _ptr(grad_W) if grad_W is not None else ctypes.c_void_p(),
-                                    _ptr(ws), ws.numel(), _stream()), "e2f_attn_backward")
+                                    _ptr(ws), ws.numel(), _stream()), entry)
 
 
 def e2f_attn_forward_materialized(ctx, cells, pos, h, seg_offsets, weights, out, ws):
@@ -375,8 +384,12 @@ class Problem:
             self.cells = e2f_build_cells(self.ctx, self.pos, self.seg, self.cells_ws)
         return self.cells
 
-    def forward(self):
-        e2f_attn_forward(self.ctx, self.cells, self.pos, self.h, self.seg, self.weights, self.out, self.attn_ws)
+    def forward(self, for_backward=False):
+        """for_backward: run in the backward pass's workspace, so that backward(after_forward=True) can follow."""
+        ws = self.attn_ws
+        if for_backward:
+            ws = self._scratch("bwd_ws", e2f_attn_backward_weights_workspace_bytes(self.ctx, self.N))
+        e2f_attn_forward(self.ctx, self.cells, self.pos, self.h, self.seg, self.weights, self.out, ws)
         return self.out
 
     def forward_static(self, out=None):
@@ -427,10 +440,10 @@ class Problem:
         e2f_attn_forward_factorized(self.ctx, self.cells, self.pos, self.h, self.seg, self.weights, out, self.fact_ws)
         return out
 
-    def backward(self, grad_out, out=None, with_h=True, with_weights=False):
+    def backward(self, grad_out, out=None, with_h=True, with_weights=False, after_forward=False):
         """Gradients of sum(out * grad_out): (grad_pos [N][3], grad_q, grad_k [N][L+1][C], grad_v [N][n][C],
         grad_h [N][n][C] or None); with_weights appends (grad_Wb [H][B], grad_w_path [L+1][L+1],
-        grad_W [5][L+1][C][C])."""
+        grad_W [5][L+1][C][C]).  after_forward: e2f_attn_backward_after_forward, right after forward(for_backward=True)."""
         import torch
         out = self.out if out is None else out
         need = (e2f_attn_backward_weights_workspace_bytes if with_weights else e2f_attn_backward_workspace_bytes)(self.ctx, self.N)
@@ -447,8 +460,8 @@ class Problem:
             gwb = torch.empty((self.cfg["H"], self.cfg["B"]), dtype=torch.float32, device=self.device)
             gwp = torch.empty((L1, L1), dtype=torch.float32, device=self.device)
             gw = torch.empty((5, L1, C, C), dtype=torch.float32, device=self.device)
-        e2f_attn_backward(self.ctx, self.cells, self.pos, self.h, self.seg, self.weights, out, grad_out, gp, gq, gk, gv,
-                          gh, ws, gwb, gwp, gw)
+        (e2f_attn_backward_after_forward if after_forward else e2f_attn_backward)(
+            self.ctx, self.cells, self.pos, self.h, self.seg, self.weights, out, grad_out, gp, gq, gk, gv, gh, ws, gwb, gwp, gw)
         return (gp, gq, gk, gv, gh, gwb, gwp, gw) if with_weights else (gp, gq, gk, gv, gh)
 
     def forward_materialized(self, out=None):

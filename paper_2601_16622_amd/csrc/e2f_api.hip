@@ -660,11 +660,12 @@ size_t e2f_attn_backward_weights_workspace_bytes(const e2f_ctx* ctx, int32_t N) 
     return bytes;
 }
 
-e2f_status e2f_attn_backward(e2f_ctx* ctx, const e2f_cells* cells, const float* pos, const void* h,
-                             const int32_t* seg_offsets, int32_t N, int32_t S, const e2f_weights* w, const float* out,
-                             const float* grad_out, float* grad_pos, float* grad_q, float* grad_k, float* grad_v,
-                             float* grad_h, float* grad_Wb, float* grad_w_path, float* grad_W, void* ws, size_t ws_bytes,
-                             void* hip_stream) {
+// saved: the workspace still holds what the forward pass wrote (projections, candidate lists, axis operators)
+static e2f_status backward_impl(e2f_ctx* ctx, const e2f_cells* cells, const float* pos, const void* h,
+                                const int32_t* seg_offsets, int32_t N, int32_t S, const e2f_weights* w, const float* out,
+                                const float* grad_out, float* grad_pos, float* grad_q, float* grad_k, float* grad_v,
+                                float* grad_h, float* grad_Wb, float* grad_w_path, float* grad_W, void* ws, size_t ws_bytes,
+                                void* hip_stream, bool saved) {
     if (!ctx) return E2F_ERR_INVALID_ARG;
     if (!e2f_backward_supported(ctx)) return E2F_ERR_UNSUPPORTED;
     // same argument checks as the fused call (out is read here), against this call's own workspace size
@@ -680,10 +681,33 @@ e2f_status e2f_attn_backward(e2f_ctx* ctx, const e2f_cells* cells, const float* 
     const E2fBwdWs Bw = bwd_ws_layout(ctx, N, ws, L.bytes, grad_W != nullptr);
     E2fBwdTileWs Tw;
     if (tile) Tw = e2f_bwd_tile_ws_layout(ctx, N, ws, Bw.bytes);
-    if ((rc = e2f_launch_prepare(ctx, cells->view, pos, w, L, st)) != E2F_OK) return rc;
-    if ((rc = e2f_launch_project_mfma(ctx, cells->view, h, w, L, v_layout, st)) != E2F_OK) return rc;
+    // (the forward pass of a configuration whose backward pass runs in tile form used the same layout of ws)
+    const bool reuse = saved && tile && ctx->use_tile_attn && !(ctx->cfg.flags & E2F_FLAG_TILE_LISTS_PER_HEAD);
+    if (!reuse) {
+        if ((rc = e2f_launch_prepare(ctx, cells->view, pos, w, L, st)) != E2F_OK) return rc;
+        if ((rc = e2f_launch_project_mfma(ctx, cells->view, h, w, L, v_layout, st)) != E2F_OK) return rc;
+    }
     return e2f_launch_backward(ctx, cells->view, w, L, Bw, out, grad_out, grad_pos, grad_q, grad_k, grad_v, h, grad_h,
-                               grad_Wb, grad_w_path, grad_W, tile ? &Tw : nullptr, st);
+                               grad_Wb, grad_w_path, grad_W, tile ? &Tw : nullptr, st, reuse);
+}
+
+e2f_status e2f_attn_backward(e2f_ctx* ctx, const e2f_cells* cells, const float* pos, const void* h,
+                             const int32_t* seg_offsets, int32_t N, int32_t S, const e2f_weights* w, const float* out,
+                             const float* grad_out, float* grad_pos, float* grad_q, float* grad_k, float* grad_v,
+                             float* grad_h, float* grad_Wb, float* grad_w_path, float* grad_W, void* ws, size_t ws_bytes,
+                             void* hip_stream) {
+    return backward_impl(ctx, cells, pos, h, seg_offsets, N, S, w, out, grad_out, grad_pos, grad_q, grad_k, grad_v, grad_h,
+                         grad_Wb, grad_w_path, grad_W, ws, ws_bytes, hip_stream, false);
+}
+
+e2f_status e2f_attn_backward_after_forward(e2f_ctx* ctx, const e2f_cells* cells, const float* pos, const void* h,
+                                           const int32_t* seg_offsets, int32_t N, int32_t S, const e2f_weights* w,
+                                           const float* out, const float* grad_out, float* grad_pos, float* grad_q,
+                                           float* grad_k, float* grad_v, float* grad_h, float* grad_Wb,
+                                           float* grad_w_path, float* grad_W, void* ws, size_t ws_bytes,
+                                           void* hip_stream) {
+    return backward_impl(ctx, cells, pos, h, seg_offsets, N, S, w, out, grad_out, grad_pos, grad_q, grad_k, grad_v, grad_h,
+                         grad_Wb, grad_w_path, grad_W, ws, ws_bytes, hip_stream, true);
 }
 
 e2f_status e2f_eaas_tensor_product(e2f_ctx* ctx, const void* h, const float* r, const float* w_path, float* out,

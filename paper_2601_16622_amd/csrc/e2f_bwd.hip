@@ -1140,7 +1140,7 @@ e2f_status e2f_launch_backward(const e2f_ctx* ctx, const E2fCellsView& cv, const
                                const E2fBwdWs& bw, const float* out, const float* grad_out, float* grad_pos,
                                float* grad_q, float* grad_k, float* grad_v, const void* h, float* grad_h,
                                float* grad_Wb, float* grad_w_path, float* grad_W, const E2fBwdTileWs* tw,
-                               hipStream_t st) {
+                               hipStream_t st, bool lists_ready) {
     if (cv.N == 0) return E2F_OK;
     const bool wgrad = grad_Wb || grad_w_path;
     if (wgrad && ctx->cfg.B > WB_PER_THREAD * ctx->Ch) return E2F_ERR_UNSUPPORTED;
@@ -1166,7 +1166,7 @@ e2f_status e2f_launch_backward(const e2f_ctx* ctx, const E2fCellsView& cv, const
     if (tw) {
         // pair work on the matrix cores, tile by tile; the atoms of crowded tiles (lists that do not fit) go through
         // the per-atom kernels, which read the same layouts and statistics
-        if ((rc = e2f_launch_tile_lists(ctx, cv, ws, st)) != E2F_OK) return rc;
+        if (!lists_ready && (rc = e2f_launch_tile_lists(ctx, cv, ws, st)) != E2F_OK) return rc;
         auto crowded = [&](int what) {
             switch (ctx->cfg.L_max) {
                 case 1: launch_crowded<1>(P, what, st); break;

@@ -218,11 +218,13 @@ e2f_status e2f_launch_backward_tile_wsum(const e2f_ctx* ctx, const E2fCellsView&
 // The candidate lists of the tile kernels and the axis operators only (a crowded tile gets the header -1 and nothing else).
 e2f_status e2f_launch_tile_lists(const e2f_ctx* ctx, const E2fCellsView& cv, const E2fAttnWs& ws, hipStream_t st);
 // tw: null for the per-atom pair kernels (plain layouts in `ws`), else the tile form (tile layouts in `ws`).
+// lists_ready: the candidate lists and axis operators of the tile form are in `ws` already (left by the forward pass).
 bool e2f_backward_supported(const e2f_ctx* ctx);
 e2f_status e2f_launch_backward(const e2f_ctx* ctx, const E2fCellsView& cv, const e2f_weights* w, const E2fAttnWs& ws,
                                const E2fBwdWs& bw, const float* out, const float* grad_out, float* grad_pos,
                                float* grad_q, float* grad_k, float* grad_v, const void* h, float* grad_h,
-                               float* grad_Wb, float* grad_w_path, float* grad_W, const E2fBwdTileWs* tw, hipStream_t st);
+                               float* grad_Wb, float* grad_w_path, float* grad_W, const E2fBwdTileWs* tw, hipStream_t st,
+                               bool lists_ready = false);
 // cw[comp][t] = P coefficient with every path weight one.
 e2f_status e2f_launch_unit_cw(const e2f_ctx* ctx, float* cw, hipStream_t st);
 // table: the caller's padded neighbour table [N][table_K], or null (every atom within the cutoff is a neighbour)

@@ -159,6 +159,39 @@ def test_backward_tile_form_with_crowded_tiles(torch_cuda):
     run_backward(torch_cuda, wl)
 
 
+def test_backward_after_forward_reuses_the_workspace(torch_cuda):
+    """e2f_attn_backward_after_forward reads the projections and candidate lists that the forward pass left in the
+    workspace: the same kernels on the same numbers as the stand-alone call, so every gradient agrees bit for bit
+    (tile form: bf16 at the benchmark's shape, open and periodic cells, a crowded core); a configuration whose backward
+    pass has no tile form takes the stand-alone path and agrees as well."""
+    from paper_2601_16622_amd import binding as B, workloads as W
+    rng = np.random.default_rng(5)
+    crowded = np.concatenate([W.dart_throw_box(rng, 700, 5.0, min_sep=0.3, origin=(4.0, 4.0, 4.0)),
+                              W.dart_throw_box(rng, 150, 13.0, min_sep=1.5)])
+    cases = [W.box(1500, 2), W.periodic_boxes((700,), 3), W.box(300, 4, dtype="f32", C=64, H=4),
+             W._pack(dict(L=2, C=64, H=4, B=8, lf=1, cutoff=4.0, dtype="bf16"), [crowded], rng, elements=False)]
+    for wl in cases:
+        P = B.Problem(wl)
+        try:
+            P.build_cells()
+            g = torch_cuda.randn(P.out.shape, generator=torch_cuda.Generator().manual_seed(1)).to(P.device)
+            P.forward()
+            alone = [x.clone() for x in P.backward(g)]
+            for x in P.backward(g): x.fill_(float("nan"))
+            P.forward(for_backward=True)
+            for with_weights in (False, True):
+                saved = P.backward(g, after_forward=True, with_weights=with_weights)
+                torch_cuda.cuda.synchronize()
+                for a, b in zip(alone, saved[:5]):
+                    assert torch_cuda.equal(a, b)
+            ref_w = P.backward(g, with_weights=True)
+            torch_cuda.cuda.synchronize()
+            for a, b in zip(ref_w[5:], saved[5:]):
+                assert torch_cuda.equal(a, b)
+        finally:
+            P.close()
+
+
 def test_backward_rejects_what_it_does_not_cover(torch_cuda):
     from paper_2601_16622_amd import binding as B
     wl = custom(30, (60,), 2, 32, 2, 4, "f32", 3.5, 7.0)
