@@ -1101,10 +1101,11 @@ static e2f_status launch_tile(const e2f_ctx* ctx, const E2fCellsView& cv, const 
     P.G_out = ws.G;
     P.lists_only = lists_only ? 1 : 0;
     P.C = ctx->cfg.C; P.H = ctx->cfg.H; P.B = ctx->cfg.B; P.n_tiles = (cv.N + 15) / 16; P.blk = tile_blk(P.n_tiles);
-    // heads per workgroup of the attention kernel: up to four, as long as about four rounds of workgroups are left
-    // for the chip (measured: two and four heads are 2 % ahead of one at 100 000 atoms, even at 10 000)
+    // heads per workgroup of the attention kernel: up to four, as long as about eight rounds of workgroups are left
+    // for the chip (measured: two and four heads are 2 % ahead of one at 100 000 atoms; at 20 000 atoms two heads are
+    // 2 % ahead of four, at 10 000 one head is even with two or 1 % ahead)
     P.hpw = 1;
-    while (P.hpw < 4 && P.H % (P.hpw * 2) == 0 && (long)P.n_tiles * P.H / (P.hpw * 2) >= 2048) P.hpw *= 2;
+    while (P.hpw < 4 && P.H % (P.hpw * 2) == 0 && (long)P.n_tiles * P.H / (P.hpw * 2) >= 4096) P.hpw *= 2;
     P.rc2 = ctx->rc2; P.cutoff = ctx->cfg.cutoff; P.rbf_step = ctx->rbf_step; P.rbf_gamma = ctx->rbf_gamma;
     switch (ctx->cfg.L_max) {
         case 1: launch_L<1>(P, ws.cw, ws.G, what, st); break;
